@@ -1,0 +1,173 @@
+"""Pins for the oracle's decode attention (Eq. 1 of the paper over dequantized K/V):
+library attention, pure-Python brute force, closed forms and invariants.  CPU only."""
+import math
+
+import numpy as np
+import pytest
+
+from oracle import cq_oracle as O
+
+
+def _case(seed, B, Hq, Hkv, d, T, c, b):
+    rng = np.random.default_rng(seed)
+    G = Hkv * d // c
+    K = 1 << b
+    q = rng.standard_normal((B, Hq, d)).astype(np.float16)
+    ck = rng.standard_normal((G, K, c)).astype(np.float16)
+    cv = rng.standard_normal((G, K, c)).astype(np.float16)
+    kc = rng.integers(0, K, size=(B, T, G)).astype(np.uint16)
+    vc = rng.integers(0, K, size=(B, T, G)).astype(np.uint16)
+    return q, kc, vc, ck, cv
+
+
+def _dequant_np(codes, cb):
+    """[B, T, G] codes -> [B, T, G*c] by numpy indexing (independent of the C code)."""
+    B, T, G = codes.shape
+    c = cb.shape[2]
+    out = np.empty((B, T, G, c))
+    for g in range(G):
+        out[:, :, g, :] = cb[g].astype(np.float64)[codes[:, :, g]]
+    return out.reshape(B, T, G * c)
+
+
+def test_attention_equals_pure_python_dequantize_then_attend():
+    B, Hq, Hkv, d, T, c, b = 2, 2, 2, 4, 5, 2, 3
+    q, kc, vc, ck, cv = _case(1, B, Hq, Hkv, d, T, c, b)
+    scale = 0.37
+    out = O.attention(q, kc, vc, ck, cv, scale, Hkv)
+    Gh = d // c
+    for n in range(B):
+        for h in range(Hq):
+            ks, vs = [], []
+            for t in range(T):
+                krow, vrow = [], []
+                for gl in range(Gh):
+                    g = h * Gh + gl
+                    krow += [float(v) for v in ck[g, kc[n, t, g]]]
+                    vrow += [float(v) for v in cv[g, vc[n, t, g]]]
+                ks.append(krow)
+                vs.append(vrow)
+            s = [scale * sum(float(q[n, h, i]) * ks[t][i] for i in range(d)) for t in range(T)]
+            m = max(s)
+            e = [math.exp(v - m) for v in s]
+            z = sum(e)
+            for i in range(d):
+                want = sum(e[t] / z * vs[t][i] for t in range(T))
+                assert out[n, h, i] == pytest.approx(want, rel=1e-13, abs=1e-15)
+
+
+@pytest.mark.parametrize("Hq,Hkv,c,b", [(4, 4, 8, 8), (8, 2, 4, 8), (4, 1, 8, 10), (2, 2, 2, 8)])
+def test_attention_equals_torch_sdpa_on_dequantized_kv(Hq, Hkv, c, b):
+    import torch
+    import torch.nn.functional as F
+    B, d, T = 2, 16, 37
+    q, kc, vc, ck, cv = _case(5, B, Hq, Hkv, d, T, c, b)
+    scale = 1.0 / math.sqrt(d)
+    out = O.attention(q, kc, vc, ck, cv, scale, Hkv)
+    kh = _dequant_np(kc, ck).reshape(B, T, Hkv, d).transpose(0, 2, 1, 3)      # [B, Hkv, T, d]
+    vh = _dequant_np(vc, cv).reshape(B, T, Hkv, d).transpose(0, 2, 1, 3)
+    rep = Hq // Hkv
+    kh = np.repeat(kh, rep, axis=1)     # query head h uses KV head h // rep
+    vh = np.repeat(vh, rep, axis=1)
+    qq = torch.from_numpy(q.astype(np.float64))[:, :, None, :]
+    want = F.scaled_dot_product_attention(qq, torch.from_numpy(kh), torch.from_numpy(vh), scale=scale)
+    np.testing.assert_allclose(out, want[:, :, 0, :].numpy(), rtol=1e-11, atol=1e-13)
+
+
+def test_single_token_context_returns_its_dequantized_value_exactly():
+    B, Hq, Hkv, d, T, c, b = 3, 4, 2, 8, 1, 4, 8
+    q, kc, vc, ck, cv = _case(2, B, Hq, Hkv, d, T, c, b)
+    out = O.attention(q, kc, vc, ck, cv, 0.5, Hkv)
+    v0 = _dequant_np(vc, cv).reshape(B, Hkv, d)
+    for h in range(Hq):
+        assert np.array_equal(out[:, h], v0[:, h // (Hq // Hkv)])
+
+
+def test_all_tokens_sharing_one_value_code_return_that_centroid():
+    B, Hq, Hkv, d, T, c, b = 1, 2, 2, 8, 50, 8, 8
+    q, kc, vc, ck, cv = _case(3, B, Hq, Hkv, d, T, c, b)
+    vc[:] = vc[:, :1]
+    out = O.attention(q, kc, vc, ck, cv, 0.2, Hkv)
+    want = _dequant_np(vc[:, :1], cv).reshape(B, Hkv, d)
+    np.testing.assert_allclose(out, want, rtol=1e-14, atol=1e-15)
+
+
+def test_zero_query_gives_uniform_weights_and_the_code_histogram_average():
+    B, Hq, Hkv, d, T, c, b = 1, 2, 2, 8, 200, 4, 4
+    q, kc, vc, ck, cv = _case(4, B, Hq, Hkv, d, T, c, b)
+    q[:] = 0
+    out, probs = O.attention(q, kc, vc, ck, cv, 1.0, Hkv, want_probs=True)
+    assert np.allclose(probs, 1.0 / T, rtol=1e-15)
+    Gh, K = d // c, 1 << b
+    for h in range(Hq):
+        for gl in range(Gh):
+            g = h * Gh + gl
+            counts = np.bincount(vc[0, :, g], minlength=K).astype(np.float64)
+            want = (counts[:, None] / T * cv[g].astype(np.float64)).sum(0)
+            np.testing.assert_allclose(out[0, h, gl * c:(gl + 1) * c], want, rtol=1e-12, atol=1e-14)
+
+
+def test_weights_sum_to_one_and_scores_are_lookup_table_sums():
+    B, Hq, Hkv, d, T, c, b = 2, 4, 2, 16, 33, 4, 8
+    q, kc, vc, ck, cv = _case(6, B, Hq, Hkv, d, T, c, b)
+    scale = 0.25
+    out, scores, probs = O.attention(q, kc, vc, ck, cv, scale, Hkv, want_scores=True, want_probs=True)
+    np.testing.assert_allclose(probs.sum(-1), 1.0, rtol=1e-14)
+    assert np.all(probs >= 0)
+    # q . dequant(k) == sum over groups of (q_g . centroid) looked up by code
+    Gh = d // c
+    rep = Hq // Hkv
+    qf = q.astype(np.float64)
+    for n in range(B):
+        for h in range(Hq):
+            hk = h // rep
+            lut = np.einsum("gi,gji->gj", qf[n, h].reshape(Gh, c),
+                            ck[hk * Gh:(hk + 1) * Gh].astype(np.float64))       # [Gh, K]
+            codes = kc[n, :, hk * Gh:(hk + 1) * Gh]                             # [T, Gh]
+            want = scale * lut[np.arange(Gh)[None, :], codes].sum(-1)
+            np.testing.assert_allclose(scores[n, h], want, rtol=1e-12, atol=1e-13)
+    # and the output is the probability-weighted sum of dequantized values
+    vh = _dequant_np(vc, cv).reshape(B, T, Hkv, d)
+    for h in range(Hq):
+        want = np.einsum("bt,btd->bd", probs[:, h], vh[:, :, h // rep])
+        np.testing.assert_allclose(out[:, h], want, rtol=1e-12, atol=1e-14)
+
+
+def test_gqa_equals_mha_with_duplicated_kv_heads():
+    B, Hq, Hkv, d, T, c, b = 2, 8, 2, 8, 20, 4, 8
+    q, kc, vc, ck, cv = _case(7, B, Hq, Hkv, d, T, c, b)
+    out = O.attention(q, kc, vc, ck, cv, 0.3, Hkv)
+    rep, Gh = Hq // Hkv, d // c
+    dup = lambda a, axis: np.repeat(a.reshape(*a.shape[:axis], Hkv, Gh, *a.shape[axis + 1:]), rep, axis=axis) \
+        .reshape(*a.shape[:axis], Hq * Gh, *a.shape[axis + 1:])
+    out2 = O.attention(q, dup(kc, 2), dup(vc, 2), dup(ck, 0), dup(cv, 0), 0.3, Hq)
+    assert np.array_equal(out, out2)
+
+
+def test_token_permutation_and_ragged_lengths():
+    B, Hq, Hkv, d, T, c, b = 2, 2, 2, 8, 40, 4, 8
+    q, kc, vc, ck, cv = _case(8, B, Hq, Hkv, d, T, c, b)
+    out = O.attention(q, kc, vc, ck, cv, 0.3, Hkv)
+    perm = np.random.default_rng(0).permutation(T)
+    out_p = O.attention(q, kc[:, perm], vc[:, perm], ck, cv, 0.3, Hkv)
+    np.testing.assert_allclose(out_p, out, rtol=1e-12, atol=1e-14)
+    lens = np.array([13, 40], dtype=np.int32)
+    out_r = O.attention(q, kc, vc, ck, cv, 0.3, Hkv, seq_lens=lens)
+    for n in range(B):
+        want = O.attention(q[n:n + 1], kc[n:n + 1, :lens[n]], vc[n:n + 1, :lens[n]], ck, cv, 0.3, Hkv)
+        assert np.array_equal(out_r[n], want[0])
+    with pytest.raises(ValueError):
+        O.attention(q, kc, vc, ck, cv, 0.3, Hkv, seq_lens=np.array([0, 40], dtype=np.int32))
+
+
+def test_large_scores_do_not_overflow():
+    B, Hq, Hkv, d, T, c, b = 1, 1, 1, 8, 16, 8, 4
+    q, kc, vc, ck, cv = _case(9, B, Hq, Hkv, d, T, c, b)
+    kc[0, :, 0] = np.random.default_rng(1).permutation(T)   # distinct keys: a unique arg-max
+    out = O.attention(q, kc, vc, ck, cv, 4000.0, Hkv)       # scores of order 1e4
+    assert np.all(np.isfinite(out))
+    # softmax saturates on the arg-max token
+    _, scores = O.attention(q, kc, vc, ck, cv, 4000.0, Hkv, want_scores=True)
+    t_star = int(np.argmax(scores[0, 0]))
+    want = _dequant_np(vc, cv)[0, t_star]
+    np.testing.assert_allclose(out[0, 0], want, rtol=1e-9, atol=1e-12)
