@@ -1,0 +1,161 @@
+/*
+ * libcq -- Coupled Quantization (CQ) KV-cache hot path for AMD MI355X (gfx950).
+ *
+ * Two operations, both defined by the CQ paper (arXiv 2405.03917):
+ *
+ *   cq_encode            Section 3.2: the channels of a key or value embedding are cut into
+ *                        non-overlapping groups of c contiguous channels; every group owns a
+ *                        codebook of 2^b c-dimensional centroids and is stored as the b-bit index
+ *                        of its nearest centroid in L2 distance (the map "CQ(.)" of Eq. 5).
+ *   cq_decode_attention  Section 2.1, Eq. 1: attention of one new token over all cached tokens,
+ *                        out = [v_1..v_t] softmax([k_1..k_t]^T q), where k_i, v_i are the centroids
+ *                        selected by the cached codes.  The library never materialises k_i / v_i:
+ *                        by linearity q.k_i is a sum over groups of (q_g . centroid) looked up by
+ *                        code, and sum_i p_i v_i is regrouped by code; both are exact rewrites of
+ *                        Eq. 1.
+ *
+ * Conventions
+ *   - plain C ABI; no C++ or framework types cross it;
+ *   - every data pointer is a DEVICE pointer owned by the caller, 16-byte aligned; the library
+ *     allocates no device memory, keeps no state and never synchronises;
+ *   - work is enqueued on `stream` (a hipStream_t passed as void*; NULL = the default stream);
+ *   - every call validates its arguments on the host before touching the GPU and returns a
+ *     cq_status; nothing is launched unless the status is CQ_OK;
+ *   - fp16 means IEEE-754 binary16.  Inputs must be finite.
+ *
+ * Where the paper is silent this library takes these readings: ties in the nearest-centroid
+ * search go to the lowest index; the softmax scale is an explicit argument (Eq. 1 has none);
+ * query head h reads KV head h / (n_q_heads / n_kv_heads); the stored key is the key the query
+ * is dotted with (no positional rotation is applied to dequantized keys).
+ *
+ * Packed code cache (the paper fixes only its density, b / c bits per stored number -- the
+ * "Bits Per FPN" column of Table 1; the arrangement below is this library's):
+ *   - one stream per (sequence n, KV head h), streams ordered [n][h];
+ *   - a stream is t_cap / 64 tiles of 64 tokens (t_cap is a multiple of 64); a tile holds
+ *     64 * Gh * b / 8 bytes, Gh = head_dim / c groups per head;
+ *   - b = 8: a tile is Gh / 16 planes of 64 x 16 bytes.  Byte w of token u's 16 bytes in plane p
+ *     is slot s = 16 p + w and holds the code of group (s + u) mod Gh of that head.  (The
+ *     per-token rotation makes the 64 tokens of a tile touch 64 different lookup-table
+ *     columns at every step of the decode kernel.)
+ *   - b = 10 (Gh = 16 only): a 64 x 16-byte plane with the low 8 bits of the code of each slot
+ *     (same rotation), then a 64 x 4-byte plane with one little-endian uint32 per token whose
+ *     bits [2 s + 1 : 2 s] are the high two bits of the code in slot s.
+ *   Supported formats: b = 8 with Gh in {16, 32, 64}; b = 10 with Gh = 16.
+ */
+#ifndef LIBCQ_H
+#define LIBCQ_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#if defined(__GNUC__)
+#define CQ_API __attribute__((visibility("default")))
+#else
+#define CQ_API
+#endif
+
+typedef enum cq_status {
+    CQ_OK = 0,
+    CQ_ERR_INVALID_ARG = 1,          /* null pointer, non-positive size, inconsistent shapes */
+    CQ_ERR_UNSUPPORTED = 2,          /* a (c, b, head_dim) with no kernel */
+    CQ_ERR_WORKSPACE_TOO_SMALL = 3,
+    CQ_ERR_HIP = 4                   /* the HIP runtime refused a launch */
+} cq_status;
+
+/* CQ-<c>c<b>b of Section 3.2, plus the shape of the KV embedding it applies to. */
+typedef struct cq_format {
+    int32_t c;            /* channels per coupled group; divides head_dim */
+    int32_t b;            /* bits per code; 2^b centroids per group */
+    int32_t head_dim;     /* channels of one head */
+    int32_t n_kv_heads;   /* KV heads; D = n_kv_heads * head_dim channels, G = D / c groups */
+} cq_format;
+
+#define CQ_TILE_TOKENS 64
+
+/* Library version, major * 10000 + minor * 100 + patch. */
+CQ_API int32_t cq_version(void);
+
+/* Static string naming a status code. */
+CQ_API const char *cq_status_string(cq_status status);
+
+/* CQ_OK if the format has kernels, else CQ_ERR_INVALID_ARG / CQ_ERR_UNSUPPORTED.  Host only. */
+CQ_API cq_status cq_format_check(const cq_format *fmt);
+
+/* Bytes of packed codes of one token of one KV head: (head_dim / c) * b / 8
+ * (16 / 32 / 64 / 20 for CQ-8c8b / 4c8b / 2c8b / 8c10b at head_dim 128).  0 on a bad format. */
+CQ_API size_t cq_code_bytes_per_token_head(const cq_format *fmt);
+
+/* Bytes of one packed cache (K or V of one layer) for `batch` sequences of capacity t_cap
+ * tokens (multiple of 64).  0 on bad arguments. */
+CQ_API size_t cq_cache_bytes(const cq_format *fmt, int32_t batch, int32_t t_cap);
+
+/*
+ * cq_encode -- Section 3.2 of the paper (nearest centroid per channel group), packed store.
+ *
+ *   x               device, fp16 [batch][t_new][D]; element strides x_batch_stride and
+ *                   x_row_stride (>= D) are given in fp16 elements; rows 16-byte aligned
+ *   centroids       device, fp16 [G][2^b][c]
+ *   codes           device, packed cache of cq_cache_bytes(fmt, batch, t_cap) bytes; the codes of
+ *                   token t of sequence n are written at cache position t_offset + t; other
+ *                   positions are left untouched
+ *   Distances are sum_i (x_i - centroid_i)^2 evaluated in fp32 in channel order; the lowest
+ *   index wins ties.
+ * Errors: CQ_ERR_INVALID_ARG for null pointers, batch/t_new <= 0, t_cap not a multiple of 64,
+ * t_offset < 0 or t_offset + t_new > t_cap, strides too small or misaligned;
+ * CQ_ERR_UNSUPPORTED for a format without kernels; CQ_ERR_HIP if a launch fails.
+ */
+CQ_API cq_status cq_encode(const void *x, int64_t x_batch_stride, int64_t x_row_stride,
+                    const void *centroids, const cq_format *fmt,
+                    int32_t batch, int32_t t_new,
+                    void *codes, int32_t t_offset, int32_t t_cap,
+                    void *stream);
+
+/* Tokens per context split the library would pick for this problem (a multiple of 64). */
+CQ_API int32_t cq_decode_default_split(const cq_format *fmt, int32_t batch, int32_t n_q_heads, int32_t t);
+
+/* Workspace bytes cq_decode_attention needs for up to t cached tokens when run with
+ * tokens_per_split (0 = the library's default).  0 on bad arguments. */
+CQ_API size_t cq_decode_workspace_bytes(const cq_format *fmt, int32_t batch, int32_t n_q_heads,
+                                 int32_t t, int32_t tokens_per_split);
+
+/*
+ * cq_decode_attention -- Eq. 1 of the paper for one query token per sequence, computed from
+ * packed codes (see the top of this file for the rewrite used).
+ *
+ *   q                 device, fp16 [batch][n_q_heads][head_dim]
+ *   k_codes, v_codes  device, packed caches (layout above) with capacity t_cap
+ *   k_centroids, v_centroids   device, fp16 [G][2^b][c]
+ *   scale             multiplies q.k before the softmax (e.g. 1/sqrt(head_dim))
+ *   t                 cached tokens attended per sequence (positions 0 .. t-1), 1 <= t <= t_cap
+ *   seq_lens          device int32 [batch] or NULL; if given, sequence n attends positions
+ *                     0 .. seq_lens[n]-1; values must lie in [1, t] (not checked on the host;
+ *                     the kernels clamp them into that range)
+ *   tokens_per_split  0 = library default; otherwise a multiple of 64: each workgroup handles
+ *                     that many tokens of one (sequence, query head) and a second kernel merges
+ *                     the partial softmax results (exact rescaling by the running maximum)
+ *   out               device, fp16 [batch][n_q_heads][head_dim]
+ *   workspace         device scratch of at least cq_decode_workspace_bytes(...) bytes; contents
+ *                     need not be initialised and are overwritten
+ *   Arithmetic: fp32 lookup tables, scores, softmax and accumulation; the result is rounded to
+ *   fp16 once (round to nearest even).
+ * Errors: as cq_encode, plus CQ_ERR_INVALID_ARG when n_q_heads is not a multiple of
+ * n_kv_heads or tokens_per_split is not a positive multiple of 64 (or too large for the
+ * kernel's on-chip score buffer), and CQ_ERR_WORKSPACE_TOO_SMALL.
+ */
+CQ_API cq_status cq_decode_attention(const void *q,
+                              const void *k_codes, const void *v_codes,
+                              const void *k_centroids, const void *v_centroids,
+                              float scale, const cq_format *fmt,
+                              int32_t batch, int32_t n_q_heads, int32_t t, int32_t t_cap,
+                              const int32_t *seq_lens, int32_t tokens_per_split,
+                              void *out, void *workspace, size_t workspace_bytes,
+                              void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LIBCQ_H */

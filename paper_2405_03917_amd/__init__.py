@@ -1,0 +1,233 @@
+"""Python binding of libcq, the MI355X-native hot path of Coupled Quantization (CQ).
+
+Argument marshalling only: every function here forwards to the C-ABI entry point of the same
+name in ``libcq.so`` (declared in ``include/libcq.h``); all arithmetic runs in the library's HIP
+kernels.  PyTorch supplies device memory and streams.  There is no fallback: if the shared
+library has not been built (``python -m paper_2405_03917_amd.build``) importing the functions
+works but the first call raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from dataclasses import dataclass
+from typing import Optional
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libcq.so")
+
+CQ_OK = 0
+CQ_ERR_INVALID_ARG = 1
+CQ_ERR_UNSUPPORTED = 2
+CQ_ERR_WORKSPACE_TOO_SMALL = 3
+CQ_ERR_HIP = 4
+TILE_TOKENS = 64
+
+EXPORTS = (
+    "cq_version", "cq_status_string", "cq_format_check", "cq_code_bytes_per_token_head",
+    "cq_cache_bytes", "cq_encode", "cq_decode_default_split", "cq_decode_workspace_bytes",
+    "cq_decode_attention",
+)
+
+
+class CQError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {status_string(status)}")
+
+
+class _Format(ctypes.Structure):
+    _fields_ = [("c", ctypes.c_int32), ("b", ctypes.c_int32),
+                ("head_dim", ctypes.c_int32), ("n_kv_heads", ctypes.c_int32)]
+
+
+@dataclass(frozen=True)
+class CQFormat:
+    """CQ-<c>c<b>b (Section 3.2 of the paper) on ``n_kv_heads`` heads of ``head_dim`` channels."""
+    c: int
+    b: int
+    head_dim: int
+    n_kv_heads: int
+
+    def _c(self) -> _Format:
+        return _Format(self.c, self.b, self.head_dim, self.n_kv_heads)
+
+    @property
+    def channels(self) -> int:
+        return self.head_dim * self.n_kv_heads
+
+    @property
+    def groups(self) -> int:
+        return self.channels // self.c
+
+
+_lib = None
+
+
+def load() -> ctypes.CDLL:
+    """dlopen libcq.so and declare its prototypes.  Raises if it has not been built."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise FileNotFoundError(
+            f"{LIB_PATH} is missing: build it with `python -m paper_2405_03917_amd.build` "
+            "(there is no non-HIP fallback)")
+    lib = ctypes.CDLL(LIB_PATH)
+    fp = ctypes.POINTER(_Format)
+    vp = ctypes.c_void_p
+    i32 = ctypes.c_int32
+    i64 = ctypes.c_int64
+    lib.cq_version.restype = i32
+    lib.cq_version.argtypes = []
+    lib.cq_status_string.restype = ctypes.c_char_p
+    lib.cq_status_string.argtypes = [ctypes.c_int]
+    lib.cq_format_check.restype = ctypes.c_int
+    lib.cq_format_check.argtypes = [fp]
+    lib.cq_code_bytes_per_token_head.restype = ctypes.c_size_t
+    lib.cq_code_bytes_per_token_head.argtypes = [fp]
+    lib.cq_cache_bytes.restype = ctypes.c_size_t
+    lib.cq_cache_bytes.argtypes = [fp, i32, i32]
+    lib.cq_encode.restype = ctypes.c_int
+    lib.cq_encode.argtypes = [vp, i64, i64, vp, fp, i32, i32, vp, i32, i32, vp]
+    lib.cq_decode_default_split.restype = i32
+    lib.cq_decode_default_split.argtypes = [fp, i32, i32, i32]
+    lib.cq_decode_workspace_bytes.restype = ctypes.c_size_t
+    lib.cq_decode_workspace_bytes.argtypes = [fp, i32, i32, i32, i32]
+    lib.cq_decode_attention.restype = ctypes.c_int
+    lib.cq_decode_attention.argtypes = [vp, vp, vp, vp, vp, ctypes.c_float, fp, i32, i32, i32, i32,
+                                        vp, i32, vp, vp, ctypes.c_size_t, vp]
+    _lib = lib
+    return lib
+
+
+def cq_version() -> int:
+    return int(load().cq_version())
+
+
+def status_string(status: int) -> str:
+    return load().cq_status_string(int(status)).decode()
+
+
+def cq_format_check(fmt: CQFormat) -> int:
+    f = fmt._c()
+    return int(load().cq_format_check(ctypes.byref(f)))
+
+
+def cq_code_bytes_per_token_head(fmt: CQFormat) -> int:
+    f = fmt._c()
+    return int(load().cq_code_bytes_per_token_head(ctypes.byref(f)))
+
+
+def cq_cache_bytes(fmt: CQFormat, batch: int, t_cap: int) -> int:
+    f = fmt._c()
+    return int(load().cq_cache_bytes(ctypes.byref(f), batch, t_cap))
+
+
+def cq_decode_default_split(fmt: CQFormat, batch: int, n_q_heads: int, t: int) -> int:
+    f = fmt._c()
+    return int(load().cq_decode_default_split(ctypes.byref(f), batch, n_q_heads, t))
+
+
+def cq_decode_workspace_bytes(fmt: CQFormat, batch: int, n_q_heads: int, t: int,
+                              tokens_per_split: int = 0) -> int:
+    f = fmt._c()
+    return int(load().cq_decode_workspace_bytes(ctypes.byref(f), batch, n_q_heads, t, tokens_per_split))
+
+
+def _stream_handle(stream) -> int:
+    import torch
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return int(stream.cuda_stream)
+
+
+def _dev(t, dtype, what: str):
+    import torch
+    if not isinstance(t, torch.Tensor) or not t.is_cuda:
+        raise TypeError(f"{what} must be a CUDA/HIP tensor")
+    if t.dtype != dtype:
+        raise TypeError(f"{what} must have dtype {dtype}, got {t.dtype}")
+    return t
+
+
+def alloc_cache(fmt: CQFormat, batch: int, t_cap: int, device="cuda"):
+    """uint8 device buffer of cq_cache_bytes(fmt, batch, t_cap) bytes (uninitialised)."""
+    import torch
+    n = cq_cache_bytes(fmt, batch, t_cap)
+    if n == 0:
+        raise CQError(CQ_ERR_INVALID_ARG, "cq_cache_bytes")
+    return torch.empty(n, dtype=torch.uint8, device=device)
+
+
+def cq_encode(x, centroids, fmt: CQFormat, codes, t_offset: int, t_cap: int, stream=None) -> None:
+    """x fp16 [B, T_new, D] (last dim contiguous), centroids fp16 [G, 2^b, c] contiguous,
+    codes uint8 packed cache; writes the codes of the new tokens at positions t_offset..."""
+    import torch
+    _dev(x, torch.float16, "x")
+    _dev(centroids, torch.float16, "centroids")
+    _dev(codes, torch.uint8, "codes")
+    if x.dim() != 3 or x.stride(2) != 1:
+        raise ValueError("x must be [B, T_new, D] with a contiguous last dimension")
+    if not centroids.is_contiguous() or not codes.is_contiguous():
+        raise ValueError("centroids and codes must be contiguous")
+    if tuple(centroids.shape) != (fmt.groups, 1 << fmt.b, fmt.c) or x.shape[2] != fmt.channels:
+        raise ValueError("shapes do not match the format")
+    batch, t_new = int(x.shape[0]), int(x.shape[1])
+    if codes.numel() < cq_cache_bytes(fmt, batch, t_cap):
+        raise ValueError("codes buffer is smaller than cq_cache_bytes(fmt, batch, t_cap)")
+    f = fmt._c()
+    st = load().cq_encode(x.data_ptr(), x.stride(0), x.stride(1), centroids.data_ptr(), ctypes.byref(f),
+                          batch, t_new, codes.data_ptr(), t_offset, t_cap, _stream_handle(stream))
+    if st != CQ_OK:
+        raise CQError(st, "cq_encode")
+
+
+def cq_decode_attention(q, k_codes, v_codes, k_centroids, v_centroids, scale: float, fmt: CQFormat,
+                        t: int, t_cap: int, seq_lens=None, tokens_per_split: int = 0,
+                        out=None, workspace=None, stream=None):
+    """q fp16 [B, Hq, head_dim]; packed caches uint8; centroids fp16 [G, 2^b, c].  Returns out
+    fp16 [B, Hq, head_dim] (allocated with torch if not given, as is the workspace)."""
+    import torch
+    _dev(q, torch.float16, "q")
+    _dev(k_codes, torch.uint8, "k_codes")
+    _dev(v_codes, torch.uint8, "v_codes")
+    _dev(k_centroids, torch.float16, "k_centroids")
+    _dev(v_centroids, torch.float16, "v_centroids")
+    if q.dim() != 3 or not q.is_contiguous() or q.shape[2] != fmt.head_dim:
+        raise ValueError("q must be contiguous [B, Hq, head_dim]")
+    for name, cb in (("k_centroids", k_centroids), ("v_centroids", v_centroids)):
+        if not cb.is_contiguous() or tuple(cb.shape) != (fmt.groups, 1 << fmt.b, fmt.c):
+            raise ValueError(f"{name} must be contiguous [G, 2^b, c]")
+    batch, n_q_heads = int(q.shape[0]), int(q.shape[1])
+    need_cache = cq_cache_bytes(fmt, batch, t_cap)
+    if k_codes.numel() < need_cache or v_codes.numel() < need_cache:
+        raise ValueError("code caches are smaller than cq_cache_bytes(fmt, batch, t_cap)")
+    sl_ptr = None
+    if seq_lens is not None:
+        _dev(seq_lens, torch.int32, "seq_lens")
+        if tuple(seq_lens.shape) != (batch,) or not seq_lens.is_contiguous():
+            raise ValueError("seq_lens must be contiguous int32 [B]")
+        sl_ptr = seq_lens.data_ptr()
+    if out is None:
+        out = torch.empty((batch, n_q_heads, fmt.head_dim), dtype=torch.float16, device=q.device)
+    else:
+        _dev(out, torch.float16, "out")
+        if tuple(out.shape) != (batch, n_q_heads, fmt.head_dim) or not out.is_contiguous():
+            raise ValueError("out must be contiguous [B, Hq, head_dim]")
+    if workspace is None:
+        nbytes = cq_decode_workspace_bytes(fmt, batch, n_q_heads, t, tokens_per_split)
+        if nbytes == 0:
+            raise CQError(CQ_ERR_INVALID_ARG, "cq_decode_workspace_bytes")
+        workspace = torch.empty(nbytes, dtype=torch.uint8, device=q.device)
+    else:
+        _dev(workspace, torch.uint8, "workspace")
+    f = fmt._c()
+    st = load().cq_decode_attention(q.data_ptr(), k_codes.data_ptr(), v_codes.data_ptr(),
+                                    k_centroids.data_ptr(), v_centroids.data_ptr(), float(scale),
+                                    ctypes.byref(f), batch, n_q_heads, t, t_cap, sl_ptr,
+                                    tokens_per_split, out.data_ptr(), workspace.data_ptr(),
+                                    workspace.numel(), _stream_handle(stream))
+    if st != CQ_OK:
+        raise CQError(st, "cq_decode_attention")
+    return out

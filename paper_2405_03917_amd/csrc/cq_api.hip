@@ -1,0 +1,193 @@
+// Host entry points of libcq: argument validation, sizing helpers and dispatch.
+// Every check here runs before any HIP call, so error paths can be exercised without a GPU.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cmath>
+
+#include "cq_internal.hpp"
+
+namespace cq {
+
+cq_status derive(const cq_format* fmt, Derived* out)
+{
+    if (!fmt) return CQ_ERR_INVALID_ARG;
+    if (fmt->c <= 0 || fmt->b <= 0 || fmt->head_dim <= 0 || fmt->n_kv_heads <= 0) return CQ_ERR_INVALID_ARG;
+    if (fmt->head_dim % fmt->c != 0) return CQ_ERR_INVALID_ARG;
+    Derived d;
+    d.c = fmt->c;
+    d.b = fmt->b;
+    d.head_dim = fmt->head_dim;
+    d.n_kv_heads = fmt->n_kv_heads;
+    d.gh = fmt->head_dim / fmt->c;
+    const bool ok8 = fmt->b == 8 && (fmt->c == 2 || fmt->c == 4 || fmt->c == 8) && fmt->head_dim == 128;
+    const bool ok10 = fmt->b == 10 && fmt->c == 8 && fmt->head_dim == 128;
+    if (!ok8 && !ok10) return CQ_ERR_UNSUPPORTED;
+    d.k = 1 << fmt->b;
+    d.channels = fmt->n_kv_heads * fmt->head_dim;
+    d.groups = d.channels / fmt->c;
+    d.bpth = d.gh * fmt->b / 8;
+    d.tile_bytes = kTileTokens * d.bpth;
+    if (out) *out = d;
+    return CQ_OK;
+}
+
+namespace {
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+int default_tiles_per_split(const Derived& f, int batch, int n_q_heads, int t)
+{
+    const int n_tiles = (t + kTileTokens - 1) / kTileTokens;
+    const long bh = (long)batch * n_q_heads;
+    const int max_tiles = std::min(63, decode_max_tiles_per_split(f));
+    // enough workgroups to fill 256 CUs a few times over, but splits long enough that building
+    // the lookup table (a fixed cost per workgroup) stays small against the streamed codes
+    const long want_wg = 2048;
+    long n_split = std::max(1L, (want_wg + bh - 1) / bh);
+    const int min_tiles = 16;
+    n_split = std::min<long>(n_split, std::max(1, n_tiles / min_tiles));
+    int tiles = (int)((n_tiles + n_split - 1) / n_split);
+    tiles = std::max(1, std::min(tiles, max_tiles));
+    return tiles;
+}
+
+}  // namespace
+}  // namespace cq
+
+using namespace cq;
+
+extern "C" {
+
+int32_t cq_version(void) { return 100; }
+
+const char* cq_status_string(cq_status status)
+{
+    switch (status) {
+        case CQ_OK: return "CQ_OK";
+        case CQ_ERR_INVALID_ARG: return "CQ_ERR_INVALID_ARG";
+        case CQ_ERR_UNSUPPORTED: return "CQ_ERR_UNSUPPORTED";
+        case CQ_ERR_WORKSPACE_TOO_SMALL: return "CQ_ERR_WORKSPACE_TOO_SMALL";
+        case CQ_ERR_HIP: return "CQ_ERR_HIP";
+    }
+    return "CQ_ERR_UNKNOWN";
+}
+
+cq_status cq_format_check(const cq_format* fmt) { return derive(fmt, nullptr); }
+
+size_t cq_code_bytes_per_token_head(const cq_format* fmt)
+{
+    Derived f;
+    if (derive(fmt, &f) != CQ_OK) return 0;
+    return (size_t)f.bpth;
+}
+
+size_t cq_cache_bytes(const cq_format* fmt, int32_t batch, int32_t t_cap)
+{
+    Derived f;
+    if (derive(fmt, &f) != CQ_OK) return 0;
+    if (batch <= 0 || t_cap <= 0 || t_cap % kTileTokens != 0) return 0;
+    return (size_t)batch * f.n_kv_heads * (t_cap / kTileTokens) * f.tile_bytes;
+}
+
+cq_status cq_encode(const void* x, int64_t x_batch_stride, int64_t x_row_stride,
+                    const void* centroids, const cq_format* fmt,
+                    int32_t batch, int32_t t_new,
+                    void* codes, int32_t t_offset, int32_t t_cap, void* stream)
+{
+    Derived f;
+    const cq_status st = derive(fmt, &f);
+    if (st != CQ_OK) return st;
+    if (!x || !centroids || !codes) return CQ_ERR_INVALID_ARG;
+    if (batch <= 0 || t_new <= 0 || t_cap <= 0 || t_cap % kTileTokens != 0) return CQ_ERR_INVALID_ARG;
+    if (batch > 65535 || f.n_kv_heads > 65535) return CQ_ERR_INVALID_ARG;
+    if (t_offset < 0 || (int64_t)t_offset + t_new > t_cap) return CQ_ERR_INVALID_ARG;
+    if (x_row_stride < f.channels || x_row_stride % 8 != 0) return CQ_ERR_INVALID_ARG;
+    if (batch > 1 && (x_batch_stride < (int64_t)t_new * x_row_stride || x_batch_stride % 8 != 0))
+        return CQ_ERR_INVALID_ARG;
+    if (!aligned16(x) || !aligned16(centroids) || !aligned16(codes)) return CQ_ERR_INVALID_ARG;
+
+    EncodeArgs a;
+    a.x = static_cast<const uint16_t*>(x);
+    a.x_batch_stride = x_batch_stride;
+    a.x_row_stride = x_row_stride;
+    a.centroids = static_cast<const uint16_t*>(centroids);
+    a.codes = static_cast<uint8_t*>(codes);
+    a.batch = batch;
+    a.t_new = t_new;
+    a.t_offset = t_offset;
+    a.t_cap = t_cap;
+    a.f = f;
+    return launch_encode(a, static_cast<hipStream_t>(stream));
+}
+
+int32_t cq_decode_default_split(const cq_format* fmt, int32_t batch, int32_t n_q_heads, int32_t t)
+{
+    Derived f;
+    if (derive(fmt, &f) != CQ_OK || batch <= 0 || n_q_heads <= 0 || t <= 0) return 0;
+    return default_tiles_per_split(f, batch, n_q_heads, t) * kTileTokens;
+}
+
+size_t cq_decode_workspace_bytes(const cq_format* fmt, int32_t batch, int32_t n_q_heads,
+                                 int32_t t, int32_t tokens_per_split)
+{
+    Derived f;
+    if (derive(fmt, &f) != CQ_OK || batch <= 0 || n_q_heads <= 0 || t <= 0) return 0;
+    if (tokens_per_split < 0 || tokens_per_split % kTileTokens != 0) return 0;
+    const int tiles = tokens_per_split ? tokens_per_split / kTileTokens
+                                       : default_tiles_per_split(f, batch, n_q_heads, t);
+    if (tiles > decode_max_tiles_per_split(f)) return 0;
+    const int n_tiles = (t + kTileTokens - 1) / kTileTokens;
+    const int n_split = (n_tiles + tiles - 1) / tiles;
+    return sizeof(float) * (size_t)batch * n_q_heads * n_split * (f.head_dim + kPartialHeader);
+}
+
+cq_status cq_decode_attention(const void* q, const void* k_codes, const void* v_codes,
+                              const void* k_centroids, const void* v_centroids,
+                              float scale, const cq_format* fmt,
+                              int32_t batch, int32_t n_q_heads, int32_t t, int32_t t_cap,
+                              const int32_t* seq_lens, int32_t tokens_per_split,
+                              void* out, void* workspace, size_t workspace_bytes, void* stream)
+{
+    Derived f;
+    const cq_status st = derive(fmt, &f);
+    if (st != CQ_OK) return st;
+    if (!q || !k_codes || !v_codes || !k_centroids || !v_centroids || !out || !workspace)
+        return CQ_ERR_INVALID_ARG;
+    if (batch <= 0 || n_q_heads <= 0 || n_q_heads % f.n_kv_heads != 0) return CQ_ERR_INVALID_ARG;
+    if (t_cap <= 0 || t_cap % kTileTokens != 0 || t <= 0 || t > t_cap) return CQ_ERR_INVALID_ARG;
+    if (!std::isfinite(scale)) return CQ_ERR_INVALID_ARG;
+    if (tokens_per_split < 0 || tokens_per_split % kTileTokens != 0) return CQ_ERR_INVALID_ARG;
+    if (!aligned16(q) || !aligned16(k_codes) || !aligned16(v_codes) || !aligned16(k_centroids) ||
+        !aligned16(v_centroids) || !aligned16(out) || !aligned16(workspace))
+        return CQ_ERR_INVALID_ARG;
+    const int tiles = tokens_per_split ? tokens_per_split / kTileTokens
+                                       : default_tiles_per_split(f, batch, n_q_heads, t);
+    if (tiles > decode_max_tiles_per_split(f)) return CQ_ERR_INVALID_ARG;
+    const int n_tiles = (t + kTileTokens - 1) / kTileTokens;
+    const int n_split = (n_tiles + tiles - 1) / tiles;
+    const size_t need = sizeof(float) * (size_t)batch * n_q_heads * n_split * (f.head_dim + kPartialHeader);
+    if (workspace_bytes < need) return CQ_ERR_WORKSPACE_TOO_SMALL;
+    if ((int64_t)batch * n_q_heads * n_split > 0x7fffffffLL) return CQ_ERR_INVALID_ARG;
+
+    DecodeArgs a;
+    a.q = static_cast<const uint16_t*>(q);
+    a.k_codes = static_cast<const uint8_t*>(k_codes);
+    a.v_codes = static_cast<const uint8_t*>(v_codes);
+    a.k_centroids = static_cast<const uint16_t*>(k_centroids);
+    a.v_centroids = static_cast<const uint16_t*>(v_centroids);
+    a.scale_log2e = scale * 1.4426950408889634f;
+    a.batch = batch;
+    a.n_q_heads = n_q_heads;
+    a.t = t;
+    a.t_cap = t_cap;
+    a.seq_lens = seq_lens;
+    a.tiles_per_split = tiles;
+    a.n_split = n_split;
+    a.partials = static_cast<float*>(workspace);
+    a.out = static_cast<uint16_t*>(out);
+    a.f = f;
+    return launch_decode(a, static_cast<hipStream_t>(stream));
+}
+
+}  // extern "C"

@@ -1,0 +1,273 @@
+// Nearest-centroid encoding of key/value activations (Section 3.2 of the paper) for gfx950.
+//
+// Two kernels, picked by the number of new tokens per sequence:
+//   encode_tokens_kernel     (prefill: many tokens)  lane = token.  A workgroup takes a block of
+//       64-token cache tiles of one (sequence, KV head), walks the head's groups, stages each
+//       group's codebook in LDS as fp32 (double buffered) and scans it in ascending index order
+//       with all lanes reading the same centroid (LDS broadcast).  Codes are collected in LDS in
+//       cache order and stored with 16-byte writes.
+//   encode_centroids_kernel  (decode step: a handful of tokens)  lane = centroid.  A workgroup
+//       takes one group and up to 16 tokens; every thread keeps its centroids in registers and
+//       the minimum over (distance, index) pairs is reduced across the workgroup.
+// Both evaluate sum_i (x_i - c_i)^2 in fp32 with one fused multiply-add per channel, in channel
+// order, and break ties towards the lowest index.
+#include <hip/hip_runtime.h>
+
+#include "cq_internal.hpp"
+
+namespace cq {
+namespace {
+
+typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
+
+template <int C>
+__device__ __forceinline__ void load_halfs(const uint16_t* p, float (&v)[C])
+{
+    if constexpr (C == 8) {
+        const uint4 a = *reinterpret_cast<const uint4*>(p);
+        const unsigned w[4] = {a.x, a.y, a.z, a.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const half2_t h = __builtin_bit_cast(half2_t, w[i]);
+            v[2 * i] = (float)h.x;
+            v[2 * i + 1] = (float)h.y;
+        }
+    } else if constexpr (C == 4) {
+        const uint2 a = *reinterpret_cast<const uint2*>(p);
+        const half2_t h0 = __builtin_bit_cast(half2_t, a.x), h1 = __builtin_bit_cast(half2_t, a.y);
+        v[0] = (float)h0.x; v[1] = (float)h0.y; v[2] = (float)h1.x; v[3] = (float)h1.y;
+    } else {
+        static_assert(C == 2, "channels per group must be 2, 4 or 8");
+        const unsigned a = *reinterpret_cast<const unsigned*>(p);
+        const half2_t h = __builtin_bit_cast(half2_t, a);
+        v[0] = (float)h.x; v[1] = (float)h.y;
+    }
+}
+
+template <int C>
+__device__ __forceinline__ float sq_dist(const float (&x)[C], const float (&c)[C])
+{
+    float acc = 0.f;
+#pragma unroll
+    for (int i = 0; i < C; ++i) {
+        const float d = x[i] - c[i];
+        acc = __builtin_fmaf(d, d, acc);
+    }
+    return acc;
+}
+
+// ------------------------------------------------------------------------------------------
+// lane = token
+// ------------------------------------------------------------------------------------------
+template <int GH, int C, int B, int NW, int TPL>
+__global__ __launch_bounds__(NW * 64) void encode_tokens_kernel(EncodeArgs a)
+{
+    constexpr int K = 1 << B;
+    constexpr int NT = NW * 64;
+    constexpr int P = GH / 16;                       // 16-byte planes of low code bytes
+    constexpr int TILE_LOW = kTileTokens * GH;       // bytes of the low-byte planes of a tile
+    constexpr int TILE_BYTES = kTileTokens * GH * B / 8;
+    constexpr int TILES_PER_WG = NW * TPL;
+
+    __shared__ float cb[2][K * C];
+    __shared__ __attribute__((aligned(16))) uint8_t rec[TILES_PER_WG][TILE_LOW];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    const int hkv = blockIdx.y;
+    const int n = blockIdx.z;
+
+    const int first_tile = a.t_offset / kTileTokens;
+    const int t_end = a.t_offset + a.t_new;           // one past the last cache position
+    const int wg_tile = first_tile + blockIdx.x * TILES_PER_WG;
+
+    // this lane's tokens: one per tile, tiles wg_tile + wave*TPL + k
+    int pos[TPL];
+    bool valid[TPL];
+    const uint16_t* xrow[TPL];
+#pragma unroll
+    for (int k = 0; k < TPL; ++k) {
+        pos[k] = (wg_tile + wave * TPL + k) * kTileTokens + lane;
+        valid[k] = pos[k] >= a.t_offset && pos[k] < t_end;
+        const int t = valid[k] ? pos[k] - a.t_offset : 0;
+        xrow[k] = a.x + (size_t)n * a.x_batch_stride + (size_t)t * a.x_row_stride + (size_t)hkv * GH * C;
+    }
+
+    auto stage = [&](int g, int buf) {
+        const uint16_t* src = a.centroids + (size_t)(hkv * GH + g) * K * C;
+        for (int i = tid * 2; i < K * C; i += NT * 2) {
+            const half2_t h = *reinterpret_cast<const half2_t*>(src + i);
+            cb[buf][i] = (float)h.x;
+            cb[buf][i + 1] = (float)h.y;
+        }
+    };
+
+    unsigned hi_word[TPL];
+#pragma unroll
+    for (int k = 0; k < TPL; ++k) hi_word[k] = 0;
+
+    stage(0, 0);
+    __syncthreads();
+    for (int g = 0; g < GH; ++g) {
+        const int buf = g & 1;
+        if (g + 1 < GH) stage(g + 1, buf ^ 1);
+
+        float x[TPL][C];
+#pragma unroll
+        for (int k = 0; k < TPL; ++k) load_halfs<C>(xrow[k] + g * C, x[k]);
+
+        float best[TPL];
+        int code[TPL];
+#pragma unroll
+        for (int k = 0; k < TPL; ++k) { best[k] = INFINITY; code[k] = 0; }
+
+        const float* cbuf = cb[buf];
+#pragma unroll 4
+        for (int j = 0; j < K; ++j) {
+            float cen[C];
+#pragma unroll
+            for (int i = 0; i < C; ++i) cen[i] = cbuf[j * C + i];
+#pragma unroll
+            for (int k = 0; k < TPL; ++k) {
+                const float d = sq_dist<C>(x[k], cen);
+                if (d < best[k]) { best[k] = d; code[k] = j; }      // strict: lowest index wins ties
+            }
+        }
+
+        const int slot = (g - lane) & (GH - 1);
+#pragma unroll
+        for (int k = 0; k < TPL; ++k) {
+            rec[wave * TPL + k][(slot >> 4) * 1024 + lane * 16 + (slot & 15)] = (uint8_t)(code[k] & 0xff);
+            if constexpr (B == 10) hi_word[k] |= (unsigned)(code[k] >> 8) << (2 * slot);
+        }
+        __syncthreads();
+    }
+
+    // store this lane's records
+    const size_t stream = (size_t)(n * a.f.n_kv_heads + hkv) * (a.t_cap / kTileTokens) * TILE_BYTES;
+#pragma unroll
+    for (int k = 0; k < TPL; ++k) {
+        if (!valid[k]) continue;
+        uint8_t* tile = a.codes + stream + (size_t)(pos[k] / kTileTokens) * TILE_BYTES;
+#pragma unroll
+        for (int p = 0; p < P; ++p) {
+            const uint4 v = *reinterpret_cast<const uint4*>(&rec[wave * TPL + k][p * 1024 + lane * 16]);
+            *reinterpret_cast<uint4*>(tile + p * 1024 + lane * 16) = v;
+        }
+        if constexpr (B == 10) *reinterpret_cast<unsigned*>(tile + TILE_LOW + lane * 4) = hi_word[k];
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// lane = centroid
+// ------------------------------------------------------------------------------------------
+constexpr int kSmallTokens = 16;     // tokens per workgroup of the lane = centroid kernel
+
+template <int GH, int C, int B>
+__global__ __launch_bounds__(256) void encode_centroids_kernel(EncodeArgs a)
+{
+    constexpr int K = 1 << B;
+    constexpr int KP = K / 256;                      // centroids per thread
+    constexpr int TILE_LOW = kTileTokens * GH;
+    constexpr int TILE_BYTES = kTileTokens * GH * B / 8;
+    __shared__ unsigned long long wkey[kSmallTokens][4];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    const int g_abs = blockIdx.x;
+    const int total = a.batch * a.t_new;
+    const int tt0 = blockIdx.y * kSmallTokens;
+    const int ntok = min(kSmallTokens, total - tt0);
+
+    float cen[KP][C];
+#pragma unroll
+    for (int kp = 0; kp < KP; ++kp)
+        load_halfs<C>(a.centroids + ((size_t)g_abs * K + kp * 256 + tid) * C, cen[kp]);
+
+    for (int i = 0; i < ntok; ++i) {
+        const int tt = tt0 + i;
+        const int n = tt / a.t_new, t = tt % a.t_new;
+        float x[C];
+        load_halfs<C>(a.x + (size_t)n * a.x_batch_stride + (size_t)t * a.x_row_stride + (size_t)g_abs * C, x);
+        unsigned long long key = ~0ull;
+#pragma unroll
+        for (int kp = 0; kp < KP; ++kp) {
+            const float d = sq_dist<C>(x, cen[kp]);
+            // d >= +0, so its bit pattern orders like the value; the index in the low word
+            // makes the minimum pick the lowest index among equal distances
+            const unsigned long long kk = ((unsigned long long)__float_as_uint(d) << 32) | (unsigned)(kp * 256 + tid);
+            key = kk < key ? kk : key;
+        }
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) {
+            const unsigned long long other = __shfl_xor(key, o);
+            key = other < key ? other : key;
+        }
+        if (lane == 0) wkey[i][wave] = key;
+    }
+    __syncthreads();
+    if (tid < ntok) {
+        unsigned long long key = wkey[tid][0];
+#pragma unroll
+        for (int w = 1; w < 4; ++w) key = wkey[tid][w] < key ? wkey[tid][w] : key;
+        const unsigned code = (unsigned)(key & 0xffffffffu);
+        const int tt = tt0 + tid;
+        const int n = tt / a.t_new, t = tt % a.t_new;
+        const int pos = a.t_offset + t;
+        const int u = pos & (kTileTokens - 1);
+        const int hkv = g_abs / GH, g = g_abs % GH;
+        const int slot = (g - u) & (GH - 1);
+        uint8_t* tile = a.codes + ((size_t)(n * a.f.n_kv_heads + hkv) * (a.t_cap / kTileTokens) + pos / kTileTokens) * TILE_BYTES;
+        tile[(slot >> 4) * 1024 + u * 16 + (slot & 15)] = (uint8_t)(code & 0xff);
+        if constexpr (B == 10) {
+            // the high bits of a token's 16 codes share one word that other workgroups update too
+            unsigned* hw = reinterpret_cast<unsigned*>(tile + TILE_LOW + u * 4);
+            atomicAnd(hw, ~(3u << (2 * slot)));
+            atomicOr(hw, (code >> 8) << (2 * slot));
+        }
+    }
+}
+
+template <int GH, int C, int B>
+cq_status launch_format(const EncodeArgs& a, hipStream_t stream)
+{
+    if (a.t_new < 32) {
+        const int total = a.batch * a.t_new;
+        dim3 grid((unsigned)a.f.groups, (unsigned)((total + kSmallTokens - 1) / kSmallTokens));
+        hipLaunchKernelGGL((encode_centroids_kernel<GH, C, B>), grid, dim3(256), 0, stream, a);
+    } else {
+        const int first_tile = a.t_offset / kTileTokens;
+        const int last_tile = (a.t_offset + a.t_new - 1) / kTileTokens;
+        const int n_tiles = last_tile - first_tile + 1;
+        const long wave_tiles = (long)n_tiles * a.f.n_kv_heads * a.batch;
+        if (wave_tiles >= 256L * 32) {
+            constexpr int NW = 4, TPL = (B == 10 ? 1 : 2);
+            dim3 grid((unsigned)((n_tiles + NW * TPL - 1) / (NW * TPL)), (unsigned)a.f.n_kv_heads, (unsigned)a.batch);
+            hipLaunchKernelGGL((encode_tokens_kernel<GH, C, B, NW, TPL>), grid, dim3(NW * 64), 0, stream, a);
+        } else {
+            constexpr int NW = (B == 10 ? 2 : 1), TPL = 1;
+            dim3 grid((unsigned)((n_tiles + NW * TPL - 1) / (NW * TPL)), (unsigned)a.f.n_kv_heads, (unsigned)a.batch);
+            hipLaunchKernelGGL((encode_tokens_kernel<GH, C, B, NW, TPL>), grid, dim3(NW * 64), 0, stream, a);
+        }
+    }
+    if (hipGetLastError() != hipSuccess) return CQ_ERR_HIP;
+    return CQ_OK;
+}
+
+}  // namespace
+
+cq_status launch_encode(const EncodeArgs& a, hipStream_t stream)
+{
+    if (a.f.b == 8) {
+        if (a.f.gh == 16 && a.f.c == 8) return launch_format<16, 8, 8>(a, stream);
+        if (a.f.gh == 32 && a.f.c == 4) return launch_format<32, 4, 8>(a, stream);
+        if (a.f.gh == 64 && a.f.c == 2) return launch_format<64, 2, 8>(a, stream);
+    } else if (a.f.b == 10) {
+        if (a.f.gh == 16 && a.f.c == 8) return launch_format<16, 8, 10>(a, stream);
+    }
+    return CQ_ERR_UNSUPPORTED;
+}
+
+}  // namespace cq

@@ -1,0 +1,59 @@
+// Internal declarations shared by the host entry points and the kernel launchers of libcq.
+// Nothing here is part of the public ABI (see include/libcq.h for that).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "libcq.h"
+
+namespace cq {
+
+constexpr int kTileTokens = CQ_TILE_TOKENS;   // tokens per cache tile == lanes per wavefront
+constexpr int kTabWords = 64;                 // 4-byte words per lookup-table row (b = 8)
+constexpr int kPartialHeader = 2;             // running max and sum in front of each partial
+
+struct Derived {
+    int c, b, head_dim, n_kv_heads;
+    int gh;            // groups per head
+    int k;             // centroids per group
+    int channels;      // n_kv_heads * head_dim
+    int groups;        // channels / c
+    int bpth;          // code bytes per token-head
+    int tile_bytes;    // 64 * bpth
+};
+
+// Host-side format check shared by every entry point.
+cq_status derive(const cq_format* fmt, Derived* out);
+
+struct EncodeArgs {
+    const uint16_t* x;
+    int64_t x_batch_stride, x_row_stride;
+    const uint16_t* centroids;
+    uint8_t* codes;
+    int batch, t_new, t_offset, t_cap;
+    Derived f;
+};
+
+struct DecodeArgs {
+    const uint16_t* q;
+    const uint8_t* k_codes;
+    const uint8_t* v_codes;
+    const uint16_t* k_centroids;
+    const uint16_t* v_centroids;
+    float scale_log2e;        // scale * log2(e): scores are kept in the base-2 domain
+    int batch, n_q_heads, t, t_cap;
+    const int32_t* seq_lens;
+    int tiles_per_split, n_split;
+    float* partials;          // [batch][n_q_heads][n_split][2 + head_dim]
+    uint16_t* out;
+    Derived f;
+};
+
+// Largest tokens_per_split the decode kernel's on-chip score buffer can hold.
+int decode_max_tiles_per_split(const Derived& f);
+
+cq_status launch_encode(const EncodeArgs& a, hipStream_t stream);
+cq_status launch_decode(const DecodeArgs& a, hipStream_t stream);
+
+}  // namespace cq

@@ -1,0 +1,98 @@
+"""Helpers shared by the GPU parity tests: run libcq through its Python binding on numpy inputs,
+bring results back, and compare with the CPU oracle under the acceptance rules:
+
+* codes: bit-exact, except that where the oracle's two smallest fp64 distances d1 <= d2 satisfy
+  (d2 - d1) / d2 < 1e-6 the GPU (fp32 distances) may pick another index, which must itself be
+  within that relative margin of the minimum;
+* attention: |gpu - ref| <= 2e-3 * max(|ref|, 1e-3 * max_i |ref_i| of the same (sequence, head)),
+  the reference being the oracle's fp64 result.
+"""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+import paper_2405_03917_amd as cq
+from oracle import code_layout as L
+from oracle import cq_oracle as O
+
+NEAR_TIE = 1e-6
+ATTN_RTOL = 2e-3
+ATTN_FLOOR = 1e-3
+
+
+def dev(a: np.ndarray) -> torch.Tensor:
+    return torch.from_numpy(np.ascontiguousarray(a)).to("cuda")
+
+
+def gpu_encode(x: np.ndarray, cb: np.ndarray, fmt: cq.CQFormat, t_cap: int, t_offset: int = 0,
+               cache: torch.Tensor | None = None, fill: int = 0xA5) -> torch.Tensor:
+    """x fp16 [B, T, D] -> packed cache (uint8 device tensor)."""
+    B = x.shape[0]
+    if cache is None:
+        cache = torch.full((cq.cq_cache_bytes(fmt, B, t_cap),), fill, dtype=torch.uint8, device="cuda")
+    cq.cq_encode(dev(x), dev(cb), fmt, cache, t_offset, t_cap)
+    torch.cuda.synchronize()
+    return cache
+
+
+def cache_to_codes(cache: torch.Tensor, fmt: cq.CQFormat, batch: int, t_cap: int, n_tokens: int,
+                   t_offset: int = 0) -> np.ndarray:
+    tb = L.tile_bytes(fmt.c, fmt.b, fmt.head_dim)
+    arr = cache.cpu().numpy().reshape(batch, fmt.n_kv_heads, t_cap // 64, tb)
+    return L.unpack(arr, fmt.c, fmt.b, fmt.head_dim, fmt.n_kv_heads, n_tokens, t_offset)
+
+
+def codes_to_cache(codes: np.ndarray, fmt: cq.CQFormat, t_cap: int, fill: int = 0x5A) -> torch.Tensor:
+    arr = L.pack(codes, fmt.c, fmt.b, fmt.head_dim, fmt.n_kv_heads, t_cap, fill=fill)
+    return dev(arr.reshape(-1))
+
+
+def check_codes(gpu_codes: np.ndarray, x: np.ndarray, cb: np.ndarray) -> dict:
+    """gpu_codes [T, G] vs the oracle on x [T, D]; returns statistics, asserts the rule above."""
+    ref, d1, d2 = O.encode(x, cb, with_distances=True)
+    diff = gpu_codes != ref
+    n_diff = int(diff.sum())
+    if n_diff:
+        T, G = ref.shape
+        c = cb.shape[2]
+        tt, gg = np.nonzero(diff)
+        with np.errstate(divide="ignore", invalid="ignore"):
+            gap = (d2[tt, gg] - d1[tt, gg]) / d2[tt, gg]
+        assert np.all(d2[tt, gg] > 0), "exact zero-distance ties must resolve to the lowest index"
+        assert np.all(gap < NEAR_TIE), f"{n_diff} codes differ, worst relative gap {gap.max():.3e}"
+        xs = x.astype(np.float64).reshape(T, G, c)[tt, gg]
+        chosen = cb.astype(np.float64)[gg, gpu_codes[tt, gg]]
+        d_gpu = ((xs - chosen) ** 2).sum(-1)
+        assert np.all(d_gpu <= (1 + NEAR_TIE) * d1[tt, gg])
+    return {"n": int(ref.size), "n_diff": n_diff}
+
+
+def gpu_attention(q: np.ndarray, k_cache: torch.Tensor, v_cache: torch.Tensor, ck: np.ndarray, cv: np.ndarray,
+                  scale: float, fmt: cq.CQFormat, t: int, t_cap: int, seq_lens=None, tokens_per_split: int = 0):
+    sl = None if seq_lens is None else dev(np.asarray(seq_lens, dtype=np.int32))
+    out = cq.cq_decode_attention(dev(q), k_cache, v_cache, dev(ck), dev(cv), scale, fmt, t, t_cap,
+                                 seq_lens=sl, tokens_per_split=tokens_per_split)
+    torch.cuda.synchronize()
+    return out.cpu().numpy()
+
+
+def attention_errors(out_gpu: np.ndarray, ref: np.ndarray) -> dict:
+    g = out_gpu.astype(np.float64)
+    rowmax = np.abs(ref).max(axis=-1, keepdims=True)
+    denom = np.maximum(np.abs(ref), ATTN_FLOOR * rowmax)
+    err = np.abs(g - ref)
+    with np.errstate(divide="ignore", invalid="ignore"):
+        unfloored = np.where(np.abs(ref) > 0, err / np.abs(ref), 0.0)
+    return {
+        "max_rel_floored": float((err / denom).max()),
+        "max_rel_unfloored": float(unfloored.max()),
+        "max_rel_to_rowmax": float((err / rowmax).max()),
+    }
+
+
+def check_attention(out_gpu: np.ndarray, ref: np.ndarray) -> dict:
+    assert np.all(np.isfinite(out_gpu.astype(np.float64)))
+    e = attention_errors(out_gpu, ref)
+    assert e["max_rel_floored"] <= ATTN_RTOL, e
+    return e

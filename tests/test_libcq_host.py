@@ -1,0 +1,136 @@
+"""Host-side checks of the C-ABI library that need no GPU: it loads, exports every symbol the
+public header declares, its sizing helpers agree with the paper's densities and with the numpy
+restatement of the layout, and every argument-validation path returns before any launch."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2405_03917_amd as cq
+from oracle import code_layout as L
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "libcq.h")
+
+FORMATS = [(8, 8), (4, 8), (2, 8), (8, 10)]
+
+
+def _declared():
+    text = open(HEADER).read()
+    return re.findall(r"CQ_API\s+[\w\s\*]+?\b(cq_\w+)\s*\(", text)
+
+
+def test_library_loads_and_exports_every_declared_symbol():
+    lib = cq.load()
+    names = _declared()
+    assert len(names) >= 9
+    assert set(names) == set(cq.EXPORTS)
+    for n in names:
+        assert hasattr(lib, n), n
+    assert cq.cq_version() >= 100
+    assert cq.status_string(cq.CQ_OK) == "CQ_OK"
+    assert cq.status_string(cq.CQ_ERR_HIP) == "CQ_ERR_HIP"
+
+
+@pytest.mark.parametrize("c,b", FORMATS)
+def test_sizes_follow_bits_per_fpn_and_the_layout(c, b):
+    fmt = cq.CQFormat(c, b, 128, 8)
+    assert cq.cq_format_check(fmt) == cq.CQ_OK
+    bpth = cq.cq_code_bytes_per_token_head(fmt)
+    assert bpth * 8 == (128 // c) * b                     # dense: b / c bits per stored number
+    assert bpth == L.bytes_per_token_head(c, b, 128)
+    assert cq.cq_cache_bytes(fmt, 3, 256) == L.cache_bytes(c, b, 128, 8, 3, 256)
+    assert cq.cq_cache_bytes(fmt, 3, 100) == 0            # t_cap must be a multiple of 64
+    assert cq.cq_cache_bytes(fmt, 0, 128) == 0
+
+
+def test_unsupported_and_invalid_formats():
+    assert cq.cq_format_check(cq.CQFormat(3, 8, 128, 8)) == cq.CQ_ERR_INVALID_ARG     # 3 does not divide 128
+    assert cq.cq_format_check(cq.CQFormat(0, 8, 128, 8)) == cq.CQ_ERR_INVALID_ARG
+    assert cq.cq_format_check(cq.CQFormat(8, 9, 128, 8)) == cq.CQ_ERR_UNSUPPORTED
+    assert cq.cq_format_check(cq.CQFormat(1, 8, 128, 8)) == cq.CQ_ERR_UNSUPPORTED
+    assert cq.cq_format_check(cq.CQFormat(4, 10, 128, 8)) == cq.CQ_ERR_UNSUPPORTED
+    assert cq.cq_code_bytes_per_token_head(cq.CQFormat(8, 9, 128, 8)) == 0
+    assert int(cq.load().cq_format_check(None)) == cq.CQ_ERR_INVALID_ARG
+
+
+def _fake(addr=0x10000):
+    return ctypes.c_void_p(addr)
+
+
+def _encode(fmt, x=0x10000, cen=0x20000, codes=0x30000, bstride=None, rstride=None, batch=1, t_new=64,
+            t_offset=0, t_cap=64):
+    f = fmt._c()
+    rstride = fmt.channels if rstride is None else rstride
+    bstride = rstride * t_new if bstride is None else bstride
+    return int(cq.load().cq_encode(_fake(x), bstride, rstride, _fake(cen), ctypes.byref(f), batch, t_new,
+                                   _fake(codes), t_offset, t_cap, None))
+
+
+def test_encode_rejects_bad_arguments_without_launching():
+    fmt = cq.CQFormat(8, 8, 128, 4)
+    E = cq.CQ_ERR_INVALID_ARG
+    assert _encode(fmt, x=0) == E
+    assert _encode(fmt, cen=0) == E
+    assert _encode(fmt, codes=0) == E
+    assert _encode(fmt, x=0x10004) == E                    # misaligned
+    assert _encode(fmt, batch=0) == E
+    assert _encode(fmt, t_new=0) == E
+    assert _encode(fmt, t_cap=100) == E
+    assert _encode(fmt, t_offset=1, t_new=64, t_cap=64) == E
+    assert _encode(fmt, t_offset=-1) == E
+    assert _encode(fmt, rstride=fmt.channels - 8) == E
+    assert _encode(fmt, rstride=fmt.channels + 4) == E     # rows would lose 16-byte alignment
+    assert _encode(fmt, batch=2, bstride=8) == E
+    assert _encode(cq.CQFormat(8, 9, 128, 4)) == cq.CQ_ERR_UNSUPPORTED
+
+
+def _decode(fmt, batch=2, hq=8, t=128, t_cap=128, split=0, ws_bytes=1 << 30, ptrs=None, scale=0.1, seq=None):
+    f = fmt._c()
+    p = dict(q=0x10000, kc=0x20000, vc=0x30000, ck=0x40000, cv=0x50000, out=0x60000, ws=0x70000)
+    p.update(ptrs or {})
+    return int(cq.load().cq_decode_attention(_fake(p["q"]), _fake(p["kc"]), _fake(p["vc"]), _fake(p["ck"]),
+                                             _fake(p["cv"]), scale, ctypes.byref(f), batch, hq, t, t_cap, seq,
+                                             split, _fake(p["out"]), _fake(p["ws"]), ws_bytes, None))
+
+
+def test_decode_rejects_bad_arguments_without_launching():
+    fmt = cq.CQFormat(8, 8, 128, 4)
+    E = cq.CQ_ERR_INVALID_ARG
+    for k in ("q", "kc", "vc", "ck", "cv", "out", "ws"):
+        assert _decode(fmt, ptrs={k: 0}) == E, k
+    assert _decode(fmt, ptrs={"q": 0x10008}) == E
+    assert _decode(fmt, hq=6) == E                         # not a multiple of the KV heads
+    assert _decode(fmt, batch=0) == E
+    assert _decode(fmt, t=0) == E
+    assert _decode(fmt, t=129, t_cap=128) == E
+    assert _decode(fmt, t_cap=96, t=64) == E
+    assert _decode(fmt, split=100) == E                    # not a multiple of 64
+    assert _decode(fmt, split=-64) == E
+    assert _decode(fmt, split=64 * 1000) == E              # beyond the on-chip score buffer
+    assert _decode(fmt, scale=float("nan")) == E
+    assert _decode(fmt, ws_bytes=16) == cq.CQ_ERR_WORKSPACE_TOO_SMALL
+    assert _decode(cq.CQFormat(8, 7, 128, 4)) == cq.CQ_ERR_UNSUPPORTED
+
+
+def test_workspace_size_matches_the_split_arithmetic():
+    fmt = cq.CQFormat(8, 8, 128, 32)
+    # explicit split: ceil(t / split) partials of (2 + head_dim) floats per (sequence, query head)
+    assert cq.cq_decode_workspace_bytes(fmt, 4, 32, 1000, 256) == 4 * 32 * 4 * 130 * 4
+    assert cq.cq_decode_workspace_bytes(fmt, 4, 32, 1024, 1024) == 4 * 32 * 1 * 130 * 4
+    assert cq.cq_decode_workspace_bytes(fmt, 4, 32, 1000, 100) == 0
+    d = cq.cq_decode_default_split(fmt, 4, 32, 131072)
+    assert d % 64 == 0 and d > 0
+    n_split = -(-131072 // d)
+    assert cq.cq_decode_workspace_bytes(fmt, 4, 32, 131072, 0) == 4 * 32 * n_split * 130 * 4
+
+
+def test_python_binding_refuses_cpu_tensors():
+    import torch
+    fmt = cq.CQFormat(8, 8, 128, 1)
+    x = torch.zeros((1, 64, 128), dtype=torch.float16)
+    cb = torch.zeros((16, 256, 8), dtype=torch.float16)
+    codes = torch.zeros(1024, dtype=torch.uint8)
+    with pytest.raises(TypeError):
+        cq.cq_encode(x, cb, fmt, codes, 0, 64)
