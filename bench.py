@@ -1,0 +1,312 @@
+#!/usr/bin/env python3
+"""Throughput of the CQ hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--no-extra] [--no-cpu]
+
+Workload (the second named configuration): CQ-4c8b (2 bits per channel) on a Llama-2-7B-shaped
+KV cache -- 32 layers, batch 16, 32 heads x 128, context 4096, MHA.  One STEP is one decode step
+of the whole hot path over all 32 layers: per layer, encode the 16 new key rows and the 16 new
+value rows into cache position 4095 (cq_encode, twice) and attend over all 4096 cached tokens
+(cq_decode_attention).  Every layer has its own codebooks, caches, queries and new rows (4 GiB of
+codes in total, far more than the 256 MB Infinity Cache, so code reads are real HBM reads).
+
+Inputs are synthetic and resident in HBM before the timed region: correlated-Gaussian K/V rows
+(synth/generator.py) drawn on the device and REALLY encoded with cq_encode to fill the caches.
+
+The timed region replays a HIP graph of the step (96 kernel launches) K times between two
+synchronisations.  After it, the same launches are run eagerly with a HIP event pair around
+every cq_decode_attention call to obtain the decode kernel's own average duration (with a single
+context split, as here, that call is exactly one kernel).
+
+One JSON line is printed on stdout; progress goes to stderr.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import math
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0          # MI355X published peak, GB/s
+METRIC = "decode-attn KV tokens/s & achieved HBM GB/s (% peak); cq_encode tokens/s"
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+class LayerState:
+    """Device buffers of one layer."""
+    __slots__ = ("ck", "cv", "kcache", "vcache", "q", "xk_new", "xv_new", "out", "ws")
+
+
+def build_workload(cq, synth, torch, cfg, n_layers, fill_chunk_tokens=16384):
+    """Allocate and fill every layer's buffers.  Cache positions 0 .. T-2 come from encoding
+    device-generated activations; the last position is written by the timed step itself."""
+    fmt = cq.CQFormat(cfg.c, cfg.b, cfg.head_dim, cfg.n_kv_heads)
+    B, T, D = cfg.batch, cfg.context, cfg.kv_channels
+    t_cap = (T + 63) // 64 * 64
+    layers = []
+    dev = lambda a: torch.from_numpy(a).cuda()
+    for layer in range(n_layers):
+        st = LayerState()
+        rk = synth.tensor_recipe(cfg.cfg_id, layer, "k", D)
+        rv = synth.tensor_recipe(cfg.cfg_id, layer, "v", D)
+        st.ck = dev(synth.sample_codebook(rk, cfg.c, cfg.b))
+        st.cv = dev(synth.sample_codebook(rv, cfg.c, cfg.b))
+        st.kcache = cq.alloc_cache(fmt, B, t_cap)
+        st.vcache = cq.alloc_cache(fmt, B, t_cap)
+        st.kcache.zero_()
+        st.vcache.zero_()
+        n_fill = T - cfg.encode_tokens if cfg.encode_tokens < T else T
+        for recipe, cb, cache, sid in ((rk, st.ck, st.kcache, 0), (rv, st.cv, st.vcache, 1)):
+            for n in range(B):
+                t0 = 0
+                while t0 < n_fill:
+                    tn = min(fill_chunk_tokens, n_fill - t0)
+                    x = synth.sample_activations_torch(recipe, tn, 7919 * n + 2 * t0 + sid, "cuda")
+                    # one sequence at a time: view the cache of sequence n as a batch of 1
+                    per_seq = cache.numel() // B
+                    cq.cq_encode(x.view(1, tn, D), cb, fmt, cache[n * per_seq:(n + 1) * per_seq], t0, t_cap)
+                    t0 += tn
+                    del x
+        st.q = dev(synth.sample_query(cfg.cfg_id, layer, B, cfg.n_q_heads, cfg.head_dim))
+        import numpy as np
+        tnew = min(cfg.encode_tokens, T)
+        st.xk_new = dev(np.stack([synth.sample_activations(rk, tnew, chunk=1000 + n) for n in range(B)]))
+        st.xv_new = dev(np.stack([synth.sample_activations(rv, tnew, chunk=1000 + n) for n in range(B)]))
+        st.out = torch.empty((B, cfg.n_q_heads, cfg.head_dim), dtype=torch.float16, device="cuda")
+        nws = cq.cq_decode_workspace_bytes(fmt, B, cfg.n_q_heads, T, 0)
+        st.ws = torch.empty(max(nws, 16), dtype=torch.uint8, device="cuda")
+        layers.append(st)
+        if layer % 8 == 7 or layer == n_layers - 1:
+            torch.cuda.synchronize()
+            log(f"[bench] layer {layer + 1}/{n_layers} caches filled")
+    return fmt, t_cap, layers
+
+
+def run_step(cq, fmt, cfg, t_cap, layers, scale, events=None):
+    T = cfg.context
+    t_off = T - layers[0].xk_new.shape[1]
+    for i, st in enumerate(layers):
+        cq.cq_encode(st.xk_new, st.ck, fmt, st.kcache, t_off, t_cap)
+        cq.cq_encode(st.xv_new, st.cv, fmt, st.vcache, t_off, t_cap)
+        if events is not None:
+            events[i][0].record()
+        cq.cq_decode_attention(st.q, st.kcache, st.vcache, st.ck, st.cv, scale, fmt, T, t_cap,
+                               out=st.out, workspace=st.ws)
+        if events is not None:
+            events[i][1].record()
+
+
+def time_calls(torch, fn, iters, warmup=2):
+    for _ in range(warmup):
+        fn()
+    torch.cuda.synchronize()
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(iters)]
+    for a, b in evs:
+        a.record()
+        fn()
+        b.record()
+    torch.cuda.synchronize()
+    ts = sorted(a.elapsed_time(b) for a, b in evs)
+    return ts[len(ts) // 2], sum(ts) / len(ts)
+
+
+def extra_measurements(cq, synth, torch):
+    """Decode attention at 1 bit per channel on a long context (CQ-8c8b, batch 4, 131072 tokens)
+    and prefill-sized cq_encode (32768 tokens): the cases the headline targets are quoted on."""
+    import numpy as np
+    out = {}
+    cfg = synth.CONFIGS[5]
+    fmt = cq.CQFormat(cfg.c, cfg.b, cfg.head_dim, cfg.n_kv_heads)
+    B, T, D = cfg.batch, cfg.context, cfg.kv_channels
+    rk = synth.tensor_recipe(5, 0, "k", D)
+    rv = synth.tensor_recipe(5, 0, "v", D)
+    ck = torch.from_numpy(synth.sample_codebook(rk, cfg.c, cfg.b)).cuda()
+    cv = torch.from_numpy(synth.sample_codebook(rv, cfg.c, cfg.b)).cuda()
+    kcache, vcache = cq.alloc_cache(fmt, B, T), cq.alloc_cache(fmt, B, T)
+    per_seq = kcache.numel() // B
+    chunk = cfg.encode_tokens
+    enc_ms = None
+    for n in range(B):
+        for t0 in range(0, T, chunk):
+            xk = synth.sample_activations_torch(rk, chunk, 31 * n + t0, "cuda").view(1, chunk, D)
+            xv = synth.sample_activations_torch(rv, chunk, 31 * n + t0 + 1, "cuda").view(1, chunk, D)
+            if enc_ms is None:      # time the 32768-token prefill encode once (per tensor)
+                enc_ms, _ = time_calls(torch, lambda: cq.cq_encode(xk, ck, fmt, kcache[:per_seq], 0, T), 5, 1)
+            cq.cq_encode(xk, ck, fmt, kcache[n * per_seq:(n + 1) * per_seq], t0, T)
+            cq.cq_encode(xv, cv, fmt, vcache[n * per_seq:(n + 1) * per_seq], t0, T)
+            del xk, xv
+    torch.cuda.synchronize()
+    out["encode_prefill"] = {"workload": "CQ-8c8b, 32768 tokens x 4096 channels, one tensor",
+                             "ms": enc_ms, "tokens_per_s": chunk / (enc_ms * 1e-3)}
+    q = torch.from_numpy(synth.sample_query(5, 0, B, cfg.n_q_heads, cfg.head_dim)).cuda()
+    o = torch.empty((B, cfg.n_q_heads, cfg.head_dim), dtype=torch.float16, device="cuda")
+    ws = torch.empty(cq.cq_decode_workspace_bytes(fmt, B, cfg.n_q_heads, T, 0), dtype=torch.uint8, device="cuda")
+    scale = 1.0 / math.sqrt(cfg.head_dim)
+    med, mean = time_calls(torch, lambda: cq.cq_decode_attention(q, kcache, vcache, ck, cv, scale, fmt, T, T,
+                                                                 out=o, workspace=ws), 20, 3)
+    code_bytes = B * T * 2 * D * cfg.b // (8 * cfg.c)
+    out["decode_long_context"] = {
+        "workload": "CQ-8c8b, batch 4, 32 heads x 128, context 131072, one layer (split kernel + merge)",
+        "ms": med, "kv_tokens_per_s": B * T / (med * 1e-3),
+        "code_read_GBps": code_bytes / (med * 1e-3) / 1e9,
+        "frac_of_hbm_peak": code_bytes / (med * 1e-3) / 1e9 / HBM_PEAK_GBPS,
+        "tokens_per_split": cq.cq_decode_default_split(fmt, B, cfg.n_q_heads, T)}
+    return out
+
+
+def cpu_baseline(synth, cfg, budget_s=15.0):
+    """The fp64 oracle, as it stands, on this host's cores: one layer-step (encode the new rows,
+    attend over the context) for a sub-batch sized to the time budget."""
+    import numpy as np
+    from oracle import cq_oracle as O
+    cores = min(len(os.sched_getaffinity(0)), int(os.environ.get("OMP_NUM_THREADS", "1000000")))
+    O.set_threads(cores)
+    D, T = cfg.kv_channels, cfg.context
+    rk = synth.tensor_recipe(cfg.cfg_id, 0, "k", D)
+    rv = synth.tensor_recipe(cfg.cfg_id, 0, "v", D)
+    ck, cv = synth.sample_codebook(rk, cfg.c, cfg.b), synth.sample_codebook(rv, cfg.c, cfg.b)
+    rng = np.random.default_rng(0)
+    # probe with one sequence, then scale the sub-batch
+    def one(bs):
+        kc = rng.integers(0, 1 << cfg.b, size=(bs, T, cfg.n_groups)).astype(np.uint16)
+        vc = rng.integers(0, 1 << cfg.b, size=(bs, T, cfg.n_groups)).astype(np.uint16)
+        xk = np.stack([synth.sample_activations(rk, 1, chunk=1000 + n) for n in range(bs)])
+        xv = np.stack([synth.sample_activations(rv, 1, chunk=1000 + n) for n in range(bs)])
+        q = synth.sample_query(cfg.cfg_id, 0, bs, cfg.n_q_heads, cfg.head_dim)
+        t0 = time.perf_counter()
+        kc[:, T - 1] = O.encode(xk[:, 0], ck)
+        vc[:, T - 1] = O.encode(xv[:, 0], cv)
+        O.attention(q, kc, vc, ck, cv, 1.0 / math.sqrt(cfg.head_dim), cfg.n_kv_heads)
+        return time.perf_counter() - t0
+    t1 = one(1)
+    bs = int(max(1, min(cfg.batch, budget_s / max(t1, 1e-3))))
+    reps = int(max(1, min(8, budget_s / max(t1 * bs, 1e-3)))) if bs == cfg.batch else 1
+    t = sum(one(bs) for _ in range(reps))
+    return {"value": reps * bs * T / t, "unit": "KV tokens/s", "cores": cores, "kind": "oracle",
+            "sample": f"{reps} layer-step(s) (2 x encode of {bs} new rows + attention over {T} cached tokens) "
+                      f"for {bs} of {cfg.batch} sequences, {t:.1f} s in total; random codes in the cache",
+            "threads_env": os.environ.get("OMP_NUM_THREADS")}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--layers", type=int, default=0, help="override the number of layers (debug only)")
+    ap.add_argument("--no-extra", action="store_true", help="skip the long-context / prefill side measurements")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        log("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1")
+        sys.exit(2)
+
+    import torch
+    import paper_2405_03917_amd as cq
+    import synth
+
+    if not torch.cuda.is_available():
+        log("bench.py: no GPU visible")
+        sys.exit(1)
+    cq.load()
+    torch.cuda.set_device(0)
+    cfg = synth.CONFIGS[2]
+    n_layers = args.layers or cfg.layers
+    scale = 1.0 / math.sqrt(cfg.head_dim)
+
+    t_setup = time.perf_counter()
+    fmt, t_cap, layers = build_workload(cq, synth, torch, cfg, n_layers)
+    torch.cuda.synchronize()
+    log(f"[bench] setup {time.perf_counter() - t_setup:.1f} s")
+
+    for _ in range(max(1, args.warmup)):
+        run_step(cq, fmt, cfg, t_cap, layers, scale)
+    torch.cuda.synchronize()
+
+    # capture the step (3 * layers launches) in a HIP graph on a side stream
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        run_step(cq, fmt, cfg, t_cap, layers, scale)
+        side.synchronize()
+        with torch.cuda.graph(graph, stream=side):
+            run_step(cq, fmt, cfg, t_cap, layers, scale)
+    torch.cuda.synchronize()
+    graph.replay()
+    torch.cuda.synchronize()
+
+    # ---- timed region: exactly K steps ----
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        graph.replay()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms_per_step = dt / args.steps * 1e3
+    kv_tokens = cfg.batch * cfg.context * n_layers
+    value = kv_tokens / (dt / args.steps)
+    log(f"[bench] graph replay: {ms_per_step:.3f} ms/step, {value:.3e} KV tokens/s")
+
+    # ---- eager replays with an event pair around every decode call (kernel duration) ----
+    t0 = time.perf_counter()
+    all_ms = []
+    for _ in range(args.steps):
+        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in layers]
+        run_step(cq, fmt, cfg, t_cap, layers, scale, events=evs)
+        torch.cuda.synchronize()
+        all_ms += [a.elapsed_time(b) for a, b in evs]
+    eager_ms = (time.perf_counter() - t0) / args.steps * 1e3
+    dec_ms = sum(all_ms) / len(all_ms)
+    code_bytes = cfg.batch * cfg.context * 2 * cfg.kv_channels * cfg.b // (8 * cfg.c)   # per launch
+    achieved = code_bytes / (dec_ms * 1e-3) / 1e9
+    roofline = {"bound": "hbm", "kernel": "decode_split_kernel<32,4,512> (one launch = one layer)",
+                "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS,
+                "traffic": None, "algorithmic_bytes_per_launch": code_bytes, "avg_launch_ms": dec_ms,
+                "launches_timed": len(all_ms)}
+    log(f"[bench] decode kernel avg {dec_ms * 1e3:.1f} us -> {achieved:.0f} GB/s of code reads "
+        f"({100 * achieved / HBM_PEAK_GBPS:.1f}% of 8 TB/s); eager step {eager_ms:.3f} ms")
+
+    # encode share of the step (same launches, events around the two encodes of each layer)
+    enc_med, _ = time_calls(torch, lambda: cq.cq_encode(layers[0].xk_new, layers[0].ck, fmt, layers[0].kcache,
+                                                        cfg.context - 1, t_cap), 20, 3)
+    result = {
+        "metric": METRIC, "value": value, "unit": "KV tokens/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "CQ-4c8b decode step, 32 layers, batch 16, 32 heads x 128, context 4096, MHA; "
+                               "per layer: cq_encode of 16 new K rows + 16 new V rows, then cq_decode_attention",
+                   "format": "CQ-4c8b", "batch": cfg.batch, "context": cfg.context, "layers": n_layers,
+                   "launch": "HIP graph of 3 launches per layer", "tokens_per_split":
+                       cq.cq_decode_default_split(fmt, cfg.batch, cfg.n_q_heads, cfg.context)},
+        "roofline": roofline,
+        "hbm_code_read_GBps_whole_step": kv_tokens * 2 * cfg.kv_channels * cfg.b // (8 * cfg.c) / (dt / args.steps) / 1e9,
+        "eager_ms_per_step": eager_ms,
+        "encode_decode_step": {"workload": "16 new rows x 4096 channels, one tensor", "ms": enc_med,
+                               "tokens_per_s": cfg.batch / (enc_med * 1e-3)},
+    }
+    del graph
+    if not args.no_extra:
+        del layers
+        torch.cuda.empty_cache()
+        try:
+            result["extra"] = extra_measurements(cq, synth, torch)
+            log(f"[bench] extra: {json.dumps(result['extra'])}")
+        except Exception as e:      # side measurements must not lose the main line
+            result["extra"] = {"error": repr(e)}
+    if not args.no_cpu:
+        result["cpu_baseline"] = cpu_baseline(synth, cfg)
+        log(f"[bench] cpu oracle: {result['cpu_baseline']}")
+    print(json.dumps(result), flush=True)
+
+
+if __name__ == "__main__":
+    main()

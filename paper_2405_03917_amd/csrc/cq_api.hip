@@ -40,10 +40,11 @@ int default_tiles_per_split(const Derived& f, int batch, int n_q_heads, int t)
 {
     const int n_tiles = (t + kTileTokens - 1) / kTileTokens;
     const long bh = (long)batch * n_q_heads;
-    const int max_tiles = std::min(63, decode_max_tiles_per_split(f));
-    // enough workgroups to fill 256 CUs a few times over, but splits long enough that building
-    // the lookup table (a fixed cost per workgroup) stays small against the streamed codes
-    const long want_wg = 2048;
+    const int max_tiles = decode_max_tiles_per_split(f);
+    // two workgroups per CU (256 CUs) are enough to keep HBM busy; beyond that, longer splits win
+    // because building the lookup table and the final bins x centroids product are fixed costs
+    // of every workgroup (each reads a whole head's codebook)
+    const long want_wg = 512;
     long n_split = std::max(1L, (want_wg + bh - 1) / bh);
     const int min_tiles = 16;
     n_split = std::min<long>(n_split, std::max(1, n_tiles / min_tiles));

@@ -6,9 +6,9 @@
 //       group's codebook in LDS as fp32 (double buffered) and scans it in ascending index order
 //       with all lanes reading the same centroid (LDS broadcast).  Codes are collected in LDS in
 //       cache order and stored with 16-byte writes.
-//   encode_centroids_kernel  (decode step: a handful of tokens)  lane = centroid.  A workgroup
-//       takes one group and up to 16 tokens; every thread keeps its centroids in registers and
-//       the minimum over (distance, index) pairs is reduced across the workgroup.
+//   encode_centroids_kernel  (decode step: a handful of tokens)  16 lanes per token.  A workgroup
+//       takes one group and up to 16 tokens; each lane scans every 16th centroid and the 16
+//       lanes of a token reduce their (distance, index) pairs.
 // Both evaluate sum_i (x_i - c_i)^2 in fp32 with one fused multiply-add per channel, in channel
 // order, and break ties towards the lowest index.
 #include <hip/hip_runtime.h>
@@ -160,61 +160,51 @@ __global__ __launch_bounds__(NW * 64) void encode_tokens_kernel(EncodeArgs a)
 }
 
 // ------------------------------------------------------------------------------------------
-// lane = centroid
+// a handful of tokens: 16 lanes per token
 // ------------------------------------------------------------------------------------------
-constexpr int kSmallTokens = 16;     // tokens per workgroup of the lane = centroid kernel
+constexpr int kSmallTokens = 16;     // tokens per workgroup
 
+// One workgroup = one group x up to 16 tokens.  Token i of the chunk is served by lanes
+// 16 i .. 16 i + 15; lane r of those scans centroids r, r + 16, r + 32, ... in ascending order,
+// then the 16 lanes reduce their (distance, index) pairs.  No LDS, no barrier.
 template <int GH, int C, int B>
 __global__ __launch_bounds__(256) void encode_centroids_kernel(EncodeArgs a)
 {
     constexpr int K = 1 << B;
-    constexpr int KP = K / 256;                      // centroids per thread
+    constexpr int PER_LANE = K / 16;
     constexpr int TILE_LOW = kTileTokens * GH;
     constexpr int TILE_BYTES = kTileTokens * GH * B / 8;
-    __shared__ unsigned long long wkey[kSmallTokens][4];
 
     const int tid = threadIdx.x;
-    const int lane = tid & 63;
-    const int wave = tid >> 6;
+    const int r = tid & 15;
     const int g_abs = blockIdx.x;
     const int total = a.batch * a.t_new;
-    const int tt0 = blockIdx.y * kSmallTokens;
-    const int ntok = min(kSmallTokens, total - tt0);
+    const int tt = blockIdx.y * kSmallTokens + (tid >> 4);
+    const bool valid = tt < total;
+    const int n = valid ? tt / a.t_new : 0, t = valid ? tt % a.t_new : 0;
 
-    float cen[KP][C];
-#pragma unroll
-    for (int kp = 0; kp < KP; ++kp)
-        load_halfs<C>(a.centroids + ((size_t)g_abs * K + kp * 256 + tid) * C, cen[kp]);
+    float x[C];
+    load_halfs<C>(a.x + (size_t)n * a.x_batch_stride + (size_t)t * a.x_row_stride + (size_t)g_abs * C, x);
+    const uint16_t* cen = a.centroids + ((size_t)g_abs * K + r) * C;
 
-    for (int i = 0; i < ntok; ++i) {
-        const int tt = tt0 + i;
-        const int n = tt / a.t_new, t = tt % a.t_new;
-        float x[C];
-        load_halfs<C>(a.x + (size_t)n * a.x_batch_stride + (size_t)t * a.x_row_stride + (size_t)g_abs * C, x);
-        unsigned long long key = ~0ull;
-#pragma unroll
-        for (int kp = 0; kp < KP; ++kp) {
-            const float d = sq_dist<C>(x, cen[kp]);
-            // d >= +0, so its bit pattern orders like the value; the index in the low word
-            // makes the minimum pick the lowest index among equal distances
-            const unsigned long long kk = ((unsigned long long)__float_as_uint(d) << 32) | (unsigned)(kp * 256 + tid);
-            key = kk < key ? kk : key;
-        }
-#pragma unroll
-        for (int o = 32; o > 0; o >>= 1) {
-            const unsigned long long other = __shfl_xor(key, o);
-            key = other < key ? other : key;
-        }
-        if (lane == 0) wkey[i][wave] = key;
+    // d >= +0, so its bit pattern orders like the value; the index in the low word makes the
+    // minimum pick the lowest index among equal distances
+    unsigned long long key = ~0ull;
+#pragma unroll 16
+    for (int k = 0; k < PER_LANE; ++k) {
+        float c[C];
+        load_halfs<C>(cen + (size_t)k * 16 * C, c);
+        const float d = sq_dist<C>(x, c);
+        const unsigned long long kk = ((unsigned long long)__float_as_uint(d) << 32) | (unsigned)(k * 16 + r);
+        key = kk < key ? kk : key;
     }
-    __syncthreads();
-    if (tid < ntok) {
-        unsigned long long key = wkey[tid][0];
 #pragma unroll
-        for (int w = 1; w < 4; ++w) key = wkey[tid][w] < key ? wkey[tid][w] : key;
+    for (int o = 8; o > 0; o >>= 1) {
+        const unsigned long long other = __shfl_xor(key, o, 16);
+        key = other < key ? other : key;
+    }
+    if (r == 0 && valid) {
         const unsigned code = (unsigned)(key & 0xffffffffu);
-        const int tt = tt0 + tid;
-        const int n = tt / a.t_new, t = tt % a.t_new;
         const int pos = a.t_offset + t;
         const int u = pos & (kTileTokens - 1);
         const int hkv = g_abs / GH, g = g_abs % GH;
