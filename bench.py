@@ -34,6 +34,9 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0          # MI355X published peak, GB/s
+# HBM bytes per decode launch from rocprofv3 counters (FETCH_SIZE x 1.9997 + WRITE_SIZE), see
+# profiles/decode_split_kernel_cq4c8b_batch16_ctx4096.md
+TRAFFIC_BYTES_PER_LAUNCH = (67750.7 * 1.9997 + 128.0) * 1024
 METRIC = "decode-attn KV tokens/s & achieved HBM GB/s (% peak); cq_encode tokens/s"
 
 
@@ -43,7 +46,7 @@ def log(*a):
 
 class LayerState:
     """Device buffers of one layer."""
-    __slots__ = ("ck", "cv", "kcache", "vcache", "q", "xk_new", "xv_new", "out", "ws")
+    __slots__ = ("ck", "cv", "kcache", "vcache", "q", "xk_new", "xv_new", "out", "ws", "enc_k", "enc_v", "dec")
 
 
 def build_workload(cq, synth, torch, cfg, n_layers, fill_chunk_tokens=16384):
@@ -91,16 +94,24 @@ def build_workload(cq, synth, torch, cfg, n_layers, fill_chunk_tokens=16384):
     return fmt, t_cap, layers
 
 
-def run_step(cq, fmt, cfg, t_cap, layers, scale, events=None):
+def prepare_calls(cq, fmt, cfg, t_cap, layers, scale):
+    """Marshal the three calls of every layer once; the step then only crosses the C ABI."""
     T = cfg.context
     t_off = T - layers[0].xk_new.shape[1]
+    for st in layers:
+        st.enc_k = cq.prepare_encode(st.xk_new, st.ck, fmt, st.kcache, t_off, t_cap)
+        st.enc_v = cq.prepare_encode(st.xv_new, st.cv, fmt, st.vcache, t_off, t_cap)
+        st.dec, _ = cq.prepare_decode_attention(st.q, st.kcache, st.vcache, st.ck, st.cv, scale, fmt, T, t_cap,
+                                                out=st.out, workspace=st.ws)
+
+
+def run_step(layers, events=None):
     for i, st in enumerate(layers):
-        cq.cq_encode(st.xk_new, st.ck, fmt, st.kcache, t_off, t_cap)
-        cq.cq_encode(st.xv_new, st.cv, fmt, st.vcache, t_off, t_cap)
+        st.enc_k()
+        st.enc_v()
         if events is not None:
             events[i][0].record()
-        cq.cq_decode_attention(st.q, st.kcache, st.vcache, st.ck, st.cv, scale, fmt, T, t_cap,
-                               out=st.out, workspace=st.ws)
+        st.dec()
         if events is not None:
             events[i][1].record()
 
@@ -228,8 +239,9 @@ def main():
     torch.cuda.synchronize()
     log(f"[bench] setup {time.perf_counter() - t_setup:.1f} s")
 
+    prepare_calls(cq, fmt, cfg, t_cap, layers, scale)
     for _ in range(max(1, args.warmup)):
-        run_step(cq, fmt, cfg, t_cap, layers, scale)
+        run_step(layers)
     torch.cuda.synchronize()
 
     # capture the step (3 * layers launches) in a HIP graph on a side stream
@@ -237,10 +249,10 @@ def main():
     side = torch.cuda.Stream()
     side.wait_stream(torch.cuda.current_stream())
     with torch.cuda.stream(side):
-        run_step(cq, fmt, cfg, t_cap, layers, scale)
+        run_step(layers)
         side.synchronize()
         with torch.cuda.graph(graph, stream=side):
-            run_step(cq, fmt, cfg, t_cap, layers, scale)
+            run_step(layers)
     torch.cuda.synchronize()
     graph.replay()
     torch.cuda.synchronize()
@@ -261,7 +273,7 @@ def main():
     all_ms = []
     for _ in range(args.steps):
         evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in layers]
-        run_step(cq, fmt, cfg, t_cap, layers, scale, events=evs)
+        run_step(layers, events=evs)
         torch.cuda.synchronize()
         all_ms += [a.elapsed_time(b) for a, b in evs]
     eager_ms = (time.perf_counter() - t0) / args.steps * 1e3
@@ -270,14 +282,35 @@ def main():
     achieved = code_bytes / (dec_ms * 1e-3) / 1e9
     roofline = {"bound": "hbm", "kernel": "decode_split_kernel<32,4,512> (one launch = one layer)",
                 "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS,
-                "traffic": None, "algorithmic_bytes_per_launch": code_bytes, "avg_launch_ms": dec_ms,
+                "traffic": TRAFFIC_BYTES_PER_LAUNCH if n_layers == cfg.layers else None,
+                "algorithmic_bytes_per_launch": code_bytes, "avg_launch_ms": dec_ms,
                 "launches_timed": len(all_ms)}
     log(f"[bench] decode kernel avg {dec_ms * 1e3:.1f} us -> {achieved:.0f} GB/s of code reads "
         f"({100 * achieved / HBM_PEAK_GBPS:.1f}% of 8 TB/s); eager step {eager_ms:.3f} ms")
 
+    # yardsticks: a read-only streaming kernel (one launch over 2 GiB) and a plain copy kernel of
+    # known size (256 MiB; its HBM counters calibrate the decode kernel's)
+    sink = torch.zeros(8192, dtype=torch.uint8, device="cuda")
+    big = torch.empty(2 << 30, dtype=torch.uint8, device="cuda")
+    big.zero_()
+    probe_med, _ = time_calls(torch, lambda: cq.cq_probe_stream_read(big, sink), 10, 2)
+    stream_gbps = big.numel() / (probe_med * 1e-3) / 1e9
+    half = 256 << 20
+    copy_med, _ = time_calls(torch, lambda: cq.cq_probe_copy(big[:half], big[half:2 * half]), 5, 1)
+    del big
+    roofline["stream_read_GBps"] = stream_gbps
+    roofline["frac_of_stream_read"] = achieved / stream_gbps
+    roofline["copy_256MiB_GBps_read_plus_write"] = 2 * half / (copy_med * 1e-3) / 1e9
+    log(f"[bench] streaming-read yardstick: {stream_gbps:.0f} GB/s; decode kernel at {100 * achieved / stream_gbps:.1f}% of it; "
+        f"copy {roofline['copy_256MiB_GBps_read_plus_write']:.0f} GB/s (read+write)")
+
     # encode share of the step (same launches, events around the two encodes of each layer)
-    enc_med, _ = time_calls(torch, lambda: cq.cq_encode(layers[0].xk_new, layers[0].ck, fmt, layers[0].kcache,
-                                                        cfg.context - 1, t_cap), 20, 3)
+    def enc_all():
+        for st in layers:
+            st.enc_k()
+            st.enc_v()
+    enc_med, _ = time_calls(torch, enc_all, 10, 2)
+    enc_med /= 2 * len(layers)
     result = {
         "metric": METRIC, "value": value, "unit": "KV tokens/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
@@ -290,7 +323,7 @@ def main():
         "roofline": roofline,
         "hbm_code_read_GBps_whole_step": kv_tokens * 2 * cfg.kv_channels * cfg.b // (8 * cfg.c) / (dt / args.steps) / 1e9,
         "eager_ms_per_step": eager_ms,
-        "encode_decode_step": {"workload": "16 new rows x 4096 channels, one tensor", "ms": enc_med,
+        "encode_decode_step": {"workload": "16 new rows x 4096 channels, one tensor (mean over 64 back-to-back launches)", "ms": enc_med,
                                "tokens_per_s": cfg.batch / (enc_med * 1e-3)},
     }
     del graph

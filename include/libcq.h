@@ -155,6 +155,20 @@ CQ_API cq_status cq_decode_attention(const void *q,
                               void *out, void *workspace, size_t workspace_bytes,
                               void *stream);
 
+/*
+ * Measurement aids (no part of the method; benchmarks use them as yardsticks).
+ *
+ * cq_probe_stream_read  reads `bytes` (multiple of 16) from device memory `src` once, 16 bytes
+ *                       per lane with the same non-temporal loads the decode kernel uses, and
+ *                       XORs what it read into `sink` (device, at least 8 KiB, any contents).
+ * cq_probe_copy         copies `bytes` (multiple of 16) from `src` to `dst` (device, 16-byte
+ *                       aligned, not overlapping): a kernel whose HBM traffic is known exactly.
+ * Errors: CQ_ERR_INVALID_ARG for null / misaligned pointers or a size that is zero or not a
+ * multiple of 16; CQ_ERR_HIP if the launch fails.
+ */
+CQ_API cq_status cq_probe_stream_read(const void *src, size_t bytes, void *sink, void *stream);
+CQ_API cq_status cq_probe_copy(const void *src, void *dst, size_t bytes, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -26,7 +26,7 @@ TILE_TOKENS = 64
 EXPORTS = (
     "cq_version", "cq_status_string", "cq_format_check", "cq_code_bytes_per_token_head",
     "cq_cache_bytes", "cq_encode", "cq_decode_default_split", "cq_decode_workspace_bytes",
-    "cq_decode_attention",
+    "cq_decode_attention", "cq_probe_stream_read", "cq_probe_copy",
 )
 
 
@@ -97,6 +97,10 @@ def load() -> ctypes.CDLL:
     lib.cq_decode_attention.restype = ctypes.c_int
     lib.cq_decode_attention.argtypes = [vp, vp, vp, vp, vp, ctypes.c_float, fp, i32, i32, i32, i32,
                                         vp, i32, vp, vp, ctypes.c_size_t, vp]
+    lib.cq_probe_stream_read.restype = ctypes.c_int
+    lib.cq_probe_stream_read.argtypes = [vp, ctypes.c_size_t, vp, vp]
+    lib.cq_probe_copy.restype = ctypes.c_int
+    lib.cq_probe_copy.argtypes = [vp, vp, ctypes.c_size_t, vp]
     _lib = lib
     return lib
 
@@ -160,9 +164,22 @@ def alloc_cache(fmt: CQFormat, batch: int, t_cap: int, device="cuda"):
     return torch.empty(n, dtype=torch.uint8, device=device)
 
 
-def cq_encode(x, centroids, fmt: CQFormat, codes, t_offset: int, t_cap: int, stream=None) -> None:
-    """x fp16 [B, T_new, D] (last dim contiguous), centroids fp16 [G, 2^b, c] contiguous,
-    codes uint8 packed cache; writes the codes of the new tokens at positions t_offset..."""
+class PreparedCall:
+    """An entry point with its arguments marshalled once: ``call()`` (or ``call(stream)``) only
+    crosses the C ABI.  Keeps the tensors it points into alive."""
+    __slots__ = ("_fn", "_args", "_keep", "_name")
+
+    def __init__(self, fn, args, keep, name):
+        self._fn, self._args, self._keep, self._name = fn, args, keep, name
+
+    def __call__(self, stream=None):
+        st = self._fn(*self._args, _stream_handle(stream))
+        if st != CQ_OK:
+            raise CQError(st, self._name)
+
+
+def prepare_encode(x, centroids, fmt: CQFormat, codes, t_offset: int, t_cap: int) -> PreparedCall:
+    """Check and marshal the arguments of cq_encode once (see cq_encode for their meaning)."""
     import torch
     _dev(x, torch.float16, "x")
     _dev(centroids, torch.float16, "centroids")
@@ -177,17 +194,21 @@ def cq_encode(x, centroids, fmt: CQFormat, codes, t_offset: int, t_cap: int, str
     if codes.numel() < cq_cache_bytes(fmt, batch, t_cap):
         raise ValueError("codes buffer is smaller than cq_cache_bytes(fmt, batch, t_cap)")
     f = fmt._c()
-    st = load().cq_encode(x.data_ptr(), x.stride(0), x.stride(1), centroids.data_ptr(), ctypes.byref(f),
-                          batch, t_new, codes.data_ptr(), t_offset, t_cap, _stream_handle(stream))
-    if st != CQ_OK:
-        raise CQError(st, "cq_encode")
+    args = (x.data_ptr(), x.stride(0), x.stride(1), centroids.data_ptr(), ctypes.byref(f),
+            batch, t_new, codes.data_ptr(), t_offset, t_cap)
+    return PreparedCall(load().cq_encode, args, (x, centroids, codes, f), "cq_encode")
 
 
-def cq_decode_attention(q, k_codes, v_codes, k_centroids, v_centroids, scale: float, fmt: CQFormat,
-                        t: int, t_cap: int, seq_lens=None, tokens_per_split: int = 0,
-                        out=None, workspace=None, stream=None):
-    """q fp16 [B, Hq, head_dim]; packed caches uint8; centroids fp16 [G, 2^b, c].  Returns out
-    fp16 [B, Hq, head_dim] (allocated with torch if not given, as is the workspace)."""
+def cq_encode(x, centroids, fmt: CQFormat, codes, t_offset: int, t_cap: int, stream=None) -> None:
+    """x fp16 [B, T_new, D] (last dim contiguous), centroids fp16 [G, 2^b, c] contiguous,
+    codes uint8 packed cache; writes the codes of the new tokens at positions t_offset..."""
+    prepare_encode(x, centroids, fmt, codes, t_offset, t_cap)(stream)
+
+
+def prepare_decode_attention(q, k_codes, v_codes, k_centroids, v_centroids, scale: float, fmt: CQFormat,
+                             t: int, t_cap: int, seq_lens=None, tokens_per_split: int = 0,
+                             out=None, workspace=None):
+    """Check and marshal the arguments of cq_decode_attention once.  Returns (call, out)."""
     import torch
     _dev(q, torch.float16, "q")
     _dev(k_codes, torch.uint8, "k_codes")
@@ -223,11 +244,43 @@ def cq_decode_attention(q, k_codes, v_codes, k_centroids, v_centroids, scale: fl
     else:
         _dev(workspace, torch.uint8, "workspace")
     f = fmt._c()
-    st = load().cq_decode_attention(q.data_ptr(), k_codes.data_ptr(), v_codes.data_ptr(),
-                                    k_centroids.data_ptr(), v_centroids.data_ptr(), float(scale),
-                                    ctypes.byref(f), batch, n_q_heads, t, t_cap, sl_ptr,
-                                    tokens_per_split, out.data_ptr(), workspace.data_ptr(),
-                                    workspace.numel(), _stream_handle(stream))
-    if st != CQ_OK:
-        raise CQError(st, "cq_decode_attention")
+    args = (q.data_ptr(), k_codes.data_ptr(), v_codes.data_ptr(), k_centroids.data_ptr(),
+            v_centroids.data_ptr(), float(scale), ctypes.byref(f), batch, n_q_heads, t, t_cap, sl_ptr,
+            tokens_per_split, out.data_ptr(), workspace.data_ptr(), workspace.numel())
+    keep = (q, k_codes, v_codes, k_centroids, v_centroids, seq_lens, out, workspace, f)
+    return PreparedCall(load().cq_decode_attention, args, keep, "cq_decode_attention"), out
+
+
+def cq_decode_attention(q, k_codes, v_codes, k_centroids, v_centroids, scale: float, fmt: CQFormat,
+                        t: int, t_cap: int, seq_lens=None, tokens_per_split: int = 0,
+                        out=None, workspace=None, stream=None):
+    """q fp16 [B, Hq, head_dim]; packed caches uint8; centroids fp16 [G, 2^b, c].  Returns out
+    fp16 [B, Hq, head_dim] (allocated with torch if not given, as is the workspace)."""
+    call, out = prepare_decode_attention(q, k_codes, v_codes, k_centroids, v_centroids, scale, fmt, t, t_cap,
+                                         seq_lens, tokens_per_split, out, workspace)
+    call(stream)
     return out
+
+
+def cq_probe_stream_read(src, sink, stream=None) -> None:
+    """Read every byte of the uint8 device tensor `src` once (measurement aid)."""
+    import torch
+    _dev(src, torch.uint8, "src")
+    _dev(sink, torch.uint8, "sink")
+    if sink.numel() < 8192:
+        raise ValueError("sink must hold at least 8 KiB")
+    st = load().cq_probe_stream_read(src.data_ptr(), src.numel(), sink.data_ptr(), _stream_handle(stream))
+    if st != CQ_OK:
+        raise CQError(st, "cq_probe_stream_read")
+
+
+def cq_probe_copy(src, dst, stream=None) -> None:
+    """dst[:] = src for uint8 device tensors of equal size (measurement aid)."""
+    import torch
+    _dev(src, torch.uint8, "src")
+    _dev(dst, torch.uint8, "dst")
+    if dst.numel() != src.numel():
+        raise ValueError("src and dst must have the same size")
+    st = load().cq_probe_copy(src.data_ptr(), dst.data_ptr(), src.numel(), _stream_handle(stream))
+    if st != CQ_OK:
+        raise CQError(st, "cq_probe_copy")

@@ -240,11 +240,12 @@ __global__ __launch_bounds__(NT, 4) void decode_split_kernel(DecodeArgs a)
     constexpr int NW = NT / 64;         // wavefronts
     constexpr int D = GH * C;           // head_dim
     // tiles in flight per wavefront (about 4 KB; less where registers are short)
-    constexpr int PF = GH == 16 ? 4 : (GH == 32 ? 2 : 1);
+    constexpr int PF = B == 10 ? 2 : (GH == 16 ? 4 : (GH == 32 ? 2 : 1));
     constexpr int JPL = 8 / C;          // centroids per 16-byte load
     constexpr int NCH = GH / 16;        // 16-group chunks
     constexpr int UNITS = 16 * K / JPL; // 16-byte loads per chunk
     constexpr int IPT = UNITS / NT;     // ... per thread
+    constexpr int KB = IPT < 8 ? IPT : 8;   // ... requested together
     static_assert(UNITS % NT == 0 && NT % 16 == 0, "thread count must divide the codebook walk");
     extern __shared__ float smem[];
     float* tab = smem;                              // [K][RW]; first the score table, then the bins
@@ -287,7 +288,6 @@ __global__ __launch_bounds__(NT, 4) void decode_split_kernel(DecodeArgs a)
     const int my_tiles = (tile1 - tile0 - wave + NW - 1) / NW;   // tiles tile0 + wave + k NW
 
     Streamer<GH, B, PF> st;
-    st.begin(kstream, my_tiles, tile0 + wave, NW, lane);         // key codes are on their way
 
     // ---- 1. score table ------------------------------------------------------------------
     // unit u = tid + k NT of a 16-group chunk: group gl = u % 16 (fixed per thread), centroids
@@ -302,24 +302,29 @@ __global__ __launch_bounds__(NT, 4) void decode_split_kernel(DecodeArgs a)
             unsigned qw[C / 2];
 #pragma unroll
             for (int i = 0; i < C / 2; ++i) qw[i] = *reinterpret_cast<const unsigned*>(qh + g * C + 2 * i);
-            Cent16 raw[IPT];
 #pragma unroll
-            for (int k = 0; k < IPT; ++k) raw[k] = load_cent16(ck + (size_t)((tid + k * NT) >> 4) * 8);
+            for (int k0 = 0; k0 < IPT; k0 += KB) {
+                Cent16 raw[KB];
 #pragma unroll
-            for (int k = 0; k < IPT; ++k) {
-                const int j0 = ((tid + k * NT) >> 4) * JPL;
+                for (int k = 0; k < KB; ++k) raw[k] = load_cent16(ck + (size_t)((tid + (k0 + k) * NT) >> 4) * 8);
+                // the first key tiles are requested behind the first centroids: loads return in
+                // order, so the table build waits for L2 only while HBM latency runs in the shadow
+                if (ch == 0 && k0 == 0) st.begin(kstream, my_tiles, tile0 + wave, NW, lane);
 #pragma unroll
-                for (int jj = 0; jj < JPL; ++jj) {
-                    float dot = 0.f;
+                for (int k = 0; k < KB; ++k) {
+                    const int j0 = ((tid + (k0 + k) * NT) >> 4) * JPL;
 #pragma unroll
-                    for (int i = 0; i < C / 2; ++i)
-                        dot = __builtin_amdgcn_fdot2(__builtin_bit_cast(half2_t, raw[k].w[jj * (C / 2) + i]),
-                                                     __builtin_bit_cast(half2_t, qw[i]), dot, false);
-                    const float v = dot * a.scale_log2e;
-                    float* dst = tab + (j0 + jj) * RW + g * R;
-                    if constexpr (R == 4) *reinterpret_cast<float4*>(dst) = make_float4(v, v, v, v);
-                    else if constexpr (R == 2) *reinterpret_cast<float2*>(dst) = make_float2(v, v);
-                    else *dst = v;
+                    for (int jj = 0; jj < JPL; ++jj) {
+                        float dot = 0.f;
+#pragma unroll
+                        for (int i = 0; i < C / 2; ++i)
+                            dot = __builtin_amdgcn_fdot2(__builtin_bit_cast(half2_t, raw[k].w[jj * (C / 2) + i]),
+                                                         __builtin_bit_cast(half2_t, qw[i]), dot, false);
+                        const float v = dot * a.scale_log2e;
+                        float* dst = tab + (j0 + jj) * RW + g * R;
+                        if constexpr (R == 2) *reinterpret_cast<float2*>(dst) = make_float2(v, v);
+                        else *dst = v;
+                    }
                 }
             }
         }
@@ -390,6 +395,18 @@ __global__ __launch_bounds__(NT, 4) void decode_split_kernel(DecodeArgs a)
     // same walk as the table build; thread-private sums over its centroids of group gl in every
     // chunk, then lanes l, l+16, l+32, l+48 and the wavefronts are added up.
     const int gl = tid & 15;
+    // the value centroids are requested before the barrier so that their latency overlaps the
+    // wait for the slowest wavefront (where registers allow: not with 1024 rows)
+    constexpr bool EARLY = IPT * NCH <= 8;
+    Cent16 rawv[EARLY ? NCH : 1][KB];
+    if constexpr (EARLY) {
+#pragma unroll
+        for (int ch = 0; ch < NCH; ++ch) {
+            const uint16_t* cv = a.v_centroids + (size_t)(hkv * GH + ch * 16 + gl) * K * C;
+#pragma unroll
+            for (int k = 0; k < IPT; ++k) rawv[ch][k] = load_cent16(cv + (size_t)((tid + k * NT) >> 4) * 8);
+        }
+    }
     lane_sum = wave_sum_u32(lane_sum);
     __syncthreads();                                // all bin updates done; the scores are dead
     if (lane == 0) scr[wave] = __uint_as_float(lane_sum);
@@ -397,28 +414,32 @@ __global__ __launch_bounds__(NT, 4) void decode_split_kernel(DecodeArgs a)
     float acc[NCH][C];
 #pragma unroll
     for (int ch = 0; ch < NCH; ++ch) {
-        const uint16_t* cv = a.v_centroids + (size_t)(hkv * GH + ch * 16 + gl) * K * C;
-        Cent16 raw[IPT];
-#pragma unroll
-        for (int k = 0; k < IPT; ++k) raw[k] = load_cent16(cv + (size_t)((tid + k * NT) >> 4) * 8);
 #pragma unroll
         for (int i = 0; i < C; ++i) acc[ch][i] = 0.f;
 #pragma unroll
-        for (int k = 0; k < IPT; ++k) {
-            const int j0 = ((tid + k * NT) >> 4) * JPL;
+        for (int k0 = 0; k0 < IPT; k0 += KB) {
+            if constexpr (!EARLY) {
+                const uint16_t* cv = a.v_centroids + (size_t)(hkv * GH + ch * 16 + gl) * K * C;
 #pragma unroll
-            for (int jj = 0; jj < JPL; ++jj) {
-                const float* src = tab + (j0 + jj) * RW + (ch * 16 + gl) * R;
-                unsigned cnt;
-                if constexpr (R == 4) { const uint4 x = *reinterpret_cast<const uint4*>(src); cnt = (x.x + x.y) + (x.z + x.w); }
-                else if constexpr (R == 2) { const uint2 x = *reinterpret_cast<const uint2*>(src); cnt = x.x + x.y; }
-                else cnt = *reinterpret_cast<const unsigned*>(src);
-                const float bin = (float)cnt * fx_inv;
+                for (int k = 0; k < KB; ++k) rawv[0][k] = load_cent16(cv + (size_t)((tid + (k0 + k) * NT) >> 4) * 8);
+            }
+            const Cent16 (&raw)[KB] = rawv[EARLY ? ch : 0];
 #pragma unroll
-                for (int i = 0; i < C / 2; ++i) {
-                    const half2_t h = __builtin_bit_cast(half2_t, raw[k].w[jj * (C / 2) + i]);
-                    acc[ch][2 * i] = __builtin_fmaf(bin, (float)h.x, acc[ch][2 * i]);
-                    acc[ch][2 * i + 1] = __builtin_fmaf(bin, (float)h.y, acc[ch][2 * i + 1]);
+            for (int k = 0; k < KB; ++k) {
+                const int j0 = ((tid + (k0 + k) * NT) >> 4) * JPL;
+#pragma unroll
+                for (int jj = 0; jj < JPL; ++jj) {
+                    const float* src = tab + (j0 + jj) * RW + (ch * 16 + gl) * R;
+                    unsigned cnt;
+                    if constexpr (R == 2) { const uint2 x = *reinterpret_cast<const uint2*>(src); cnt = x.x + x.y; }
+                    else cnt = *reinterpret_cast<const unsigned*>(src);
+                    const float bin = (float)cnt * fx_inv;
+#pragma unroll
+                    for (int i = 0; i < C / 2; ++i) {
+                        const half2_t h = __builtin_bit_cast(half2_t, raw[k].w[jj * (C / 2) + i]);
+                        acc[ch][2 * i] = __builtin_fmaf(bin, (float)h.x, acc[ch][2 * i]);
+                        acc[ch][2 * i + 1] = __builtin_fmaf(bin, (float)h.y, acc[ch][2 * i + 1]);
+                    }
                 }
             }
         }

@@ -96,3 +96,29 @@ def check_attention(out_gpu: np.ndarray, ref: np.ndarray) -> dict:
     e = attention_errors(out_gpu, ref)
     assert e["max_rel_floored"] <= ATTN_RTOL, e
     return e
+
+
+def head_stream_codes(cache: torch.Tensor, fmt: cq.CQFormat, batch: int, t_cap: int, n: int, h: int,
+                      n_tokens: int) -> np.ndarray:
+    """Codes [n_tokens, Gh] of one (sequence, KV head) stream of a packed cache."""
+    tb = L.tile_bytes(fmt.c, fmt.b, fmt.head_dim)
+    per_stream = (t_cap // 64) * tb
+    off = (n * fmt.n_kv_heads + h) * per_stream
+    arr = cache[off:off + per_stream].cpu().numpy().reshape(1, 1, t_cap // 64, tb)
+    return L.unpack(arr, fmt.c, fmt.b, fmt.head_dim, 1, n_tokens)[0]
+
+
+def sequence_codes(cache: torch.Tensor, fmt: cq.CQFormat, batch: int, t_cap: int, n: int, n_tokens: int,
+                   t_offset: int = 0) -> np.ndarray:
+    """Codes [n_tokens, G] of one sequence of a packed cache."""
+    tb = L.tile_bytes(fmt.c, fmt.b, fmt.head_dim)
+    per_seq = fmt.n_kv_heads * (t_cap // 64) * tb
+    arr = cache[n * per_seq:(n + 1) * per_seq].cpu().numpy().reshape(1, fmt.n_kv_heads, t_cap // 64, tb)
+    return L.unpack(arr, fmt.c, fmt.b, fmt.head_dim, fmt.n_kv_heads, n_tokens, t_offset)[0]
+
+
+def oracle_head_attention(q_row: np.ndarray, k_codes: np.ndarray, v_codes: np.ndarray, ck_head: np.ndarray,
+                          cv_head: np.ndarray, scale: float) -> np.ndarray:
+    """Oracle attention of ONE query head over one KV head's codes: q_row fp16 [d], codes [T, Gh],
+    codebooks fp16 [Gh, 2^b, c] -> fp64 [d]."""
+    return O.attention(q_row[None, None, :], k_codes[None], v_codes[None], ck_head, cv_head, scale, 1)[0, 0]

@@ -1,0 +1,82 @@
+"""GPU parity at the full sizes of the named workloads, in the launch configuration bench.py
+times (default context split, caches filled by REALLY encoding generated activations on the
+device).  The oracle cannot redo these sizes whole, so it recomputes sampled outputs one by one:
+all groups of sampled tokens for cq_encode, whole (sequence, head) rows for cq_decode_attention."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import paper_2405_03917_amd as cq
+import synth
+
+from gpu_util import (check_attention, check_codes, dev, head_stream_codes, oracle_head_attention,
+                      sequence_codes)
+
+pytestmark = pytest.mark.gpu
+
+
+def _fill_and_check(cfg_id, n_attn_samples, n_token_samples, chunk_tokens):
+    cfg = synth.CONFIGS[cfg_id]
+    fmt = cq.CQFormat(cfg.c, cfg.b, cfg.head_dim, cfg.n_kv_heads)
+    B, T, D = cfg.batch, cfg.context, cfg.kv_channels
+    Gh = cfg.head_dim // cfg.c
+    rng = np.random.default_rng(1000 + cfg_id)
+    rk, rv = synth.tensor_recipe(cfg_id, 0, "k", D), synth.tensor_recipe(cfg_id, 0, "v", D)
+    ck_h, cv_h = synth.sample_codebook(rk, cfg.c, cfg.b), synth.sample_codebook(rv, cfg.c, cfg.b)
+    ck, cv = dev(ck_h), dev(cv_h)
+    kcache, vcache = cq.alloc_cache(fmt, B, T), cq.alloc_cache(fmt, B, T)
+    per_seq = kcache.numel() // B
+    check_seq = int(rng.integers(0, B))
+    for n in range(B):
+        for t0 in range(0, T, chunk_tokens):
+            tn = min(chunk_tokens, T - t0)
+            xk = synth.sample_activations_torch(rk, tn, 17 * n + t0, "cuda").view(1, tn, D)
+            xv = synth.sample_activations_torch(rv, tn, 17 * n + t0 + 5, "cuda").view(1, tn, D)
+            cq.cq_encode(xk, ck, fmt, kcache[n * per_seq:(n + 1) * per_seq], t0, T)
+            cq.cq_encode(xv, cv, fmt, vcache[n * per_seq:(n + 1) * per_seq], t0, T)
+            if n == check_seq and t0 == 0:
+                # cq_encode, sampled tokens of this chunk, all groups, both tensors
+                rows = np.sort(rng.choice(tn, size=n_token_samples, replace=False))
+                rows[0], rows[-1] = 0, tn - 1
+                torch.cuda.synchronize()
+                kc = sequence_codes(kcache, fmt, B, T, n, tn)
+                vc = sequence_codes(vcache, fmt, B, T, n, tn)
+                check_codes(kc[rows], xk[0, rows].cpu().numpy(), ck_h)
+                check_codes(vc[rows], xv[0, rows].cpu().numpy(), cv_h)
+            del xk, xv
+    q_h = synth.sample_query(cfg_id, 0, B, cfg.n_q_heads, cfg.head_dim)
+    scale = 1.0 / math.sqrt(cfg.head_dim)
+    out = cq.cq_decode_attention(dev(q_h), kcache, vcache, ck, cv, scale, fmt, T, T)
+    torch.cuda.synchronize()
+    out_h = out.cpu().numpy()
+    assert np.all(np.isfinite(out_h.astype(np.float64)))
+    rep = cfg.n_q_heads // cfg.n_kv_heads
+    picks = {(0, 0), (B - 1, cfg.n_q_heads - 1)}
+    while len(picks) < n_attn_samples:
+        picks.add((int(rng.integers(0, B)), int(rng.integers(0, cfg.n_q_heads))))
+    for n, hq in sorted(picks):
+        hk = hq // rep
+        kc = head_stream_codes(kcache, fmt, B, T, n, hk, T)
+        vc = head_stream_codes(vcache, fmt, B, T, n, hk, T)
+        ref = oracle_head_attention(q_h[n, hq], kc, vc, ck_h[hk * Gh:(hk + 1) * Gh], cv_h[hk * Gh:(hk + 1) * Gh], scale)
+        check_attention(out_h[n, hq][None], ref[None])
+    return cq.cq_decode_default_split(fmt, B, cfg.n_q_heads, T)
+
+
+def test_config2_one_layer_cq4c8b_batch16_ctx4096():
+    split = _fill_and_check(2, n_attn_samples=6, n_token_samples=12, chunk_tokens=4096)
+    assert split == 4096           # the configuration bench.py times: one split, no merge kernel
+
+
+def test_config3_cq2c8b_batch64_ctx8192():
+    _fill_and_check(3, n_attn_samples=4, n_token_samples=8, chunk_tokens=8192)
+
+
+def test_config4_cq8c10b_gqa_batch32_ctx16384():
+    _fill_and_check(4, n_attn_samples=4, n_token_samples=8, chunk_tokens=16384)
+
+
+def test_config5_cq8c8b_batch4_ctx131072():
+    _fill_and_check(5, n_attn_samples=3, n_token_samples=8, chunk_tokens=32768)
