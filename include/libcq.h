@@ -104,7 +104,7 @@ CQ_API size_t cq_cache_bytes(const cq_format *fmt, int32_t batch, int32_t t_cap)
  *                   positions are left untouched
  *   Distances are sum_i (x_i - centroid_i)^2 evaluated in fp32 in channel order; the lowest
  *   index wins ties.
- * Errors: CQ_ERR_INVALID_ARG for null pointers, batch/t_new <= 0, t_cap not a multiple of 64,
+ * Errors: CQ_ERR_INVALID_ARG for null pointers, batch/t_new <= 0, batch > 32767, t_cap not a multiple of 64,
  * t_offset < 0 or t_offset + t_new > t_cap, strides too small or misaligned;
  * CQ_ERR_UNSUPPORTED for a format without kernels; CQ_ERR_HIP if a launch fails.
  */
@@ -113,6 +113,18 @@ CQ_API cq_status cq_encode(const void *x, int64_t x_batch_stride, int64_t x_row_
                     int32_t batch, int32_t t_new,
                     void *codes, int32_t t_offset, int32_t t_cap,
                     void *stream);
+
+/*
+ * cq_encode_kv -- cq_encode of a key tensor and a value tensor of the same shape and strides in
+ * ONE launch (a decode step encodes a handful of rows of each: two launches would cost more than
+ * the work).  Arguments as for cq_encode, per tensor; k_codes and v_codes must differ.  The result
+ * is identical to two cq_encode calls.
+ */
+CQ_API cq_status cq_encode_kv(const void *x_k, const void *x_v, int64_t x_batch_stride, int64_t x_row_stride,
+                       const void *k_centroids, const void *v_centroids, const cq_format *fmt,
+                       int32_t batch, int32_t t_new,
+                       void *k_codes, void *v_codes, int32_t t_offset, int32_t t_cap,
+                       void *stream);
 
 /* Tokens per context split the library would pick for this problem (a multiple of 64). */
 CQ_API int32_t cq_decode_default_split(const cq_format *fmt, int32_t batch, int32_t n_q_heads, int32_t t);

@@ -25,7 +25,7 @@ TILE_TOKENS = 64
 
 EXPORTS = (
     "cq_version", "cq_status_string", "cq_format_check", "cq_code_bytes_per_token_head",
-    "cq_cache_bytes", "cq_encode", "cq_decode_default_split", "cq_decode_workspace_bytes",
+    "cq_cache_bytes", "cq_encode", "cq_encode_kv", "cq_decode_default_split", "cq_decode_workspace_bytes",
     "cq_decode_attention", "cq_probe_stream_read", "cq_probe_copy",
 )
 
@@ -90,6 +90,8 @@ def load() -> ctypes.CDLL:
     lib.cq_cache_bytes.argtypes = [fp, i32, i32]
     lib.cq_encode.restype = ctypes.c_int
     lib.cq_encode.argtypes = [vp, i64, i64, vp, fp, i32, i32, vp, i32, i32, vp]
+    lib.cq_encode_kv.restype = ctypes.c_int
+    lib.cq_encode_kv.argtypes = [vp, vp, i64, i64, vp, vp, fp, i32, i32, vp, vp, i32, i32, vp]
     lib.cq_decode_default_split.restype = i32
     lib.cq_decode_default_split.argtypes = [fp, i32, i32, i32]
     lib.cq_decode_workspace_bytes.restype = ctypes.c_size_t
@@ -197,6 +199,39 @@ def prepare_encode(x, centroids, fmt: CQFormat, codes, t_offset: int, t_cap: int
     args = (x.data_ptr(), x.stride(0), x.stride(1), centroids.data_ptr(), ctypes.byref(f),
             batch, t_new, codes.data_ptr(), t_offset, t_cap)
     return PreparedCall(load().cq_encode, args, (x, centroids, codes, f), "cq_encode")
+
+
+def prepare_encode_kv(x_k, x_v, k_centroids, v_centroids, fmt: CQFormat, k_codes, v_codes, t_offset: int,
+                      t_cap: int) -> PreparedCall:
+    """Check and marshal the arguments of cq_encode_kv once (K and V in one launch)."""
+    import torch
+    for name, t in (("x_k", x_k), ("x_v", x_v), ("k_centroids", k_centroids), ("v_centroids", v_centroids)):
+        _dev(t, torch.float16, name)
+    _dev(k_codes, torch.uint8, "k_codes")
+    _dev(v_codes, torch.uint8, "v_codes")
+    if x_k.dim() != 3 or x_k.stride(2) != 1 or x_v.shape != x_k.shape or x_v.stride() != x_k.stride():
+        raise ValueError("x_k and x_v must be [B, T_new, D] with equal shapes and strides")
+    for cb in (k_centroids, v_centroids):
+        if not cb.is_contiguous() or tuple(cb.shape) != (fmt.groups, 1 << fmt.b, fmt.c):
+            raise ValueError("centroids must be contiguous [G, 2^b, c]")
+    if x_k.shape[2] != fmt.channels:
+        raise ValueError("shapes do not match the format")
+    batch, t_new = int(x_k.shape[0]), int(x_k.shape[1])
+    need = cq_cache_bytes(fmt, batch, t_cap)
+    if k_codes.numel() < need or v_codes.numel() < need:
+        raise ValueError("code buffers are smaller than cq_cache_bytes(fmt, batch, t_cap)")
+    f = fmt._c()
+    args = (x_k.data_ptr(), x_v.data_ptr(), x_k.stride(0), x_k.stride(1), k_centroids.data_ptr(),
+            v_centroids.data_ptr(), ctypes.byref(f), batch, t_new, k_codes.data_ptr(), v_codes.data_ptr(),
+            t_offset, t_cap)
+    keep = (x_k, x_v, k_centroids, v_centroids, k_codes, v_codes, f)
+    return PreparedCall(load().cq_encode_kv, args, keep, "cq_encode_kv")
+
+
+def cq_encode_kv(x_k, x_v, k_centroids, v_centroids, fmt: CQFormat, k_codes, v_codes, t_offset: int, t_cap: int,
+                 stream=None) -> None:
+    """cq_encode of a key and a value tensor of the same shape in one launch."""
+    prepare_encode_kv(x_k, x_v, k_centroids, v_centroids, fmt, k_codes, v_codes, t_offset, t_cap)(stream)
 
 
 def cq_encode(x, centroids, fmt: CQFormat, codes, t_offset: int, t_cap: int, stream=None) -> None:

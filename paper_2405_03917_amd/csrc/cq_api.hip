@@ -91,29 +91,72 @@ size_t cq_cache_bytes(const cq_format* fmt, int32_t batch, int32_t t_cap)
     return (size_t)batch * f.n_kv_heads * (t_cap / kTileTokens) * f.tile_bytes;
 }
 
+namespace {
+
+cq_status check_encode_tensor(const Derived& f, const void* x, int64_t x_batch_stride, int64_t x_row_stride,
+                              const void* centroids, const void* codes, int32_t batch, int32_t t_new)
+{
+    if (!x || !centroids || !codes) return CQ_ERR_INVALID_ARG;
+    if (x_row_stride < f.channels || x_row_stride % 8 != 0) return CQ_ERR_INVALID_ARG;
+    if (batch > 1 && (x_batch_stride < (int64_t)t_new * x_row_stride || x_batch_stride % 8 != 0))
+        return CQ_ERR_INVALID_ARG;
+    if (!aligned16(x) || !aligned16(centroids) || !aligned16(codes)) return CQ_ERR_INVALID_ARG;
+    return CQ_OK;
+}
+
+cq_status check_encode_shape(const Derived& f, int32_t batch, int32_t t_new, int32_t t_offset, int32_t t_cap)
+{
+    if (batch <= 0 || t_new <= 0 || t_cap <= 0 || t_cap % kTileTokens != 0) return CQ_ERR_INVALID_ARG;
+    if (batch > 32767 || f.n_kv_heads > 65535) return CQ_ERR_INVALID_ARG;
+    if (t_offset < 0 || (int64_t)t_offset + t_new > t_cap) return CQ_ERR_INVALID_ARG;
+    return CQ_OK;
+}
+
+}  // namespace
+
 cq_status cq_encode(const void* x, int64_t x_batch_stride, int64_t x_row_stride,
                     const void* centroids, const cq_format* fmt,
                     int32_t batch, int32_t t_new,
                     void* codes, int32_t t_offset, int32_t t_cap, void* stream)
 {
     Derived f;
-    const cq_status st = derive(fmt, &f);
+    cq_status st = derive(fmt, &f);
     if (st != CQ_OK) return st;
-    if (!x || !centroids || !codes) return CQ_ERR_INVALID_ARG;
-    if (batch <= 0 || t_new <= 0 || t_cap <= 0 || t_cap % kTileTokens != 0) return CQ_ERR_INVALID_ARG;
-    if (batch > 65535 || f.n_kv_heads > 65535) return CQ_ERR_INVALID_ARG;
-    if (t_offset < 0 || (int64_t)t_offset + t_new > t_cap) return CQ_ERR_INVALID_ARG;
-    if (x_row_stride < f.channels || x_row_stride % 8 != 0) return CQ_ERR_INVALID_ARG;
-    if (batch > 1 && (x_batch_stride < (int64_t)t_new * x_row_stride || x_batch_stride % 8 != 0))
-        return CQ_ERR_INVALID_ARG;
-    if (!aligned16(x) || !aligned16(centroids) || !aligned16(codes)) return CQ_ERR_INVALID_ARG;
+    if ((st = check_encode_shape(f, batch, t_new, t_offset, t_cap)) != CQ_OK) return st;
+    if ((st = check_encode_tensor(f, x, x_batch_stride, x_row_stride, centroids, codes, batch, t_new)) != CQ_OK) return st;
 
     EncodeArgs a;
-    a.x = static_cast<const uint16_t*>(x);
-    a.x_batch_stride = x_batch_stride;
-    a.x_row_stride = x_row_stride;
-    a.centroids = static_cast<const uint16_t*>(centroids);
-    a.codes = static_cast<uint8_t*>(codes);
+    a.tensor[0] = EncodeTensor{static_cast<const uint16_t*>(x), x_batch_stride, x_row_stride,
+                               static_cast<const uint16_t*>(centroids), static_cast<uint8_t*>(codes)};
+    a.tensor[1] = a.tensor[0];
+    a.n_tensors = 1;
+    a.batch = batch;
+    a.t_new = t_new;
+    a.t_offset = t_offset;
+    a.t_cap = t_cap;
+    a.f = f;
+    return launch_encode(a, static_cast<hipStream_t>(stream));
+}
+
+cq_status cq_encode_kv(const void* x_k, const void* x_v, int64_t x_batch_stride, int64_t x_row_stride,
+                       const void* k_centroids, const void* v_centroids, const cq_format* fmt,
+                       int32_t batch, int32_t t_new,
+                       void* k_codes, void* v_codes, int32_t t_offset, int32_t t_cap, void* stream)
+{
+    Derived f;
+    cq_status st = derive(fmt, &f);
+    if (st != CQ_OK) return st;
+    if ((st = check_encode_shape(f, batch, t_new, t_offset, t_cap)) != CQ_OK) return st;
+    if ((st = check_encode_tensor(f, x_k, x_batch_stride, x_row_stride, k_centroids, k_codes, batch, t_new)) != CQ_OK) return st;
+    if ((st = check_encode_tensor(f, x_v, x_batch_stride, x_row_stride, v_centroids, v_codes, batch, t_new)) != CQ_OK) return st;
+    if (k_codes == v_codes) return CQ_ERR_INVALID_ARG;
+
+    EncodeArgs a;
+    a.tensor[0] = EncodeTensor{static_cast<const uint16_t*>(x_k), x_batch_stride, x_row_stride,
+                               static_cast<const uint16_t*>(k_centroids), static_cast<uint8_t*>(k_codes)};
+    a.tensor[1] = EncodeTensor{static_cast<const uint16_t*>(x_v), x_batch_stride, x_row_stride,
+                               static_cast<const uint16_t*>(v_centroids), static_cast<uint8_t*>(v_codes)};
+    a.n_tensors = 2;
     a.batch = batch;
     a.t_new = t_new;
     a.t_offset = t_offset;

@@ -206,8 +206,11 @@ struct Streamer {
         }
     }
 
-    template <class Fn>
-    __device__ __forceinline__ void run(const uint8_t* stream, int n, int first, int stride, int lane, Fn&& fn)
+    // `last_requests()` is called once, after the last tile has been requested and before the
+    // last tiles are consumed: loads the caller issues there ride behind the stream.
+    template <class Fn, class Hook>
+    __device__ __forceinline__ void run(const uint8_t* stream, int n, int first, int stride, int lane, Fn&& fn,
+                                        Hook&& last_requests)
     {
         int k = 0;
         if (n >= 2 * PF) {
@@ -226,6 +229,8 @@ struct Streamer {
             for (int i = 0; i < TAIL; ++i)
                 if (k + i < n) buf[i] = load_tile<GH, B>(stream, first + (k + i) * stride, lane);
         }
+        last_requests();
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int i = 0; i < TAIL; ++i)
             if (k + i < n) fn(buf[i], k + i);
@@ -345,7 +350,7 @@ __global__ __launch_bounds__(NT, 4) void decode_split_kernel(DecodeArgs a)
         const float sv = tok < t_n ? acc0 + acc1 : -INFINITY;
         sc[sidx(lt * kTileTokens + lane)] = sv;
         lane_max = fmaxf(lane_max, sv);
-    });
+    }, [] {});
     st.begin(vstream, my_tiles, tile0 + wave, NW, lane);         // value codes are on their way
 
     lane_max = wave_max(lane_max);
@@ -381,6 +386,9 @@ __global__ __launch_bounds__(NT, 4) void decode_split_kernel(DecodeArgs a)
     __syncthreads();
 
     // ---- 3. phase V: probability bins ----------------------------------------------------
+    const int gl = tid & 15;
+    constexpr bool EARLY = IPT * NCH <= 8;
+    Cent16 rawv[EARLY ? NCH : 1][KB];
     unsigned lane_sum = 0;
     st.run(vstream, my_tiles, tile0 + wave, NW, lane, [&](const Tile<GH, B>& w, int k) {
         const int lt = wave + k * NW;
@@ -389,24 +397,23 @@ __global__ __launch_bounds__(NT, 4) void decode_split_kernel(DecodeArgs a)
         lane_sum += pf;
 #pragma unroll
         for (int s = 0; s < GH; ++s) lds_add(slot_addr<GH, B>(w, col, s), pf);
+    }, [&] {
+        // the value centroids of the epilogue are requested behind the last value tiles, so their
+        // latency overlaps the last tiles and the wait for the slowest wavefront (where registers
+        // allow: not with 1024 rows)
+        if constexpr (EARLY) {
+#pragma unroll
+            for (int ch = 0; ch < NCH; ++ch) {
+                const uint16_t* cv = a.v_centroids + (size_t)(hkv * GH + ch * 16 + gl) * K * C;
+#pragma unroll
+                for (int k = 0; k < IPT; ++k) rawv[ch][k] = load_cent16(cv + (size_t)((tid + k * NT) >> 4) * 8);
+            }
+        }
     });
 
     // ---- 4. epilogue: o = bins . C_V -----------------------------------------------------
     // same walk as the table build; thread-private sums over its centroids of group gl in every
     // chunk, then lanes l, l+16, l+32, l+48 and the wavefronts are added up.
-    const int gl = tid & 15;
-    // the value centroids are requested before the barrier so that their latency overlaps the
-    // wait for the slowest wavefront (where registers allow: not with 1024 rows)
-    constexpr bool EARLY = IPT * NCH <= 8;
-    Cent16 rawv[EARLY ? NCH : 1][KB];
-    if constexpr (EARLY) {
-#pragma unroll
-        for (int ch = 0; ch < NCH; ++ch) {
-            const uint16_t* cv = a.v_centroids + (size_t)(hkv * GH + ch * 16 + gl) * K * C;
-#pragma unroll
-            for (int k = 0; k < IPT; ++k) rawv[ch][k] = load_cent16(cv + (size_t)((tid + k * NT) >> 4) * 8);
-        }
-    }
     lane_sum = wave_sum_u32(lane_sum);
     __syncthreads();                                // all bin updates done; the scores are dead
     if (lane == 0) scr[wave] = __uint_as_float(lane_sum);

@@ -13,6 +13,8 @@
 // order, and break ties towards the lowest index.
 #include <hip/hip_runtime.h>
 
+#include <type_traits>
+
 #include "cq_internal.hpp"
 
 namespace cq {
@@ -76,7 +78,8 @@ __global__ __launch_bounds__(NW * 64) void encode_tokens_kernel(EncodeArgs a)
     const int lane = tid & 63;
     const int wave = tid >> 6;
     const int hkv = blockIdx.y;
-    const int n = blockIdx.z;
+    const int n = blockIdx.z % a.batch;
+    const EncodeTensor& ten = a.tensor[blockIdx.z / a.batch];
 
     const int first_tile = a.t_offset / kTileTokens;
     const int t_end = a.t_offset + a.t_new;           // one past the last cache position
@@ -91,11 +94,11 @@ __global__ __launch_bounds__(NW * 64) void encode_tokens_kernel(EncodeArgs a)
         pos[k] = (wg_tile + wave * TPL + k) * kTileTokens + lane;
         valid[k] = pos[k] >= a.t_offset && pos[k] < t_end;
         const int t = valid[k] ? pos[k] - a.t_offset : 0;
-        xrow[k] = a.x + (size_t)n * a.x_batch_stride + (size_t)t * a.x_row_stride + (size_t)hkv * GH * C;
+        xrow[k] = ten.x + (size_t)n * ten.x_batch_stride + (size_t)t * ten.x_row_stride + (size_t)hkv * GH * C;
     }
 
     auto stage = [&](int g, int buf) {
-        const uint16_t* src = a.centroids + (size_t)(hkv * GH + g) * K * C;
+        const uint16_t* src = ten.centroids + (size_t)(hkv * GH + g) * K * C;
         for (int i = tid * 2; i < K * C; i += NT * 2) {
             const half2_t h = *reinterpret_cast<const half2_t*>(src + i);
             cb[buf][i] = (float)h.x;
@@ -149,7 +152,7 @@ __global__ __launch_bounds__(NW * 64) void encode_tokens_kernel(EncodeArgs a)
 #pragma unroll
     for (int k = 0; k < TPL; ++k) {
         if (!valid[k]) continue;
-        uint8_t* tile = a.codes + stream + (size_t)(pos[k] / kTileTokens) * TILE_BYTES;
+        uint8_t* tile = ten.codes + stream + (size_t)(pos[k] / kTileTokens) * TILE_BYTES;
 #pragma unroll
         for (int p = 0; p < P; ++p) {
             const uint4 v = *reinterpret_cast<const uint4*>(&rec[wave * TPL + k][p * 1024 + lane * 16]);
@@ -178,14 +181,15 @@ __global__ __launch_bounds__(256) void encode_centroids_kernel(EncodeArgs a)
     const int tid = threadIdx.x;
     const int r = tid & 15;
     const int g_abs = blockIdx.x;
+    const EncodeTensor& ten = a.tensor[blockIdx.z];
     const int total = a.batch * a.t_new;
     const int tt = blockIdx.y * kSmallTokens + (tid >> 4);
     const bool valid = tt < total;
     const int n = valid ? tt / a.t_new : 0, t = valid ? tt % a.t_new : 0;
 
     float x[C];
-    load_halfs<C>(a.x + (size_t)n * a.x_batch_stride + (size_t)t * a.x_row_stride + (size_t)g_abs * C, x);
-    const uint16_t* cen = a.centroids + ((size_t)g_abs * K + r) * C;
+    load_halfs<C>(ten.x + (size_t)n * ten.x_batch_stride + (size_t)t * ten.x_row_stride + (size_t)g_abs * C, x);
+    const uint16_t* cen = ten.centroids + ((size_t)g_abs * K + r) * C;
 
     // d >= +0, so its bit pattern orders like the value; the index in the low word makes the
     // minimum pick the lowest index among equal distances
@@ -209,7 +213,7 @@ __global__ __launch_bounds__(256) void encode_centroids_kernel(EncodeArgs a)
         const int u = pos & (kTileTokens - 1);
         const int hkv = g_abs / GH, g = g_abs % GH;
         const int slot = (g - u) & (GH - 1);
-        uint8_t* tile = a.codes + ((size_t)(n * a.f.n_kv_heads + hkv) * (a.t_cap / kTileTokens) + pos / kTileTokens) * TILE_BYTES;
+        uint8_t* tile = ten.codes + ((size_t)(n * a.f.n_kv_heads + hkv) * (a.t_cap / kTileTokens) + pos / kTileTokens) * TILE_BYTES;
         tile[(slot >> 4) * 1024 + u * 16 + (slot & 15)] = (uint8_t)(code & 0xff);
         if constexpr (B == 10) {
             // the high bits of a token's 16 codes share one word that other workgroups update too
@@ -225,22 +229,24 @@ cq_status launch_format(const EncodeArgs& a, hipStream_t stream)
 {
     if (a.t_new < 32) {
         const int total = a.batch * a.t_new;
-        dim3 grid((unsigned)a.f.groups, (unsigned)((total + kSmallTokens - 1) / kSmallTokens));
+        dim3 grid((unsigned)a.f.groups, (unsigned)((total + kSmallTokens - 1) / kSmallTokens), (unsigned)a.n_tensors);
         hipLaunchKernelGGL((encode_centroids_kernel<GH, C, B>), grid, dim3(256), 0, stream, a);
     } else {
         const int first_tile = a.t_offset / kTileTokens;
         const int last_tile = (a.t_offset + a.t_new - 1) / kTileTokens;
         const int n_tiles = last_tile - first_tile + 1;
-        const long wave_tiles = (long)n_tiles * a.f.n_kv_heads * a.batch;
-        if (wave_tiles >= 256L * 32) {
-            constexpr int NW = 4, TPL = (B == 10 ? 1 : 2);
-            dim3 grid((unsigned)((n_tiles + NW * TPL - 1) / (NW * TPL)), (unsigned)a.f.n_kv_heads, (unsigned)a.batch);
+        const long wave_tiles = (long)n_tiles * a.f.n_kv_heads * a.batch * a.n_tensors;
+        // tokens per lane trade LDS broadcast reads (one per centroid and workgroup pass) against
+        // parallelism: the more (tile, head, sequence) work there is, the more tiles a workgroup takes
+        auto launch = [&](auto nw, auto tpl) {
+            constexpr int NW = decltype(nw)::value, TPL = decltype(tpl)::value;
+            dim3 grid((unsigned)((n_tiles + NW * TPL - 1) / (NW * TPL)), (unsigned)a.f.n_kv_heads, (unsigned)(a.batch * a.n_tensors));
             hipLaunchKernelGGL((encode_tokens_kernel<GH, C, B, NW, TPL>), grid, dim3(NW * 64), 0, stream, a);
-        } else {
-            constexpr int NW = (B == 10 ? 2 : 1), TPL = 1;
-            dim3 grid((unsigned)((n_tiles + NW * TPL - 1) / (NW * TPL)), (unsigned)a.f.n_kv_heads, (unsigned)a.batch);
-            hipLaunchKernelGGL((encode_tokens_kernel<GH, C, B, NW, TPL>), grid, dim3(NW * 64), 0, stream, a);
-        }
+        };
+        using std::integral_constant;
+        if (wave_tiles >= 16384 && n_tiles >= 16) launch(integral_constant<int, 4>{}, integral_constant<int, (B == 10 ? 2 : 4)>{});
+        else if (wave_tiles >= 4096 && n_tiles >= 4) launch(integral_constant<int, 2>{}, integral_constant<int, 2>{});
+        else launch(integral_constant<int, 1>{}, integral_constant<int, 1>{});
     }
     if (hipGetLastError() != hipSuccess) return CQ_ERR_HIP;
     return CQ_OK;

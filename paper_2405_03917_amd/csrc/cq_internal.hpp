@@ -26,11 +26,17 @@ struct Derived {
 // Host-side format check shared by every entry point.
 cq_status derive(const cq_format* fmt, Derived* out);
 
-struct EncodeArgs {
+// One or two tensors (K alone, or K and V of the same shape) encoded by one launch.
+struct EncodeTensor {
     const uint16_t* x;
     int64_t x_batch_stride, x_row_stride;
     const uint16_t* centroids;
     uint8_t* codes;
+};
+
+struct EncodeArgs {
+    EncodeTensor tensor[2];
+    int n_tensors;
     int batch, t_new, t_offset, t_cap;
     Derived f;
 };

@@ -89,6 +89,23 @@ def test_encode_large_batch_of_tiles_uses_the_wide_kernel():
         check_codes(codes[n, rows], xg[n, rows].cpu().numpy(), cb)
 
 
+@pytest.mark.parametrize("c,b", FORMATS)
+@pytest.mark.parametrize("t_new,t_off", [(3, 130), (200, 37)])
+def test_encode_kv_equals_two_encodes(c, b, t_new, t_off):
+    hkv, B, t_cap = 2, 3, 320
+    fmt = cq.CQFormat(c, b, 128, hkv)
+    xk, ck = _inputs(15, c, b, hkv, B, t_new, "k")
+    xv, cv = _inputs(15, c, b, hkv, B, t_new, "v")
+    kc1 = gpu_encode(xk, ck, fmt, t_cap, t_off)
+    vc1 = gpu_encode(xv, cv, fmt, t_cap, t_off)
+    nbytes = cq.cq_cache_bytes(fmt, B, t_cap)
+    kc2 = torch.full((nbytes,), 0xA5, dtype=torch.uint8, device="cuda")
+    vc2 = torch.full((nbytes,), 0xA5, dtype=torch.uint8, device="cuda")
+    cq.cq_encode_kv(dev(xk), dev(xv), dev(ck), dev(cv), fmt, kc2, vc2, t_off, t_cap)
+    torch.cuda.synchronize()
+    assert torch.equal(kc1, kc2) and torch.equal(vc1, vc2)
+
+
 def test_encode_ties_and_exact_hits():
     c, b, hkv = 8, 8, 1
     fmt = cq.CQFormat(c, b, 128, hkv)
