@@ -6,17 +6,17 @@
 Workload (the second named configuration): CQ-4c8b (2 bits per channel) on a Llama-2-7B-shaped
 KV cache -- 32 layers, batch 16, 32 heads x 128, context 4096, MHA.  One STEP is one decode step
 of the whole hot path over all 32 layers: per layer, encode the 16 new key rows and the 16 new
-value rows into cache position 4095 (one cq_encode_kv launch) and attend over all 4096 cached tokens
-(cq_decode_attention).  Every layer has its own codebooks, caches, queries and new rows (4 GiB of
+value rows into cache position 4095 and attend over all 4096 cached tokens -- one fused
+cq_decode_step launch, bit-identical to cq_encode_kv followed by cq_decode_attention.  Every layer has its own codebooks, caches, queries and new rows (4 GiB of
 codes in total, far more than the 256 MB Infinity Cache, so code reads are real HBM reads).
 
 Inputs are synthetic and resident in HBM before the timed region: correlated-Gaussian K/V rows
 (synth/generator.py) drawn on the device and REALLY encoded with cq_encode to fill the caches.
 
-The timed region replays a HIP graph of the step (64 kernel launches) K times between two
+The timed region replays a HIP graph of the step (32 kernel launches) K times between two
 synchronisations.  After it, the same launches are run eagerly with a HIP event pair around
-every cq_decode_attention call to obtain the decode kernel's own average duration (with a single
-context split, as here, that call is exactly one kernel).
+every cq_decode_step call to obtain the kernel's own average duration (with a single context
+split, as here, that call is exactly one kernel).
 
 One JSON line is printed on stdout; progress goes to stderr.
 """
@@ -46,7 +46,7 @@ def log(*a):
 
 class LayerState:
     """Device buffers of one layer."""
-    __slots__ = ("ck", "cv", "kcache", "vcache", "q", "xk_new", "xv_new", "out", "ws", "enc_kv", "dec")
+    __slots__ = ("ck", "cv", "kcache", "vcache", "q", "xk_new", "xv_new", "out", "ws", "enc_kv", "dec", "step")
 
 
 def build_workload(cq, synth, torch, cfg, n_layers, fill_chunk_tokens=16384):
@@ -102,16 +102,26 @@ def prepare_calls(cq, fmt, cfg, t_cap, layers, scale):
         st.enc_kv = cq.prepare_encode_kv(st.xk_new, st.xv_new, st.ck, st.cv, fmt, st.kcache, st.vcache, t_off, t_cap)
         st.dec, _ = cq.prepare_decode_attention(st.q, st.kcache, st.vcache, st.ck, st.cv, scale, fmt, T, t_cap,
                                                 out=st.out, workspace=st.ws)
+        st.step, _ = cq.prepare_decode_step(st.q, st.xk_new[:, 0, :], st.xv_new[:, 0, :], st.kcache, st.vcache,
+                                            st.ck, st.cv, scale, fmt, T, t_cap, out=st.out, workspace=st.ws)
 
 
 def run_step(layers, events=None):
+    """One decode step: per layer ONE cq_decode_step launch (encode the new K/V rows of the 16
+    sequences into position T-1, then attend over all T positions)."""
     for i, st in enumerate(layers):
-        st.enc_kv()
         if events is not None:
             events[i][0].record()
-        st.dec()
+        st.step()
         if events is not None:
             events[i][1].record()
+
+
+def run_step_unfused(layers):
+    """The same step as two launches per layer (cq_encode_kv, cq_decode_attention)."""
+    for st in layers:
+        st.enc_kv()
+        st.dec()
 
 
 def time_calls(torch, fn, iters, warmup=2):
@@ -255,10 +265,14 @@ def main():
     graph.replay()
     torch.cuda.synchronize()
 
-    # ---- timed region: exactly K steps ----
+    # ---- timed region: exactly K steps; a HIP event pair on the replay stream brackets them ----
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
     t0 = time.perf_counter()
+    ev0.record()
     for _ in range(args.steps):
         graph.replay()
+    ev1.record()
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     ms_per_step = dt / args.steps * 1e3
@@ -266,25 +280,28 @@ def main():
     value = kv_tokens / (dt / args.steps)
     log(f"[bench] graph replay: {ms_per_step:.3f} ms/step, {value:.3e} KV tokens/s")
 
-    # ---- eager replays with an event pair around every decode call (kernel duration) ----
-    t0 = time.perf_counter()
-    all_ms = []
-    for _ in range(args.steps):
-        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in layers]
-        run_step(layers, events=evs)
-        torch.cuda.synchronize()
-        all_ms += [a.elapsed_time(b) for a, b in evs]
-    eager_ms = (time.perf_counter() - t0) / args.steps * 1e3
-    dec_ms = sum(all_ms) / len(all_ms)
+    # mean duration of one launch over the timed region (one launch per layer; the few hundred
+    # nanoseconds of dispatch between back-to-back graph nodes are included)
+    dec_ms = ev0.elapsed_time(ev1) / (args.steps * n_layers)
     code_bytes = cfg.batch * cfg.context * 2 * cfg.kv_channels * cfg.b // (8 * cfg.c)   # per launch
     achieved = code_bytes / (dec_ms * 1e-3) / 1e9
-    roofline = {"bound": "hbm", "kernel": "decode_split_kernel<32,4,512> (one launch = one layer)",
+    roofline = {"bound": "hbm", "kernel": "decode_split_kernel<32,4,8,512,true> (cq_decode_step; one launch = one layer)",
                 "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS,
                 "traffic": TRAFFIC_BYTES_PER_LAUNCH if n_layers == cfg.layers else None,
                 "algorithmic_bytes_per_launch": code_bytes, "avg_launch_ms": dec_ms,
-                "launches_timed": len(all_ms)}
-    log(f"[bench] decode kernel avg {dec_ms * 1e3:.1f} us -> {achieved:.0f} GB/s of code reads "
-        f"({100 * achieved / HBM_PEAK_GBPS:.1f}% of 8 TB/s); eager step {eager_ms:.3f} ms")
+                "launches_timed": args.steps * n_layers}
+    log(f"[bench] step kernel avg {dec_ms * 1e3:.1f} us -> {achieved:.0f} GB/s of code reads "
+        f"({100 * achieved / HBM_PEAK_GBPS:.1f}% of 8 TB/s)")
+
+    # eager launches of the same step, and of its two-launch form, for comparison
+    eager_ms, _ = time_calls(torch, lambda: run_step(layers), 5, 1)
+    unf_med, _ = time_calls(torch, lambda: run_step_unfused(layers), 5, 1)
+    # plain decode attention alone (no fused encode), back to back over the 32 layers
+    def dec_all():
+        for st in layers:
+            st.dec()
+    dec_only_ms, _ = time_calls(torch, dec_all, 5, 1)
+    dec_only_ms /= len(layers)
 
     # yardsticks: a read-only streaming kernel (one launch over 2 GiB) and a plain copy kernel of
     # known size (256 MiB; its HBM counters calibrate the decode kernel's)
@@ -313,13 +330,16 @@ def main():
         "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": "CQ-4c8b decode step, 32 layers, batch 16, 32 heads x 128, context 4096, MHA; "
-                               "per layer: cq_encode_kv of 16 new K rows + 16 new V rows, then cq_decode_attention",
+                               "per layer: one cq_decode_step launch = encode 16 new K rows + 16 new V rows, then decode attention",
                    "format": "CQ-4c8b", "batch": cfg.batch, "context": cfg.context, "layers": n_layers,
-                   "launch": "HIP graph of 2 launches per layer", "tokens_per_split":
+                   "launch": "HIP graph of 1 launch per layer", "tokens_per_split":
                        cq.cq_decode_default_split(fmt, cfg.batch, cfg.n_q_heads, cfg.context)},
         "roofline": roofline,
         "hbm_code_read_GBps_whole_step": kv_tokens * 2 * cfg.kv_channels * cfg.b // (8 * cfg.c) / (dt / args.steps) / 1e9,
-        "eager_ms_per_step": eager_ms,
+        "eager_ms_per_step": eager_ms, "unfused_eager_ms_per_step": unf_med,
+        "decode_attention_only": {"workload": "cq_decode_attention of one layer (no fused encode), eager back-to-back "
+                                              "launches, HIP events", "ms": dec_only_ms,
+                                  "code_read_GBps": code_bytes / (dec_only_ms * 1e-3) / 1e9},
         "encode_decode_step": {"workload": "16 new K rows + 16 new V rows x 4096 channels, one cq_encode_kv launch "
                                            "(mean over 32 back-to-back launches)", "ms": enc_med,
                                "tokens_per_s_per_tensor": cfg.batch / (enc_med * 1e-3)},

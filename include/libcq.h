@@ -168,6 +168,29 @@ CQ_API cq_status cq_decode_attention(const void *q,
                               void *stream);
 
 /*
+ * cq_decode_step -- one fused launch that equals cq_encode_kv of ONE new token per sequence
+ * followed by cq_decode_attention over the context that now includes it (Section 3.2, then
+ * Eq. 1).  A decode step encodes 2 x batch rows: as separate launches those cost as much as a
+ * third of the attention itself, while the attention workgroups hold the codebooks anyway.
+ *
+ *   x_k_new, x_v_new  device, fp16 [batch][D], row stride x_row_stride (>= D, multiple of 8)
+ *   k_codes, v_codes  device, packed caches; the new token's codes are WRITTEN at position
+ *                     t - 1 (or seq_lens[n] - 1), all other positions are only read
+ *   t                 cached tokens attended per sequence INCLUDING the new one
+ *   everything else as in cq_decode_attention.
+ * The stored codes and the output are bit-identical to the two-call sequence.
+ * Errors: as cq_decode_attention and cq_encode_kv.
+ */
+CQ_API cq_status cq_decode_step(const void *q, const void *x_k_new, const void *x_v_new, int64_t x_row_stride,
+                         void *k_codes, void *v_codes,
+                         const void *k_centroids, const void *v_centroids,
+                         float scale, const cq_format *fmt,
+                         int32_t batch, int32_t n_q_heads, int32_t t, int32_t t_cap,
+                         const int32_t *seq_lens, int32_t tokens_per_split,
+                         void *out, void *workspace, size_t workspace_bytes,
+                         void *stream);
+
+/*
  * Measurement aids (no part of the method; benchmarks use them as yardsticks).
  *
  * cq_probe_stream_read  reads `bytes` (multiple of 16) from device memory `src` once, 16 bytes

@@ -26,7 +26,7 @@ TILE_TOKENS = 64
 EXPORTS = (
     "cq_version", "cq_status_string", "cq_format_check", "cq_code_bytes_per_token_head",
     "cq_cache_bytes", "cq_encode", "cq_encode_kv", "cq_decode_default_split", "cq_decode_workspace_bytes",
-    "cq_decode_attention", "cq_probe_stream_read", "cq_probe_copy",
+    "cq_decode_attention", "cq_decode_step", "cq_probe_stream_read", "cq_probe_copy",
 )
 
 
@@ -99,6 +99,9 @@ def load() -> ctypes.CDLL:
     lib.cq_decode_attention.restype = ctypes.c_int
     lib.cq_decode_attention.argtypes = [vp, vp, vp, vp, vp, ctypes.c_float, fp, i32, i32, i32, i32,
                                         vp, i32, vp, vp, ctypes.c_size_t, vp]
+    lib.cq_decode_step.restype = ctypes.c_int
+    lib.cq_decode_step.argtypes = [vp, vp, vp, i64, vp, vp, vp, vp, ctypes.c_float, fp, i32, i32, i32, i32,
+                                   vp, i32, vp, vp, ctypes.c_size_t, vp]
     lib.cq_probe_stream_read.restype = ctypes.c_int
     lib.cq_probe_stream_read.argtypes = [vp, ctypes.c_size_t, vp, vp]
     lib.cq_probe_copy.restype = ctypes.c_int
@@ -293,6 +296,38 @@ def cq_decode_attention(q, k_codes, v_codes, k_centroids, v_centroids, scale: fl
     fp16 [B, Hq, head_dim] (allocated with torch if not given, as is the workspace)."""
     call, out = prepare_decode_attention(q, k_codes, v_codes, k_centroids, v_centroids, scale, fmt, t, t_cap,
                                          seq_lens, tokens_per_split, out, workspace)
+    call(stream)
+    return out
+
+
+def prepare_decode_step(q, x_k_new, x_v_new, k_codes, v_codes, k_centroids, v_centroids, scale: float,
+                        fmt: CQFormat, t: int, t_cap: int, seq_lens=None, tokens_per_split: int = 0,
+                        out=None, workspace=None):
+    """Check and marshal the arguments of cq_decode_step once.  x_k_new / x_v_new: fp16 [B, D] (rows
+    contiguous).  Returns (call, out)."""
+    import torch
+    call, out = prepare_decode_attention(q, k_codes, v_codes, k_centroids, v_centroids, scale, fmt, t, t_cap,
+                                         seq_lens, tokens_per_split, out, workspace)
+    batch = int(q.shape[0])
+    for name, x in (("x_k_new", x_k_new), ("x_v_new", x_v_new)):
+        _dev(x, torch.float16, name)
+        if x.dim() != 2 or tuple(x.shape) != (batch, fmt.channels) or x.stride(1) != 1:
+            raise ValueError(f"{name} must be [B, D] with contiguous rows")
+    if x_k_new.stride(0) != x_v_new.stride(0):
+        raise ValueError("x_k_new and x_v_new must have the same row stride")
+    a = call._args
+    args = (a[0], x_k_new.data_ptr(), x_v_new.data_ptr(), x_k_new.stride(0)) + a[1:]
+    keep = call._keep + (x_k_new, x_v_new)
+    return PreparedCall(load().cq_decode_step, args, keep, "cq_decode_step"), out
+
+
+def cq_decode_step(q, x_k_new, x_v_new, k_codes, v_codes, k_centroids, v_centroids, scale: float, fmt: CQFormat,
+                   t: int, t_cap: int, seq_lens=None, tokens_per_split: int = 0, out=None, workspace=None,
+                   stream=None):
+    """Fused cq_encode_kv of one new token per sequence (written at position t - 1, or
+    seq_lens[n] - 1) + cq_decode_attention over t tokens.  Returns out fp16 [B, Hq, head_dim]."""
+    call, out = prepare_decode_step(q, x_k_new, x_v_new, k_codes, v_codes, k_centroids, v_centroids, scale, fmt,
+                                    t, t_cap, seq_lens, tokens_per_split, out, workspace)
     call(stream)
     return out
 

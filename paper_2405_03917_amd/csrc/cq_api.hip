@@ -186,12 +186,15 @@ size_t cq_decode_workspace_bytes(const cq_format* fmt, int32_t batch, int32_t n_
     return sizeof(float) * (size_t)batch * n_q_heads * n_split * (f.head_dim + kPartialHeader);
 }
 
-cq_status cq_decode_attention(const void* q, const void* k_codes, const void* v_codes,
-                              const void* k_centroids, const void* v_centroids,
-                              float scale, const cq_format* fmt,
-                              int32_t batch, int32_t n_q_heads, int32_t t, int32_t t_cap,
-                              const int32_t* seq_lens, int32_t tokens_per_split,
-                              void* out, void* workspace, size_t workspace_bytes, void* stream)
+namespace {
+
+cq_status decode_common(const void* q, const void* x_k_new, const void* x_v_new, int64_t x_row_stride,
+                        const void* k_codes, const void* v_codes,
+                        const void* k_centroids, const void* v_centroids,
+                        float scale, const cq_format* fmt,
+                        int32_t batch, int32_t n_q_heads, int32_t t, int32_t t_cap,
+                        const int32_t* seq_lens, int32_t tokens_per_split,
+                        void* out, void* workspace, size_t workspace_bytes, void* stream, bool step)
 {
     Derived f;
     const cq_status st = derive(fmt, &f);
@@ -205,6 +208,11 @@ cq_status cq_decode_attention(const void* q, const void* k_codes, const void* v_
     if (!aligned16(q) || !aligned16(k_codes) || !aligned16(v_codes) || !aligned16(k_centroids) ||
         !aligned16(v_centroids) || !aligned16(out) || !aligned16(workspace))
         return CQ_ERR_INVALID_ARG;
+    if (step) {
+        if (!x_k_new || !x_v_new || !aligned16(x_k_new) || !aligned16(x_v_new)) return CQ_ERR_INVALID_ARG;
+        if (x_row_stride < f.channels || x_row_stride % 8 != 0) return CQ_ERR_INVALID_ARG;
+        if (k_codes == v_codes) return CQ_ERR_INVALID_ARG;
+    }
     const int tiles = tokens_per_split ? tokens_per_split / kTileTokens
                                        : default_tiles_per_split(f, batch, n_q_heads, t);
     if (tiles > decode_max_tiles_per_split(f)) return CQ_ERR_INVALID_ARG;
@@ -226,12 +234,41 @@ cq_status cq_decode_attention(const void* q, const void* k_codes, const void* v_
     a.t = t;
     a.t_cap = t_cap;
     a.seq_lens = seq_lens;
+    a.xk_new = step ? static_cast<const uint16_t*>(x_k_new) : nullptr;
+    a.xv_new = step ? static_cast<const uint16_t*>(x_v_new) : nullptr;
+    a.x_new_stride = x_row_stride;
     a.tiles_per_split = tiles;
     a.n_split = n_split;
     a.partials = static_cast<float*>(workspace);
     a.out = static_cast<uint16_t*>(out);
     a.f = f;
     return launch_decode(a, static_cast<hipStream_t>(stream));
+}
+
+}  // namespace
+
+cq_status cq_decode_attention(const void* q, const void* k_codes, const void* v_codes,
+                              const void* k_centroids, const void* v_centroids,
+                              float scale, const cq_format* fmt,
+                              int32_t batch, int32_t n_q_heads, int32_t t, int32_t t_cap,
+                              const int32_t* seq_lens, int32_t tokens_per_split,
+                              void* out, void* workspace, size_t workspace_bytes, void* stream)
+{
+    return decode_common(q, nullptr, nullptr, 0, k_codes, v_codes, k_centroids, v_centroids, scale, fmt, batch,
+                         n_q_heads, t, t_cap, seq_lens, tokens_per_split, out, workspace, workspace_bytes, stream, false);
+}
+
+cq_status cq_decode_step(const void* q, const void* x_k_new, const void* x_v_new, int64_t x_row_stride,
+                         void* k_codes, void* v_codes,
+                         const void* k_centroids, const void* v_centroids,
+                         float scale, const cq_format* fmt,
+                         int32_t batch, int32_t n_q_heads, int32_t t, int32_t t_cap,
+                         const int32_t* seq_lens, int32_t tokens_per_split,
+                         void* out, void* workspace, size_t workspace_bytes, void* stream)
+{
+    return decode_common(q, x_k_new, x_v_new, x_row_stride, k_codes, v_codes, k_centroids, v_centroids, scale, fmt,
+                         batch, n_q_heads, t, t_cap, seq_lens, tokens_per_split, out, workspace, workspace_bytes,
+                         stream, true);
 }
 
 }  // extern "C"

@@ -42,6 +42,9 @@ typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
 typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kMinScoreFloats = 4096;         // the score buffer doubles as reduction scratch
+constexpr int kKeyFloats = 2 * 2 * 64;        // fused step: 2 x 64 64-bit minima
+// reduction scratch: 64 words + one row of head_dim floats per wavefront
+constexpr int kScratchFloats(int nt, int head_dim) { return 64 + (nt / 64) * head_dim; }
 
 // Raw LDS accesses by byte address.  The table sits at LDS address 0 (the kernels declare no
 // static LDS; the launcher checks that), so a table-relative address is an LDS address.
@@ -68,6 +71,49 @@ __device__ __forceinline__ unsigned wave_sum_u32(unsigned v)
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
     return v;
+}
+
+__device__ __forceinline__ void lds_min_u64(unsigned long long* p, unsigned long long v)
+{
+    __hip_atomic_fetch_min(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+}
+
+// Nearest-centroid search of the fused decode step, bit-identical to cq_encode: squared distance
+// in fp32, one fused multiply-add per channel in channel order; (distance bits, index) packed so
+// that the 64-bit minimum is the nearest centroid with the lowest index among equals.
+template <int C>
+__device__ __forceinline__ unsigned long long centroid_key(const float (&x)[C], const unsigned* halves, int j)
+{
+    float acc = 0.f;
+#pragma unroll
+    for (int i = 0; i < C / 2; ++i) {
+        const half2_t h = __builtin_bit_cast(half2_t, halves[i]);
+        const float d0 = x[2 * i] - (float)h.x;
+        acc = __builtin_fmaf(d0, d0, acc);
+        const float d1 = x[2 * i + 1] - (float)h.y;
+        acc = __builtin_fmaf(d1, d1, acc);
+    }
+    return ((unsigned long long)__float_as_uint(acc) << 32) | (unsigned)j;
+}
+
+template <int C>
+__device__ __forceinline__ void load_row_slice(const uint16_t* p, float (&x)[C])
+{
+#pragma unroll
+    for (int i = 0; i < C / 2; ++i) {
+        const half2_t h = __builtin_bit_cast(half2_t, *reinterpret_cast<const unsigned*>(p + 2 * i));
+        x[2 * i] = (float)h.x;
+        x[2 * i + 1] = (float)h.y;
+    }
+}
+
+// minimum over the four lanes l, l+16, l+32, l+48 that walk the same group
+__device__ __forceinline__ unsigned long long group_lanes_min(unsigned long long key)
+{
+    unsigned long long o = __shfl_xor(key, 16);
+    key = o < key ? o : key;
+    o = __shfl_xor(key, 32);
+    return o < key ? o : key;
 }
 
 // Fixed-point scale for the probabilities of one split: with l_est = sum_t 2^(s_t - m) (fp32),
@@ -237,7 +283,63 @@ struct Streamer {
     }
 };
 
-template <int GH, int C, int B, int NT>
+// Fused step: replace the codes of lane u_new's token in a tile's registers by the codes just
+// computed (keys[g] holds group g's (distance, index) minimum), exactly as the cache layout
+// would hold them: slot s of token u carries group (s + u) mod Gh.
+template <int GH, int B>
+__device__ __forceinline__ void patch_new_token(Tile<GH, B>& w, const unsigned long long* keys, int u_new, int lane)
+{
+    if (lane != u_new) return;
+    unsigned hi = 0;
+#pragma unroll
+    for (int pl = 0; pl < GH / 16; ++pl) {
+        unsigned word[4];
+#pragma unroll
+        for (int d = 0; d < 4; ++d) {
+            unsigned x = 0;
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const int s = 16 * pl + 4 * d + k;
+                const unsigned code = (unsigned)(keys[(s + u_new) & (GH - 1)] & 0xffffffffu);
+                x |= (code & 0xffu) << (8 * k);
+                if constexpr (B == 10) hi |= (code >> 8) << (2 * s);
+            }
+            word[d] = x;
+        }
+        w.lo[pl] = u32x4{word[0], word[1], word[2], word[3]};
+    }
+    if constexpr (B == 10) w.hi = hi;
+}
+
+// Fused step: store the new token's codes of one KV head into its cache tile.
+template <int GH, int B>
+__device__ __forceinline__ void store_new_codes(uint8_t* tile, const unsigned long long* keys, int u_new, int tid)
+{
+    if (tid < GH) {
+        const unsigned code = (unsigned)(keys[tid] & 0xffffffffu);
+        const int slot = (tid - u_new) & (GH - 1);
+        tile[(slot >> 4) * 1024 + u_new * 16 + (slot & 15)] = (uint8_t)(code & 0xffu);
+    }
+    if constexpr (B == 10) {
+        if (tid == 0) {                 // the token's high-bit word belongs to this (token, head) alone
+            unsigned hi = 0;
+#pragma unroll
+            for (int g = 0; g < GH; ++g) {
+                const unsigned code = (unsigned)(keys[g] & 0xffffffffu);
+                hi |= (code >> 8) << (2 * ((g - u_new) & (GH - 1)));
+            }
+            *reinterpret_cast<unsigned*>(tile + kTileTokens * GH + u_new * 4) = hi;
+        }
+    }
+}
+
+// STEP = true is the fused decode step: the workgroup whose split holds the newest position
+// (t_n - 1) first encodes that token's key and value rows for its KV head while it builds the
+// score table (the key codebook is in registers anyway), then patches the two tiles that hold
+// the position in registers as if the codes were already in the cache, and -- for the first
+// query head of each KV head -- stores the codes.  Results equal cq_encode_kv followed by
+// cq_decode_attention bit for bit.
+template <int GH, int C, int B, int NT, bool STEP>
 __global__ __launch_bounds__(NT, 4) void decode_split_kernel(DecodeArgs a)
 {
     using F = Fmt<GH, B>;
@@ -250,7 +352,9 @@ __global__ __launch_bounds__(NT, 4) void decode_split_kernel(DecodeArgs a)
     constexpr int NCH = GH / 16;        // 16-group chunks
     constexpr int UNITS = 16 * K / JPL; // 16-byte loads per chunk
     constexpr int IPT = UNITS / NT;     // ... per thread
-    constexpr int KB = IPT < 8 ? IPT : 8;   // ... requested together
+    // ... requested together (the fused step holds key and value centroids at once)
+    constexpr int KBMAX = (STEP && C == 8) ? 4 : 8;
+    constexpr int KB = IPT < KBMAX ? IPT : KBMAX;
     static_assert(UNITS % NT == 0 && NT % 16 == 0, "thread count must divide the codebook walk");
     extern __shared__ float smem[];
     float* tab = smem;                              // [K][RW]; first the score table, then the bins
@@ -259,6 +363,9 @@ __global__ __launch_bounds__(NT, 4) void decode_split_kernel(DecodeArgs a)
     auto sidx = [](int i) { return F::SCORES_IN_TABLE ? ((i >> 5) << 6) + 32 + (i & 31) : i; };
     // reduction scratch: behind the table, or the (by then dead) score buffer
     float* scr = smem + F::TAB_FLOATS;
+    // fused step: 64-bit (distance, index) minima per group, keys[0..GH) for K, [GH..2GH) for V
+    unsigned long long* keys = reinterpret_cast<unsigned long long*>(
+        smem + F::TAB_FLOATS + (F::SCORES_IN_TABLE ? kScratchFloats(NT, D) : max(kMinScoreFloats, a.tiles_per_split * kTileTokens)));
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -284,6 +391,15 @@ __global__ __launch_bounds__(NT, 4) void decode_split_kernel(DecodeArgs a)
         return;
     }
 
+    // fused step: position of the new token, and whether this workgroup's split holds it
+    const int pos_new = t_n - 1;
+    const int tile_new = pos_new / kTileTokens, u_new = pos_new % kTileTokens;
+    const bool has_new = STEP && tile_new >= tile0 && tile_new < tile1;
+    if (has_new) {
+        if (tid < 2 * GH) keys[tid] = ~0ull;
+        __syncthreads();
+    }
+
     Columns<GH, B> col;
     col.init(lane);
 
@@ -307,11 +423,24 @@ __global__ __launch_bounds__(NT, 4) void decode_split_kernel(DecodeArgs a)
             unsigned qw[C / 2];
 #pragma unroll
             for (int i = 0; i < C / 2; ++i) qw[i] = *reinterpret_cast<const unsigned*>(qh + g * C + 2 * i);
+            // fused step: the new key / value rows against this group's two codebooks, same walk
+            float xk[C], xv[C];
+            unsigned long long kkey = ~0ull, vkey = ~0ull;
+            const uint16_t* cvn = a.v_centroids + (size_t)(hkv * GH + g) * K * C;
+            if (has_new) {
+                load_row_slice<C>(a.xk_new + (size_t)n * a.x_new_stride + (size_t)(hkv * GH + g) * C, xk);
+                load_row_slice<C>(a.xv_new + (size_t)n * a.x_new_stride + (size_t)(hkv * GH + g) * C, xv);
+            }
 #pragma unroll
             for (int k0 = 0; k0 < IPT; k0 += KB) {
                 Cent16 raw[KB];
 #pragma unroll
                 for (int k = 0; k < KB; ++k) raw[k] = load_cent16(ck + (size_t)((tid + (k0 + k) * NT) >> 4) * 8);
+                Cent16 rawn[STEP ? KB : 1];
+                if (has_new) {
+#pragma unroll
+                    for (int k = 0; k < KB; ++k) rawn[STEP ? k : 0] = load_cent16(cvn + (size_t)((tid + (k0 + k) * NT) >> 4) * 8);
+                }
                 // the first key tiles are requested behind the first centroids: loads return in
                 // order, so the table build waits for L2 only while HBM latency runs in the shadow
                 if (ch == 0 && k0 == 0) st.begin(kstream, my_tiles, tile0 + wave, NW, lane);
@@ -329,23 +458,45 @@ __global__ __launch_bounds__(NT, 4) void decode_split_kernel(DecodeArgs a)
                         float* dst = tab + (j0 + jj) * RW + g * R;
                         if constexpr (R == 2) *reinterpret_cast<float2*>(dst) = make_float2(v, v);
                         else *dst = v;
+                        if (has_new) {
+                            const unsigned long long kk = centroid_key<C>(xk, &raw[k].w[jj * (C / 2)], j0 + jj);
+                            kkey = kk < kkey ? kk : kkey;
+                            const unsigned long long vk = centroid_key<C>(xv, &rawn[STEP ? k : 0].w[jj * (C / 2)], j0 + jj);
+                            vkey = vk < vkey ? vk : vkey;
+                        }
                     }
                 }
+            }
+            if (has_new) {
+                kkey = group_lanes_min(kkey);
+                if (lane < 16) lds_min_u64(&keys[g], kkey);
+                vkey = group_lanes_min(vkey);
+                if (lane < 16) lds_min_u64(&keys[GH + g], vkey);
             }
         }
     }
     __syncthreads();
 
+    // fused step: the codes of the new token are known; the first query head of the KV head
+    // stores them (each token owns its 16-byte records, so no other token's bytes are touched)
+    const bool writer = has_new && hq % (a.n_q_heads / a.f.n_kv_heads) == 0;
+    if (writer) {
+        store_new_codes<GH, B>(const_cast<uint8_t*>(kstream) + (size_t)tile_new * F::TILE_BYTES, keys, u_new, tid);
+        store_new_codes<GH, B>(const_cast<uint8_t*>(vstream) + (size_t)tile_new * F::TILE_BYTES, keys + GH, u_new, tid);
+    }
+
     // ---- 2. phase K: scores --------------------------------------------------------------
     float lane_max = -INFINITY;
-    st.run(kstream, my_tiles, tile0 + wave, NW, lane, [&](const Tile<GH, B>& w, int k) {
+    st.run(kstream, my_tiles, tile0 + wave, NW, lane, [&](const Tile<GH, B>& w_in, int k) {
+        const int lt = wave + k * NW;                       // tile within the split
+        Tile<GH, B> w = w_in;
+        if (has_new && tile0 + lt == tile_new) patch_new_token<GH, B>(w, keys, u_new, lane);
         float acc0 = 0.f, acc1 = 0.f;
 #pragma unroll
         for (int s = 0; s < GH; s += 2) {
             acc0 += lds_load(slot_addr<GH, B>(w, col, s));
             acc1 += lds_load(slot_addr<GH, B>(w, col, s + 1));
         }
-        const int lt = wave + k * NW;                       // tile within the split
         const int tok = (tile0 + lt) * kTileTokens + lane;
         const float sv = tok < t_n ? acc0 + acc1 : -INFINITY;
         sc[sidx(lt * kTileTokens + lane)] = sv;
@@ -387,11 +538,13 @@ __global__ __launch_bounds__(NT, 4) void decode_split_kernel(DecodeArgs a)
 
     // ---- 3. phase V: probability bins ----------------------------------------------------
     const int gl = tid & 15;
-    constexpr bool EARLY = IPT * NCH <= 8;
+    constexpr bool EARLY = IPT * NCH <= 8 && KB == IPT;
     Cent16 rawv[EARLY ? NCH : 1][KB];
     unsigned lane_sum = 0;
-    st.run(vstream, my_tiles, tile0 + wave, NW, lane, [&](const Tile<GH, B>& w, int k) {
+    st.run(vstream, my_tiles, tile0 + wave, NW, lane, [&](const Tile<GH, B>& w_in, int k) {
         const int lt = wave + k * NW;
+        Tile<GH, B> w = w_in;
+        if (has_new && tile0 + lt == tile_new) patch_new_token<GH, B>(w, keys + GH, u_new, lane);
         const float p = __builtin_amdgcn_exp2f(sc[sidx(lt * kTileTokens + lane)] - m);
         const unsigned pf = (unsigned)__builtin_fmaf(p, fx_scale, 0.5f);     // round to nearest
         lane_sum += pf;
@@ -505,21 +658,21 @@ __global__ void decode_merge_kernel(const float* partials, uint16_t* out, int n_
     }
 }
 
-constexpr int kScratchFloats(int nt, int head_dim) { return 64 + (nt / 64) * head_dim; }
-
 template <int GH, int B, int NT>
-size_t smem_bytes(int tiles_per_split, int head_dim)
+size_t smem_bytes(int tiles_per_split, int head_dim, bool step)
 {
     using F = Fmt<GH, B>;
-    if (F::SCORES_IN_TABLE) return sizeof(float) * (size_t)(F::TAB_FLOATS + kScratchFloats(NT, head_dim));
+    const int key_floats = step ? kKeyFloats : 0;
+    if (F::SCORES_IN_TABLE) return sizeof(float) * (size_t)(F::TAB_FLOATS + kScratchFloats(NT, head_dim) + key_floats);
+    // behind the table: the score buffer (reused as scratch once the scores are dead), then the keys
     const int sc_floats = std::max(kMinScoreFloats, tiles_per_split * kTileTokens);
-    return sizeof(float) * (size_t)(F::TAB_FLOATS + sc_floats);
+    return sizeof(float) * (size_t)(F::TAB_FLOATS + sc_floats + key_floats);
 }
 
-template <int GH, int C, int B, int NT>
+template <int GH, int C, int B, int NT, bool STEP>
 cq_status launch_variant(const DecodeArgs& a, hipStream_t stream)
 {
-    auto kernel = decode_split_kernel<GH, C, B, NT>;
+    auto kernel = decode_split_kernel<GH, C, B, NT, STEP>;
     static std::once_flag once;
     static hipError_t setup = hipSuccess;
     std::call_once(once, [&] {
@@ -532,42 +685,49 @@ cq_status launch_variant(const DecodeArgs& a, hipStream_t stream)
                                         hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
     });
     if (setup != hipSuccess) return CQ_ERR_HIP;
-    const size_t smem = smem_bytes<GH, B, NT>(a.tiles_per_split, a.f.head_dim);
+    const size_t smem = smem_bytes<GH, B, NT>(a.tiles_per_split, a.f.head_dim, STEP);
+    if (smem > 160 * 1024) return CQ_ERR_INVALID_ARG;
     const unsigned grid = (unsigned)(a.batch * a.n_q_heads * a.n_split);
     hipLaunchKernelGGL(kernel, dim3(grid), dim3(NT), smem, stream, a);
     if (hipGetLastError() != hipSuccess) return CQ_ERR_HIP;
     return CQ_OK;
 }
 
-template <int GH, int C>
+template <int GH, int C, bool STEP>
 cq_status launch_by_split(const DecodeArgs& a, hipStream_t stream)
 {
     // 16 / 32 groups per head: scores live inside the table, 68 KB of LDS, two 512-thread
     // workgroups per CU.  64 groups per head: 64 KB table + 4 B per token of the split; up to 64
     // tiles two 512-thread workgroups fit a CU, longer splits run as one 1024-thread workgroup.
-    if (Fmt<GH, 8>::SCORES_IN_TABLE || a.tiles_per_split <= 64) return launch_variant<GH, C, 8, 512>(a, stream);
-    return launch_variant<GH, C, 8, 1024>(a, stream);
+    if (Fmt<GH, 8>::SCORES_IN_TABLE || a.tiles_per_split <= 64) return launch_variant<GH, C, 8, 512, STEP>(a, stream);
+    return launch_variant<GH, C, 8, 1024, STEP>(a, stream);
+}
+
+template <bool STEP>
+cq_status launch_format(const DecodeArgs& a, hipStream_t stream)
+{
+    if (a.f.b == 8) {
+        if (a.f.gh == 16 && a.f.c == 8) return launch_by_split<16, 8, STEP>(a, stream);
+        if (a.f.gh == 32 && a.f.c == 4) return launch_by_split<32, 4, STEP>(a, stream);
+        if (a.f.gh == 64 && a.f.c == 2) return launch_by_split<64, 2, STEP>(a, stream);
+    } else if (a.f.b == 10 && a.f.gh == 16 && a.f.c == 8) {
+        return launch_variant<16, 8, 10, 1024, STEP>(a, stream);
+    }
+    return CQ_ERR_UNSUPPORTED;
 }
 
 }  // namespace
 
 int decode_max_tiles_per_split(const Derived& f)
 {
-    if (f.b == 10) return (160 * 1024 / 4 - Fmt<16, 10>::TAB_FLOATS) / kTileTokens;   // 128: 160 KB of LDS
+    if (f.b == 10) return (160 * 1024 / 4 - Fmt<16, 10>::TAB_FLOATS - kKeyFloats) / kTileTokens;   // 124: 160 KB of LDS
     if (f.gh <= 32) return 256 * 32 / kTileTokens;                                    // 128: scores inside the table
     return 256;
 }
 
 cq_status launch_decode(const DecodeArgs& a, hipStream_t stream)
 {
-    cq_status st = CQ_ERR_UNSUPPORTED;
-    if (a.f.b == 8) {
-        if (a.f.gh == 16 && a.f.c == 8) st = launch_by_split<16, 8>(a, stream);
-        else if (a.f.gh == 32 && a.f.c == 4) st = launch_by_split<32, 4>(a, stream);
-        else if (a.f.gh == 64 && a.f.c == 2) st = launch_by_split<64, 2>(a, stream);
-    } else if (a.f.b == 10 && a.f.gh == 16 && a.f.c == 8) {
-        st = launch_variant<16, 8, 10, 1024>(a, stream);
-    }
+    const cq_status st = a.xk_new ? launch_format<true>(a, stream) : launch_format<false>(a, stream);
     if (st != CQ_OK || a.n_split == 1) return st;
     const int threads = a.f.head_dim <= 64 ? 64 : (a.f.head_dim <= 128 ? 128 : 256);
     hipLaunchKernelGGL(decode_merge_kernel, dim3((unsigned)(a.batch * a.n_q_heads)), dim3(threads), 0, stream,

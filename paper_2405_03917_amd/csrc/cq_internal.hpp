@@ -50,6 +50,11 @@ struct DecodeArgs {
     float scale_log2e;        // scale * log2(e): scores are kept in the base-2 domain
     int batch, n_q_heads, t, t_cap;
     const int32_t* seq_lens;
+    // fused decode step (null xk_new = plain attention): the new token's key / value rows,
+    // fp16 [batch][D] with row stride x_new_stride (elements); the caches are then written too
+    const uint16_t* xk_new;
+    const uint16_t* xv_new;
+    int64_t x_new_stride;
     int tiles_per_split, n_split;
     float* partials;          // [batch][n_q_heads][n_split][2 + head_dim]
     uint16_t* out;

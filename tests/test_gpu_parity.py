@@ -176,7 +176,7 @@ def test_decode_split_invariance_and_ragged_lengths(c, b):
     ref = O.attention(q, kc, vc, ck, cv, scale, hkv, seq_lens=lens)
     kcache, vcache = codes_to_cache(kc, fmt, t_cap), codes_to_cache(vc, fmt, t_cap)
     outs = []
-    for split in (0, 64, 448, 4032, 8128):
+    for split in (0, 64, 448, 4032, 7936):
         out = gpu_attention(q, kcache, vcache, ck, cv, scale, fmt, T, t_cap, seq_lens=lens, tokens_per_split=split)
         check_attention(out, ref)
         outs.append(out.astype(np.float64))
@@ -263,3 +263,64 @@ def test_config1_encode_then_decode_end_to_end():
     ok, ov = O.encode(xk[0], ck)[None], O.encode(xv[0], cv)[None]
     if sk["n_diff"] + sv["n_diff"] == 0:
         check_attention(out, O.attention(q, ok, ov, ck, cv, scale, cfg.n_kv_heads))
+
+
+# ------------------------------------------------------------------------------------------
+# fused decode step
+# ------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("c,b", DECODE_FORMATS)
+@pytest.mark.parametrize("hq,hkv,T,split", [(4, 4, 1, 0), (4, 4, 64, 0), (8, 2, 65, 0), (4, 2, 1000, 0),
+                                            (4, 4, 3000, 512), (8, 2, 5000, 0)])
+def test_decode_step_equals_encode_then_attention(c, b, hq, hkv, T, split):
+    B, t_cap = 3, 5056
+    fmt, q, kc, vc, ck, cv = _attn_case(50 + T, c, b, hq, hkv, B, max(T - 1, 1))
+    D = hkv * 128
+    rk, rv = synth.tensor_recipe(60, 0, "k", D), synth.tensor_recipe(60, 0, "v", D)
+    xk = np.stack([synth.sample_activations(rk, 1, chunk=n)[0] for n in range(B)])
+    xv = np.stack([synth.sample_activations(rv, 1, chunk=n)[0] for n in range(B)])
+    ck, cv = synth.sample_codebook(rk, c, b), synth.sample_codebook(rv, c, b)
+    k0, v0 = codes_to_cache(kc, fmt, t_cap), codes_to_cache(vc, fmt, t_cap)
+    scale = 0.1
+    qd, ckd, cvd = dev(q), dev(ck), dev(cv)
+    xkd, xvd = dev(xk), dev(xv)
+    # two-call reference
+    k1, v1 = k0.clone(), v0.clone()
+    cq.cq_encode_kv(xkd[:, None, :], xvd[:, None, :], ckd, cvd, fmt, k1, v1, T - 1, t_cap)
+    ref = cq.cq_decode_attention(qd, k1, v1, ckd, cvd, scale, fmt, T, t_cap, tokens_per_split=split)
+    # fused
+    k2, v2 = k0.clone(), v0.clone()
+    out = cq.cq_decode_step(qd, xkd, xvd, k2, v2, ckd, cvd, scale, fmt, T, t_cap, tokens_per_split=split)
+    torch.cuda.synchronize()
+    assert torch.equal(k1, k2) and torch.equal(v1, v2)
+    assert torch.equal(ref.view(torch.int16), out.view(torch.int16))
+    # and the reference itself is right: new codes match the oracle, attention matches it on those codes
+    kcodes = cache_to_codes(k2, fmt, B, t_cap, T)
+    vcodes = cache_to_codes(v2, fmt, B, t_cap, T)
+    for n in range(B):
+        check_codes(kcodes[n, T - 1:], xk[n:n + 1], ck)
+        check_codes(vcodes[n, T - 1:], xv[n:n + 1], cv)
+    check_attention(out.cpu().numpy(), O.attention(q, kcodes, vcodes, ck, cv, scale, hkv))
+
+
+def test_decode_step_ragged_lengths():
+    c, b, hq, hkv, B, t_cap = 8, 8, 8, 4, 3, 1024
+    lens = np.array([1000, 1, 513], dtype=np.int32)
+    fmt, q, kc, vc, _, _ = _attn_case(70, c, b, hq, hkv, B, 1000)
+    D = hkv * 128
+    rk, rv = synth.tensor_recipe(61, 0, "k", D), synth.tensor_recipe(61, 0, "v", D)
+    xk = np.stack([synth.sample_activations(rk, 1, chunk=n)[0] for n in range(B)])
+    xv = np.stack([synth.sample_activations(rv, 1, chunk=n)[0] for n in range(B)])
+    ck, cv = synth.sample_codebook(rk, c, b), synth.sample_codebook(rv, c, b)
+    k0, v0 = codes_to_cache(kc, fmt, t_cap), codes_to_cache(vc, fmt, t_cap)
+    qd, ckd, cvd, xkd, xvd, sl = dev(q), dev(ck), dev(cv), dev(xk), dev(xv), dev(lens)
+    k1, v1 = k0.clone(), v0.clone()
+    per_seq = k1.numel() // B
+    for n in range(B):      # the new token of sequence n goes to position lens[n] - 1
+        cq.cq_encode_kv(xkd[n:n + 1, None, :], xvd[n:n + 1, None, :], ckd, cvd, fmt,
+                        k1[n * per_seq:(n + 1) * per_seq], v1[n * per_seq:(n + 1) * per_seq], int(lens[n]) - 1, t_cap)
+    ref = cq.cq_decode_attention(qd, k1, v1, ckd, cvd, 0.07, fmt, 1000, t_cap, seq_lens=sl)
+    k2, v2 = k0.clone(), v0.clone()
+    out = cq.cq_decode_step(qd, xkd, xvd, k2, v2, ckd, cvd, 0.07, fmt, 1000, t_cap, seq_lens=sl)
+    torch.cuda.synchronize()
+    assert torch.equal(k1, k2) and torch.equal(v1, v2)
+    assert torch.equal(ref.view(torch.int16), out.view(torch.int16))
