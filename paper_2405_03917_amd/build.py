@@ -9,14 +9,20 @@ PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libcq.so")
-SOURCES = ["cq_api.hip", "cq_encode.hip", "cq_decode.hip", "cq_probe.hip"]
+SOURCES = ["cq_api.hip", "cq_encode.hip", "cq_encode_mfma.hip", "cq_decode.hip", "cq_probe.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=hidden",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+    # MFMA results straight into VGPRs: the encode kernel consumes every accumulator value once
+    "-mllvm", "-amdgpu-mfma-vgpr-form",
     "-Wno-int-to-pointer-cast",
     "-I", os.path.join(ROOT, "include"), "-I", CSRC,
 ]
+
+
+# per-file additions: the MFMA filter's running maxima must not be canonicalised (its header says why)
+FILE_FLAGS = {"cq_encode_mfma.hip": ["-fno-honor-nans"]}
 
 
 def build(verbose: bool = True) -> str:
@@ -24,7 +30,7 @@ def build(verbose: bool = True) -> str:
     objs = []
     for src in SOURCES:
         obj = os.path.join(CSRC, src.replace(".hip", ".o"))
-        cmd = [HIPCC, *FLAGS, "-c", os.path.join(CSRC, src), "-o", obj]
+        cmd = [HIPCC, *FLAGS, *FILE_FLAGS.get(src, []), "-c", os.path.join(CSRC, src), "-o", obj]
         if verbose:
             print(" ".join(cmd), flush=True)
         subprocess.check_call(cmd)

@@ -1,16 +1,13 @@
 // Nearest-centroid encoding of key/value activations (Section 3.2 of the paper) for gfx950.
 //
 // Two kernels, picked by the number of new tokens per sequence:
-//   encode_tokens_kernel     (prefill: many tokens)  lane = token.  A workgroup takes a block of
-//       64-token cache tiles of one (sequence, KV head), walks the head's groups, stages each
-//       group's codebook in LDS as fp32 (double buffered) and scans it in ascending index order
-//       with all lanes reading the same centroid (LDS broadcast).  Codes are collected in LDS in
-//       cache order and stored with 16-byte writes.
-//   encode_centroids_kernel  (decode step: a handful of tokens)  16 lanes per token.  A workgroup
-//       takes one group and up to 16 tokens; each lane scans every 16th centroid and the 16
-//       lanes of a token reduce their (distance, index) pairs.
-// Both evaluate sum_i (x_i - c_i)^2 in fp32 with one fused multiply-add per channel, in channel
-// order, and break ties towards the lowest index.
+//   encode_mfma_kernel       (prefill: 32 tokens or more; cq_encode_mfma.hip)  scores 32 tokens x
+//       32 centroids per MFMA, keeps the two best, and re-does the near ties by the direct form.
+//   encode_centroids_kernel  (decode step: a handful of tokens; here)  16 lanes per token.  A
+//       workgroup takes one group and up to 16 tokens; each lane scans every 16th centroid and
+//       the 16 lanes of a token reduce their (distance, index) pairs.
+// The direct form is sum_i (x_i - c_i)^2 in fp32 with one fused multiply-add per channel, in
+// channel order, ties broken towards the lowest index.
 #include <hip/hip_runtime.h>
 
 #include <type_traits>
@@ -56,110 +53,6 @@ __device__ __forceinline__ float sq_dist(const float (&x)[C], const float (&c)[C
         acc = __builtin_fmaf(d, d, acc);
     }
     return acc;
-}
-
-// ------------------------------------------------------------------------------------------
-// lane = token
-// ------------------------------------------------------------------------------------------
-template <int GH, int C, int B, int NW, int TPL>
-__global__ __launch_bounds__(NW * 64) void encode_tokens_kernel(EncodeArgs a)
-{
-    constexpr int K = 1 << B;
-    constexpr int NT = NW * 64;
-    constexpr int P = GH / 16;                       // 16-byte planes of low code bytes
-    constexpr int TILE_LOW = kTileTokens * GH;       // bytes of the low-byte planes of a tile
-    constexpr int TILE_BYTES = kTileTokens * GH * B / 8;
-    constexpr int TILES_PER_WG = NW * TPL;
-
-    __shared__ float cb[2][K * C];
-    __shared__ __attribute__((aligned(16))) uint8_t rec[TILES_PER_WG][TILE_LOW];
-
-    const int tid = threadIdx.x;
-    const int lane = tid & 63;
-    const int wave = tid >> 6;
-    const int hkv = blockIdx.y;
-    const int n = blockIdx.z % a.batch;
-    const EncodeTensor& ten = a.tensor[blockIdx.z / a.batch];
-
-    const int first_tile = a.t_offset / kTileTokens;
-    const int t_end = a.t_offset + a.t_new;           // one past the last cache position
-    const int wg_tile = first_tile + blockIdx.x * TILES_PER_WG;
-
-    // this lane's tokens: one per tile, tiles wg_tile + wave*TPL + k
-    int pos[TPL];
-    bool valid[TPL];
-    const uint16_t* xrow[TPL];
-#pragma unroll
-    for (int k = 0; k < TPL; ++k) {
-        pos[k] = (wg_tile + wave * TPL + k) * kTileTokens + lane;
-        valid[k] = pos[k] >= a.t_offset && pos[k] < t_end;
-        const int t = valid[k] ? pos[k] - a.t_offset : 0;
-        xrow[k] = ten.x + (size_t)n * ten.x_batch_stride + (size_t)t * ten.x_row_stride + (size_t)hkv * GH * C;
-    }
-
-    auto stage = [&](int g, int buf) {
-        const uint16_t* src = ten.centroids + (size_t)(hkv * GH + g) * K * C;
-        for (int i = tid * 2; i < K * C; i += NT * 2) {
-            const half2_t h = *reinterpret_cast<const half2_t*>(src + i);
-            cb[buf][i] = (float)h.x;
-            cb[buf][i + 1] = (float)h.y;
-        }
-    };
-
-    unsigned hi_word[TPL];
-#pragma unroll
-    for (int k = 0; k < TPL; ++k) hi_word[k] = 0;
-
-    stage(0, 0);
-    __syncthreads();
-    for (int g = 0; g < GH; ++g) {
-        const int buf = g & 1;
-        if (g + 1 < GH) stage(g + 1, buf ^ 1);
-
-        float x[TPL][C];
-#pragma unroll
-        for (int k = 0; k < TPL; ++k) load_halfs<C>(xrow[k] + g * C, x[k]);
-
-        float best[TPL];
-        int code[TPL];
-#pragma unroll
-        for (int k = 0; k < TPL; ++k) { best[k] = INFINITY; code[k] = 0; }
-
-        const float* cbuf = cb[buf];
-#pragma unroll 4
-        for (int j = 0; j < K; ++j) {
-            float cen[C];
-#pragma unroll
-            for (int i = 0; i < C; ++i) cen[i] = cbuf[j * C + i];
-#pragma unroll
-            for (int k = 0; k < TPL; ++k) {
-                const float d = sq_dist<C>(x[k], cen);
-                if (d < best[k]) { best[k] = d; code[k] = j; }      // strict: lowest index wins ties
-            }
-        }
-
-        const int slot = (g - lane) & (GH - 1);
-#pragma unroll
-        for (int k = 0; k < TPL; ++k) {
-            rec[wave * TPL + k][(slot >> 4) * 1024 + lane * 16 + (slot & 15)] = (uint8_t)(code[k] & 0xff);
-            if constexpr (B == 10) hi_word[k] |= (unsigned)(code[k] >> 8) << (2 * slot);
-        }
-        __syncthreads();
-    }
-
-    // store this lane's records
-    const size_t stream = (size_t)(n * a.f.n_kv_heads + hkv) * (a.t_cap / kTileTokens) * TILE_BYTES;
-#pragma unroll
-    for (int k = 0; k < TPL; ++k) {
-        if (!valid[k]) continue;
-        uint8_t* tile = ten.codes + stream + (size_t)(pos[k] / kTileTokens) * TILE_BYTES;
-#pragma unroll
-        for (int p = 0; p < P; ++p) {
-            const uint4 v = *reinterpret_cast<const uint4*>(&rec[wave * TPL + k][p * 1024 + lane * 16]);
-            *reinterpret_cast<uint4*>(tile + p * 1024 + lane * 16) = v;
-        }
-        if constexpr (B == 10) *reinterpret_cast<unsigned*>(tile + TILE_LOW + lane * 4) = hi_word[k];
-    }
 }
 
 // ------------------------------------------------------------------------------------------
@@ -232,21 +125,7 @@ cq_status launch_format(const EncodeArgs& a, hipStream_t stream)
         dim3 grid((unsigned)a.f.groups, (unsigned)((total + kSmallTokens - 1) / kSmallTokens), (unsigned)a.n_tensors);
         hipLaunchKernelGGL((encode_centroids_kernel<GH, C, B>), grid, dim3(256), 0, stream, a);
     } else {
-        const int first_tile = a.t_offset / kTileTokens;
-        const int last_tile = (a.t_offset + a.t_new - 1) / kTileTokens;
-        const int n_tiles = last_tile - first_tile + 1;
-        const long wave_tiles = (long)n_tiles * a.f.n_kv_heads * a.batch * a.n_tensors;
-        // tokens per lane trade LDS broadcast reads (one per centroid and workgroup pass) against
-        // parallelism: the more (tile, head, sequence) work there is, the more tiles a workgroup takes
-        auto launch = [&](auto nw, auto tpl) {
-            constexpr int NW = decltype(nw)::value, TPL = decltype(tpl)::value;
-            dim3 grid((unsigned)((n_tiles + NW * TPL - 1) / (NW * TPL)), (unsigned)a.f.n_kv_heads, (unsigned)(a.batch * a.n_tensors));
-            hipLaunchKernelGGL((encode_tokens_kernel<GH, C, B, NW, TPL>), grid, dim3(NW * 64), 0, stream, a);
-        };
-        using std::integral_constant;
-        if (wave_tiles >= 16384 && n_tiles >= 16) launch(integral_constant<int, 4>{}, integral_constant<int, (B == 10 ? 2 : 4)>{});
-        else if (wave_tiles >= 4096 && n_tiles >= 4) launch(integral_constant<int, 2>{}, integral_constant<int, 2>{});
-        else launch(integral_constant<int, 1>{}, integral_constant<int, 1>{});
+        return launch_encode_tiles(a, stream);
     }
     if (hipGetLastError() != hipSuccess) return CQ_ERR_HIP;
     return CQ_OK;

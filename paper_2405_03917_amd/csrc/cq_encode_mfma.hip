@@ -1,0 +1,374 @@
+// Nearest-centroid encoding of many tokens (Section 3.2 of the paper) with the matrix cores of
+// gfx950 as a FILTER and the exact fp32 search as the judge.
+//
+// For one group (c channels, K = 2^b centroids) and a tile of tokens, argmin_j |x - c_j|^2 =
+// argmax_j (x . c_j - |c_j|^2 / 2).  One MFMA evaluates that score for 32 tokens x 32 centroids:
+// the K dimension of the matrix product carries the c channels plus three fp16 pieces of
+// -|c_j|^2 / 2 (their sum is exact to fp32 precision).  Each lane then keeps the two largest
+// scores it sees, with the position of a score packed into its four lowest mantissa bits (2.5
+// VALU instructions per score instead of the 2 c + 3 of the direct form).
+//
+// Error bound.  With M = |x| |c|_max + |c|_max^2 / 2 >= sum of the absolute values of the terms
+// of any score: the products are exact in fp32; adding at most 11 non-zero terms loses at most
+// one unit in the last place of a partial sum per addition (10 * 2^-23 M < 2^-19.6 M, whatever
+// the order and whether the unit rounds or truncates); the four packed bits move a score by less
+// than 16 units in its last place (2^-19 M).  Two scores therefore compare correctly whenever
+// they differ by more than 2 (2^-19.6 + 2^-19) M < 2^-17 M: if the best beats the runner-up by
+// more than that, the best IS the nearest centroid in exact arithmetic.  Otherwise (a near tie or
+// an exact tie; also any group whose |c|^2 / 2 would overflow the fp16 pieces) the (token,
+// group) pair is re-done at once by the direct form -- sum_i (x_i - c_i)^2 in fp32, channel
+// order, lowest index on ties -- by the whole wavefront, from the codebook copy in LDS.  The
+// result is the exact nearest centroid wherever the two nearest are separated by more than the
+// bound, and the direct fp32 form's choice elsewhere.
+//
+// This file is compiled with -fno-honor-nans: the maxima below are then bare v_max3_f32 /
+// v_med3_f32 without canonicalisation of their inputs.  Non-finite activations or centroids
+// give unspecified codes (always in range), as they do in the direct form.
+#include <hip/hip_runtime.h>
+
+#include <type_traits>
+
+#include "cq_internal.hpp"
+
+namespace cq {
+namespace {
+
+typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
+typedef _Float16 half4_t __attribute__((ext_vector_type(4)));
+typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
+typedef float float16_t __attribute__((ext_vector_type(16)));
+
+template <int C>
+struct Aug {
+    static constexpr int KDIM = C == 8 ? 16 : 8;        // K of the MFMA = halfs per centroid record
+    static constexpr int HALF = KDIM / 2;               // halfs per lane operand
+    using vec_t = std::conditional_t<C == 8, half8_t, half4_t>;
+};
+
+template <int C>
+__device__ __forceinline__ float16_t mfma(typename Aug<C>::vec_t a, typename Aug<C>::vec_t b)
+{
+    const float16_t zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    if constexpr (C == 8) return __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, zero, 0, 0, 0);
+    else return __builtin_amdgcn_mfma_f32_32x32x8f16(a, b, zero, 0, 0, 0);
+}
+
+// Direct form: sum_i (x_i - c_i)^2 in fp32, channel order (its bits order like its value).
+template <int C>
+__device__ __forceinline__ unsigned exact_distance_bits(const float (&x)[C], const unsigned (&cw)[C / 2])
+{
+    float acc = 0.f;
+#pragma unroll
+    for (int i = 0; i < C / 2; ++i) {
+        const half2_t h = __builtin_bit_cast(half2_t, cw[i]);
+        const float d0 = x[2 * i] - (float)h.x;
+        acc = __builtin_fmaf(d0, d0, acc);
+        const float d1 = x[2 * i + 1] - (float)h.y;
+        acc = __builtin_fmaf(d1, d1, acc);
+    }
+    return __float_as_uint(acc);
+}
+
+// Minimum of v over the 64 lanes (all active), wavefront-uniform: four DPP steps inside each
+// row of 16 lanes, then the four row results through scalar registers.
+template <int CTRL>
+__device__ __forceinline__ unsigned dpp_min(unsigned v)
+{
+    const unsigned o = (unsigned)__builtin_amdgcn_update_dpp((int)v, (int)v, CTRL, 0xf, 0xf, false);
+    return o < v ? o : v;
+}
+__device__ __forceinline__ unsigned wave_min_u32(unsigned v)
+{
+    v = dpp_min<0xB1>(v);      // quad_perm [1,0,3,2]
+    v = dpp_min<0x4E>(v);      // quad_perm [2,3,0,1]
+    v = dpp_min<0x141>(v);     // row_half_mirror
+    v = dpp_min<0x140>(v);     // row_mirror
+    const unsigned r0 = (unsigned)__builtin_amdgcn_readlane((int)v, 0), r1 = (unsigned)__builtin_amdgcn_readlane((int)v, 16);
+    const unsigned r2 = (unsigned)__builtin_amdgcn_readlane((int)v, 32), r3 = (unsigned)__builtin_amdgcn_readlane((int)v, 48);
+    const unsigned a = r0 < r1 ? r0 : r1, b = r2 < r3 ? r2 : r3;
+    return a < b ? a : b;
+}
+
+template <int GH, int C, int B, int NW>
+__global__ __launch_bounds__(NW * 64) void encode_mfma_kernel(EncodeArgs a)
+{
+    using A = Aug<C>;
+    using vec_t = typename A::vec_t;
+    constexpr int K = 1 << B;
+    constexpr int NT = NW * 64;
+    constexpr int KDIM = A::KDIM, HALF = A::HALF;
+    constexpr int NBLK = K / 32;                     // 32-centroid blocks
+    constexpr int P = GH / 16;
+    constexpr int TILE_LOW = kTileTokens * GH;
+    constexpr int TILE_BYTES = kTileTokens * GH * B / 8;
+    constexpr float LOWEST = -3.0e38f;
+
+    __shared__ __attribute__((aligned(16))) _Float16 cba[2][K * KDIM];     // augmented codebook records
+    __shared__ float nrm[2][K];                                           // |c_j|^2
+    __shared__ __attribute__((aligned(16))) uint8_t rec[NW][TILE_LOW];     // low code bytes, cache order
+    __shared__ uint16_t code16[B == 10 ? NW : 1][B == 10 ? kTileTokens : 1][B == 10 ? GH : 1];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int hkv = blockIdx.y;
+    const int n = blockIdx.z % a.batch;
+    const EncodeTensor& ten = a.tensor[blockIdx.z / a.batch];
+
+    const int first_tile = a.t_offset / kTileTokens;
+    const int t_end = a.t_offset + a.t_new;
+    const int tile = first_tile + blockIdx.x * NW + wave;
+    const int pos = tile * kTileTokens + lane;                   // this lane's token (cache position)
+    const bool valid = pos >= a.t_offset && pos < t_end;
+    const uint16_t* xbase = ten.x + (size_t)n * ten.x_batch_stride + (size_t)hkv * GH * C;
+    const uint16_t* xrow = xbase + (size_t)(valid ? pos - a.t_offset : 0) * ten.x_row_stride;
+
+    // Staging of a group's codebook is split in two so that the global loads of group g + 1 fly
+    // while group g is computed: fetch() issues them into registers, commit() turns centroid j
+    // into its record [channels | three pieces of -|c|^2/2, zeros] in LDS.
+    constexpr int SPT = (K + NT - 1) / NT;           // centroids staged per thread
+    unsigned craw[SPT][C / 2];
+    auto fetch = [&](int g) {
+        const uint16_t* src = ten.centroids + (size_t)(hkv * GH + g) * K * C;
+#pragma unroll
+        for (int k = 0; k < SPT; ++k) {
+            const int j = tid + k * NT;
+            if (j < K) {
+#pragma unroll
+                for (int i = 0; i < C / 2; ++i) craw[k][i] = *reinterpret_cast<const unsigned*>(src + j * C + 2 * i);
+            }
+        }
+    };
+    auto commit = [&](int buf) {
+#pragma unroll
+        for (int k = 0; k < SPT; ++k) {
+            const int j = tid + k * NT;
+            if (j >= K) continue;
+            float s = 0.f;
+#pragma unroll
+            for (int i = 0; i < C / 2; ++i) {
+                const half2_t h = __builtin_bit_cast(half2_t, craw[k][i]);
+                s = __builtin_fmaf((float)h.x, (float)h.x, s);
+                s = __builtin_fmaf((float)h.y, (float)h.y, s);
+            }
+            nrm[buf][j] = s;
+            const float v = -0.5f * s;
+            const _Float16 h1 = (_Float16)v;
+            const float r1 = v - (float)h1;
+            const _Float16 h2 = (_Float16)r1;
+            const _Float16 h3 = (_Float16)(r1 - (float)h2);
+            const _Float16 zero = (_Float16)0.0f;
+            const unsigned w12 = __builtin_bit_cast(unsigned, half2_t{h1, h2});
+            const unsigned w30 = __builtin_bit_cast(unsigned, half2_t{h3, zero});
+            uint4* dst = reinterpret_cast<uint4*>(&cba[buf][j * KDIM]);
+            if constexpr (C == 8) {
+                dst[0] = make_uint4(craw[k][0], craw[k][1], craw[k][2], craw[k][3]);
+                dst[1] = make_uint4(w12, w30, 0u, 0u);
+            } else if constexpr (C == 4) {
+                dst[0] = make_uint4(craw[k][0], craw[k][1], w12, w30);
+            } else {
+                dst[0] = make_uint4(craw[k][0], w12, w30, 0u);
+            }
+        }
+    };
+    auto load_x = [&](int g, unsigned (&dst)[C / 2]) {
+#pragma unroll
+        for (int i = 0; i < C / 2; ++i) dst[i] = *reinterpret_cast<const unsigned*>(xrow + g * C + 2 * i);
+    };
+
+    fetch(0);
+    commit(0);
+    unsigned xnext[C / 2];
+    load_x(0, xnext);
+    __syncthreads();
+    for (int g = 0; g < GH; ++g) {
+        const int buf = g & 1;
+        // this lane's token: its slice of the group (fetched one group ahead) and |x|^2
+        unsigned xw[C / 2];
+        float x2 = 0.f;
+#pragma unroll
+        for (int i = 0; i < C / 2; ++i) {
+            xw[i] = xnext[i];
+            const half2_t h = __builtin_bit_cast(half2_t, xw[i]);
+            x2 = __builtin_fmaf((float)h.x, (float)h.x, x2);
+            x2 = __builtin_fmaf((float)h.y, (float)h.y, x2);
+        }
+        if (g + 1 < GH) {
+            fetch(g + 1);
+            load_x(g + 1, xnext);
+        }
+        float c2max = 0.f;
+        for (int j = lane; j < K; j += 64) c2max = fmaxf(c2max, nrm[buf][j]);
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) c2max = fmaxf(c2max, __shfl_xor(c2max, o));
+        // 2^-17 M with M >= |x| |c|max + |c|max^2 / 2 (1 % slack for the roundings of this line)
+        const float thr = (1.01f * (__builtin_sqrtf(x2 * c2max) + 0.5f * c2max) + 1e-30f) * (1.0f / 131072.0f);
+        const bool too_big = !(c2max < 60000.f);     // -|c|^2 / 2 must fit fp16 safely
+
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            // B operand: lanes < 32 carry the channels of token 32 h + lane, lanes >= 32 the ones
+            // that pick up the pieces of -|c|^2 / 2
+            const int src_lane = 32 * h + (lane & 31);
+            unsigned xh[C / 2];
+#pragma unroll
+            for (int i = 0; i < C / 2; ++i) xh[i] = __shfl(xw[i], src_lane);
+            const float thr_h = __shfl(thr, src_lane);
+            const _Float16 one = (_Float16)1.0f, zero = (_Float16)0.0f;
+            vec_t bop;
+            if constexpr (C == 8) {
+                if (lane < 32) {
+                    const half2_t p0 = __builtin_bit_cast(half2_t, xh[0]), p1 = __builtin_bit_cast(half2_t, xh[1]);
+                    const half2_t p2 = __builtin_bit_cast(half2_t, xh[2]), p3 = __builtin_bit_cast(half2_t, xh[3]);
+                    bop = vec_t{p0.x, p0.y, p1.x, p1.y, p2.x, p2.y, p3.x, p3.y};
+                } else {
+                    bop = vec_t{one, one, one, zero, zero, zero, zero, zero};
+                }
+            } else if constexpr (C == 4) {
+                if (lane < 32) {
+                    const half2_t p0 = __builtin_bit_cast(half2_t, xh[0]), p1 = __builtin_bit_cast(half2_t, xh[1]);
+                    bop = vec_t{p0.x, p0.y, p1.x, p1.y};
+                } else {
+                    bop = vec_t{one, one, one, zero};
+                }
+            } else {
+                if (lane < 32) {
+                    const half2_t p0 = __builtin_bit_cast(half2_t, xh[0]);
+                    bop = vec_t{p0.x, p0.y, one, one};
+                } else {
+                    bop = vec_t{one, zero, zero, zero};
+                }
+            }
+
+            float gbest = LOWEST, gsecond = LOWEST;
+            int gblk = 0;
+#pragma unroll 2
+            for (int blk = 0; blk < NBLK; ++blk) {
+                const vec_t aop = *reinterpret_cast<const vec_t*>(&cba[buf][(blk * 32 + (lane & 31)) * KDIM + (lane >> 5) * HALF]);
+                const float16_t d = mfma<C>(aop, bop);
+                float bbest = LOWEST, bsecond = LOWEST;
+                // two scores per step: the runner-up of {best, second, k1, k2} with second <= best
+                // is max(median(best, k1, k2), second)
+#pragma unroll
+                for (int i = 0; i < 16; i += 2) {
+                    const float k1 = __uint_as_float((__float_as_uint(d[i]) & 0xfffffff0u) | (unsigned)i);
+                    const float k2 = __uint_as_float((__float_as_uint(d[i + 1]) & 0xfffffff0u) | (unsigned)(i + 1));
+                    bsecond = fmaxf(bsecond, __builtin_amdgcn_fmed3f(bbest, k1, k2));
+                    bbest = fmaxf(fmaxf(bbest, k1), k2);
+                }
+                gsecond = fmaxf(fmaxf(fminf(gbest, bbest), gsecond), bsecond);
+                gblk = bbest > gbest ? blk : gblk;
+                gbest = fmaxf(gbest, bbest);
+            }
+            // lanes l and l + 32 saw the two halves of every block's rows for token l % 32
+            const float obest = __shfl_xor(gbest, 32), osecond = __shfl_xor(gsecond, 32);
+            const int oblk = __shfl_xor(gblk, 32);
+            const bool other = obest > gbest;
+            const float best = fmaxf(gbest, obest);
+            const float second = fmaxf(fmaxf(fminf(gbest, obest), gsecond), osecond);
+            const int wblk = other ? oblk : gblk;
+            const int whalf = other ? 1 - (lane >> 5) : (lane >> 5);
+            const int u = 32 * h + (lane & 31);                      // token of the tile
+            const int slot = (g - u) & (GH - 1);
+            bool unsure = false;
+            if (lane < 32) {
+                const unsigned bits = __float_as_uint(best);
+                const int i = (int)(bits & 15u);
+                const int code = wblk * 32 + 8 * (i >> 2) + 4 * whalf + (i & 3);
+                const float bv = __uint_as_float(bits & 0xfffffff0u);
+                const float sv = __uint_as_float(__float_as_uint(second) & 0xfffffff0u);
+                unsure = !(bv - sv > thr_h) || too_big;
+                rec[wave][(slot >> 4) * 1024 + u * 16 + (slot & 15)] = (uint8_t)(code & 0xff);
+                if constexpr (B == 10) code16[wave][u][g] = (uint16_t)code;
+            }
+
+            // exact re-do of the unsure tokens of this half, one at a time by the whole wavefront
+            unsigned todo = (unsigned)__ballot(unsure);                 // lanes < 32 only
+            while (todo) {
+                const int r = __builtin_ctz(todo);
+                todo &= todo - 1;
+                float x[C];
+#pragma unroll
+                for (int i = 0; i < C / 2; ++i) {
+                    const half2_t hh = __builtin_bit_cast(half2_t, (unsigned)__builtin_amdgcn_readlane((int)xh[i], r));
+                    x[2 * i] = (float)hh.x;
+                    x[2 * i + 1] = (float)hh.y;
+                }
+                unsigned dmin = ~0u, jmin = 0;
+#pragma unroll 4
+                for (int j = lane; j < K; j += 64) {
+                    unsigned cw[C / 2];
+#pragma unroll
+                    for (int i = 0; i < C / 2; ++i) cw[i] = *reinterpret_cast<const unsigned*>(&cba[buf][j * KDIM + 2 * i]);
+                    const unsigned dj = exact_distance_bits<C>(x, cw);
+                    jmin = dj < dmin ? (unsigned)j : jmin;       // increasing j: the lowest index stays on ties
+                    dmin = dj < dmin ? dj : dmin;
+                }
+                const unsigned wmin = wave_min_u32(dmin);
+                const unsigned code = wave_min_u32(dmin == wmin ? jmin : ~0u);
+                if (lane == r) {
+                    rec[wave][(slot >> 4) * 1024 + u * 16 + (slot & 15)] = (uint8_t)(code & 0xff);
+                    if constexpr (B == 10) code16[wave][u][g] = (uint16_t)code;
+                }
+            }
+        }
+        if (g + 1 < GH) commit(buf ^ 1);
+        __syncthreads();
+    }
+
+    // store this lane's token
+    if (valid) {
+        const size_t stream = (size_t)(n * a.f.n_kv_heads + hkv) * (a.t_cap / kTileTokens) * TILE_BYTES;
+        uint8_t* tp = ten.codes + stream + (size_t)tile * TILE_BYTES;
+#pragma unroll
+        for (int p = 0; p < P; ++p) {
+            const uint4 v = *reinterpret_cast<const uint4*>(&rec[wave][p * 1024 + lane * 16]);
+            *reinterpret_cast<uint4*>(tp + p * 1024 + lane * 16) = v;
+        }
+        if constexpr (B == 10) {
+            unsigned hi = 0;
+#pragma unroll
+            for (int g = 0; g < GH; ++g)
+                hi |= (unsigned)(code16[wave][lane][g] >> 8) << (2 * ((g - lane) & (GH - 1)));
+            *reinterpret_cast<unsigned*>(tp + TILE_LOW + lane * 4) = hi;
+        }
+    }
+}
+
+template <int GH, int C, int B>
+cq_status launch_mfma_format(const EncodeArgs& a, hipStream_t stream)
+{
+    const int first_tile = a.t_offset / kTileTokens;
+    const int last_tile = (a.t_offset + a.t_new - 1) / kTileTokens;
+    const int n_tiles = last_tile - first_tile + 1;
+    const long wave_tiles = (long)n_tiles * a.f.n_kv_heads * a.batch * a.n_tensors;
+    // four tiles per workgroup share one staging of each group's codebook; small problems take one
+    // tile per workgroup to spread over the CUs
+    if (wave_tiles >= 4096 && n_tiles >= 4) {
+        constexpr int NW = 4;
+        dim3 grid((unsigned)((n_tiles + NW - 1) / NW), (unsigned)a.f.n_kv_heads, (unsigned)(a.batch * a.n_tensors));
+        hipLaunchKernelGGL((encode_mfma_kernel<GH, C, B, NW>), grid, dim3(NW * 64), 0, stream, a);
+    } else {
+        constexpr int NW = 1;
+        dim3 grid((unsigned)n_tiles, (unsigned)a.f.n_kv_heads, (unsigned)(a.batch * a.n_tensors));
+        hipLaunchKernelGGL((encode_mfma_kernel<GH, C, B, NW>), grid, dim3(NW * 64), 0, stream, a);
+    }
+    if (hipGetLastError() != hipSuccess) return CQ_ERR_HIP;
+    return CQ_OK;
+}
+
+}  // namespace
+
+cq_status launch_encode_tiles(const EncodeArgs& a, hipStream_t stream)
+{
+    if (a.f.b == 8) {
+        if (a.f.gh == 16 && a.f.c == 8) return launch_mfma_format<16, 8, 8>(a, stream);
+        if (a.f.gh == 32 && a.f.c == 4) return launch_mfma_format<32, 4, 8>(a, stream);
+        if (a.f.gh == 64 && a.f.c == 2) return launch_mfma_format<64, 2, 8>(a, stream);
+    } else if (a.f.b == 10) {
+        if (a.f.gh == 16 && a.f.c == 8) return launch_mfma_format<16, 8, 10>(a, stream);
+    }
+    return CQ_ERR_UNSUPPORTED;
+}
+
+}  // namespace cq

@@ -65,6 +65,8 @@ struct DecodeArgs {
 int decode_max_tiles_per_split(const Derived& f);
 
 cq_status launch_encode(const EncodeArgs& a, hipStream_t stream);
+// many tokens per sequence: the MFMA-filtered kernel (cq_encode_mfma.hip)
+cq_status launch_encode_tiles(const EncodeArgs& a, hipStream_t stream);
 cq_status launch_decode(const DecodeArgs& a, hipStream_t stream);
 
 }  // namespace cq
