@@ -4,22 +4,31 @@
 // For one group (c channels, K = 2^b centroids) and a tile of tokens, argmin_j |x - c_j|^2 =
 // argmax_j (x . c_j - |c_j|^2 / 2).  One MFMA evaluates that score for 32 tokens x 32 centroids:
 // the K dimension of the matrix product carries the c channels plus three fp16 pieces of
-// -|c_j|^2 / 2 (their sum is exact to fp32 precision).  Each lane then keeps the two largest
+// -|c_j|^2 / 2 (their sum is exact to fp32 precision; see "Scaling").  Each lane then keeps the two largest
 // scores it sees, with the position of a score packed into its four lowest mantissa bits (2.5
 // VALU instructions per score instead of the 2 c + 3 of the direct form).
 //
-// Error bound.  With M = |x| |c|_max + |c|_max^2 / 2 >= sum of the absolute values of the terms
-// of any score: the products are exact in fp32; adding at most 11 non-zero terms loses at most
-// one unit in the last place of a partial sum per addition (10 * 2^-23 M < 2^-19.6 M, whatever
-// the order and whether the unit rounds or truncates); the four packed bits move a score by less
-// than 16 units in its last place (2^-19 M).  Two scores therefore compare correctly whenever
-// they differ by more than 2 (2^-19.6 + 2^-19) M < 2^-17 M: if the best beats the runner-up by
-// more than that, the best IS the nearest centroid in exact arithmetic.  Otherwise (a near tie or
-// an exact tie; also any group whose |c|^2 / 2 would overflow the fp16 pieces) the (token,
+// Scaling.  A group whose largest |c_j|^2 is small is multiplied (centroids and tokens alike)
+// by a power of two 2^s, s >= 0, that brings the largest scaled |c'|^2 into [2^12, 2^14): the
+// pieces of |c'|^2 / 2 then sit well inside fp16's normal range however small the data (the
+// argmax does not change and scaling up is exact).  Nothing is scaled down: a group whose
+// |c|^2 / 2 would not fit fp16 (|c|^2 >= 60000), and a token whose scaled channels would not,
+// are handed to the exact path whole.
+//
+// Error bound.  With M = |x'| |c'|_max + |c'|_max^2 / 2 >= sum of the absolute values of the
+// terms of any score, in units of 2^-20 M: |c|^2 summed in fp32 (0.5); the matrix core aligns the
+// exact products to the largest one and drops what falls below about 2^-24 of it -- at most
+// 2^-23 M for each of at most 11 terms and the final rounding (1.5; measured on such operands:
+// never above 0.2); the four packed bits move a score by less than 16 units in its last place
+// (1.9).  Two scores therefore
+// compare correctly whenever they differ by more than 2 * 3.9 * 2^-20 M < 2^-17 M; the test
+// below uses 1.5 * 2^-17 M.  If the best beats the runner-up by more than that, the best IS the
+// nearest centroid in exact arithmetic.  Otherwise (a near tie or an exact tie) the (token,
 // group) pair is re-done at once by the direct form -- sum_i (x_i - c_i)^2 in fp32, channel
-// order, lowest index on ties -- by the whole wavefront, from the codebook copy in LDS.  The
-// result is the exact nearest centroid wherever the two nearest are separated by more than the
-// bound, and the direct fp32 form's choice elsewhere.
+// order, lowest index on ties; on the scaled values, which changes no bit of the comparison --
+// by the whole wavefront, from the codebook copy in LDS.  The result is
+// the exact nearest centroid wherever the two nearest are separated by more than the bound, and
+// the direct fp32 form's choice elsewhere.
 //
 // This file is compiled with -fno-honor-nans: the maxima below are then bare v_max3_f32 /
 // v_med3_f32 without canonicalisation of their inputs.  Non-finite activations or centroids
@@ -89,6 +98,69 @@ __device__ __forceinline__ unsigned wave_min_u32(unsigned v)
     return a < b ? a : b;
 }
 
+template <int CTRL>
+__device__ __forceinline__ unsigned dpp_max(unsigned v)
+{
+    const unsigned o = (unsigned)__builtin_amdgcn_update_dpp((int)v, (int)v, CTRL, 0xf, 0xf, false);
+    return o > v ? o : v;
+}
+__device__ __forceinline__ unsigned wave_max_u32(unsigned v)
+{
+    v = dpp_max<0xB1>(v);
+    v = dpp_max<0x4E>(v);
+    v = dpp_max<0x141>(v);
+    v = dpp_max<0x140>(v);
+    const unsigned r0 = (unsigned)__builtin_amdgcn_readlane((int)v, 0), r1 = (unsigned)__builtin_amdgcn_readlane((int)v, 16);
+    const unsigned r2 = (unsigned)__builtin_amdgcn_readlane((int)v, 32), r3 = (unsigned)__builtin_amdgcn_readlane((int)v, 48);
+    const unsigned a = r0 > r1 ? r0 : r1, b = r2 > r3 ? r2 : r3;
+    return a > b ? a : b;
+}
+
+// |c|^2 of the fp16 pairs in n words, fp32, channel order
+template <int N>
+__device__ __forceinline__ float norm2(const unsigned (&w)[N])
+{
+    float s = 0.f;
+#pragma unroll
+    for (int i = 0; i < N; ++i) {
+        const half2_t h = __builtin_bit_cast(half2_t, w[i]);
+        s = __builtin_fmaf((float)h.x, (float)h.x, s);
+        s = __builtin_fmaf((float)h.y, (float)h.y, s);
+    }
+    return s;
+}
+
+// The group's power-of-two scale from its largest |c|^2 (bits of a non-negative float):
+// s >= 0 with 4^s c2max in [2^12, 2^14) when c2max < 2^12, else s = 0; at most 30 (fp16 data
+// needs no more; an all-zero group gets 30 and ties everywhere).
+struct GroupScale {
+    half2_t m1, m2;         // 2^s = m1 * m2, both fp16 powers of two
+    float f1, f2;           // 2^s, 4^s
+    float c2max_scaled;     // c2max * 4^s
+    bool too_big;           // |c|^2 / 2 would not fit fp16: the filter steps aside
+};
+__device__ __forceinline__ GroupScale group_scale(unsigned c2bits)
+{
+    GroupScale r;
+    const int e = (int)((c2bits >> 23) & 0xffu) - 127;
+    int s = (13 - e) >> 1;
+    s = s > 30 ? 30 : (s < 0 ? 0 : s);
+    const int s1 = s >> 1, s2 = s - s1;
+    const _Float16 a = (_Float16)__uint_as_float((unsigned)(127 + s1) << 23);
+    const _Float16 b = (_Float16)__uint_as_float((unsigned)(127 + s2) << 23);
+    r.m1 = half2_t{a, a};
+    r.m2 = half2_t{b, b};
+    r.f1 = __uint_as_float((unsigned)(127 + s) << 23);
+    r.f2 = __uint_as_float((unsigned)(127 + 2 * s) << 23);
+    r.c2max_scaled = __uint_as_float(c2bits) * r.f2;
+    r.too_big = !(__uint_as_float(c2bits) < 60000.f);
+    return r;
+}
+__device__ __forceinline__ unsigned scale_pair(unsigned w, const GroupScale& gs)
+{
+    return __builtin_bit_cast(unsigned, __builtin_bit_cast(half2_t, w) * gs.m1 * gs.m2);
+}
+
 template <int GH, int C, int B, int NW>
 __global__ __launch_bounds__(NW * 64) void encode_mfma_kernel(EncodeArgs a)
 {
@@ -104,7 +176,7 @@ __global__ __launch_bounds__(NW * 64) void encode_mfma_kernel(EncodeArgs a)
     constexpr float LOWEST = -3.0e38f;
 
     __shared__ __attribute__((aligned(16))) _Float16 cba[2][K * KDIM];     // augmented codebook records
-    __shared__ float nrm[2][K];                                           // |c_j|^2
+    __shared__ unsigned c2bits[GH];                                       // bits of max_j |c_j|^2 per group
     __shared__ __attribute__((aligned(16))) uint8_t rec[NW][TILE_LOW];     // low code bytes, cache order
     __shared__ uint16_t code16[B == 10 ? NW : 1][B == 10 ? kTileTokens : 1][B == 10 ? GH : 1];
 
@@ -139,20 +211,13 @@ __global__ __launch_bounds__(NW * 64) void encode_mfma_kernel(EncodeArgs a)
             }
         }
     };
-    auto commit = [&](int buf) {
+    auto commit = [&](int buf, int g) {
+        const GroupScale gs = group_scale(c2bits[g]);
 #pragma unroll
         for (int k = 0; k < SPT; ++k) {
             const int j = tid + k * NT;
             if (j >= K) continue;
-            float s = 0.f;
-#pragma unroll
-            for (int i = 0; i < C / 2; ++i) {
-                const half2_t h = __builtin_bit_cast(half2_t, craw[k][i]);
-                s = __builtin_fmaf((float)h.x, (float)h.x, s);
-                s = __builtin_fmaf((float)h.y, (float)h.y, s);
-            }
-            nrm[buf][j] = s;
-            const float v = -0.5f * s;
+            const float v = gs.too_big ? 0.f : -0.5f * gs.f2 * norm2<C / 2>(craw[k]);    // -|c'|^2 / 2
             const _Float16 h1 = (_Float16)v;
             const float r1 = v - (float)h1;
             const _Float16 h2 = (_Float16)r1;
@@ -160,14 +225,17 @@ __global__ __launch_bounds__(NW * 64) void encode_mfma_kernel(EncodeArgs a)
             const _Float16 zero = (_Float16)0.0f;
             const unsigned w12 = __builtin_bit_cast(unsigned, half2_t{h1, h2});
             const unsigned w30 = __builtin_bit_cast(unsigned, half2_t{h3, zero});
+            unsigned cs[C / 2];
+#pragma unroll
+            for (int i = 0; i < C / 2; ++i) cs[i] = scale_pair(craw[k][i], gs);
             uint4* dst = reinterpret_cast<uint4*>(&cba[buf][j * KDIM]);
             if constexpr (C == 8) {
-                dst[0] = make_uint4(craw[k][0], craw[k][1], craw[k][2], craw[k][3]);
+                dst[0] = make_uint4(cs[0], cs[1], cs[2], cs[3]);
                 dst[1] = make_uint4(w12, w30, 0u, 0u);
             } else if constexpr (C == 4) {
-                dst[0] = make_uint4(craw[k][0], craw[k][1], w12, w30);
+                dst[0] = make_uint4(cs[0], cs[1], w12, w30);
             } else {
-                dst[0] = make_uint4(craw[k][0], w12, w30, 0u);
+                dst[0] = make_uint4(cs[0], w12, w30, 0u);
             }
         }
     };
@@ -176,34 +244,64 @@ __global__ __launch_bounds__(NW * 64) void encode_mfma_kernel(EncodeArgs a)
         for (int i = 0; i < C / 2; ++i) dst[i] = *reinterpret_cast<const unsigned*>(xrow + g * C + 2 * i);
     };
 
+    // max_j |c_j|^2 of every group of this head: each thread takes 16-byte pieces of the head's
+    // codebooks; a group's pieces are a multiple of 64, so a wavefront works on one group at a time
+    {
+        constexpr int CH = K * C / 8;                // 16-byte pieces per group
+        constexpr int ROUNDS = GH * CH / NT;
+        static_assert(CH % 64 == 0 && (GH * CH) % NT == 0, "a wavefront's pieces must share a group");
+        for (int i = tid; i < GH; i += NT) c2bits[i] = 0u;
+        __syncthreads();
+        const uint4* cen16 = reinterpret_cast<const uint4*>(ten.centroids + (size_t)hkv * GH * K * C);
+        constexpr int RPG = CH >= NT ? CH / NT : 1;      // consecutive rounds inside one group
+        constexpr int STEPS = ROUNDS / RPG;
+        constexpr int UNR = RPG >= 16 ? 1 : 16 / RPG;    // about 16 loads in flight
+#pragma unroll(UNR)
+        for (int st = 0; st < STEPS; ++st) {
+            float m = 0.f;
+#pragma unroll
+            for (int rr = 0; rr < RPG; ++rr) {
+                const uint4 w = cen16[(st * RPG + rr) * NT + tid];
+                if constexpr (C == 8) {
+                    const unsigned a0[4] = {w.x, w.y, w.z, w.w};
+                    m = fmaxf(m, norm2<4>(a0));
+                } else if constexpr (C == 4) {
+                    const unsigned a0[2] = {w.x, w.y}, a1[2] = {w.z, w.w};
+                    m = fmaxf(m, fmaxf(norm2<2>(a0), norm2<2>(a1)));
+                } else {
+                    const unsigned a0[1] = {w.x}, a1[1] = {w.y}, a2[1] = {w.z}, a3[1] = {w.w};
+                    m = fmaxf(m, fmaxf(fmaxf(norm2<1>(a0), norm2<1>(a1)), fmaxf(norm2<1>(a2), norm2<1>(a3))));
+                }
+            }
+            const unsigned mb = wave_max_u32(__float_as_uint(m));
+            if (lane == 0) atomicMax(&c2bits[(st * RPG * NT + wave * 64) / CH], mb);
+        }
+        __syncthreads();
+    }
+
     fetch(0);
-    commit(0);
+    commit(0, 0);
     unsigned xnext[C / 2];
     load_x(0, xnext);
     __syncthreads();
     for (int g = 0; g < GH; ++g) {
         const int buf = g & 1;
-        // this lane's token: its slice of the group (fetched one group ahead) and |x|^2
-        unsigned xw[C / 2];
-        float x2 = 0.f;
+        const GroupScale gs = group_scale(c2bits[g]);
+        // this lane's token: its slice of the group (fetched one group ahead), scaled, and |x'|^2
+        unsigned xw[C / 2], xs[C / 2];
 #pragma unroll
-        for (int i = 0; i < C / 2; ++i) {
-            xw[i] = xnext[i];
-            const half2_t h = __builtin_bit_cast(half2_t, xw[i]);
-            x2 = __builtin_fmaf((float)h.x, (float)h.x, x2);
-            x2 = __builtin_fmaf((float)h.y, (float)h.y, x2);
-        }
+        for (int i = 0; i < C / 2; ++i) xw[i] = xnext[i];
+        const float x2 = norm2<C / 2>(xw) * gs.f2;
+        const bool x_over = !(x2 < 1.0e9f);                      // |x'| beyond 2^15: not as fp16
+#pragma unroll
+        for (int i = 0; i < C / 2; ++i) xs[i] = x_over ? 0u : scale_pair(xw[i], gs);
         if (g + 1 < GH) {
             fetch(g + 1);
             load_x(g + 1, xnext);
         }
-        float c2max = 0.f;
-        for (int j = lane; j < K; j += 64) c2max = fmaxf(c2max, nrm[buf][j]);
-#pragma unroll
-        for (int o = 32; o > 0; o >>= 1) c2max = fmaxf(c2max, __shfl_xor(c2max, o));
-        // 2^-17 M with M >= |x| |c|max + |c|max^2 / 2 (1 % slack for the roundings of this line)
-        const float thr = (1.01f * (__builtin_sqrtf(x2 * c2max) + 0.5f * c2max) + 1e-30f) * (1.0f / 131072.0f);
-        const bool too_big = !(c2max < 60000.f);     // -|c|^2 / 2 must fit fp16 safely
+        // 1.5 * 2^-17 M with M >= |x'| |c'|max + |c'|max^2 / 2 (1 % slack for the roundings of this line)
+        const float thr = (1.01f * (__builtin_sqrtf(x2 * gs.c2max_scaled) + 0.5f * gs.c2max_scaled)) * (1.5f / 131072.0f);
+        const bool exact_only = gs.too_big || x_over;
 
 #pragma unroll
         for (int h = 0; h < 2; ++h) {
@@ -212,8 +310,9 @@ __global__ __launch_bounds__(NW * 64) void encode_mfma_kernel(EncodeArgs a)
             const int src_lane = 32 * h + (lane & 31);
             unsigned xh[C / 2];
 #pragma unroll
-            for (int i = 0; i < C / 2; ++i) xh[i] = __shfl(xw[i], src_lane);
+            for (int i = 0; i < C / 2; ++i) xh[i] = __shfl(xs[i], src_lane);
             const float thr_h = __shfl(thr, src_lane);
+            const int exact_h = __shfl(exact_only ? 1 : 0, src_lane);
             const _Float16 one = (_Float16)1.0f, zero = (_Float16)0.0f;
             vec_t bop;
             if constexpr (C == 8) {
@@ -277,7 +376,7 @@ __global__ __launch_bounds__(NW * 64) void encode_mfma_kernel(EncodeArgs a)
                 const int code = wblk * 32 + 8 * (i >> 2) + 4 * whalf + (i & 3);
                 const float bv = __uint_as_float(bits & 0xfffffff0u);
                 const float sv = __uint_as_float(__float_as_uint(second) & 0xfffffff0u);
-                unsure = !(bv - sv > thr_h) || too_big;
+                unsure = !(bv - sv > thr_h) || exact_h != 0;
                 rec[wave][(slot >> 4) * 1024 + u * 16 + (slot & 15)] = (uint8_t)(code & 0xff);
                 if constexpr (B == 10) code16[wave][u][g] = (uint16_t)code;
             }
@@ -290,9 +389,9 @@ __global__ __launch_bounds__(NW * 64) void encode_mfma_kernel(EncodeArgs a)
                 float x[C];
 #pragma unroll
                 for (int i = 0; i < C / 2; ++i) {
-                    const half2_t hh = __builtin_bit_cast(half2_t, (unsigned)__builtin_amdgcn_readlane((int)xh[i], r));
-                    x[2 * i] = (float)hh.x;
-                    x[2 * i + 1] = (float)hh.y;
+                    const half2_t hh = __builtin_bit_cast(half2_t, (unsigned)__builtin_amdgcn_readlane((int)xw[i], 32 * h + r));
+                    x[2 * i] = (float)hh.x * gs.f1;                // exact in fp32
+                    x[2 * i + 1] = (float)hh.y * gs.f1;
                 }
                 unsigned dmin = ~0u, jmin = 0;
 #pragma unroll 4
@@ -312,7 +411,7 @@ __global__ __launch_bounds__(NW * 64) void encode_mfma_kernel(EncodeArgs a)
                 }
             }
         }
-        if (g + 1 < GH) commit(buf ^ 1);
+        if (g + 1 < GH) commit(buf ^ 1, g + 1);
         __syncthreads();
     }
 

@@ -137,6 +137,39 @@ def test_encode_ties_and_exact_hits():
     assert np.all(codes == 40)
 
 
+@pytest.mark.parametrize("c,b", FORMATS)
+def test_encode_wide_dynamic_range_and_near_ties(c, b):
+    """Cases built to stress a filtered search: groups whose |c|^2 is far beyond fp16's comfort
+    (the filter must step aside), groups of tiny values next to huge ones, tokens of all zeros,
+    and centroids that differ from each other by one fp16 unit in one channel far from the origin
+    (score gaps far below any fp16/fp32 filter's resolution): the codes must still be the exact
+    nearest centroids."""
+    hkv, T = 1, 160
+    fmt = cq.CQFormat(c, b, 128, hkv)
+    G, K = fmt.groups, 1 << b
+    rng = np.random.default_rng(11)
+    cb = rng.standard_normal((G, K, c)).astype(np.float32)
+    x = rng.standard_normal((T, G, c)).astype(np.float32)
+    scales = np.array([1.0, 300.0, 1e-3, 40.0, 2000.0, 0.05, 8.0, 120.0])
+    for g in range(G):
+        s = scales[g % len(scales)]
+        cb[g] *= s
+        x[:, g] *= s
+    # group 1 (if present more than once, every 8th + 1): a cluster of near-identical centroids far out
+    far = np.full(c, 180.0, dtype=np.float32)
+    for j in range(16):
+        cb[1, 30 + j] = far
+        cb[1, 30 + j, j % c] = np.float32(np.float16(180.0)) + (j // c + 1) * 0.125   # fp16 spacing at 180 is 0.125
+    x[::3, 1] = far + rng.uniform(-0.3, 0.3, size=(len(x[::3]), c)).astype(np.float32)
+    x[5] = 0.0                                       # a token of zeros
+    cbh = cb.astype(np.float16)
+    xh = x.reshape(1, T, G * c).astype(np.float16)
+    assert np.isfinite(cbh.astype(np.float32)).all() and np.isfinite(xh.astype(np.float32)).all()
+    cache = gpu_encode(xh, cbh, fmt, 192, 0)
+    codes = cache_to_codes(cache, fmt, 1, 192, T, 0)[0]
+    check_codes(codes, xh[0], cbh)
+
+
 # ------------------------------------------------------------------------------------------
 # decode attention
 # ------------------------------------------------------------------------------------------
