@@ -198,11 +198,17 @@ CQ_API cq_status cq_decode_step(const void *q, const void *x_k_new, const void *
  *                       XORs what it read into `sink` (device, at least 8 KiB, any contents).
  * cq_probe_copy         copies `bytes` (multiple of 16) from `src` to `dst` (device, 16-byte
  *                       aligned, not overlapping): a kernel whose HBM traffic is known exactly.
- * Errors: CQ_ERR_INVALID_ARG for null / misaligned pointers or a size that is zero or not a
- * multiple of 16; CQ_ERR_HIP if the launch fails.
+ * cq_probe_mfma         one matrix-core product D = A B exactly as the prefill encode kernel
+ *                       issues it (v_mfma_f32_32x32x16_f16 for kdim 16, v_mfma_f32_32x32x8_f16
+ *                       for kdim 8; zero accumulator): a fp16 [32][kdim] row-major, b fp16
+ *                       [kdim][32] row-major, d fp32 [32][32] row-major, all device.  Tests pin
+ *                       the rounding model that the encode kernel's error bound assumes to it.
+ * Errors: CQ_ERR_INVALID_ARG for null / misaligned pointers, a size that is zero or not a
+ * multiple of 16, or a kdim other than 8 and 16; CQ_ERR_HIP if the launch fails.
  */
 CQ_API cq_status cq_probe_stream_read(const void *src, size_t bytes, void *sink, void *stream);
 CQ_API cq_status cq_probe_copy(const void *src, void *dst, size_t bytes, void *stream);
+CQ_API cq_status cq_probe_mfma(const void *a, const void *b, void *d, int32_t kdim, void *stream);
 
 #ifdef __cplusplus
 }

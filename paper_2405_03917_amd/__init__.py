@@ -26,7 +26,7 @@ TILE_TOKENS = 64
 EXPORTS = (
     "cq_version", "cq_status_string", "cq_format_check", "cq_code_bytes_per_token_head",
     "cq_cache_bytes", "cq_encode", "cq_encode_kv", "cq_decode_default_split", "cq_decode_workspace_bytes",
-    "cq_decode_attention", "cq_decode_step", "cq_probe_stream_read", "cq_probe_copy",
+    "cq_decode_attention", "cq_decode_step", "cq_probe_stream_read", "cq_probe_copy", "cq_probe_mfma",
 )
 
 
@@ -106,6 +106,8 @@ def load() -> ctypes.CDLL:
     lib.cq_probe_stream_read.argtypes = [vp, ctypes.c_size_t, vp, vp]
     lib.cq_probe_copy.restype = ctypes.c_int
     lib.cq_probe_copy.argtypes = [vp, vp, ctypes.c_size_t, vp]
+    lib.cq_probe_mfma.restype = ctypes.c_int
+    lib.cq_probe_mfma.argtypes = [vp, vp, vp, i32, vp]
     _lib = lib
     return lib
 
@@ -354,3 +356,19 @@ def cq_probe_copy(src, dst, stream=None) -> None:
     st = load().cq_probe_copy(src.data_ptr(), dst.data_ptr(), src.numel(), _stream_handle(stream))
     if st != CQ_OK:
         raise CQError(st, "cq_probe_copy")
+
+
+def cq_probe_mfma(a, b, stream=None):
+    """D = A B by one matrix-core instruction: a fp16 [32, kdim], b fp16 [kdim, 32] (kdim 8 or 16,
+    contiguous device tensors) -> fp32 [32, 32] (measurement aid)."""
+    import torch
+    _dev(a, torch.float16, "a")
+    _dev(b, torch.float16, "b")
+    kdim = a.shape[1]
+    if tuple(a.shape) != (32, kdim) or tuple(b.shape) != (kdim, 32) or not (a.is_contiguous() and b.is_contiguous()):
+        raise ValueError("a must be [32, kdim] and b [kdim, 32], contiguous")
+    d = torch.empty((32, 32), dtype=torch.float32, device=a.device)
+    st = load().cq_probe_mfma(a.data_ptr(), b.data_ptr(), d.data_ptr(), kdim, _stream_handle(stream))
+    if st != CQ_OK:
+        raise CQError(st, "cq_probe_mfma")
+    return d

@@ -134,3 +134,12 @@ def test_python_binding_refuses_cpu_tensors():
     codes = torch.zeros(1024, dtype=torch.uint8)
     with pytest.raises(TypeError):
         cq.cq_encode(x, cb, fmt, codes, 0, 64)
+
+
+def test_probes_reject_bad_arguments_without_launching():
+    lib = cq.load()
+    assert lib.cq_probe_mfma(_fake(), _fake(0x20000), _fake(0x30000), 7, None) == cq.CQ_ERR_INVALID_ARG
+    assert lib.cq_probe_mfma(None, _fake(0x20000), _fake(0x30000), 16, None) == cq.CQ_ERR_INVALID_ARG
+    assert lib.cq_probe_mfma(_fake(0x10004), _fake(0x20000), _fake(0x30000), 8, None) == cq.CQ_ERR_INVALID_ARG
+    assert lib.cq_probe_copy(_fake(), _fake(0x20000), 24, None) == cq.CQ_ERR_INVALID_ARG
+    assert lib.cq_probe_stream_read(_fake(), 0, _fake(0x20000), None) == cq.CQ_ERR_INVALID_ARG
