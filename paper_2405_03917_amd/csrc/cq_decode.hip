@@ -42,7 +42,8 @@ typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
 typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kMinScoreFloats = 4096;         // the score buffer doubles as reduction scratch
-constexpr int kKeyFloats = 2 * 2 * 64;        // fused step: 2 x 64 64-bit minima
+// fused step: 2 x Gh 64-bit (distance, index) minima, then the new token's fixed-point weight
+constexpr int kKeyFloats(int gh) { return 2 * 2 * gh + 2; }
 // reduction scratch: 64 words + one row of head_dim floats per wavefront
 constexpr int kScratchFloats(int nt, int head_dim) { return 64 + (nt / 64) * head_dim; }
 
@@ -52,6 +53,17 @@ __device__ __forceinline__ float lds_load(unsigned byte_addr) { return *(lds_f32
 __device__ __forceinline__ void lds_add(unsigned byte_addr, unsigned v)
 {
     __hip_atomic_fetch_add((lds_u32*)(byte_addr), v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+}
+
+// Workgroup barrier that orders LDS traffic only.  __syncthreads() would also wait for every
+// outstanding global load, i.e. for the code tiles that are deliberately kept in flight across
+// the barriers of this kernel.  (No barrier here orders global memory: what the workgroup
+// exchanges lives in LDS.)
+__device__ __forceinline__ void lds_barrier()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
 }
 
 __device__ __forceinline__ float wave_max(float v)
@@ -334,11 +346,13 @@ __device__ __forceinline__ void store_new_codes(uint8_t* tile, const unsigned lo
 }
 
 // STEP = true is the fused decode step: the workgroup whose split holds the newest position
-// (t_n - 1) first encodes that token's key and value rows for its KV head while it builds the
-// score table (the key codebook is in registers anyway), then patches the two tiles that hold
-// the position in registers as if the codes were already in the cache, and -- for the first
-// query head of each KV head -- stores the codes.  Results equal cq_encode_kv followed by
-// cq_decode_attention bit for bit.
+// (t_n - 1) also encodes that token's key and value rows for its KV head.  Keys: while it builds
+// the score table (the key codebook is in registers anyway); the tile that holds the position is
+// then patched in registers as if the codes were already in the cache.  Values: in the epilogue
+// (the value codebook is in registers there); phase V leaves the position out of the bins and
+// its weight is added to the bins of the codes just found.  The first query head of each KV head
+// stores the codes.  Results equal cq_encode_kv followed by cq_decode_attention bit for bit
+// (the bins are integers: the order of the additions does not matter).
 template <int GH, int C, int B, int NT, bool STEP>
 __global__ __launch_bounds__(NT, 4) void decode_split_kernel(DecodeArgs a)
 {
@@ -352,9 +366,7 @@ __global__ __launch_bounds__(NT, 4) void decode_split_kernel(DecodeArgs a)
     constexpr int NCH = GH / 16;        // 16-group chunks
     constexpr int UNITS = 16 * K / JPL; // 16-byte loads per chunk
     constexpr int IPT = UNITS / NT;     // ... per thread
-    // ... requested together (the fused step holds key and value centroids at once)
-    constexpr int KBMAX = (STEP && C == 8) ? 4 : 8;
-    constexpr int KB = IPT < KBMAX ? IPT : KBMAX;
+    constexpr int KB = IPT < 8 ? IPT : 8;   // ... requested together
     static_assert(UNITS % NT == 0 && NT % 16 == 0, "thread count must divide the codebook walk");
     extern __shared__ float smem[];
     float* tab = smem;                              // [K][RW]; first the score table, then the bins
@@ -397,7 +409,7 @@ __global__ __launch_bounds__(NT, 4) void decode_split_kernel(DecodeArgs a)
     const bool has_new = STEP && tile_new >= tile0 && tile_new < tile1;
     if (has_new) {
         if (tid < 2 * GH) keys[tid] = ~0ull;
-        __syncthreads();
+        lds_barrier();
     }
 
     Columns<GH, B> col;
@@ -413,8 +425,9 @@ __global__ __launch_bounds__(NT, 4) void decode_split_kernel(DecodeArgs a)
     // ---- 1. score table ------------------------------------------------------------------
     // unit u = tid + k NT of a 16-group chunk: group gl = u % 16 (fixed per thread), centroids
     // j0 .. j0 + JPL - 1 with j0 = (u / 16) * JPL.  A wavefront's loads are 16 segments of 64 B.
+    const int gl = tid & 15;
+    unsigned xvw[STEP ? NCH : 1][C / 2];            // fused step: this thread's slices of the new value row
     {
-        const int gl = tid & 15;
         const uint16_t* qh = a.q + (size_t)(n * a.n_q_heads + hq) * D;
 #pragma unroll
         for (int ch = 0; ch < NCH; ++ch) {
@@ -423,26 +436,23 @@ __global__ __launch_bounds__(NT, 4) void decode_split_kernel(DecodeArgs a)
             unsigned qw[C / 2];
 #pragma unroll
             for (int i = 0; i < C / 2; ++i) qw[i] = *reinterpret_cast<const unsigned*>(qh + g * C + 2 * i);
-            // fused step: the new key / value rows against this group's two codebooks, same walk
-            float xk[C], xv[C];
-            unsigned long long kkey = ~0ull, vkey = ~0ull;
-            const uint16_t* cvn = a.v_centroids + (size_t)(hkv * GH + g) * K * C;
+            // fused step: the new key row against this group's codebook, same walk
+            float xk[C];
+            unsigned long long kkey = ~0ull;
             if (has_new) {
-                load_row_slice<C>(a.xk_new + (size_t)n * a.x_new_stride + (size_t)(hkv * GH + g) * C, xk);
-                load_row_slice<C>(a.xv_new + (size_t)n * a.x_new_stride + (size_t)(hkv * GH + g) * C, xv);
+                const size_t xoff = (size_t)n * a.x_new_stride + (size_t)(hkv * GH + g) * C;
+                load_row_slice<C>(a.xk_new + xoff, xk);
+#pragma unroll
+                for (int i = 0; i < C / 2; ++i) xvw[ch][i] = *reinterpret_cast<const unsigned*>(a.xv_new + xoff + 2 * i);
             }
 #pragma unroll
             for (int k0 = 0; k0 < IPT; k0 += KB) {
                 Cent16 raw[KB];
 #pragma unroll
                 for (int k = 0; k < KB; ++k) raw[k] = load_cent16(ck + (size_t)((tid + (k0 + k) * NT) >> 4) * 8);
-                Cent16 rawn[STEP ? KB : 1];
-                if (has_new) {
-#pragma unroll
-                    for (int k = 0; k < KB; ++k) rawn[STEP ? k : 0] = load_cent16(cvn + (size_t)((tid + (k0 + k) * NT) >> 4) * 8);
-                }
-                // the first key tiles are requested behind the first centroids: loads return in
-                // order, so the table build waits for L2 only while HBM latency runs in the shadow
+                // the first key tiles are requested behind the first centroids: tile requests must
+                // go out as early as possible (the kernel is bound by HBM from its first
+                // microsecond), but not in front of the loads the table build waits for
                 if (ch == 0 && k0 == 0) st.begin(kstream, my_tiles, tile0 + wave, NW, lane);
 #pragma unroll
                 for (int k = 0; k < KB; ++k) {
@@ -461,8 +471,6 @@ __global__ __launch_bounds__(NT, 4) void decode_split_kernel(DecodeArgs a)
                         if (has_new) {
                             const unsigned long long kk = centroid_key<C>(xk, &raw[k].w[jj * (C / 2)], j0 + jj);
                             kkey = kk < kkey ? kk : kkey;
-                            const unsigned long long vk = centroid_key<C>(xv, &rawn[STEP ? k : 0].w[jj * (C / 2)], j0 + jj);
-                            vkey = vk < vkey ? vk : vkey;
                         }
                     }
                 }
@@ -470,20 +478,16 @@ __global__ __launch_bounds__(NT, 4) void decode_split_kernel(DecodeArgs a)
             if (has_new) {
                 kkey = group_lanes_min(kkey);
                 if (lane < 16) lds_min_u64(&keys[g], kkey);
-                vkey = group_lanes_min(vkey);
-                if (lane < 16) lds_min_u64(&keys[GH + g], vkey);
             }
         }
     }
-    __syncthreads();
+    lds_barrier();
 
-    // fused step: the codes of the new token are known; the first query head of the KV head
+    // fused step: the key codes of the new token are known; the first query head of the KV head
     // stores them (each token owns its 16-byte records, so no other token's bytes are touched)
     const bool writer = has_new && hq % (a.n_q_heads / a.f.n_kv_heads) == 0;
-    if (writer) {
+    if (writer)
         store_new_codes<GH, B>(const_cast<uint8_t*>(kstream) + (size_t)tile_new * F::TILE_BYTES, keys, u_new, tid);
-        store_new_codes<GH, B>(const_cast<uint8_t*>(vstream) + (size_t)tile_new * F::TILE_BYTES, keys + GH, u_new, tid);
-    }
 
     // ---- 2. phase K: scores --------------------------------------------------------------
     float lane_max = -INFINITY;
@@ -505,9 +509,9 @@ __global__ __launch_bounds__(NT, 4) void decode_split_kernel(DecodeArgs a)
     st.begin(vstream, my_tiles, tile0 + wave, NW, lane);         // value codes are on their way
 
     lane_max = wave_max(lane_max);
-    __syncthreads();                                // all table reads done, all scores written
+    lds_barrier();                                // all table reads done, all scores written
     if (lane == 0) tab[wave] = lane_max;            // the table is dead: its head carries the maxima
-    __syncthreads();
+    lds_barrier();
     float m = tab[0];
 #pragma unroll
     for (int w = 1; w < NW; ++w) m = fmaxf(m, tab[w]);
@@ -517,13 +521,13 @@ __global__ __launch_bounds__(NT, 4) void decode_split_kernel(DecodeArgs a)
     for (int i = tid; i < (tile1 - tile0) * kTileTokens; i += NT) l_est += __builtin_amdgcn_exp2f(sc[sidx(i)] - m);
     l_est = wave_sum(l_est);
     if (lane == 0) tab[16 + wave] = l_est;
-    __syncthreads();
+    lds_barrier();
     l_est = 0.f;
 #pragma unroll
     for (int w = 0; w < NW; ++w) l_est += tab[16 + w];
     const int fx = fixed_point_exponent(l_est);
     const float fx_scale = ldexpf(1.f, fx), fx_inv = ldexpf(1.f, -fx);
-    __syncthreads();                                // everyone holds m and fx before the table is cleared
+    lds_barrier();                                // everyone holds m and fx before the table is cleared
     {
         float4* t4 = reinterpret_cast<float4*>(tab);
         if constexpr (F::SCORES_IN_TABLE) {         // clear words 0..31 of every row, keep the scores
@@ -534,20 +538,25 @@ __global__ __launch_bounds__(NT, 4) void decode_split_kernel(DecodeArgs a)
             for (int i = tid; i < F::TAB_FLOATS / 4; i += NT) t4[i] = make_float4(0.f, 0.f, 0.f, 0.f);
         }
     }
-    __syncthreads();
+    lds_barrier();
 
     // ---- 3. phase V: probability bins ----------------------------------------------------
-    const int gl = tid & 15;
+    unsigned* pf_new = reinterpret_cast<unsigned*>(keys + 2 * GH);
     constexpr bool EARLY = IPT * NCH <= 8 && KB == IPT;
     Cent16 rawv[EARLY ? NCH : 1][KB];
     unsigned lane_sum = 0;
     st.run(vstream, my_tiles, tile0 + wave, NW, lane, [&](const Tile<GH, B>& w_in, int k) {
         const int lt = wave + k * NW;
-        Tile<GH, B> w = w_in;
-        if (has_new && tile0 + lt == tile_new) patch_new_token<GH, B>(w, keys + GH, u_new, lane);
+        const Tile<GH, B>& w = w_in;
         const float p = __builtin_amdgcn_exp2f(sc[sidx(lt * kTileTokens + lane)] - m);
-        const unsigned pf = (unsigned)__builtin_fmaf(p, fx_scale, 0.5f);     // round to nearest
+        unsigned pf = (unsigned)__builtin_fmaf(p, fx_scale, 0.5f);           // round to nearest
         lane_sum += pf;
+        // fused step: the new token's value codes are found in the epilogue (the value codebook is
+        // loaded there anyway); its weight waits in LDS and joins the bins then
+        if (has_new && tile0 + lt == tile_new && lane == u_new) {
+            *pf_new = pf;
+            pf = 0;
+        }
 #pragma unroll
         for (int s = 0; s < GH; ++s) lds_add(slot_addr<GH, B>(w, col, s), pf);
     }, [&] {
@@ -568,8 +577,53 @@ __global__ __launch_bounds__(NT, 4) void decode_split_kernel(DecodeArgs a)
     // same walk as the table build; thread-private sums over its centroids of group gl in every
     // chunk, then lanes l, l+16, l+32, l+48 and the wavefronts are added up.
     lane_sum = wave_sum_u32(lane_sum);
-    __syncthreads();                                // all bin updates done; the scores are dead
+    lds_barrier();                                // all bin updates done; the scores are dead
     if (lane == 0) scr[wave] = __uint_as_float(lane_sum);
+
+    // fused step: encode the new value row against the value codebook (same walk, same registers
+    // as the sums below), add its weight to the bins of its codes, store the codes
+    if (has_new) {
+#pragma unroll
+        for (int ch = 0; ch < NCH; ++ch) {
+            float xv[C];
+#pragma unroll
+            for (int i = 0; i < C / 2; ++i) {
+                const half2_t h = __builtin_bit_cast(half2_t, xvw[ch][i]);
+                xv[2 * i] = (float)h.x;
+                xv[2 * i + 1] = (float)h.y;
+            }
+            const uint16_t* cv = a.v_centroids + (size_t)(hkv * GH + ch * 16 + gl) * K * C;
+            unsigned long long vkey = ~0ull;
+#pragma unroll
+            for (int k0 = 0; k0 < IPT; k0 += KB) {
+                Cent16 rawb[EARLY ? 1 : KB];
+                if constexpr (!EARLY) {
+#pragma unroll
+                    for (int k = 0; k < KB; ++k) rawb[k] = load_cent16(cv + (size_t)((tid + (k0 + k) * NT) >> 4) * 8);
+                }
+#pragma unroll
+                for (int k = 0; k < KB; ++k) {
+                    const int j0 = ((tid + (k0 + k) * NT) >> 4) * JPL;
+                    const Cent16& r = EARLY ? rawv[EARLY ? ch : 0][k] : rawb[EARLY ? 0 : k];
+#pragma unroll
+                    for (int jj = 0; jj < JPL; ++jj) {
+                        const unsigned long long vk = centroid_key<C>(xv, &r.w[jj * (C / 2)], j0 + jj);
+                        vkey = vk < vkey ? vk : vkey;
+                    }
+                }
+            }
+            vkey = group_lanes_min(vkey);
+            if (lane < 16) lds_min_u64(&keys[GH + ch * 16 + gl], vkey);
+        }
+        lds_barrier();
+        if (tid < GH) {
+            const unsigned code = (unsigned)(keys[GH + tid] & 0xffffffffu);
+            lds_add((code * RW + tid * R) * 4u, *pf_new);
+        }
+        if (writer)
+            store_new_codes<GH, B>(const_cast<uint8_t*>(vstream) + (size_t)tile_new * F::TILE_BYTES, keys + GH, u_new, tid);
+        lds_barrier();
+    }
 
     float acc[NCH][C];
 #pragma unroll
@@ -616,7 +670,7 @@ __global__ __launch_bounds__(NT, 4) void decode_split_kernel(DecodeArgs a)
 #pragma unroll
             for (int i = 0; i < C; ++i) scr[64 + wave * D + (ch * 16 + gl) * C + i] = acc[ch][i];
     }
-    __syncthreads();
+    lds_barrier();
     unsigned l_fix = 0;                             // exact: integer adds
 #pragma unroll
     for (int w = 0; w < NW; ++w) l_fix += __float_as_uint(scr[w]);
@@ -662,7 +716,7 @@ template <int GH, int B, int NT>
 size_t smem_bytes(int tiles_per_split, int head_dim, bool step)
 {
     using F = Fmt<GH, B>;
-    const int key_floats = step ? kKeyFloats : 0;
+    const int key_floats = step ? kKeyFloats(GH) : 0;
     if (F::SCORES_IN_TABLE) return sizeof(float) * (size_t)(F::TAB_FLOATS + kScratchFloats(NT, head_dim) + key_floats);
     // behind the table: the score buffer (reused as scratch once the scores are dead), then the keys
     const int sc_floats = std::max(kMinScoreFloats, tiles_per_split * kTileTokens);
@@ -720,7 +774,7 @@ cq_status launch_format(const DecodeArgs& a, hipStream_t stream)
 
 int decode_max_tiles_per_split(const Derived& f)
 {
-    if (f.b == 10) return (160 * 1024 / 4 - Fmt<16, 10>::TAB_FLOATS - kKeyFloats) / kTileTokens;   // 124: 160 KB of LDS
+    if (f.b == 10) return (160 * 1024 / 4 - Fmt<16, 10>::TAB_FLOATS - kKeyFloats(16)) / kTileTokens;   // 126: 160 KB of LDS
     if (f.gh <= 32) return 256 * 32 / kTileTokens;                                    // 128: scores inside the table
     return 256;
 }
