@@ -91,22 +91,38 @@ __device__ __forceinline__ void lds_min_u64(unsigned long long* p, unsigned long
 }
 
 // Nearest-centroid search of the fused decode step, bit-identical to cq_encode: squared distance
-// in fp32, one fused multiply-add per channel in channel order; (distance bits, index) packed so
-// that the 64-bit minimum is the nearest centroid with the lowest index among equals.
+// in fp32, one fused multiply-add per channel in channel order.  x - c is formed as
+// fma(c, -1, x): one rounding like the subtraction, and the fp16 centroid is read directly by
+// the mixed-precision FMA.  A thread walks its centroids in ascending index order and keeps
+// the first minimum; (distance bits, index) packed into 64 bits then make the minimum over
+// threads the nearest centroid with the lowest index among equals.
 template <int C>
-__device__ __forceinline__ unsigned long long centroid_key(const float (&x)[C], const unsigned* halves, int j)
+__device__ __forceinline__ float centroid_distance(const float (&x)[C], const unsigned* halves)
 {
     float acc = 0.f;
 #pragma unroll
     for (int i = 0; i < C / 2; ++i) {
         const half2_t h = __builtin_bit_cast(half2_t, halves[i]);
-        const float d0 = x[2 * i] - (float)h.x;
+        const float d0 = __builtin_fmaf((float)h.x, -1.0f, x[2 * i]);
         acc = __builtin_fmaf(d0, d0, acc);
-        const float d1 = x[2 * i + 1] - (float)h.y;
+        const float d1 = __builtin_fmaf((float)h.y, -1.0f, x[2 * i + 1]);
         acc = __builtin_fmaf(d1, d1, acc);
     }
-    return ((unsigned long long)__float_as_uint(acc) << 32) | (unsigned)j;
+    return acc;
 }
+struct Nearest {
+    float d = __builtin_inff();
+    int j = 0;
+    __device__ __forceinline__ void offer(float dist, int idx)
+    {
+        j = dist < d ? idx : j;
+        d = dist < d ? dist : d;
+    }
+    __device__ __forceinline__ unsigned long long key() const
+    {
+        return ((unsigned long long)__float_as_uint(d) << 32) | (unsigned)j;
+    }
+};
 
 template <int C>
 __device__ __forceinline__ void load_row_slice(const uint16_t* p, float (&x)[C])
@@ -436,14 +452,18 @@ __global__ __launch_bounds__(NT, 4) void decode_split_kernel(DecodeArgs a)
             unsigned qw[C / 2];
 #pragma unroll
             for (int i = 0; i < C / 2; ++i) qw[i] = *reinterpret_cast<const unsigned*>(qh + g * C + 2 * i);
-            // fused step: the new key row against this group's codebook, same walk
+            // fused step: the new key row against this group's codebook, same walk (the row's
+            // words are only requested here; they are converted after the loads below went out)
+            unsigned xkw[C / 2];
             float xk[C];
-            unsigned long long kkey = ~0ull;
+            Nearest knear;
             if (has_new) {
                 const size_t xoff = (size_t)n * a.x_new_stride + (size_t)(hkv * GH + g) * C;
-                load_row_slice<C>(a.xk_new + xoff, xk);
 #pragma unroll
-                for (int i = 0; i < C / 2; ++i) xvw[ch][i] = *reinterpret_cast<const unsigned*>(a.xv_new + xoff + 2 * i);
+                for (int i = 0; i < C / 2; ++i) {
+                    xkw[i] = *reinterpret_cast<const unsigned*>(a.xk_new + xoff + 2 * i);
+                    xvw[ch][i] = *reinterpret_cast<const unsigned*>(a.xv_new + xoff + 2 * i);
+                }
             }
 #pragma unroll
             for (int k0 = 0; k0 < IPT; k0 += KB) {
@@ -454,6 +474,15 @@ __global__ __launch_bounds__(NT, 4) void decode_split_kernel(DecodeArgs a)
                 // go out as early as possible (the kernel is bound by HBM from its first
                 // microsecond), but not in front of the loads the table build waits for
                 if (ch == 0 && k0 == 0) st.begin(kstream, my_tiles, tile0 + wave, NW, lane);
+                if constexpr (STEP) __builtin_amdgcn_sched_barrier(0);
+                if (has_new && k0 == 0) {
+#pragma unroll
+                    for (int i = 0; i < C / 2; ++i) {
+                        const half2_t h = __builtin_bit_cast(half2_t, xkw[i]);
+                        xk[2 * i] = (float)h.x;
+                        xk[2 * i + 1] = (float)h.y;
+                    }
+                }
 #pragma unroll
                 for (int k = 0; k < KB; ++k) {
                     const int j0 = ((tid + (k0 + k) * NT) >> 4) * JPL;
@@ -468,15 +497,12 @@ __global__ __launch_bounds__(NT, 4) void decode_split_kernel(DecodeArgs a)
                         float* dst = tab + (j0 + jj) * RW + g * R;
                         if constexpr (R == 2) *reinterpret_cast<float2*>(dst) = make_float2(v, v);
                         else *dst = v;
-                        if (has_new) {
-                            const unsigned long long kk = centroid_key<C>(xk, &raw[k].w[jj * (C / 2)], j0 + jj);
-                            kkey = kk < kkey ? kk : kkey;
-                        }
+                        if (has_new) knear.offer(centroid_distance<C>(xk, &raw[k].w[jj * (C / 2)]), j0 + jj);
                     }
                 }
             }
             if (has_new) {
-                kkey = group_lanes_min(kkey);
+                const unsigned long long kkey = group_lanes_min(knear.key());
                 if (lane < 16) lds_min_u64(&keys[g], kkey);
             }
         }
@@ -593,7 +619,7 @@ __global__ __launch_bounds__(NT, 4) void decode_split_kernel(DecodeArgs a)
                 xv[2 * i + 1] = (float)h.y;
             }
             const uint16_t* cv = a.v_centroids + (size_t)(hkv * GH + ch * 16 + gl) * K * C;
-            unsigned long long vkey = ~0ull;
+            Nearest vnear;
 #pragma unroll
             for (int k0 = 0; k0 < IPT; k0 += KB) {
                 Cent16 rawb[EARLY ? 1 : KB];
@@ -606,13 +632,10 @@ __global__ __launch_bounds__(NT, 4) void decode_split_kernel(DecodeArgs a)
                     const int j0 = ((tid + (k0 + k) * NT) >> 4) * JPL;
                     const Cent16& r = EARLY ? rawv[EARLY ? ch : 0][k] : rawb[EARLY ? 0 : k];
 #pragma unroll
-                    for (int jj = 0; jj < JPL; ++jj) {
-                        const unsigned long long vk = centroid_key<C>(xv, &r.w[jj * (C / 2)], j0 + jj);
-                        vkey = vk < vkey ? vk : vkey;
-                    }
+                    for (int jj = 0; jj < JPL; ++jj) vnear.offer(centroid_distance<C>(xv, &r.w[jj * (C / 2)]), j0 + jj);
                 }
             }
-            vkey = group_lanes_min(vkey);
+            const unsigned long long vkey = group_lanes_min(vnear.key());
             if (lane < 16) lds_min_u64(&keys[GH + ch * 16 + gl], vkey);
         }
         lds_barrier();
