@@ -34,9 +34,9 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0          # MI355X published peak, GB/s
-# HBM bytes per decode launch from rocprofv3 counters (FETCH_SIZE x 1.9997 + WRITE_SIZE), see
-# profiles/decode_split_kernel_cq4c8b_batch16_ctx4096.md
-TRAFFIC_BYTES_PER_LAUNCH = (67750.7 * 1.9997 + 128.0) * 1024
+# HBM bytes per launch of the fused decode-step kernel from rocprofv3 counters (FETCH_SIZE x 1.9998
+# + WRITE_SIZE, KiB per dispatch), see profiles/decode_step_kernel_cq4c8b_batch16_ctx4096.md
+TRAFFIC_BYTES_PER_LAUNCH = (67950.1 * 1.9998 + 192.0) * 1024
 METRIC = "decode-attn KV tokens/s & achieved HBM GB/s (% peak); cq_encode tokens/s"
 
 
