@@ -191,6 +191,45 @@ CQ_API cq_status cq_decode_step(const void *q, const void *x_k_new, const void *
                          void *stream);
 
 /*
+ * Centroid learning (Section 3.2 of the paper, "Centroid Learning"): for every channel group an
+ * independent k-means run over the tokens of a calibration tensor -- Eq. 5; with `weights`,
+ * the weighted objective of Eq. 6 (weighted k-means; the caller supplies the weight of each
+ * token and group, e.g. the sum of the squared gradients of the group's channels) -- with
+ * k-means++ initialisation and a fixed number of Lloyd iterations (Section 4.3: 100).
+ *
+ * Every decision is taken in arithmetic that does not depend on processing order (fp32
+ * distances with one fused multiply-add per channel in channel order, lowest index on ties;
+ * integer weights floor(w 2^kw) with the largest weight of a group in [2^21, 2^22); exact
+ * integer sums for the means; k-means++ sampled on integers from the caller's random words), so
+ * the result is a function of the inputs alone, bit for bit.
+ *
+ *   x                 fp16 [n_points][D], row stride x_row_stride (>= D, multiple of 8) elements
+ *   weights           fp32 [n_points][G], >= 0, or NULL (all tokens weigh the same); a group whose
+ *                     weights are all zero is treated as unweighted
+ *   n_points          1 .. CQ_KMEANS_MAX_POINTS
+ *   n_iter            Lloyd iterations (>= 0; 0 with rnd: k-means++ only)
+ *   rnd               uint64 [G][2^b]: one random word per centre to draw (k-means++), or NULL
+ *   init_centroids    fp32 [G][2^b][c] starting centroids, or NULL; exactly one of rnd and
+ *                     init_centroids must be given
+ *   picks             out, optional (needs rnd): int32 [G][2^b], the tokens chosen by k-means++
+ *   centroids         out, optional: fp16 [G][2^b][c], the fp32 result rounded to nearest even --
+ *                     the codebook cq_encode and cq_decode_attention take
+ *   centroids_f32     out, optional: fp32 [G][2^b][c]; at least one of the two must be given
+ *   assignment        out, optional: uint16 [G][n_points], the cluster of every token in the last
+ *                     iteration's assignment step (untouched when n_iter = 0)
+ *   workspace         at least cq_kmeans_workspace_bytes(fmt, n_points) bytes (0: invalid arguments)
+ * All pointers are device pointers, 16-byte aligned.  A cluster that owns no token keeps its
+ * centroid.  Errors: CQ_ERR_INVALID_ARG, CQ_ERR_UNSUPPORTED (format), CQ_ERR_WORKSPACE_TOO_SMALL,
+ * CQ_ERR_HIP.
+ */
+#define CQ_KMEANS_MAX_POINTS 524288
+CQ_API size_t cq_kmeans_workspace_bytes(const cq_format *fmt, int32_t n_points);
+CQ_API cq_status cq_kmeans_fit(const void *x, int64_t x_row_stride, const float *weights, const cq_format *fmt,
+                        int32_t n_points, int32_t n_iter, const uint64_t *rnd, const float *init_centroids,
+                        int32_t *picks, void *centroids, float *centroids_f32, uint16_t *assignment,
+                        void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * Measurement aids (no part of the method; benchmarks use them as yardsticks).
  *
  * cq_probe_stream_read  reads `bytes` (multiple of 16) from device memory `src` once, 16 bytes

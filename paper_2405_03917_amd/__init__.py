@@ -26,7 +26,8 @@ TILE_TOKENS = 64
 EXPORTS = (
     "cq_version", "cq_status_string", "cq_format_check", "cq_code_bytes_per_token_head",
     "cq_cache_bytes", "cq_encode", "cq_encode_kv", "cq_decode_default_split", "cq_decode_workspace_bytes",
-    "cq_decode_attention", "cq_decode_step", "cq_probe_stream_read", "cq_probe_copy", "cq_probe_mfma",
+    "cq_decode_attention", "cq_decode_step", "cq_kmeans_workspace_bytes", "cq_kmeans_fit",
+    "cq_probe_stream_read", "cq_probe_copy", "cq_probe_mfma",
 )
 
 
@@ -104,6 +105,10 @@ def load() -> ctypes.CDLL:
                                    vp, i32, vp, vp, ctypes.c_size_t, vp]
     lib.cq_probe_stream_read.restype = ctypes.c_int
     lib.cq_probe_stream_read.argtypes = [vp, ctypes.c_size_t, vp, vp]
+    lib.cq_kmeans_workspace_bytes.restype = ctypes.c_size_t
+    lib.cq_kmeans_workspace_bytes.argtypes = [fp, i32]
+    lib.cq_kmeans_fit.restype = ctypes.c_int
+    lib.cq_kmeans_fit.argtypes = [vp, i64, vp, fp, i32, i32, vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
     lib.cq_probe_copy.restype = ctypes.c_int
     lib.cq_probe_copy.argtypes = [vp, vp, ctypes.c_size_t, vp]
     lib.cq_probe_mfma.restype = ctypes.c_int
@@ -356,6 +361,64 @@ def cq_probe_copy(src, dst, stream=None) -> None:
     st = load().cq_probe_copy(src.data_ptr(), dst.data_ptr(), src.numel(), _stream_handle(stream))
     if st != CQ_OK:
         raise CQError(st, "cq_probe_copy")
+
+
+KMEANS_MAX_POINTS = 524288
+
+
+def cq_kmeans_workspace_bytes(fmt: CQFormat, n_points: int) -> int:
+    n = load().cq_kmeans_workspace_bytes(ctypes.byref(fmt._c()), n_points)
+    if n == 0:
+        raise CQError(CQ_ERR_INVALID_ARG, "cq_kmeans_workspace_bytes")
+    return n
+
+
+def cq_kmeans_fit(x, fmt: CQFormat, n_iter: int, rnd=None, init_centroids=None, weights=None,
+                  want_picks: bool = False, want_assignment: bool = False, workspace=None, stream=None) -> dict:
+    """Centroid learning for every channel group of x fp16 [n, D] (device): k-means++ from the
+    random words rnd uint64-as-int64 [G, 2^b] (or the given fp32 init_centroids [G, 2^b, c]), then
+    n_iter Lloyd iterations, optionally weighted by weights fp32 [n, G].  Returns a dict with
+    "centroids" (fp16 [G, 2^b, c]), "centroids_f32", and on request "picks" (int32 [G, 2^b]) and
+    "assignment" (int16 view of uint16 [G, n])."""
+    import torch
+    _dev(x, torch.float16, "x")
+    if x.dim() != 2 or x.shape[1] != fmt.n_kv_heads * fmt.head_dim or x.stride(1) != 1:
+        raise ValueError("x must be [n, D] with unit channel stride")
+    n = x.shape[0]
+    G, K, c = fmt.groups, 1 << fmt.b, fmt.c
+    dev = x.device
+    if rnd is not None:
+        _dev(rnd, torch.int64, "rnd")
+        if tuple(rnd.shape) != (G, K) or not rnd.is_contiguous():
+            raise ValueError("rnd must be a contiguous int64 tensor [G, 2^b] holding the 64-bit random words")
+    if init_centroids is not None:
+        _dev(init_centroids, torch.float32, "init_centroids")
+        if tuple(init_centroids.shape) != (G, K, c) or not init_centroids.is_contiguous():
+            raise ValueError("init_centroids must be contiguous fp32 [G, 2^b, c]")
+    if weights is not None:
+        _dev(weights, torch.float32, "weights")
+        if tuple(weights.shape) != (n, G) or not weights.is_contiguous():
+            raise ValueError("weights must be contiguous fp32 [n, G]")
+    need = cq_kmeans_workspace_bytes(fmt, n)
+    if workspace is None:
+        workspace = torch.empty(need, dtype=torch.uint8, device=dev)
+    _dev(workspace, torch.uint8, "workspace")
+    cent16 = torch.empty((G, K, c), dtype=torch.float16, device=dev)
+    cent32 = torch.empty((G, K, c), dtype=torch.float32, device=dev)
+    picks = torch.empty((G, K), dtype=torch.int32, device=dev) if want_picks else None
+    assign = torch.empty((G, n), dtype=torch.int16, device=dev) if want_assignment else None
+    ptr = lambda t: None if t is None else t.data_ptr()
+    st = load().cq_kmeans_fit(x.data_ptr(), x.stride(0), ptr(weights), ctypes.byref(fmt._c()), n, n_iter, ptr(rnd),
+                              ptr(init_centroids), ptr(picks), cent16.data_ptr(), cent32.data_ptr(), ptr(assign),
+                              workspace.data_ptr(), workspace.numel(), _stream_handle(stream))
+    if st != CQ_OK:
+        raise CQError(st, "cq_kmeans_fit")
+    out = {"centroids": cent16, "centroids_f32": cent32}
+    if want_picks:
+        out["picks"] = picks
+    if want_assignment:
+        out["assignment"] = assign
+    return out
 
 
 def cq_probe_mfma(a, b, stream=None):

@@ -165,6 +165,52 @@ cq_status cq_encode_kv(const void* x_k, const void* x_v, int64_t x_batch_stride,
     return launch_encode(a, static_cast<hipStream_t>(stream));
 }
 
+size_t cq_kmeans_workspace_bytes(const cq_format* fmt, int32_t n_points)
+{
+    Derived f;
+    if (derive(fmt, &f) != CQ_OK || n_points <= 0 || n_points > CQ_KMEANS_MAX_POINTS) return 0;
+    return kmeans_workspace_layout(f, n_points, nullptr, nullptr);
+}
+
+cq_status cq_kmeans_fit(const void* x, int64_t x_row_stride, const float* weights, const cq_format* fmt,
+                        int32_t n_points, int32_t n_iter, const uint64_t* rnd, const float* init_centroids,
+                        int32_t* picks, void* centroids, float* centroids_f32, uint16_t* assignment,
+                        void* workspace, size_t workspace_bytes, void* stream)
+{
+    Derived f;
+    cq_status st = derive(fmt, &f);
+    if (st != CQ_OK) return st;
+    if (n_points <= 0 || n_points > CQ_KMEANS_MAX_POINTS || n_iter < 0) return CQ_ERR_INVALID_ARG;
+    if (!x || !aligned16(x) || x_row_stride < f.channels || x_row_stride % 8 != 0) return CQ_ERR_INVALID_ARG;
+    if (weights && !aligned16(weights)) return CQ_ERR_INVALID_ARG;
+    // exactly one source of starting centroids: k-means++ from random words, or the caller's
+    if ((rnd == nullptr) == (init_centroids == nullptr)) return CQ_ERR_INVALID_ARG;
+    if ((rnd && !aligned16(rnd)) || (init_centroids && !aligned16(init_centroids))) return CQ_ERR_INVALID_ARG;
+    if (picks && !rnd) return CQ_ERR_INVALID_ARG;
+    if (!centroids && !centroids_f32) return CQ_ERR_INVALID_ARG;
+    if ((centroids && !aligned16(centroids)) || (centroids_f32 && !aligned16(centroids_f32)) ||
+        (assignment && !aligned16(assignment)) || (picks && !aligned16(picks)))
+        return CQ_ERR_INVALID_ARG;
+    if (!workspace || !aligned16(workspace)) return CQ_ERR_INVALID_ARG;
+    if (workspace_bytes < kmeans_workspace_layout(f, n_points, nullptr, nullptr)) return CQ_ERR_WORKSPACE_TOO_SMALL;
+
+    KMeansArgs a;
+    a.x = static_cast<const uint16_t*>(x);
+    a.x_row_stride = x_row_stride;
+    a.weights = weights;
+    a.n = n_points;
+    a.n_iter = n_iter;
+    a.rnd = rnd;
+    a.do_init = rnd != nullptr;
+    a.cent_in = init_centroids;
+    a.picks = picks;
+    a.cent16_out = static_cast<uint16_t*>(centroids);
+    a.cent32_out = centroids_f32;
+    a.assign_out = assignment;
+    a.f = f;
+    return launch_kmeans(a, workspace, static_cast<hipStream_t>(stream));
+}
+
 int32_t cq_decode_default_split(const cq_format* fmt, int32_t batch, int32_t n_q_heads, int32_t t)
 {
     Derived f;

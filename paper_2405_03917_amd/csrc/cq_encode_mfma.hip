@@ -256,7 +256,7 @@ __global__ __launch_bounds__(NW * 64) void encode_mfma_kernel(EncodeArgs a)
         constexpr int RPG = CH >= NT ? CH / NT : 1;      // consecutive rounds inside one group
         constexpr int STEPS = ROUNDS / RPG;
         constexpr int UNR = RPG >= 16 ? 1 : 16 / RPG;    // about 16 loads in flight
-#pragma unroll(UNR)
+#pragma unroll UNR
         for (int st = 0; st < STEPS; ++st) {
             float m = 0.f;
 #pragma unroll

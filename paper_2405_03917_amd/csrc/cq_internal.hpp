@@ -64,6 +64,33 @@ struct DecodeArgs {
 // Largest tokens_per_split the decode kernel's on-chip score buffer can hold.
 int decode_max_tiles_per_split(const Derived& f);
 
+// Centroid learning: k-means++ (do_init) or given starting centroids, then n_iter Lloyd iterations.
+struct KMeansArgs {
+    const uint16_t* x;        // fp16 [n][D]
+    int64_t x_row_stride;
+    const float* weights;     // fp32 [n][G] or null
+    int n, n_iter;
+    const uint64_t* rnd;      // [G][K] random words (k-means++)
+    bool do_init;
+    const float* cent_in;     // fp32 [G][K][c] starting centroids when !do_init
+    int32_t* picks;           // [G][K] out, optional
+    uint16_t* cent16_out;     // fp16 [G][K][c] out, optional
+    float* cent32_out;        // fp32 [G][K][c] out, optional
+    uint16_t* assign_out;     // [G][n] out, optional
+    Derived f;
+};
+struct KMeansWorkspace {
+    uint16_t* xg;             // fp16 [G][n][c]: the tokens, group-major
+    uint32_t* wq;             // [G][n] integer weights
+    float* dmin;              // [G][n] distance to the nearest chosen centre
+    uint16_t* assign;         // [G][n]
+    float* cent;              // fp32 [G][K][c]
+    unsigned* wmax_bits;      // [G]
+};
+// Carves `base` (null: sizes only) into the workspace arrays; returns the bytes needed.
+size_t kmeans_workspace_layout(const Derived& f, int n, void* base, KMeansWorkspace* ws);
+cq_status launch_kmeans(const KMeansArgs& a, void* workspace, hipStream_t stream);
+
 cq_status launch_encode(const EncodeArgs& a, hipStream_t stream);
 // many tokens per sequence: the MFMA-filtered kernel (cq_encode_mfma.hip)
 cq_status launch_encode_tiles(const EncodeArgs& a, hipStream_t stream);

@@ -143,3 +143,33 @@ def test_probes_reject_bad_arguments_without_launching():
     assert lib.cq_probe_mfma(_fake(0x10004), _fake(0x20000), _fake(0x30000), 8, None) == cq.CQ_ERR_INVALID_ARG
     assert lib.cq_probe_copy(_fake(), _fake(0x20000), 24, None) == cq.CQ_ERR_INVALID_ARG
     assert lib.cq_probe_stream_read(_fake(), 0, _fake(0x20000), None) == cq.CQ_ERR_INVALID_ARG
+
+
+def test_kmeans_sizes_and_argument_checks_without_launching():
+    lib = cq.load()
+    f = cq.CQFormat(8, 8, 128, 2)._c()
+    n = 1000
+    G, K, c = 32, 256, 8
+    need = lib.cq_kmeans_workspace_bytes(ctypes.byref(f), n)
+    # tokens (group-major fp16), integer weights, nearest-centre distances, assignment, fp32 centroids, weight maxima
+    assert need >= G * n * c * 2 + G * n * 4 + G * n * 4 + G * n * 2 + G * K * c * 4 + G * 4
+    assert need < 1.02 * (G * n * c * 2 + G * n * 10 + G * K * c * 4) + 4096
+    assert lib.cq_kmeans_workspace_bytes(ctypes.byref(f), 0) == 0
+    assert lib.cq_kmeans_workspace_bytes(ctypes.byref(f), cq.KMEANS_MAX_POINTS + 1) == 0
+
+    def fit(x=0x10000, stride=256, w=None, n_points=n, n_iter=3, rnd=0x20000, init=None, picks=None, cent=0x30000,
+            cent32=None, assign=None, ws=0x40000, ws_bytes=need):
+        p = lambda v: None if v is None else _fake(v)
+        return int(lib.cq_kmeans_fit(p(x), stride, p(w), ctypes.byref(f), n_points, n_iter, p(rnd), p(init), p(picks),
+                                     p(cent), p(cent32), p(assign), p(ws), ws_bytes, None))
+
+    assert fit(x=None) == cq.CQ_ERR_INVALID_ARG
+    assert fit(stride=255) == cq.CQ_ERR_INVALID_ARG and fit(stride=260) == cq.CQ_ERR_INVALID_ARG
+    assert fit(n_points=0) == cq.CQ_ERR_INVALID_ARG and fit(n_iter=-1) == cq.CQ_ERR_INVALID_ARG
+    assert fit(rnd=None) == cq.CQ_ERR_INVALID_ARG                    # no source of starting centroids
+    assert fit(init=0x50000) == cq.CQ_ERR_INVALID_ARG                # two sources
+    assert fit(rnd=None, init=0x50000, picks=0x60000) == cq.CQ_ERR_INVALID_ARG
+    assert fit(cent=None) == cq.CQ_ERR_INVALID_ARG
+    assert fit(x=0x10002) == cq.CQ_ERR_INVALID_ARG
+    assert fit(ws=None) == cq.CQ_ERR_INVALID_ARG
+    assert fit(ws_bytes=need - 1) == cq.CQ_ERR_WORKSPACE_TOO_SMALL
