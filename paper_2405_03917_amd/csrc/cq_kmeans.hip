@@ -151,37 +151,33 @@ __device__ __forceinline__ unsigned long long wave_incl_scan_u64(unsigned long l
     }
     return v;
 }
-
-// exclusive prefix of `local` over the workgroup's threads (thread order) and the total
-__device__ __forceinline__ unsigned long long block_excl_scan_u64(unsigned long long local, unsigned long long* wave_tot,
-                                                                  unsigned long long* total)
+__device__ __forceinline__ unsigned long long wave_sum_u64(unsigned long long v)
 {
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const unsigned long long incl = wave_incl_scan_u64(local, lane);
-    if (lane == 63) wave_tot[wave] = incl;
-    __syncthreads();
-    unsigned long long off = 0, tot = 0;
 #pragma unroll
-    for (int w = 0; w < kPPThreads / 64; ++w) {
-        const unsigned long long t = wave_tot[w];
-        off += w < wave ? t : 0ull;
-        tot += t;
-    }
-    __syncthreads();
-    *total = tot;
-    return off + incl - local;
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+    return v;
 }
 
+// One workgroup per group.  Wavefront w owns the contiguous tokens [w W, (w + 1) W), W a multiple
+// of 64; in round p its lane l handles token w W + 64 p + l, so every load is one contiguous run
+// and (wavefront, round, lane) order is token order.  A pick: the wavefronts' totals locate the
+// wavefront that holds the r-th unit of mass, that wavefront walks its rounds to the round, and
+// a scan over its lanes finds the token.
 template <int C>
-__global__ __launch_bounds__(kPPThreads) void kmeanspp_kernel(const uint16_t* xg_all, const uint32_t* wq_all,
-                                                              float* dmin_all, const uint64_t* rnd_all, int32_t* picks_all,
-                                                              float* cent_all, int n, int K, int log2n)
+__global__ __launch_bounds__(kPPThreads) void kmeanspp_kernel(const uint16_t* __restrict__ xg_all,
+                                                              const uint32_t* __restrict__ wq_all,
+                                                              float* __restrict__ dmin_all,
+                                                              const uint64_t* __restrict__ rnd_all,
+                                                              int32_t* __restrict__ picks_all, float* __restrict__ cent_all,
+                                                              int n, int K, int log2n)
 {
-    __shared__ unsigned long long wave_tot[kPPThreads / 64];
+    constexpr int NWAVE = kPPThreads / 64;
+    __shared__ unsigned long long wave_tot[NWAVE];
     __shared__ unsigned long long pmax_bits;
     __shared__ int pick_sh;
 
     const int g = blockIdx.x, tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const uint16_t* xg = xg_all + (size_t)g * n * C;
     const uint32_t* wq = wq_all + (size_t)g * n;
     float* dmin = dmin_all + (size_t)g * n;
@@ -189,30 +185,53 @@ __global__ __launch_bounds__(kPPThreads) void kmeanspp_kernel(const uint16_t* xg
     int32_t* picks = picks_all ? picks_all + (size_t)g * K : nullptr;
     float* cent = cent_all + (size_t)g * K * C;
 
-    // thread t owns tokens [i0, i1): prefix sums in thread order are prefix sums in token order
-    const int chunk = (n + kPPThreads - 1) / kPPThreads;
-    const int i0 = min(tid * chunk, n), i1 = min(i0 + chunk, n);
+    const int rounds = (n + kPPThreads - 1) / kPPThreads;    // rounds of 64 tokens per wavefront
+    const int t0 = wave * rounds * 64;                       // this wavefront's first token
 
-    // first centre: proportional to the integer weights
-    {
+    // q of this lane's token in round p: the integer weight (kq < -9000: first pick) or
+    // floor(wq * dmin * 2^kq)
+    auto mass = [&](int p, int kq) -> unsigned long long {
+        const int i = t0 + p * 64 + lane;
+        if (i >= n) return 0ull;
+        if (kq < -9000) return wq[i];
+        return (unsigned long long)ldexp((double)wq[i] * (double)dmin[i], kq);
+    };
+    // draws the token that holds unit r of the total mass (all threads call; sets pick_sh)
+    auto draw = [&](uint64_t word, int kq) {
         unsigned long long local = 0;
-        for (int i = i0; i < i1; ++i) local += wq[i];
-        unsigned long long total;
-        const unsigned long long off = block_excl_scan_u64(local, wave_tot, &total);
-        const unsigned long long r = __umul64hi(rnd[0], total);
-        if (r >= off && r < off + local) {
-            unsigned long long run = off;
-            int i = i0;
-            for (; i < i1; ++i) {
-                run += wq[i];
-                if (run > r) break;
-            }
-            pick_sh = i;
+        for (int p = 0; p < rounds; ++p) local += mass(p, kq);
+        const unsigned long long wtot = wave_sum_u64(local);
+        if (lane == 0) wave_tot[wave] = wtot;
+        __syncthreads();
+        unsigned long long off = 0, total = 0;
+#pragma unroll
+        for (int w = 0; w < NWAVE; ++w) {
+            const unsigned long long t = wave_tot[w];
+            off += w < wave ? t : 0ull;
+            total += t;
         }
-    }
+        const unsigned long long r = __umul64hi(word, total);
+        if (r >= off && r < off + wtot) {                    // wavefront-uniform: exactly one wavefront
+            unsigned long long run = off;
+            for (int p = 0; p < rounds; ++p) {
+                const unsigned long long q = mass(p, kq);
+                const unsigned long long rsum = wave_sum_u64(q);
+                if (run + rsum > r) {
+                    const unsigned long long incl = run + wave_incl_scan_u64(q, lane);
+                    const unsigned long long hit = __ballot(incl > r);
+                    if (lane == 0) pick_sh = t0 + p * 64 + __builtin_ctzll(hit);
+                    break;
+                }
+                run += rsum;
+            }
+        }
+        __syncthreads();
+    };
+
+    draw(rnd[0], -10000);                                    // first centre: proportional to the integer weights
     for (int j = 0;; ++j) {
-        __syncthreads();                            // pick_sh is set
         const int pick = pick_sh;
+        __syncthreads();                                     // everyone has read pick_sh
         if (tid == 0) {
             if (picks) picks[j] = pick;
             pmax_bits = 0ull;
@@ -225,14 +244,18 @@ __global__ __launch_bounds__(kPPThreads) void kmeanspp_kernel(const uint16_t* xg
         // distance to the nearest centre so far; largest weighted distance (non-negative doubles
         // order like their bits)
         double pmax = 0.0;
-        for (int i = i0; i < i1; ++i) {
-            float xi[C];
-            widen<C>(xg + (size_t)i * C, xi);
-            const float d = dist2<C>(xi, cj);
-            const float dm = (j == 0 || d < dmin[i]) ? d : dmin[i];
-            dmin[i] = dm;
-            const double p = (double)wq[i] * (double)dm;
-            pmax = p > pmax ? p : pmax;
+#pragma unroll 4
+        for (int p = 0; p < rounds; ++p) {
+            const int i = t0 + p * 64 + lane;
+            if (i < n) {
+                float xi[C];
+                widen<C>(xg + (size_t)i * C, xi);
+                const float d = dist2<C>(xi, cj);
+                const float dm = (j == 0 || d < dmin[i]) ? d : dmin[i];
+                dmin[i] = dm;
+                const double pr = (double)wq[i] * (double)dm;
+                pmax = pr > pmax ? pr : pmax;
+            }
         }
         unsigned long long pb = (unsigned long long)__double_as_longlong(pmax);
 #pragma unroll
@@ -240,29 +263,17 @@ __global__ __launch_bounds__(kPPThreads) void kmeanspp_kernel(const uint16_t* xg
             const unsigned long long other = __shfl_xor(pb, o);
             pb = other > pb ? other : pb;
         }
-        __syncthreads();                            // pmax_bits was cleared
+        __syncthreads();                                     // pmax_bits was cleared; dmin is written
         if (lane == 0) atomicMax(&pmax_bits, pb);
         __syncthreads();
         const unsigned long long pm = pmax_bits;
-        if (pm == 0ull) {
+        if (pm == 0ull) {                                    // every token sits on a centre already
             if (tid == 0) pick_sh = (int)__umul64hi(rnd[j + 1], (unsigned long long)n);
+            __syncthreads();
             continue;
         }
         const int kq = 62 - log2n - ((int)((pm >> 52) & 0x7ffull) - 1023 + 1);
-        unsigned long long local = 0;
-        for (int i = i0; i < i1; ++i) local += (unsigned long long)ldexp((double)wq[i] * (double)dmin[i], kq);
-        unsigned long long total;
-        const unsigned long long off = block_excl_scan_u64(local, wave_tot, &total);
-        const unsigned long long r = __umul64hi(rnd[j + 1], total);
-        if (r >= off && r < off + local) {
-            unsigned long long run = off;
-            int i = i0;
-            for (; i < i1; ++i) {
-                run += (unsigned long long)ldexp((double)wq[i] * (double)dmin[i], kq);
-                if (run > r) break;
-            }
-            pick_sh = i;
-        }
+        draw(rnd[j + 1], kq);
     }
 }
 
