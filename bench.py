@@ -179,6 +179,22 @@ def extra_measurements(cq, synth, torch):
         "code_read_GBps": code_bytes / (med * 1e-3) / 1e9,
         "frac_of_hbm_peak": code_bytes / (med * 1e-3) / 1e9 / HBM_PEAK_GBPS,
         "tokens_per_split": cq.cq_decode_default_split(fmt, B, cfg.n_q_heads, T)}
+    del kcache, vcache
+    # centroid learning on a calibration tensor of the paper's size (16 sequences x 2048 tokens):
+    # k-means++ and 100 Lloyd iterations for each of the 512 groups of one CQ-8c8b tensor
+    n_cal, iters = 16 * 2048, 100
+    xcal = synth.sample_activations_torch(rk, n_cal, 977, "cuda").view(n_cal, D)
+    g = torch.Generator(device="cuda")
+    g.manual_seed(240503917)
+    rnd = torch.randint(-2 ** 63, 2 ** 63 - 1, (fmt.groups, 1 << cfg.b), dtype=torch.int64, device="cuda", generator=g)
+    wsk = torch.empty(cq.cq_kmeans_workspace_bytes(fmt, n_cal), dtype=torch.uint8, device="cuda")
+    init_ms, _ = time_calls(torch, lambda: cq.cq_kmeans_fit(xcal, fmt, 0, rnd=rnd, workspace=wsk), 3, 1)
+    fit_ms, _ = time_calls(torch, lambda: cq.cq_kmeans_fit(xcal, fmt, iters, rnd=rnd, workspace=wsk), 3, 1)
+    out["centroid_learning"] = {
+        "workload": "CQ-8c8b, 32768 calibration tokens x 4096 channels, one tensor: k-means++ then 100 Lloyd "
+                    "iterations in each of 512 groups (cq_kmeans_fit)",
+        "ms": fit_ms, "kmeanspp_ms": init_ms, "ms_per_iteration": (fit_ms - init_ms) / iters,
+        "seconds_for_64_tensors": fit_ms * 64 / 1e3}
     return out
 
 
