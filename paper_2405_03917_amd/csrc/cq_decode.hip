@@ -399,12 +399,30 @@ __global__ __launch_bounds__(NT, 4) void decode_split_kernel(DecodeArgs a)
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
 
-    int idx = blockIdx.x;
-    const int hq = idx % a.n_q_heads;
-    idx /= a.n_q_heads;
-    const int split = idx % a.n_split;
-    const int n = idx / a.n_split;
-    const int hkv = hq / (a.n_q_heads / a.f.n_kv_heads);
+    // Workgroup -> (sequence, split, query head).  Consecutive workgroups go to consecutive XCDs
+    // (8 of them, each with its own L2), so the KV head is made a function of blockIdx % 8 where
+    // the head count allows: every workgroup that reads a head's codebooks and code streams then
+    // shares one L2 (with grouped queries that is 4 query heads x splits x sequences per head).
+    const int qper = a.n_q_heads / a.f.n_kv_heads;
+    int hq, split, n;
+    if (a.f.n_kv_heads % 8 == 0) {
+        const int xcd = blockIdx.x & 7;
+        int r = blockIdx.x >> 3;
+        const int per_xcd = a.f.n_kv_heads >> 3;
+        const int hkv_ = xcd + 8 * (r % per_xcd);
+        r /= per_xcd;
+        hq = hkv_ * qper + r % qper;
+        r /= qper;
+        split = r % a.n_split;
+        n = r / a.n_split;
+    } else {
+        int idx = blockIdx.x;
+        hq = idx % a.n_q_heads;
+        idx /= a.n_q_heads;
+        split = idx % a.n_split;
+        n = idx / a.n_split;
+    }
+    const int hkv = hq / qper;
 
     int t_n = a.t;
     if (a.seq_lens) t_n = min(max(a.seq_lens[n], 1), a.t);
