@@ -357,3 +357,58 @@ def test_decode_step_ragged_lengths():
     torch.cuda.synchronize()
     assert torch.equal(k1, k2) and torch.equal(v1, v2)
     assert torch.equal(ref.view(torch.int16), out.view(torch.int16))
+
+
+# ------------------------------------------------------------------------------------------
+# seeded sweep over shapes
+# ------------------------------------------------------------------------------------------
+def _sweep_cases():
+    rng = np.random.default_rng(20240503)
+    cases = []
+    for i in range(24):
+        c, b = FORMATS[i % 4]
+        hkv = int(rng.choice([1, 2, 3, 8]))
+        qper = int(rng.choice([1, 2, 4]))
+        B = int(rng.integers(1, 4))
+        T = int(rng.choice([1, 2, 64, 127, 128, 129, 500, 1337, 2049]))
+        tiles = -(-T // 64)
+        max_split_tiles = 126 if b == 10 else (128 if c >= 4 else 256)
+        split_tiles = int(rng.integers(1, min(tiles, max_split_tiles) + 1)) if rng.random() < 0.6 else 0
+        ragged = bool(rng.random() < 0.5)
+        cases.append((i, c, b, hkv * qper, hkv, B, T, split_tiles * 64, ragged))
+    return cases
+
+
+@pytest.mark.parametrize("case", _sweep_cases(), ids=lambda cs: "case%d-%dc%db-hq%d-hkv%d-B%d-T%d-split%d-%s" % (
+    cs[0], cs[1], cs[2], cs[3], cs[4], cs[5], cs[6], cs[7], "ragged" if cs[8] else "full"))
+def test_decode_and_fused_step_sweep(case):
+    i, c, b, hq, hkv, B, T, split, ragged = case
+    rng = np.random.default_rng(1000 + i)
+    t_cap = 64 * (-(-T // 64) + int(rng.integers(0, 3)))
+    fmt, q, kc, vc, ck, cv = _attn_case(100 + i, c, b, hq, hkv, B, T)
+    lens = rng.integers(1, T + 1, size=B).astype(np.int32) if ragged else np.full(B, T, np.int32)
+    lens[int(rng.integers(0, B))] = T
+    scale = float(rng.uniform(0.03, 0.2))
+    sl = dev(lens) if ragged else None
+    kcache, vcache = codes_to_cache(kc, fmt, t_cap), codes_to_cache(vc, fmt, t_cap)
+    ref = O.attention(q, kc, vc, ck, cv, scale, hkv, seq_lens=lens)
+    out = gpu_attention(q, kcache, vcache, ck, cv, scale, fmt, T, t_cap, seq_lens=lens if ragged else None,
+                        tokens_per_split=split)
+    check_attention(out, ref)
+    # fused step on the same caches: the token at position lens[n] - 1 is replaced by a freshly encoded one
+    D = hkv * 128
+    rk, rv = synth.tensor_recipe(20 + 100 + i, 0, "k", D), synth.tensor_recipe(20 + 100 + i, 0, "v", D)
+    xk = np.stack([synth.sample_activations(rk, 1, chunk=50 + n)[0] for n in range(B)])
+    xv = np.stack([synth.sample_activations(rv, 1, chunk=50 + n)[0] for n in range(B)])
+    out2 = cq.cq_decode_step(dev(q), dev(xk), dev(xv), kcache, vcache, dev(ck), dev(cv), scale, fmt, T, t_cap,
+                             seq_lens=sl, tokens_per_split=split)
+    torch.cuda.synchronize()
+    kc2 = cache_to_codes(kcache, fmt, B, t_cap, T)
+    vc2 = cache_to_codes(vcache, fmt, B, t_cap, T)
+    for n in range(B):
+        p = int(lens[n]) - 1
+        keep = np.arange(T) != p
+        assert np.array_equal(kc2[n, keep], kc[n, keep]) and np.array_equal(vc2[n, keep], vc[n, keep])
+        check_codes(kc2[n, p:p + 1], xk[n:n + 1], ck)
+        check_codes(vc2[n, p:p + 1], xv[n:n + 1], cv)
+    check_attention(out2.cpu().numpy(), O.attention(q, kc2, vc2, ck, cv, scale, hkv, seq_lens=lens))
