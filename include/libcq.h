@@ -191,6 +191,22 @@ CQ_API cq_status cq_decode_step(const void *q, const void *x_k_new, const void *
                          void *stream);
 
 /*
+ * cq_dequantize -- the inverse lookup ("dequantization", Section 2.2; CQ(A) of Eq. 5 as values):
+ * out[n][t][g c + i] = centroids[g][code(n, t_offset + t, g)][i] for t = 0 .. t_count - 1, bit
+ * for bit the stored fp16 centroids.  For callers that need dense keys / values (e.g. a
+ * multi-query attention over a coded cache).
+ *
+ *   codes           device, packed cache (cq_cache_bytes(fmt, batch, t_cap) bytes)
+ *   centroids       device, fp16 [G][2^b][c]
+ *   out             device, fp16 [batch][t_count][D]; element strides out_batch_stride and
+ *                   out_row_stride (>= D, multiples of 8)
+ * Errors: as cq_encode.
+ */
+CQ_API cq_status cq_dequantize(const void *codes, const void *centroids, const cq_format *fmt,
+                        int32_t batch, int32_t t_offset, int32_t t_count, int32_t t_cap,
+                        void *out, int64_t out_batch_stride, int64_t out_row_stride, void *stream);
+
+/*
  * Centroid learning (Section 3.2 of the paper, "Centroid Learning"): for every channel group an
  * independent k-means run over the tokens of a calibration tensor -- Eq. 5; with `weights`,
  * the weighted objective of Eq. 6 (weighted k-means; the caller supplies the weight of each

@@ -26,7 +26,7 @@ TILE_TOKENS = 64
 EXPORTS = (
     "cq_version", "cq_status_string", "cq_format_check", "cq_code_bytes_per_token_head",
     "cq_cache_bytes", "cq_encode", "cq_encode_kv", "cq_decode_default_split", "cq_decode_workspace_bytes",
-    "cq_decode_attention", "cq_decode_step", "cq_kmeans_workspace_bytes", "cq_kmeans_fit",
+    "cq_decode_attention", "cq_decode_step", "cq_dequantize", "cq_kmeans_workspace_bytes", "cq_kmeans_fit",
     "cq_probe_stream_read", "cq_probe_copy", "cq_probe_mfma",
 )
 
@@ -105,6 +105,8 @@ def load() -> ctypes.CDLL:
                                    vp, i32, vp, vp, ctypes.c_size_t, vp]
     lib.cq_probe_stream_read.restype = ctypes.c_int
     lib.cq_probe_stream_read.argtypes = [vp, ctypes.c_size_t, vp, vp]
+    lib.cq_dequantize.restype = ctypes.c_int
+    lib.cq_dequantize.argtypes = [vp, vp, fp, i32, i32, i32, i32, vp, i64, i64, vp]
     lib.cq_kmeans_workspace_bytes.restype = ctypes.c_size_t
     lib.cq_kmeans_workspace_bytes.argtypes = [fp, i32]
     lib.cq_kmeans_fit.restype = ctypes.c_int
@@ -361,6 +363,26 @@ def cq_probe_copy(src, dst, stream=None) -> None:
     st = load().cq_probe_copy(src.data_ptr(), dst.data_ptr(), src.numel(), _stream_handle(stream))
     if st != CQ_OK:
         raise CQError(st, "cq_probe_copy")
+
+
+def cq_dequantize(codes, centroids, fmt: CQFormat, batch: int, t_offset: int, t_count: int, t_cap: int, out=None,
+                  stream=None):
+    """fp16 [batch, t_count, D] = the centroids the cached codes of positions t_offset .. t_offset +
+    t_count - 1 select (out may be a strided view with unit channel stride)."""
+    import torch
+    _dev(codes, torch.uint8, "codes")
+    _dev(centroids, torch.float16, "centroids")
+    D = fmt.channels
+    if out is None:
+        out = torch.empty((batch, t_count, D), dtype=torch.float16, device=codes.device)
+    _dev(out, torch.float16, "out")
+    if tuple(out.shape) != (batch, t_count, D) or out.stride(2) != 1:
+        raise ValueError("out must be [batch, t_count, D] with unit channel stride")
+    st = load().cq_dequantize(codes.data_ptr(), centroids.data_ptr(), ctypes.byref(fmt._c()), batch, t_offset, t_count,
+                              t_cap, out.data_ptr(), out.stride(0), out.stride(1), _stream_handle(stream))
+    if st != CQ_OK:
+        raise CQError(st, "cq_dequantize")
+    return out
 
 
 KMEANS_MAX_POINTS = 524288

@@ -165,6 +165,31 @@ cq_status cq_encode_kv(const void* x_k, const void* x_v, int64_t x_batch_stride,
     return launch_encode(a, static_cast<hipStream_t>(stream));
 }
 
+cq_status cq_dequantize(const void* codes, const void* centroids, const cq_format* fmt,
+                        int32_t batch, int32_t t_offset, int32_t t_count, int32_t t_cap,
+                        void* out, int64_t out_batch_stride, int64_t out_row_stride, void* stream)
+{
+    Derived f;
+    cq_status st = derive(fmt, &f);
+    if (st != CQ_OK) return st;
+    if ((st = check_encode_shape(f, batch, t_count, t_offset, t_cap)) != CQ_OK) return st;
+    if (!codes || !centroids || !out || !aligned16(codes) || !aligned16(centroids) || !aligned16(out)) return CQ_ERR_INVALID_ARG;
+    if (out_row_stride < f.channels || out_row_stride % 8 != 0) return CQ_ERR_INVALID_ARG;
+    if (batch > 1 && (out_batch_stride < (int64_t)t_count * out_row_stride || out_batch_stride % 8 != 0)) return CQ_ERR_INVALID_ARG;
+    DequantArgs a;
+    a.codes = static_cast<const uint8_t*>(codes);
+    a.centroids = static_cast<const uint16_t*>(centroids);
+    a.out = static_cast<uint16_t*>(out);
+    a.out_batch_stride = out_batch_stride;
+    a.out_row_stride = out_row_stride;
+    a.batch = batch;
+    a.t_offset = t_offset;
+    a.t_count = t_count;
+    a.t_cap = t_cap;
+    a.f = f;
+    return launch_dequantize(a, static_cast<hipStream_t>(stream));
+}
+
 size_t cq_kmeans_workspace_bytes(const cq_format* fmt, int32_t n_points)
 {
     Derived f;

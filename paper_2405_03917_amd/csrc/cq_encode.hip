@@ -131,6 +131,65 @@ cq_status launch_format(const EncodeArgs& a, hipStream_t stream)
     return CQ_OK;
 }
 
+// ------------------------------------------------------------------------------------------
+// dequantize: code -> centroid (the inverse lookup of Section 2.2 / "CQ(A)" of Eq. 5)
+// ------------------------------------------------------------------------------------------
+// One workgroup = one 64-token tile of one (sequence, KV head): the tile's bytes go through LDS
+// (one coalesced read), then every thread writes 16-byte pieces of the fp16 rows: piece q of
+// token u covers channels 8 q .. 8 q + 7 of the head, i.e. 8 / C consecutive groups.
+template <int GH, int C, int B>
+__global__ __launch_bounds__(256) void dequantize_kernel(DequantArgs a)
+{
+    constexpr int K = 1 << B;
+    constexpr int TILE_LOW = kTileTokens * GH;
+    constexpr int TILE_BYTES = kTileTokens * GH * B / 8;
+    constexpr int GPP = 8 / C;                      // groups per 16-byte piece
+    constexpr int PIECES = GH * C / 8;              // pieces per token-head
+    __shared__ __attribute__((aligned(16))) uint8_t tb[TILE_BYTES];
+
+    const int tid = threadIdx.x;
+    const int first_tile = a.t_offset / kTileTokens;
+    const int tile = first_tile + blockIdx.x, hkv = blockIdx.y, n = blockIdx.z;
+    const uint8_t* src = a.codes + ((size_t)(n * a.f.n_kv_heads + hkv) * (a.t_cap / kTileTokens) + tile) * TILE_BYTES;
+    for (int i = tid; i < TILE_BYTES / 16; i += 256)
+        reinterpret_cast<uint4*>(tb)[i] = reinterpret_cast<const uint4*>(src)[i];
+    __syncthreads();
+
+    const int t_end = a.t_offset + a.t_count;
+    for (int e = tid; e < kTileTokens * PIECES; e += 256) {
+        const int u = e / PIECES, q = e % PIECES;
+        const int pos = tile * kTileTokens + u;
+        if (pos < a.t_offset || pos >= t_end) continue;
+        unsigned w[4];
+#pragma unroll
+        for (int k = 0; k < GPP; ++k) {
+            const int g = q * GPP + k;
+            const int slot = (g - u) & (GH - 1);
+            unsigned code = tb[(slot >> 4) * 1024 + u * 16 + (slot & 15)];
+            if constexpr (B == 10) {
+                const unsigned hi = *reinterpret_cast<const unsigned*>(tb + TILE_LOW + u * 4);
+                code |= ((hi >> (2 * slot)) & 3u) << 8;
+            }
+            const uint16_t* cen = a.centroids + ((size_t)(hkv * GH + g) * K + code) * C;
+#pragma unroll
+            for (int i = 0; i < C / 2; ++i) w[k * (C / 2) + i] = *reinterpret_cast<const unsigned*>(cen + 2 * i);
+        }
+        uint16_t* dst = a.out + (size_t)n * a.out_batch_stride + (size_t)(pos - a.t_offset) * a.out_row_stride +
+                        (size_t)hkv * GH * C + q * 8;
+        *reinterpret_cast<uint4*>(dst) = make_uint4(w[0], w[1], w[2], w[3]);
+    }
+}
+
+template <int GH, int C, int B>
+cq_status launch_dequant_format(const DequantArgs& a, hipStream_t stream)
+{
+    const int first_tile = a.t_offset / kTileTokens;
+    const int last_tile = (a.t_offset + a.t_count - 1) / kTileTokens;
+    dim3 grid((unsigned)(last_tile - first_tile + 1), (unsigned)a.f.n_kv_heads, (unsigned)a.batch);
+    hipLaunchKernelGGL((dequantize_kernel<GH, C, B>), grid, dim3(256), 0, stream, a);
+    return hipGetLastError() == hipSuccess ? CQ_OK : CQ_ERR_HIP;
+}
+
 }  // namespace
 
 cq_status launch_encode(const EncodeArgs& a, hipStream_t stream)
@@ -141,6 +200,18 @@ cq_status launch_encode(const EncodeArgs& a, hipStream_t stream)
         if (a.f.gh == 64 && a.f.c == 2) return launch_format<64, 2, 8>(a, stream);
     } else if (a.f.b == 10) {
         if (a.f.gh == 16 && a.f.c == 8) return launch_format<16, 8, 10>(a, stream);
+    }
+    return CQ_ERR_UNSUPPORTED;
+}
+
+cq_status launch_dequantize(const DequantArgs& a, hipStream_t stream)
+{
+    if (a.f.b == 8) {
+        if (a.f.gh == 16 && a.f.c == 8) return launch_dequant_format<16, 8, 8>(a, stream);
+        if (a.f.gh == 32 && a.f.c == 4) return launch_dequant_format<32, 4, 8>(a, stream);
+        if (a.f.gh == 64 && a.f.c == 2) return launch_dequant_format<64, 2, 8>(a, stream);
+    } else if (a.f.b == 10) {
+        if (a.f.gh == 16 && a.f.c == 8) return launch_dequant_format<16, 8, 10>(a, stream);
     }
     return CQ_ERR_UNSUPPORTED;
 }

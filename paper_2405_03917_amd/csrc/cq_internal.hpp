@@ -64,6 +64,16 @@ struct DecodeArgs {
 // Largest tokens_per_split the decode kernel's on-chip score buffer can hold.
 int decode_max_tiles_per_split(const Derived& f);
 
+struct DequantArgs {
+    const uint8_t* codes;
+    const uint16_t* centroids;
+    uint16_t* out;            // fp16 [batch][t_count][D]
+    int64_t out_batch_stride, out_row_stride;
+    int batch, t_offset, t_count, t_cap;
+    Derived f;
+};
+cq_status launch_dequantize(const DequantArgs& a, hipStream_t stream);
+
 // Centroid learning: k-means++ (do_init) or given starting centroids, then n_iter Lloyd iterations.
 struct KMeansArgs {
     const uint16_t* x;        // fp16 [n][D]

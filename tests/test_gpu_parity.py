@@ -170,6 +170,43 @@ def test_encode_wide_dynamic_range_and_near_ties(c, b):
     check_codes(codes, xh[0], cbh)
 
 
+@pytest.mark.parametrize("c,b", FORMATS)
+def test_dequantize_returns_the_stored_centroids_bit_for_bit(c, b):
+    hkv, B, T, t_cap = 2, 2, 200, 256
+    fmt = cq.CQFormat(c, b, 128, hkv)
+    rng = np.random.default_rng(c + b)
+    K, G, D = 1 << b, fmt.groups, hkv * 128
+    codes = rng.integers(0, K, size=(B, T, G)).astype(np.uint16)
+    codes[0, 0] = 0
+    codes[0, 1] = K - 1
+    cb = synth.sample_codebook(synth.tensor_recipe(31, 0, "v", D), c, b)
+    cache = codes_to_cache(codes, fmt, t_cap)
+    for t0, cnt in ((0, T), (37, 101), (64, 64), (199, 1)):
+        want = np.stack([O.dequantize(codes[n, t0:t0 + cnt], cb) for n in range(B)]).astype(np.float16)
+        got = cq.cq_dequantize(cache, dev(cb), fmt, B, t0, cnt, t_cap)
+        torch.cuda.synchronize()
+        assert np.array_equal(got.cpu().numpy().view(np.uint16), want.view(np.uint16))
+    # strided output rows, untouched padding
+    wide = torch.full((B, T, D + 64), 7.0, dtype=torch.float16, device="cuda")
+    cq.cq_dequantize(cache, dev(cb), fmt, B, 0, T, t_cap, out=wide[:, :, :D])
+    torch.cuda.synchronize()
+    want = np.stack([O.dequantize(codes[n], cb) for n in range(B)]).astype(np.float16)
+    assert np.array_equal(wide[:, :, :D].cpu().numpy(), want) and bool((wide[:, :, D:] == 7.0).all())
+
+
+def test_encode_then_dequantize_is_the_nearest_centroid_reconstruction():
+    c, b, hkv, T = 4, 8, 2, 300
+    fmt = cq.CQFormat(c, b, 128, hkv)
+    x, cb = _inputs(33, c, b, hkv, 1, T)
+    cache = gpu_encode(x, cb, fmt, 320, 0)
+    rec = cq.cq_dequantize(cache, dev(cb), fmt, 1, 0, T, 320).cpu().numpy()[0].astype(np.float64)
+    codes = cache_to_codes(cache, fmt, 1, 320, T, 0)[0]
+    assert np.array_equal(rec, O.dequantize(codes, cb))
+    # Eq. 5's error of the reconstruction equals the sum of the minimal distances (up to the near ties)
+    _, d1, _ = O.encode(x[0], cb, with_distances=True)
+    assert ((x[0].astype(np.float64) - rec) ** 2).sum() == pytest.approx(d1.sum(), rel=1e-6)
+
+
 # ------------------------------------------------------------------------------------------
 # decode attention
 # ------------------------------------------------------------------------------------------

@@ -173,3 +173,19 @@ def test_kmeans_sizes_and_argument_checks_without_launching():
     assert fit(x=0x10002) == cq.CQ_ERR_INVALID_ARG
     assert fit(ws=None) == cq.CQ_ERR_INVALID_ARG
     assert fit(ws_bytes=need - 1) == cq.CQ_ERR_WORKSPACE_TOO_SMALL
+
+
+def test_dequantize_argument_checks_without_launching():
+    lib = cq.load()
+    f = cq.CQFormat(8, 8, 128, 2)._c()
+
+    def deq(codes=0x10000, cen=0x20000, batch=2, t0=0, cnt=100, t_cap=128, out=0x30000, bs=100 * 256, rs=256):
+        p = lambda v: None if v is None else _fake(v)
+        return int(lib.cq_dequantize(p(codes), p(cen), ctypes.byref(f), batch, t0, cnt, t_cap, p(out), bs, rs, None))
+
+    assert deq(codes=None) == cq.CQ_ERR_INVALID_ARG and deq(out=None) == cq.CQ_ERR_INVALID_ARG
+    assert deq(t0=30, cnt=100) == cq.CQ_ERR_INVALID_ARG              # runs past t_cap
+    assert deq(t_cap=100) == cq.CQ_ERR_INVALID_ARG
+    assert deq(rs=255) == cq.CQ_ERR_INVALID_ARG and deq(rs=260) == cq.CQ_ERR_INVALID_ARG
+    assert deq(bs=99 * 256) == cq.CQ_ERR_INVALID_ARG
+    assert deq(out=0x30008) == cq.CQ_ERR_INVALID_ARG
