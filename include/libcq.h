@@ -191,6 +191,44 @@ CQ_API cq_status cq_decode_step(const void *q, const void *x_k_new, const void *
                          void *stream);
 
 /*
+ * Paged caches.  Instead of t_cap contiguous positions per sequence, the codes live in a pool
+ * of pages; a page is the 64-token tile of EVERY KV head ([n_kv_heads][tile bytes], tile bytes =
+ * 64 * cq_code_bytes_per_token_head), and a block table names the page of each tile of each
+ * sequence: block_table[n * row_stride + i] = page of tokens 64 i .. 64 i + 63 of sequence n, for
+ * i < max_tiles (device memory, int32; the K pool and the V pool share the table).  Entries are
+ * clamped to [0, n_pages) by the kernels.  The *_paged calls take the same arguments as their
+ * contiguous namesakes with (pool, cq_page_table) in the place of (cache, t_cap); capacity is
+ * max_tiles * 64 tokens per sequence; results are identical to the contiguous calls on the same
+ * logical contents.
+ */
+typedef struct cq_page_table {
+    int32_t n_pages;               /* pages in each pool */
+    int32_t max_tiles;             /* valid entries per sequence */
+    int64_t row_stride;            /* entries between sequences (>= max_tiles) */
+    const int32_t *block_table;    /* device */
+} cq_page_table;
+
+/* Bytes of one pool (K or V of one layer) of n_pages pages.  0 on bad arguments. */
+CQ_API size_t cq_paged_cache_bytes(const cq_format *fmt, int32_t n_pages);
+CQ_API cq_status cq_encode_kv_paged(const void *x_k, const void *x_v, int64_t x_batch_stride, int64_t x_row_stride,
+                             const void *k_centroids, const void *v_centroids, const cq_format *fmt,
+                             int32_t batch, int32_t t_new,
+                             void *k_pool, void *v_pool, const cq_page_table *pages, int32_t t_offset, void *stream);
+CQ_API cq_status cq_decode_attention_paged(const void *q, const void *k_pool, const void *v_pool,
+                                    const void *k_centroids, const void *v_centroids,
+                                    float scale, const cq_format *fmt,
+                                    int32_t batch, int32_t n_q_heads, int32_t t, const cq_page_table *pages,
+                                    const int32_t *seq_lens, int32_t tokens_per_split,
+                                    void *out, void *workspace, size_t workspace_bytes, void *stream);
+CQ_API cq_status cq_decode_step_paged(const void *q, const void *x_k_new, const void *x_v_new, int64_t x_row_stride,
+                               void *k_pool, void *v_pool,
+                               const void *k_centroids, const void *v_centroids,
+                               float scale, const cq_format *fmt,
+                               int32_t batch, int32_t n_q_heads, int32_t t, const cq_page_table *pages,
+                               const int32_t *seq_lens, int32_t tokens_per_split,
+                               void *out, void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * cq_dequantize -- the inverse lookup ("dequantization", Section 2.2; CQ(A) of Eq. 5 as values):
  * out[n][t][g c + i] = centroids[g][code(n, t_offset + t, g)][i] for t = 0 .. t_count - 1, bit
  * for bit the stored fp16 centroids.  For callers that need dense keys / values (e.g. a

@@ -26,7 +26,8 @@ TILE_TOKENS = 64
 EXPORTS = (
     "cq_version", "cq_status_string", "cq_format_check", "cq_code_bytes_per_token_head",
     "cq_cache_bytes", "cq_encode", "cq_encode_kv", "cq_decode_default_split", "cq_decode_workspace_bytes",
-    "cq_decode_attention", "cq_decode_step", "cq_dequantize", "cq_kmeans_workspace_bytes", "cq_kmeans_fit",
+    "cq_decode_attention", "cq_decode_step", "cq_dequantize", "cq_paged_cache_bytes", "cq_encode_kv_paged",
+    "cq_decode_attention_paged", "cq_decode_step_paged", "cq_kmeans_workspace_bytes", "cq_kmeans_fit",
     "cq_probe_stream_read", "cq_probe_copy", "cq_probe_mfma",
 )
 
@@ -40,6 +41,11 @@ class CQError(RuntimeError):
 class _Format(ctypes.Structure):
     _fields_ = [("c", ctypes.c_int32), ("b", ctypes.c_int32),
                 ("head_dim", ctypes.c_int32), ("n_kv_heads", ctypes.c_int32)]
+
+
+class _PageTable(ctypes.Structure):
+    _fields_ = [("n_pages", ctypes.c_int32), ("max_tiles", ctypes.c_int32), ("row_stride", ctypes.c_int64),
+                ("block_table", ctypes.c_void_p)]
 
 
 @dataclass(frozen=True)
@@ -105,6 +111,17 @@ def load() -> ctypes.CDLL:
                                    vp, i32, vp, vp, ctypes.c_size_t, vp]
     lib.cq_probe_stream_read.restype = ctypes.c_int
     lib.cq_probe_stream_read.argtypes = [vp, ctypes.c_size_t, vp, vp]
+    pp = ctypes.POINTER(_PageTable)
+    lib.cq_paged_cache_bytes.restype = ctypes.c_size_t
+    lib.cq_paged_cache_bytes.argtypes = [fp, i32]
+    lib.cq_encode_kv_paged.restype = ctypes.c_int
+    lib.cq_encode_kv_paged.argtypes = [vp, vp, i64, i64, vp, vp, fp, i32, i32, vp, vp, pp, i32, vp]
+    lib.cq_decode_attention_paged.restype = ctypes.c_int
+    lib.cq_decode_attention_paged.argtypes = [vp, vp, vp, vp, vp, ctypes.c_float, fp, i32, i32, i32, pp, vp, i32, vp, vp,
+                                              ctypes.c_size_t, vp]
+    lib.cq_decode_step_paged.restype = ctypes.c_int
+    lib.cq_decode_step_paged.argtypes = [vp, vp, vp, i64, vp, vp, vp, vp, ctypes.c_float, fp, i32, i32, i32, pp, vp, i32,
+                                         vp, vp, ctypes.c_size_t, vp]
     lib.cq_dequantize.restype = ctypes.c_int
     lib.cq_dequantize.argtypes = [vp, vp, fp, i32, i32, i32, i32, vp, i64, i64, vp]
     lib.cq_kmeans_workspace_bytes.restype = ctypes.c_size_t
@@ -363,6 +380,112 @@ def cq_probe_copy(src, dst, stream=None) -> None:
     st = load().cq_probe_copy(src.data_ptr(), dst.data_ptr(), src.numel(), _stream_handle(stream))
     if st != CQ_OK:
         raise CQError(st, "cq_probe_copy")
+
+
+class PageTable:
+    """A paged cache's block table: int32 device tensor [batch, max_tiles] (page of each 64-token
+    tile of each sequence) over pools of n_pages pages."""
+
+    def __init__(self, block_table, n_pages: int):
+        import torch
+        _dev(block_table, torch.int32, "block_table")
+        if block_table.dim() != 2 or block_table.stride(1) != 1:
+            raise ValueError("block_table must be [batch, max_tiles] with unit stride along tiles")
+        self.block_table = block_table
+        self.n_pages = int(n_pages)
+        self._c = _PageTable(self.n_pages, int(block_table.shape[1]), int(block_table.stride(0)), block_table.data_ptr())
+
+    @property
+    def max_tiles(self) -> int:
+        return int(self.block_table.shape[1])
+
+
+def cq_paged_cache_bytes(fmt: CQFormat, n_pages: int) -> int:
+    n = load().cq_paged_cache_bytes(ctypes.byref(fmt._c()), n_pages)
+    if n == 0:
+        raise CQError(CQ_ERR_INVALID_ARG, "cq_paged_cache_bytes")
+    return n
+
+
+def cq_encode_kv_paged(x_k, x_v, k_centroids, v_centroids, fmt: CQFormat, k_pool, v_pool, pages: PageTable,
+                       t_offset: int, stream=None) -> None:
+    """cq_encode_kv into paged pools: x fp16 [B, T_new, D]; tokens go to positions t_offset ... of
+    each sequence, i.e. to the pages pages.block_table names."""
+    import torch
+    for name, x in (("x_k", x_k), ("x_v", x_v)):
+        _dev(x, torch.float16, name)
+        if x.dim() != 3 or x.stride(2) != 1 or x.shape[2] != fmt.channels:
+            raise ValueError(f"{name} must be [B, T_new, D] with unit channel stride")
+    if x_k.shape != x_v.shape or x_k.stride() != x_v.stride():
+        raise ValueError("x_k and x_v must have the same shape and strides")
+    need = cq_paged_cache_bytes(fmt, pages.n_pages)
+    for name, t in (("k_pool", k_pool), ("v_pool", v_pool)):
+        _dev(t, torch.uint8, name)
+        if t.numel() < need:
+            raise ValueError(f"{name} is smaller than cq_paged_cache_bytes(fmt, n_pages)")
+    st = load().cq_encode_kv_paged(x_k.data_ptr(), x_v.data_ptr(), x_k.stride(0), x_k.stride(1), k_centroids.data_ptr(),
+                                   v_centroids.data_ptr(), ctypes.byref(fmt._c()), int(x_k.shape[0]), int(x_k.shape[1]),
+                                   k_pool.data_ptr(), v_pool.data_ptr(), ctypes.byref(pages._c), t_offset,
+                                   _stream_handle(stream))
+    if st != CQ_OK:
+        raise CQError(st, "cq_encode_kv_paged")
+
+
+def _paged_decode(fn_name, q, x_k_new, x_v_new, k_pool, v_pool, k_centroids, v_centroids, scale, fmt, t, pages, seq_lens,
+                  tokens_per_split, out, workspace, stream):
+    import torch
+    _dev(q, torch.float16, "q")
+    if q.dim() != 3 or not q.is_contiguous() or q.shape[2] != fmt.head_dim:
+        raise ValueError("q must be contiguous [B, Hq, head_dim]")
+    batch, n_q_heads = int(q.shape[0]), int(q.shape[1])
+    need = cq_paged_cache_bytes(fmt, pages.n_pages)
+    for name, p in (("k_pool", k_pool), ("v_pool", v_pool)):
+        _dev(p, torch.uint8, name)
+        if p.numel() < need:
+            raise ValueError(f"{name} is smaller than cq_paged_cache_bytes(fmt, n_pages)")
+    if pages.block_table.shape[0] < batch:
+        raise ValueError("block table has fewer rows than the batch")
+    sl_ptr = None
+    if seq_lens is not None:
+        _dev(seq_lens, torch.int32, "seq_lens")
+        sl_ptr = seq_lens.data_ptr()
+    if out is None:
+        out = torch.empty((batch, n_q_heads, fmt.head_dim), dtype=torch.float16, device=q.device)
+    if workspace is None:
+        workspace = torch.empty(max(16, cq_decode_workspace_bytes(fmt, batch, n_q_heads, t, tokens_per_split)),
+                                dtype=torch.uint8, device=q.device)
+    common = (k_pool.data_ptr(), v_pool.data_ptr(), k_centroids.data_ptr(), v_centroids.data_ptr(), float(scale),
+              ctypes.byref(fmt._c()), batch, n_q_heads, t, ctypes.byref(pages._c), sl_ptr, tokens_per_split,
+              out.data_ptr(), workspace.data_ptr(), workspace.numel(), _stream_handle(stream))
+    if x_k_new is None:
+        st = load().cq_decode_attention_paged(q.data_ptr(), *common)
+    else:
+        for name, x in (("x_k_new", x_k_new), ("x_v_new", x_v_new)):
+            _dev(x, torch.float16, name)
+            if tuple(x.shape) != (batch, fmt.channels) or x.stride(1) != 1:
+                raise ValueError(f"{name} must be [B, D] with unit channel stride")
+        if x_k_new.stride(0) != x_v_new.stride(0):
+            raise ValueError("x_k_new and x_v_new must share their row stride")
+        st = load().cq_decode_step_paged(q.data_ptr(), x_k_new.data_ptr(), x_v_new.data_ptr(), x_k_new.stride(0), *common)
+    if st != CQ_OK:
+        raise CQError(st, fn_name)
+    return out
+
+
+def cq_decode_attention_paged(q, k_pool, v_pool, k_centroids, v_centroids, scale: float, fmt: CQFormat, t: int,
+                              pages: PageTable, seq_lens=None, tokens_per_split: int = 0, out=None, workspace=None,
+                              stream=None):
+    """cq_decode_attention over paged pools."""
+    return _paged_decode("cq_decode_attention_paged", q, None, None, k_pool, v_pool, k_centroids, v_centroids, scale, fmt,
+                         t, pages, seq_lens, tokens_per_split, out, workspace, stream)
+
+
+def cq_decode_step_paged(q, x_k_new, x_v_new, k_pool, v_pool, k_centroids, v_centroids, scale: float, fmt: CQFormat,
+                         t: int, pages: PageTable, seq_lens=None, tokens_per_split: int = 0, out=None, workspace=None,
+                         stream=None):
+    """cq_decode_step over paged pools (the new token's codes go to the page of position t - 1)."""
+    return _paged_decode("cq_decode_step_paged", q, x_k_new, x_v_new, k_pool, v_pool, k_centroids, v_centroids, scale,
+                         fmt, t, pages, seq_lens, tokens_per_split, out, workspace, stream)
 
 
 def cq_dequantize(codes, centroids, fmt: CQFormat, batch: int, t_offset: int, t_count: int, t_cap: int, out=None,

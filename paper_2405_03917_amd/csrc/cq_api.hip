@@ -104,6 +104,22 @@ cq_status check_encode_tensor(const Derived& f, const void* x, int64_t x_batch_s
     return CQ_OK;
 }
 
+CacheMap contiguous_map(const Derived& f, int32_t t_cap)
+{
+    return CacheMap{nullptr, 0, 0, t_cap / kTileTokens, f.n_kv_heads};
+}
+
+// Checks a page table and turns it into the kernels' map; *t_cap receives the token capacity.
+cq_status paged_map(const Derived& f, const cq_page_table* pt, int32_t batch, CacheMap* map, int32_t* t_cap)
+{
+    if (!pt || !pt->block_table || pt->n_pages <= 0 || pt->max_tiles <= 0 || pt->max_tiles > (1 << 24)) return CQ_ERR_INVALID_ARG;
+    if (pt->row_stride < pt->max_tiles || (reinterpret_cast<uintptr_t>(pt->block_table) & 3u)) return CQ_ERR_INVALID_ARG;
+    (void)batch;
+    *map = CacheMap{pt->block_table, pt->row_stride, pt->n_pages, 0, f.n_kv_heads};
+    *t_cap = pt->max_tiles * kTileTokens;
+    return CQ_OK;
+}
+
 cq_status check_encode_shape(const Derived& f, int32_t batch, int32_t t_new, int32_t t_offset, int32_t t_cap)
 {
     if (batch <= 0 || t_new <= 0 || t_cap <= 0 || t_cap % kTileTokens != 0) return CQ_ERR_INVALID_ARG;
@@ -114,28 +130,49 @@ cq_status check_encode_shape(const Derived& f, int32_t batch, int32_t t_new, int
 
 }  // namespace
 
+namespace {
+
+cq_status encode_common(const void* x_k, const void* x_v, int64_t x_batch_stride, int64_t x_row_stride,
+                        const void* k_centroids, const void* v_centroids, const Derived& f,
+                        int32_t batch, int32_t t_new, void* k_codes, void* v_codes, int32_t t_offset, int32_t t_cap,
+                        const CacheMap& map, void* stream)
+{
+    cq_status st;
+    if ((st = check_encode_shape(f, batch, t_new, t_offset, t_cap)) != CQ_OK) return st;
+    if ((st = check_encode_tensor(f, x_k, x_batch_stride, x_row_stride, k_centroids, k_codes, batch, t_new)) != CQ_OK) return st;
+    const bool two = x_v != nullptr || v_centroids != nullptr || v_codes != nullptr;
+    if (two) {
+        if ((st = check_encode_tensor(f, x_v, x_batch_stride, x_row_stride, v_centroids, v_codes, batch, t_new)) != CQ_OK) return st;
+        if (k_codes == v_codes) return CQ_ERR_INVALID_ARG;
+    }
+    EncodeArgs a;
+    a.tensor[0] = EncodeTensor{static_cast<const uint16_t*>(x_k), x_batch_stride, x_row_stride,
+                               static_cast<const uint16_t*>(k_centroids), static_cast<uint8_t*>(k_codes)};
+    a.tensor[1] = two ? EncodeTensor{static_cast<const uint16_t*>(x_v), x_batch_stride, x_row_stride,
+                                     static_cast<const uint16_t*>(v_centroids), static_cast<uint8_t*>(v_codes)}
+                      : a.tensor[0];
+    a.n_tensors = two ? 2 : 1;
+    a.batch = batch;
+    a.t_new = t_new;
+    a.t_offset = t_offset;
+    a.map = map;
+    a.f = f;
+    return launch_encode(a, static_cast<hipStream_t>(stream));
+}
+
+}  // namespace
+
 cq_status cq_encode(const void* x, int64_t x_batch_stride, int64_t x_row_stride,
                     const void* centroids, const cq_format* fmt,
                     int32_t batch, int32_t t_new,
                     void* codes, int32_t t_offset, int32_t t_cap, void* stream)
 {
     Derived f;
-    cq_status st = derive(fmt, &f);
+    const cq_status st = derive(fmt, &f);
     if (st != CQ_OK) return st;
-    if ((st = check_encode_shape(f, batch, t_new, t_offset, t_cap)) != CQ_OK) return st;
-    if ((st = check_encode_tensor(f, x, x_batch_stride, x_row_stride, centroids, codes, batch, t_new)) != CQ_OK) return st;
-
-    EncodeArgs a;
-    a.tensor[0] = EncodeTensor{static_cast<const uint16_t*>(x), x_batch_stride, x_row_stride,
-                               static_cast<const uint16_t*>(centroids), static_cast<uint8_t*>(codes)};
-    a.tensor[1] = a.tensor[0];
-    a.n_tensors = 1;
-    a.batch = batch;
-    a.t_new = t_new;
-    a.t_offset = t_offset;
-    a.t_cap = t_cap;
-    a.f = f;
-    return launch_encode(a, static_cast<hipStream_t>(stream));
+    if (t_cap <= 0 || t_cap % kTileTokens != 0) return CQ_ERR_INVALID_ARG;
+    return encode_common(x, nullptr, x_batch_stride, x_row_stride, centroids, nullptr, f, batch, t_new, codes, nullptr,
+                         t_offset, t_cap, contiguous_map(f, t_cap), stream);
 }
 
 cq_status cq_encode_kv(const void* x_k, const void* x_v, int64_t x_batch_stride, int64_t x_row_stride,
@@ -144,25 +181,35 @@ cq_status cq_encode_kv(const void* x_k, const void* x_v, int64_t x_batch_stride,
                        void* k_codes, void* v_codes, int32_t t_offset, int32_t t_cap, void* stream)
 {
     Derived f;
+    const cq_status st = derive(fmt, &f);
+    if (st != CQ_OK) return st;
+    if (t_cap <= 0 || t_cap % kTileTokens != 0) return CQ_ERR_INVALID_ARG;
+    if (!x_v || !v_centroids || !v_codes) return CQ_ERR_INVALID_ARG;
+    return encode_common(x_k, x_v, x_batch_stride, x_row_stride, k_centroids, v_centroids, f, batch, t_new, k_codes,
+                         v_codes, t_offset, t_cap, contiguous_map(f, t_cap), stream);
+}
+
+size_t cq_paged_cache_bytes(const cq_format* fmt, int32_t n_pages)
+{
+    Derived f;
+    if (derive(fmt, &f) != CQ_OK || n_pages <= 0) return 0;
+    return (size_t)n_pages * f.n_kv_heads * f.tile_bytes;
+}
+
+cq_status cq_encode_kv_paged(const void* x_k, const void* x_v, int64_t x_batch_stride, int64_t x_row_stride,
+                             const void* k_centroids, const void* v_centroids, const cq_format* fmt,
+                             int32_t batch, int32_t t_new,
+                             void* k_pool, void* v_pool, const cq_page_table* pages, int32_t t_offset, void* stream)
+{
+    Derived f;
     cq_status st = derive(fmt, &f);
     if (st != CQ_OK) return st;
-    if ((st = check_encode_shape(f, batch, t_new, t_offset, t_cap)) != CQ_OK) return st;
-    if ((st = check_encode_tensor(f, x_k, x_batch_stride, x_row_stride, k_centroids, k_codes, batch, t_new)) != CQ_OK) return st;
-    if ((st = check_encode_tensor(f, x_v, x_batch_stride, x_row_stride, v_centroids, v_codes, batch, t_new)) != CQ_OK) return st;
-    if (k_codes == v_codes) return CQ_ERR_INVALID_ARG;
-
-    EncodeArgs a;
-    a.tensor[0] = EncodeTensor{static_cast<const uint16_t*>(x_k), x_batch_stride, x_row_stride,
-                               static_cast<const uint16_t*>(k_centroids), static_cast<uint8_t*>(k_codes)};
-    a.tensor[1] = EncodeTensor{static_cast<const uint16_t*>(x_v), x_batch_stride, x_row_stride,
-                               static_cast<const uint16_t*>(v_centroids), static_cast<uint8_t*>(v_codes)};
-    a.n_tensors = 2;
-    a.batch = batch;
-    a.t_new = t_new;
-    a.t_offset = t_offset;
-    a.t_cap = t_cap;
-    a.f = f;
-    return launch_encode(a, static_cast<hipStream_t>(stream));
+    CacheMap map;
+    int32_t t_cap = 0;
+    if ((st = paged_map(f, pages, batch, &map, &t_cap)) != CQ_OK) return st;
+    if (!x_v || !v_centroids || !v_pool) return CQ_ERR_INVALID_ARG;
+    return encode_common(x_k, x_v, x_batch_stride, x_row_stride, k_centroids, v_centroids, f, batch, t_new, k_pool,
+                         v_pool, t_offset, t_cap, map, stream);
 }
 
 cq_status cq_dequantize(const void* codes, const void* centroids, const cq_format* fmt,
@@ -185,7 +232,7 @@ cq_status cq_dequantize(const void* codes, const void* centroids, const cq_forma
     a.batch = batch;
     a.t_offset = t_offset;
     a.t_count = t_count;
-    a.t_cap = t_cap;
+    a.map = contiguous_map(f, t_cap);
     a.f = f;
     return launch_dequantize(a, static_cast<hipStream_t>(stream));
 }
@@ -263,17 +310,24 @@ cq_status decode_common(const void* q, const void* x_k_new, const void* x_v_new,
                         const void* k_codes, const void* v_codes,
                         const void* k_centroids, const void* v_centroids,
                         float scale, const cq_format* fmt,
-                        int32_t batch, int32_t n_q_heads, int32_t t, int32_t t_cap,
+                        int32_t batch, int32_t n_q_heads, int32_t t, int32_t t_cap, const cq_page_table* pages,
                         const int32_t* seq_lens, int32_t tokens_per_split,
                         void* out, void* workspace, size_t workspace_bytes, void* stream, bool step)
 {
     Derived f;
-    const cq_status st = derive(fmt, &f);
+    cq_status st = derive(fmt, &f);
     if (st != CQ_OK) return st;
+    CacheMap map;
+    if (pages) {
+        if ((st = paged_map(f, pages, batch, &map, &t_cap)) != CQ_OK) return st;
+    } else {
+        if (t_cap <= 0 || t_cap % kTileTokens != 0) return CQ_ERR_INVALID_ARG;
+        map = contiguous_map(f, t_cap);
+    }
     if (!q || !k_codes || !v_codes || !k_centroids || !v_centroids || !out || !workspace)
         return CQ_ERR_INVALID_ARG;
     if (batch <= 0 || n_q_heads <= 0 || n_q_heads % f.n_kv_heads != 0) return CQ_ERR_INVALID_ARG;
-    if (t_cap <= 0 || t_cap % kTileTokens != 0 || t <= 0 || t > t_cap) return CQ_ERR_INVALID_ARG;
+    if (t <= 0 || t > t_cap) return CQ_ERR_INVALID_ARG;
     if (!std::isfinite(scale)) return CQ_ERR_INVALID_ARG;
     if (tokens_per_split < 0 || tokens_per_split % kTileTokens != 0) return CQ_ERR_INVALID_ARG;
     if (!aligned16(q) || !aligned16(k_codes) || !aligned16(v_codes) || !aligned16(k_centroids) ||
@@ -303,7 +357,7 @@ cq_status decode_common(const void* q, const void* x_k_new, const void* x_v_new,
     a.batch = batch;
     a.n_q_heads = n_q_heads;
     a.t = t;
-    a.t_cap = t_cap;
+    a.map = map;
     a.seq_lens = seq_lens;
     a.xk_new = step ? static_cast<const uint16_t*>(x_k_new) : nullptr;
     a.xv_new = step ? static_cast<const uint16_t*>(x_v_new) : nullptr;
@@ -326,7 +380,20 @@ cq_status cq_decode_attention(const void* q, const void* k_codes, const void* v_
                               void* out, void* workspace, size_t workspace_bytes, void* stream)
 {
     return decode_common(q, nullptr, nullptr, 0, k_codes, v_codes, k_centroids, v_centroids, scale, fmt, batch,
-                         n_q_heads, t, t_cap, seq_lens, tokens_per_split, out, workspace, workspace_bytes, stream, false);
+                         n_q_heads, t, t_cap, nullptr, seq_lens, tokens_per_split, out, workspace, workspace_bytes, stream,
+                         false);
+}
+
+cq_status cq_decode_attention_paged(const void* q, const void* k_pool, const void* v_pool,
+                                    const void* k_centroids, const void* v_centroids,
+                                    float scale, const cq_format* fmt,
+                                    int32_t batch, int32_t n_q_heads, int32_t t, const cq_page_table* pages,
+                                    const int32_t* seq_lens, int32_t tokens_per_split,
+                                    void* out, void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (!pages) return CQ_ERR_INVALID_ARG;
+    return decode_common(q, nullptr, nullptr, 0, k_pool, v_pool, k_centroids, v_centroids, scale, fmt, batch,
+                         n_q_heads, t, 0, pages, seq_lens, tokens_per_split, out, workspace, workspace_bytes, stream, false);
 }
 
 cq_status cq_decode_step(const void* q, const void* x_k_new, const void* x_v_new, int64_t x_row_stride,
@@ -338,7 +405,21 @@ cq_status cq_decode_step(const void* q, const void* x_k_new, const void* x_v_new
                          void* out, void* workspace, size_t workspace_bytes, void* stream)
 {
     return decode_common(q, x_k_new, x_v_new, x_row_stride, k_codes, v_codes, k_centroids, v_centroids, scale, fmt,
-                         batch, n_q_heads, t, t_cap, seq_lens, tokens_per_split, out, workspace, workspace_bytes,
+                         batch, n_q_heads, t, t_cap, nullptr, seq_lens, tokens_per_split, out, workspace, workspace_bytes,
+                         stream, true);
+}
+
+cq_status cq_decode_step_paged(const void* q, const void* x_k_new, const void* x_v_new, int64_t x_row_stride,
+                               void* k_pool, void* v_pool,
+                               const void* k_centroids, const void* v_centroids,
+                               float scale, const cq_format* fmt,
+                               int32_t batch, int32_t n_q_heads, int32_t t, const cq_page_table* pages,
+                               const int32_t* seq_lens, int32_t tokens_per_split,
+                               void* out, void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (!pages) return CQ_ERR_INVALID_ARG;
+    return decode_common(q, x_k_new, x_v_new, x_row_stride, k_pool, v_pool, k_centroids, v_centroids, scale, fmt,
+                         batch, n_q_heads, t, 0, pages, seq_lens, tokens_per_split, out, workspace, workspace_bytes,
                          stream, true);
 }
 

@@ -198,10 +198,9 @@ struct Tile {
 };
 
 template <int GH, int B>
-__device__ __forceinline__ Tile<GH, B> load_tile(const uint8_t* stream, int tile, int lane)
+__device__ __forceinline__ Tile<GH, B> load_tile(const uint8_t* base, int lane)
 {
     Tile<GH, B> w;
-    const uint8_t* base = stream + (size_t)tile * Fmt<GH, B>::TILE_BYTES;
     const u32x4* p = reinterpret_cast<const u32x4*>(base) + lane;
 #pragma unroll
     for (int pl = 0; pl < GH / 16; ++pl) w.lo[pl] = __builtin_nontemporal_load(p + pl * 64);
@@ -211,6 +210,23 @@ __device__ __forceinline__ Tile<GH, B> load_tile(const uint8_t* stream, int tile
         w.hi = 0;
     return w;
 }
+
+// A wavefront's tiles of one code stream: tile k of its walk is tile first + k stride of the
+// (sequence, KV head).  Contiguous cache: consecutive tiles are TILE_BYTES apart from `base`.
+// Paged cache: lane j of `pages` holds the page of the walk's j-th tile (read once, before the
+// walk; a walk has at most 64 tiles), and a tile sits at base + page * page_bytes.
+template <int GH, int B>
+struct TileWalk {
+    const uint8_t* base;
+    int first, stride;
+    int pages;                  // per lane
+    size_t page_bytes;          // 0: contiguous
+    __device__ __forceinline__ const uint8_t* at(int k) const
+    {
+        if (page_bytes) return base + (size_t)__builtin_amdgcn_readlane(pages, k) * page_bytes;
+        return base + (size_t)(first + k * stride) * Fmt<GH, B>::TILE_BYTES;
+    }
+};
 
 // Per-lane column constants for the Gh steps: b = 8 packs 4 byte offsets per register (the
 // v_perm_b32 picks one), b = 10 keeps one register per step.
@@ -265,26 +281,25 @@ struct Streamer {
     static constexpr int TAIL = 2 * PF - 1;
     Tile<GH, B> buf[TAIL];
 
-    __device__ __forceinline__ void begin(const uint8_t* stream, int n, int first, int stride, int lane)
+    __device__ __forceinline__ void begin(const TileWalk<GH, B>& tw, int n, int lane)
     {
         if (n >= 2 * PF) {
 #pragma unroll
             for (int i = 0; i < PF; ++i) {
-                buf[i] = load_tile<GH, B>(stream, first + i * stride, lane);
+                buf[i] = load_tile<GH, B>(tw.at(i), lane);
                 __builtin_amdgcn_sched_barrier(0);      // keep request order == consumption order
             }
         } else {
 #pragma unroll
             for (int i = 0; i < TAIL; ++i)
-                if (i < n) buf[i] = load_tile<GH, B>(stream, first + i * stride, lane);
+                if (i < n) buf[i] = load_tile<GH, B>(tw.at(i), lane);
         }
     }
 
     // `last_requests()` is called once, after the last tile has been requested and before the
     // last tiles are consumed: loads the caller issues there ride behind the stream.
     template <class Fn, class Hook>
-    __device__ __forceinline__ void run(const uint8_t* stream, int n, int first, int stride, int lane, Fn&& fn,
-                                        Hook&& last_requests)
+    __device__ __forceinline__ void run(const TileWalk<GH, B>& tw, int n, int lane, Fn&& fn, Hook&& last_requests)
     {
         int k = 0;
         if (n >= 2 * PF) {
@@ -292,7 +307,7 @@ struct Streamer {
 #pragma unroll
                 for (int i = 0; i < PF; ++i) {
                     fn(buf[i], k + i);
-                    buf[i] = load_tile<GH, B>(stream, first + (k + PF + i) * stride, lane);
+                    buf[i] = load_tile<GH, B>(tw.at(k + PF + i), lane);
                     __builtin_amdgcn_sched_barrier(0);
                 }
             }
@@ -301,7 +316,7 @@ struct Streamer {
             k += PF;
 #pragma unroll
             for (int i = 0; i < TAIL; ++i)
-                if (k + i < n) buf[i] = load_tile<GH, B>(stream, first + (k + i) * stride, lane);
+                if (k + i < n) buf[i] = load_tile<GH, B>(tw.at(k + i), lane);
         }
         last_requests();
         __builtin_amdgcn_sched_barrier(0);
@@ -449,10 +464,26 @@ __global__ __launch_bounds__(NT, 4) void decode_split_kernel(DecodeArgs a)
     Columns<GH, B> col;
     col.init(lane);
 
-    const size_t stream_idx = (size_t)(n * a.f.n_kv_heads + hkv) * (a.t_cap / kTileTokens) * F::TILE_BYTES;
-    const uint8_t* kstream = a.k_codes + stream_idx;
-    const uint8_t* vstream = a.v_codes + stream_idx;
     const int my_tiles = (tile1 - tile0 - wave + NW - 1) / NW;   // tiles tile0 + wave + k NW
+    // the two code streams of this (sequence, KV head); a paged cache first reads the pages of
+    // this wavefront's tiles (lane j: its j-th tile; a split has at most 64 tiles per wavefront)
+    TileWalk<GH, B> kwalk, vwalk;
+    kwalk.first = tile0 + wave;
+    kwalk.stride = NW;
+    kwalk.pages = 0;
+    if (a.map.block_table) {
+        if (lane < my_tiles) kwalk.pages = a.map.page(n, tile0 + wave + lane * NW);
+        kwalk.page_bytes = (size_t)a.f.n_kv_heads * F::TILE_BYTES;
+        kwalk.base = a.k_codes + (size_t)hkv * F::TILE_BYTES;
+        vwalk = kwalk;
+        vwalk.base = a.v_codes + (size_t)hkv * F::TILE_BYTES;
+    } else {
+        const size_t stream_idx = a.map.tile_index(n, hkv, 0) * F::TILE_BYTES;
+        kwalk.page_bytes = 0;
+        kwalk.base = a.k_codes + stream_idx;
+        vwalk = kwalk;
+        vwalk.base = a.v_codes + stream_idx;
+    }
 
     Streamer<GH, B, PF> st;
 
@@ -491,7 +522,7 @@ __global__ __launch_bounds__(NT, 4) void decode_split_kernel(DecodeArgs a)
                 // the first key tiles are requested behind the first centroids: tile requests must
                 // go out as early as possible (the kernel is bound by HBM from its first
                 // microsecond), but not in front of the loads the table build waits for
-                if (ch == 0 && k0 == 0) st.begin(kstream, my_tiles, tile0 + wave, NW, lane);
+                if (ch == 0 && k0 == 0) st.begin(kwalk, my_tiles, lane);
                 if constexpr (STEP) __builtin_amdgcn_sched_barrier(0);
                 if (has_new && k0 == 0) {
 #pragma unroll
@@ -531,11 +562,11 @@ __global__ __launch_bounds__(NT, 4) void decode_split_kernel(DecodeArgs a)
     // stores them (each token owns its 16-byte records, so no other token's bytes are touched)
     const bool writer = has_new && hq % (a.n_q_heads / a.f.n_kv_heads) == 0;
     if (writer)
-        store_new_codes<GH, B>(const_cast<uint8_t*>(kstream) + (size_t)tile_new * F::TILE_BYTES, keys, u_new, tid);
+        store_new_codes<GH, B>(const_cast<uint8_t*>(a.k_codes) + a.map.tile_index(n, hkv, tile_new) * F::TILE_BYTES, keys, u_new, tid);
 
     // ---- 2. phase K: scores --------------------------------------------------------------
     float lane_max = -INFINITY;
-    st.run(kstream, my_tiles, tile0 + wave, NW, lane, [&](const Tile<GH, B>& w_in, int k) {
+    st.run(kwalk, my_tiles, lane, [&](const Tile<GH, B>& w_in, int k) {
         const int lt = wave + k * NW;                       // tile within the split
         Tile<GH, B> w = w_in;
         if (has_new && tile0 + lt == tile_new) patch_new_token<GH, B>(w, keys, u_new, lane);
@@ -550,7 +581,7 @@ __global__ __launch_bounds__(NT, 4) void decode_split_kernel(DecodeArgs a)
         sc[sidx(lt * kTileTokens + lane)] = sv;
         lane_max = fmaxf(lane_max, sv);
     }, [] {});
-    st.begin(vstream, my_tiles, tile0 + wave, NW, lane);         // value codes are on their way
+    st.begin(vwalk, my_tiles, lane);         // value codes are on their way
 
     lane_max = wave_max(lane_max);
     lds_barrier();                                // all table reads done, all scores written
@@ -589,7 +620,7 @@ __global__ __launch_bounds__(NT, 4) void decode_split_kernel(DecodeArgs a)
     constexpr bool EARLY = IPT * NCH <= 8 && KB == IPT;
     Cent16 rawv[EARLY ? NCH : 1][KB];
     unsigned lane_sum = 0;
-    st.run(vstream, my_tiles, tile0 + wave, NW, lane, [&](const Tile<GH, B>& w_in, int k) {
+    st.run(vwalk, my_tiles, lane, [&](const Tile<GH, B>& w_in, int k) {
         const int lt = wave + k * NW;
         const Tile<GH, B>& w = w_in;
         const float p = __builtin_amdgcn_exp2f(sc[sidx(lt * kTileTokens + lane)] - m);
@@ -662,7 +693,7 @@ __global__ __launch_bounds__(NT, 4) void decode_split_kernel(DecodeArgs a)
             lds_add((code * RW + tid * R) * 4u, *pf_new);
         }
         if (writer)
-            store_new_codes<GH, B>(const_cast<uint8_t*>(vstream) + (size_t)tile_new * F::TILE_BYTES, keys + GH, u_new, tid);
+            store_new_codes<GH, B>(const_cast<uint8_t*>(a.v_codes) + a.map.tile_index(n, hkv, tile_new) * F::TILE_BYTES, keys + GH, u_new, tid);
         lds_barrier();
     }
 

@@ -106,7 +106,7 @@ __global__ __launch_bounds__(256) void encode_centroids_kernel(EncodeArgs a)
         const int u = pos & (kTileTokens - 1);
         const int hkv = g_abs / GH, g = g_abs % GH;
         const int slot = (g - u) & (GH - 1);
-        uint8_t* tile = ten.codes + ((size_t)(n * a.f.n_kv_heads + hkv) * (a.t_cap / kTileTokens) + pos / kTileTokens) * TILE_BYTES;
+        uint8_t* tile = ten.codes + a.map.tile_index(n, hkv, pos / kTileTokens) * TILE_BYTES;
         tile[(slot >> 4) * 1024 + u * 16 + (slot & 15)] = (uint8_t)(code & 0xff);
         if constexpr (B == 10) {
             // the high bits of a token's 16 codes share one word that other workgroups update too
@@ -150,7 +150,7 @@ __global__ __launch_bounds__(256) void dequantize_kernel(DequantArgs a)
     const int tid = threadIdx.x;
     const int first_tile = a.t_offset / kTileTokens;
     const int tile = first_tile + blockIdx.x, hkv = blockIdx.y, n = blockIdx.z;
-    const uint8_t* src = a.codes + ((size_t)(n * a.f.n_kv_heads + hkv) * (a.t_cap / kTileTokens) + tile) * TILE_BYTES;
+    const uint8_t* src = a.codes + a.map.tile_index(n, hkv, tile) * TILE_BYTES;
     for (int i = tid; i < TILE_BYTES / 16; i += 256)
         reinterpret_cast<uint4*>(tb)[i] = reinterpret_cast<const uint4*>(src)[i];
     __syncthreads();

@@ -417,8 +417,7 @@ __global__ __launch_bounds__(NW * 64) void encode_mfma_kernel(EncodeArgs a)
 
     // store this lane's token
     if (valid) {
-        const size_t stream = (size_t)(n * a.f.n_kv_heads + hkv) * (a.t_cap / kTileTokens) * TILE_BYTES;
-        uint8_t* tp = ten.codes + stream + (size_t)tile * TILE_BYTES;
+        uint8_t* tp = ten.codes + a.map.tile_index(n, hkv, tile) * TILE_BYTES;
 #pragma unroll
         for (int p = 0; p < P; ++p) {
             const uint4 v = *reinterpret_cast<const uint4*>(&rec[wave][p * 1024 + lane * 16]);

@@ -26,6 +26,30 @@ struct Derived {
 // Host-side format check shared by every entry point.
 cq_status derive(const cq_format* fmt, Derived* out);
 
+// Where the 64-token tiles of a packed cache live.  Contiguous: [sequence][kv head][tile] with
+// t_cap / 64 tiles per stream.  Paged: a pool of pages, a page being one tile of every KV head
+// ([page][kv head][tile bytes]), and block_table[n * bt_stride + tile] names the page of tile
+// `tile` of sequence n (entries are clamped to the pool, so a bad table cannot cause a fault).
+struct CacheMap {
+    const int32_t* block_table;   // null: contiguous
+    int64_t bt_stride;
+    int n_pages;
+    int tiles_cap;                // contiguous: t_cap / 64
+    int n_kv_heads;
+
+    __device__ __forceinline__ int page(int n, int tile) const
+    {
+        const int p = block_table[(size_t)n * bt_stride + tile];
+        return p < 0 ? 0 : (p >= n_pages ? n_pages - 1 : p);
+    }
+    // index of the tile in units of tile bytes
+    __device__ __forceinline__ size_t tile_index(int n, int hkv, int tile) const
+    {
+        if (block_table) return (size_t)page(n, tile) * n_kv_heads + hkv;
+        return (size_t)(n * n_kv_heads + hkv) * tiles_cap + tile;
+    }
+};
+
 // One or two tensors (K alone, or K and V of the same shape) encoded by one launch.
 struct EncodeTensor {
     const uint16_t* x;
@@ -37,7 +61,8 @@ struct EncodeTensor {
 struct EncodeArgs {
     EncodeTensor tensor[2];
     int n_tensors;
-    int batch, t_new, t_offset, t_cap;
+    int batch, t_new, t_offset;
+    CacheMap map;
     Derived f;
 };
 
@@ -48,7 +73,8 @@ struct DecodeArgs {
     const uint16_t* k_centroids;
     const uint16_t* v_centroids;
     float scale_log2e;        // scale * log2(e): scores are kept in the base-2 domain
-    int batch, n_q_heads, t, t_cap;
+    int batch, n_q_heads, t;
+    CacheMap map;
     const int32_t* seq_lens;
     // fused decode step (null xk_new = plain attention): the new token's key / value rows,
     // fp16 [batch][D] with row stride x_new_stride (elements); the caches are then written too
@@ -69,7 +95,8 @@ struct DequantArgs {
     const uint16_t* centroids;
     uint16_t* out;            // fp16 [batch][t_count][D]
     int64_t out_batch_stride, out_row_stride;
-    int batch, t_offset, t_count, t_cap;
+    int batch, t_offset, t_count;
+    CacheMap map;
     Derived f;
 };
 cq_status launch_dequantize(const DequantArgs& a, hipStream_t stream);

@@ -189,3 +189,29 @@ def test_dequantize_argument_checks_without_launching():
     assert deq(rs=255) == cq.CQ_ERR_INVALID_ARG and deq(rs=260) == cq.CQ_ERR_INVALID_ARG
     assert deq(bs=99 * 256) == cq.CQ_ERR_INVALID_ARG
     assert deq(out=0x30008) == cq.CQ_ERR_INVALID_ARG
+
+
+def test_paged_argument_checks_without_launching():
+    lib = cq.load()
+    f = cq.CQFormat(8, 8, 128, 2)._c()
+    assert lib.cq_paged_cache_bytes(ctypes.byref(f), 10) == 10 * 2 * 1024
+    assert lib.cq_paged_cache_bytes(ctypes.byref(f), 0) == 0
+    PT = cq._PageTable
+
+    def dec(pt, t=100, ws_bytes=1 << 20):
+        p = None if pt is None else ctypes.byref(pt)
+        return int(lib.cq_decode_attention_paged(_fake(0x10000), _fake(0x20000), _fake(0x30000), _fake(0x40000),
+                                                 _fake(0x50000), 0.1, ctypes.byref(f), 2, 4, t, p, None, 0,
+                                                 _fake(0x60000), _fake(0x70000), ws_bytes, None))
+
+    good = PT(8, 2, 2, 0x80000)
+    assert dec(None) == cq.CQ_ERR_INVALID_ARG
+    assert dec(PT(0, 2, 2, 0x80000)) == cq.CQ_ERR_INVALID_ARG            # no pages
+    assert dec(PT(8, 2, 1, 0x80000)) == cq.CQ_ERR_INVALID_ARG            # row stride < max_tiles
+    assert dec(PT(8, 2, 2, 0)) == cq.CQ_ERR_INVALID_ARG                  # no table
+    assert dec(PT(8, 2, 2, 0x80002)) == cq.CQ_ERR_INVALID_ARG            # misaligned table
+    assert dec(good, t=129) == cq.CQ_ERR_INVALID_ARG                     # beyond max_tiles * 64
+    assert dec(good, ws_bytes=0) == cq.CQ_ERR_WORKSPACE_TOO_SMALL
+    enc = int(lib.cq_encode_kv_paged(_fake(0x10000), _fake(0x20000), 256 * 100, 256, _fake(0x30000), _fake(0x40000),
+                                     ctypes.byref(f), 2, 100, _fake(0x50000), _fake(0x60000), ctypes.byref(good), 30, None))
+    assert enc == cq.CQ_ERR_INVALID_ARG                                  # 30 + 100 tokens > 128
