@@ -1,7 +1,8 @@
 """GPU parity at the full sizes of the named workloads, in the launch configuration bench.py
 times (default context split, caches filled by REALLY encoding generated activations on the
 device).  The oracle cannot redo these sizes whole, so it recomputes sampled outputs one by one:
-all groups of sampled tokens for cq_encode, whole (sequence, head) rows for cq_decode_attention."""
+all groups of sampled tokens for cq_encode, whole (sequence, head) rows for cq_decode_attention
+and, for the workload bench.py times, for the fused cq_decode_step."""
 import math
 
 import numpy as np
@@ -17,7 +18,7 @@ from gpu_util import (check_attention, check_codes, dev, head_stream_codes, orac
 pytestmark = pytest.mark.gpu
 
 
-def _fill_and_check(cfg_id, n_attn_samples, n_token_samples, chunk_tokens):
+def _fill_and_check(cfg_id, n_attn_samples, n_token_samples, chunk_tokens, fused_step=False):
     cfg = synth.CONFIGS[cfg_id]
     fmt = cq.CQFormat(cfg.c, cfg.b, cfg.head_dim, cfg.n_kv_heads)
     B, T, D = cfg.batch, cfg.context, cfg.kv_channels
@@ -62,11 +63,33 @@ def _fill_and_check(cfg_id, n_attn_samples, n_token_samples, chunk_tokens):
         vc = head_stream_codes(vcache, fmt, B, T, n, hk, T)
         ref = oracle_head_attention(q_h[n, hq], kc, vc, ck_h[hk * Gh:(hk + 1) * Gh], cv_h[hk * Gh:(hk + 1) * Gh], scale)
         check_attention(out_h[n, hq][None], ref[None])
+    if fused_step:
+        # the launch bench.py times: one cq_decode_step per layer (new rows go to position T - 1)
+        xk1 = synth.sample_activations_torch(rk, B, 9001, "cuda").view(B, D)
+        xv1 = synth.sample_activations_torch(rv, B, 9002, "cuda").view(B, D)
+        k1, v1 = kcache.clone(), vcache.clone()
+        cq.cq_encode_kv(xk1[:, None, :], xv1[:, None, :], ck, cv, fmt, k1, v1, T - 1, T)
+        ref = cq.cq_decode_attention(dev(q_h), k1, v1, ck, cv, scale, fmt, T, T)
+        out2 = cq.cq_decode_step(dev(q_h), xk1, xv1, kcache, vcache, ck, cv, scale, fmt, T, T)
+        torch.cuda.synchronize()
+        assert torch.equal(kcache, k1) and torch.equal(vcache, v1)
+        assert torch.equal(out2.view(torch.int16), ref.view(torch.int16))
+        out2_h = out2.cpu().numpy()
+        xk1_h, xv1_h = xk1.cpu().numpy(), xv1.cpu().numpy()
+        for n, hq in sorted(picks):
+            hk = hq // rep
+            kc = head_stream_codes(kcache, fmt, B, T, n, hk, T)
+            vc = head_stream_codes(vcache, fmt, B, T, n, hk, T)
+            sl = slice(hk * cfg.head_dim, (hk + 1) * cfg.head_dim)
+            check_codes(kc[T - 1:], xk1_h[n:n + 1, sl], ck_h[hk * Gh:(hk + 1) * Gh])
+            check_codes(vc[T - 1:], xv1_h[n:n + 1, sl], cv_h[hk * Gh:(hk + 1) * Gh])
+            ref64 = oracle_head_attention(q_h[n, hq], kc, vc, ck_h[hk * Gh:(hk + 1) * Gh], cv_h[hk * Gh:(hk + 1) * Gh], scale)
+            check_attention(out2_h[n, hq][None], ref64[None])
     return cq.cq_decode_default_split(fmt, B, cfg.n_q_heads, T)
 
 
 def test_config2_one_layer_cq4c8b_batch16_ctx4096():
-    split = _fill_and_check(2, n_attn_samples=6, n_token_samples=12, chunk_tokens=4096)
+    split = _fill_and_check(2, n_attn_samples=6, n_token_samples=12, chunk_tokens=4096, fused_step=True)
     assert split == 4096           # the configuration bench.py times: one split, no merge kernel
 
 
