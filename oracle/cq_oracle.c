@@ -152,11 +152,11 @@ int cq_oracle_dequantize(const uint16_t *codes, int64_t n_tokens, int64_t n_chan
  *   probs_out    NULL or [B][Hq][T]: softmax weights
  * Returns 0, or -1 on bad arguments.
  */
-int cq_oracle_attention(const uint16_t *q, const uint16_t *k_codes, const uint16_t *v_codes,
-                        const uint16_t *k_centroids, const uint16_t *v_centroids, double scale,
-                        int batch, int n_q_heads, int n_kv_heads, int head_dim, int64_t T,
-                        int c, int b, const int32_t *seq_lens, double *out,
-                        double *scores_out, double *probs_out)
+static int attention_impl(const uint16_t *q, const uint16_t *k_codes, const uint16_t *v_codes,
+                          const uint16_t *k_centroids, const uint16_t *v_centroids, double scale,
+                          int batch, int n_q_heads, int n_kv_heads, int head_dim, int64_t T,
+                          int c, int b, const int32_t *seq_lens, double rope_base, int64_t pos_offset,
+                          double *out, double *scores_out, double *probs_out)
 {
     if (!q || !k_codes || !v_codes || !k_centroids || !v_centroids || !out) return -1;
     if (batch <= 0 || n_q_heads <= 0 || n_kv_heads <= 0 || head_dim <= 0 || T <= 0) return -1;
@@ -198,6 +198,16 @@ int cq_oracle_attention(const uint16_t *q, const uint16_t *k_codes, const uint16
                             cq_oracle_half_to_double(v_centroids[(g * K + jv) * c + i]);
                     }
                 }
+            /* stored keys are pre-rotation keys: rotate channel pairs (i, i + d/2) of the key at
+             * position p = t + pos_offset by the angle p * base^(-2i/d) */
+            if (rope_base > 0.0)
+                for (int64_t t = 0; t < L; ++t)
+                    for (int64_t i = 0; i < d / 2; ++i) {
+                        const double ang = (double)(t + pos_offset) * pow(rope_base, -2.0 * (double)i / (double)d);
+                        const double x = khat[t * d + i], y = khat[t * d + i + d / 2];
+                        khat[t * d + i] = x * cos(ang) - y * sin(ang);
+                        khat[t * d + i + d / 2] = x * sin(ang) + y * cos(ang);
+                    }
             /* scores = scale * K^T q */
             const uint16_t *qh = q + ((int64_t)n * n_q_heads + h) * d;
             double m = -INFINITY;
@@ -232,4 +242,34 @@ int cq_oracle_attention(const uint16_t *q, const uint16_t *k_codes, const uint16
         }
     }
     return failed ? -2 : 0;
+}
+
+int cq_oracle_attention(const uint16_t *q, const uint16_t *k_codes, const uint16_t *v_codes,
+                        const uint16_t *k_centroids, const uint16_t *v_centroids, double scale,
+                        int batch, int n_q_heads, int n_kv_heads, int head_dim, int64_t T,
+                        int c, int b, const int32_t *seq_lens, double *out,
+                        double *scores_out, double *probs_out)
+{
+    return attention_impl(q, k_codes, v_codes, k_centroids, v_centroids, scale, batch, n_q_heads, n_kv_heads,
+                          head_dim, T, c, b, seq_lens, 0.0, 0, out, scores_out, probs_out);
+}
+
+/*
+ * The same attention when the cache holds keys quantized BEFORE the rotary position embedding
+ * (Section 3.2 of the paper quantizes keys before RoPE; Section 2.1 counts the positional
+ * encoding into f_K): the dequantized key of position p is rotated before the dot product.
+ * The paper cites RoPE without restating it; the form used here is the one of the models it
+ * evaluates (LLaMA, Mistral): head channels i and i + d/2 form a pair that is rotated by the
+ * angle p * rope_base^(-2i/d); the query is given already rotated to its own position.  Cached
+ * token t has position t + pos_offset.  rope_base must be > 0.
+ */
+int cq_oracle_attention_rope(const uint16_t *q, const uint16_t *k_codes, const uint16_t *v_codes,
+                             const uint16_t *k_centroids, const uint16_t *v_centroids, double scale,
+                             int batch, int n_q_heads, int n_kv_heads, int head_dim, int64_t T,
+                             int c, int b, const int32_t *seq_lens, double rope_base, int64_t pos_offset,
+                             double *out, double *scores_out, double *probs_out)
+{
+    if (!(rope_base > 0.0) || head_dim % 2 != 0) return -1;
+    return attention_impl(q, k_codes, v_codes, k_centroids, v_centroids, scale, batch, n_q_heads, n_kv_heads,
+                          head_dim, T, c, b, seq_lens, rope_base, pos_offset, out, scores_out, probs_out);
 }

@@ -54,6 +54,11 @@ def _load():
                                             ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int,
                                             ctypes.c_int64, ctypes.c_int, ctypes.c_int, i32p,
                                             f64p, f64p, f64p]
+        lib.cq_oracle_attention_rope.restype = ctypes.c_int
+        lib.cq_oracle_attention_rope.argtypes = [u16p, u16p, u16p, u16p, u16p, ctypes.c_double,
+                                                 ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int,
+                                                 ctypes.c_int64, ctypes.c_int, ctypes.c_int, i32p,
+                                                 ctypes.c_double, ctypes.c_int64, f64p, f64p, f64p]
         _lib = lib
     return _lib
 
@@ -130,9 +135,13 @@ def dequantize(codes: np.ndarray, centroids: np.ndarray) -> np.ndarray:
 def attention(q: np.ndarray, k_codes: np.ndarray, v_codes: np.ndarray,
               k_centroids: np.ndarray, v_centroids: np.ndarray, scale: float,
               n_kv_heads: int, seq_lens: Optional[np.ndarray] = None,
-              want_scores: bool = False, want_probs: bool = False):
+              want_scores: bool = False, want_probs: bool = False,
+              rope_base: Optional[float] = None, pos_offset: int = 0):
     """q fp16 [B, Hq, d]; codes uint16 [B, T, G]; centroids fp16 [G, 2^b, c].
-    Returns out fp64 [B, Hq, d] (plus scores / probabilities [B, Hq, T] if asked)."""
+    Returns out fp64 [B, Hq, d] (plus scores / probabilities [B, Hq, T] if asked).
+    With rope_base the cached keys are pre-rotation keys: the key of cached token t is rotated
+    to position t + pos_offset (pairs (i, i + d/2), angle position * rope_base^(-2i/d)) before
+    the dot product with q, which is taken as already rotated."""
     lib = _load()
     qb = _bits(q)
     kc = np.ascontiguousarray(k_codes, dtype=np.uint16)
@@ -155,8 +164,13 @@ def attention(q: np.ndarray, k_codes: np.ndarray, v_codes: np.ndarray,
         if sl.shape != (B,):
             raise ValueError("seq_lens must have shape [B]")
         slp = sl.ctypes.data_as(ctypes.POINTER(ctypes.c_int32))
-    rc = lib.cq_oracle_attention(_u16(qb), _u16(kc), _u16(vc), _u16(ckb), _u16(cvb), float(scale),
-                                 B, Hq, n_kv_heads, d, T, c, b, slp, _f64(out), _f64(scores), _f64(probs))
+    if rope_base is None:
+        rc = lib.cq_oracle_attention(_u16(qb), _u16(kc), _u16(vc), _u16(ckb), _u16(cvb), float(scale),
+                                     B, Hq, n_kv_heads, d, T, c, b, slp, _f64(out), _f64(scores), _f64(probs))
+    else:
+        rc = lib.cq_oracle_attention_rope(_u16(qb), _u16(kc), _u16(vc), _u16(ckb), _u16(cvb), float(scale),
+                                          B, Hq, n_kv_heads, d, T, c, b, slp, float(rope_base), int(pos_offset),
+                                          _f64(out), _f64(scores), _f64(probs))
     if rc != 0:
         raise ValueError("cq_oracle_attention failed (rc=%d)" % rc)
     res: Tuple = (out,)

@@ -171,3 +171,95 @@ def test_large_scores_do_not_overflow():
     t_star = int(np.argmax(scores[0, 0]))
     want = _dequant_np(vc, cv)[0, t_star]
     np.testing.assert_allclose(out[0, 0], want, rtol=1e-9, atol=1e-12)
+
+
+# ------------------------------------------------------------------------------------------
+# keys cached before the rotary position embedding
+# ------------------------------------------------------------------------------------------
+def _rope_case(seed, T=37, hq=2, hkv=1, c=8, b=4):
+    rng = np.random.default_rng(seed)
+    d, K = 128, 1 << b
+    G = hkv * d // c
+    ck = rng.standard_normal((G, K, c)).astype(np.float16)
+    cv = rng.standard_normal((G, K, c)).astype(np.float16)
+    kc = rng.integers(0, K, size=(1, T, G)).astype(np.uint16)
+    vc = rng.integers(0, K, size=(1, T, G)).astype(np.uint16)
+    q = rng.standard_normal((1, hq, d)).astype(np.float16)
+    return q, kc, vc, ck, cv
+
+
+def _rotate_complex(x, pos, base):
+    """Rotary embedding through complex numbers: (x_i + j x_{i+d/2}) * exp(j pos theta_i)."""
+    d = x.shape[-1]
+    theta = base ** (-2.0 * np.arange(d // 2) / d)
+    z = (x[..., :d // 2] + 1j * x[..., d // 2:]) * np.exp(1j * np.asarray(pos)[..., None] * theta)
+    return np.concatenate([z.real, z.imag], axis=-1)
+
+
+def test_rope_scores_match_the_complex_number_form():
+    q, kc, vc, ck, cv = _rope_case(1)
+    _, scores = O.attention(q, kc, vc, ck, cv, 0.3, 1, want_scores=True, rope_base=10000.0, pos_offset=5)
+    khat = O.dequantize(kc[0], ck)                                  # [T, 128], pre-rotation
+    krot = _rotate_complex(khat, np.arange(kc.shape[1]) + 5, 10000.0)
+    want = 0.3 * np.einsum("hd,td->ht", q[0].astype(np.float64), krot)
+    assert np.allclose(scores[0], want, rtol=1e-12, atol=1e-12)
+
+
+def test_rope_output_is_plain_attention_over_rotated_keys():
+    # rotating the dequantized keys by hand and running textbook softmax attention
+    q, kc, vc, ck, cv = _rope_case(2, T=50, hq=4, hkv=2)
+    out = O.attention(q, kc, vc, ck, cv, 0.2, 2, rope_base=500.0)
+    khat = O.dequantize(kc[0], ck).reshape(50, 2, 128)
+    vhat = O.dequantize(vc[0], cv).reshape(50, 2, 128)
+    for h in range(4):
+        kr = _rotate_complex(khat[:, h // 2], np.arange(50), 500.0)
+        s = 0.2 * kr @ q[0, h].astype(np.float64)
+        p = np.exp(s - s.max())
+        p /= p.sum()
+        assert np.allclose(out[0, h], p @ vhat[:, h // 2], rtol=1e-11, atol=1e-12)
+
+
+def test_rope_depends_on_relative_positions_only():
+    # q0 rotated to position p against keys at t + off  ==  q0 rotated to p + s against keys at t + off + s
+    q, kc, vc, ck, cv = _rope_case(3)
+    q0 = q.astype(np.float64)
+    outs = []
+    for shift in (0, 11, 1000):
+        qrot = _rotate_complex(q0, np.full(q0.shape[:2], 40 + shift), 10000.0)
+        q16 = qrot.astype(np.float16)
+        # the comparison needs the same fp16 query: rotate in fp64 and feed the fp64 scores directly
+        _, s = O.attention(q16, kc, vc, ck, cv, 1.0, 1, want_scores=True, rope_base=10000.0, pos_offset=shift)
+        khat = O.dequantize(kc[0], ck)
+        krot = _rotate_complex(khat, np.arange(kc.shape[1]) + shift, 10000.0)
+        outs.append(np.einsum("hd,td->ht", qrot[0], krot))
+        assert np.allclose(s[0], np.einsum("hd,td->ht", q16[0].astype(np.float64), krot), rtol=1e-12, atol=1e-12)
+    assert np.allclose(outs[0], outs[1], rtol=1e-9, atol=1e-9) and np.allclose(outs[0], outs[2], rtol=1e-9, atol=1e-9)
+
+
+def test_rope_at_position_zero_and_norms():
+    q, kc, vc, ck, cv = _rope_case(4, T=1)
+    plain = O.attention(q, kc, vc, ck, cv, 0.5, 1, want_scores=True)
+    roped = O.attention(q, kc, vc, ck, cv, 0.5, 1, want_scores=True, rope_base=10000.0, pos_offset=0)
+    assert np.array_equal(plain[1], roped[1]) and np.array_equal(plain[0], roped[0])     # angle 0: identity
+    # a rotation preserves the norm of every pair: with q = the rotated key itself the score is |k|^2
+    q2, kc2, vc2, ck2, cv2 = _rope_case(5, T=9, hq=1)
+    khat = O.dequantize(kc2[0], ck2)
+    for t in (0, 3, 8):
+        qk = _rotate_complex(khat[t], t + 7, 10000.0)
+        # exact fp64 route: compare through the complex form (fp16 rounding of q would blur it)
+        assert np.isclose((qk ** 2).sum(), (khat[t] ** 2).sum(), rtol=1e-12)
+
+
+def test_rope_matches_the_rotate_half_formulation_in_torch():
+    import torch
+    q, kc, vc, ck, cv = _rope_case(6, T=20)
+    _, scores = O.attention(q, kc, vc, ck, cv, 1.0, 1, want_scores=True, rope_base=10000.0)
+    k = torch.from_numpy(O.dequantize(kc[0], ck))
+    d = 128
+    inv_freq = 1.0 / (10000.0 ** (torch.arange(0, d, 2, dtype=torch.float64) / d))
+    freqs = torch.outer(torch.arange(20, dtype=torch.float64), inv_freq)
+    emb = torch.cat([freqs, freqs], dim=-1)
+    rot_half = torch.cat([-k[:, d // 2:], k[:, :d // 2]], dim=-1)
+    k_rot = k * emb.cos() + rot_half * emb.sin()
+    want = torch.from_numpy(q[0].astype(np.float64)) @ k_rot.T
+    assert np.allclose(scores[0], want.numpy(), rtol=1e-12, atol=1e-12)
