@@ -229,6 +229,56 @@ CQ_API cq_status cq_decode_step_paged(const void *q, const void *x_k_new, const 
                                void *out, void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * Keys cached BEFORE the rotary position embedding.  Section 3.2 quantizes key activations
+ * before RoPE (the position-dependent rotation would otherwise spread each channel pair over a
+ * circle and cost codebook resolution), and Eq. 1 counts the positional encoding into the
+ * attention function; the cache then holds codes of un-rotated keys and attention has to apply
+ * the rotation of position t to the key of token t.  The paper cites RoPE without restating it;
+ * the form implemented is that of the models it evaluates: for head_dim d, channels i and
+ * i + d/2 (i < d/2) of a head form a pair, and the key at position t enters the score as
+ *     k'_i       = k_i cos(t th_i) - k_{i+d/2} sin(t th_i)
+ *     k'_{i+d/2} = k_{i+d/2} cos(t th_i) + k_i sin(t th_i),      th_i = base^(-2 i / d).
+ * The query is passed already rotated (it is one row; the caller's projection kernel rotates
+ * it).  Token u of the cache has position u.  Values are not rotated.
+ *
+ * cq_rope_table fills the trigonometric table the attention call reads (fp64 arithmetic,
+ * rounded once to fp32): one call per (base, longest context), reused by every layer and step.
+ *   head_dim       128 (others: CQ_ERR_UNSUPPORTED)
+ *   positions      table covers token positions [0, positions); a positive multiple of 64
+ *   table          device, 16-byte aligned, cq_rope_table_bytes(head_dim, positions) bytes,
+ *                  written asynchronously on `stream`; owned by the caller
+ * cq_rope_table_bytes returns 0 on bad arguments.
+ *
+ * cq_decode_attention_rope[_paged]: as cq_decode_attention[_paged], plus
+ *   q              rotated to its own position, otherwise as before
+ *   rope_table     device, as written by cq_rope_table(base, 128, rope_positions, ...)
+ *   rope_positions must be >= t
+ *   tokens_per_split  0 = cq_decode_rope_default_split(...); at most 8192
+ * b = 8 formats with head_dim 128 only (CQ-8c8b, CQ-4c8b, CQ-2c8b): the kernel keeps a head's
+ * key centroids (64 KiB) on chip; CQ-8c10b returns CQ_ERR_UNSUPPORTED.  Workspace size:
+ * cq_decode_workspace_bytes with the tokens_per_split actually used.
+ * Errors: as cq_decode_attention; CQ_ERR_INVALID_ARG also for a missing or too short table.
+ */
+CQ_API size_t cq_rope_table_bytes(int32_t head_dim, int32_t positions);
+CQ_API cq_status cq_rope_table(double base, int32_t head_dim, int32_t positions,
+                        void *table, size_t table_bytes, void *stream);
+CQ_API int32_t cq_decode_rope_default_split(const cq_format *fmt, int32_t batch, int32_t n_q_heads, int32_t t);
+CQ_API cq_status cq_decode_attention_rope(const void *q, const void *k_codes, const void *v_codes,
+                                   const void *k_centroids, const void *v_centroids,
+                                   float scale, const cq_format *fmt,
+                                   int32_t batch, int32_t n_q_heads, int32_t t, int32_t t_cap,
+                                   const int32_t *seq_lens, int32_t tokens_per_split,
+                                   const void *rope_table, int32_t rope_positions,
+                                   void *out, void *workspace, size_t workspace_bytes, void *stream);
+CQ_API cq_status cq_decode_attention_rope_paged(const void *q, const void *k_pool, const void *v_pool,
+                                         const void *k_centroids, const void *v_centroids,
+                                         float scale, const cq_format *fmt,
+                                         int32_t batch, int32_t n_q_heads, int32_t t, const cq_page_table *pages,
+                                         const int32_t *seq_lens, int32_t tokens_per_split,
+                                         const void *rope_table, int32_t rope_positions,
+                                         void *out, void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * cq_dequantize -- the inverse lookup ("dequantization", Section 2.2; CQ(A) of Eq. 5 as values):
  * out[n][t][g c + i] = centroids[g][code(n, t_offset + t, g)][i] for t = 0 .. t_count - 1, bit
  * for bit the stored fp16 centroids.  For callers that need dense keys / values (e.g. a

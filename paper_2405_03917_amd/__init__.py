@@ -28,7 +28,8 @@ EXPORTS = (
     "cq_cache_bytes", "cq_encode", "cq_encode_kv", "cq_decode_default_split", "cq_decode_workspace_bytes",
     "cq_decode_attention", "cq_decode_step", "cq_dequantize", "cq_paged_cache_bytes", "cq_encode_kv_paged",
     "cq_decode_attention_paged", "cq_decode_step_paged", "cq_kmeans_workspace_bytes", "cq_kmeans_fit",
-    "cq_probe_stream_read", "cq_probe_copy", "cq_probe_mfma",
+    "cq_rope_table_bytes", "cq_rope_table", "cq_decode_rope_default_split", "cq_decode_attention_rope",
+    "cq_decode_attention_rope_paged", "cq_probe_stream_read", "cq_probe_copy", "cq_probe_mfma",
 )
 
 
@@ -128,6 +129,18 @@ def load() -> ctypes.CDLL:
     lib.cq_kmeans_workspace_bytes.argtypes = [fp, i32]
     lib.cq_kmeans_fit.restype = ctypes.c_int
     lib.cq_kmeans_fit.argtypes = [vp, i64, vp, fp, i32, i32, vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
+    lib.cq_rope_table_bytes.restype = ctypes.c_size_t
+    lib.cq_rope_table_bytes.argtypes = [i32, i32]
+    lib.cq_rope_table.restype = ctypes.c_int
+    lib.cq_rope_table.argtypes = [ctypes.c_double, i32, i32, vp, ctypes.c_size_t, vp]
+    lib.cq_decode_rope_default_split.restype = i32
+    lib.cq_decode_rope_default_split.argtypes = [fp, i32, i32, i32]
+    lib.cq_decode_attention_rope.restype = ctypes.c_int
+    lib.cq_decode_attention_rope.argtypes = [vp, vp, vp, vp, vp, ctypes.c_float, fp, i32, i32, i32, i32,
+                                             vp, i32, vp, i32, vp, vp, ctypes.c_size_t, vp]
+    lib.cq_decode_attention_rope_paged.restype = ctypes.c_int
+    lib.cq_decode_attention_rope_paged.argtypes = [vp, vp, vp, vp, vp, ctypes.c_float, fp, i32, i32, i32, pp, vp, i32,
+                                                   vp, i32, vp, vp, ctypes.c_size_t, vp]
     lib.cq_probe_copy.restype = ctypes.c_int
     lib.cq_probe_copy.argtypes = [vp, vp, ctypes.c_size_t, vp]
     lib.cq_probe_mfma.restype = ctypes.c_int
@@ -326,6 +339,54 @@ def cq_decode_attention(q, k_codes, v_codes, k_centroids, v_centroids, scale: fl
     return out
 
 
+class RopeTable:
+    """The trigonometric table of cq_rope_table on the device: covers positions [0, positions)."""
+
+    def __init__(self, base: float, positions: int, head_dim: int = 128, device="cuda", stream=None):
+        import torch
+        nbytes = int(load().cq_rope_table_bytes(head_dim, positions))
+        if nbytes == 0:
+            raise CQError(CQ_ERR_INVALID_ARG, "cq_rope_table_bytes")
+        self.base, self.positions, self.head_dim = float(base), int(positions), int(head_dim)
+        self.table = torch.empty(nbytes, dtype=torch.uint8, device=device)
+        st = load().cq_rope_table(self.base, head_dim, positions, self.table.data_ptr(), nbytes, _stream_handle(stream))
+        if st != CQ_OK:
+            raise CQError(st, "cq_rope_table")
+
+
+def cq_decode_rope_default_split(fmt: CQFormat, batch: int, n_q_heads: int, t: int) -> int:
+    f = fmt._c()
+    return int(load().cq_decode_rope_default_split(ctypes.byref(f), batch, n_q_heads, t))
+
+
+def prepare_decode_attention_rope(q, k_codes, v_codes, k_centroids, v_centroids, scale: float, fmt: CQFormat,
+                                  t: int, t_cap: int, rope: RopeTable, seq_lens=None, tokens_per_split: int = 0,
+                                  out=None, workspace=None):
+    """Check and marshal the arguments of cq_decode_attention_rope once.  Returns (call, out)."""
+    if not isinstance(rope, RopeTable):
+        raise TypeError("rope must be a RopeTable")
+    if tokens_per_split == 0:
+        tokens_per_split = cq_decode_rope_default_split(fmt, int(q.shape[0]), int(q.shape[1]), t)
+        if tokens_per_split == 0:
+            raise CQError(CQ_ERR_UNSUPPORTED, "cq_decode_rope_default_split")
+    call, out = prepare_decode_attention(q, k_codes, v_codes, k_centroids, v_centroids, scale, fmt, t, t_cap,
+                                         seq_lens, tokens_per_split, out, workspace)
+    a = call._args
+    args = a[:13] + (rope.table.data_ptr(), rope.positions) + a[13:]
+    return PreparedCall(load().cq_decode_attention_rope, args, call._keep + (rope,), "cq_decode_attention_rope"), out
+
+
+def cq_decode_attention_rope(q, k_codes, v_codes, k_centroids, v_centroids, scale: float, fmt: CQFormat,
+                             t: int, t_cap: int, rope: RopeTable, seq_lens=None, tokens_per_split: int = 0,
+                             out=None, workspace=None, stream=None):
+    """Decode attention over keys that were quantized before the rotary position embedding: q is
+    already rotated to its position, the key of token u is rotated to position u on the fly."""
+    call, out = prepare_decode_attention_rope(q, k_codes, v_codes, k_centroids, v_centroids, scale, fmt, t, t_cap,
+                                              rope, seq_lens, tokens_per_split, out, workspace)
+    call(stream)
+    return out
+
+
 def prepare_decode_step(q, x_k_new, x_v_new, k_codes, v_codes, k_centroids, v_centroids, scale: float,
                         fmt: CQFormat, t: int, t_cap: int, seq_lens=None, tokens_per_split: int = 0,
                         out=None, workspace=None):
@@ -432,7 +493,7 @@ def cq_encode_kv_paged(x_k, x_v, k_centroids, v_centroids, fmt: CQFormat, k_pool
 
 
 def _paged_decode(fn_name, q, x_k_new, x_v_new, k_pool, v_pool, k_centroids, v_centroids, scale, fmt, t, pages, seq_lens,
-                  tokens_per_split, out, workspace, stream):
+                  tokens_per_split, out, workspace, stream, rope=None):
     import torch
     _dev(q, torch.float16, "q")
     if q.dim() != 3 or not q.is_contiguous() or q.shape[2] != fmt.head_dim:
@@ -457,7 +518,10 @@ def _paged_decode(fn_name, q, x_k_new, x_v_new, k_pool, v_pool, k_centroids, v_c
     common = (k_pool.data_ptr(), v_pool.data_ptr(), k_centroids.data_ptr(), v_centroids.data_ptr(), float(scale),
               ctypes.byref(fmt._c()), batch, n_q_heads, t, ctypes.byref(pages._c), sl_ptr, tokens_per_split,
               out.data_ptr(), workspace.data_ptr(), workspace.numel(), _stream_handle(stream))
-    if x_k_new is None:
+    if rope is not None:
+        st = load().cq_decode_attention_rope_paged(q.data_ptr(), *common[:12], rope.table.data_ptr(), rope.positions,
+                                                   *common[12:])
+    elif x_k_new is None:
         st = load().cq_decode_attention_paged(q.data_ptr(), *common)
     else:
         for name, x in (("x_k_new", x_k_new), ("x_v_new", x_v_new)):
@@ -478,6 +542,16 @@ def cq_decode_attention_paged(q, k_pool, v_pool, k_centroids, v_centroids, scale
     """cq_decode_attention over paged pools."""
     return _paged_decode("cq_decode_attention_paged", q, None, None, k_pool, v_pool, k_centroids, v_centroids, scale, fmt,
                          t, pages, seq_lens, tokens_per_split, out, workspace, stream)
+
+
+def cq_decode_attention_rope_paged(q, k_pool, v_pool, k_centroids, v_centroids, scale: float, fmt: CQFormat, t: int,
+                                   pages: PageTable, rope: RopeTable, seq_lens=None, tokens_per_split: int = 0,
+                                   out=None, workspace=None, stream=None):
+    """cq_decode_attention_rope over paged pools."""
+    if tokens_per_split == 0:
+        tokens_per_split = cq_decode_rope_default_split(fmt, int(q.shape[0]), int(q.shape[1]), t)
+    return _paged_decode("cq_decode_attention_rope_paged", q, None, None, k_pool, v_pool, k_centroids, v_centroids,
+                         scale, fmt, t, pages, seq_lens, tokens_per_split, out, workspace, stream, rope=rope)
 
 
 def cq_decode_step_paged(q, x_k_new, x_v_new, k_pool, v_pool, k_centroids, v_centroids, scale: float, fmt: CQFormat,

@@ -312,11 +312,14 @@ cq_status decode_common(const void* q, const void* x_k_new, const void* x_v_new,
                         float scale, const cq_format* fmt,
                         int32_t batch, int32_t n_q_heads, int32_t t, int32_t t_cap, const cq_page_table* pages,
                         const int32_t* seq_lens, int32_t tokens_per_split,
-                        void* out, void* workspace, size_t workspace_bytes, void* stream, bool step)
+                        void* out, void* workspace, size_t workspace_bytes, void* stream, bool step,
+                        const void* rope_table = nullptr, int32_t rope_positions = 0)
 {
     Derived f;
     cq_status st = derive(fmt, &f);
     if (st != CQ_OK) return st;
+    const bool rope = rope_positions != 0;
+    if (rope && (f.b != 8 || f.head_dim != 128)) return CQ_ERR_UNSUPPORTED;
     CacheMap map;
     if (pages) {
         if ((st = paged_map(f, pages, batch, &map, &t_cap)) != CQ_OK) return st;
@@ -338,9 +341,14 @@ cq_status decode_common(const void* q, const void* x_k_new, const void* x_v_new,
         if (x_row_stride < f.channels || x_row_stride % 8 != 0) return CQ_ERR_INVALID_ARG;
         if (k_codes == v_codes) return CQ_ERR_INVALID_ARG;
     }
+    if (rope) {
+        if (!rope_table || !aligned16(rope_table)) return CQ_ERR_INVALID_ARG;
+        if (rope_positions < 0 || rope_positions % kTileTokens != 0 || t > rope_positions) return CQ_ERR_INVALID_ARG;
+    }
+    const int max_tiles = rope ? decode_rope_max_tiles_per_split() : decode_max_tiles_per_split(f);
     const int tiles = tokens_per_split ? tokens_per_split / kTileTokens
-                                       : default_tiles_per_split(f, batch, n_q_heads, t);
-    if (tiles > decode_max_tiles_per_split(f)) return CQ_ERR_INVALID_ARG;
+                                       : std::min(max_tiles, default_tiles_per_split(f, batch, n_q_heads, t));
+    if (tiles > max_tiles) return CQ_ERR_INVALID_ARG;
     const int n_tiles = (t + kTileTokens - 1) / kTileTokens;
     const int n_split = (n_tiles + tiles - 1) / tiles;
     const size_t need = sizeof(float) * (size_t)batch * n_q_heads * n_split * (f.head_dim + kPartialHeader);
@@ -367,6 +375,7 @@ cq_status decode_common(const void* q, const void* x_k_new, const void* x_v_new,
     a.partials = static_cast<float*>(workspace);
     a.out = static_cast<uint16_t*>(out);
     a.f = f;
+    if (rope) return launch_decode_rope(a, static_cast<const float*>(rope_table), rope_positions, static_cast<hipStream_t>(stream));
     return launch_decode(a, static_cast<hipStream_t>(stream));
 }
 
@@ -421,6 +430,56 @@ cq_status cq_decode_step_paged(const void* q, const void* x_k_new, const void* x
     return decode_common(q, x_k_new, x_v_new, x_row_stride, k_pool, v_pool, k_centroids, v_centroids, scale, fmt,
                          batch, n_q_heads, t, 0, pages, seq_lens, tokens_per_split, out, workspace, workspace_bytes,
                          stream, true);
+}
+
+size_t cq_rope_table_bytes(int32_t head_dim, int32_t positions)
+{
+    if (head_dim != 128 || positions <= 0 || positions % kTileTokens != 0) return 0;
+    return sizeof(float) * rope_table_floats(positions);
+}
+
+cq_status cq_rope_table(double base, int32_t head_dim, int32_t positions, void* table, size_t table_bytes, void* stream)
+{
+    if (head_dim != 128) return CQ_ERR_UNSUPPORTED;
+    if (positions <= 0 || positions % kTileTokens != 0 || !table || !aligned16(table)) return CQ_ERR_INVALID_ARG;
+    if (!(base > 1.0) || !std::isfinite(base)) return CQ_ERR_INVALID_ARG;
+    if (table_bytes < sizeof(float) * rope_table_floats(positions)) return CQ_ERR_WORKSPACE_TOO_SMALL;
+    return launch_rope_table(base, positions, static_cast<float*>(table), static_cast<hipStream_t>(stream));
+}
+
+int32_t cq_decode_rope_default_split(const cq_format* fmt, int32_t batch, int32_t n_q_heads, int32_t t)
+{
+    Derived f;
+    if (derive(fmt, &f) != CQ_OK || f.b != 8 || f.head_dim != 128 || batch <= 0 || n_q_heads <= 0 || t <= 0) return 0;
+    return std::min(decode_rope_max_tiles_per_split(), default_tiles_per_split(f, batch, n_q_heads, t)) * kTileTokens;
+}
+
+cq_status cq_decode_attention_rope(const void* q, const void* k_codes, const void* v_codes,
+                                   const void* k_centroids, const void* v_centroids,
+                                   float scale, const cq_format* fmt,
+                                   int32_t batch, int32_t n_q_heads, int32_t t, int32_t t_cap,
+                                   const int32_t* seq_lens, int32_t tokens_per_split,
+                                   const void* rope_table, int32_t rope_positions,
+                                   void* out, void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (rope_positions <= 0) return CQ_ERR_INVALID_ARG;
+    return decode_common(q, nullptr, nullptr, 0, k_codes, v_codes, k_centroids, v_centroids, scale, fmt, batch,
+                         n_q_heads, t, t_cap, nullptr, seq_lens, tokens_per_split, out, workspace, workspace_bytes, stream,
+                         false, rope_table, rope_positions);
+}
+
+cq_status cq_decode_attention_rope_paged(const void* q, const void* k_pool, const void* v_pool,
+                                         const void* k_centroids, const void* v_centroids,
+                                         float scale, const cq_format* fmt,
+                                         int32_t batch, int32_t n_q_heads, int32_t t, const cq_page_table* pages,
+                                         const int32_t* seq_lens, int32_t tokens_per_split,
+                                         const void* rope_table, int32_t rope_positions,
+                                         void* out, void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (!pages || rope_positions <= 0) return CQ_ERR_INVALID_ARG;
+    return decode_common(q, nullptr, nullptr, 0, k_pool, v_pool, k_centroids, v_centroids, scale, fmt, batch,
+                         n_q_heads, t, 0, pages, seq_lens, tokens_per_split, out, workspace, workspace_bytes, stream,
+                         false, rope_table, rope_positions);
 }
 
 }  // extern "C"

@@ -31,300 +31,10 @@
 
 #include <mutex>
 
-#include "cq_internal.hpp"
+#include "cq_decode_common.hpp"
 
 namespace cq {
 namespace {
-
-typedef __attribute__((address_space(3))) float lds_f32;
-typedef __attribute__((address_space(3))) unsigned lds_u32;
-typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
-typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
-
-constexpr int kMinScoreFloats = 4096;         // the score buffer doubles as reduction scratch
-// fused step: 2 x Gh 64-bit (distance, index) minima, then the new token's fixed-point weight
-constexpr int kKeyFloats(int gh) { return 2 * 2 * gh + 2; }
-// reduction scratch: 64 words + one row of head_dim floats per wavefront
-constexpr int kScratchFloats(int nt, int head_dim) { return 64 + (nt / 64) * head_dim; }
-
-// Raw LDS accesses by byte address.  The table sits at LDS address 0 (the kernels declare no
-// static LDS; the launcher checks that), so a table-relative address is an LDS address.
-__device__ __forceinline__ float lds_load(unsigned byte_addr) { return *(lds_f32*)(byte_addr); }
-__device__ __forceinline__ void lds_add(unsigned byte_addr, unsigned v)
-{
-    __hip_atomic_fetch_add((lds_u32*)(byte_addr), v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-}
-
-// Workgroup barrier that orders LDS traffic only.  __syncthreads() would also wait for every
-// outstanding global load, i.e. for the code tiles that are deliberately kept in flight across
-// the barriers of this kernel.  (No barrier here orders global memory: what the workgroup
-// exchanges lives in LDS.)
-__device__ __forceinline__ void lds_barrier()
-{
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
-    __builtin_amdgcn_s_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
-}
-
-__device__ __forceinline__ float wave_max(float v)
-{
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o));
-    return v;
-}
-__device__ __forceinline__ float wave_sum(float v)
-{
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
-    return v;
-}
-__device__ __forceinline__ unsigned wave_sum_u32(unsigned v)
-{
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
-    return v;
-}
-
-__device__ __forceinline__ void lds_min_u64(unsigned long long* p, unsigned long long v)
-{
-    __hip_atomic_fetch_min(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-}
-
-// Nearest-centroid search of the fused decode step, bit-identical to cq_encode: squared distance
-// in fp32, one fused multiply-add per channel in channel order.  x - c is formed as
-// fma(c, -1, x): one rounding like the subtraction, and the fp16 centroid is read directly by
-// the mixed-precision FMA.  A thread walks its centroids in ascending index order and keeps
-// the first minimum; (distance bits, index) packed into 64 bits then make the minimum over
-// threads the nearest centroid with the lowest index among equals.
-template <int C>
-__device__ __forceinline__ float centroid_distance(const float (&x)[C], const unsigned* halves)
-{
-    float acc = 0.f;
-#pragma unroll
-    for (int i = 0; i < C / 2; ++i) {
-        const half2_t h = __builtin_bit_cast(half2_t, halves[i]);
-        const float d0 = __builtin_fmaf((float)h.x, -1.0f, x[2 * i]);
-        acc = __builtin_fmaf(d0, d0, acc);
-        const float d1 = __builtin_fmaf((float)h.y, -1.0f, x[2 * i + 1]);
-        acc = __builtin_fmaf(d1, d1, acc);
-    }
-    return acc;
-}
-struct Nearest {
-    float d = __builtin_inff();
-    int j = 0;
-    __device__ __forceinline__ void offer(float dist, int idx)
-    {
-        j = dist < d ? idx : j;
-        d = dist < d ? dist : d;
-    }
-    __device__ __forceinline__ unsigned long long key() const
-    {
-        return ((unsigned long long)__float_as_uint(d) << 32) | (unsigned)j;
-    }
-};
-
-template <int C>
-__device__ __forceinline__ void load_row_slice(const uint16_t* p, float (&x)[C])
-{
-#pragma unroll
-    for (int i = 0; i < C / 2; ++i) {
-        const half2_t h = __builtin_bit_cast(half2_t, *reinterpret_cast<const unsigned*>(p + 2 * i));
-        x[2 * i] = (float)h.x;
-        x[2 * i + 1] = (float)h.y;
-    }
-}
-
-// minimum over the four lanes l, l+16, l+32, l+48 that walk the same group
-__device__ __forceinline__ unsigned long long group_lanes_min(unsigned long long key)
-{
-    unsigned long long o = __shfl_xor(key, 16);
-    key = o < key ? o : key;
-    o = __shfl_xor(key, 32);
-    return o < key ? o : key;
-}
-
-// Fixed-point scale for the probabilities of one split: with l_est = sum_t 2^(s_t - m) (fp32),
-// 2^29 <= 2^e * l_est < 2^30, so no bin (each holds a partial sum of the p_t) can overflow 32
-// bits, and each p_t is kept to an absolute error of 2^-(e+1) <= 2^-30 * l_est.
-__device__ __forceinline__ int fixed_point_exponent(float l_est)
-{
-    int ex;
-    (void)frexpf(l_est, &ex);           // l_est = f * 2^ex, f in [0.5, 1)
-    return 30 - ex;
-}
-
-// Format constants.
-template <int GH, int B>
-struct Fmt {
-    static constexpr int K = 1 << B;                    // rows
-    static constexpr int RW = B == 8 ? 64 : 32;         // words per row
-    static constexpr int R = GH == 16 ? 2 : 1;          // replicas per group
-    static constexpr bool SCORES_IN_TABLE = B == 8 && GH <= 32;   // words 32..63 of each row
-    static constexpr int P = GH / 16;                   // 16-byte planes of low code bytes
-    static constexpr int TAB_FLOATS = K * RW;
-    static constexpr int TILE_BYTES = kTileTokens * GH * B / 8;
-    static_assert(B == 8 || (B == 10 && GH == 16), "formats: b = 8, or b = 10 with 16 groups per head");
-    static_assert(GH == 16 || GH == 32 || GH == 64, "groups per head must be 16, 32 or 64");
-};
-
-// Word column of lane `lane` when it handles group g.
-template <int GH, int B>
-__device__ __forceinline__ int column(int lane, int g)
-{
-    if constexpr (GH == 16) {
-        return 2 * g + ((lane >> 4) & 1);       // lanes l and l + 16 differ, l and l + 32 share
-    } else {
-        (void)lane;
-        return g;
-    }
-}
-
-// 16 bytes of fp16 centroids: 8 / C consecutive centroids of one group.
-struct Cent16 {
-    unsigned w[4];
-};
-__device__ __forceinline__ Cent16 load_cent16(const uint16_t* p)
-{
-    const uint4 a = *reinterpret_cast<const uint4*>(p);
-    return Cent16{{a.x, a.y, a.z, a.w}};
-}
-
-// The codes of one 64-token tile, one token per lane.
-template <int GH, int B>
-struct Tile {
-    u32x4 lo[GH / 16];
-    unsigned hi;                        // b = 10 only: bits [2s+1 : 2s] = high bits of slot s
-};
-
-template <int GH, int B>
-__device__ __forceinline__ Tile<GH, B> load_tile(const uint8_t* base, int lane)
-{
-    Tile<GH, B> w;
-    const u32x4* p = reinterpret_cast<const u32x4*>(base) + lane;
-#pragma unroll
-    for (int pl = 0; pl < GH / 16; ++pl) w.lo[pl] = __builtin_nontemporal_load(p + pl * 64);
-    if constexpr (B == 10)
-        w.hi = __builtin_nontemporal_load(reinterpret_cast<const unsigned*>(base + kTileTokens * GH) + lane);
-    else
-        w.hi = 0;
-    return w;
-}
-
-// A wavefront's tiles of one code stream: tile k of its walk is tile first + k stride of the
-// (sequence, KV head).  Contiguous cache: consecutive tiles are TILE_BYTES apart from `base`.
-// Paged cache: lane j of `pages` holds the page of the walk's j-th tile (read once, before the
-// walk; a walk has at most 64 tiles), and a tile sits at base + page * page_bytes.
-template <int GH, int B>
-struct TileWalk {
-    const uint8_t* base;
-    int first, stride;
-    int pages;                  // per lane
-    size_t page_bytes;          // 0: contiguous
-    __device__ __forceinline__ const uint8_t* at(int k) const
-    {
-        if (page_bytes) return base + (size_t)__builtin_amdgcn_readlane(pages, k) * page_bytes;
-        return base + (size_t)(first + k * stride) * Fmt<GH, B>::TILE_BYTES;
-    }
-};
-
-// Per-lane column constants for the Gh steps: b = 8 packs 4 byte offsets per register (the
-// v_perm_b32 picks one), b = 10 keeps one register per step.
-template <int GH, int B>
-struct Columns {
-    unsigned v[B == 8 ? GH / 4 : GH];
-    __device__ __forceinline__ void init(int lane)
-    {
-        if constexpr (B == 8) {
-#pragma unroll
-            for (int i = 0; i < GH / 4; ++i) {
-                unsigned x = 0;
-#pragma unroll
-                for (int k = 0; k < 4; ++k) {
-                    const int g = (lane + 4 * i + k) & (GH - 1);
-                    x |= (unsigned)(4 * column<GH, B>(lane, g)) << (8 * k);
-                }
-                v[i] = x;
-            }
-        } else {
-#pragma unroll
-            for (int s = 0; s < GH; ++s) v[s] = 4u * (unsigned)column<GH, B>(lane, (lane + s) & (GH - 1));
-        }
-    }
-};
-
-// Byte address of the table word for slot s of this lane's token.
-template <int GH, int B>
-__device__ __forceinline__ unsigned slot_addr(const Tile<GH, B>& w, const Columns<GH, B>& col, int s)
-{
-    const u32x4 q = w.lo[s >> 4];
-    const int dw = (s >> 2) & 3;
-    const unsigned code_word = dw == 0 ? q.x : dw == 1 ? q.y : dw == 2 ? q.z : q.w;
-    const unsigned k = s & 3;
-    if constexpr (B == 8) {
-        const unsigned sel = 0x0c0c0000u | ((4u + k) << 8) | k;   // {0, 0, code byte k, column byte k}
-        return __builtin_amdgcn_perm(code_word, col.v[s >> 2], sel);
-    } else {
-        const unsigned lo = (code_word >> (8 * k)) & 0xffu;
-        const unsigned hi = (w.hi >> (2 * s)) & 3u;
-        return ((lo << 7) | (hi << 15)) | col.v[s];
-    }
-}
-
-// Walk tiles first, first + stride, ... (n of them) of a code stream with PF tiles in flight.
-// begin() requests the first tiles (so that the latency overlaps whatever the caller does
-// next); run() consumes.  The steady state is straight-line code (consume one tile, request the
-// tile PF steps ahead) so that the compiler keeps PF loads outstanding; the last tiles are
-// requested together and then consumed.  `fn(words, k)` is called once per tile k = 0 .. n-1.
-template <int GH, int B, int PF>
-struct Streamer {
-    static constexpr int TAIL = 2 * PF - 1;
-    Tile<GH, B> buf[TAIL];
-
-    __device__ __forceinline__ void begin(const TileWalk<GH, B>& tw, int n, int lane)
-    {
-        if (n >= 2 * PF) {
-#pragma unroll
-            for (int i = 0; i < PF; ++i) {
-                buf[i] = load_tile<GH, B>(tw.at(i), lane);
-                __builtin_amdgcn_sched_barrier(0);      // keep request order == consumption order
-            }
-        } else {
-#pragma unroll
-            for (int i = 0; i < TAIL; ++i)
-                if (i < n) buf[i] = load_tile<GH, B>(tw.at(i), lane);
-        }
-    }
-
-    // `last_requests()` is called once, after the last tile has been requested and before the
-    // last tiles are consumed: loads the caller issues there ride behind the stream.
-    template <class Fn, class Hook>
-    __device__ __forceinline__ void run(const TileWalk<GH, B>& tw, int n, int lane, Fn&& fn, Hook&& last_requests)
-    {
-        int k = 0;
-        if (n >= 2 * PF) {
-            for (; k + 2 * PF <= n; k += PF) {
-#pragma unroll
-                for (int i = 0; i < PF; ++i) {
-                    fn(buf[i], k + i);
-                    buf[i] = load_tile<GH, B>(tw.at(k + PF + i), lane);
-                    __builtin_amdgcn_sched_barrier(0);
-                }
-            }
-#pragma unroll
-            for (int i = 0; i < PF; ++i) fn(buf[i], k + i);
-            k += PF;
-#pragma unroll
-            for (int i = 0; i < TAIL; ++i)
-                if (k + i < n) buf[i] = load_tile<GH, B>(tw.at(k + i), lane);
-        }
-        last_requests();
-        __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-        for (int i = 0; i < TAIL; ++i)
-            if (k + i < n) fn(buf[i], k + i);
-    }
-};
 
 // Fused step: replace the codes of lane u_new's token in a tile's registers by the codes just
 // computed (keys[g] holds group g's (distance, index) minimum), exactly as the cache layout
@@ -843,6 +553,12 @@ cq_status launch_format(const DecodeArgs& a, hipStream_t stream)
 }
 
 }  // namespace
+
+cq_status launch_decode_merge(const float* partials, uint16_t* out, int rows, int n_split, int head_dim, hipStream_t stream)
+{
+    hipLaunchKernelGGL(decode_merge_kernel, dim3((unsigned)rows), dim3(128), 0, stream, partials, out, n_split, head_dim);
+    return hipGetLastError() == hipSuccess ? CQ_OK : CQ_ERR_HIP;
+}
 
 int decode_max_tiles_per_split(const Derived& f)
 {

@@ -1,0 +1,445 @@
+// Decode attention from packed CQ codes when the cached KEYS were quantized before the rotary
+// position embedding (Section 3.2 of the paper quantizes keys "before RoPE"; Eq. 1's f_K counts
+// the positional encoding in), for gfx950.  The paper cites RoPE without restating it; the form
+// implemented is the one of the models it evaluates (LLaMA, Mistral): channels i and i + d/2 of a
+// head form a pair that is rotated by position * base^(-2i/d); the query arrives already rotated.
+//
+// The rotation angle differs per channel pair, so the score of a token can no longer be summed
+// from one table entry per group.  Instead the rotation is moved to the query side,
+//     q . R_t k  =  sum_i  k_i a_i(t) + k_{i+64} b_i(t),
+//     a_i(t) = q_i cos(t th_i) + q_{i+64} sin(t th_i),  b_i(t) = q_{i+64} cos(t th_i) - q_i sin(t th_i),
+// and split by the angle-addition theorem into a per-tile part (t0 = 64 * tile: one rotated query
+// per tile and wavefront, lane i computing pair i, kept in LDS) and a per-lane part (the token's
+// offset within the tile: a table cos / sin(lane * th_i), 32 KB of LDS):
+//     a_i(t0 + u) = cos(u th_i) a_i(t0) + sin(u th_i) b_i(t0),   b_i(t0 + u) = cos(u th_i) b_i(t0) - sin(u th_i) a_i(t0).
+// Lane = token as in the position-independent kernel; the key centroids themselves (fp16, 64 KB
+// per head) take the place of the score table in LDS, and a token costs, per channel pair, two
+// 8-byte LDS reads and eight VALU instructions (against one gather and one add per GROUP
+// without rotation).  Phase V, the epilogue and the split-context merge are those of
+// cq_decode.hip.  Both trigonometric tables come from cq_rope_tables (computed in fp64).
+#include <mutex>
+
+#include "cq_decode_common.hpp"
+
+namespace cq {
+namespace {
+
+constexpr int kPairs = 64;                        // head_dim / 2
+constexpr unsigned kTabBytes = 65536;             // centroids (phase K), then bins (phase V)
+constexpr unsigned kTrgBytes = kPairs * 64 * 8;   // cos / sin(lane * theta_i)
+
+__global__ void rope_tables_kernel(double base, int n_tiles, float2* tile_tab, float2* lane_tab)
+{
+    const int idx = blockIdx.x * blockDim.x + threadIdx.x;
+    const int n_tile_entries = n_tiles * kPairs;
+    if (idx >= n_tile_entries + kPairs * 64) return;
+    int i;
+    double pos;
+    float2* dst;
+    if (idx < n_tile_entries) {
+        i = idx % kPairs;
+        pos = (double)(idx / kPairs) * 64.0;
+        dst = tile_tab + idx;
+    } else {
+        const int j = idx - n_tile_entries;
+        i = j / 64;
+        pos = (double)(j % 64);
+        dst = lane_tab + j;
+    }
+    const double ang = pos * pow(base, -2.0 * (double)i / 128.0);
+    *dst = make_float2((float)cos(ang), (float)sin(ang));
+}
+
+template <int C>
+struct CenVec {
+    unsigned w[C / 2];
+};
+template <int C>
+__device__ __forceinline__ CenVec<C> lds_centroid(unsigned byte_addr)
+{
+    typedef __attribute__((address_space(3))) unsigned lds_u;
+    CenVec<C> v;
+    if constexpr (C == 8) {
+        typedef unsigned u4 __attribute__((ext_vector_type(4)));
+        const u4 a = *(__attribute__((address_space(3))) u4*)(byte_addr);
+        v.w[0] = a.x; v.w[1] = a.y; v.w[2] = a.z; v.w[3] = a.w;
+    } else if constexpr (C == 4) {
+        typedef unsigned u2 __attribute__((ext_vector_type(2)));
+        const u2 a = *(__attribute__((address_space(3))) u2*)(byte_addr);
+        v.w[0] = a.x; v.w[1] = a.y;
+    } else {
+        v.w[0] = *(lds_u*)(byte_addr);
+    }
+    return v;
+}
+__device__ __forceinline__ float2 lds_load2(unsigned byte_addr)
+{
+    typedef float f2 __attribute__((ext_vector_type(2)));
+    const f2 a = *(__attribute__((address_space(3))) f2*)(byte_addr);
+    return make_float2(a.x, a.y);
+}
+__device__ __forceinline__ void lds_store2(unsigned byte_addr, float x, float y)
+{
+    typedef float f2 __attribute__((ext_vector_type(2)));
+    *(__attribute__((address_space(3))) f2*)(byte_addr) = f2{x, y};
+}
+
+// A token's codes in group order.  The cache stores the code of group (s + u) mod Gh in slot s
+// of token u (the position-independent kernel wants neighbouring lanes on different groups);
+// here every lane should work on the same channel pair at the same time (the rotated query is
+// then one broadcast read, and every address a compile-time offset), so the token's Gh bytes are
+// rotated by u positions once per tile: bytes first (v_alignbyte), then whole dwords (selects).
+struct Unrotate {
+    unsigned bytes;             // (Gh - u) mod 4
+    unsigned dwords;            // ((Gh - u) mod Gh) / 4
+};
+template <int GH>
+__device__ __forceinline__ void group_order(const Tile<GH, 8>& w, const Unrotate& r, unsigned (&d)[GH / 4])
+{
+    constexpr int N = GH / 4;
+    unsigned x[N];
+#pragma unroll
+    for (int i = 0; i < N; ++i) {
+        const u32x4 q = w.lo[i >> 2];
+        x[i] = (i & 3) == 0 ? q.x : (i & 3) == 1 ? q.y : (i & 3) == 2 ? q.z : q.w;
+    }
+    // group g sits in slot (g - u) mod Gh = (g + r) mod Gh with r = (Gh - u) mod Gh
+#pragma unroll
+    for (int i = 0; i < N; ++i) d[i] = __builtin_amdgcn_alignbyte(x[(i + 1) % N], x[i], r.bytes);
+#pragma unroll
+    for (int bit = 1; bit < N; bit <<= 1) {
+        const bool on = (r.dwords & bit) != 0;
+        unsigned y[N];
+#pragma unroll
+        for (int i = 0; i < N; ++i) y[i] = on ? d[(i + bit) % N] : d[i];
+#pragma unroll
+        for (int i = 0; i < N; ++i) d[i] = y[i];
+    }
+}
+
+template <int GH, int C, int NT>
+__global__ __launch_bounds__(NT) void decode_rope_kernel(DecodeArgs a, const float2* tile_tab, const float2* lane_tab)
+{
+    constexpr int B = 8;
+    using F = Fmt<GH, B>;
+    constexpr int K = F::K, RW = F::RW, R = F::R;
+    constexpr int NW = NT / 64;
+    constexpr int D = GH * C;
+    constexpr int HALF = GH / 2;                    // groups per half of the head
+    constexpr int PF = GH == 16 ? 4 : (GH == 32 ? 2 : 1);
+    constexpr int JPL = 8 / C;
+    constexpr int NCH = GH / 16;
+    constexpr int UNITS = 16 * K / JPL;
+    constexpr int IPT = UNITS / NT;
+    static_assert(D == 128 && UNITS % NT == 0, "head_dim 128");
+    constexpr unsigned Q0_BASE = kTabBytes + kTrgBytes;
+    constexpr unsigned SC_BASE = Q0_BASE + NW * kPairs * 8;
+    extern __shared__ float smem[];
+    float* tab = smem;                                              // bins in phase V
+    float* sc = smem + SC_BASE / 4;                                 // scores of the split
+    float* scr = smem + kTabBytes / 4;                              // reductions (the lane table is dead by then)
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+
+    // workgroup -> (sequence, split, query head), KV head a function of blockIdx % 8 (see cq_decode.hip)
+    const int qper = a.n_q_heads / a.f.n_kv_heads;
+    int hq, split, n;
+    if (a.f.n_kv_heads % 8 == 0) {
+        const int xcd = blockIdx.x & 7;
+        int r = blockIdx.x >> 3;
+        const int per_xcd = a.f.n_kv_heads >> 3;
+        const int hkv_ = xcd + 8 * (r % per_xcd);
+        r /= per_xcd;
+        hq = hkv_ * qper + r % qper;
+        r /= qper;
+        split = r % a.n_split;
+        n = r / a.n_split;
+    } else {
+        int idx = blockIdx.x;
+        hq = idx % a.n_q_heads;
+        idx /= a.n_q_heads;
+        split = idx % a.n_split;
+        n = idx / a.n_split;
+    }
+    const int hkv = hq / qper;
+
+    int t_n = a.t;
+    if (a.seq_lens) t_n = min(max(a.seq_lens[n], 1), a.t);
+    const int n_tiles = (t_n + kTileTokens - 1) / kTileTokens;
+    const int tile0 = split * a.tiles_per_split;
+    const int tile1 = min(tile0 + a.tiles_per_split, n_tiles);
+    float* part = a.partials + ((size_t)(n * a.n_q_heads + hq) * a.n_split + split) * (D + kPartialHeader);
+    if (tile0 >= tile1) {
+        if (tid == 0) { part[0] = -INFINITY; part[1] = 0.f; }
+        for (int i = tid; i < D; i += NT) part[kPartialHeader + i] = 0.f;
+        return;
+    }
+
+    Columns<GH, B> col;
+    const int my_tiles = (tile1 - tile0 - wave + NW - 1) / NW;
+    TileWalk<GH, B> kwalk, vwalk;
+    kwalk.first = tile0 + wave;
+    kwalk.stride = NW;
+    kwalk.pages = 0;
+    if (a.map.block_table) {
+        if (lane < my_tiles) kwalk.pages = a.map.page(n, tile0 + wave + lane * NW);
+        kwalk.page_bytes = (size_t)a.f.n_kv_heads * F::TILE_BYTES;
+        kwalk.base = a.k_codes + (size_t)hkv * F::TILE_BYTES;
+        vwalk = kwalk;
+        vwalk.base = a.v_codes + (size_t)hkv * F::TILE_BYTES;
+    } else {
+        const size_t stream_idx = a.map.tile_index(n, hkv, 0) * F::TILE_BYTES;
+        kwalk.page_bytes = 0;
+        kwalk.base = a.k_codes + stream_idx;
+        vwalk = kwalk;
+        vwalk.base = a.v_codes + stream_idx;
+    }
+    Streamer<GH, B, PF> st;
+
+    // ---- 1. the head's key centroids and the lane table go to LDS; this lane's query pair ----
+    {
+        const uint4* src = reinterpret_cast<const uint4*>(a.k_centroids + (size_t)hkv * GH * K * C);
+        for (int i = tid; i < (int)(kTabBytes / 16); i += NT) reinterpret_cast<uint4*>(smem)[i] = src[i];
+        const uint4* lt = reinterpret_cast<const uint4*>(lane_tab);
+        for (int i = tid; i < (int)(kTrgBytes / 16); i += NT) reinterpret_cast<uint4*>(smem + kTabBytes / 4)[i] = lt[i];
+    }
+    const uint16_t* qh = a.q + (size_t)(n * a.n_q_heads + hq) * D;
+    const float qa = (float)__builtin_bit_cast(_Float16, qh[lane]) * a.scale_log2e;
+    const float qb = (float)__builtin_bit_cast(_Float16, qh[lane + kPairs]) * a.scale_log2e;
+    st.begin(kwalk, my_tiles, lane);
+    // cos / sin of the first tile's base position for this lane's pair (one tile ahead from now on)
+    auto tile_cs = [&](int k) {
+        const int kk = k < my_tiles ? k : (my_tiles > 0 ? my_tiles - 1 : 0);
+        const int tile = my_tiles > 0 ? tile0 + wave + kk * NW : tile0;
+        return tile_tab[(size_t)tile * kPairs + lane];
+    };
+    float2 cs_next = tile_cs(0);
+    lds_barrier();
+
+    // ---- 2. phase K: scores ----------------------------------------------------------------
+    const unsigned q0_wave = Q0_BASE + (unsigned)wave * (kPairs * 8);
+    const unsigned trg_lane = kTabBytes + (unsigned)lane * 8;
+    Unrotate unrot;
+    unrot.bytes = (unsigned)(GH - lane) & 3u;
+    unrot.dwords = ((unsigned)(GH - lane) & (unsigned)(GH - 1)) >> 2;
+    float lane_max = -INFINITY;
+    st.run(kwalk, my_tiles, lane, [&](const Tile<GH, B>& w, int k) {
+        const int lt = wave + k * NW;
+        // the query rotated to the tile's base position: lane i holds pair i
+        const float2 cs = cs_next;
+        cs_next = tile_cs(k + 1);
+        lds_store2(q0_wave + (unsigned)lane * 8, __builtin_fmaf(qa, cs.x, qb * cs.y), __builtin_fmaf(qb, cs.x, -(qa * cs.y)));
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront", "local");
+        __builtin_amdgcn_wave_barrier();
+        // codes in group order: byte g of d[] is the code of group g
+        unsigned d[GH / 4];
+        group_order<GH>(w, unrot, d);
+        // the two table bases are re-materialised per tile: were they loop invariants, the
+        // compiler would keep base + offset of every channel pair in a register of its own
+        // (128 of them) instead of using the offset field of the LDS instructions
+        unsigned q0_base = q0_wave, trg_base = trg_lane;
+        asm volatile("" : "+v"(q0_base), "+v"(trg_base));
+        float acc0 = 0.f, acc1 = 0.f;
+#pragma unroll
+        for (int g = 0; g < HALF; ++g) {
+            const unsigned c_first = (d[g >> 2] >> (8 * (g & 3))) & 0xffu;                       // channels < 64
+            const unsigned c_second = (d[(g + HALF) >> 2] >> (8 * ((g + HALF) & 3))) & 0xffu;    // their partners
+            const CenVec<C> ka = lds_centroid<C>(c_first * (C * 2) + (unsigned)(g * K * C * 2));
+            const CenVec<C> kb = lds_centroid<C>(c_second * (C * 2) + (unsigned)((g + HALF) * K * C * 2));
+#pragma unroll
+            for (int j = 0; j < C; ++j) {
+                const int i = g * C + j;                                    // channel pair (i, i + 64)
+                const float2 q0 = lds_load2(q0_base + i * 8);               // same address in every lane
+                const float2 tr = lds_load2(trg_base + i * 512);
+                const float av = __builtin_fmaf(tr.x, q0.x, tr.y * q0.y);
+                const float bv = __builtin_fmaf(tr.x, q0.y, -(tr.y * q0.x));
+                const half2_t ha = __builtin_bit_cast(half2_t, ka.w[j >> 1]);
+                const half2_t hb = __builtin_bit_cast(half2_t, kb.w[j >> 1]);
+                const float kav = (float)((j & 1) ? ha.y : ha.x), kbv = (float)((j & 1) ? hb.y : hb.x);
+                acc0 = __builtin_fmaf(kav, av, acc0);
+                acc1 = __builtin_fmaf(kbv, bv, acc1);
+            }
+        }
+        const int tok = (tile0 + lt) * kTileTokens + lane;
+        const float sv = tok < t_n ? acc0 + acc1 : -INFINITY;
+        sc[lt * kTileTokens + lane] = sv;
+        lane_max = fmaxf(lane_max, sv);
+        __builtin_amdgcn_wave_barrier();
+    }, [] {});
+    st.begin(vwalk, my_tiles, lane);
+
+    lane_max = wave_max(lane_max);
+    lds_barrier();                                  // all centroid / table reads done, all scores written
+    if (lane == 0) scr[wave] = lane_max;
+    lds_barrier();
+    float m = scr[0];
+#pragma unroll
+    for (int w = 1; w < NW; ++w) m = fmaxf(m, scr[w]);
+    float l_est = 0.f;
+    for (int i = tid; i < (tile1 - tile0) * kTileTokens; i += NT) l_est += __builtin_amdgcn_exp2f(sc[i] - m);
+    l_est = wave_sum(l_est);
+    if (lane == 0) scr[32 + wave] = l_est;
+    lds_barrier();
+    l_est = 0.f;
+#pragma unroll
+    for (int w = 0; w < NW; ++w) l_est += scr[32 + w];
+    const int fx = fixed_point_exponent(l_est);
+    const float fx_scale = ldexpf(1.f, fx), fx_inv = ldexpf(1.f, -fx);
+    {
+        float4* t4 = reinterpret_cast<float4*>(tab);
+#pragma unroll 4
+        for (int i = tid; i < F::TAB_FLOATS / 4; i += NT) t4[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+    }
+    lds_barrier();
+
+    // ---- 3. phase V: probability bins (as in the position-independent kernel) -------------
+    col.init(lane);
+    const int gl16 = tid & 15;
+    constexpr int KB = IPT < 8 ? IPT : 8;
+    constexpr bool EARLY = IPT * NCH <= 8 && KB == IPT;
+    Cent16 rawv[EARLY ? NCH : 1][KB];
+    unsigned lane_sum = 0;
+    st.run(vwalk, my_tiles, lane, [&](const Tile<GH, B>& w, int k) {
+        const int lt = wave + k * NW;
+        const float p = __builtin_amdgcn_exp2f(sc[lt * kTileTokens + lane] - m);
+        const unsigned pf = (unsigned)__builtin_fmaf(p, fx_scale, 0.5f);
+        lane_sum += pf;
+#pragma unroll
+        for (int s = 0; s < GH; ++s) lds_add(slot_addr<GH, B>(w, col, s), pf);
+    }, [&] {
+        if constexpr (EARLY) {
+#pragma unroll
+            for (int ch = 0; ch < NCH; ++ch) {
+                const uint16_t* cv = a.v_centroids + (size_t)(hkv * GH + ch * 16 + gl16) * K * C;
+#pragma unroll
+                for (int k = 0; k < IPT; ++k) rawv[ch][k] = load_cent16(cv + (size_t)((tid + k * NT) >> 4) * 8);
+            }
+        }
+    });
+
+    // ---- 4. epilogue: o = bins . C_V -------------------------------------------------------
+    lane_sum = wave_sum_u32(lane_sum);
+    lds_barrier();
+    if (lane == 0) scr[wave] = __uint_as_float(lane_sum);
+    float acc[NCH][C];
+#pragma unroll
+    for (int ch = 0; ch < NCH; ++ch) {
+#pragma unroll
+        for (int i = 0; i < C; ++i) acc[ch][i] = 0.f;
+#pragma unroll
+        for (int k0 = 0; k0 < IPT; k0 += KB) {
+            if constexpr (!EARLY) {
+                const uint16_t* cv = a.v_centroids + (size_t)(hkv * GH + ch * 16 + gl16) * K * C;
+#pragma unroll
+                for (int k = 0; k < KB; ++k) rawv[0][k] = load_cent16(cv + (size_t)((tid + (k0 + k) * NT) >> 4) * 8);
+            }
+            const Cent16 (&raw)[KB] = rawv[EARLY ? ch : 0];
+#pragma unroll
+            for (int k = 0; k < KB; ++k) {
+                const int j0 = ((tid + (k0 + k) * NT) >> 4) * JPL;
+#pragma unroll
+                for (int jj = 0; jj < JPL; ++jj) {
+                    const float* src = tab + (j0 + jj) * RW + (ch * 16 + gl16) * R;
+                    unsigned cnt;
+                    if constexpr (R == 2) { const uint2 x = *reinterpret_cast<const uint2*>(src); cnt = x.x + x.y; }
+                    else cnt = *reinterpret_cast<const unsigned*>(src);
+                    const float bin = (float)cnt * fx_inv;
+#pragma unroll
+                    for (int i = 0; i < C / 2; ++i) {
+                        const half2_t h = __builtin_bit_cast(half2_t, raw[k].w[jj * (C / 2) + i]);
+                        acc[ch][2 * i] = __builtin_fmaf(bin, (float)h.x, acc[ch][2 * i]);
+                        acc[ch][2 * i + 1] = __builtin_fmaf(bin, (float)h.y, acc[ch][2 * i + 1]);
+                    }
+                }
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < C; ++i) {
+            acc[ch][i] += __shfl_xor(acc[ch][i], 16);
+            acc[ch][i] += __shfl_xor(acc[ch][i], 32);
+        }
+    }
+    if (lane < 16) {
+#pragma unroll
+        for (int ch = 0; ch < NCH; ++ch)
+#pragma unroll
+            for (int i = 0; i < C; ++i) scr[64 + wave * D + (ch * 16 + gl16) * C + i] = acc[ch][i];
+    }
+    lds_barrier();
+    unsigned l_fix = 0;
+#pragma unroll
+    for (int w = 0; w < NW; ++w) l_fix += __float_as_uint(scr[w]);
+    const float l = (float)l_fix * fx_inv;
+    const bool direct = a.n_split == 1;
+    if (tid == 0 && !direct) {
+        part[0] = m;
+        part[1] = l;
+    }
+    for (int chn = tid; chn < D; chn += NT) {
+        float o = 0.f;
+#pragma unroll
+        for (int w = 0; w < NW; ++w) o += scr[64 + w * D + chn];
+        if (direct) a.out[(size_t)(n * a.n_q_heads + hq) * D + chn] = __builtin_bit_cast(uint16_t, (_Float16)(o / l));
+        else part[kPartialHeader + chn] = o;
+    }
+}
+
+template <int GH, int C>
+cq_status launch_rope_variant(const DecodeArgs& a, const float2* tile_tab, const float2* lane_tab, hipStream_t stream)
+{
+    constexpr int NT = 1024;
+    auto kernel = decode_rope_kernel<GH, C, NT>;
+    static std::once_flag once;
+    static hipError_t setup = hipSuccess;
+    std::call_once(once, [&] {
+        hipFuncAttributes attr;
+        setup = hipFuncGetAttributes(&attr, reinterpret_cast<const void*>(kernel));
+        // LDS is addressed from 0: no static LDS may precede the dynamic block
+        if (setup == hipSuccess && attr.sharedSizeBytes != 0) setup = hipErrorInvalidValue;
+        if (setup == hipSuccess)
+            setup = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+    });
+    if (setup != hipSuccess) return CQ_ERR_HIP;
+    const size_t smem = kTabBytes + kTrgBytes + (NT / 64) * kPairs * 8 + (size_t)a.tiles_per_split * kTileTokens * 4;
+    if (smem > 160 * 1024) return CQ_ERR_INVALID_ARG;
+    const unsigned grid = (unsigned)(a.batch * a.n_q_heads * a.n_split);
+    hipLaunchKernelGGL(kernel, dim3(grid), dim3(NT), smem, stream, a, tile_tab, lane_tab);
+    return hipGetLastError() == hipSuccess ? CQ_OK : CQ_ERR_HIP;
+}
+
+}  // namespace
+
+int decode_rope_max_tiles_per_split() { return 128; }
+
+size_t rope_table_floats(int t_cap) { return ((size_t)(t_cap / kTileTokens) * kPairs + (size_t)kPairs * 64) * 2; }
+
+cq_status launch_rope_table(double base, int t_cap, float* tables, hipStream_t stream)
+{
+    const int n_tiles = t_cap / kTileTokens;
+    float2* tile_tab = reinterpret_cast<float2*>(tables);
+    float2* lane_tab = tile_tab + (size_t)n_tiles * kPairs;
+    const int total = n_tiles * kPairs + kPairs * 64;
+    hipLaunchKernelGGL(rope_tables_kernel, dim3((total + 255) / 256), dim3(256), 0, stream, base, n_tiles, tile_tab, lane_tab);
+    return hipGetLastError() == hipSuccess ? CQ_OK : CQ_ERR_HIP;
+}
+
+cq_status launch_decode_rope(const DecodeArgs& a, const float* tables, int t_cap, hipStream_t stream)
+{
+    const float2* tile_tab = reinterpret_cast<const float2*>(tables);
+    const float2* lane_tab = tile_tab + (size_t)(t_cap / kTileTokens) * kPairs;
+    cq_status st = CQ_ERR_UNSUPPORTED;
+    if (a.f.b == 8 && a.f.head_dim == 128) {
+        if (a.f.gh == 16 && a.f.c == 8) st = launch_rope_variant<16, 8>(a, tile_tab, lane_tab, stream);
+        else if (a.f.gh == 32 && a.f.c == 4) st = launch_rope_variant<32, 4>(a, tile_tab, lane_tab, stream);
+        else if (a.f.gh == 64 && a.f.c == 2) st = launch_rope_variant<64, 2>(a, tile_tab, lane_tab, stream);
+    }
+    if (st != CQ_OK) return st;
+    if (a.n_split > 1)
+        return launch_decode_merge(a.partials, a.out, a.batch * a.n_q_heads, a.n_split, a.f.head_dim, stream);
+    return CQ_OK;
+}
+
+}  // namespace cq

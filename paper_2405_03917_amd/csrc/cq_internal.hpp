@@ -132,5 +132,15 @@ cq_status launch_encode(const EncodeArgs& a, hipStream_t stream);
 // many tokens per sequence: the MFMA-filtered kernel (cq_encode_mfma.hip)
 cq_status launch_encode_tiles(const EncodeArgs& a, hipStream_t stream);
 cq_status launch_decode(const DecodeArgs& a, hipStream_t stream);
+// merges the partials of `rows` (sequence, query head) pairs, n_split each, into fp16 rows
+cq_status launch_decode_merge(const float* partials, uint16_t* out, int rows, int n_split, int head_dim, hipStream_t stream);
+
+// Keys cached before the rotary position embedding (cq_decode_rope.hip).  The table holds, for
+// head_dim 128, cos / sin of (64 * tile) * theta_i for every tile of `positions` tokens, then
+// cos / sin of u * theta_i for u < 64 (theta_i = base^(-2i/128), i < 64).
+size_t rope_table_floats(int positions);
+cq_status launch_rope_table(double base, int positions, float* table, hipStream_t stream);
+int decode_rope_max_tiles_per_split();
+cq_status launch_decode_rope(const DecodeArgs& a, const float* table, int positions, hipStream_t stream);
 
 }  // namespace cq

@@ -1,0 +1,162 @@
+"""GPU parity of decode attention over keys cached before the rotary position embedding
+(cq_decode_attention_rope) against the CPU oracle (attention with rope_base), element by element:
+every supported format, lengths around the tile size, split contexts, ragged batches, grouped
+queries, paged pools, long contexts (large angles)."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import paper_2405_03917_amd as cq
+import synth
+from oracle import cq_oracle as O
+
+from gpu_util import check_attention, codes_to_cache, dev, gpu_attention
+
+pytestmark = pytest.mark.gpu
+
+ROPE_FORMATS = [(8, 8), (4, 8), (2, 8)]
+BASE = 10000.0
+
+
+def _case(seed, c, b, hq, hkv, B, T):
+    rng = np.random.default_rng(1000 + seed)
+    fmt = cq.CQFormat(c, b, 128, hkv)
+    D = hkv * 128
+    ck = synth.sample_codebook(synth.tensor_recipe(40 + seed, 0, "k", D), c, b)
+    cv = synth.sample_codebook(synth.tensor_recipe(40 + seed, 0, "v", D), c, b)
+    kc = rng.integers(0, 1 << b, size=(B, T, fmt.groups)).astype(np.uint16)
+    vc = rng.integers(0, 1 << b, size=(B, T, fmt.groups)).astype(np.uint16)
+    q = rng.standard_normal((B, hq, 128)).astype(np.float16)
+    return fmt, q, kc, vc, ck, cv
+
+
+def _gpu(q, kcache, vcache, ck, cv, scale, fmt, T, t_cap, rope, seq_lens=None, split=0):
+    sl = None if seq_lens is None else dev(np.asarray(seq_lens, dtype=np.int32))
+    out = cq.cq_decode_attention_rope(dev(q), kcache, vcache, dev(ck), dev(cv), scale, fmt, T, t_cap, rope,
+                                      seq_lens=sl, tokens_per_split=split)
+    torch.cuda.synchronize()
+    return out.cpu().numpy()
+
+
+def test_rope_table_holds_cos_and_sin_of_tile_bases_and_lane_offsets():
+    positions = 64 * 300
+    rope = cq.RopeTable(BASE, positions)
+    torch.cuda.synchronize()
+    tab = rope.table.cpu().numpy().view(np.float32).reshape(-1, 2)
+    theta = BASE ** (-2.0 * np.arange(64) / 128.0)
+    tiles = (np.arange(300)[:, None] * 64.0) * theta[None, :]              # [tile][pair]
+    lanes = theta[:, None] * np.arange(64.0)[None, :]                      # [pair][lane]
+    want = np.concatenate([tiles.reshape(-1), lanes.reshape(-1)])
+    assert tab.shape[0] == want.size
+    # fp64 evaluation rounded once to fp32: half an ulp of a value <= 1, plus the fp64 error of the
+    # angle (<= 2^-52 * 19200)
+    assert np.max(np.abs(tab[:, 0] - np.cos(want))) <= 2.0 ** -24
+    assert np.max(np.abs(tab[:, 1] - np.sin(want))) <= 2.0 ** -24
+
+
+@pytest.mark.parametrize("c,b", ROPE_FORMATS)
+@pytest.mark.parametrize("T", [1, 63, 64, 65, 1000])
+def test_rope_attention_matches_oracle(c, b, T):
+    hq, hkv, B, t_cap = 4, 2, 2, 1024
+    fmt, q, kc, vc, ck, cv = _case(T, c, b, hq, hkv, B, T)
+    scale = 1.0 / math.sqrt(128)
+    rope = cq.RopeTable(BASE, 1024)
+    ref = O.attention(q, kc, vc, ck, cv, scale, hkv, rope_base=BASE)
+    out = _gpu(q, codes_to_cache(kc, fmt, t_cap), codes_to_cache(vc, fmt, t_cap), ck, cv, scale, fmt, T, t_cap, rope)
+    check_attention(out, ref)
+    # the rotation matters: without it the result is a different one (except for a single token,
+    # where the output is the value row whatever the score)
+    if T > 1:
+        plain = O.attention(q, kc, vc, ck, cv, scale, hkv)
+        assert np.max(np.abs(plain - ref)) > 1e-2 * np.max(np.abs(ref))
+
+
+@pytest.mark.parametrize("c,b", ROPE_FORMATS)
+def test_rope_split_invariance_and_ragged_lengths(c, b):
+    hq, hkv, B, T, t_cap = 4, 4, 3, 5000, 5056
+    fmt, q, kc, vc, ck, cv = _case(7, c, b, hq, hkv, B, T)
+    scale = 0.11
+    lens = np.array([5000, 1, 2500], dtype=np.int32)
+    rope = cq.RopeTable(BASE, 8192)                    # longer than the cache: only a prefix is read
+    ref = O.attention(q, kc, vc, ck, cv, scale, hkv, seq_lens=lens, rope_base=BASE)
+    kcache, vcache = codes_to_cache(kc, fmt, t_cap), codes_to_cache(vc, fmt, t_cap)
+    outs = []
+    for split in (0, 64, 448, 4032, 8192):
+        out = _gpu(q, kcache, vcache, ck, cv, scale, fmt, T, t_cap, rope, seq_lens=lens, split=split)
+        check_attention(out, ref)
+        outs.append(out.astype(np.float64))
+    for o in outs[1:]:
+        assert np.max(np.abs(o - outs[0])) <= 2e-3 * np.max(np.abs(outs[0]))
+
+
+def test_rope_grouped_queries_and_eight_kv_heads():
+    # 8 KV heads: the workgroup numbering that keeps a KV head on one XCD; 4 query heads per KV head
+    c, b, hq, hkv, B, T, t_cap = 4, 8, 32, 8, 2, 700, 704
+    fmt, q, kc, vc, ck, cv = _case(3, c, b, hq, hkv, B, T)
+    rope = cq.RopeTable(BASE, t_cap)
+    ref = O.attention(q, kc, vc, ck, cv, 0.09, hkv, rope_base=BASE)
+    out = _gpu(q, codes_to_cache(kc, fmt, t_cap), codes_to_cache(vc, fmt, t_cap), ck, cv, 0.09, fmt, T, t_cap, rope)
+    check_attention(out, ref)
+
+
+def test_rope_long_context_and_other_base():
+    # positions up to 40000: angles of tens of thousands of radians for the fast pairs
+    c, b, hq, hkv, B, T = 8, 8, 2, 1, 1, 40000
+    t_cap = 40000 // 64 * 64 + 64
+    fmt, q, kc, vc, ck, cv = _case(5, c, b, hq, hkv, B, T)
+    base = 500000.0
+    rope = cq.RopeTable(base, t_cap)
+    ref = O.attention(q, kc, vc, ck, cv, 0.1, hkv, rope_base=base)
+    out = _gpu(q, codes_to_cache(kc, fmt, t_cap), codes_to_cache(vc, fmt, t_cap), ck, cv, 0.1, fmt, T, t_cap, rope)
+    check_attention(out, ref)
+
+
+def test_rope_zero_query_gives_the_uniform_weights_of_plain_attention():
+    # q = 0: every score is 0 whatever the rotation, so the result equals the position-independent
+    # kernel's bit for bit (same bins, same epilogue)
+    c, b, hq, hkv, B, T, t_cap = 4, 8, 2, 2, 1, 300, 320
+    fmt, q, kc, vc, ck, cv = _case(6, c, b, hq, hkv, B, T)
+    rope = cq.RopeTable(BASE, t_cap)
+    kcache, vcache = codes_to_cache(kc, fmt, t_cap), codes_to_cache(vc, fmt, t_cap)
+    out0 = _gpu(np.zeros_like(q), kcache, vcache, ck, cv, 1.0, fmt, T, t_cap, rope)
+    plain0 = gpu_attention(np.zeros_like(q), kcache, vcache, ck, cv, 1.0, fmt, T, t_cap)
+    assert np.array_equal(out0.view(np.uint16), plain0.view(np.uint16))
+
+
+def test_rope_paged_equals_contiguous_bit_for_bit():
+    c, b, hq, hkv, B, T = 4, 8, 8, 4, 3, 900
+    fmt, q, kc, vc, ck, cv = _case(8, c, b, hq, hkv, B, T)
+    t_cap = 960
+    n_tiles = t_cap // 64
+    rope = cq.RopeTable(BASE, 1024)
+    kcache, vcache = codes_to_cache(kc, fmt, t_cap), codes_to_cache(vc, fmt, t_cap)
+    lens = np.array([900, 130, 64], dtype=np.int32)
+    want = _gpu(q, kcache, vcache, ck, cv, 0.1, fmt, T, t_cap, rope, seq_lens=lens, split=256)
+    # scatter the tiles over a pool in a random page order
+    rng = np.random.default_rng(9)
+    n_pages = B * n_tiles + 5
+    perm = rng.permutation(n_pages)[:B * n_tiles].astype(np.int32).reshape(B, n_tiles)
+    tb = cq.cq_code_bytes_per_token_head(fmt) * 64
+    pools = []
+    for cache in (kcache, vcache):
+        src = cache.cpu().numpy().reshape(B, hkv, n_tiles, tb)
+        pool = np.full((n_pages, hkv, tb), 0x77, dtype=np.uint8)
+        for n in range(B):
+            for i in range(n_tiles):
+                pool[perm[n, i]] = src[n, :, i]
+        pools.append(dev(pool.reshape(-1)))
+    pages = cq.PageTable(dev(perm), n_pages)
+    got = cq.cq_decode_attention_rope_paged(dev(q), pools[0], pools[1], dev(ck), dev(cv), 0.1, fmt, T, pages, rope,
+                                            seq_lens=dev(lens), tokens_per_split=256)
+    torch.cuda.synchronize()
+    assert np.array_equal(got.cpu().numpy().view(np.uint16), want.view(np.uint16))
+
+
+def test_rope_rejects_the_1024_centroid_format():
+    fmt, q, kc, vc, ck, cv = _case(2, 8, 10, 2, 2, 1, 64)
+    rope = cq.RopeTable(BASE, 64)
+    with pytest.raises(cq.CQError):
+        cq.cq_decode_attention_rope(dev(q), codes_to_cache(kc, fmt, 64), codes_to_cache(vc, fmt, 64), dev(ck), dev(cv),
+                                    0.1, fmt, 64, 64, rope)

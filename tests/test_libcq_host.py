@@ -215,3 +215,33 @@ def test_paged_argument_checks_without_launching():
     enc = int(lib.cq_encode_kv_paged(_fake(0x10000), _fake(0x20000), 256 * 100, 256, _fake(0x30000), _fake(0x40000),
                                      ctypes.byref(f), 2, 100, _fake(0x50000), _fake(0x60000), ctypes.byref(good), 30, None))
     assert enc == cq.CQ_ERR_INVALID_ARG                                  # 30 + 100 tokens > 128
+
+
+def test_rope_sizes_and_argument_checks_without_launching():
+    lib = cq.load()
+    assert lib.cq_rope_table_bytes(128, 4096) == 8 * (64 * 64 + 64 * 64)      # 64 tiles + 64 lane offsets, 64 pairs each
+    assert lib.cq_rope_table_bytes(128, 100) == 0 and lib.cq_rope_table_bytes(64, 4096) == 0
+    assert lib.cq_rope_table_bytes(128, 0) == 0
+    E = cq.CQ_ERR_INVALID_ARG
+    tab = lambda base=1e4, hd=128, pos=4096, p=0x10000, nbytes=1 << 20: int(
+        lib.cq_rope_table(base, hd, pos, _fake(p) if p else None, nbytes, None))
+    assert tab(hd=64) == cq.CQ_ERR_UNSUPPORTED
+    assert tab(pos=100) == E and tab(pos=0) == E and tab(p=0) == E and tab(p=0x10004) == E
+    assert tab(base=1.0) == E and tab(base=float("nan")) == E and tab(base=float("inf")) == E
+    assert tab(nbytes=1024) == cq.CQ_ERR_WORKSPACE_TOO_SMALL
+
+    def dec(fmt, t=128, t_cap=128, split=0, table=0x80000, positions=4096, ws_bytes=1 << 30):
+        f = fmt._c()
+        return int(lib.cq_decode_attention_rope(_fake(0x10000), _fake(0x20000), _fake(0x30000), _fake(0x40000),
+                                                _fake(0x50000), 0.1, ctypes.byref(f), 2, 8, t, t_cap, None, split,
+                                                _fake(table) if table else None, positions, _fake(0x60000),
+                                                _fake(0x70000), ws_bytes, None))
+    fmt = cq.CQFormat(4, 8, 128, 4)
+    assert dec(fmt, table=0) == E and dec(fmt, table=0x80004) == E
+    assert dec(fmt, positions=0) == E and dec(fmt, positions=100) == E
+    assert dec(fmt, t=128, t_cap=128, positions=64) == E           # table shorter than the context
+    assert dec(fmt, split=64 * 129, t=64 * 200, t_cap=64 * 200, positions=64 * 200) == E   # beyond the score buffer
+    assert dec(fmt, ws_bytes=16) == cq.CQ_ERR_WORKSPACE_TOO_SMALL
+    assert dec(cq.CQFormat(8, 10, 128, 4)) == cq.CQ_ERR_UNSUPPORTED    # 1024 centroids per group do not fit on chip
+    assert cq.cq_decode_rope_default_split(cq.CQFormat(8, 10, 128, 4), 2, 8, 4096) == 0
+    assert cq.cq_decode_rope_default_split(cq.CQFormat(2, 8, 128, 32), 64, 32, 64 * 1000) == 64 * 128    # 256 without the rotation
