@@ -179,6 +179,18 @@ def extra_measurements(cq, synth, torch):
         "code_read_GBps": code_bytes / (med * 1e-3) / 1e9,
         "frac_of_hbm_peak": code_bytes / (med * 1e-3) / 1e9 / HBM_PEAK_GBPS,
         "tokens_per_split": cq.cq_decode_default_split(fmt, B, cfg.n_q_heads, T)}
+    # the same caches read as pre-RoPE keys (query-side rotation; phase K is ALU-bound)
+    rope = cq.RopeTable(10000.0, T)
+    split_r = cq.cq_decode_rope_default_split(fmt, B, cfg.n_q_heads, T)
+    ws_r = torch.empty(cq.cq_decode_workspace_bytes(fmt, B, cfg.n_q_heads, T, split_r), dtype=torch.uint8, device="cuda")
+    call_r, _ = cq.prepare_decode_attention_rope(q, kcache, vcache, ck, cv, scale, fmt, T, T, rope,
+                                                 tokens_per_split=split_r, out=o, workspace=ws_r)
+    med_r, _ = time_calls(torch, call_r, 10, 2)
+    out["decode_long_context_pre_rope_keys"] = {
+        "workload": "as decode_long_context, keys cached before RoPE (cq_decode_attention_rope, base 10000)",
+        "ms": med_r, "kv_tokens_per_s": B * T / (med_r * 1e-3),
+        "code_read_GBps": code_bytes / (med_r * 1e-3) / 1e9, "tokens_per_split": split_r,
+        "slowdown_vs_position_independent": med_r / med}
     del kcache, vcache
     # centroid learning on a calibration tensor of the paper's size (16 sequences x 2048 tokens):
     # k-means++ and 100 Lloyd iterations for each of the 512 groups of one CQ-8c8b tensor

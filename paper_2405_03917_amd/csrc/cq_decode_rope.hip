@@ -9,14 +9,15 @@
 //     q . R_t k  =  sum_i  k_i a_i(t) + k_{i+64} b_i(t),
 //     a_i(t) = q_i cos(t th_i) + q_{i+64} sin(t th_i),  b_i(t) = q_{i+64} cos(t th_i) - q_i sin(t th_i),
 // and split by the angle-addition theorem into a per-tile part (t0 = 64 * tile: one rotated query
-// per tile and wavefront, lane i computing pair i, kept in LDS) and a per-lane part (the token's
-// offset within the tile: a table cos / sin(lane * th_i), 32 KB of LDS):
+// per tile and wavefront, lane i computing pair i; the other lanes fetch it with v_readlane) and a
+// per-lane part (the token's offset within the tile: a table cos / sin(lane * th_i), 32 KB of LDS):
 //     a_i(t0 + u) = cos(u th_i) a_i(t0) + sin(u th_i) b_i(t0),   b_i(t0 + u) = cos(u th_i) b_i(t0) - sin(u th_i) a_i(t0).
 // Lane = token as in the position-independent kernel; the key centroids themselves (fp16, 64 KB
-// per head) take the place of the score table in LDS, and a token costs, per channel pair, two
-// 8-byte LDS reads and eight VALU instructions (against one gather and one add per GROUP
-// without rotation).  Phase V, the epilogue and the split-context merge are those of
-// cq_decode.hip.  Both trigonometric tables come from cq_rope_tables (computed in fp64).
+// per head) take the place of the score table in LDS, and a token costs, per channel pair, one
+// 8-byte LDS read, two lane reads and six VALU instructions (against one gather and one add per
+// GROUP without rotation): phase K is bound by the vector ALU, not by HBM.  Phase V, the
+// epilogue and the split-context merge are those of cq_decode.hip.  Both trigonometric tables
+// come from cq_rope_table (computed in fp64).
 #include <mutex>
 
 #include "cq_decode_common.hpp"
@@ -78,16 +79,11 @@ __device__ __forceinline__ float2 lds_load2(unsigned byte_addr)
     const f2 a = *(__attribute__((address_space(3))) f2*)(byte_addr);
     return make_float2(a.x, a.y);
 }
-__device__ __forceinline__ void lds_store2(unsigned byte_addr, float x, float y)
-{
-    typedef float f2 __attribute__((ext_vector_type(2)));
-    *(__attribute__((address_space(3))) f2*)(byte_addr) = f2{x, y};
-}
 
 // A token's codes in group order.  The cache stores the code of group (s + u) mod Gh in slot s
 // of token u (the position-independent kernel wants neighbouring lanes on different groups);
 // here every lane should work on the same channel pair at the same time (the rotated query is
-// then one broadcast read, and every address a compile-time offset), so the token's Gh bytes are
+// then a scalar, and every table address a compile-time offset), so the token's Gh bytes are
 // rotated by u positions once per tile: bytes first (v_alignbyte), then whole dwords (selects).
 struct Unrotate {
     unsigned bytes;             // (Gh - u) mod 4
@@ -132,8 +128,7 @@ __global__ __launch_bounds__(NT) void decode_rope_kernel(DecodeArgs a, const flo
     constexpr int UNITS = 16 * K / JPL;
     constexpr int IPT = UNITS / NT;
     static_assert(D == 128 && UNITS % NT == 0, "head_dim 128");
-    constexpr unsigned Q0_BASE = kTabBytes + kTrgBytes;
-    constexpr unsigned SC_BASE = Q0_BASE + NW * kPairs * 8;
+    constexpr unsigned SC_BASE = kTabBytes + kTrgBytes;
     extern __shared__ float smem[];
     float* tab = smem;                                              // bins in phase V
     float* sc = smem + SC_BASE / 4;                                 // scores of the split
@@ -219,7 +214,6 @@ __global__ __launch_bounds__(NT) void decode_rope_kernel(DecodeArgs a, const flo
     lds_barrier();
 
     // ---- 2. phase K: scores ----------------------------------------------------------------
-    const unsigned q0_wave = Q0_BASE + (unsigned)wave * (kPairs * 8);
     const unsigned trg_lane = kTabBytes + (unsigned)lane * 8;
     Unrotate unrot;
     unrot.bytes = (unsigned)(GH - lane) & 3u;
@@ -230,17 +224,15 @@ __global__ __launch_bounds__(NT) void decode_rope_kernel(DecodeArgs a, const flo
         // the query rotated to the tile's base position: lane i holds pair i
         const float2 cs = cs_next;
         cs_next = tile_cs(k + 1);
-        lds_store2(q0_wave + (unsigned)lane * 8, __builtin_fmaf(qa, cs.x, qb * cs.y), __builtin_fmaf(qb, cs.x, -(qa * cs.y)));
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront", "local");
-        __builtin_amdgcn_wave_barrier();
+        const float qa0 = __builtin_fmaf(qa, cs.x, qb * cs.y), qb0 = __builtin_fmaf(qb, cs.x, -(qa * cs.y));
         // codes in group order: byte g of d[] is the code of group g
         unsigned d[GH / 4];
         group_order<GH>(w, unrot, d);
-        // the two table bases are re-materialised per tile: were they loop invariants, the
-        // compiler would keep base + offset of every channel pair in a register of its own
-        // (128 of them) instead of using the offset field of the LDS instructions
-        unsigned q0_base = q0_wave, trg_base = trg_lane;
-        asm volatile("" : "+v"(q0_base), "+v"(trg_base));
+        // the table base is re-materialised per tile: were it a loop invariant, the compiler
+        // would keep base + offset of every channel pair in a register of its own (64 of them)
+        // instead of using the offset field of the LDS instructions
+        unsigned trg_base = trg_lane;
+        asm volatile("" : "+v"(trg_base));
         float acc0 = 0.f, acc1 = 0.f;
 #pragma unroll
         for (int g = 0; g < HALF; ++g) {
@@ -251,7 +243,9 @@ __global__ __launch_bounds__(NT) void decode_rope_kernel(DecodeArgs a, const flo
 #pragma unroll
             for (int j = 0; j < C; ++j) {
                 const int i = g * C + j;                                    // channel pair (i, i + 64)
-                const float2 q0 = lds_load2(q0_base + i * 8);               // same address in every lane
+                // the tile-rotated query of pair i sits in lane i: one scalar each
+                const float2 q0 = make_float2(__uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(qa0), i)),
+                                              __uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(qb0), i)));
                 const float2 tr = lds_load2(trg_base + i * 512);
                 const float av = __builtin_fmaf(tr.x, q0.x, tr.y * q0.y);
                 const float bv = __builtin_fmaf(tr.x, q0.y, -(tr.y * q0.x));
@@ -266,7 +260,6 @@ __global__ __launch_bounds__(NT) void decode_rope_kernel(DecodeArgs a, const flo
         const float sv = tok < t_n ? acc0 + acc1 : -INFINITY;
         sc[lt * kTileTokens + lane] = sv;
         lane_max = fmaxf(lane_max, sv);
-        __builtin_amdgcn_wave_barrier();
     }, [] {});
     st.begin(vwalk, my_tiles, lane);
 
@@ -403,7 +396,7 @@ cq_status launch_rope_variant(const DecodeArgs& a, const float2* tile_tab, const
                                         hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
     });
     if (setup != hipSuccess) return CQ_ERR_HIP;
-    const size_t smem = kTabBytes + kTrgBytes + (NT / 64) * kPairs * 8 + (size_t)a.tiles_per_split * kTileTokens * 4;
+    const size_t smem = kTabBytes + kTrgBytes + (size_t)a.tiles_per_split * kTileTokens * 4;
     if (smem > 160 * 1024) return CQ_ERR_INVALID_ARG;
     const unsigned grid = (unsigned)(a.batch * a.n_q_heads * a.n_split);
     hipLaunchKernelGGL(kernel, dim3(grid), dim3(NT), smem, stream, a, tile_tab, lane_tab);
