@@ -191,6 +191,46 @@ CQ_API cq_status cq_decode_step(const void *q, const void *x_k_new, const void *
                          void *stream);
 
 /*
+ * cq_decode_step for several layers in ONE launch (the decode step of a workload whose layers are
+ * independent of each other, as in a benchmark over stored per-layer inputs; in a model the
+ * query of layer l + 1 depends on layer l's output and the layers have to be launched one by
+ * one).  Without the drain and ramp-up between per-layer launches, workgroups of the next layer
+ * start as soon as a compute unit is free.
+ *
+ * The per-layer tensors are named by a table in device memory, written once by
+ * cq_layer_table_fill from a host array of cq_layer_io records (each pointer: device memory,
+ * non-null, 16-byte aligned, with the meaning, shape and ownership of the argument of the same
+ * name of cq_decode_step; no two layers may share a cache or an output).  The fill validates what
+ * the host can see of them and copies the records on `stream`; the host array may be reused when
+ * it returns.  The table (cq_layer_table_bytes(n_layers) bytes, 16-byte aligned) stays owned by
+ * the caller and is only read by cq_decode_step_layers, which trusts its contents.
+ *
+ * cq_decode_step_layers: all layers share format, batch, head counts, t, t_cap, seq_lens, scale,
+ * x_row_stride and the split; workspace: n_layers * cq_decode_workspace_bytes(...) bytes.
+ * Results per layer are bit-identical to n_layers calls of cq_decode_step.
+ * Errors: as cq_decode_step (the per-layer pointers are checked by cq_layer_table_fill instead).
+ */
+typedef struct cq_layer_io {
+    const void *q;
+    const void *x_k_new;
+    const void *x_v_new;
+    void *k_codes;
+    void *v_codes;
+    const void *k_centroids;
+    const void *v_centroids;
+    void *out;
+} cq_layer_io;
+
+CQ_API size_t cq_layer_table_bytes(int32_t n_layers);
+CQ_API cq_status cq_layer_table_fill(const cq_layer_io *layers, int32_t n_layers,
+                              void *table, size_t table_bytes, void *stream);
+CQ_API cq_status cq_decode_step_layers(const void *layer_table, int32_t n_layers, int64_t x_row_stride,
+                                float scale, const cq_format *fmt,
+                                int32_t batch, int32_t n_q_heads, int32_t t, int32_t t_cap,
+                                const int32_t *seq_lens, int32_t tokens_per_split,
+                                void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * Paged caches.  Instead of t_cap contiguous positions per sequence, the codes live in a pool
  * of pages; a page is the 64-token tile of EVERY KV head ([n_kv_heads][tile bytes], tile bytes =
  * 64 * cq_code_bytes_per_token_head), and a block table names the page of each tile of each

@@ -28,6 +28,7 @@ EXPORTS = (
     "cq_cache_bytes", "cq_encode", "cq_encode_kv", "cq_decode_default_split", "cq_decode_workspace_bytes",
     "cq_decode_attention", "cq_decode_step", "cq_dequantize", "cq_paged_cache_bytes", "cq_encode_kv_paged",
     "cq_decode_attention_paged", "cq_decode_step_paged", "cq_kmeans_workspace_bytes", "cq_kmeans_fit",
+    "cq_layer_table_bytes", "cq_layer_table_fill", "cq_decode_step_layers",
     "cq_rope_table_bytes", "cq_rope_table", "cq_decode_rope_default_split", "cq_decode_attention_rope",
     "cq_decode_attention_rope_paged", "cq_probe_stream_read", "cq_probe_copy", "cq_probe_mfma",
 )
@@ -42,6 +43,11 @@ class CQError(RuntimeError):
 class _Format(ctypes.Structure):
     _fields_ = [("c", ctypes.c_int32), ("b", ctypes.c_int32),
                 ("head_dim", ctypes.c_int32), ("n_kv_heads", ctypes.c_int32)]
+
+
+class _LayerIO(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_void_p) for n in ("q", "x_k_new", "x_v_new", "k_codes", "v_codes", "k_centroids",
+                                                "v_centroids", "out")]
 
 
 class _PageTable(ctypes.Structure):
@@ -129,6 +135,13 @@ def load() -> ctypes.CDLL:
     lib.cq_kmeans_workspace_bytes.argtypes = [fp, i32]
     lib.cq_kmeans_fit.restype = ctypes.c_int
     lib.cq_kmeans_fit.argtypes = [vp, i64, vp, fp, i32, i32, vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
+    lib.cq_layer_table_bytes.restype = ctypes.c_size_t
+    lib.cq_layer_table_bytes.argtypes = [i32]
+    lib.cq_layer_table_fill.restype = ctypes.c_int
+    lib.cq_layer_table_fill.argtypes = [ctypes.POINTER(_LayerIO), i32, vp, ctypes.c_size_t, vp]
+    lib.cq_decode_step_layers.restype = ctypes.c_int
+    lib.cq_decode_step_layers.argtypes = [vp, i32, i64, ctypes.c_float, fp, i32, i32, i32, i32, vp, i32, vp,
+                                          ctypes.c_size_t, vp]
     lib.cq_rope_table_bytes.restype = ctypes.c_size_t
     lib.cq_rope_table_bytes.argtypes = [i32, i32]
     lib.cq_rope_table.restype = ctypes.c_int
@@ -337,6 +350,87 @@ def cq_decode_attention(q, k_codes, v_codes, k_centroids, v_centroids, scale: fl
                                          seq_lens, tokens_per_split, out, workspace)
     call(stream)
     return out
+
+
+class LayerTable:
+    """The device table of cq_layer_table_fill.  `layers`: one dict per layer with the tensors
+    q [B, Hq, head_dim], x_k_new / x_v_new [B, D], k_codes, v_codes, k_centroids, v_centroids and
+    out [B, Hq, head_dim] (as for cq_decode_step; all layers share shapes and the row stride)."""
+    FIELDS = ("q", "x_k_new", "x_v_new", "k_codes", "v_codes", "k_centroids", "v_centroids", "out")
+
+    def __init__(self, layers, fmt: CQFormat, t_cap: int, stream=None):
+        import torch
+        if not layers:
+            raise ValueError("at least one layer")
+        dtypes = dict(q=torch.float16, x_k_new=torch.float16, x_v_new=torch.float16, k_codes=torch.uint8,
+                      v_codes=torch.uint8, k_centroids=torch.float16, v_centroids=torch.float16, out=torch.float16)
+        first = layers[0]
+        batch, n_q_heads = int(first["q"].shape[0]), int(first["q"].shape[1])
+        need_cache = cq_cache_bytes(fmt, batch, t_cap)
+        rec = (_LayerIO * len(layers))()
+        for i, lay in enumerate(layers):
+            for name in self.FIELDS:
+                _dev(lay[name], dtypes[name], name)
+            if tuple(lay["q"].shape) != (batch, n_q_heads, fmt.head_dim) or not lay["q"].is_contiguous():
+                raise ValueError("q must be contiguous [B, Hq, head_dim], the same shape in every layer")
+            if tuple(lay["out"].shape) != (batch, n_q_heads, fmt.head_dim) or not lay["out"].is_contiguous():
+                raise ValueError("out must be contiguous [B, Hq, head_dim]")
+            for name in ("x_k_new", "x_v_new"):
+                x = lay[name]
+                if tuple(x.shape) != (batch, fmt.channels) or x.stride(1) != 1 or x.stride(0) != first["x_k_new"].stride(0):
+                    raise ValueError(f"{name} must be [B, D] with unit channel stride and one row stride for all layers")
+            for name in ("k_centroids", "v_centroids"):
+                if not lay[name].is_contiguous() or tuple(lay[name].shape) != (fmt.groups, 1 << fmt.b, fmt.c):
+                    raise ValueError(f"{name} must be contiguous [G, 2^b, c]")
+            for name in ("k_codes", "v_codes"):
+                if lay[name].numel() < need_cache:
+                    raise ValueError(f"{name} is smaller than cq_cache_bytes(fmt, batch, t_cap)")
+            for j, name in enumerate(self.FIELDS):
+                setattr(rec[i], name, lay[name].data_ptr())
+        self.n_layers, self.batch, self.n_q_heads, self.t_cap, self.fmt = len(layers), batch, n_q_heads, int(t_cap), fmt
+        self.x_row_stride = int(first["x_k_new"].stride(0))
+        self._keep = [dict(lay) for lay in layers]
+        nbytes = int(load().cq_layer_table_bytes(self.n_layers))
+        self.table = torch.empty(nbytes, dtype=torch.uint8, device=first["q"].device)
+        st = load().cq_layer_table_fill(rec, self.n_layers, self.table.data_ptr(), nbytes, _stream_handle(stream))
+        if st != CQ_OK:
+            raise CQError(st, "cq_layer_table_fill")
+
+    def outputs(self):
+        return [lay["out"] for lay in self._keep]
+
+
+def prepare_decode_step_layers(table: LayerTable, scale: float, t: int, seq_lens=None, tokens_per_split: int = 0,
+                               workspace=None) -> PreparedCall:
+    """Check and marshal the arguments of cq_decode_step_layers once."""
+    import torch
+    if not isinstance(table, LayerTable):
+        raise TypeError("table must be a LayerTable")
+    fmt = table.fmt
+    sl_ptr = None
+    if seq_lens is not None:
+        _dev(seq_lens, torch.int32, "seq_lens")
+        if tuple(seq_lens.shape) != (table.batch,) or not seq_lens.is_contiguous():
+            raise ValueError("seq_lens must be contiguous int32 [B]")
+        sl_ptr = seq_lens.data_ptr()
+    if workspace is None:
+        nbytes = cq_decode_workspace_bytes(fmt, table.batch, table.n_q_heads, t, tokens_per_split)
+        if nbytes == 0:
+            raise CQError(CQ_ERR_INVALID_ARG, "cq_decode_workspace_bytes")
+        workspace = torch.empty(nbytes * table.n_layers, dtype=torch.uint8, device=table.table.device)
+    else:
+        _dev(workspace, torch.uint8, "workspace")
+    f = fmt._c()
+    args = (table.table.data_ptr(), table.n_layers, table.x_row_stride, float(scale), ctypes.byref(f), table.batch,
+            table.n_q_heads, t, table.t_cap, sl_ptr, tokens_per_split, workspace.data_ptr(), workspace.numel())
+    return PreparedCall(load().cq_decode_step_layers, args, (table, seq_lens, workspace, f), "cq_decode_step_layers")
+
+
+def cq_decode_step_layers(table: LayerTable, scale: float, t: int, seq_lens=None, tokens_per_split: int = 0,
+                          workspace=None, stream=None):
+    """cq_decode_step of every layer of the table in one launch; returns the layers' out tensors."""
+    prepare_decode_step_layers(table, scale, t, seq_lens, tokens_per_split, workspace)(stream)
+    return table.outputs()
 
 
 class RopeTable:

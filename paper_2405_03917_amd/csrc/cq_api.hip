@@ -313,7 +313,8 @@ cq_status decode_common(const void* q, const void* x_k_new, const void* x_v_new,
                         int32_t batch, int32_t n_q_heads, int32_t t, int32_t t_cap, const cq_page_table* pages,
                         const int32_t* seq_lens, int32_t tokens_per_split,
                         void* out, void* workspace, size_t workspace_bytes, void* stream, bool step,
-                        const void* rope_table = nullptr, int32_t rope_positions = 0)
+                        const void* rope_table = nullptr, int32_t rope_positions = 0,
+                        const LayerPtrs* layers = nullptr, int32_t n_layers = 1)
 {
     Derived f;
     cq_status st = derive(fmt, &f);
@@ -327,8 +328,9 @@ cq_status decode_common(const void* q, const void* x_k_new, const void* x_v_new,
         if (t_cap <= 0 || t_cap % kTileTokens != 0) return CQ_ERR_INVALID_ARG;
         map = contiguous_map(f, t_cap);
     }
-    if (!q || !k_codes || !v_codes || !k_centroids || !v_centroids || !out || !workspace)
-        return CQ_ERR_INVALID_ARG;
+    // (a layer-batched call brings these per layer in its table, checked when the table was filled)
+    if (!layers && (!q || !k_codes || !v_codes || !k_centroids || !v_centroids || !out)) return CQ_ERR_INVALID_ARG;
+    if (!workspace || n_layers <= 0) return CQ_ERR_INVALID_ARG;
     if (batch <= 0 || n_q_heads <= 0 || n_q_heads % f.n_kv_heads != 0) return CQ_ERR_INVALID_ARG;
     if (t <= 0 || t > t_cap) return CQ_ERR_INVALID_ARG;
     if (!std::isfinite(scale)) return CQ_ERR_INVALID_ARG;
@@ -337,9 +339,9 @@ cq_status decode_common(const void* q, const void* x_k_new, const void* x_v_new,
         !aligned16(v_centroids) || !aligned16(out) || !aligned16(workspace))
         return CQ_ERR_INVALID_ARG;
     if (step) {
-        if (!x_k_new || !x_v_new || !aligned16(x_k_new) || !aligned16(x_v_new)) return CQ_ERR_INVALID_ARG;
+        if (!layers && (!x_k_new || !x_v_new || !aligned16(x_k_new) || !aligned16(x_v_new))) return CQ_ERR_INVALID_ARG;
         if (x_row_stride < f.channels || x_row_stride % 8 != 0) return CQ_ERR_INVALID_ARG;
-        if (k_codes == v_codes) return CQ_ERR_INVALID_ARG;
+        if (!layers && k_codes == v_codes) return CQ_ERR_INVALID_ARG;
     }
     if (rope) {
         if (!rope_table || !aligned16(rope_table)) return CQ_ERR_INVALID_ARG;
@@ -351,11 +353,14 @@ cq_status decode_common(const void* q, const void* x_k_new, const void* x_v_new,
     if (tiles > max_tiles) return CQ_ERR_INVALID_ARG;
     const int n_tiles = (t + kTileTokens - 1) / kTileTokens;
     const int n_split = (n_tiles + tiles - 1) / tiles;
-    const size_t need = sizeof(float) * (size_t)batch * n_q_heads * n_split * (f.head_dim + kPartialHeader);
+    const size_t need = sizeof(float) * (size_t)batch * n_q_heads * n_split * (f.head_dim + kPartialHeader) * n_layers;
     if (workspace_bytes < need) return CQ_ERR_WORKSPACE_TOO_SMALL;
-    if ((int64_t)batch * n_q_heads * n_split > 0x7fffffffLL) return CQ_ERR_INVALID_ARG;
+    if ((int64_t)batch * n_q_heads * n_split * n_layers > 0x7fffffffLL) return CQ_ERR_INVALID_ARG;
 
     DecodeArgs a;
+    a.layers = layers;
+    a.n_layers = n_layers;
+    a.wgs_per_layer = batch * n_q_heads * n_split;
     a.q = static_cast<const uint16_t*>(q);
     a.k_codes = static_cast<const uint8_t*>(k_codes);
     a.v_codes = static_cast<const uint8_t*>(v_codes);
@@ -430,6 +435,47 @@ cq_status cq_decode_step_paged(const void* q, const void* x_k_new, const void* x
     return decode_common(q, x_k_new, x_v_new, x_row_stride, k_pool, v_pool, k_centroids, v_centroids, scale, fmt,
                          batch, n_q_heads, t, 0, pages, seq_lens, tokens_per_split, out, workspace, workspace_bytes,
                          stream, true);
+}
+
+size_t cq_layer_table_bytes(int32_t n_layers)
+{
+    return n_layers > 0 ? sizeof(LayerPtrs) * (size_t)n_layers : 0;
+}
+
+cq_status cq_layer_table_fill(const cq_layer_io* layers, int32_t n_layers, void* table, size_t table_bytes, void* stream)
+{
+    static_assert(sizeof(cq_layer_io) == sizeof(LayerPtrs), "the device table holds the caller's records as they are");
+    if (!layers || n_layers <= 0 || !table || !aligned16(table)) return CQ_ERR_INVALID_ARG;
+    if (table_bytes < sizeof(LayerPtrs) * (size_t)n_layers) return CQ_ERR_WORKSPACE_TOO_SMALL;
+    for (int32_t l = 0; l < n_layers; ++l) {
+        const cq_layer_io& io = layers[l];
+        const void* all[] = {io.q, io.x_k_new, io.x_v_new, io.k_codes, io.v_codes, io.k_centroids, io.v_centroids, io.out};
+        for (const void* p : all)
+            if (!p || !aligned16(p)) return CQ_ERR_INVALID_ARG;
+        if (io.k_codes == io.v_codes) return CQ_ERR_INVALID_ARG;
+        // two layers may not share a cache or an output (they are written concurrently)
+        for (int32_t m = 0; m < l; ++m)
+            if (layers[m].k_codes == io.k_codes || layers[m].v_codes == io.v_codes || layers[m].k_codes == io.v_codes ||
+                layers[m].v_codes == io.k_codes || layers[m].out == io.out)
+                return CQ_ERR_INVALID_ARG;
+    }
+    // (the copy engine reads pageable host memory before the call returns)
+    if (hipMemcpyAsync(table, layers, sizeof(LayerPtrs) * (size_t)n_layers, hipMemcpyHostToDevice,
+                       static_cast<hipStream_t>(stream)) != hipSuccess)
+        return CQ_ERR_HIP;
+    return CQ_OK;
+}
+
+cq_status cq_decode_step_layers(const void* layer_table, int32_t n_layers, int64_t x_row_stride,
+                                float scale, const cq_format* fmt,
+                                int32_t batch, int32_t n_q_heads, int32_t t, int32_t t_cap,
+                                const int32_t* seq_lens, int32_t tokens_per_split,
+                                void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (!layer_table || !aligned16(layer_table) || n_layers <= 0) return CQ_ERR_INVALID_ARG;
+    return decode_common(nullptr, nullptr, nullptr, x_row_stride, nullptr, nullptr, nullptr, nullptr, scale, fmt, batch,
+                         n_q_heads, t, t_cap, nullptr, seq_lens, tokens_per_split, nullptr, workspace, workspace_bytes,
+                         stream, true, nullptr, 0, static_cast<const LayerPtrs*>(layer_table), n_layers);
 }
 
 size_t cq_rope_table_bytes(int32_t head_dim, int32_t positions)

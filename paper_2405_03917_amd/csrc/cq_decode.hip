@@ -94,7 +94,25 @@ __device__ __forceinline__ void store_new_codes(uint8_t* tile, const unsigned lo
 // its weight is added to the bins of the codes just found.  The first query head of each KV head
 // stores the codes.  Results equal cq_encode_kv followed by cq_decode_attention bit for bit
 // (the bins are integers: the order of the additions does not matter).
-template <int GH, int C, int B, int NT, bool STEP>
+// LayerPtrs as the kernel reads it.  A pointer read from memory could point anywhere (LDS,
+// scratch) as far as the compiler knows, and every access through it would be a flat instruction,
+// which waits on the LDS counter and the memory counter at once; the table's pointers are
+// therefore declared as what they are, pointers into global memory.
+#define CQ_GLOBAL __attribute__((address_space(1)))
+struct LayerPtrsGlobal {
+    CQ_GLOBAL const uint16_t* q;
+    CQ_GLOBAL const uint16_t* xk_new;
+    CQ_GLOBAL const uint16_t* xv_new;
+    CQ_GLOBAL uint8_t* k_codes;
+    CQ_GLOBAL uint8_t* v_codes;
+    CQ_GLOBAL const uint16_t* k_centroids;
+    CQ_GLOBAL const uint16_t* v_centroids;
+    CQ_GLOBAL uint16_t* out;
+};
+#undef CQ_GLOBAL
+static_assert(sizeof(LayerPtrsGlobal) == sizeof(LayerPtrs), "same record");
+
+template <int GH, int C, int B, int NT, bool STEP, bool LAYERS>
 __global__ __launch_bounds__(NT, 4) void decode_split_kernel(DecodeArgs a)
 {
     using F = Fmt<GH, B>;
@@ -129,10 +147,35 @@ __global__ __launch_bounds__(NT, 4) void decode_split_kernel(DecodeArgs a)
     // the head count allows: every workgroup that reads a head's codebooks and code streams then
     // shares one L2 (with grouped queries that is 4 query heads x splits x sequences per head).
     const int qper = a.n_q_heads / a.f.n_kv_heads;
+    // layer-batched launch: this workgroup's layer and that layer's tensors
+    int bid = blockIdx.x;
+    const uint16_t* q_ptr = a.q;
+    const uint16_t* xk_new = a.xk_new;
+    const uint16_t* xv_new = a.xv_new;
+    const uint8_t* k_codes = a.k_codes;
+    const uint8_t* v_codes = a.v_codes;
+    const uint16_t* k_centroids = a.k_centroids;
+    const uint16_t* v_centroids = a.v_centroids;
+    uint16_t* out_ptr = a.out;
+    float* partials = a.partials;
+    if constexpr (LAYERS) {
+        const int layer = bid / a.wgs_per_layer;
+        bid -= layer * a.wgs_per_layer;
+        const LayerPtrsGlobal& lp = reinterpret_cast<const LayerPtrsGlobal*>(a.layers)[layer];
+        q_ptr = (const uint16_t*)lp.q;
+        xk_new = (const uint16_t*)lp.xk_new;
+        xv_new = (const uint16_t*)lp.xv_new;
+        k_codes = (const uint8_t*)lp.k_codes;
+        v_codes = (const uint8_t*)lp.v_codes;
+        k_centroids = (const uint16_t*)lp.k_centroids;
+        v_centroids = (const uint16_t*)lp.v_centroids;
+        out_ptr = (uint16_t*)lp.out;
+        partials += (size_t)layer * a.wgs_per_layer * (D + kPartialHeader);
+    }
     int hq, split, n;
     if (a.f.n_kv_heads % 8 == 0) {
-        const int xcd = blockIdx.x & 7;
-        int r = blockIdx.x >> 3;
+        const int xcd = bid & 7;
+        int r = bid >> 3;
         const int per_xcd = a.f.n_kv_heads >> 3;
         const int hkv_ = xcd + 8 * (r % per_xcd);
         r /= per_xcd;
@@ -141,7 +184,7 @@ __global__ __launch_bounds__(NT, 4) void decode_split_kernel(DecodeArgs a)
         split = r % a.n_split;
         n = r / a.n_split;
     } else {
-        int idx = blockIdx.x;
+        int idx = bid;
         hq = idx % a.n_q_heads;
         idx /= a.n_q_heads;
         split = idx % a.n_split;
@@ -155,7 +198,7 @@ __global__ __launch_bounds__(NT, 4) void decode_split_kernel(DecodeArgs a)
     const int tile0 = split * a.tiles_per_split;
     const int tile1 = min(tile0 + a.tiles_per_split, n_tiles);
 
-    float* part = a.partials + ((size_t)(n * a.n_q_heads + hq) * a.n_split + split) * (D + kPartialHeader);
+    float* part = partials + ((size_t)(n * a.n_q_heads + hq) * a.n_split + split) * (D + kPartialHeader);
     if (tile0 >= tile1) {               // this split lies beyond the sequence: neutral partial
         if (tid == 0) { part[0] = -INFINITY; part[1] = 0.f; }
         for (int i = tid; i < D; i += NT) part[kPartialHeader + i] = 0.f;
@@ -184,15 +227,15 @@ __global__ __launch_bounds__(NT, 4) void decode_split_kernel(DecodeArgs a)
     if (a.map.block_table) {
         if (lane < my_tiles) kwalk.pages = a.map.page(n, tile0 + wave + lane * NW);
         kwalk.page_bytes = (size_t)a.f.n_kv_heads * F::TILE_BYTES;
-        kwalk.base = a.k_codes + (size_t)hkv * F::TILE_BYTES;
+        kwalk.base = k_codes + (size_t)hkv * F::TILE_BYTES;
         vwalk = kwalk;
-        vwalk.base = a.v_codes + (size_t)hkv * F::TILE_BYTES;
+        vwalk.base = v_codes + (size_t)hkv * F::TILE_BYTES;
     } else {
         const size_t stream_idx = a.map.tile_index(n, hkv, 0) * F::TILE_BYTES;
         kwalk.page_bytes = 0;
-        kwalk.base = a.k_codes + stream_idx;
+        kwalk.base = k_codes + stream_idx;
         vwalk = kwalk;
-        vwalk.base = a.v_codes + stream_idx;
+        vwalk.base = v_codes + stream_idx;
     }
 
     Streamer<GH, B, PF> st;
@@ -203,11 +246,11 @@ __global__ __launch_bounds__(NT, 4) void decode_split_kernel(DecodeArgs a)
     const int gl = tid & 15;
     unsigned xvw[STEP ? NCH : 1][C / 2];            // fused step: this thread's slices of the new value row
     {
-        const uint16_t* qh = a.q + (size_t)(n * a.n_q_heads + hq) * D;
+        const uint16_t* qh = q_ptr + (size_t)(n * a.n_q_heads + hq) * D;
 #pragma unroll
         for (int ch = 0; ch < NCH; ++ch) {
             const int g = ch * 16 + gl;
-            const uint16_t* ck = a.k_centroids + (size_t)(hkv * GH + g) * K * C;
+            const uint16_t* ck = k_centroids + (size_t)(hkv * GH + g) * K * C;
             unsigned qw[C / 2];
 #pragma unroll
             for (int i = 0; i < C / 2; ++i) qw[i] = *reinterpret_cast<const unsigned*>(qh + g * C + 2 * i);
@@ -220,8 +263,8 @@ __global__ __launch_bounds__(NT, 4) void decode_split_kernel(DecodeArgs a)
                 const size_t xoff = (size_t)n * a.x_new_stride + (size_t)(hkv * GH + g) * C;
 #pragma unroll
                 for (int i = 0; i < C / 2; ++i) {
-                    xkw[i] = *reinterpret_cast<const unsigned*>(a.xk_new + xoff + 2 * i);
-                    xvw[ch][i] = *reinterpret_cast<const unsigned*>(a.xv_new + xoff + 2 * i);
+                    xkw[i] = *reinterpret_cast<const unsigned*>(xk_new + xoff + 2 * i);
+                    xvw[ch][i] = *reinterpret_cast<const unsigned*>(xv_new + xoff + 2 * i);
                 }
             }
 #pragma unroll
@@ -272,7 +315,7 @@ __global__ __launch_bounds__(NT, 4) void decode_split_kernel(DecodeArgs a)
     // stores them (each token owns its 16-byte records, so no other token's bytes are touched)
     const bool writer = has_new && hq % (a.n_q_heads / a.f.n_kv_heads) == 0;
     if (writer)
-        store_new_codes<GH, B>(const_cast<uint8_t*>(a.k_codes) + a.map.tile_index(n, hkv, tile_new) * F::TILE_BYTES, keys, u_new, tid);
+        store_new_codes<GH, B>(const_cast<uint8_t*>(k_codes) + a.map.tile_index(n, hkv, tile_new) * F::TILE_BYTES, keys, u_new, tid);
 
     // ---- 2. phase K: scores --------------------------------------------------------------
     float lane_max = -INFINITY;
@@ -351,7 +394,7 @@ __global__ __launch_bounds__(NT, 4) void decode_split_kernel(DecodeArgs a)
         if constexpr (EARLY) {
 #pragma unroll
             for (int ch = 0; ch < NCH; ++ch) {
-                const uint16_t* cv = a.v_centroids + (size_t)(hkv * GH + ch * 16 + gl) * K * C;
+                const uint16_t* cv = v_centroids + (size_t)(hkv * GH + ch * 16 + gl) * K * C;
 #pragma unroll
                 for (int k = 0; k < IPT; ++k) rawv[ch][k] = load_cent16(cv + (size_t)((tid + k * NT) >> 4) * 8);
             }
@@ -377,7 +420,7 @@ __global__ __launch_bounds__(NT, 4) void decode_split_kernel(DecodeArgs a)
                 xv[2 * i] = (float)h.x;
                 xv[2 * i + 1] = (float)h.y;
             }
-            const uint16_t* cv = a.v_centroids + (size_t)(hkv * GH + ch * 16 + gl) * K * C;
+            const uint16_t* cv = v_centroids + (size_t)(hkv * GH + ch * 16 + gl) * K * C;
             Nearest vnear;
 #pragma unroll
             for (int k0 = 0; k0 < IPT; k0 += KB) {
@@ -403,7 +446,7 @@ __global__ __launch_bounds__(NT, 4) void decode_split_kernel(DecodeArgs a)
             lds_add((code * RW + tid * R) * 4u, *pf_new);
         }
         if (writer)
-            store_new_codes<GH, B>(const_cast<uint8_t*>(a.v_codes) + a.map.tile_index(n, hkv, tile_new) * F::TILE_BYTES, keys + GH, u_new, tid);
+            store_new_codes<GH, B>(const_cast<uint8_t*>(v_codes) + a.map.tile_index(n, hkv, tile_new) * F::TILE_BYTES, keys + GH, u_new, tid);
         lds_barrier();
     }
 
@@ -415,7 +458,7 @@ __global__ __launch_bounds__(NT, 4) void decode_split_kernel(DecodeArgs a)
 #pragma unroll
         for (int k0 = 0; k0 < IPT; k0 += KB) {
             if constexpr (!EARLY) {
-                const uint16_t* cv = a.v_centroids + (size_t)(hkv * GH + ch * 16 + gl) * K * C;
+                const uint16_t* cv = v_centroids + (size_t)(hkv * GH + ch * 16 + gl) * K * C;
 #pragma unroll
                 for (int k = 0; k < KB; ++k) rawv[0][k] = load_cent16(cv + (size_t)((tid + (k0 + k) * NT) >> 4) * 8);
             }
@@ -466,18 +509,24 @@ __global__ __launch_bounds__(NT, 4) void decode_split_kernel(DecodeArgs a)
         float o = 0.f;
 #pragma unroll
         for (int w = 0; w < NW; ++w) o += scr[64 + w * D + chn];
-        if (direct) a.out[(size_t)(n * a.n_q_heads + hq) * D + chn] = __builtin_bit_cast(uint16_t, (_Float16)(o / l));
+        if (direct) out_ptr[(size_t)(n * a.n_q_heads + hq) * D + chn] = __builtin_bit_cast(uint16_t, (_Float16)(o / l));
         else part[kPartialHeader + chn] = o;
     }
 }
 
 // Merge the partials of all splits of one (sequence, query head): exact rescaling by the
 // overall maximum, then one rounding to fp16.
-__global__ void decode_merge_kernel(const float* partials, uint16_t* out, int n_split, int head_dim)
+__global__ void decode_merge_kernel(const float* partials, uint16_t* out, int n_split, int head_dim,
+                                    const LayerPtrs* layers, int rows_per_layer)
 {
-    const int bh = blockIdx.x;
+    int bh = blockIdx.x;
     const int stride = head_dim + kPartialHeader;
     const float* p = partials + (size_t)bh * n_split * stride;
+    if (layers) {                       // layer-batched: row bh of layer blockIdx / rows_per_layer
+        const int layer = bh / rows_per_layer;
+        bh -= layer * rows_per_layer;
+        out = layers[layer].out;
+    }
     float m = -INFINITY;
     for (int s = 0; s < n_split; ++s) m = fmaxf(m, p[s * stride]);
     for (int i = threadIdx.x; i < head_dim; i += blockDim.x) {
@@ -505,10 +554,10 @@ size_t smem_bytes(int tiles_per_split, int head_dim, bool step)
     return sizeof(float) * (size_t)(F::TAB_FLOATS + sc_floats + key_floats);
 }
 
-template <int GH, int C, int B, int NT, bool STEP>
+template <int GH, int C, int B, int NT, bool STEP, bool LAYERS>
 cq_status launch_variant(const DecodeArgs& a, hipStream_t stream)
 {
-    auto kernel = decode_split_kernel<GH, C, B, NT, STEP>;
+    auto kernel = decode_split_kernel<GH, C, B, NT, STEP, LAYERS>;
     static std::once_flag once;
     static hipError_t setup = hipSuccess;
     std::call_once(once, [&] {
@@ -523,31 +572,31 @@ cq_status launch_variant(const DecodeArgs& a, hipStream_t stream)
     if (setup != hipSuccess) return CQ_ERR_HIP;
     const size_t smem = smem_bytes<GH, B, NT>(a.tiles_per_split, a.f.head_dim, STEP);
     if (smem > 160 * 1024) return CQ_ERR_INVALID_ARG;
-    const unsigned grid = (unsigned)(a.batch * a.n_q_heads * a.n_split);
+    const unsigned grid = (unsigned)(a.batch * a.n_q_heads * a.n_split) * (unsigned)(a.layers ? a.n_layers : 1);
     hipLaunchKernelGGL(kernel, dim3(grid), dim3(NT), smem, stream, a);
     if (hipGetLastError() != hipSuccess) return CQ_ERR_HIP;
     return CQ_OK;
 }
 
-template <int GH, int C, bool STEP>
+template <int GH, int C, bool STEP, bool LAYERS>
 cq_status launch_by_split(const DecodeArgs& a, hipStream_t stream)
 {
     // 16 / 32 groups per head: scores live inside the table, 68 KB of LDS, two 512-thread
     // workgroups per CU.  64 groups per head: 64 KB table + 4 B per token of the split; up to 64
     // tiles two 512-thread workgroups fit a CU, longer splits run as one 1024-thread workgroup.
-    if (Fmt<GH, 8>::SCORES_IN_TABLE || a.tiles_per_split <= 64) return launch_variant<GH, C, 8, 512, STEP>(a, stream);
-    return launch_variant<GH, C, 8, 1024, STEP>(a, stream);
+    if (Fmt<GH, 8>::SCORES_IN_TABLE || a.tiles_per_split <= 64) return launch_variant<GH, C, 8, 512, STEP, LAYERS>(a, stream);
+    return launch_variant<GH, C, 8, 1024, STEP, LAYERS>(a, stream);
 }
 
-template <bool STEP>
+template <bool STEP, bool LAYERS>
 cq_status launch_format(const DecodeArgs& a, hipStream_t stream)
 {
     if (a.f.b == 8) {
-        if (a.f.gh == 16 && a.f.c == 8) return launch_by_split<16, 8, STEP>(a, stream);
-        if (a.f.gh == 32 && a.f.c == 4) return launch_by_split<32, 4, STEP>(a, stream);
-        if (a.f.gh == 64 && a.f.c == 2) return launch_by_split<64, 2, STEP>(a, stream);
+        if (a.f.gh == 16 && a.f.c == 8) return launch_by_split<16, 8, STEP, LAYERS>(a, stream);
+        if (a.f.gh == 32 && a.f.c == 4) return launch_by_split<32, 4, STEP, LAYERS>(a, stream);
+        if (a.f.gh == 64 && a.f.c == 2) return launch_by_split<64, 2, STEP, LAYERS>(a, stream);
     } else if (a.f.b == 10 && a.f.gh == 16 && a.f.c == 8) {
-        return launch_variant<16, 8, 10, 1024, STEP>(a, stream);
+        return launch_variant<16, 8, 10, 1024, STEP, LAYERS>(a, stream);
     }
     return CQ_ERR_UNSUPPORTED;
 }
@@ -556,7 +605,8 @@ cq_status launch_format(const DecodeArgs& a, hipStream_t stream)
 
 cq_status launch_decode_merge(const float* partials, uint16_t* out, int rows, int n_split, int head_dim, hipStream_t stream)
 {
-    hipLaunchKernelGGL(decode_merge_kernel, dim3((unsigned)rows), dim3(128), 0, stream, partials, out, n_split, head_dim);
+    hipLaunchKernelGGL(decode_merge_kernel, dim3((unsigned)rows), dim3(128), 0, stream, partials, out, n_split, head_dim,
+                       static_cast<const LayerPtrs*>(nullptr), 0);
     return hipGetLastError() == hipSuccess ? CQ_OK : CQ_ERR_HIP;
 }
 
@@ -569,11 +619,14 @@ int decode_max_tiles_per_split(const Derived& f)
 
 cq_status launch_decode(const DecodeArgs& a, hipStream_t stream)
 {
-    const cq_status st = a.xk_new ? launch_format<true>(a, stream) : launch_format<false>(a, stream);
+    // (a layer-batched launch is always a fused step: its table holds the new rows)
+    const cq_status st = a.layers ? launch_format<true, true>(a, stream)
+                         : a.xk_new ? launch_format<true, false>(a, stream) : launch_format<false, false>(a, stream);
     if (st != CQ_OK || a.n_split == 1) return st;
     const int threads = a.f.head_dim <= 64 ? 64 : (a.f.head_dim <= 128 ? 128 : 256);
-    hipLaunchKernelGGL(decode_merge_kernel, dim3((unsigned)(a.batch * a.n_q_heads)), dim3(threads), 0, stream,
-                       a.partials, a.out, a.n_split, a.f.head_dim);
+    const int rows = a.batch * a.n_q_heads;
+    hipLaunchKernelGGL(decode_merge_kernel, dim3((unsigned)(rows * (a.layers ? a.n_layers : 1))), dim3(threads), 0, stream,
+                       a.partials, a.out, a.n_split, a.f.head_dim, a.layers, rows);
     if (hipGetLastError() != hipSuccess) return CQ_ERR_HIP;
     return CQ_OK;
 }

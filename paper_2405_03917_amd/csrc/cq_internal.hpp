@@ -66,6 +66,18 @@ struct EncodeArgs {
     Derived f;
 };
 
+// One layer's tensors of a layer-batched decode step (mirrors cq_layer_io; lives in device memory).
+struct LayerPtrs {
+    const uint16_t* q;
+    const uint16_t* xk_new;
+    const uint16_t* xv_new;
+    uint8_t* k_codes;
+    uint8_t* v_codes;
+    const uint16_t* k_centroids;
+    const uint16_t* v_centroids;
+    uint16_t* out;
+};
+
 struct DecodeArgs {
     const uint16_t* q;
     const uint8_t* k_codes;
@@ -84,6 +96,11 @@ struct DecodeArgs {
     int tiles_per_split, n_split;
     float* partials;          // [batch][n_q_heads][n_split][2 + head_dim]
     uint16_t* out;
+    // layer-batched launch (null: one layer): workgroup blockIdx / wgs_per_layer serves layer
+    // layers[...], whose pointers replace q, xk_new, xv_new, the caches, the codebooks and out;
+    // its partials follow those of the layers before it
+    const LayerPtrs* layers;
+    int n_layers, wgs_per_layer;
     Derived f;
 };
 

@@ -245,3 +245,32 @@ def test_rope_sizes_and_argument_checks_without_launching():
     assert dec(cq.CQFormat(8, 10, 128, 4)) == cq.CQ_ERR_UNSUPPORTED    # 1024 centroids per group do not fit on chip
     assert cq.cq_decode_rope_default_split(cq.CQFormat(8, 10, 128, 4), 2, 8, 4096) == 0
     assert cq.cq_decode_rope_default_split(cq.CQFormat(2, 8, 128, 32), 64, 32, 64 * 1000) == 64 * 128    # 256 without the rotation
+
+
+def test_layer_table_argument_checks_without_copying():
+    lib = cq.load()
+    assert lib.cq_layer_table_bytes(32) == 32 * 8 * 8 and lib.cq_layer_table_bytes(0) == 0
+    E = cq.CQ_ERR_INVALID_ARG
+
+    def rec(n=2, **kw):
+        r = (cq._LayerIO * n)()
+        for i in range(n):
+            for j, name in enumerate(cq.LayerTable.FIELDS):
+                setattr(r[i], name, 0x100000 * (i + 1) + 0x1000 * (j + 1))
+        for k, v in kw.items():
+            setattr(r[n - 1], k, v)
+        return r
+    fill = lambda r, n=2, table=0x900000, nbytes=1 << 12: int(lib.cq_layer_table_fill(r, n, _fake(table) if table else None, nbytes, None))
+    assert fill(None) == E and fill(rec(), n=0) == E and fill(rec(), table=0) == E and fill(rec(), table=0x900008) == E
+    assert fill(rec(), nbytes=64) == cq.CQ_ERR_WORKSPACE_TOO_SMALL
+    for name in cq.LayerTable.FIELDS:
+        assert fill(rec(**{name: 0})) == E, name
+        assert fill(rec(**{name: 0x555554})) == E, name
+    assert fill(rec(v_codes=0x200000 + 0x4000)) == E          # a layer's K and V caches coincide
+    assert fill(rec(k_codes=0x100000 + 0x4000)) == E          # two layers share a cache
+    assert fill(rec(out=0x100000 + 0x8000)) == E              # two layers share an output
+    f = cq.CQFormat(4, 8, 128, 4)._c()
+    step = lambda table=0x900000, n=2, stride=512, ws=1 << 30: int(lib.cq_decode_step_layers(
+        _fake(table) if table else None, n, stride, 0.1, ctypes.byref(f), 2, 8, 128, 128, None, 0, _fake(0x70000), ws, None))
+    assert step(table=0) == E and step(n=0) == E and step(stride=100) == E and step(table=0x900004) == E
+    assert step(ws=cq.cq_decode_workspace_bytes(cq.CQFormat(4, 8, 128, 4), 2, 8, 128)) == cq.CQ_ERR_WORKSPACE_TOO_SMALL   # one layer's worth
