@@ -25,8 +25,10 @@
  *
  * Where the paper is silent this library takes these readings: ties in the nearest-centroid
  * search go to the lowest index; the softmax scale is an explicit argument (Eq. 1 has none);
- * query head h reads KV head h / (n_q_heads / n_kv_heads); the stored key is the key the query
- * is dotted with (no positional rotation is applied to dequantized keys).
+ * query head h reads KV head h / (n_q_heads / n_kv_heads); in cq_decode_attention and
+ * cq_decode_step the stored key is the key the query is dotted with (no positional rotation);
+ * the *_rope calls are for caches of keys quantized before the rotary position embedding and
+ * rotate each key to its position.
  *
  * Packed code cache (the paper fixes only its density, b / c bits per stored number -- the
  * "Bits Per FPN" column of Table 1; the arrangement below is this library's):
@@ -294,6 +296,11 @@ CQ_API cq_status cq_decode_step_paged(const void *q, const void *x_k_new, const 
  *   rope_table     device, as written by cq_rope_table(base, 128, rope_positions, ...)
  *   rope_positions must be >= t
  *   tokens_per_split  0 = cq_decode_rope_default_split(...); at most 8192
+ * cq_decode_step_rope[_paged]: the fused decode step (cq_decode_step[_paged]) for such caches:
+ * the new key row is passed BEFORE the rotation (it is quantized as it is; position t - 1, or
+ * seq_lens[n] - 1, rotates it like every cached key), the new value row as always; same
+ * arguments as cq_decode_step plus the table, same results as cq_encode_kv followed by
+ * cq_decode_attention_rope, bit for bit.
  * b = 8 formats with head_dim 128 only (CQ-8c8b, CQ-4c8b, CQ-2c8b): the kernel keeps a head's
  * key centroids (64 KiB) on chip; CQ-8c10b returns CQ_ERR_UNSUPPORTED.  Workspace size:
  * cq_decode_workspace_bytes with the tokens_per_split actually used.
@@ -310,6 +317,22 @@ CQ_API cq_status cq_decode_attention_rope(const void *q, const void *k_codes, co
                                    const int32_t *seq_lens, int32_t tokens_per_split,
                                    const void *rope_table, int32_t rope_positions,
                                    void *out, void *workspace, size_t workspace_bytes, void *stream);
+CQ_API cq_status cq_decode_step_rope(const void *q, const void *x_k_new, const void *x_v_new, int64_t x_row_stride,
+                              void *k_codes, void *v_codes,
+                              const void *k_centroids, const void *v_centroids,
+                              float scale, const cq_format *fmt,
+                              int32_t batch, int32_t n_q_heads, int32_t t, int32_t t_cap,
+                              const int32_t *seq_lens, int32_t tokens_per_split,
+                              const void *rope_table, int32_t rope_positions,
+                              void *out, void *workspace, size_t workspace_bytes, void *stream);
+CQ_API cq_status cq_decode_step_rope_paged(const void *q, const void *x_k_new, const void *x_v_new, int64_t x_row_stride,
+                                    void *k_pool, void *v_pool,
+                                    const void *k_centroids, const void *v_centroids,
+                                    float scale, const cq_format *fmt,
+                                    int32_t batch, int32_t n_q_heads, int32_t t, const cq_page_table *pages,
+                                    const int32_t *seq_lens, int32_t tokens_per_split,
+                                    const void *rope_table, int32_t rope_positions,
+                                    void *out, void *workspace, size_t workspace_bytes, void *stream);
 CQ_API cq_status cq_decode_attention_rope_paged(const void *q, const void *k_pool, const void *v_pool,
                                          const void *k_centroids, const void *v_centroids,
                                          float scale, const cq_format *fmt,

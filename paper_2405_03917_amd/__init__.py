@@ -30,7 +30,7 @@ EXPORTS = (
     "cq_decode_attention_paged", "cq_decode_step_paged", "cq_kmeans_workspace_bytes", "cq_kmeans_fit",
     "cq_layer_table_bytes", "cq_layer_table_fill", "cq_decode_step_layers",
     "cq_rope_table_bytes", "cq_rope_table", "cq_decode_rope_default_split", "cq_decode_attention_rope",
-    "cq_decode_attention_rope_paged", "cq_probe_stream_read", "cq_probe_copy", "cq_probe_mfma",
+    "cq_decode_attention_rope_paged", "cq_decode_step_rope", "cq_decode_step_rope_paged", "cq_probe_stream_read", "cq_probe_copy", "cq_probe_mfma",
 )
 
 
@@ -154,6 +154,12 @@ def load() -> ctypes.CDLL:
     lib.cq_decode_attention_rope_paged.restype = ctypes.c_int
     lib.cq_decode_attention_rope_paged.argtypes = [vp, vp, vp, vp, vp, ctypes.c_float, fp, i32, i32, i32, pp, vp, i32,
                                                    vp, i32, vp, vp, ctypes.c_size_t, vp]
+    lib.cq_decode_step_rope.restype = ctypes.c_int
+    lib.cq_decode_step_rope.argtypes = [vp, vp, vp, i64, vp, vp, vp, vp, ctypes.c_float, fp, i32, i32, i32, i32,
+                                        vp, i32, vp, i32, vp, vp, ctypes.c_size_t, vp]
+    lib.cq_decode_step_rope_paged.restype = ctypes.c_int
+    lib.cq_decode_step_rope_paged.argtypes = [vp, vp, vp, i64, vp, vp, vp, vp, ctypes.c_float, fp, i32, i32, i32, pp, vp,
+                                              i32, vp, i32, vp, vp, ctypes.c_size_t, vp]
     lib.cq_probe_copy.restype = ctypes.c_int
     lib.cq_probe_copy.argtypes = [vp, vp, ctypes.c_size_t, vp]
     lib.cq_probe_mfma.restype = ctypes.c_int
@@ -481,6 +487,33 @@ def cq_decode_attention_rope(q, k_codes, v_codes, k_centroids, v_centroids, scal
     return out
 
 
+def prepare_decode_step_rope(q, x_k_new, x_v_new, k_codes, v_codes, k_centroids, v_centroids, scale: float,
+                             fmt: CQFormat, t: int, t_cap: int, rope: RopeTable, seq_lens=None,
+                             tokens_per_split: int = 0, out=None, workspace=None):
+    """Check and marshal the arguments of cq_decode_step_rope once.  Returns (call, out)."""
+    if not isinstance(rope, RopeTable):
+        raise TypeError("rope must be a RopeTable")
+    if tokens_per_split == 0:
+        tokens_per_split = cq_decode_rope_default_split(fmt, int(q.shape[0]), int(q.shape[1]), t)
+        if tokens_per_split == 0:
+            raise CQError(CQ_ERR_UNSUPPORTED, "cq_decode_rope_default_split")
+    call, out = prepare_decode_step(q, x_k_new, x_v_new, k_codes, v_codes, k_centroids, v_centroids, scale, fmt, t,
+                                    t_cap, seq_lens, tokens_per_split, out, workspace)
+    a = call._args
+    args = a[:16] + (rope.table.data_ptr(), rope.positions) + a[16:]
+    return PreparedCall(load().cq_decode_step_rope, args, call._keep + (rope,), "cq_decode_step_rope"), out
+
+
+def cq_decode_step_rope(q, x_k_new, x_v_new, k_codes, v_codes, k_centroids, v_centroids, scale: float, fmt: CQFormat,
+                        t: int, t_cap: int, rope: RopeTable, seq_lens=None, tokens_per_split: int = 0, out=None,
+                        workspace=None, stream=None):
+    """cq_decode_step for caches of pre-rotation keys: x_k_new is the new key row BEFORE RoPE."""
+    call, out = prepare_decode_step_rope(q, x_k_new, x_v_new, k_codes, v_codes, k_centroids, v_centroids, scale, fmt,
+                                         t, t_cap, rope, seq_lens, tokens_per_split, out, workspace)
+    call(stream)
+    return out
+
+
 def prepare_decode_step(q, x_k_new, x_v_new, k_codes, v_codes, k_centroids, v_centroids, scale: float,
                         fmt: CQFormat, t: int, t_cap: int, seq_lens=None, tokens_per_split: int = 0,
                         out=None, workspace=None):
@@ -612,7 +645,7 @@ def _paged_decode(fn_name, q, x_k_new, x_v_new, k_pool, v_pool, k_centroids, v_c
     common = (k_pool.data_ptr(), v_pool.data_ptr(), k_centroids.data_ptr(), v_centroids.data_ptr(), float(scale),
               ctypes.byref(fmt._c()), batch, n_q_heads, t, ctypes.byref(pages._c), sl_ptr, tokens_per_split,
               out.data_ptr(), workspace.data_ptr(), workspace.numel(), _stream_handle(stream))
-    if rope is not None:
+    if rope is not None and x_k_new is None:
         st = load().cq_decode_attention_rope_paged(q.data_ptr(), *common[:12], rope.table.data_ptr(), rope.positions,
                                                    *common[12:])
     elif x_k_new is None:
@@ -624,7 +657,11 @@ def _paged_decode(fn_name, q, x_k_new, x_v_new, k_pool, v_pool, k_centroids, v_c
                 raise ValueError(f"{name} must be [B, D] with unit channel stride")
         if x_k_new.stride(0) != x_v_new.stride(0):
             raise ValueError("x_k_new and x_v_new must share their row stride")
-        st = load().cq_decode_step_paged(q.data_ptr(), x_k_new.data_ptr(), x_v_new.data_ptr(), x_k_new.stride(0), *common)
+        if rope is not None:
+            st = load().cq_decode_step_rope_paged(q.data_ptr(), x_k_new.data_ptr(), x_v_new.data_ptr(), x_k_new.stride(0),
+                                                  *common[:12], rope.table.data_ptr(), rope.positions, *common[12:])
+        else:
+            st = load().cq_decode_step_paged(q.data_ptr(), x_k_new.data_ptr(), x_v_new.data_ptr(), x_k_new.stride(0), *common)
     if st != CQ_OK:
         raise CQError(st, fn_name)
     return out
@@ -645,6 +682,16 @@ def cq_decode_attention_rope_paged(q, k_pool, v_pool, k_centroids, v_centroids, 
     if tokens_per_split == 0:
         tokens_per_split = cq_decode_rope_default_split(fmt, int(q.shape[0]), int(q.shape[1]), t)
     return _paged_decode("cq_decode_attention_rope_paged", q, None, None, k_pool, v_pool, k_centroids, v_centroids,
+                         scale, fmt, t, pages, seq_lens, tokens_per_split, out, workspace, stream, rope=rope)
+
+
+def cq_decode_step_rope_paged(q, x_k_new, x_v_new, k_pool, v_pool, k_centroids, v_centroids, scale: float,
+                              fmt: CQFormat, t: int, pages: PageTable, rope: RopeTable, seq_lens=None,
+                              tokens_per_split: int = 0, out=None, workspace=None, stream=None):
+    """cq_decode_step_rope over paged pools."""
+    if tokens_per_split == 0:
+        tokens_per_split = cq_decode_rope_default_split(fmt, int(q.shape[0]), int(q.shape[1]), t)
+    return _paged_decode("cq_decode_step_rope_paged", q, x_k_new, x_v_new, k_pool, v_pool, k_centroids, v_centroids,
                          scale, fmt, t, pages, seq_lens, tokens_per_split, out, workspace, stream, rope=rope)
 
 

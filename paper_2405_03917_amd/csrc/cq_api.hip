@@ -514,6 +514,36 @@ cq_status cq_decode_attention_rope(const void* q, const void* k_codes, const voi
                          false, rope_table, rope_positions);
 }
 
+cq_status cq_decode_step_rope(const void* q, const void* x_k_new, const void* x_v_new, int64_t x_row_stride,
+                              void* k_codes, void* v_codes,
+                              const void* k_centroids, const void* v_centroids,
+                              float scale, const cq_format* fmt,
+                              int32_t batch, int32_t n_q_heads, int32_t t, int32_t t_cap,
+                              const int32_t* seq_lens, int32_t tokens_per_split,
+                              const void* rope_table, int32_t rope_positions,
+                              void* out, void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (rope_positions <= 0) return CQ_ERR_INVALID_ARG;
+    return decode_common(q, x_k_new, x_v_new, x_row_stride, k_codes, v_codes, k_centroids, v_centroids, scale, fmt,
+                         batch, n_q_heads, t, t_cap, nullptr, seq_lens, tokens_per_split, out, workspace, workspace_bytes,
+                         stream, true, rope_table, rope_positions);
+}
+
+cq_status cq_decode_step_rope_paged(const void* q, const void* x_k_new, const void* x_v_new, int64_t x_row_stride,
+                                    void* k_pool, void* v_pool,
+                                    const void* k_centroids, const void* v_centroids,
+                                    float scale, const cq_format* fmt,
+                                    int32_t batch, int32_t n_q_heads, int32_t t, const cq_page_table* pages,
+                                    const int32_t* seq_lens, int32_t tokens_per_split,
+                                    const void* rope_table, int32_t rope_positions,
+                                    void* out, void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (!pages || rope_positions <= 0) return CQ_ERR_INVALID_ARG;
+    return decode_common(q, x_k_new, x_v_new, x_row_stride, k_pool, v_pool, k_centroids, v_centroids, scale, fmt,
+                         batch, n_q_heads, t, 0, pages, seq_lens, tokens_per_split, out, workspace, workspace_bytes,
+                         stream, true, rope_table, rope_positions);
+}
+
 cq_status cq_decode_attention_rope_paged(const void* q, const void* k_pool, const void* v_pool,
                                          const void* k_centroids, const void* v_centroids,
                                          float scale, const cq_format* fmt,

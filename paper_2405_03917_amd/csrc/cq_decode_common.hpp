@@ -246,6 +246,56 @@ __device__ __forceinline__ unsigned slot_addr(const Tile<GH, B>& w, const Column
     }
 }
 
+// Fused step: replace the codes of lane u_new's token in a tile's registers by the codes just
+// computed (keys[g] holds group g's (distance, index) minimum), exactly as the cache layout
+// would hold them: slot s of token u carries group (s + u) mod Gh.
+template <int GH, int B>
+__device__ __forceinline__ void patch_new_token(Tile<GH, B>& w, const unsigned long long* keys, int u_new, int lane)
+{
+    if (lane != u_new) return;
+    unsigned hi = 0;
+#pragma unroll
+    for (int pl = 0; pl < GH / 16; ++pl) {
+        unsigned word[4];
+#pragma unroll
+        for (int d = 0; d < 4; ++d) {
+            unsigned x = 0;
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const int s = 16 * pl + 4 * d + k;
+                const unsigned code = (unsigned)(keys[(s + u_new) & (GH - 1)] & 0xffffffffu);
+                x |= (code & 0xffu) << (8 * k);
+                if constexpr (B == 10) hi |= (code >> 8) << (2 * s);
+            }
+            word[d] = x;
+        }
+        w.lo[pl] = u32x4{word[0], word[1], word[2], word[3]};
+    }
+    if constexpr (B == 10) w.hi = hi;
+}
+
+// Fused step: store the new token's codes of one KV head into its cache tile.
+template <int GH, int B>
+__device__ __forceinline__ void store_new_codes(uint8_t* tile, const unsigned long long* keys, int u_new, int tid)
+{
+    if (tid < GH) {
+        const unsigned code = (unsigned)(keys[tid] & 0xffffffffu);
+        const int slot = (tid - u_new) & (GH - 1);
+        tile[(slot >> 4) * 1024 + u_new * 16 + (slot & 15)] = (uint8_t)(code & 0xffu);
+    }
+    if constexpr (B == 10) {
+        if (tid == 0) {                 // the token's high-bit word belongs to this (token, head) alone
+            unsigned hi = 0;
+#pragma unroll
+            for (int g = 0; g < GH; ++g) {
+                const unsigned code = (unsigned)(keys[g] & 0xffffffffu);
+                hi |= (code >> 8) << (2 * ((g - u_new) & (GH - 1)));
+            }
+            *reinterpret_cast<unsigned*>(tile + kTileTokens * GH + u_new * 4) = hi;
+        }
+    }
+}
+
 // Walk tiles first, first + stride, ... (n of them) of a code stream with PF tiles in flight.
 // begin() requests the first tiles (so that the latency overlaps whatever the caller does
 // next); run() consumes.  The steady state is straight-line code (consume one tile, request the

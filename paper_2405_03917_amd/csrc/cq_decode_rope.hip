@@ -113,7 +113,12 @@ __device__ __forceinline__ void group_order(const Tile<GH, 8>& w, const Unrotate
     }
 }
 
-template <int GH, int C, int NT>
+// STEP = true is the fused decode step, as in cq_decode.hip: the workgroup whose split holds the
+// newest position also encodes that token's key row (before any rotation: the cache holds
+// pre-rotation keys) against the centroids it has just brought into LDS, patches the tile that
+// holds the position in registers, and finds the value codes in the epilogue.  Same results as
+// cq_encode_kv followed by the attention call, bit for bit.
+template <int GH, int C, int NT, bool STEP>
 __global__ __launch_bounds__(NT) void decode_rope_kernel(DecodeArgs a, const float2* tile_tab, const float2* lane_tab)
 {
     constexpr int B = 8;
@@ -133,6 +138,8 @@ __global__ __launch_bounds__(NT) void decode_rope_kernel(DecodeArgs a, const flo
     float* tab = smem;                                              // bins in phase V
     float* sc = smem + SC_BASE / 4;                                 // scores of the split
     float* scr = smem + kTabBytes / 4;                              // reductions (the lane table is dead by then)
+    // fused step: (distance, index) minima per group, keys[0..GH) for K, [GH..2GH) for V, then the new token's weight
+    unsigned long long* keys = reinterpret_cast<unsigned long long*>(smem + SC_BASE / 4 + a.tiles_per_split * kTileTokens);
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -171,6 +178,11 @@ __global__ __launch_bounds__(NT) void decode_rope_kernel(DecodeArgs a, const flo
         for (int i = tid; i < D; i += NT) part[kPartialHeader + i] = 0.f;
         return;
     }
+
+    const int pos_new = t_n - 1;
+    const int tile_new = pos_new / kTileTokens, u_new = pos_new % kTileTokens;
+    const bool has_new = STEP && tile_new >= tile0 && tile_new < tile1;
+    if (has_new && tid < 2 * GH) keys[tid] = ~0ull;         // (ordered by the barrier behind the table copy)
 
     Columns<GH, B> col;
     const int my_tiles = (tile1 - tile0 - wave + NW - 1) / NW;
@@ -211,7 +223,35 @@ __global__ __launch_bounds__(NT) void decode_rope_kernel(DecodeArgs a, const flo
         return tile_tab[(size_t)tile * kPairs + lane];
     };
     float2 cs_next = tile_cs(0);
+    const int gl16 = tid & 15;
+    unsigned xvw[STEP ? NCH : 1][C / 2];            // fused step: this thread's slices of the new value row
     lds_barrier();
+
+    // fused step: nearest key centroids of the new row, NT / GH threads per group over the
+    // centroids in LDS (ascending index per thread, 64-bit minimum over the threads: the exact
+    // search of cq_encode with its tie rule); the first query head of the KV head stores the codes
+    if (has_new) {
+        constexpr int TPG = NT / GH;
+        const int g = tid / TPG;
+        const size_t xrow = (size_t)n * a.x_new_stride + (size_t)hkv * GH * C;
+        float xk[C];
+        load_row_slice<C>(a.xk_new + xrow + g * C, xk);
+#pragma unroll
+        for (int ch = 0; ch < NCH; ++ch)
+#pragma unroll
+            for (int i = 0; i < C / 2; ++i)
+                xvw[ch][i] = *reinterpret_cast<const unsigned*>(a.xv_new + xrow + (ch * 16 + gl16) * C + 2 * i);
+        Nearest knear;
+        for (int j = tid % TPG; j < K; j += TPG) {
+            const CenVec<C> cen = lds_centroid<C>((unsigned)(g * K + j) * (C * 2));
+            knear.offer(centroid_distance<C>(xk, cen.w), j);
+        }
+        lds_min_u64(&keys[g], knear.key());
+        lds_barrier();
+    }
+    const bool writer = has_new && hq % qper == 0;
+    if (writer)
+        store_new_codes<GH, B>(const_cast<uint8_t*>(a.k_codes) + a.map.tile_index(n, hkv, tile_new) * F::TILE_BYTES, keys, u_new, tid);
 
     // ---- 2. phase K: scores ----------------------------------------------------------------
     const unsigned trg_lane = kTabBytes + (unsigned)lane * 8;
@@ -219,8 +259,10 @@ __global__ __launch_bounds__(NT) void decode_rope_kernel(DecodeArgs a, const flo
     unrot.bytes = (unsigned)(GH - lane) & 3u;
     unrot.dwords = ((unsigned)(GH - lane) & (unsigned)(GH - 1)) >> 2;
     float lane_max = -INFINITY;
-    st.run(kwalk, my_tiles, lane, [&](const Tile<GH, B>& w, int k) {
+    st.run(kwalk, my_tiles, lane, [&](const Tile<GH, B>& w_in, int k) {
         const int lt = wave + k * NW;
+        Tile<GH, B> w = w_in;
+        if (has_new && tile0 + lt == tile_new) patch_new_token<GH, B>(w, keys, u_new, lane);
         // the query rotated to the tile's base position: lane i holds pair i
         const float2 cs = cs_next;
         cs_next = tile_cs(k + 1);
@@ -289,7 +331,7 @@ __global__ __launch_bounds__(NT) void decode_rope_kernel(DecodeArgs a, const flo
 
     // ---- 3. phase V: probability bins (as in the position-independent kernel) -------------
     col.init(lane);
-    const int gl16 = tid & 15;
+    unsigned* pf_new = reinterpret_cast<unsigned*>(keys + 2 * GH);
     constexpr int KB = IPT < 8 ? IPT : 8;
     constexpr bool EARLY = IPT * NCH <= 8 && KB == IPT;
     Cent16 rawv[EARLY ? NCH : 1][KB];
@@ -297,8 +339,13 @@ __global__ __launch_bounds__(NT) void decode_rope_kernel(DecodeArgs a, const flo
     st.run(vwalk, my_tiles, lane, [&](const Tile<GH, B>& w, int k) {
         const int lt = wave + k * NW;
         const float p = __builtin_amdgcn_exp2f(sc[lt * kTileTokens + lane] - m);
-        const unsigned pf = (unsigned)__builtin_fmaf(p, fx_scale, 0.5f);
+        unsigned pf = (unsigned)__builtin_fmaf(p, fx_scale, 0.5f);
         lane_sum += pf;
+        // fused step: the new token's value codes are found in the epilogue; its weight waits in LDS
+        if (has_new && tile0 + lt == tile_new && lane == u_new) {
+            *pf_new = pf;
+            pf = 0;
+        }
 #pragma unroll
         for (int s = 0; s < GH; ++s) lds_add(slot_addr<GH, B>(w, col, s), pf);
     }, [&] {
@@ -316,6 +363,40 @@ __global__ __launch_bounds__(NT) void decode_rope_kernel(DecodeArgs a, const flo
     lane_sum = wave_sum_u32(lane_sum);
     lds_barrier();
     if (lane == 0) scr[wave] = __uint_as_float(lane_sum);
+
+    // fused step: encode the new value row against the value codebook (the registers of the sums
+    // below), add its weight to the bins of its codes, store the codes
+    if (has_new) {
+        static_assert(!STEP || EARLY, "the value codebook of the epilogue is in registers");
+#pragma unroll
+        for (int ch = 0; ch < NCH; ++ch) {
+            float xv[C];
+#pragma unroll
+            for (int i = 0; i < C / 2; ++i) {
+                const half2_t h = __builtin_bit_cast(half2_t, xvw[ch][i]);
+                xv[2 * i] = (float)h.x;
+                xv[2 * i + 1] = (float)h.y;
+            }
+            Nearest vnear;
+#pragma unroll
+            for (int k = 0; k < KB; ++k) {
+                const int j0 = ((tid + k * NT) >> 4) * JPL;
+#pragma unroll
+                for (int jj = 0; jj < JPL; ++jj)
+                    vnear.offer(centroid_distance<C>(xv, &rawv[EARLY ? ch : 0][k].w[jj * (C / 2)]), j0 + jj);
+            }
+            const unsigned long long vkey = group_lanes_min(vnear.key());
+            if (lane < 16) lds_min_u64(&keys[GH + ch * 16 + gl16], vkey);
+        }
+        lds_barrier();
+        if (tid < GH) {
+            const unsigned code = (unsigned)(keys[GH + tid] & 0xffffffffu);
+            lds_add((code * RW + tid * R) * 4u, *pf_new);
+        }
+        if (writer)
+            store_new_codes<GH, B>(const_cast<uint8_t*>(a.v_codes) + a.map.tile_index(n, hkv, tile_new) * F::TILE_BYTES, keys + GH, u_new, tid);
+        lds_barrier();
+    }
     float acc[NCH][C];
 #pragma unroll
     for (int ch = 0; ch < NCH; ++ch) {
@@ -379,11 +460,11 @@ __global__ __launch_bounds__(NT) void decode_rope_kernel(DecodeArgs a, const flo
     }
 }
 
-template <int GH, int C>
+template <int GH, int C, bool STEP>
 cq_status launch_rope_variant(const DecodeArgs& a, const float2* tile_tab, const float2* lane_tab, hipStream_t stream)
 {
     constexpr int NT = 1024;
-    auto kernel = decode_rope_kernel<GH, C, NT>;
+    auto kernel = decode_rope_kernel<GH, C, NT, STEP>;
     static std::once_flag once;
     static hipError_t setup = hipSuccess;
     std::call_once(once, [&] {
@@ -396,7 +477,7 @@ cq_status launch_rope_variant(const DecodeArgs& a, const float2* tile_tab, const
                                         hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
     });
     if (setup != hipSuccess) return CQ_ERR_HIP;
-    const size_t smem = kTabBytes + kTrgBytes + (size_t)a.tiles_per_split * kTileTokens * 4;
+    const size_t smem = kTabBytes + kTrgBytes + (size_t)a.tiles_per_split * kTileTokens * 4 + (STEP ? kKeyFloats(GH) * 4 : 0);
     if (smem > 160 * 1024) return CQ_ERR_INVALID_ARG;
     const unsigned grid = (unsigned)(a.batch * a.n_q_heads * a.n_split);
     hipLaunchKernelGGL(kernel, dim3(grid), dim3(NT), smem, stream, a, tile_tab, lane_tab);
@@ -425,9 +506,13 @@ cq_status launch_decode_rope(const DecodeArgs& a, const float* tables, int t_cap
     const float2* lane_tab = tile_tab + (size_t)(t_cap / kTileTokens) * kPairs;
     cq_status st = CQ_ERR_UNSUPPORTED;
     if (a.f.b == 8 && a.f.head_dim == 128) {
-        if (a.f.gh == 16 && a.f.c == 8) st = launch_rope_variant<16, 8>(a, tile_tab, lane_tab, stream);
-        else if (a.f.gh == 32 && a.f.c == 4) st = launch_rope_variant<32, 4>(a, tile_tab, lane_tab, stream);
-        else if (a.f.gh == 64 && a.f.c == 2) st = launch_rope_variant<64, 2>(a, tile_tab, lane_tab, stream);
+        const bool step = a.xk_new != nullptr;
+        if (a.f.gh == 16 && a.f.c == 8)
+            st = step ? launch_rope_variant<16, 8, true>(a, tile_tab, lane_tab, stream) : launch_rope_variant<16, 8, false>(a, tile_tab, lane_tab, stream);
+        else if (a.f.gh == 32 && a.f.c == 4)
+            st = step ? launch_rope_variant<32, 4, true>(a, tile_tab, lane_tab, stream) : launch_rope_variant<32, 4, false>(a, tile_tab, lane_tab, stream);
+        else if (a.f.gh == 64 && a.f.c == 2)
+            st = step ? launch_rope_variant<64, 2, true>(a, tile_tab, lane_tab, stream) : launch_rope_variant<64, 2, false>(a, tile_tab, lane_tab, stream);
     }
     if (st != CQ_OK) return st;
     if (a.n_split > 1)

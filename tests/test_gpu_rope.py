@@ -160,3 +160,100 @@ def test_rope_rejects_the_1024_centroid_format():
     with pytest.raises(cq.CQError):
         cq.cq_decode_attention_rope(dev(q), codes_to_cache(kc, fmt, 64), codes_to_cache(vc, fmt, 64), dev(ck), dev(cv),
                                     0.1, fmt, 64, 64, rope)
+
+
+# ------------------------------------------------------------------------------------------
+# fused decode step on pre-rotation caches
+# ------------------------------------------------------------------------------------------
+def _step_case(seed, c, b, hq, hkv, B, T, t_cap):
+    """Caches holding T - 1 encoded tokens per sequence, the new (pre-rotation) rows, a query."""
+    fmt = cq.CQFormat(c, b, 128, hkv)
+    D = hkv * 128
+    rk, rv = synth.tensor_recipe(70 + seed, 0, "k", D), synth.tensor_recipe(70 + seed, 0, "v", D)
+    ck, cv = dev(synth.sample_codebook(rk, c, b)), dev(synth.sample_codebook(rv, c, b))
+    kc = torch.full((cq.cq_cache_bytes(fmt, B, t_cap),), 0x3C, dtype=torch.uint8, device="cuda")
+    vc = torch.full_like(kc, 0xC3)
+    if T > 1:
+        xk = np.stack([synth.sample_activations(rk, T - 1, chunk=n) for n in range(B)])
+        xv = np.stack([synth.sample_activations(rv, T - 1, chunk=n) for n in range(B)])
+        cq.cq_encode_kv(dev(xk), dev(xv), ck, cv, fmt, kc, vc, 0, t_cap)
+    xk1 = np.concatenate([synth.sample_activations(rk, 1, chunk=500 + n) for n in range(B)])
+    xv1 = np.concatenate([synth.sample_activations(rv, 1, chunk=500 + n) for n in range(B)])
+    q = dev(synth.sample_query(70 + seed, 0, B, hq, 128))
+    torch.cuda.synchronize()
+    return fmt, q, dev(xk1), dev(xv1), kc, vc, ck, cv
+
+
+@pytest.mark.parametrize("c,b", ROPE_FORMATS)
+@pytest.mark.parametrize("hq,hkv,T,split", [(4, 4, 1, 0), (4, 4, 64, 0), (8, 2, 65, 0), (4, 2, 1000, 0),
+                                            (4, 4, 1000, 256), (16, 8, 300, 64)])
+def test_rope_step_equals_encode_then_rope_attention(c, b, hq, hkv, T, split):
+    B, t_cap = 2, 1024
+    fmt, q, xk1, xv1, kc, vc, ck, cv = _step_case(T, c, b, hq, hkv, B, T, t_cap)
+    rope = cq.RopeTable(BASE, t_cap)
+    kc2, vc2 = kc.clone(), vc.clone()
+    cq.cq_encode_kv(xk1.view(B, 1, -1), xv1.view(B, 1, -1), ck, cv, fmt, kc2, vc2, T - 1, t_cap)
+    want = cq.cq_decode_attention_rope(q, kc2, vc2, ck, cv, 0.09, fmt, T, t_cap, rope, tokens_per_split=split)
+    got = cq.cq_decode_step_rope(q, xk1, xv1, kc, vc, ck, cv, 0.09, fmt, T, t_cap, rope, tokens_per_split=split)
+    torch.cuda.synchronize()
+    assert torch.equal(kc, kc2) and torch.equal(vc, vc2), "stored codes differ from cq_encode_kv"
+    assert torch.equal(got.view(torch.int16), want.view(torch.int16)), "outputs differ"
+
+
+def test_rope_step_ragged_lengths_and_oracle():
+    # sequences of different lengths: each new token lands at its own position; also against the
+    # oracle end to end (codes of the new rows, then attention with rotation)
+    c, b, hq, hkv, B, T, t_cap = 4, 8, 8, 4, 3, 700, 704
+    fmt, q, xk1, xv1, kc, vc, ck, cv = _step_case(9, c, b, hq, hkv, B, T, t_cap)
+    rope = cq.RopeTable(BASE, t_cap)
+    lens = np.array([700, 1, 65], dtype=np.int32)
+    kc2, vc2 = kc.clone(), vc.clone()
+    per_seq = kc.numel() // B
+    for n in range(B):
+        sl = slice(n * per_seq, (n + 1) * per_seq)
+        cq.cq_encode_kv(xk1[n].view(1, 1, -1), xv1[n].view(1, 1, -1), ck, cv, fmt, kc2[sl], vc2[sl], int(lens[n]) - 1, t_cap)
+    want = cq.cq_decode_attention_rope(q, kc2, vc2, ck, cv, 0.1, fmt, T, t_cap, rope, seq_lens=dev(lens), tokens_per_split=128)
+    got = cq.cq_decode_step_rope(q, xk1, xv1, kc, vc, ck, cv, 0.1, fmt, T, t_cap, rope, seq_lens=dev(lens), tokens_per_split=128)
+    torch.cuda.synchronize()
+    assert torch.equal(kc, kc2) and torch.equal(vc, vc2)
+    assert torch.equal(got.view(torch.int16), want.view(torch.int16))
+    from gpu_util import cache_to_codes
+    kcodes, vcodes = cache_to_codes(kc, fmt, B, t_cap, T), cache_to_codes(vc, fmt, B, t_cap, T)
+    ref = O.attention(q.cpu().numpy(), kcodes, vcodes, ck.cpu().numpy(), cv.cpu().numpy(), 0.1, hkv, seq_lens=lens,
+                      rope_base=BASE)
+    check_attention(got.cpu().numpy(), ref)
+    for n in range(B):
+        p = int(lens[n]) - 1
+        for codes, x1, cb in ((kcodes, xk1, ck), (vcodes, xv1, cv)):
+            wantc, d1, d2 = O.encode(x1[n:n + 1].cpu().numpy(), cb.cpu().numpy(), with_distances=True)
+            assert not ((codes[n, p:p + 1] != wantc) & ~((d2 - d1) < 1e-6 * d2)).any()
+
+
+def test_rope_step_paged_equals_contiguous():
+    c, b, hq, hkv, B, T, t_cap = 8, 8, 4, 4, 2, 200, 256
+    fmt, q, xk1, xv1, kc, vc, ck, cv = _step_case(10, c, b, hq, hkv, B, T, t_cap)
+    rope = cq.RopeTable(BASE, t_cap)
+    n_tiles = t_cap // 64
+    n_pages = B * n_tiles + 3
+    rng = np.random.default_rng(3)
+    perm = rng.permutation(n_pages)[:B * n_tiles].astype(np.int32).reshape(B, n_tiles)
+    tb = cq.cq_code_bytes_per_token_head(fmt) * 64
+    pools = []
+    for cache in (kc, vc):
+        src = cache.cpu().numpy().reshape(B, hkv, n_tiles, tb)
+        pool = np.full((n_pages, hkv, tb), 0x77, dtype=np.uint8)
+        for n in range(B):
+            for i in range(n_tiles):
+                pool[perm[n, i]] = src[n, :, i]
+        pools.append(dev(pool.reshape(-1)))
+    pages = cq.PageTable(dev(perm), n_pages)
+    want = cq.cq_decode_step_rope(q, xk1, xv1, kc, vc, ck, cv, 0.1, fmt, T, t_cap, rope)
+    got = cq.cq_decode_step_rope_paged(q, xk1, xv1, pools[0], pools[1], ck, cv, 0.1, fmt, T, pages, rope)
+    torch.cuda.synchronize()
+    assert torch.equal(got.view(torch.int16), want.view(torch.int16))
+    for cache, pool in ((kc, pools[0]), (vc, pools[1])):
+        src = cache.cpu().numpy().reshape(B, hkv, n_tiles, tb)
+        pl = pool.cpu().numpy().reshape(n_pages, hkv, tb)
+        for n in range(B):
+            for i in range(n_tiles):
+                assert np.array_equal(pl[perm[n, i]], src[n, :, i])
