@@ -562,7 +562,7 @@ cq_status launch_decode_merge(const float* partials, uint16_t* out, int rows, in
 
 int decode_max_tiles_per_split(const Derived& f)
 {
-    if (f.b == 10) return (160 * 1024 / 4 - Fmt<16, 10>::TAB_FLOATS - kKeyFloats(16)) / kTileTokens;   // 126: 160 KB of LDS
+    if (f.b == 10) return (160 * 1024 / 4 - Fmt<16, 10>::TAB_FLOATS - kKeyFloats(16)) / kTileTokens;   // 382: 160 KB of LDS
     if (f.gh <= 32) return 256 * 32 / kTileTokens;                                    // 128: scores inside the table
     return 256;
 }

@@ -133,8 +133,11 @@ __device__ __forceinline__ int fixed_point_exponent(float l_est)
 template <int GH, int B>
 struct Fmt {
     static constexpr int K = 1 << B;                    // rows
-    static constexpr int RW = B == 8 ? 64 : 32;         // words per row
-    static constexpr int R = GH == 16 ? 2 : 1;          // replicas per group
+    // replicas per group: two where a row would otherwise be 16 words and 4 lanes of a wavefront
+    // would share each column; not for b = 10, whose 1024 rows would then fill 128 KB and leave
+    // room for short splits only (fixed costs per split dominate that format)
+    static constexpr int R = (GH == 16 && B == 8) ? 2 : 1;
+    static constexpr int RW = B == 8 ? 64 : 16;         // words per row
     static constexpr bool SCORES_IN_TABLE = B == 8 && GH <= 32;   // words 32..63 of each row
     static constexpr int P = GH / 16;                   // 16-byte planes of low code bytes
     static constexpr int TAB_FLOATS = K * RW;
@@ -147,7 +150,7 @@ struct Fmt {
 template <int GH, int B>
 __device__ __forceinline__ int column(int lane, int g)
 {
-    if constexpr (GH == 16) {
+    if constexpr (Fmt<GH, B>::R == 2) {
         return 2 * g + ((lane >> 4) & 1);       // lanes l and l + 16 differ, l and l + 32 share
     } else {
         (void)lane;
@@ -242,7 +245,8 @@ __device__ __forceinline__ unsigned slot_addr(const Tile<GH, B>& w, const Column
     } else {
         const unsigned lo = (code_word >> (8 * k)) & 0xffu;
         const unsigned hi = (w.hi >> (2 * s)) & 3u;
-        return ((lo << 7) | (hi << 15)) | col.v[s];
+        constexpr int SH = Fmt<GH, B>::RW == 32 ? 7 : 6;      // log2 of the row size in bytes
+        return ((lo << SH) | (hi << (SH + 8))) | col.v[s];
     }
 }
 

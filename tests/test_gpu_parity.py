@@ -246,13 +246,25 @@ def test_decode_split_invariance_and_ragged_lengths(c, b):
     ref = O.attention(q, kc, vc, ck, cv, scale, hkv, seq_lens=lens)
     kcache, vcache = codes_to_cache(kc, fmt, t_cap), codes_to_cache(vc, fmt, t_cap)
     outs = []
-    for split in (0, 64, 448, 4032, 7936):
+    for split in (0, 64, 448, 4032, 7936 if b != 10 else 24448):
         out = gpu_attention(q, kcache, vcache, ck, cv, scale, fmt, T, t_cap, seq_lens=lens, tokens_per_split=split)
         check_attention(out, ref)
         outs.append(out.astype(np.float64))
     # the number of splits changes summation order only
     for o in outs[1:]:
         assert np.max(np.abs(o - outs[0])) <= 2e-3 * np.max(np.abs(outs[0]))
+
+
+def test_decode_1024_centroid_format_one_long_split():
+    # CQ-8c10b keeps up to 24448 tokens per split on chip: 20000 tokens in one split, and in three
+    c, b, hq, hkv, B, T, t_cap = 8, 10, 2, 1, 1, 20000, 20032
+    fmt, q, kc, vc, ck, cv = _attn_case(11, c, b, hq, hkv, B, T)
+    ref = O.attention(q, kc, vc, ck, cv, 0.1, hkv)
+    kcache, vcache = codes_to_cache(kc, fmt, t_cap), codes_to_cache(vc, fmt, t_cap)
+    for split in (24448, 8064, 0):
+        out = gpu_attention(q, kcache, vcache, ck, cv, 0.1, fmt, T, t_cap, tokens_per_split=split)
+        check_attention(out, ref)
+    assert cq.cq_decode_workspace_bytes(fmt, B, hq, T, 24448 + 64) == 0        # beyond the on-chip buffer
 
 
 def test_decode_single_token_returns_the_dequantized_value_bit_exactly():
@@ -409,7 +421,7 @@ def _sweep_cases():
         B = int(rng.integers(1, 4))
         T = int(rng.choice([1, 2, 64, 127, 128, 129, 500, 1337, 2049]))
         tiles = -(-T // 64)
-        max_split_tiles = 126 if b == 10 else (128 if c >= 4 else 256)
+        max_split_tiles = 382 if b == 10 else (128 if c >= 4 else 256)
         split_tiles = int(rng.integers(1, min(tiles, max_split_tiles) + 1)) if rng.random() < 0.6 else 0
         ragged = bool(rng.random() < 0.5)
         cases.append((i, c, b, hkv * qper, hkv, B, T, split_tiles * 64, ragged))
