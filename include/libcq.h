@@ -203,7 +203,8 @@ CQ_API cq_status cq_decode_step(const void *q, const void *x_k_new, const void *
  * cq_layer_table_fill from a host array of cq_layer_io records (each pointer: device memory,
  * non-null, 16-byte aligned, with the meaning, shape and ownership of the argument of the same
  * name of cq_decode_step; no two layers may share a cache or an output).  The fill validates what
- * the host can see of them and copies the records on `stream`; the host array may be reused when
+ * the host can see of them and writes the records with a small kernel on `stream` (they travel
+ * as kernel arguments, so the call may also be captured into a graph); the host array may be reused when
  * it returns.  The table (cq_layer_table_bytes(n_layers) bytes, 16-byte aligned) stays owned by
  * the caller and is only read by cq_decode_step_layers, which trusts its contents.
  *

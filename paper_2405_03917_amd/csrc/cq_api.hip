@@ -4,6 +4,7 @@
 
 #include <algorithm>
 #include <cmath>
+#include <cstring>
 
 #include "cq_internal.hpp"
 
@@ -459,10 +460,16 @@ cq_status cq_layer_table_fill(const cq_layer_io* layers, int32_t n_layers, void*
                 layers[m].v_codes == io.k_codes || layers[m].out == io.out)
                 return CQ_ERR_INVALID_ARG;
     }
-    // (the copy engine reads pageable host memory before the call returns)
-    if (hipMemcpyAsync(table, layers, sizeof(LayerPtrs) * (size_t)n_layers, hipMemcpyHostToDevice,
-                       static_cast<hipStream_t>(stream)) != hipSuccess)
-        return CQ_ERR_HIP;
+    // the records travel as kernel arguments (copied at launch: the host array is free again when
+    // this returns, and the write is an ordinary kernel on the stream, also under graph capture)
+    for (int32_t l0 = 0; l0 < n_layers; l0 += LayerChunk::N) {
+        LayerChunk chunk;
+        const int32_t cnt = std::min<int32_t>(LayerChunk::N, n_layers - l0);
+        std::memcpy(chunk.p, layers + l0, sizeof(LayerPtrs) * (size_t)cnt);
+        const cq_status st = launch_layer_table_write(chunk, cnt, static_cast<LayerPtrs*>(table) + l0,
+                                                      static_cast<hipStream_t>(stream));
+        if (st != CQ_OK) return st;
+    }
     return CQ_OK;
 }
 

@@ -54,6 +54,11 @@ struct LayerPtrsGlobal {
 #undef CQ_GLOBAL
 static_assert(sizeof(LayerPtrsGlobal) == sizeof(LayerPtrs), "same record");
 
+__global__ void layer_table_write_kernel(LayerChunk chunk, int count, LayerPtrs* dst)
+{
+    if ((int)threadIdx.x < count) dst[threadIdx.x] = chunk.p[threadIdx.x];
+}
+
 // STEP = true is the fused decode step: the workgroup whose split holds the newest position
 // (t_n - 1) also encodes that token's key and value rows for its KV head.  Keys: while it builds
 // the score table (the key codebook is in registers anyway); the tile that holds the position is
@@ -552,6 +557,12 @@ cq_status launch_format(const DecodeArgs& a, hipStream_t stream)
 }
 
 }  // namespace
+
+cq_status launch_layer_table_write(const LayerChunk& chunk, int count, LayerPtrs* dst, hipStream_t stream)
+{
+    hipLaunchKernelGGL(layer_table_write_kernel, dim3(1), dim3(64), 0, stream, chunk, count, dst);
+    return hipGetLastError() == hipSuccess ? CQ_OK : CQ_ERR_HIP;
+}
 
 cq_status launch_decode_merge(const float* partials, uint16_t* out, int rows, int n_split, int head_dim, hipStream_t stream)
 {

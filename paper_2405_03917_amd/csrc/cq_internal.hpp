@@ -78,6 +78,12 @@ struct LayerPtrs {
     uint16_t* out;
 };
 
+// Up to N records passed by value to the kernel that writes them into the device table.
+struct LayerChunk {
+    static constexpr int N = 32;
+    LayerPtrs p[N];
+};
+
 struct DecodeArgs {
     const uint16_t* q;
     const uint8_t* k_codes;
@@ -150,6 +156,7 @@ cq_status launch_encode(const EncodeArgs& a, hipStream_t stream);
 cq_status launch_encode_tiles(const EncodeArgs& a, hipStream_t stream);
 cq_status launch_decode(const DecodeArgs& a, hipStream_t stream);
 // merges the partials of `rows` (sequence, query head) pairs, n_split each, into fp16 rows
+cq_status launch_layer_table_write(const LayerChunk& chunk, int count, LayerPtrs* dst, hipStream_t stream);
 cq_status launch_decode_merge(const float* partials, uint16_t* out, int rows, int n_split, int head_dim, hipStream_t stream);
 
 // Keys cached before the rotary position embedding (cq_decode_rope.hip).  The table holds, for

@@ -68,6 +68,7 @@ def _fill_and_check(cfg_id, n_attn_samples, n_token_samples, chunk_tokens, fused
         xk1 = synth.sample_activations_torch(rk, B, 9001, "cuda").view(B, D)
         xv1 = synth.sample_activations_torch(rv, B, 9002, "cuda").view(B, D)
         k1, v1 = kcache.clone(), vcache.clone()
+        k_before, v_before = kcache.clone(), vcache.clone()
         cq.cq_encode_kv(xk1[:, None, :], xv1[:, None, :], ck, cv, fmt, k1, v1, T - 1, T)
         ref = cq.cq_decode_attention(dev(q_h), k1, v1, ck, cv, scale, fmt, T, T)
         out2 = cq.cq_decode_step(dev(q_h), xk1, xv1, kcache, vcache, ck, cv, scale, fmt, T, T)
@@ -85,6 +86,30 @@ def _fill_and_check(cfg_id, n_attn_samples, n_token_samples, chunk_tokens, fused
             check_codes(vc[T - 1:], xv1_h[n:n + 1, sl], cv_h[hk * Gh:(hk + 1) * Gh])
             ref64 = oracle_head_attention(q_h[n, hq], kc, vc, ck_h[hk * Gh:(hk + 1) * Gh], cv_h[hk * Gh:(hk + 1) * Gh], scale)
             check_attention(out2_h[n, hq][None], ref64[None])
+        # the same step for two layers in one launch (cq_decode_step_layers): this layer, and a second
+        # one with its own caches and the query heads in another order
+        q2 = dev(np.ascontiguousarray(q_h[:, ::-1]))
+        want2 = cq.cq_decode_step(q2, xv1, xk1, v_before.clone(), k_before.clone(), cv, ck, scale, fmt, T, T)
+        layers = [dict(q=dev(q_h), x_k_new=xk1, x_v_new=xv1, k_codes=k_before, v_codes=v_before, k_centroids=ck,
+                       v_centroids=cv, out=torch.empty_like(out2)),
+                  dict(q=q2, x_k_new=xv1, x_v_new=xk1, k_codes=v_before.clone(), v_codes=k_before.clone(),
+                       k_centroids=cv, v_centroids=ck, out=torch.empty_like(out2))]
+        outs = cq.cq_decode_step_layers(cq.LayerTable(layers, fmt, T), scale, T)
+        torch.cuda.synchronize()
+        assert torch.equal(outs[0].view(torch.int16), out2.view(torch.int16))
+        assert torch.equal(outs[1].view(torch.int16), want2.view(torch.int16))
+        assert torch.equal(k_before, k1) and torch.equal(v_before, v1)
+        # and the caches read as pre-rotation keys (cq_decode_attention_rope), sampled rows by the oracle
+        from oracle import cq_oracle as O
+        rope = cq.RopeTable(10000.0, T)
+        out3 = cq.cq_decode_attention_rope(dev(q_h), kcache, vcache, ck, cv, scale, fmt, T, T, rope).cpu().numpy()
+        for n, hq in sorted(picks)[:3]:
+            hk = hq // rep
+            kc = head_stream_codes(kcache, fmt, B, T, n, hk, T)
+            vc = head_stream_codes(vcache, fmt, B, T, n, hk, T)
+            ref3 = O.attention(q_h[n, hq][None, None, :], kc[None], vc[None], ck_h[hk * Gh:(hk + 1) * Gh],
+                               cv_h[hk * Gh:(hk + 1) * Gh], scale, 1, rope_base=10000.0)[0, 0]
+            check_attention(out3[n, hq][None], ref3[None])
     return cq.cq_decode_default_split(fmt, B, cfg.n_q_heads, T)
 
 
