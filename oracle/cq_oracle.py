@@ -179,3 +179,27 @@ def attention(q: np.ndarray, k_codes: np.ndarray, v_codes: np.ndarray,
     if want_probs:
         res += (probs,)
     return res[0] if len(res) == 1 else res
+
+
+def chunk_attention(q: np.ndarray, k_codes: np.ndarray, v_codes: np.ndarray,
+                    k_centroids: np.ndarray, v_centroids: np.ndarray, scale: float,
+                    n_kv_heads: int, seq_lens: Optional[np.ndarray] = None) -> np.ndarray:
+    """Causal attention of the LAST m tokens of each sequence over its coded cache: Eq. 1 of the
+    paper applied once per query token, each over the cached tokens up to and including its own
+    position (the cache already holds the codes of the m tokens).
+
+    q fp16 [B, m, Hq, d]: query j of sequence n sits at position t_n - m + j, where t_n =
+    seq_lens[n] (default: all T cached tokens), and attends to tokens 0 .. t_n - m + j.
+    Returns fp64 [B, m, Hq, d].  One call of attention() per query token: no blocking, no reuse."""
+    q = np.asarray(q)
+    B, m, Hq, d = q.shape
+    T = k_codes.shape[1]
+    t_n = np.full(B, T, dtype=np.int64) if seq_lens is None else np.asarray(seq_lens, dtype=np.int64)
+    if np.any(t_n < m) or np.any(t_n > T):
+        raise ValueError("every sequence must hold its m query tokens: m <= seq_len <= T")
+    out = np.empty((B, m, Hq, d), dtype=np.float64)
+    for j in range(m):
+        lens = (t_n - m + j + 1).astype(np.int32)
+        out[:, j] = attention(np.ascontiguousarray(q[:, j]), k_codes, v_codes, k_centroids, v_centroids, scale,
+                              n_kv_heads, seq_lens=lens)
+    return out

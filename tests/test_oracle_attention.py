@@ -263,3 +263,56 @@ def test_rope_matches_the_rotate_half_formulation_in_torch():
     k_rot = k * emb.cos() + rot_half * emb.sin()
     want = torch.from_numpy(q[0].astype(np.float64)) @ k_rot.T
     assert np.allclose(scores[0], want.numpy(), rtol=1e-12, atol=1e-12)
+
+
+# ------------------------------------------------------------------------------------------
+# causal attention of the last m tokens over the coded cache (chunk_attention)
+# ------------------------------------------------------------------------------------------
+def _chunk_case(seed, B, m, Hq, Hkv, d, T, c, b):
+    q1, kc, vc, ck, cv = _case(seed, B, Hq, Hkv, d, T, c, b)
+    q = np.random.default_rng(seed + 50).standard_normal((B, m, Hq, d)).astype(np.float16)
+    return q, kc, vc, ck, cv
+
+
+@pytest.mark.parametrize("Hq,Hkv", [(4, 4), (4, 2)])
+def test_chunk_attention_equals_torch_sdpa_with_a_causal_mask(Hq, Hkv):
+    import torch
+    B, m, d, T, c, b = 2, 7, 16, 23, 4, 4
+    q, kc, vc, ck, cv = _chunk_case(31, B, m, Hq, Hkv, d, T, c, b)
+    scale = 0.21
+    out = O.chunk_attention(q, kc, vc, ck, cv, scale, Hkv)
+    k = torch.from_numpy(_dequant_np(kc, ck)).reshape(B, T, Hkv, d).permute(0, 2, 1, 3)
+    v = torch.from_numpy(_dequant_np(vc, cv)).reshape(B, T, Hkv, d).permute(0, 2, 1, 3)
+    rep = Hq // Hkv
+    k, v = k.repeat_interleave(rep, dim=1), v.repeat_interleave(rep, dim=1)
+    qt = torch.from_numpy(q.astype(np.float64)).permute(0, 2, 1, 3)               # [B, Hq, m, d]
+    # query j sits at position T - m + j: it sees tokens 0 .. T - m + j
+    mask = torch.arange(T)[None, :] <= (T - m + torch.arange(m))[:, None]
+    want = torch.nn.functional.scaled_dot_product_attention(qt, k, v, attn_mask=mask, scale=scale)
+    assert np.allclose(out, want.permute(0, 2, 1, 3).numpy(), rtol=1e-12, atol=1e-13)
+
+
+def test_chunk_attention_special_cases():
+    B, m, Hq, Hkv, d, T, c, b = 2, 5, 2, 2, 8, 11, 2, 3
+    q, kc, vc, ck, cv = _chunk_case(32, B, m, Hq, Hkv, d, T, c, b)
+    out = O.chunk_attention(q, kc, vc, ck, cv, 0.3, Hkv)
+    # the last query is plain decode attention over the whole cache, the first sees T - m + 1 tokens
+    assert np.array_equal(out[:, -1], O.attention(np.ascontiguousarray(q[:, -1]), kc, vc, ck, cv, 0.3, Hkv))
+    first = O.attention(np.ascontiguousarray(q[:, 0]), kc[:, :T - m + 1], vc[:, :T - m + 1], ck, cv, 0.3, Hkv)
+    assert np.allclose(out[:, 0], first, rtol=1e-13, atol=0)
+    # m = T: the first query sees only token 0 and returns its dequantized value exactly
+    qT = np.random.default_rng(5).standard_normal((B, T, Hq, d)).astype(np.float16)
+    full = O.chunk_attention(qT, kc, vc, ck, cv, 0.3, Hkv)
+    v0 = _dequant_np(vc[:, :1], cv).reshape(B, Hkv, d)
+    assert np.array_equal(full[:, 0], v0)
+    # ragged: each sequence's chunk ends at its own length; tokens behind it are never read
+    lens = np.array([11, 6], dtype=np.int32)
+    rag = O.chunk_attention(q, kc, vc, ck, cv, 0.3, Hkv, seq_lens=lens)
+    assert np.array_equal(rag[0], out[0])
+    kc2, vc2 = kc.copy(), vc.copy()
+    kc2[1, 6:], vc2[1, 6:] = 0, 0
+    assert np.array_equal(O.chunk_attention(q, kc2, vc2, ck, cv, 0.3, Hkv, seq_lens=lens)[1], rag[1])
+    short = O.chunk_attention(q[1:], kc[1:, :6], vc[1:, :6], ck, cv, 0.3, Hkv)
+    assert np.allclose(rag[1], short[0], rtol=1e-13, atol=0)
+    with pytest.raises(ValueError):
+        O.chunk_attention(q, kc, vc, ck, cv, 0.3, Hkv, seq_lens=np.array([11, 4], dtype=np.int32))   # shorter than the chunk
