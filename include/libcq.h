@@ -272,6 +272,41 @@ CQ_API cq_status cq_decode_step_paged(const void *q, const void *x_k_new, const 
                                void *out, void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * cq_chunk_attention -- Eq. 1 of the paper for the LAST m tokens of each sequence at once, with
+ * the causal restriction that makes it m single-token attentions: query token j sits at position
+ * t_n - m + j (t_n = seq_lens[n], default t) and attends to the cached tokens 0 .. t_n - m + j.
+ * The caches already hold the codes of the m tokens (cq_encode_kv first).  Use: a prefill chunk
+ * after the first, or the verification of m speculated tokens.
+ *
+ *   q                 device, fp16 [batch][m][n_q_heads][head_dim]
+ *   out               device, fp16 [batch][m][n_q_heads][head_dim]
+ *   m                 query tokens per sequence, 1 <= m <= seq_lens[n] <= t <= t_cap
+ *   tokens_per_split  0 = cq_chunk_default_split(...); otherwise a multiple of 64: the context is
+ *                     cut into pieces of this many tokens, each handled by its own workgroups
+ *   workspace         device, cq_chunk_workspace_bytes(...) bytes (may be null when that is 0 or
+ *                     the context is not split)
+ *   everything else as in cq_decode_attention; stored keys are the keys the queries are dotted
+ *   with (no positional rotation).
+ * The contraction runs on the matrix cores in fp16 with fp32 accumulation: scores are exact
+ * products summed in fp32; probabilities enter the value product as two fp16 numbers (22 bits).
+ * b = 8 formats with head_dim 128 only (CQ_ERR_UNSUPPORTED otherwise).
+ * Errors: as cq_decode_attention; CQ_ERR_INVALID_ARG also for m <= 0 or m > t.
+ */
+CQ_API int32_t cq_chunk_default_split(const cq_format *fmt, int32_t batch, int32_t n_q_heads, int32_t m, int32_t t);
+CQ_API size_t cq_chunk_workspace_bytes(const cq_format *fmt, int32_t batch, int32_t n_q_heads, int32_t m, int32_t t,
+                                int32_t tokens_per_split);
+CQ_API cq_status cq_chunk_attention(const void *q, const void *k_codes, const void *v_codes,
+                             const void *k_centroids, const void *v_centroids, float scale, const cq_format *fmt,
+                             int32_t batch, int32_t n_q_heads, int32_t m, int32_t t, int32_t t_cap,
+                             const int32_t *seq_lens, int32_t tokens_per_split,
+                             void *out, void *workspace, size_t workspace_bytes, void *stream);
+CQ_API cq_status cq_chunk_attention_paged(const void *q, const void *k_pool, const void *v_pool,
+                                   const void *k_centroids, const void *v_centroids, float scale, const cq_format *fmt,
+                                   int32_t batch, int32_t n_q_heads, int32_t m, int32_t t, const cq_page_table *pages,
+                                   const int32_t *seq_lens, int32_t tokens_per_split,
+                                   void *out, void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * Keys cached BEFORE the rotary position embedding.  Section 3.2 quantizes key activations
  * before RoPE (the position-dependent rotation would otherwise spread each channel pair over a
  * circle and cost codebook resolution), and Eq. 1 counts the positional encoding into the

@@ -28,6 +28,7 @@ EXPORTS = (
     "cq_cache_bytes", "cq_encode", "cq_encode_kv", "cq_decode_default_split", "cq_decode_workspace_bytes",
     "cq_decode_attention", "cq_decode_step", "cq_dequantize", "cq_paged_cache_bytes", "cq_encode_kv_paged",
     "cq_decode_attention_paged", "cq_decode_step_paged", "cq_kmeans_workspace_bytes", "cq_kmeans_fit",
+    "cq_chunk_default_split", "cq_chunk_workspace_bytes", "cq_chunk_attention", "cq_chunk_attention_paged",
     "cq_layer_table_bytes", "cq_layer_table_fill", "cq_decode_step_layers",
     "cq_rope_table_bytes", "cq_rope_table", "cq_decode_rope_default_split", "cq_decode_attention_rope",
     "cq_decode_attention_rope_paged", "cq_decode_step_rope", "cq_decode_step_rope_paged", "cq_probe_stream_read", "cq_probe_copy", "cq_probe_mfma",
@@ -135,6 +136,16 @@ def load() -> ctypes.CDLL:
     lib.cq_kmeans_workspace_bytes.argtypes = [fp, i32]
     lib.cq_kmeans_fit.restype = ctypes.c_int
     lib.cq_kmeans_fit.argtypes = [vp, i64, vp, fp, i32, i32, vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
+    lib.cq_chunk_default_split.restype = i32
+    lib.cq_chunk_default_split.argtypes = [fp, i32, i32, i32, i32]
+    lib.cq_chunk_workspace_bytes.restype = ctypes.c_size_t
+    lib.cq_chunk_workspace_bytes.argtypes = [fp, i32, i32, i32, i32, i32]
+    lib.cq_chunk_attention.restype = ctypes.c_int
+    lib.cq_chunk_attention.argtypes = [vp, vp, vp, vp, vp, ctypes.c_float, fp, i32, i32, i32, i32, i32, vp, i32,
+                                       vp, vp, ctypes.c_size_t, vp]
+    lib.cq_chunk_attention_paged.restype = ctypes.c_int
+    lib.cq_chunk_attention_paged.argtypes = [vp, vp, vp, vp, vp, ctypes.c_float, fp, i32, i32, i32, i32, pp, vp, i32,
+                                             vp, vp, ctypes.c_size_t, vp]
     lib.cq_layer_table_bytes.restype = ctypes.c_size_t
     lib.cq_layer_table_bytes.argtypes = [i32]
     lib.cq_layer_table_fill.restype = ctypes.c_int
@@ -354,6 +365,80 @@ def cq_decode_attention(q, k_codes, v_codes, k_centroids, v_centroids, scale: fl
     fp16 [B, Hq, head_dim] (allocated with torch if not given, as is the workspace)."""
     call, out = prepare_decode_attention(q, k_codes, v_codes, k_centroids, v_centroids, scale, fmt, t, t_cap,
                                          seq_lens, tokens_per_split, out, workspace)
+    call(stream)
+    return out
+
+
+def cq_chunk_default_split(fmt: CQFormat, batch: int, n_q_heads: int, m: int, t: int) -> int:
+    return int(load().cq_chunk_default_split(ctypes.byref(fmt._c()), batch, n_q_heads, m, t))
+
+
+def cq_chunk_workspace_bytes(fmt: CQFormat, batch: int, n_q_heads: int, m: int, t: int, tokens_per_split: int = 0) -> int:
+    return int(load().cq_chunk_workspace_bytes(ctypes.byref(fmt._c()), batch, n_q_heads, m, t, tokens_per_split))
+
+
+def prepare_chunk_attention(q, k_codes, v_codes, k_centroids, v_centroids, scale: float, fmt: CQFormat, t: int,
+                            t_cap: int = 0, pages=None, seq_lens=None, tokens_per_split: int = 0, out=None,
+                            workspace=None):
+    """Check and marshal the arguments of cq_chunk_attention (or, with `pages`, of its paged form)
+    once.  q fp16 [B, m, Hq, head_dim].  Returns (call, out)."""
+    import torch
+    _dev(q, torch.float16, "q")
+    for name, x, dt in (("k_codes", k_codes, torch.uint8), ("v_codes", v_codes, torch.uint8),
+                        ("k_centroids", k_centroids, torch.float16), ("v_centroids", v_centroids, torch.float16)):
+        _dev(x, dt, name)
+    if q.dim() != 4 or not q.is_contiguous() or q.shape[3] != fmt.head_dim:
+        raise ValueError("q must be contiguous [B, m, Hq, head_dim]")
+    for name, cb in (("k_centroids", k_centroids), ("v_centroids", v_centroids)):
+        if not cb.is_contiguous() or tuple(cb.shape) != (fmt.groups, 1 << fmt.b, fmt.c):
+            raise ValueError(f"{name} must be contiguous [G, 2^b, c]")
+    batch, m, n_q_heads = int(q.shape[0]), int(q.shape[1]), int(q.shape[2])
+    need = cq_paged_cache_bytes(fmt, pages.n_pages) if pages is not None else cq_cache_bytes(fmt, batch, t_cap)
+    if k_codes.numel() < need or v_codes.numel() < need:
+        raise ValueError("code caches are smaller than the format, batch and capacity need")
+    sl_ptr = None
+    if seq_lens is not None:
+        _dev(seq_lens, torch.int32, "seq_lens")
+        if tuple(seq_lens.shape) != (batch,) or not seq_lens.is_contiguous():
+            raise ValueError("seq_lens must be contiguous int32 [B]")
+        sl_ptr = seq_lens.data_ptr()
+    if out is None:
+        out = torch.empty((batch, m, n_q_heads, fmt.head_dim), dtype=torch.float16, device=q.device)
+    else:
+        _dev(out, torch.float16, "out")
+        if tuple(out.shape) != (batch, m, n_q_heads, fmt.head_dim) or not out.is_contiguous():
+            raise ValueError("out must be contiguous [B, m, Hq, head_dim]")
+    if workspace is None:
+        workspace = torch.empty(max(16, cq_chunk_workspace_bytes(fmt, batch, n_q_heads, m, t, tokens_per_split)),
+                                dtype=torch.uint8, device=q.device)
+    else:
+        _dev(workspace, torch.uint8, "workspace")
+    f = fmt._c()
+    head = (q.data_ptr(), k_codes.data_ptr(), v_codes.data_ptr(), k_centroids.data_ptr(), v_centroids.data_ptr(),
+            float(scale), ctypes.byref(f), batch, n_q_heads, m, t)
+    tail = (sl_ptr, tokens_per_split, out.data_ptr(), workspace.data_ptr(), workspace.numel())
+    keep = (q, k_codes, v_codes, k_centroids, v_centroids, seq_lens, out, workspace, f, pages)
+    if pages is not None:
+        return PreparedCall(load().cq_chunk_attention_paged, head + (ctypes.byref(pages._c),) + tail, keep,
+                            "cq_chunk_attention_paged"), out
+    return PreparedCall(load().cq_chunk_attention, head + (t_cap,) + tail, keep, "cq_chunk_attention"), out
+
+
+def cq_chunk_attention(q, k_codes, v_codes, k_centroids, v_centroids, scale: float, fmt: CQFormat, t: int, t_cap: int,
+                       seq_lens=None, tokens_per_split: int = 0, out=None, workspace=None, stream=None):
+    """Causal attention of the last m tokens of each sequence over its cache: q, out fp16
+    [B, m, Hq, head_dim]; query j sits at position seq_len - m + j."""
+    call, out = prepare_chunk_attention(q, k_codes, v_codes, k_centroids, v_centroids, scale, fmt, t, t_cap, None,
+                                        seq_lens, tokens_per_split, out, workspace)
+    call(stream)
+    return out
+
+
+def cq_chunk_attention_paged(q, k_pool, v_pool, k_centroids, v_centroids, scale: float, fmt: CQFormat, t: int, pages,
+                             seq_lens=None, tokens_per_split: int = 0, out=None, workspace=None, stream=None):
+    """cq_chunk_attention over paged pools."""
+    call, out = prepare_chunk_attention(q, k_pool, v_pool, k_centroids, v_centroids, scale, fmt, t, 0, pages,
+                                        seq_lens, tokens_per_split, out, workspace)
     call(stream)
     return out
 

@@ -9,7 +9,7 @@ PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libcq.so")
-SOURCES = ["cq_api.hip", "cq_encode.hip", "cq_encode_mfma.hip", "cq_decode.hip", "cq_decode_rope.hip", "cq_kmeans.hip", "cq_probe.hip"]
+SOURCES = ["cq_api.hip", "cq_encode.hip", "cq_encode_mfma.hip", "cq_decode.hip", "cq_decode_rope.hip", "cq_chunk.hip", "cq_kmeans.hip", "cq_probe.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=hidden",

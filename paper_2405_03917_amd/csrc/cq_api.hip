@@ -438,6 +438,122 @@ cq_status cq_decode_step_paged(const void* q, const void* x_k_new, const void* x
                          stream, true);
 }
 
+namespace {
+
+// context split of the chunk kernel: enough workgroups to fill the chip, at least 8 tiles each
+int chunk_tiles_per_split(const Derived& f, int batch, int n_q_heads, int m, int t)
+{
+    const int qper = n_q_heads / f.n_kv_heads;
+    const long row_blocks = ((long)m * qper + chunk_rows_per_workgroup() - 1) / chunk_rows_per_workgroup();
+    const long base = (long)batch * f.n_kv_heads * row_blocks;
+    const int n_tiles = (t + kTileTokens - 1) / kTileTokens;
+    long n_split = std::max(1L, (512 + base - 1) / base);
+    n_split = std::min<long>(n_split, std::max(1, n_tiles / 8));
+    return (int)((n_tiles + n_split - 1) / n_split);
+}
+
+cq_status chunk_common(const void* q, const void* k_codes, const void* v_codes,
+                       const void* k_centroids, const void* v_centroids, float scale, const cq_format* fmt,
+                       int32_t batch, int32_t n_q_heads, int32_t m, int32_t t, int32_t t_cap, const cq_page_table* pages,
+                       const int32_t* seq_lens, int32_t tokens_per_split,
+                       void* out, void* workspace, size_t workspace_bytes, void* stream)
+{
+    Derived f;
+    cq_status st = derive(fmt, &f);
+    if (st != CQ_OK) return st;
+    if (f.b != 8 || f.head_dim != 128) return CQ_ERR_UNSUPPORTED;
+    CacheMap map;
+    if (pages) {
+        if ((st = paged_map(f, pages, batch, &map, &t_cap)) != CQ_OK) return st;
+    } else {
+        if (t_cap <= 0 || t_cap % kTileTokens != 0) return CQ_ERR_INVALID_ARG;
+        map = contiguous_map(f, t_cap);
+    }
+    if (!q || !k_codes || !v_codes || !k_centroids || !v_centroids || !out) return CQ_ERR_INVALID_ARG;
+    if (batch <= 0 || n_q_heads <= 0 || n_q_heads % f.n_kv_heads != 0) return CQ_ERR_INVALID_ARG;
+    if (m <= 0 || t < m || t > t_cap) return CQ_ERR_INVALID_ARG;
+    if (!std::isfinite(scale)) return CQ_ERR_INVALID_ARG;
+    if (tokens_per_split < 0 || tokens_per_split % kTileTokens != 0) return CQ_ERR_INVALID_ARG;
+    if (!aligned16(q) || !aligned16(k_codes) || !aligned16(v_codes) || !aligned16(k_centroids) ||
+        !aligned16(v_centroids) || !aligned16(out) || !aligned16(workspace))
+        return CQ_ERR_INVALID_ARG;
+    const int tiles = tokens_per_split ? tokens_per_split / kTileTokens : chunk_tiles_per_split(f, batch, n_q_heads, m, t);
+    const int n_tiles = (t + kTileTokens - 1) / kTileTokens;
+    const int n_split = (n_tiles + tiles - 1) / tiles;
+    const size_t rows = (size_t)batch * m * n_q_heads;
+    if (n_split > 1) {
+        if (!workspace) return CQ_ERR_INVALID_ARG;
+        if (workspace_bytes < sizeof(float) * rows * n_split * (f.head_dim + kPartialHeader)) return CQ_ERR_WORKSPACE_TOO_SMALL;
+    }
+    const int qper = n_q_heads / f.n_kv_heads;
+    const int64_t row_blocks = ((int64_t)m * qper + chunk_rows_per_workgroup() - 1) / chunk_rows_per_workgroup();
+    if ((int64_t)batch * f.n_kv_heads * row_blocks * n_split > 0x7fffffffLL || rows * n_split > 0x7fffffffULL)
+        return CQ_ERR_INVALID_ARG;
+    ChunkArgs a;
+    a.q = static_cast<const uint16_t*>(q);
+    a.k_codes = static_cast<const uint8_t*>(k_codes);
+    a.v_codes = static_cast<const uint8_t*>(v_codes);
+    a.k_centroids = static_cast<const uint16_t*>(k_centroids);
+    a.v_centroids = static_cast<const uint16_t*>(v_centroids);
+    a.scale_log2e = scale * 1.4426950408889634f;
+    a.batch = batch;
+    a.m = m;
+    a.n_q_heads = n_q_heads;
+    a.t = t;
+    a.map = map;
+    a.seq_lens = seq_lens;
+    a.tiles_per_split = tiles;
+    a.n_split = n_split;
+    a.partials = static_cast<float*>(workspace);
+    a.out = static_cast<uint16_t*>(out);
+    a.f = f;
+    return launch_chunk_attention(a, static_cast<hipStream_t>(stream));
+}
+
+}  // namespace
+
+int32_t cq_chunk_default_split(const cq_format* fmt, int32_t batch, int32_t n_q_heads, int32_t m, int32_t t)
+{
+    Derived f;
+    if (derive(fmt, &f) != CQ_OK || f.b != 8 || f.head_dim != 128) return 0;
+    if (batch <= 0 || n_q_heads <= 0 || n_q_heads % f.n_kv_heads != 0 || m <= 0 || t < m) return 0;
+    return chunk_tiles_per_split(f, batch, n_q_heads, m, t) * kTileTokens;
+}
+
+size_t cq_chunk_workspace_bytes(const cq_format* fmt, int32_t batch, int32_t n_q_heads, int32_t m, int32_t t,
+                                int32_t tokens_per_split)
+{
+    Derived f;
+    if (derive(fmt, &f) != CQ_OK || f.b != 8 || f.head_dim != 128) return 0;
+    if (batch <= 0 || n_q_heads <= 0 || n_q_heads % f.n_kv_heads != 0 || m <= 0 || t < m) return 0;
+    if (tokens_per_split < 0 || tokens_per_split % kTileTokens != 0) return 0;
+    const int tiles = tokens_per_split ? tokens_per_split / kTileTokens : chunk_tiles_per_split(f, batch, n_q_heads, m, t);
+    const int n_tiles = (t + kTileTokens - 1) / kTileTokens;
+    const int n_split = (n_tiles + tiles - 1) / tiles;
+    return sizeof(float) * (size_t)batch * m * n_q_heads * n_split * (f.head_dim + kPartialHeader);
+}
+
+cq_status cq_chunk_attention(const void* q, const void* k_codes, const void* v_codes,
+                             const void* k_centroids, const void* v_centroids, float scale, const cq_format* fmt,
+                             int32_t batch, int32_t n_q_heads, int32_t m, int32_t t, int32_t t_cap,
+                             const int32_t* seq_lens, int32_t tokens_per_split,
+                             void* out, void* workspace, size_t workspace_bytes, void* stream)
+{
+    return chunk_common(q, k_codes, v_codes, k_centroids, v_centroids, scale, fmt, batch, n_q_heads, m, t, t_cap, nullptr,
+                        seq_lens, tokens_per_split, out, workspace, workspace_bytes, stream);
+}
+
+cq_status cq_chunk_attention_paged(const void* q, const void* k_pool, const void* v_pool,
+                                   const void* k_centroids, const void* v_centroids, float scale, const cq_format* fmt,
+                                   int32_t batch, int32_t n_q_heads, int32_t m, int32_t t, const cq_page_table* pages,
+                                   const int32_t* seq_lens, int32_t tokens_per_split,
+                                   void* out, void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (!pages) return CQ_ERR_INVALID_ARG;
+    return chunk_common(q, k_pool, v_pool, k_centroids, v_centroids, scale, fmt, batch, n_q_heads, m, t, 0, pages,
+                        seq_lens, tokens_per_split, out, workspace, workspace_bytes, stream);
+}
+
 size_t cq_layer_table_bytes(int32_t n_layers)
 {
     return n_layers > 0 ? sizeof(LayerPtrs) * (size_t)n_layers : 0;

@@ -1,0 +1,323 @@
+// Causal attention of the last m tokens of each sequence over its packed CQ cache (a prefill
+// chunk, or the verification step of speculative decoding), for gfx950.  Eq. 1 of the paper once
+// per query token; the cache already holds the codes of the m tokens.
+//
+// With many queries per (sequence, KV head) the per-query lookup tables of the decode kernel
+// no longer fit on chip and the path becomes a dense contraction, so this one is built on the
+// matrix cores: a workgroup (4 wavefronts) owns up to 128 query rows of one KV head (query
+// tokens x the query heads that share the KV head), walks the context in 64-token tiles, turns
+// each tile's codes back into fp16 keys and values ONCE in LDS (centroid gathers from the
+// L2-resident codebooks), and every wavefront runs a flash-attention step on its 32 rows:
+//     S^T = K Q^T      v_mfma_f32_32x32x16_f16, A = keys of 32 tokens (LDS), B = queries (registers)
+//     online softmax   each lane owns ONE query (a column of S^T): running maximum, sum and the
+//                      rescaling of its output column are lane-local
+//     O^T += V^T P^T   A = values, stored transposed in LDS, B = the probabilities just computed,
+//                      scaled by 2^12 and split into two fp16 numbers (high and low part: 22
+//                      bits; one fp16 alone leaves errors of 1e-5 of the largest output element,
+//                      too much for the small ones); fp32 accumulation
+// HBM traffic is the codes, read once per workgroup; the kernel is bound by the matrix cores and
+// the LDS reads that feed them.  Long contexts with few rows are split over workgroups and
+// merged by the decode path's merge kernel (same (m, l, o) partials).
+#include <mutex>
+
+#include "cq_decode_common.hpp"
+
+namespace cq {
+namespace {
+
+typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
+typedef _Float16 half4_t __attribute__((ext_vector_type(4)));
+typedef float float16_t __attribute__((ext_vector_type(16)));
+
+constexpr int kChunkThreads = 256;                // 4 wavefronts x 32 query rows
+constexpr int kRowsPerWg = 128;
+constexpr int kKsStride = 272;                    // bytes per token row of the key tile (256 + 16: conflict-free 16-byte reads)
+constexpr int kVtStride = 136;                    // bytes per channel row of the transposed value tile (128 + 8)
+constexpr int kKsBytes = kTileTokens * kKsStride; // 17408
+constexpr int kVtBytes = 128 * kVtStride;         // 17408
+constexpr int kStageBytes = kKsBytes + kVtBytes;
+constexpr float kProbScale = 4096.f;              // 2^12
+
+__device__ __forceinline__ half8_t lds_half8(unsigned byte_addr)
+{
+    return *(__attribute__((address_space(3))) half8_t*)(byte_addr);
+}
+__device__ __forceinline__ half4_t lds_half4(unsigned byte_addr)
+{
+    return *(__attribute__((address_space(3))) half4_t*)(byte_addr);
+}
+
+// Codes of 64 tokens -> fp16 keys [token][channel] and values [channel][token] in LDS.  Thread
+// (token u = tid % 64, quarter = tid / 64) handles Gh / 4 consecutive slots of its token: slot s
+// holds group (s + u) mod Gh.
+template <int GH, int C>
+struct Dequant {
+    static constexpr int SPQ = GH / 4;                  // slots per quarter
+    unsigned kcode[SPQ / 4], vcode[SPQ / 4];            // code bytes, 4 per register
+
+    __device__ __forceinline__ void load_codes(const uint8_t* ktile, const uint8_t* vtile, int tid)
+    {
+        const int u = tid & 63, s0 = (tid >> 6) * SPQ;
+        const size_t off = (size_t)(s0 >> 4) * 1024 + (size_t)u * 16 + (s0 & 15);
+#pragma unroll
+        for (int i = 0; i < SPQ / 4; ++i) {
+            kcode[i] = __builtin_nontemporal_load(reinterpret_cast<const unsigned*>(ktile + off) + i);
+            vcode[i] = __builtin_nontemporal_load(reinterpret_cast<const unsigned*>(vtile + off) + i);
+        }
+    }
+
+    __device__ __forceinline__ void expand(const uint16_t* ck_head, const uint16_t* cv_head, unsigned stage, int tid) const
+    {
+        typedef __attribute__((address_space(3))) unsigned lds_u;
+        typedef __attribute__((address_space(3))) uint16_t lds_h;
+        const int u = tid & 63, s0 = (tid >> 6) * SPQ;
+        unsigned kw[SPQ][C / 2], vw[SPQ][C / 2];
+#pragma unroll
+        for (int si = 0; si < SPQ; ++si) {
+            const int g = (s0 + si + u) & (GH - 1);
+            const unsigned kc = (kcode[si >> 2] >> (8 * (si & 3))) & 0xffu;
+            const unsigned vc = (vcode[si >> 2] >> (8 * (si & 3))) & 0xffu;
+            const unsigned* kp = reinterpret_cast<const unsigned*>(ck_head + ((size_t)g * 256 + kc) * C);
+            const unsigned* vp = reinterpret_cast<const unsigned*>(cv_head + ((size_t)g * 256 + vc) * C);
+#pragma unroll
+            for (int i = 0; i < C / 2; ++i) {
+                kw[si][i] = kp[i];
+                vw[si][i] = vp[i];
+            }
+        }
+#pragma unroll
+        for (int si = 0; si < SPQ; ++si) {
+            const int g = (s0 + si + u) & (GH - 1);
+            const unsigned kaddr = stage + (unsigned)u * kKsStride + (unsigned)g * (C * 2);
+#pragma unroll
+            for (int i = 0; i < C / 2; ++i) *(lds_u*)(kaddr + 4 * i) = kw[si][i];
+            const unsigned vaddr = stage + kKsBytes + (unsigned)(g * C) * kVtStride + (unsigned)u * 2;
+#pragma unroll
+            for (int i = 0; i < C / 2; ++i) {
+                *(lds_h*)(vaddr + (2 * i) * kVtStride) = (uint16_t)(vw[si][i] & 0xffffu);
+                *(lds_h*)(vaddr + (2 * i + 1) * kVtStride) = (uint16_t)(vw[si][i] >> 16);
+            }
+        }
+    }
+};
+
+template <int GH, int C>
+__global__ __launch_bounds__(kChunkThreads) void chunk_attention_kernel(ChunkArgs a)
+{
+    using F = Fmt<GH, 8>;
+    constexpr int D = 128;
+    static_assert(GH * C == D, "head_dim 128");
+    extern __shared__ float smem[];
+    (void)smem;
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int rc = lane & 31, kh = lane >> 5;
+
+    // workgroup -> (sequence, KV head, block of 128 query rows, context split)
+    const int qper = a.n_q_heads / a.f.n_kv_heads;
+    const int rows_total = a.m * qper;                      // row r = (query token r / qper, query head r % qper)
+    const int row_blocks = (rows_total + kRowsPerWg - 1) / kRowsPerWg;
+    int idx = blockIdx.x;
+    const int hkv = idx % a.f.n_kv_heads;
+    idx /= a.f.n_kv_heads;
+    const int rb = idx % row_blocks;
+    idx /= row_blocks;
+    const int split = idx % a.n_split;
+    const int n = idx / a.n_split;
+
+    int t_n = a.t;
+    if (a.seq_lens) t_n = min(max(a.seq_lens[n], a.m), a.t);
+    const int pos0 = t_n - a.m;                             // position of query token 0
+
+    // this lane's query row
+    const int row = rb * kRowsPerWg + wave * 32 + rc;
+    const bool valid = row < rows_total;
+    const int row_c = valid ? row : rows_total - 1;
+    const int j = row_c / qper, hq = hkv * qper + row_c % qper;
+    const int pos = pos0 + j;
+    // tiles this workgroup needs: up to the position of its last row, within its split
+    const int last_row = min(rb * kRowsPerWg + kRowsPerWg, rows_total) - 1;
+    const int tiles_needed = (pos0 + last_row / qper) / kTileTokens + 1;
+    const int tile0 = split * a.tiles_per_split;
+    const int tile1 = min(tile0 + a.tiles_per_split, tiles_needed);
+    // the wavefront's own last tile (rows of later wavefronts reach further)
+    const int wave_last_row = min(rb * kRowsPerWg + wave * 32 + 31, rows_total - 1);
+    const int wave_tiles = (pos0 + wave_last_row / qper) / kTileTokens + 1;
+
+    const size_t out_row = ((size_t)n * a.m + j) * a.n_q_heads + hq;
+    float* part = a.partials + (out_row * a.n_split + split) * (D + kPartialHeader);
+
+    // queries: B operand of S^T = K Q^T, lane (rc, kh) holds Q[row][16 s + 8 kh .. + 7] for the 8 steps
+    half8_t qreg[8];
+    {
+        const uint16_t* qrow = a.q + out_row * D;
+#pragma unroll
+        for (int s = 0; s < 8; ++s) qreg[s] = *reinterpret_cast<const half8_t*>(qrow + 16 * s + 8 * kh);
+    }
+
+    const uint16_t* ck_head = a.k_centroids + (size_t)hkv * GH * 256 * C;
+    const uint16_t* cv_head = a.v_centroids + (size_t)hkv * GH * 256 * C;
+    auto tile_ptr = [&](const uint8_t* base, int tile) {
+        return base + a.map.tile_index(n, hkv, tile) * F::TILE_BYTES;
+    };
+
+    float16_t o[4];
+#pragma unroll
+    for (int cb = 0; cb < 4; ++cb)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) o[cb][i] = 0.f;
+    float m_run = -INFINITY, l_run = 0.f;
+
+    Dequant<GH, C> dq;
+    if (tile0 < tile1) {
+        dq.load_codes(tile_ptr(a.k_codes, tile0), tile_ptr(a.v_codes, tile0), tid);
+        dq.expand(ck_head, cv_head, 0, tid);
+    }
+    lds_barrier();
+
+    for (int tile = tile0; tile < tile1; ++tile) {
+        const unsigned stage = (unsigned)((tile - tile0) & 1) * kStageBytes;
+        const bool more = tile + 1 < tile1;
+        if (more) dq.load_codes(tile_ptr(a.k_codes, tile + 1), tile_ptr(a.v_codes, tile + 1), tid);
+
+        if (tile < wave_tiles) {
+#pragma unroll
+            for (int tb = 0; tb < 2; ++tb) {
+                // ---- scores of 32 tokens x 32 queries ----
+                float16_t acc;
+#pragma unroll
+                for (int i = 0; i < 16; ++i) acc[i] = 0.f;
+                const unsigned krow = stage + (unsigned)(tb * 32 + rc) * kKsStride + (unsigned)kh * 16;
+#pragma unroll
+                for (int s = 0; s < 8; ++s)
+                    acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(lds_half8(krow + 32 * s), qreg[s], acc, 0, 0, 0);
+                // acc[i] is token 8 (i / 4) + 4 kh + i % 4 of the block, query rc
+                const int tok0 = tile * kTileTokens + tb * 32 + 4 * kh;
+                float bmax = -INFINITY;
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    const int tok = tok0 + 8 * (i >> 2) + (i & 3);
+                    acc[i] = tok <= pos ? acc[i] * a.scale_log2e : -INFINITY;
+                    bmax = fmaxf(bmax, acc[i]);
+                }
+                bmax = fmaxf(bmax, __shfl_xor(bmax, 32));
+                const float m_new = fmaxf(m_run, bmax);
+                const float m_safe = m_new == -INFINITY ? 0.f : m_new;      // nothing visible yet: all weights 0
+                const float alpha = __builtin_amdgcn_exp2f(m_run - m_safe);
+                m_run = m_new;
+                float psum = 0.f;
+                half8_t ph[2], pl[2];            // p * 2^12 = ph + pl to 22 bits
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    const float p = __builtin_amdgcn_exp2f(acc[i] - m_safe);
+                    psum += p;
+                    const float ps = p * kProbScale;
+                    const _Float16 hi = (_Float16)ps;
+                    ph[i >> 3][i & 7] = hi;
+                    pl[i >> 3][i & 7] = (_Float16)(ps - (float)hi);
+                }
+                l_run = __builtin_fmaf(l_run, alpha, psum);
+                if (__builtin_amdgcn_ballot_w64(alpha != 1.f) != 0) {
+#pragma unroll
+                    for (int cb = 0; cb < 4; ++cb)
+#pragma unroll
+                        for (int i = 0; i < 16; ++i) o[cb][i] *= alpha;
+                }
+                // ---- O^T += V^T P^T: contraction index (kh, i) is token 16 t + 8 (i / 4) + 4 kh + i % 4 ----
+#pragma unroll
+                for (int cb = 0; cb < 4; ++cb) {
+                    const unsigned vrow = stage + kKsBytes + (unsigned)(cb * 32 + rc) * kVtStride + (unsigned)(tb * 32 + 4 * kh) * 2;
+#pragma unroll
+                    for (int t = 0; t < 2; ++t) {
+                        const half4_t v0 = lds_half4(vrow + 32 * t), v1 = lds_half4(vrow + 32 * t + 16);
+                        const half8_t av = {v0[0], v0[1], v0[2], v0[3], v1[0], v1[1], v1[2], v1[3]};
+                        o[cb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(av, ph[t], o[cb], 0, 0, 0);
+                        o[cb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(av, pl[t], o[cb], 0, 0, 0);
+                    }
+                }
+            }
+        }
+        // the next tile goes to the other stage (its last readers passed the previous barrier)
+        if (more) dq.expand(ck_head, cv_head, stage ^ kStageBytes, tid);
+        lds_barrier();
+    }
+
+    // ---- output: lane (rc, kh) holds channels 32 cb + 8 (i / 4) + 4 kh + i % 4 of query rc ----
+    const float l = l_run + __shfl_xor(l_run, 32);
+    if (!valid) return;
+    if (a.n_split == 1) {
+        const float inv = 1.f / (l * kProbScale);
+        uint16_t* orow = a.out + out_row * D;
+#pragma unroll
+        for (int cb = 0; cb < 4; ++cb)
+#pragma unroll
+            for (int i4 = 0; i4 < 4; ++i4) {
+                half4_t h;
+#pragma unroll
+                for (int b = 0; b < 4; ++b) h[b] = (_Float16)(o[cb][4 * i4 + b] * inv);
+                *reinterpret_cast<half4_t*>(orow + 32 * cb + 8 * i4 + 4 * kh) = h;
+            }
+    } else {
+        if (kh == 0) {
+            part[0] = m_run;
+            part[1] = l;
+        }
+#pragma unroll
+        for (int cb = 0; cb < 4; ++cb)
+#pragma unroll
+            for (int i4 = 0; i4 < 4; ++i4) {
+                float4 v;
+                v.x = o[cb][4 * i4 + 0] * (1.f / kProbScale);
+                v.y = o[cb][4 * i4 + 1] * (1.f / kProbScale);
+                v.z = o[cb][4 * i4 + 2] * (1.f / kProbScale);
+                v.w = o[cb][4 * i4 + 3] * (1.f / kProbScale);
+                float* dst = part + kPartialHeader + 32 * cb + 8 * i4 + 4 * kh;
+                dst[0] = v.x; dst[1] = v.y; dst[2] = v.z; dst[3] = v.w;
+            }
+    }
+}
+
+template <int GH, int C>
+cq_status launch_chunk_variant(const ChunkArgs& a, hipStream_t stream)
+{
+    auto kernel = chunk_attention_kernel<GH, C>;
+    static std::once_flag once;
+    static hipError_t setup = hipSuccess;
+    std::call_once(once, [&] {
+        hipFuncAttributes attr;
+        setup = hipFuncGetAttributes(&attr, reinterpret_cast<const void*>(kernel));
+        // the tiles are addressed from LDS address 0: no static LDS may precede the dynamic block
+        if (setup == hipSuccess && attr.sharedSizeBytes != 0) setup = hipErrorInvalidValue;
+        if (setup == hipSuccess)
+            setup = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+    });
+    if (setup != hipSuccess) return CQ_ERR_HIP;
+    const int qper = a.n_q_heads / a.f.n_kv_heads;
+    const int row_blocks = (a.m * qper + kRowsPerWg - 1) / kRowsPerWg;
+    const unsigned grid = (unsigned)(a.batch * a.n_split * row_blocks * a.f.n_kv_heads);
+    hipLaunchKernelGGL(kernel, dim3(grid), dim3(kChunkThreads), 2 * kStageBytes, stream, a);
+    return hipGetLastError() == hipSuccess ? CQ_OK : CQ_ERR_HIP;
+}
+
+}  // namespace
+
+int chunk_rows_per_workgroup() { return kRowsPerWg; }
+
+cq_status launch_chunk_attention(const ChunkArgs& a, hipStream_t stream)
+{
+    cq_status st = CQ_ERR_UNSUPPORTED;
+    if (a.f.b == 8 && a.f.head_dim == 128) {
+        if (a.f.gh == 16 && a.f.c == 8) st = launch_chunk_variant<16, 8>(a, stream);
+        else if (a.f.gh == 32 && a.f.c == 4) st = launch_chunk_variant<32, 4>(a, stream);
+        else if (a.f.gh == 64 && a.f.c == 2) st = launch_chunk_variant<64, 2>(a, stream);
+    }
+    if (st != CQ_OK) return st;
+    if (a.n_split > 1)
+        return launch_decode_merge(a.partials, a.out, a.batch * a.m * a.n_q_heads, a.n_split, a.f.head_dim, stream);
+    return CQ_OK;
+}
+
+}  // namespace cq

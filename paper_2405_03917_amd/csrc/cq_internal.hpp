@@ -110,6 +110,25 @@ struct DecodeArgs {
     Derived f;
 };
 
+// Causal attention of the last m tokens of every sequence over its cache (cq_chunk.hip).
+struct ChunkArgs {
+    const uint16_t* q;        // fp16 [batch][m][n_q_heads][head_dim]
+    const uint8_t* k_codes;
+    const uint8_t* v_codes;
+    const uint16_t* k_centroids;
+    const uint16_t* v_centroids;
+    float scale_log2e;
+    int batch, m, n_q_heads, t;
+    CacheMap map;
+    const int32_t* seq_lens;
+    int tiles_per_split, n_split;
+    float* partials;          // [batch][m][n_q_heads][n_split][2 + head_dim]
+    uint16_t* out;            // fp16 [batch][m][n_q_heads][head_dim]
+    Derived f;
+};
+int chunk_rows_per_workgroup();
+cq_status launch_chunk_attention(const ChunkArgs& a, hipStream_t stream);
+
 // Largest tokens_per_split the decode kernel's on-chip score buffer can hold.
 int decode_max_tiles_per_split(const Derived& f);
 

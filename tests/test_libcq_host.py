@@ -274,3 +274,27 @@ def test_layer_table_argument_checks_without_copying():
         _fake(table) if table else None, n, stride, 0.1, ctypes.byref(f), 2, 8, 128, 128, None, 0, _fake(0x70000), ws, None))
     assert step(table=0) == E and step(n=0) == E and step(stride=100) == E and step(table=0x900004) == E
     assert step(ws=cq.cq_decode_workspace_bytes(cq.CQFormat(4, 8, 128, 4), 2, 8, 128)) == cq.CQ_ERR_WORKSPACE_TOO_SMALL   # one layer's worth
+
+
+def test_chunk_attention_sizes_and_argument_checks_without_launching():
+    lib = cq.load()
+    fmt = cq.CQFormat(4, 8, 128, 4)
+    f = fmt._c()
+    E = cq.CQ_ERR_INVALID_ARG
+    # batch 16 x 4 KV heads x 1 row block = 64 workgroups: the context of 64 tiles is cut in 8
+    assert cq.cq_chunk_default_split(fmt, 16, 8, 16, 4096) == 512
+    assert cq.cq_chunk_workspace_bytes(fmt, 16, 8, 16, 4096) == 4 * 16 * 16 * 8 * 8 * 130
+    # plenty of rows: one split
+    assert cq.cq_chunk_default_split(fmt, 64, 32, 512, 4096) == 4096
+    assert cq.cq_chunk_default_split(cq.CQFormat(8, 10, 128, 4), 16, 8, 16, 4096) == 0
+    assert cq.cq_chunk_default_split(fmt, 16, 8, 5000, 4096) == 0            # more queries than cached tokens
+
+    def run(fm=f, q=0x10000, m=16, t=128, t_cap=128, split=0, ws=0x70000, ws_bytes=1 << 30, hq=8, scale=0.1):
+        return int(lib.cq_chunk_attention(_fake(q) if q else None, _fake(0x20000), _fake(0x30000), _fake(0x40000),
+                                          _fake(0x50000), scale, ctypes.byref(fm), 2, hq, m, t, t_cap, None, split,
+                                          _fake(0x60000), _fake(ws) if ws else None, ws_bytes, None))
+    assert run(q=0) == E and run(q=0x10004) == E and run(m=0) == E and run(m=129) == E and run(t=129) == E
+    assert run(t_cap=100) == E and run(split=100) == E and run(hq=6) == E and run(scale=float("inf")) == E
+    assert run(split=64, ws=0) == E                                          # split context needs the workspace
+    assert run(split=64, ws_bytes=64) == cq.CQ_ERR_WORKSPACE_TOO_SMALL
+    assert run(fm=cq.CQFormat(8, 10, 128, 4)._c()) == cq.CQ_ERR_UNSUPPORTED
