@@ -444,7 +444,8 @@ namespace {
 int chunk_tiles_per_split(const Derived& f, int batch, int n_q_heads, int m, int t)
 {
     const int qper = n_q_heads / f.n_kv_heads;
-    const long row_blocks = ((long)m * qper + chunk_rows_per_workgroup() - 1) / chunk_rows_per_workgroup();
+    const int rpw = chunk_rows_per_workgroup(m * qper);
+    const long row_blocks = ((long)m * qper + rpw - 1) / rpw;
     const long base = (long)batch * f.n_kv_heads * row_blocks;
     const int n_tiles = (t + kTileTokens - 1) / kTileTokens;
     long n_split = std::max(1L, (512 + base - 1) / base);
@@ -486,7 +487,8 @@ cq_status chunk_common(const void* q, const void* k_codes, const void* v_codes,
         if (workspace_bytes < sizeof(float) * rows * n_split * (f.head_dim + kPartialHeader)) return CQ_ERR_WORKSPACE_TOO_SMALL;
     }
     const int qper = n_q_heads / f.n_kv_heads;
-    const int64_t row_blocks = ((int64_t)m * qper + chunk_rows_per_workgroup() - 1) / chunk_rows_per_workgroup();
+    const int rpw = chunk_rows_per_workgroup(m * qper);
+    const int64_t row_blocks = ((int64_t)m * qper + rpw - 1) / rpw;
     if ((int64_t)batch * f.n_kv_heads * row_blocks * n_split > 0x7fffffffLL || rows * n_split > 0x7fffffffULL)
         return CQ_ERR_INVALID_ARG;
     ChunkArgs a;

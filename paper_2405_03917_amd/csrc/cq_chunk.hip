@@ -4,7 +4,7 @@
 //
 // With many queries per (sequence, KV head) the per-query lookup tables of the decode kernel
 // no longer fit on chip and the path becomes a dense contraction, so this one is built on the
-// matrix cores: a workgroup (4 wavefronts) owns up to 128 query rows of one KV head (query
+// matrix cores: a workgroup (8 wavefronts) owns up to 256 query rows of one KV head (query
 // tokens x the query heads that share the KV head), walks the context in 64-token tiles, turns
 // each tile's codes back into fp16 keys and values ONCE in LDS (centroid gathers from the
 // L2-resident codebooks), and every wavefront runs a flash-attention step on its 32 rows:
@@ -29,13 +29,14 @@ typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
 typedef _Float16 half4_t __attribute__((ext_vector_type(4)));
 typedef float float16_t __attribute__((ext_vector_type(16)));
 
-constexpr int kChunkThreads = 256;                // 4 wavefronts x 32 query rows
-constexpr int kRowsPerWg = 128;
+// 8 wavefronts x 32 query rows per workgroup (one workgroup per CU), or 4 x 32 where a KV head has
+// no more than 128 rows (two workgroups per CU then)
 constexpr int kKsStride = 272;                    // bytes per token row of the key tile (256 + 16: conflict-free 16-byte reads)
 constexpr int kVtStride = 136;                    // bytes per channel row of the transposed value tile (128 + 8)
 constexpr int kKsBytes = kTileTokens * kKsStride; // 17408
 constexpr int kVtBytes = 128 * kVtStride;         // 17408
 constexpr int kStageBytes = kKsBytes + kVtBytes;
+constexpr unsigned kRawBase = 2 * kStageBytes;    // behind the two stages: the raw code tiles (K, V) of two tiles
 constexpr float kProbScale = 4096.f;              // 2^12
 
 __device__ __forceinline__ half8_t lds_half8(unsigned byte_addr)
@@ -47,63 +48,87 @@ __device__ __forceinline__ half4_t lds_half4(unsigned byte_addr)
     return *(__attribute__((address_space(3))) half4_t*)(byte_addr);
 }
 
-// Codes of 64 tokens -> fp16 keys [token][channel] and values [channel][token] in LDS.  Thread
-// (token u = tid % 64, quarter = tid / 64) handles Gh / 4 consecutive slots of its token: slot s
-// holds group (s + u) mod Gh.
-template <int GH, int C>
+// Codes of 64 tokens -> fp16 keys [token][channel] and values [channel][token] in LDS.
+// The codes of a tile first go to LDS as they are (load_raw / store_raw: one 16-byte record per
+// thread).  Then thread (token u = tid % 64, wavefront e = tid / 64) expands groups
+// e Gh/8 .. (e + 1) Gh/8 - 1 of its token: the code of group g sits in slot (g - u) mod Gh of the
+// token's record.  A wavefront thus gathers from ONE group's centroids at a time: its 64 lanes
+// touch the 8 to 32 cache lines of that group's table instead of 64 lines of 64 tables, which is
+// what the texture path charges for.
+template <int GH, int C, int NW>
 struct Dequant {
-    static constexpr int SPQ = GH / 4;                  // slots per quarter
-    unsigned kcode[SPQ / 4], vcode[SPQ / 4];            // code bytes, 4 per register
+    static constexpr int GPT = GH / NW;                 // groups per thread
+    static constexpr int TILE = kTileTokens * GH;       // bytes of one tile's codes
+    static constexpr int LOADERS = TILE / 16;           // threads that carry one record of K and one of V
+    static constexpr int RAW_STAGE = 2 * TILE;          // K tile, V tile
+    static_assert(LOADERS <= NW * 64, "one record per thread");
+    u32x4 kraw, vraw;                                   // 16-byte records of the next tile's codes
+    unsigned kw[GPT][C / 2], vw[GPT][C / 2];            // the centroids of this thread's (token, group) pairs
 
-    __device__ __forceinline__ void load_codes(const uint8_t* ktile, const uint8_t* vtile, int tid)
+    __device__ __forceinline__ void load_raw(const uint8_t* ktile, const uint8_t* vtile, int tid)
     {
-        const int u = tid & 63, s0 = (tid >> 6) * SPQ;
-        const size_t off = (size_t)(s0 >> 4) * 1024 + (size_t)u * 16 + (s0 & 15);
-#pragma unroll
-        for (int i = 0; i < SPQ / 4; ++i) {
-            kcode[i] = __builtin_nontemporal_load(reinterpret_cast<const unsigned*>(ktile + off) + i);
-            vcode[i] = __builtin_nontemporal_load(reinterpret_cast<const unsigned*>(vtile + off) + i);
+        if (tid < LOADERS) {
+            kraw = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(ktile) + tid);
+            vraw = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(vtile) + tid);
+        }
+    }
+    __device__ __forceinline__ void store_raw(unsigned raw_stage, int tid) const
+    {
+        typedef __attribute__((address_space(3))) u32x4 lds_q;
+        if (tid < LOADERS) {
+            *(lds_q*)(raw_stage + (unsigned)tid * 16) = kraw;
+            *(lds_q*)(raw_stage + TILE + (unsigned)tid * 16) = vraw;
         }
     }
 
-    __device__ __forceinline__ void expand(const uint16_t* ck_head, const uint16_t* cv_head, unsigned stage, int tid) const
+    // read this thread's codes from the raw tile and request their centroids (L2-resident codebooks)
+    __device__ __forceinline__ void gather(unsigned raw_stage, const uint16_t* ck_head, const uint16_t* cv_head, int tid)
     {
-        typedef __attribute__((address_space(3))) unsigned lds_u;
-        typedef __attribute__((address_space(3))) uint16_t lds_h;
-        const int u = tid & 63, s0 = (tid >> 6) * SPQ;
-        unsigned kw[SPQ][C / 2], vw[SPQ][C / 2];
+        typedef __attribute__((address_space(3))) uint8_t lds_b;
+        const int u = tid & 63, g0 = (tid >> 6) * GPT;
 #pragma unroll
-        for (int si = 0; si < SPQ; ++si) {
-            const int g = (s0 + si + u) & (GH - 1);
-            const unsigned kc = (kcode[si >> 2] >> (8 * (si & 3))) & 0xffu;
-            const unsigned vc = (vcode[si >> 2] >> (8 * (si & 3))) & 0xffu;
+        for (int gi = 0; gi < GPT; ++gi) {
+            const int g = g0 + gi;
+            const unsigned slot = (unsigned)(g - u) & (unsigned)(GH - 1);
+            const unsigned off = (slot >> 4) * 1024 + (unsigned)u * 16 + (slot & 15);
+            const unsigned kc = *(lds_b*)(raw_stage + off);
+            const unsigned vc = *(lds_b*)(raw_stage + TILE + off);
             const unsigned* kp = reinterpret_cast<const unsigned*>(ck_head + ((size_t)g * 256 + kc) * C);
             const unsigned* vp = reinterpret_cast<const unsigned*>(cv_head + ((size_t)g * 256 + vc) * C);
 #pragma unroll
             for (int i = 0; i < C / 2; ++i) {
-                kw[si][i] = kp[i];
-                vw[si][i] = vp[i];
+                kw[gi][i] = kp[i];
+                vw[gi][i] = vp[i];
             }
         }
+    }
+
+    __device__ __forceinline__ void store(unsigned stage, int tid) const
+    {
+        typedef __attribute__((address_space(3))) unsigned lds_u;
+        typedef __attribute__((address_space(3))) uint16_t lds_h;
+        const int u = tid & 63, g0 = (tid >> 6) * GPT;
 #pragma unroll
-        for (int si = 0; si < SPQ; ++si) {
-            const int g = (s0 + si + u) & (GH - 1);
+        for (int gi = 0; gi < GPT; ++gi) {
+            const int g = g0 + gi;
             const unsigned kaddr = stage + (unsigned)u * kKsStride + (unsigned)g * (C * 2);
 #pragma unroll
-            for (int i = 0; i < C / 2; ++i) *(lds_u*)(kaddr + 4 * i) = kw[si][i];
+            for (int i = 0; i < C / 2; ++i) *(lds_u*)(kaddr + 4 * i) = kw[gi][i];
             const unsigned vaddr = stage + kKsBytes + (unsigned)(g * C) * kVtStride + (unsigned)u * 2;
 #pragma unroll
             for (int i = 0; i < C / 2; ++i) {
-                *(lds_h*)(vaddr + (2 * i) * kVtStride) = (uint16_t)(vw[si][i] & 0xffffu);
-                *(lds_h*)(vaddr + (2 * i + 1) * kVtStride) = (uint16_t)(vw[si][i] >> 16);
+                *(lds_h*)(vaddr + (2 * i) * kVtStride) = (uint16_t)(vw[gi][i] & 0xffffu);
+                *(lds_h*)(vaddr + (2 * i + 1) * kVtStride) = (uint16_t)(vw[gi][i] >> 16);
             }
         }
     }
 };
 
-template <int GH, int C>
-__global__ __launch_bounds__(kChunkThreads) void chunk_attention_kernel(ChunkArgs a)
+template <int GH, int C, int NW>
+__global__ __launch_bounds__(NW * 64) void chunk_attention_kernel(ChunkArgs a)
 {
+    constexpr int kRowsPerWg = NW * 32;
+    constexpr unsigned kRawStageBytes = Dequant<GH, C, NW>::RAW_STAGE;
     using F = Fmt<GH, 8>;
     constexpr int D = 128;
     static_assert(GH * C == D, "head_dim 128");
@@ -170,17 +195,29 @@ __global__ __launch_bounds__(kChunkThreads) void chunk_attention_kernel(ChunkArg
         for (int i = 0; i < 16; ++i) o[cb][i] = 0.f;
     float m_run = -INFINITY, l_run = 0.f;
 
-    Dequant<GH, C> dq;
+    // software pipeline over the tiles: while tile k is multiplied, the centroids of tile k + 1
+    // are on their way from L2 and the codes of tile k + 2 from HBM
+    Dequant<GH, C, NW> dq;
     if (tile0 < tile1) {
-        dq.load_codes(tile_ptr(a.k_codes, tile0), tile_ptr(a.v_codes, tile0), tid);
-        dq.expand(ck_head, cv_head, 0, tid);
+        dq.load_raw(tile_ptr(a.k_codes, tile0), tile_ptr(a.v_codes, tile0), tid);
+        dq.store_raw(kRawBase, tid);
+        if (tile0 + 1 < tile1) dq.load_raw(tile_ptr(a.k_codes, tile0 + 1), tile_ptr(a.v_codes, tile0 + 1), tid);
+        lds_barrier();
+        dq.gather(kRawBase, ck_head, cv_head, tid);
+        dq.store(0, tid);
+        if (tile0 + 1 < tile1) dq.store_raw(kRawBase + kRawStageBytes, tid);
     }
     lds_barrier();
 
     for (int tile = tile0; tile < tile1; ++tile) {
-        const unsigned stage = (unsigned)((tile - tile0) & 1) * kStageBytes;
+        const unsigned par = (unsigned)((tile - tile0) & 1);
+        const unsigned stage = par * kStageBytes;
         const bool more = tile + 1 < tile1;
-        if (more) dq.load_codes(tile_ptr(a.k_codes, tile + 1), tile_ptr(a.v_codes, tile + 1), tid);
+        if (more) {
+            dq.gather(kRawBase + (par ^ 1u) * kRawStageBytes, ck_head, cv_head, tid);     // codes of tile + 1
+            if (tile + 2 < tile1) dq.load_raw(tile_ptr(a.k_codes, tile + 2), tile_ptr(a.v_codes, tile + 2), tid);
+            __builtin_amdgcn_sched_barrier(0);          // requests first, then the multiplications
+        }
 
         if (tile < wave_tiles) {
 #pragma unroll
@@ -240,7 +277,11 @@ __global__ __launch_bounds__(kChunkThreads) void chunk_attention_kernel(ChunkArg
             }
         }
         // the next tile goes to the other stage (its last readers passed the previous barrier)
-        if (more) dq.expand(ck_head, cv_head, stage ^ kStageBytes, tid);
+        if (more) {
+            dq.store(stage ^ kStageBytes, tid);
+            // the raw tile read two steps ago (tile's own codes) makes room for those of tile + 2
+            if (tile + 2 < tile1) dq.store_raw(kRawBase + par * kRawStageBytes, tid);
+        }
         lds_barrier();
     }
 
@@ -279,10 +320,10 @@ __global__ __launch_bounds__(kChunkThreads) void chunk_attention_kernel(ChunkArg
     }
 }
 
-template <int GH, int C>
+template <int GH, int C, int NW>
 cq_status launch_chunk_variant(const ChunkArgs& a, hipStream_t stream)
 {
-    auto kernel = chunk_attention_kernel<GH, C>;
+    auto kernel = chunk_attention_kernel<GH, C, NW>;
     static std::once_flag once;
     static hipError_t setup = hipSuccess;
     std::call_once(once, [&] {
@@ -296,23 +337,32 @@ cq_status launch_chunk_variant(const ChunkArgs& a, hipStream_t stream)
     });
     if (setup != hipSuccess) return CQ_ERR_HIP;
     const int qper = a.n_q_heads / a.f.n_kv_heads;
-    const int row_blocks = (a.m * qper + kRowsPerWg - 1) / kRowsPerWg;
+    const int row_blocks = (a.m * qper + NW * 32 - 1) / (NW * 32);
     const unsigned grid = (unsigned)(a.batch * a.n_split * row_blocks * a.f.n_kv_heads);
-    hipLaunchKernelGGL(kernel, dim3(grid), dim3(kChunkThreads), 2 * kStageBytes, stream, a);
+    const size_t lds = 2 * kStageBytes + 2 * Dequant<GH, C, NW>::RAW_STAGE;
+    hipLaunchKernelGGL(kernel, dim3(grid), dim3(NW * 64), lds, stream, a);
     return hipGetLastError() == hipSuccess ? CQ_OK : CQ_ERR_HIP;
+}
+
+template <int GH, int C>
+cq_status launch_chunk_rows(const ChunkArgs& a, hipStream_t stream)
+{
+    const int rows = a.m * (a.n_q_heads / a.f.n_kv_heads);
+    if (chunk_rows_per_workgroup(rows) == 128) return launch_chunk_variant<GH, C, 4>(a, stream);
+    return launch_chunk_variant<GH, C, 8>(a, stream);
 }
 
 }  // namespace
 
-int chunk_rows_per_workgroup() { return kRowsPerWg; }
+int chunk_rows_per_workgroup(int rows_per_kv_head) { return rows_per_kv_head <= 128 ? 128 : 256; }
 
 cq_status launch_chunk_attention(const ChunkArgs& a, hipStream_t stream)
 {
     cq_status st = CQ_ERR_UNSUPPORTED;
     if (a.f.b == 8 && a.f.head_dim == 128) {
-        if (a.f.gh == 16 && a.f.c == 8) st = launch_chunk_variant<16, 8>(a, stream);
-        else if (a.f.gh == 32 && a.f.c == 4) st = launch_chunk_variant<32, 4>(a, stream);
-        else if (a.f.gh == 64 && a.f.c == 2) st = launch_chunk_variant<64, 2>(a, stream);
+        if (a.f.gh == 16 && a.f.c == 8) st = launch_chunk_rows<16, 8>(a, stream);
+        else if (a.f.gh == 32 && a.f.c == 4) st = launch_chunk_rows<32, 4>(a, stream);
+        else if (a.f.gh == 64 && a.f.c == 2) st = launch_chunk_rows<64, 2>(a, stream);
     }
     if (st != CQ_OK) return st;
     if (a.n_split > 1)

@@ -126,7 +126,7 @@ struct ChunkArgs {
     uint16_t* out;            // fp16 [batch][m][n_q_heads][head_dim]
     Derived f;
 };
-int chunk_rows_per_workgroup();
+int chunk_rows_per_workgroup(int rows_per_kv_head);
 cq_status launch_chunk_attention(const ChunkArgs& a, hipStream_t stream);
 
 // Largest tokens_per_split the decode kernel's on-chip score buffer can hold.
