@@ -191,7 +191,21 @@ def extra_measurements(cq, synth, torch):
         "ms": med_r, "kv_tokens_per_s": B * T / (med_r * 1e-3),
         "code_read_GBps": code_bytes / (med_r * 1e-3) / 1e9, "tokens_per_split": split_r,
         "slowdown_vs_position_independent": med_r / med}
-    del kcache, vcache
+    # a prefill chunk over the same caches: the last 512 tokens of each sequence attend causally
+    # (cq_chunk_attention on the matrix cores); 4 x 32 x 512 query rows x ~130816 visible tokens each
+    m_chunk = 512
+    qc = torch.randn((B, m_chunk, cfg.n_q_heads, cfg.head_dim), device="cuda").half()
+    call_c, _ = cq.prepare_chunk_attention(qc, kcache, vcache, ck, cv, scale, fmt, T, T)
+    med_c, _ = time_calls(torch, call_c, 5, 1)
+    pairs = B * cfg.n_q_heads * sum(T - m_chunk + j + 1 for j in range(m_chunk))
+    out["chunk_attention_long_context"] = {
+        "workload": "CQ-8c8b, batch 4, 32 heads x 128, context 131072: causal attention of the last 512 tokens "
+                    "(cq_chunk_attention)",
+        "ms": med_c, "query_token_pairs_per_s": pairs / (med_c * 1e-3),
+        "useful_TFLOPs": pairs * 4 * cfg.head_dim / (med_c * 1e-3) / 1e12,
+        "mfma_TFLOPs_executed": pairs * 6 * cfg.head_dim / (med_c * 1e-3) / 1e12,
+        "frac_of_fp16_mfma_peak_executed": pairs * 6 * cfg.head_dim / (med_c * 1e-3) / 1e12 / 2500.0}
+    del kcache, vcache, qc
     # centroid learning on a calibration tensor of the paper's size (16 sequences x 2048 tokens):
     # k-means++ and 100 Lloyd iterations for each of the 512 groups of one CQ-8c8b tensor
     n_cal, iters = 16 * 2048, 100

@@ -220,24 +220,30 @@ __global__ __launch_bounds__(NW * 64) void chunk_attention_kernel(ChunkArgs a)
         }
 
         if (tile < wave_tiles) {
+            // The two 32-token blocks of the tile are interleaved so that the matrix pipe and the
+            // vector ALU overlap within the wavefront: scores of both blocks first; the softmax
+            // arithmetic of block 0 runs while the scores of block 1 are still being multiplied,
+            // that of block 1 while block 0's values are.
+            float16_t acc[2];
 #pragma unroll
             for (int tb = 0; tb < 2; ++tb) {
-                // ---- scores of 32 tokens x 32 queries ----
-                float16_t acc;
 #pragma unroll
-                for (int i = 0; i < 16; ++i) acc[i] = 0.f;
+                for (int i = 0; i < 16; ++i) acc[tb][i] = 0.f;
                 const unsigned krow = stage + (unsigned)(tb * 32 + rc) * kKsStride + (unsigned)kh * 16;
 #pragma unroll
                 for (int s = 0; s < 8; ++s)
-                    acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(lds_half8(krow + 32 * s), qreg[s], acc, 0, 0, 0);
-                // acc[i] is token 8 (i / 4) + 4 kh + i % 4 of the block, query rc
+                    acc[tb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(lds_half8(krow + 32 * s), qreg[s], acc[tb], 0, 0, 0);
+            }
+#pragma unroll
+            for (int tb = 0; tb < 2; ++tb) {
+                // acc[tb][i] is token 8 (i / 4) + 4 kh + i % 4 of the block, query rc
                 const int tok0 = tile * kTileTokens + tb * 32 + 4 * kh;
                 float bmax = -INFINITY;
 #pragma unroll
                 for (int i = 0; i < 16; ++i) {
                     const int tok = tok0 + 8 * (i >> 2) + (i & 3);
-                    acc[i] = tok <= pos ? acc[i] * a.scale_log2e : -INFINITY;
-                    bmax = fmaxf(bmax, acc[i]);
+                    acc[tb][i] = tok <= pos ? acc[tb][i] * a.scale_log2e : -INFINITY;
+                    bmax = fmaxf(bmax, acc[tb][i]);
                 }
                 bmax = fmaxf(bmax, __shfl_xor(bmax, 32));
                 const float m_new = fmaxf(m_run, bmax);
@@ -248,7 +254,7 @@ __global__ __launch_bounds__(NW * 64) void chunk_attention_kernel(ChunkArgs a)
                 half8_t ph[2], pl[2];            // p * 2^12 = ph + pl to 22 bits
 #pragma unroll
                 for (int i = 0; i < 16; ++i) {
-                    const float p = __builtin_amdgcn_exp2f(acc[i] - m_safe);
+                    const float p = __builtin_amdgcn_exp2f(acc[tb][i] - m_safe);
                     psum += p;
                     const float ps = p * kProbScale;
                     const _Float16 hi = (_Float16)ps;
@@ -264,15 +270,18 @@ __global__ __launch_bounds__(NW * 64) void chunk_attention_kernel(ChunkArgs a)
                 }
                 // ---- O^T += V^T P^T: contraction index (kh, i) is token 16 t + 8 (i / 4) + 4 kh + i % 4 ----
 #pragma unroll
-                for (int cb = 0; cb < 4; ++cb) {
-                    const unsigned vrow = stage + kKsBytes + (unsigned)(cb * 32 + rc) * kVtStride + (unsigned)(tb * 32 + 4 * kh) * 2;
+                for (int t = 0; t < 2; ++t) {
+                    half8_t av[4];
 #pragma unroll
-                    for (int t = 0; t < 2; ++t) {
+                    for (int cb = 0; cb < 4; ++cb) {
+                        const unsigned vrow = stage + kKsBytes + (unsigned)(cb * 32 + rc) * kVtStride + (unsigned)(tb * 32 + 4 * kh) * 2;
                         const half4_t v0 = lds_half4(vrow + 32 * t), v1 = lds_half4(vrow + 32 * t + 16);
-                        const half8_t av = {v0[0], v0[1], v0[2], v0[3], v1[0], v1[1], v1[2], v1[3]};
-                        o[cb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(av, ph[t], o[cb], 0, 0, 0);
-                        o[cb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(av, pl[t], o[cb], 0, 0, 0);
+                        av[cb] = half8_t{v0[0], v0[1], v0[2], v0[3], v1[0], v1[1], v1[2], v1[3]};
                     }
+#pragma unroll
+                    for (int cb = 0; cb < 4; ++cb) o[cb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(av[cb], ph[t], o[cb], 0, 0, 0);
+#pragma unroll
+                    for (int cb = 0; cb < 4; ++cb) o[cb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(av[cb], pl[t], o[cb], 0, 0, 0);
                 }
             }
         }
