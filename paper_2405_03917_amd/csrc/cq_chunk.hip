@@ -162,6 +162,8 @@ __global__ __launch_bounds__(NW * 64) void chunk_attention_kernel(ChunkArgs a)
     const int row_c = valid ? row : rows_total - 1;
     const int j = row_c / qper, hq = hkv * qper + row_c % qper;
     const int pos = pos0 + j;
+    // (rows ascend with the lane: the wavefront's earliest position is its first lane's)
+    const int pos_first = __builtin_amdgcn_readfirstlane(pos);
     // tiles this workgroup needs: up to the position of its last row, within its split
     const int last_row = min(rb * kRowsPerWg + kRowsPerWg, rows_total) - 1;
     const int tiles_needed = (pos0 + last_row / qper) / kTileTokens + 1;
@@ -239,24 +241,34 @@ __global__ __launch_bounds__(NW * 64) void chunk_attention_kernel(ChunkArgs a)
                 // acc[tb][i] is token 8 (i / 4) + 4 kh + i % 4 of the block, query rc
                 const int tok0 = tile * kTileTokens + tb * 32 + 4 * kh;
                 float bmax = -INFINITY;
+                if (tile * kTileTokens + tb * 32 + 31 > pos_first) {
+                    // a block on the causal diagonal of some query of this wavefront: mask
 #pragma unroll
-                for (int i = 0; i < 16; ++i) {
-                    const int tok = tok0 + 8 * (i >> 2) + (i & 3);
-                    acc[tb][i] = tok <= pos ? acc[tb][i] * a.scale_log2e : -INFINITY;
-                    bmax = fmaxf(bmax, acc[tb][i]);
+                    for (int i = 0; i < 16; ++i) {
+                        const int tok = tok0 + 8 * (i >> 2) + (i & 3);
+                        acc[tb][i] = tok <= pos ? acc[tb][i] * a.scale_log2e : -INFINITY;
+                        bmax = fmaxf(bmax, acc[tb][i]);
+                    }
+                } else {
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) {
+                        acc[tb][i] *= a.scale_log2e;
+                        bmax = fmaxf(bmax, acc[tb][i]);
+                    }
                 }
                 bmax = fmaxf(bmax, __shfl_xor(bmax, 32));
                 const float m_new = fmaxf(m_run, bmax);
                 const float m_safe = m_new == -INFINITY ? 0.f : m_new;      // nothing visible yet: all weights 0
                 const float alpha = __builtin_amdgcn_exp2f(m_run - m_safe);
                 m_run = m_new;
+                // probabilities times 2^12 (the sum l_run is kept in that scale too)
+                const float m_shift = m_safe - 12.f;
                 float psum = 0.f;
                 half8_t ph[2], pl[2];            // p * 2^12 = ph + pl to 22 bits
 #pragma unroll
                 for (int i = 0; i < 16; ++i) {
-                    const float p = __builtin_amdgcn_exp2f(acc[tb][i] - m_safe);
-                    psum += p;
-                    const float ps = p * kProbScale;
+                    const float ps = __builtin_amdgcn_exp2f(acc[tb][i] - m_shift);
+                    psum += ps;
                     const _Float16 hi = (_Float16)ps;
                     ph[i >> 3][i & 7] = hi;
                     pl[i >> 3][i & 7] = (_Float16)(ps - (float)hi);
@@ -298,7 +310,7 @@ __global__ __launch_bounds__(NW * 64) void chunk_attention_kernel(ChunkArgs a)
     const float l = l_run + __shfl_xor(l_run, 32);
     if (!valid) return;
     if (a.n_split == 1) {
-        const float inv = 1.f / (l * kProbScale);
+        const float inv = 1.f / l;
         uint16_t* orow = a.out + out_row * D;
 #pragma unroll
         for (int cb = 0; cb < 4; ++cb)
@@ -312,7 +324,7 @@ __global__ __launch_bounds__(NW * 64) void chunk_attention_kernel(ChunkArgs a)
     } else {
         if (kh == 0) {
             part[0] = m_run;
-            part[1] = l;
+            part[1] = l * (1.f / kProbScale);
         }
 #pragma unroll
         for (int cb = 0; cb < 4; ++cb)
