@@ -42,7 +42,8 @@
  *   - b = 10 (Gh = 16 only): a 64 x 16-byte plane with the low 8 bits of the code of each slot
  *     (same rotation), then a 64 x 4-byte plane with one little-endian uint32 per token whose
  *     bits [2 s + 1 : 2 s] are the high two bits of the code in slot s.
- *   Supported formats: b = 8 with Gh in {16, 32, 64}; b = 10 with Gh = 16.
+ *   Supported formats: b = 8 with Gh in {16, 32, 64}; b = 10 with Gh = 16; b = 2, 4 through their
+ *   fused b = 8 format (see cq_fused_format).
  */
 #ifndef LIBCQ_H
 #define LIBCQ_H
@@ -191,6 +192,37 @@ CQ_API cq_status cq_decode_step(const void *q, const void *x_k_new, const void *
                          const int32_t *seq_lens, int32_t tokens_per_split,
                          void *out, void *workspace, size_t workspace_bytes,
                          void *stream);
+
+/*
+ * Sub-byte formats: CQ-<c>c<b>b with b = 2 or 4 (the low-bit variants of the paper's ablation on
+ * the number of coupled channels, Section 4.3 / Figure 4: CQ-1c2b, 2c2b, 1c4b, 2c4b, 4c4b at
+ * head_dim 128; density b / c bits per stored number as in Table 1).
+ *
+ * 8 / b neighbouring groups share one code byte: group i of the byte sits in bits [b i, b i + b).
+ * That byte IS a code of the product codebook of those groups -- the 256 concatenations of their
+ * centroids -- so a sub-byte cache is, byte for byte, a cache of the fused format
+ * CQ-<c 8/b>c8b (cq_fused_format) with the expanded codebook (cq_expand_codebook), and every
+ * attention call (cq_decode_attention, the paged, rope and chunk variants) and cq_dequantize
+ * take (fused format, expanded codebook) for it; the scores and outputs are those of Eq. 1 over
+ * the sub-byte centroids, since a concatenation's dot product is the sum of its parts'.  (The
+ * fused decode STEP on the fused format searches the product codebook, where the rounding of
+ * one group's distance can decide another group's near tie; append with cq_encode_kv in the
+ * sub-byte format instead when the format's own search is wanted bit for bit.)
+ *
+ * cq_encode, cq_encode_kv, cq_encode_kv_paged, cq_cache_bytes, cq_paged_cache_bytes,
+ * cq_code_bytes_per_token_head and cq_format_check accept the sub-byte format itself, with its
+ * own codebook fp16 [G][2^b][c]: every group is searched against its own 2^b centroids
+ * (squared distance in fp32 in channel order, lowest index on ties), not the product codebook.
+ *
+ * cq_fused_format     host only; *fused = the format whose layout and decode kernels apply
+ *                     (the format itself for b = 8, 10)
+ * cq_expand_codebook  centroids fp16 [G][2^b][c] -> fused_centroids fp16 [G b/8][256][8 c/b]
+ *                     (device, 16-byte aligned, distinct; written on `stream`); entry j of fused
+ *                     group f is the concatenation over i of centroid (j >> b i) mod 2^b of
+ *                     group f 8/b + i.  CQ_ERR_INVALID_ARG for b = 8, 10 (nothing to expand).
+ */
+CQ_API cq_status cq_fused_format(const cq_format *fmt, cq_format *fused);
+CQ_API cq_status cq_expand_codebook(const void *centroids, const cq_format *fmt, void *fused_centroids, void *stream);
 
 /*
  * cq_decode_step for several layers in ONE launch (the decode step of a workload whose layers are

@@ -28,7 +28,7 @@ EXPORTS = (
     "cq_cache_bytes", "cq_encode", "cq_encode_kv", "cq_decode_default_split", "cq_decode_workspace_bytes",
     "cq_decode_attention", "cq_decode_step", "cq_dequantize", "cq_paged_cache_bytes", "cq_encode_kv_paged",
     "cq_decode_attention_paged", "cq_decode_step_paged", "cq_kmeans_workspace_bytes", "cq_kmeans_fit",
-    "cq_chunk_default_split", "cq_chunk_workspace_bytes", "cq_chunk_attention", "cq_chunk_attention_paged",
+    "cq_fused_format", "cq_expand_codebook", "cq_chunk_default_split", "cq_chunk_workspace_bytes", "cq_chunk_attention", "cq_chunk_attention_paged",
     "cq_layer_table_bytes", "cq_layer_table_fill", "cq_decode_step_layers",
     "cq_rope_table_bytes", "cq_rope_table", "cq_decode_rope_default_split", "cq_decode_attention_rope",
     "cq_decode_attention_rope_paged", "cq_decode_step_rope", "cq_decode_step_rope_paged", "cq_probe_stream_read", "cq_probe_copy", "cq_probe_mfma",
@@ -136,6 +136,10 @@ def load() -> ctypes.CDLL:
     lib.cq_kmeans_workspace_bytes.argtypes = [fp, i32]
     lib.cq_kmeans_fit.restype = ctypes.c_int
     lib.cq_kmeans_fit.argtypes = [vp, i64, vp, fp, i32, i32, vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
+    lib.cq_fused_format.restype = ctypes.c_int
+    lib.cq_fused_format.argtypes = [fp, fp]
+    lib.cq_expand_codebook.restype = ctypes.c_int
+    lib.cq_expand_codebook.argtypes = [vp, fp, vp, vp]
     lib.cq_chunk_default_split.restype = i32
     lib.cq_chunk_default_split.argtypes = [fp, i32, i32, i32, i32]
     lib.cq_chunk_workspace_bytes.restype = ctypes.c_size_t
@@ -366,6 +370,34 @@ def cq_decode_attention(q, k_codes, v_codes, k_centroids, v_centroids, scale: fl
     call, out = prepare_decode_attention(q, k_codes, v_codes, k_centroids, v_centroids, scale, fmt, t, t_cap,
                                          seq_lens, tokens_per_split, out, workspace)
     call(stream)
+    return out
+
+
+def cq_fused_format(fmt: CQFormat) -> CQFormat:
+    """The format whose cache layout and decode kernels a format uses: itself for b = 8, 10,
+    CQ-<c 8/b>c8b for the sub-byte formats b = 2, 4."""
+    f, out = fmt._c(), _Format()
+    st = load().cq_fused_format(ctypes.byref(f), ctypes.byref(out))
+    if st != CQ_OK:
+        raise CQError(st, "cq_fused_format")
+    return CQFormat(out.c, out.b, out.head_dim, out.n_kv_heads)
+
+
+def cq_expand_codebook(centroids, fmt: CQFormat, out=None, stream=None):
+    """Sub-byte codebook fp16 [G, 2^b, c] -> the fused format's codebook fp16 [G b/8, 256, 8 c/b]."""
+    import torch
+    _dev(centroids, torch.float16, "centroids")
+    if not centroids.is_contiguous() or tuple(centroids.shape) != (fmt.groups, 1 << fmt.b, fmt.c):
+        raise ValueError("centroids must be contiguous [G, 2^b, c]")
+    fused = cq_fused_format(fmt)
+    if out is None:
+        out = torch.empty((fused.groups, 256, fused.c), dtype=torch.float16, device=centroids.device)
+    _dev(out, torch.float16, "out")
+    if not out.is_contiguous() or tuple(out.shape) != (fused.groups, 256, fused.c):
+        raise ValueError("out must be contiguous [G b/8, 256, 8 c/b]")
+    st = load().cq_expand_codebook(centroids.data_ptr(), ctypes.byref(fmt._c()), out.data_ptr(), _stream_handle(stream))
+    if st != CQ_OK:
+        raise CQError(st, "cq_expand_codebook")
     return out
 
 

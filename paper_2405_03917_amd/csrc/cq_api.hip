@@ -29,6 +29,30 @@ cq_status derive(const cq_format* fmt, Derived* out)
     d.groups = d.channels / fmt->c;
     d.bpth = d.gh * fmt->b / 8;
     d.tile_bytes = kTileTokens * d.bpth;
+    d.fuse = 1;
+    d.sub_c = d.c;
+    d.sub_b = d.b;
+    if (out) *out = d;
+    return CQ_OK;
+}
+
+cq_status derive_any(const cq_format* fmt, Derived* out)
+{
+    const cq_status st = derive(fmt, out);
+    if (st != CQ_ERR_UNSUPPORTED) return st;
+    // CQ-<c>c<b>b with b = 2 or 4: 8 / b neighbouring groups are stored as one byte, i.e. as one code
+    // of the product codebook of those groups
+    if (fmt->b != 2 && fmt->b != 4) return CQ_ERR_UNSUPPORTED;
+    const int fuse = 8 / fmt->b;
+    cq_format fused = *fmt;
+    fused.c = fmt->c * fuse;
+    fused.b = 8;
+    Derived d;
+    const cq_status sf = derive(&fused, &d);
+    if (sf != CQ_OK) return sf;
+    d.fuse = fuse;
+    d.sub_c = fmt->c;
+    d.sub_b = fmt->b;
     if (out) *out = d;
     return CQ_OK;
 }
@@ -75,19 +99,19 @@ const char* cq_status_string(cq_status status)
     return "CQ_ERR_UNKNOWN";
 }
 
-cq_status cq_format_check(const cq_format* fmt) { return derive(fmt, nullptr); }
+cq_status cq_format_check(const cq_format* fmt) { return derive_any(fmt, nullptr); }
 
 size_t cq_code_bytes_per_token_head(const cq_format* fmt)
 {
     Derived f;
-    if (derive(fmt, &f) != CQ_OK) return 0;
+    if (derive_any(fmt, &f) != CQ_OK) return 0;
     return (size_t)f.bpth;
 }
 
 size_t cq_cache_bytes(const cq_format* fmt, int32_t batch, int32_t t_cap)
 {
     Derived f;
-    if (derive(fmt, &f) != CQ_OK) return 0;
+    if (derive_any(fmt, &f) != CQ_OK) return 0;
     if (batch <= 0 || t_cap <= 0 || t_cap % kTileTokens != 0) return 0;
     return (size_t)batch * f.n_kv_heads * (t_cap / kTileTokens) * f.tile_bytes;
 }
@@ -169,7 +193,7 @@ cq_status cq_encode(const void* x, int64_t x_batch_stride, int64_t x_row_stride,
                     void* codes, int32_t t_offset, int32_t t_cap, void* stream)
 {
     Derived f;
-    const cq_status st = derive(fmt, &f);
+    const cq_status st = derive_any(fmt, &f);
     if (st != CQ_OK) return st;
     if (t_cap <= 0 || t_cap % kTileTokens != 0) return CQ_ERR_INVALID_ARG;
     return encode_common(x, nullptr, x_batch_stride, x_row_stride, centroids, nullptr, f, batch, t_new, codes, nullptr,
@@ -182,7 +206,7 @@ cq_status cq_encode_kv(const void* x_k, const void* x_v, int64_t x_batch_stride,
                        void* k_codes, void* v_codes, int32_t t_offset, int32_t t_cap, void* stream)
 {
     Derived f;
-    const cq_status st = derive(fmt, &f);
+    const cq_status st = derive_any(fmt, &f);
     if (st != CQ_OK) return st;
     if (t_cap <= 0 || t_cap % kTileTokens != 0) return CQ_ERR_INVALID_ARG;
     if (!x_v || !v_centroids || !v_codes) return CQ_ERR_INVALID_ARG;
@@ -190,10 +214,32 @@ cq_status cq_encode_kv(const void* x_k, const void* x_v, int64_t x_batch_stride,
                          v_codes, t_offset, t_cap, contiguous_map(f, t_cap), stream);
 }
 
+cq_status cq_fused_format(const cq_format* fmt, cq_format* fused)
+{
+    Derived f;
+    const cq_status st = derive_any(fmt, &f);
+    if (st != CQ_OK) return st;
+    if (!fused) return CQ_ERR_INVALID_ARG;
+    *fused = cq_format{f.c, f.b, f.head_dim, f.n_kv_heads};
+    return CQ_OK;
+}
+
+cq_status cq_expand_codebook(const void* centroids, const cq_format* fmt, void* fused_centroids, void* stream)
+{
+    Derived f;
+    const cq_status st = derive_any(fmt, &f);
+    if (st != CQ_OK) return st;
+    if (f.fuse == 1) return CQ_ERR_INVALID_ARG;          // nothing to expand: the format is its own fused format
+    if (!centroids || !fused_centroids || !aligned16(centroids) || !aligned16(fused_centroids) || centroids == fused_centroids)
+        return CQ_ERR_INVALID_ARG;
+    return launch_expand_codebook(static_cast<const uint16_t*>(centroids), f, static_cast<uint16_t*>(fused_centroids),
+                                  static_cast<hipStream_t>(stream));
+}
+
 size_t cq_paged_cache_bytes(const cq_format* fmt, int32_t n_pages)
 {
     Derived f;
-    if (derive(fmt, &f) != CQ_OK || n_pages <= 0) return 0;
+    if (derive_any(fmt, &f) != CQ_OK || n_pages <= 0) return 0;
     return (size_t)n_pages * f.n_kv_heads * f.tile_bytes;
 }
 
@@ -203,7 +249,7 @@ cq_status cq_encode_kv_paged(const void* x_k, const void* x_v, int64_t x_batch_s
                              void* k_pool, void* v_pool, const cq_page_table* pages, int32_t t_offset, void* stream)
 {
     Derived f;
-    cq_status st = derive(fmt, &f);
+    cq_status st = derive_any(fmt, &f);
     if (st != CQ_OK) return st;
     CacheMap map;
     int32_t t_cap = 0;

@@ -190,10 +190,95 @@ cq_status launch_dequant_format(const DequantArgs& a, hipStream_t stream)
     return hipGetLastError() == hipSuccess ? CQ_OK : CQ_ERR_HIP;
 }
 
+// ------------------------------------------------------------------------------------------
+// sub-byte formats (b = 2, 4; the CQ-<c>c<b>b variants of the paper's ablation on coupled channels)
+// ------------------------------------------------------------------------------------------
+// 8 / b neighbouring groups share one code byte (group i of the byte in bits [b i, b i + b)), and
+// the byte is stored where the fused format CQ-<c 8/b>c8b stores its code, so every decode kernel
+// reads these caches with the expanded codebook of expand_codebook_kernel.  The search itself is
+// the format's own: each group against its 2^b centroids, squared distance in fp32 in channel
+// order, lowest index on ties (searching the product codebook instead would let the rounding of
+// one group's distance decide the other's near ties).  One thread per (token, code byte).
+template <int SUB_B>
+__global__ __launch_bounds__(256) void encode_subbyte_kernel(EncodeArgs a)
+{
+    constexpr int FUSE = 8 / SUB_B, KS = 1 << SUB_B;
+    const EncodeTensor& tsr = a.tensor[blockIdx.z];
+    const int sub_c = a.f.sub_c;
+    const int bytes_per_token = a.f.groups;                 // fused groups = code bytes per token
+    const long long total = (long long)a.batch * a.t_new * bytes_per_token;
+    const long long idx = (long long)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= total) return;
+    const int gf = (int)(idx % bytes_per_token);            // fused group (all heads)
+    const long long row = idx / bytes_per_token;
+    const int t = (int)(row % a.t_new), n = (int)(row / a.t_new);
+    const uint16_t* x = tsr.x + (size_t)n * tsr.x_batch_stride + (size_t)t * tsr.x_row_stride + (size_t)gf * a.f.c;
+    unsigned code_byte = 0;
+    for (int i = 0; i < FUSE; ++i) {
+        const uint16_t* cen = tsr.centroids + ((size_t)gf * FUSE + i) * KS * sub_c;
+        float best = __builtin_inff();
+        int best_j = 0;
+        for (int j = 0; j < KS; ++j) {
+            float acc = 0.f;
+            for (int ch = 0; ch < sub_c; ++ch) {
+                const float d = (float)__builtin_bit_cast(_Float16, x[i * sub_c + ch]) -
+                                (float)__builtin_bit_cast(_Float16, cen[j * sub_c + ch]);
+                acc = __builtin_fmaf(d, d, acc);
+            }
+            if (acc < best) {
+                best = acc;
+                best_j = j;
+            }
+        }
+        code_byte |= (unsigned)best_j << (SUB_B * i);
+    }
+    const int hkv = gf / a.f.gh, g = gf % a.f.gh;
+    const int pos = a.t_offset + t, tile = pos / kTileTokens, u = pos % kTileTokens;
+    const int slot = (g - u) & (a.f.gh - 1);
+    uint8_t* dst = tsr.codes + a.map.tile_index(n, hkv, tile) * (size_t)a.f.tile_bytes;
+    dst[(slot >> 4) * 1024 + u * 16 + (slot & 15)] = (uint8_t)code_byte;
+}
+
+__global__ __launch_bounds__(256) void expand_codebook_kernel(const uint16_t* centroids, uint16_t* fused, int n_fused_groups,
+                                                              int sub_c, int sub_b)
+{
+    const int fuse = 8 / sub_b, ks = 1 << sub_b, cf = sub_c * fuse;
+    const long long total = (long long)n_fused_groups * 256 * cf;
+    const long long idx = (long long)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= total) return;
+    const int ch = (int)(idx % cf);
+    const int j = (int)((idx / cf) % 256);
+    const int gf = (int)(idx / ((long long)cf * 256));
+    const int i = ch / sub_c;                                // which of the fused groups
+    const int ji = (j >> (sub_b * i)) & (ks - 1);
+    fused[idx] = centroids[(((size_t)gf * fuse + i) * ks + ji) * sub_c + ch % sub_c];
+}
+
+cq_status launch_encode_subbyte(const EncodeArgs& a, hipStream_t stream)
+{
+    const long long total = (long long)a.batch * a.t_new * a.f.groups;
+    const long long blocks = (total + 255) / 256;
+    if (blocks > 0x7fffffffLL) return CQ_ERR_INVALID_ARG;
+    const dim3 grid((unsigned)blocks, 1, (unsigned)a.n_tensors);
+    if (a.f.sub_b == 4) hipLaunchKernelGGL(encode_subbyte_kernel<4>, grid, dim3(256), 0, stream, a);
+    else if (a.f.sub_b == 2) hipLaunchKernelGGL(encode_subbyte_kernel<2>, grid, dim3(256), 0, stream, a);
+    else return CQ_ERR_UNSUPPORTED;
+    return hipGetLastError() == hipSuccess ? CQ_OK : CQ_ERR_HIP;
+}
+
 }  // namespace
+
+cq_status launch_expand_codebook(const uint16_t* centroids, const Derived& f, uint16_t* fused, hipStream_t stream)
+{
+    const long long total = (long long)f.groups * 256 * f.c;
+    hipLaunchKernelGGL(expand_codebook_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream, centroids, fused,
+                       f.groups, f.sub_c, f.sub_b);
+    return hipGetLastError() == hipSuccess ? CQ_OK : CQ_ERR_HIP;
+}
 
 cq_status launch_encode(const EncodeArgs& a, hipStream_t stream)
 {
+    if (a.f.fuse > 1) return launch_encode_subbyte(a, stream);
     if (a.f.b == 8) {
         if (a.f.gh == 16 && a.f.c == 8) return launch_format<16, 8, 8>(a, stream);
         if (a.f.gh == 32 && a.f.c == 4) return launch_format<32, 4, 8>(a, stream);

@@ -21,10 +21,17 @@ struct Derived {
     int groups;        // channels / c
     int bpth;          // code bytes per token-head
     int tile_bytes;    // 64 * bpth
+    // sub-byte formats (b = 2, 4; derive_any only): `fuse` = 8 / b neighbouring groups share a code
+    // byte, and everything above describes the fused format CQ-<c fuse>c8b whose cache layout
+    // they use; sub_c / sub_b are the format's own c and b.  fuse = 1 otherwise.
+    int fuse, sub_c, sub_b;
 };
 
-// Host-side format check shared by every entry point.
+// Host-side format check shared by the entry points: formats with decode kernels (b = 8, 10).
 cq_status derive(const cq_format* fmt, Derived* out);
+// ... and also the sub-byte formats, which only cq_encode*, the size functions and
+// cq_expand_codebook take (they are decoded through their fused format).
+cq_status derive_any(const cq_format* fmt, Derived* out);
 
 // Where the 64-token tiles of a packed cache live.  Contiguous: [sequence][kv head][tile] with
 // t_cap / 64 tiles per stream.  Paged: a pool of pages, a page being one tile of every KV head
@@ -174,6 +181,8 @@ cq_status launch_encode(const EncodeArgs& a, hipStream_t stream);
 // many tokens per sequence: the MFMA-filtered kernel (cq_encode_mfma.hip)
 cq_status launch_encode_tiles(const EncodeArgs& a, hipStream_t stream);
 cq_status launch_decode(const DecodeArgs& a, hipStream_t stream);
+// centroids fp16 [G][2^b][c] of a sub-byte format -> fp16 [G / fuse][256][c fuse] of its fused format
+cq_status launch_expand_codebook(const uint16_t* centroids, const Derived& f, uint16_t* fused, hipStream_t stream);
 // merges the partials of `rows` (sequence, query head) pairs, n_split each, into fp16 rows
 cq_status launch_layer_table_write(const LayerChunk& chunk, int count, LayerPtrs* dst, hipStream_t stream);
 cq_status launch_decode_merge(const float* partials, uint16_t* out, int rows, int n_split, int head_dim, hipStream_t stream);

@@ -298,3 +298,25 @@ def test_chunk_attention_sizes_and_argument_checks_without_launching():
     assert run(split=64, ws=0) == E                                          # split context needs the workspace
     assert run(split=64, ws_bytes=64) == cq.CQ_ERR_WORKSPACE_TOO_SMALL
     assert run(fm=cq.CQFormat(8, 10, 128, 4)._c()) == cq.CQ_ERR_UNSUPPORTED
+
+
+def test_subbyte_formats_sizes_and_argument_checks_without_launching():
+    lib = cq.load()
+    for (c, b), (cf, bytes_th) in {(1, 2): (4, 32), (2, 2): (8, 16), (1, 4): (2, 64), (2, 4): (4, 32), (4, 4): (8, 16)}.items():
+        fmt = cq.CQFormat(c, b, 128, 4)
+        fused = cq.cq_fused_format(fmt)
+        assert (fused.c, fused.b) == (cf, 8)
+        assert cq.cq_code_bytes_per_token_head(fmt) == bytes_th == 128 * b // c // 8
+    assert cq.cq_fused_format(cq.CQFormat(8, 10, 128, 4)) == cq.CQFormat(8, 10, 128, 4)
+    f = cq.CQFormat(2, 4, 128, 4)._c()
+    E = cq.CQ_ERR_INVALID_ARG
+    assert lib.cq_expand_codebook(None, ctypes.byref(f), _fake(0x20000), None) == E
+    assert lib.cq_expand_codebook(_fake(0x10000), ctypes.byref(f), _fake(0x10000), None) == E
+    assert lib.cq_expand_codebook(_fake(0x10004), ctypes.byref(f), _fake(0x20000), None) == E
+    f8 = cq.CQFormat(4, 8, 128, 4)._c()
+    assert lib.cq_expand_codebook(_fake(0x10000), ctypes.byref(f8), _fake(0x20000), None) == E
+    assert lib.cq_fused_format(ctypes.byref(f), None) == E
+    bad = cq.CQFormat(8, 4, 128, 4)._c()
+    assert lib.cq_fused_format(ctypes.byref(bad), ctypes.byref(f8)) == cq.CQ_ERR_UNSUPPORTED
+    # the decode side refuses the sub-byte format itself
+    assert _decode(cq.CQFormat(2, 4, 128, 4)) == cq.CQ_ERR_UNSUPPORTED

@@ -227,3 +227,25 @@ def test_kmeanspp_then_lloyd_beats_random_codebooks_on_correlated_data():
     sampled = synth.sample_codebook(r, c, 8)[:, :K].astype(np.float32)
     base, _ = KO.objective(x, c, sampled)
     assert np.all(obj[:, -1] < 0.8 * base)
+
+
+def test_more_coupled_channels_lower_the_error_at_equal_bits_per_channel():
+    """The trend of the paper's ablation on coupled channels (Section 4.3, Figure 4) on the
+    correlated synthetic activations: at a fixed bit budget per channel the learned codebooks'
+    quantization error (Eq. 5) falls as more channels are coupled."""
+    import synth
+    D, n = 16, 6000
+    x = synth.sample_activations(synth.tensor_recipe(7, 0, "v", D), n)
+    rng = np.random.default_rng(5)
+
+    def err(c, b):
+        K = 1 << b
+        rnd = rng.integers(0, 2 ** 64, size=(D // c, K), dtype=np.uint64)
+        _, cent, _, obj = KO.fit(x, c, K, rnd, 25)
+        total, _ = KO.objective(x, c, cent)
+        return float(total.sum())
+    one_bit = [err(2, 2), err(4, 4), err(8, 8)]            # 1 bit per channel
+    two_bits = [err(1, 2), err(2, 4), err(4, 8)]           # 2 bits per channel
+    assert one_bit[0] > one_bit[1] > one_bit[2]
+    assert two_bits[0] > two_bits[1] > two_bits[2]
+    assert two_bits[2] < one_bit[2]                        # and more bits help at equal coupling
