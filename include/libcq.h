@@ -210,7 +210,8 @@ CQ_API cq_status cq_decode_step(const void *q, const void *x_k_new, const void *
  * sub-byte format instead when the format's own search is wanted bit for bit.)
  *
  * cq_encode, cq_encode_kv, cq_encode_kv_paged, cq_cache_bytes, cq_paged_cache_bytes,
- * cq_code_bytes_per_token_head and cq_format_check accept the sub-byte format itself, with its
+ * cq_code_bytes_per_token_head, cq_format_check, cq_kmeans_workspace_bytes and cq_kmeans_fit
+ * accept the sub-byte format itself, with its
  * own codebook fp16 [G][2^b][c]: every group is searched against its own 2^b centroids
  * (squared distance in fp32 in channel order, lowest index on ties), not the product codebook.
  *

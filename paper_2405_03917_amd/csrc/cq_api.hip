@@ -284,10 +284,27 @@ cq_status cq_dequantize(const void* codes, const void* centroids, const cq_forma
     return launch_dequantize(a, static_cast<hipStream_t>(stream));
 }
 
+namespace {
+
+// The centroid learning sees a sub-byte format as what it is: channels / c groups of 2^b centroids.
+cq_status derive_for_learning(const cq_format* fmt, Derived* f)
+{
+    const cq_status st = derive_any(fmt, f);
+    if (st != CQ_OK || f->fuse == 1) return st;
+    f->c = f->sub_c;
+    f->b = f->sub_b;
+    f->k = 1 << f->sub_b;
+    f->gh = f->head_dim / f->sub_c;
+    f->groups = f->channels / f->sub_c;
+    return CQ_OK;
+}
+
+}  // namespace
+
 size_t cq_kmeans_workspace_bytes(const cq_format* fmt, int32_t n_points)
 {
     Derived f;
-    if (derive(fmt, &f) != CQ_OK || n_points <= 0 || n_points > CQ_KMEANS_MAX_POINTS) return 0;
+    if (derive_for_learning(fmt, &f) != CQ_OK || n_points <= 0 || n_points > CQ_KMEANS_MAX_POINTS) return 0;
     return kmeans_workspace_layout(f, n_points, nullptr, nullptr);
 }
 
@@ -297,7 +314,7 @@ cq_status cq_kmeans_fit(const void* x, int64_t x_row_stride, const float* weight
                         void* workspace, size_t workspace_bytes, void* stream)
 {
     Derived f;
-    cq_status st = derive(fmt, &f);
+    cq_status st = derive_for_learning(fmt, &f);
     if (st != CQ_OK) return st;
     if (n_points <= 0 || n_points > CQ_KMEANS_MAX_POINTS || n_iter < 0) return CQ_ERR_INVALID_ARG;
     if (!x || !aligned16(x) || x_row_stride < f.channels || x_row_stride % 8 != 0) return CQ_ERR_INVALID_ARG;

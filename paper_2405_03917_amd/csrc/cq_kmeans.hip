@@ -56,9 +56,12 @@ __device__ __forceinline__ void widen(const uint16_t* p, float (&v)[C])
         const uint2 a = *reinterpret_cast<const uint2*>(p);
         const half2_t h0 = __builtin_bit_cast(half2_t, a.x), h1 = __builtin_bit_cast(half2_t, a.y);
         v[0] = (float)h0.x; v[1] = (float)h0.y; v[2] = (float)h1.x; v[3] = (float)h1.y;
-    } else {
+    } else if constexpr (C == 2) {
         const half2_t h = __builtin_bit_cast(half2_t, *reinterpret_cast<const unsigned*>(p));
         v[0] = (float)h.x; v[1] = (float)h.y;
+    } else {
+        static_assert(C == 1, "channels per group: 1, 2, 4 or 8");
+        v[0] = (float)__builtin_bit_cast(_Float16, *p);
     }
 }
 
@@ -105,7 +108,7 @@ __global__ __launch_bounds__(256) void kmeans_prepare_kernel(const uint16_t* x, 
                                                              const unsigned* wmax_bits, int n, int G, uint16_t* xg,
                                                              uint32_t* wq)
 {
-    using unit_t = std::conditional_t<C == 8, uint4, std::conditional_t<C == 4, uint2, unsigned>>;
+    using unit_t = std::conditional_t<C == 8, uint4, std::conditional_t<C == 4, uint2, std::conditional_t<C == 2, unsigned, uint16_t>>>;
     __shared__ unit_t tile[kPrepTokens][kPrepGroups + 1];
     __shared__ uint32_t wt[kPrepTokens][kPrepGroups + 1];
     const int i0 = blockIdx.x * kPrepTokens, g0 = blockIdx.y * kPrepGroups;
@@ -493,6 +496,7 @@ cq_status launch_kmeans(const KMeansArgs& a, void* workspace, hipStream_t stream
     case 8: return run_all<8>(a, ws, stream);
     case 4: return run_all<4>(a, ws, stream);
     case 2: return run_all<2>(a, ws, stream);
+    case 1: return run_all<1>(a, ws, stream);
     default: return CQ_ERR_UNSUPPORTED;
     }
 }

@@ -34,7 +34,8 @@ def _weights(seed, n, G, zero_fraction=0.1):
     return w
 
 
-@pytest.mark.parametrize("c,b,n", [(8, 8, 1000), (4, 8, 2500), (2, 8, 700), (8, 10, 3000)])
+@pytest.mark.parametrize("c,b,n", [(8, 8, 1000), (4, 8, 2500), (2, 8, 700), (8, 10, 3000),
+                                   (1, 2, 900), (2, 2, 333), (1, 4, 1100), (2, 4, 2000), (4, 4, 650)])
 @pytest.mark.parametrize("weighted", [False, True])
 def test_kmeanspp_picks_are_the_oracles(c, b, n, weighted):
     fmt = cq.CQFormat(c, b, 128, 1)
@@ -51,7 +52,8 @@ def test_kmeanspp_picks_are_the_oracles(c, b, n, weighted):
     assert np.array_equal(out["centroids"].cpu().numpy(), cent.astype(np.float16))
 
 
-@pytest.mark.parametrize("c,b,n", [(8, 8, 1500), (4, 8, 3001), (2, 8, 640), (8, 10, 2100)])
+@pytest.mark.parametrize("c,b,n", [(8, 8, 1500), (4, 8, 3001), (2, 8, 640), (8, 10, 2100),
+                                   (1, 2, 777), (2, 2, 1500), (1, 4, 640), (2, 4, 901), (4, 4, 3001)])
 @pytest.mark.parametrize("weighted", [False, True])
 def test_lloyd_iterations_are_bit_identical(c, b, n, weighted):
     fmt = cq.CQFormat(c, b, 128, 2)
