@@ -322,7 +322,7 @@ CQ_API cq_status cq_decode_step_paged(const void *q, const void *x_k_new, const 
  *   with (no positional rotation).
  * The contraction runs on the matrix cores in fp16 with fp32 accumulation: scores are exact
  * products summed in fp32; probabilities enter the value product as two fp16 numbers (22 bits).
- * b = 8 formats with head_dim 128 only (CQ_ERR_UNSUPPORTED otherwise).
+ * Formats: those of cq_decode_attention (b = 8, 10 at head_dim 128).
  * Errors: as cq_decode_attention; CQ_ERR_INVALID_ARG also for m <= 0 or m > t.
  */
 CQ_API int32_t cq_chunk_default_split(const cq_format *fmt, int32_t batch, int32_t n_q_heads, int32_t m, int32_t t);

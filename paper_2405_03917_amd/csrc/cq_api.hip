@@ -525,7 +525,7 @@ cq_status chunk_common(const void* q, const void* k_codes, const void* v_codes,
     Derived f;
     cq_status st = derive(fmt, &f);
     if (st != CQ_OK) return st;
-    if (f.b != 8 || f.head_dim != 128) return CQ_ERR_UNSUPPORTED;
+    if (f.head_dim != 128) return CQ_ERR_UNSUPPORTED;
     CacheMap map;
     if (pages) {
         if ((st = paged_map(f, pages, batch, &map, &t_cap)) != CQ_OK) return st;
@@ -580,7 +580,7 @@ cq_status chunk_common(const void* q, const void* k_codes, const void* v_codes,
 int32_t cq_chunk_default_split(const cq_format* fmt, int32_t batch, int32_t n_q_heads, int32_t m, int32_t t)
 {
     Derived f;
-    if (derive(fmt, &f) != CQ_OK || f.b != 8 || f.head_dim != 128) return 0;
+    if (derive(fmt, &f) != CQ_OK || f.head_dim != 128) return 0;
     if (batch <= 0 || n_q_heads <= 0 || n_q_heads % f.n_kv_heads != 0 || m <= 0 || t < m) return 0;
     return chunk_tiles_per_split(f, batch, n_q_heads, m, t) * kTileTokens;
 }
@@ -589,7 +589,7 @@ size_t cq_chunk_workspace_bytes(const cq_format* fmt, int32_t batch, int32_t n_q
                                 int32_t tokens_per_split)
 {
     Derived f;
-    if (derive(fmt, &f) != CQ_OK || f.b != 8 || f.head_dim != 128) return 0;
+    if (derive(fmt, &f) != CQ_OK || f.head_dim != 128) return 0;
     if (batch <= 0 || n_q_heads <= 0 || n_q_heads % f.n_kv_heads != 0 || m <= 0 || t < m) return 0;
     if (tokens_per_split < 0 || tokens_per_split % kTileTokens != 0) return 0;
     const int tiles = tokens_per_split ? tokens_per_split / kTileTokens : chunk_tiles_per_split(f, batch, n_q_heads, m, t);

@@ -55,10 +55,11 @@ __device__ __forceinline__ half4_t lds_half4(unsigned byte_addr)
 // token's record.  A wavefront thus gathers from ONE group's centroids at a time: its 64 lanes
 // touch the 8 to 32 cache lines of that group's table instead of 64 lines of 64 tables, which is
 // what the texture path charges for.
-template <int GH, int C, int NW>
+template <int GH, int C, int NW, int B>
 struct Dequant {
     static constexpr int GPT = GH / NW;                 // groups per thread
-    static constexpr int TILE = kTileTokens * GH;       // bytes of one tile's codes
+    static constexpr int K = 1 << B;                    // centroids per group
+    static constexpr int TILE = kTileTokens * GH * B / 8;   // bytes of one tile's codes (b = 10: low bytes, then high-bit words)
     static constexpr int LOADERS = TILE / 16;           // threads that carry one record of K and one of V
     static constexpr int RAW_STAGE = 2 * TILE;          // K tile, V tile
     static_assert(LOADERS <= NW * 64, "one record per thread");
@@ -91,10 +92,16 @@ struct Dequant {
             const int g = g0 + gi;
             const unsigned slot = (unsigned)(g - u) & (unsigned)(GH - 1);
             const unsigned off = (slot >> 4) * 1024 + (unsigned)u * 16 + (slot & 15);
-            const unsigned kc = *(lds_b*)(raw_stage + off);
-            const unsigned vc = *(lds_b*)(raw_stage + TILE + off);
-            const unsigned* kp = reinterpret_cast<const unsigned*>(ck_head + ((size_t)g * 256 + kc) * C);
-            const unsigned* vp = reinterpret_cast<const unsigned*>(cv_head + ((size_t)g * 256 + vc) * C);
+            unsigned kc = *(lds_b*)(raw_stage + off);
+            unsigned vc = *(lds_b*)(raw_stage + TILE + off);
+            if constexpr (B == 10) {        // bits [2 s + 1 : 2 s] of the token's high-bit word
+                typedef __attribute__((address_space(3))) unsigned lds_w;
+                const unsigned hoff = (unsigned)(kTileTokens * GH) + (unsigned)u * 4;
+                kc |= ((*(lds_w*)(raw_stage + hoff) >> (2 * slot)) & 3u) << 8;
+                vc |= ((*(lds_w*)(raw_stage + TILE + hoff) >> (2 * slot)) & 3u) << 8;
+            }
+            const unsigned* kp = reinterpret_cast<const unsigned*>(ck_head + ((size_t)g * K + kc) * C);
+            const unsigned* vp = reinterpret_cast<const unsigned*>(cv_head + ((size_t)g * K + vc) * C);
 #pragma unroll
             for (int i = 0; i < C / 2; ++i) {
                 kw[gi][i] = kp[i];
@@ -124,12 +131,12 @@ struct Dequant {
     }
 };
 
-template <int GH, int C, int NW>
+template <int GH, int C, int NW, int B>
 __global__ __launch_bounds__(NW * 64) void chunk_attention_kernel(ChunkArgs a)
 {
     constexpr int kRowsPerWg = NW * 32;
-    constexpr unsigned kRawStageBytes = Dequant<GH, C, NW>::RAW_STAGE;
-    using F = Fmt<GH, 8>;
+    constexpr unsigned kRawStageBytes = Dequant<GH, C, NW, B>::RAW_STAGE;
+    using F = Fmt<GH, B>;
     constexpr int D = 128;
     static_assert(GH * C == D, "head_dim 128");
     extern __shared__ float smem[];
@@ -184,8 +191,8 @@ __global__ __launch_bounds__(NW * 64) void chunk_attention_kernel(ChunkArgs a)
         for (int s = 0; s < 8; ++s) qreg[s] = *reinterpret_cast<const half8_t*>(qrow + 16 * s + 8 * kh);
     }
 
-    const uint16_t* ck_head = a.k_centroids + (size_t)hkv * GH * 256 * C;
-    const uint16_t* cv_head = a.v_centroids + (size_t)hkv * GH * 256 * C;
+    const uint16_t* ck_head = a.k_centroids + (size_t)hkv * GH * F::K * C;
+    const uint16_t* cv_head = a.v_centroids + (size_t)hkv * GH * F::K * C;
     auto tile_ptr = [&](const uint8_t* base, int tile) {
         return base + a.map.tile_index(n, hkv, tile) * F::TILE_BYTES;
     };
@@ -199,7 +206,7 @@ __global__ __launch_bounds__(NW * 64) void chunk_attention_kernel(ChunkArgs a)
 
     // software pipeline over the tiles: while tile k is multiplied, the centroids of tile k + 1
     // are on their way from L2 and the codes of tile k + 2 from HBM
-    Dequant<GH, C, NW> dq;
+    Dequant<GH, C, NW, B> dq;
     if (tile0 < tile1) {
         dq.load_raw(tile_ptr(a.k_codes, tile0), tile_ptr(a.v_codes, tile0), tid);
         dq.store_raw(kRawBase, tid);
@@ -341,10 +348,10 @@ __global__ __launch_bounds__(NW * 64) void chunk_attention_kernel(ChunkArgs a)
     }
 }
 
-template <int GH, int C, int NW>
+template <int GH, int C, int NW, int B>
 cq_status launch_chunk_variant(const ChunkArgs& a, hipStream_t stream)
 {
-    auto kernel = chunk_attention_kernel<GH, C, NW>;
+    auto kernel = chunk_attention_kernel<GH, C, NW, B>;
     static std::once_flag once;
     static hipError_t setup = hipSuccess;
     std::call_once(once, [&] {
@@ -360,17 +367,17 @@ cq_status launch_chunk_variant(const ChunkArgs& a, hipStream_t stream)
     const int qper = a.n_q_heads / a.f.n_kv_heads;
     const int row_blocks = (a.m * qper + NW * 32 - 1) / (NW * 32);
     const unsigned grid = (unsigned)(a.batch * a.n_split * row_blocks * a.f.n_kv_heads);
-    const size_t lds = 2 * kStageBytes + 2 * Dequant<GH, C, NW>::RAW_STAGE;
+    const size_t lds = 2 * kStageBytes + 2 * Dequant<GH, C, NW, B>::RAW_STAGE;
     hipLaunchKernelGGL(kernel, dim3(grid), dim3(NW * 64), lds, stream, a);
     return hipGetLastError() == hipSuccess ? CQ_OK : CQ_ERR_HIP;
 }
 
-template <int GH, int C>
+template <int GH, int C, int B>
 cq_status launch_chunk_rows(const ChunkArgs& a, hipStream_t stream)
 {
     const int rows = a.m * (a.n_q_heads / a.f.n_kv_heads);
-    if (chunk_rows_per_workgroup(rows) == 128) return launch_chunk_variant<GH, C, 4>(a, stream);
-    return launch_chunk_variant<GH, C, 8>(a, stream);
+    if (chunk_rows_per_workgroup(rows) == 128) return launch_chunk_variant<GH, C, 4, B>(a, stream);
+    return launch_chunk_variant<GH, C, 8, B>(a, stream);
 }
 
 }  // namespace
@@ -381,9 +388,11 @@ cq_status launch_chunk_attention(const ChunkArgs& a, hipStream_t stream)
 {
     cq_status st = CQ_ERR_UNSUPPORTED;
     if (a.f.b == 8 && a.f.head_dim == 128) {
-        if (a.f.gh == 16 && a.f.c == 8) st = launch_chunk_rows<16, 8>(a, stream);
-        else if (a.f.gh == 32 && a.f.c == 4) st = launch_chunk_rows<32, 4>(a, stream);
-        else if (a.f.gh == 64 && a.f.c == 2) st = launch_chunk_rows<64, 2>(a, stream);
+        if (a.f.gh == 16 && a.f.c == 8) st = launch_chunk_rows<16, 8, 8>(a, stream);
+        else if (a.f.gh == 32 && a.f.c == 4) st = launch_chunk_rows<32, 4, 8>(a, stream);
+        else if (a.f.gh == 64 && a.f.c == 2) st = launch_chunk_rows<64, 2, 8>(a, stream);
+    } else if (a.f.b == 10 && a.f.head_dim == 128 && a.f.gh == 16 && a.f.c == 8) {
+        st = launch_chunk_rows<16, 8, 10>(a, stream);
     }
     if (st != CQ_OK) return st;
     if (a.n_split > 1)

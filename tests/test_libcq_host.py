@@ -286,7 +286,8 @@ def test_chunk_attention_sizes_and_argument_checks_without_launching():
     assert cq.cq_chunk_workspace_bytes(fmt, 16, 8, 16, 4096) == 4 * 16 * 16 * 8 * 8 * 130
     # plenty of rows: one split
     assert cq.cq_chunk_default_split(fmt, 64, 32, 512, 4096) == 4096
-    assert cq.cq_chunk_default_split(cq.CQFormat(8, 10, 128, 4), 16, 8, 16, 4096) == 0
+    assert cq.cq_chunk_default_split(cq.CQFormat(8, 10, 128, 4), 16, 8, 16, 4096) == 512
+    assert cq.cq_chunk_default_split(cq.CQFormat(2, 4, 128, 4), 16, 8, 16, 4096) == 0        # sub-byte: through the fused format
     assert cq.cq_chunk_default_split(fmt, 16, 8, 5000, 4096) == 0            # more queries than cached tokens
 
     def run(fm=f, q=0x10000, m=16, t=128, t_cap=128, split=0, ws=0x70000, ws_bytes=1 << 30, hq=8, scale=0.1):
@@ -297,7 +298,7 @@ def test_chunk_attention_sizes_and_argument_checks_without_launching():
     assert run(t_cap=100) == E and run(split=100) == E and run(hq=6) == E and run(scale=float("inf")) == E
     assert run(split=64, ws=0) == E                                          # split context needs the workspace
     assert run(split=64, ws_bytes=64) == cq.CQ_ERR_WORKSPACE_TOO_SMALL
-    assert run(fm=cq.CQFormat(8, 10, 128, 4)._c()) == cq.CQ_ERR_UNSUPPORTED
+    assert run(fm=cq.CQFormat(2, 4, 128, 4)._c()) == cq.CQ_ERR_UNSUPPORTED
 
 
 def test_subbyte_formats_sizes_and_argument_checks_without_launching():
