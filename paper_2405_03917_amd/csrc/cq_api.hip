@@ -61,21 +61,36 @@ namespace {
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
-int default_tiles_per_split(const Derived& f, int batch, int n_q_heads, int t)
+int default_tiles_per_split(const Derived& f, int batch, int n_q_heads, int t, int max_tiles)
 {
+    // A workgroup costs its tiles plus a fixed part (table build, reductions, bins x centroids:
+    // each reads a whole head's codebook), here expressed in tiles of streaming time; the chip
+    // runs `slots` workgroups at a time (two per CU; one for the 1024-centroid format), in
+    // rounds.  Take the number of splits that minimises rounds x (tiles + fixed) over the
+    // splits the on-chip score buffer allows, down to 16 tiles per split.
     const int n_tiles = (t + kTileTokens - 1) / kTileTokens;
     const long bh = (long)batch * n_q_heads;
-    const int max_tiles = decode_max_tiles_per_split(f);
-    // two workgroups per CU (256 CUs) are enough to keep HBM busy; beyond that, longer splits win
-    // because building the lookup table and the final bins x centroids product are fixed costs
-    // of every workgroup (each reads a whole head's codebook)
-    const long want_wg = 512;
-    long n_split = std::max(1L, (want_wg + bh - 1) / bh);
-    const int min_tiles = 16;
-    n_split = std::min<long>(n_split, std::max(1, n_tiles / min_tiles));
-    int tiles = (int)((n_tiles + n_split - 1) / n_split);
-    tiles = std::max(1, std::min(tiles, max_tiles));
-    return tiles;
+    const long slots = f.b == 10 ? 256 : 512;
+    const long fixed = f.b == 10 ? 180 : (f.gh == 16 ? 60 : (f.gh == 32 ? 30 : 15));
+    const long ns_min = (n_tiles + max_tiles - 1) / max_tiles;
+    const long ns_max = std::max<long>(ns_min, n_tiles / 16);
+    long best_ns = ns_min, best_cost = -1;
+    for (long ns = ns_min; ns <= ns_max && ns < ns_min + 4096; ++ns) {
+        const long tiles = (n_tiles + ns - 1) / ns;
+        const long rounds = (bh * ns + slots - 1) / slots;
+        const long cost = rounds * (tiles + fixed);
+        if (best_cost < 0 || cost < best_cost) {
+            best_cost = cost;
+            best_ns = ns;
+        }
+        if (bh * ns >= 8 * slots && tiles <= 2 * fixed) break;      // further splits only add fixed cost
+    }
+    return (int)((n_tiles + best_ns - 1) / best_ns);
+}
+
+int default_tiles_per_split(const Derived& f, int batch, int n_q_heads, int t)
+{
+    return default_tiles_per_split(f, batch, n_q_heads, t, decode_max_tiles_per_split(f));
 }
 
 }  // namespace
@@ -413,7 +428,7 @@ cq_status decode_common(const void* q, const void* x_k_new, const void* x_v_new,
     }
     const int max_tiles = rope ? decode_rope_max_tiles_per_split() : decode_max_tiles_per_split(f);
     const int tiles = tokens_per_split ? tokens_per_split / kTileTokens
-                                       : std::min(max_tiles, default_tiles_per_split(f, batch, n_q_heads, t));
+                                       : default_tiles_per_split(f, batch, n_q_heads, t, max_tiles);
     if (tiles > max_tiles) return CQ_ERR_INVALID_ARG;
     const int n_tiles = (t + kTileTokens - 1) / kTileTokens;
     const int n_split = (n_tiles + tiles - 1) / tiles;
@@ -685,7 +700,7 @@ int32_t cq_decode_rope_default_split(const cq_format* fmt, int32_t batch, int32_
 {
     Derived f;
     if (derive(fmt, &f) != CQ_OK || f.b != 8 || f.head_dim != 128 || batch <= 0 || n_q_heads <= 0 || t <= 0) return 0;
-    return std::min(decode_rope_max_tiles_per_split(), default_tiles_per_split(f, batch, n_q_heads, t)) * kTileTokens;
+    return default_tiles_per_split(f, batch, n_q_heads, t, std::min(decode_rope_max_tiles_per_split(), decode_max_tiles_per_split(f))) * kTileTokens;
 }
 
 cq_status cq_decode_attention_rope(const void* q, const void* k_codes, const void* v_codes,

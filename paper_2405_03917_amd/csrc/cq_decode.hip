@@ -67,15 +67,19 @@ __global__ void layer_table_write_kernel(LayerChunk chunk, int count, LayerPtrs*
 // its weight is added to the bins of the codes just found.  The first query head of each KV head
 // stores the codes.  Results equal cq_encode_kv followed by cq_decode_attention bit for bit
 // (the bins are integers: the order of the additions does not matter).
-template <int GH, int C, int B, int NT, bool STEP, bool LAYERS>
+template <int GH, int C, int B, int NT, bool STEP, bool LAYERS, bool LONG>
 __global__ __launch_bounds__(NT, 4) void decode_split_kernel(DecodeArgs a)
 {
-    using F = Fmt<GH, B>;
+    using F = Fmt<GH, B, LONG>;
     constexpr int K = F::K, RW = F::RW, R = F::R;
     constexpr int NW = NT / 64;         // wavefronts
     constexpr int D = GH * C;           // head_dim
     // tiles in flight per wavefront (about 4 KB; less where registers are short)
+#ifdef CQ_PF16
+    constexpr int PF = B == 10 ? 2 : (GH == 16 ? CQ_PF16 : (GH == 32 ? CQ_PF32 : 1));
+#else
     constexpr int PF = B == 10 ? 2 : (GH == 16 ? 4 : (GH == 32 ? 2 : 1));
+#endif
     constexpr int JPL = 8 / C;          // centroids per 16-byte load
     constexpr int NCH = GH / 16;        // 16-group chunks
     constexpr int UNITS = 16 * K / JPL; // 16-byte loads per chunk
@@ -86,7 +90,7 @@ __global__ __launch_bounds__(NT, 4) void decode_split_kernel(DecodeArgs a)
     float* tab = smem;                              // [K][RW]; first the score table, then the bins
     // scores of the split: interleaved into the table rows, or a buffer behind the table
     float* sc = F::SCORES_IN_TABLE ? smem : smem + F::TAB_FLOATS;
-    auto sidx = [](int i) { return F::SCORES_IN_TABLE ? ((i >> 5) << 6) + 32 + (i & 31) : i; };
+    auto sidx = [](int i) { return F::SCORES_IN_TABLE ? (i / F::SCORE_WORDS) * 64 + F::LUT_WORDS + i % F::SCORE_WORDS : i; };
     // reduction scratch: behind the table, or the (by then dead) score buffer
     float* scr = smem + F::TAB_FLOATS;
     // fused step: 64-bit (distance, index) minima per group, keys[0..GH) for K, [GH..2GH) for V
@@ -169,7 +173,7 @@ __global__ __launch_bounds__(NT, 4) void decode_split_kernel(DecodeArgs a)
         lds_barrier();
     }
 
-    Columns<GH, B> col;
+    Columns<GH, B, LONG> col;
     col.init(lane);
 
     const int my_tiles = (tile1 - tile0 - wave + NW - 1) / NW;   // tiles tile0 + wave + k NW
@@ -281,8 +285,8 @@ __global__ __launch_bounds__(NT, 4) void decode_split_kernel(DecodeArgs a)
         float acc0 = 0.f, acc1 = 0.f;
 #pragma unroll
         for (int s = 0; s < GH; s += 2) {
-            acc0 += lds_load(slot_addr<GH, B>(w, col, s));
-            acc1 += lds_load(slot_addr<GH, B>(w, col, s + 1));
+            acc0 += lds_load(slot_addr<GH, B, LONG>(w, col, s));
+            acc1 += lds_load(slot_addr<GH, B, LONG>(w, col, s + 1));
         }
         const int tok = (tile0 + lt) * kTileTokens + lane;
         const float sv = tok < t_n ? acc0 + acc1 : -INFINITY;
@@ -293,7 +297,10 @@ __global__ __launch_bounds__(NT, 4) void decode_split_kernel(DecodeArgs a)
 
     lane_max = wave_max(lane_max);
     lds_barrier();                                // all table reads done, all scores written
-    if (lane == 0) tab[wave] = lane_max;            // the table is dead: its head carries the maxima
+    // the table is dead: the first 2 NW words of its first row (table columns, never scores)
+    // carry the wavefronts' maxima and sums
+    static_assert(!F::SCORES_IN_TABLE || 2 * NW <= F::LUT_WORDS, "the reduction slots must not touch the scores");
+    if (lane == 0) tab[wave] = lane_max;
     lds_barrier();
     float m = tab[0];
 #pragma unroll
@@ -303,19 +310,20 @@ __global__ __launch_bounds__(NT, 4) void decode_split_kernel(DecodeArgs a)
     float l_est = 0.f;
     for (int i = tid; i < (tile1 - tile0) * kTileTokens; i += NT) l_est += __builtin_amdgcn_exp2f(sc[sidx(i)] - m);
     l_est = wave_sum(l_est);
-    if (lane == 0) tab[16 + wave] = l_est;
+    if (lane == 0) tab[NW + wave] = l_est;
     lds_barrier();
     l_est = 0.f;
 #pragma unroll
-    for (int w = 0; w < NW; ++w) l_est += tab[16 + w];
+    for (int w = 0; w < NW; ++w) l_est += tab[NW + w];
     const int fx = fixed_point_exponent(l_est);
     const float fx_scale = ldexpf(1.f, fx), fx_inv = ldexpf(1.f, -fx);
     lds_barrier();                                // everyone holds m and fx before the table is cleared
     {
         float4* t4 = reinterpret_cast<float4*>(tab);
-        if constexpr (F::SCORES_IN_TABLE) {         // clear words 0..31 of every row, keep the scores
+        if constexpr (F::SCORES_IN_TABLE) {         // clear the table columns of every row, keep the scores
+            constexpr int Q = F::LUT_WORDS / 4;     // float4 per row
 #pragma unroll 4
-            for (int i = tid; i < K * 8; i += NT) t4[(i >> 3) * 16 + (i & 7)] = make_float4(0.f, 0.f, 0.f, 0.f);
+            for (int i = tid; i < K * Q; i += NT) t4[(i / Q) * 16 + (i % Q)] = make_float4(0.f, 0.f, 0.f, 0.f);
         } else {
 #pragma unroll 4
             for (int i = tid; i < F::TAB_FLOATS / 4; i += NT) t4[i] = make_float4(0.f, 0.f, 0.f, 0.f);
@@ -341,7 +349,7 @@ __global__ __launch_bounds__(NT, 4) void decode_split_kernel(DecodeArgs a)
             pf = 0;
         }
 #pragma unroll
-        for (int s = 0; s < GH; ++s) lds_add(slot_addr<GH, B>(w, col, s), pf);
+        for (int s = 0; s < GH; ++s) lds_add(slot_addr<GH, B, LONG>(w, col, s), pf);
     }, [&] {
         // the value centroids of the epilogue are requested behind the last value tiles, so their
         // latency overlaps the last tiles and the wait for the slowest wavefront (where registers
@@ -498,10 +506,10 @@ __global__ void decode_merge_kernel(const float* partials, uint16_t* out, int n_
     }
 }
 
-template <int GH, int B, int NT>
+template <int GH, int B, int NT, bool LONG>
 size_t smem_bytes(int tiles_per_split, int head_dim, bool step)
 {
-    using F = Fmt<GH, B>;
+    using F = Fmt<GH, B, LONG>;
     const int key_floats = step ? kKeyFloats(GH) : 0;
     if (F::SCORES_IN_TABLE) return sizeof(float) * (size_t)(F::TAB_FLOATS + kScratchFloats(NT, head_dim) + key_floats);
     // behind the table: the score buffer (reused as scratch once the scores are dead), then the keys
@@ -509,10 +517,10 @@ size_t smem_bytes(int tiles_per_split, int head_dim, bool step)
     return sizeof(float) * (size_t)(F::TAB_FLOATS + sc_floats + key_floats);
 }
 
-template <int GH, int C, int B, int NT, bool STEP, bool LAYERS>
+template <int GH, int C, int B, int NT, bool STEP, bool LAYERS, bool LONG = false>
 cq_status launch_variant(const DecodeArgs& a, hipStream_t stream)
 {
-    auto kernel = decode_split_kernel<GH, C, B, NT, STEP, LAYERS>;
+    auto kernel = decode_split_kernel<GH, C, B, NT, STEP, LAYERS, LONG>;
     static std::once_flag once;
     static hipError_t setup = hipSuccess;
     std::call_once(once, [&] {
@@ -525,7 +533,7 @@ cq_status launch_variant(const DecodeArgs& a, hipStream_t stream)
                                         hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
     });
     if (setup != hipSuccess) return CQ_ERR_HIP;
-    const size_t smem = smem_bytes<GH, B, NT>(a.tiles_per_split, a.f.head_dim, STEP);
+    const size_t smem = smem_bytes<GH, B, NT, LONG>(a.tiles_per_split, a.f.head_dim, STEP);
     if (smem > 160 * 1024) return CQ_ERR_INVALID_ARG;
     const unsigned grid = (unsigned)(a.batch * a.n_q_heads * a.n_split) * (unsigned)(a.layers ? a.n_layers : 1);
     hipLaunchKernelGGL(kernel, dim3(grid), dim3(NT), smem, stream, a);
@@ -539,6 +547,11 @@ cq_status launch_by_split(const DecodeArgs& a, hipStream_t stream)
     // 16 / 32 groups per head: scores live inside the table, 68 KB of LDS, two 512-thread
     // workgroups per CU.  64 groups per head: 64 KB table + 4 B per token of the split; up to 64
     // tiles two 512-thread workgroups fit a CU, longer splits run as one 1024-thread workgroup.
+    // 16 groups per head, more than 8192 tokens per split: the table without replicas (12288 tokens)
+    if constexpr (GH == 16) {
+        if (a.tiles_per_split > 256 * Fmt<16, 8>::SCORE_WORDS / kTileTokens)
+            return launch_variant<GH, C, 8, 512, STEP, LAYERS, true>(a, stream);
+    }
     if (Fmt<GH, 8>::SCORES_IN_TABLE || a.tiles_per_split <= 64) return launch_variant<GH, C, 8, 512, STEP, LAYERS>(a, stream);
     return launch_variant<GH, C, 8, 1024, STEP, LAYERS>(a, stream);
 }
@@ -574,7 +587,8 @@ cq_status launch_decode_merge(const float* partials, uint16_t* out, int rows, in
 int decode_max_tiles_per_split(const Derived& f)
 {
     if (f.b == 10) return (160 * 1024 / 4 - Fmt<16, 10>::TAB_FLOATS - kKeyFloats(16)) / kTileTokens;   // 382: 160 KB of LDS
-    if (f.gh <= 32) return 256 * 32 / kTileTokens;                                    // 128: scores inside the table
+    if (f.gh == 16) return 256 * Fmt<16, 8, true>::SCORE_WORDS / kTileTokens;         // 192: scores inside the table, no replicas
+    if (f.gh == 32) return 256 * Fmt<32, 8>::SCORE_WORDS / kTileTokens;               // 128
     return 256;
 }
 

@@ -130,15 +130,19 @@ __device__ __forceinline__ int fixed_point_exponent(float l_est)
 }
 
 // Format constants.
-template <int GH, int B>
+// LONG (16 groups per head, b = 8 only): one column per group instead of two replicas, which
+// leaves 48 instead of 32 words of every row for scores, i.e. splits of 12288 instead of 8192 tokens.
+template <int GH, int B, bool LONG = false>
 struct Fmt {
     static constexpr int K = 1 << B;                    // rows
     // replicas per group: two where a row would otherwise be 16 words and 4 lanes of a wavefront
     // would share each column; not for b = 10, whose 1024 rows would then fill 128 KB and leave
     // room for short splits only (fixed costs per split dominate that format)
-    static constexpr int R = (GH == 16 && B == 8) ? 2 : 1;
+    static constexpr int R = (GH == 16 && B == 8 && !LONG) ? 2 : 1;
     static constexpr int RW = B == 8 ? 64 : 16;         // words per row
-    static constexpr bool SCORES_IN_TABLE = B == 8 && GH <= 32;   // words 32..63 of each row
+    static constexpr bool SCORES_IN_TABLE = B == 8 && GH <= 32;   // behind the table's columns in each row
+    static constexpr int LUT_WORDS = GH * R;            // words of a row that hold table columns
+    static constexpr int SCORE_WORDS = 64 - LUT_WORDS;  // scores per row (SCORES_IN_TABLE)
     static constexpr int P = GH / 16;                   // 16-byte planes of low code bytes
     static constexpr int TAB_FLOATS = K * RW;
     static constexpr int TILE_BYTES = kTileTokens * GH * B / 8;
@@ -147,10 +151,10 @@ struct Fmt {
 };
 
 // Word column of lane `lane` when it handles group g.
-template <int GH, int B>
+template <int GH, int B, bool LONG>
 __device__ __forceinline__ int column(int lane, int g)
 {
-    if constexpr (Fmt<GH, B>::R == 2) {
+    if constexpr (Fmt<GH, B, LONG>::R == 2) {
         return 2 * g + ((lane >> 4) & 1);       // lanes l and l + 16 differ, l and l + 32 share
     } else {
         (void)lane;
@@ -208,7 +212,7 @@ struct TileWalk {
 
 // Per-lane column constants for the Gh steps: b = 8 packs 4 byte offsets per register (the
 // v_perm_b32 picks one), b = 10 keeps one register per step.
-template <int GH, int B>
+template <int GH, int B, bool LONG = false>
 struct Columns {
     unsigned v[B == 8 ? GH / 4 : GH];
     __device__ __forceinline__ void init(int lane)
@@ -220,20 +224,20 @@ struct Columns {
 #pragma unroll
                 for (int k = 0; k < 4; ++k) {
                     const int g = (lane + 4 * i + k) & (GH - 1);
-                    x |= (unsigned)(4 * column<GH, B>(lane, g)) << (8 * k);
+                    x |= (unsigned)(4 * column<GH, B, LONG>(lane, g)) << (8 * k);
                 }
                 v[i] = x;
             }
         } else {
 #pragma unroll
-            for (int s = 0; s < GH; ++s) v[s] = 4u * (unsigned)column<GH, B>(lane, (lane + s) & (GH - 1));
+            for (int s = 0; s < GH; ++s) v[s] = 4u * (unsigned)column<GH, B, LONG>(lane, (lane + s) & (GH - 1));
         }
     }
 };
 
 // Byte address of the table word for slot s of this lane's token.
-template <int GH, int B>
-__device__ __forceinline__ unsigned slot_addr(const Tile<GH, B>& w, const Columns<GH, B>& col, int s)
+template <int GH, int B, bool LONG>
+__device__ __forceinline__ unsigned slot_addr(const Tile<GH, B>& w, const Columns<GH, B, LONG>& col, int s)
 {
     const u32x4 q = w.lo[s >> 4];
     const int dw = (s >> 2) & 3;

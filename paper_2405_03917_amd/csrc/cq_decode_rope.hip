@@ -347,7 +347,7 @@ __global__ __launch_bounds__(NT) void decode_rope_kernel(DecodeArgs a, const flo
             pf = 0;
         }
 #pragma unroll
-        for (int s = 0; s < GH; ++s) lds_add(slot_addr<GH, B>(w, col, s), pf);
+        for (int s = 0; s < GH; ++s) lds_add(slot_addr<GH, B, false>(w, col, s), pf);
     }, [&] {
         if constexpr (EARLY) {
 #pragma unroll

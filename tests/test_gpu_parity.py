@@ -267,6 +267,34 @@ def test_decode_1024_centroid_format_one_long_split():
     assert cq.cq_decode_workspace_bytes(fmt, B, hq, T, 24448 + 64) == 0        # beyond the on-chip buffer
 
 
+def test_decode_cq8c8b_splits_beyond_8192_tokens_use_the_table_without_replicas():
+    # 16 groups per head: up to 8192 tokens per split the table has two columns per group, beyond
+    # (to 12288) one; both against the oracle, and the fused step in the long form bit for bit
+    c, b, hq, hkv, B, T, t_cap = 8, 8, 2, 1, 2, 12200, 12288
+    fmt, q, kc, vc, ck, cv = _attn_case(12, c, b, hq, hkv, B, T)
+    lens = np.array([12200, 9000], dtype=np.int32)
+    ref = O.attention(q, kc, vc, ck, cv, 0.1, hkv, seq_lens=lens)
+    kcache, vcache = codes_to_cache(kc, fmt, t_cap), codes_to_cache(vc, fmt, t_cap)
+    for split in (8192, 8256, 10944, 12288):
+        out = gpu_attention(q, kcache, vcache, ck, cv, 0.1, fmt, T, t_cap, seq_lens=lens, tokens_per_split=split)
+        check_attention(out, ref)
+    assert cq.cq_decode_workspace_bytes(fmt, B, hq, T, 12288 + 64) == 0
+    x1k = np.concatenate([synth.sample_activations(synth.tensor_recipe(32, 0, "k", 128), 1, chunk=n) for n in range(B)])
+    x1v = np.concatenate([synth.sample_activations(synth.tensor_recipe(32, 0, "v", 128), 1, chunk=n) for n in range(B)])
+    k2, v2 = kcache.clone(), vcache.clone()
+    per_seq = kcache.numel() // B
+    for n in range(B):
+        sl = slice(n * per_seq, (n + 1) * per_seq)
+        cq.cq_encode_kv(dev(x1k[n].copy().reshape(1, 1, -1)), dev(x1v[n].copy().reshape(1, 1, -1)), dev(ck), dev(cv), fmt, k2[sl], v2[sl],
+                        int(lens[n]) - 1, t_cap)
+    want = cq.cq_decode_attention(dev(q), k2, v2, dev(ck), dev(cv), 0.1, fmt, T, t_cap, seq_lens=dev(lens), tokens_per_split=12288)
+    got = cq.cq_decode_step(dev(q), dev(x1k), dev(x1v), kcache, vcache, dev(ck), dev(cv), 0.1, fmt, T, t_cap, seq_lens=dev(lens),
+                            tokens_per_split=12288)
+    torch.cuda.synchronize()
+    assert torch.equal(kcache, k2) and torch.equal(vcache, v2)
+    assert torch.equal(got.view(torch.int16), want.view(torch.int16))
+
+
 def test_decode_single_token_returns_the_dequantized_value_bit_exactly():
     for c, b in DECODE_FORMATS:
         fmt, q, kc, vc, ck, cv = _attn_case(1, c, b, 8, 2, 3, 1)
@@ -421,7 +449,7 @@ def _sweep_cases():
         B = int(rng.integers(1, 4))
         T = int(rng.choice([1, 2, 64, 127, 128, 129, 500, 1337, 2049]))
         tiles = -(-T // 64)
-        max_split_tiles = 382 if b == 10 else (128 if c >= 4 else 256)
+        max_split_tiles = 382 if b == 10 else (192 if c == 8 else (128 if c == 4 else 256))
         split_tiles = int(rng.integers(1, min(tiles, max_split_tiles) + 1)) if rng.random() < 0.6 else 0
         ragged = bool(rng.random() < 0.5)
         cases.append((i, c, b, hkv * qper, hkv, B, T, split_tiles * 64, ragged))

@@ -244,7 +244,7 @@ def test_rope_sizes_and_argument_checks_without_launching():
     assert dec(fmt, ws_bytes=16) == cq.CQ_ERR_WORKSPACE_TOO_SMALL
     assert dec(cq.CQFormat(8, 10, 128, 4)) == cq.CQ_ERR_UNSUPPORTED    # 1024 centroids per group do not fit on chip
     assert cq.cq_decode_rope_default_split(cq.CQFormat(8, 10, 128, 4), 2, 8, 4096) == 0
-    assert cq.cq_decode_rope_default_split(cq.CQFormat(2, 8, 128, 32), 64, 32, 64 * 1000) == 64 * 128    # 256 without the rotation
+    assert cq.cq_decode_rope_default_split(cq.CQFormat(2, 8, 128, 32), 64, 32, 64 * 1000) == 64 * 125    # 8 balanced splits of at most 128 tiles (256 without the rotation)
 
 
 def test_layer_table_argument_checks_without_copying():
