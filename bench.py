@@ -36,7 +36,7 @@ if ROOT not in sys.path:
 HBM_PEAK_GBPS = 8000.0          # MI355X published peak, GB/s
 # HBM bytes per launch of the fused decode-step kernel from rocprofv3 counters (FETCH_SIZE x 1.9998
 # + WRITE_SIZE, KiB per dispatch), see profiles/decode_step_kernel_cq4c8b_batch16_ctx4096.md
-TRAFFIC_BYTES_PER_LAUNCH = (67974.1 * 1.9998 + 192.0) * 1024
+TRAFFIC_BYTES_PER_LAUNCH = (67982.3 * 1.9998 + 192.0) * 1024
 METRIC = "decode-attn KV tokens/s & achieved HBM GB/s (% peak); cq_encode tokens/s"
 
 
@@ -344,7 +344,7 @@ def main():
     dec_ms = ev_ms / (args.steps * n_layers)
     code_bytes = cfg.batch * cfg.context * 2 * cfg.kv_channels * cfg.b // (8 * cfg.c)   # per launch
     achieved = code_bytes / (dec_ms * 1e-3) / 1e9
-    roofline = {"bound": "hbm", "kernel": "decode_split_kernel<32,4,8,512,true,false> (cq_decode_step; one launch = one layer)",
+    roofline = {"bound": "hbm", "kernel": "decode_split_kernel<32,4,8,512,true,false,false> (cq_decode_step; one launch = one layer)",
                 "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS,
                 "traffic": TRAFFIC_BYTES_PER_LAUNCH if n_layers == cfg.layers else None,
                 "algorithmic_bytes_per_launch": code_bytes, "avg_launch_ms": dec_ms,
