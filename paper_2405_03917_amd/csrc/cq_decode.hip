@@ -75,11 +75,7 @@ __global__ __launch_bounds__(NT, 4) void decode_split_kernel(DecodeArgs a)
     constexpr int NW = NT / 64;         // wavefronts
     constexpr int D = GH * C;           // head_dim
     // tiles in flight per wavefront (about 4 KB; less where registers are short)
-#ifdef CQ_PF16
-    constexpr int PF = B == 10 ? 2 : (GH == 16 ? CQ_PF16 : (GH == 32 ? CQ_PF32 : 1));
-#else
     constexpr int PF = B == 10 ? 2 : (GH == 16 ? 4 : (GH == 32 ? 2 : 1));
-#endif
     constexpr int JPL = 8 / C;          // centroids per 16-byte load
     constexpr int NCH = GH / 16;        // 16-group chunks
     constexpr int UNITS = 16 * K / JPL; // 16-byte loads per chunk
