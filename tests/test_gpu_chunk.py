@@ -123,3 +123,35 @@ def test_chunk_rejects_short_sequences():
     fmt, q, kc, vc, ck, cv = _case(2, 8, 8, 2, 2, 1, 4, 64)
     with pytest.raises(cq.CQError):      # fewer cached tokens than queries
         cq.cq_chunk_attention(dev(q), codes_to_cache(kc, fmt, 64), codes_to_cache(vc, fmt, 64), dev(ck), dev(cv), 0.1, fmt, 3, 64)
+
+
+def _sweep_cases():
+    rng = np.random.default_rng(20240503)
+    cases = []
+    for i in range(16):
+        c, b = CHUNK_FORMATS[i % 4]
+        hkv = int(rng.choice([1, 2, 3, 8]))
+        qper = int(rng.choice([1, 2, 4, 8]))
+        B = int(rng.integers(1, 4))
+        T = int(rng.choice([1, 2, 64, 127, 129, 500, 1337]))
+        m = int(min(T, rng.choice([1, 2, 7, 33, 64, 150])))
+        tiles = -(-T // 64)
+        split_tiles = int(rng.integers(1, tiles + 1)) if rng.random() < 0.5 else 0
+        ragged = bool(rng.random() < 0.5)
+        cases.append((i, c, b, hkv * qper, hkv, B, m, T, split_tiles * 64, ragged))
+    return cases
+
+
+@pytest.mark.parametrize("case", _sweep_cases(), ids=lambda cs: "case%d-%dc%db-hq%d-hkv%d-B%d-m%d-T%d-split%d-%s" % (
+    cs[:9] + ("ragged" if cs[9] else "full",)))
+def test_chunk_attention_sweep(case):
+    i, c, b, hq, hkv, B, m, T, split, ragged = case
+    fmt, q, kc, vc, ck, cv = _case(100 + i, c, b, hq, hkv, B, m, T)
+    t_cap = -(-T // 64) * 64
+    lens = None
+    if ragged:
+        lens = np.random.default_rng(i).integers(m, T + 1, size=B).astype(np.int32)
+    ref = O.chunk_attention(q, kc, vc, ck, cv, 0.09, hkv, seq_lens=lens)
+    out = _gpu(q, codes_to_cache(kc, fmt, t_cap), codes_to_cache(vc, fmt, t_cap), ck, cv, 0.09, fmt, T, t_cap,
+               seq_lens=lens, split=split)
+    _check(out, ref)

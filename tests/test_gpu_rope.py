@@ -257,3 +257,52 @@ def test_rope_step_paged_equals_contiguous():
         for n in range(B):
             for i in range(n_tiles):
                 assert np.array_equal(pl[perm[n, i]], src[n, :, i])
+
+
+def _rope_sweep_cases():
+    rng = np.random.default_rng(24050391)
+    cases = []
+    for i in range(12):
+        c, b = ROPE_FORMATS[i % 3]
+        hkv = int(rng.choice([1, 2, 3, 8]))
+        qper = int(rng.choice([1, 2, 4]))
+        B = int(rng.integers(1, 4))
+        T = int(rng.choice([1, 2, 64, 127, 129, 500, 1337, 2049]))
+        tiles = -(-T // 64)
+        split_tiles = int(rng.integers(1, min(tiles, 128) + 1)) if rng.random() < 0.6 else 0
+        ragged = bool(rng.random() < 0.5)
+        step = bool(rng.random() < 0.5)
+        cases.append((i, c, b, hkv * qper, hkv, B, T, split_tiles * 64, ragged, step))
+    return cases
+
+
+@pytest.mark.parametrize("case", _rope_sweep_cases(), ids=lambda cs: "case%d-%dc%db-hq%d-hkv%d-B%d-T%d-split%d-%s-%s" % (
+    cs[:8] + ("ragged" if cs[8] else "full", "step" if cs[9] else "attn")))
+def test_rope_attention_and_step_sweep(case):
+    i, c, b, hq, hkv, B, T, split, ragged, step = case
+    fmt, q, kc, vc, ck, cv = _case(200 + i, c, b, hq, hkv, B, T)
+    t_cap = -(-T // 64) * 64
+    rope = cq.RopeTable(BASE, t_cap)
+    lens = np.random.default_rng(i).integers(1, T + 1, size=B).astype(np.int32) if ragged else None
+    kcache, vcache = codes_to_cache(kc, fmt, t_cap), codes_to_cache(vc, fmt, t_cap)
+    if step:
+        # the newest token of every sequence comes in as fp16 rows instead of cached codes
+        D = hkv * 128
+        xk1 = np.concatenate([synth.sample_activations(synth.tensor_recipe(300 + i, 0, "k", D), 1, chunk=n) for n in range(B)])
+        xv1 = np.concatenate([synth.sample_activations(synth.tensor_recipe(300 + i, 0, "v", D), 1, chunk=n) for n in range(B)])
+        sl = None if lens is None else dev(lens)
+        out = cq.cq_decode_step_rope(dev(q), dev(xk1), dev(xv1), kcache, vcache, dev(ck), dev(cv), 0.09, fmt, T, t_cap, rope,
+                                     seq_lens=sl, tokens_per_split=split)
+        torch.cuda.synchronize()
+        from gpu_util import cache_to_codes
+        kc, vc = cache_to_codes(kcache, fmt, B, t_cap, T), cache_to_codes(vcache, fmt, B, t_cap, T)
+        out = out.cpu().numpy()
+        for n in range(B):
+            p = (T if lens is None else int(lens[n])) - 1
+            for codes, x1, cb in ((kc, xk1, ck), (vc, xv1, cv)):
+                want, d1, d2 = O.encode(x1[n:n + 1], cb, with_distances=True)
+                assert not ((codes[n, p:p + 1] != want) & ~((d2 - d1) < 1e-6 * d2)).any()
+    else:
+        out = _gpu(q, kcache, vcache, ck, cv, 0.09, fmt, T, t_cap, rope, seq_lens=lens, split=split)
+    ref = O.attention(q, kc, vc, ck, cv, 0.09, hkv, seq_lens=lens, rope_base=BASE)
+    check_attention(out, ref)
