@@ -321,3 +321,28 @@ def test_subbyte_formats_sizes_and_argument_checks_without_launching():
     assert lib.cq_fused_format(ctypes.byref(bad), ctypes.byref(f8)) == cq.CQ_ERR_UNSUPPORTED
     # the decode side refuses the sub-byte format itself
     assert _decode(cq.CQFormat(2, 4, 128, 4)) == cq.CQ_ERR_UNSUPPORTED
+
+
+def test_default_split_is_balanced_within_the_on_chip_limits_and_fills_the_chip():
+    import numpy as np
+    rng = np.random.default_rng(11)
+    limit = {(8, 8): 12288, (4, 8): 8192, (2, 8): 16384, (8, 10): 24448}
+    for _ in range(300):
+        c, b = [(8, 8), (4, 8), (2, 8), (8, 10)][int(rng.integers(0, 4))]
+        hkv = int(rng.choice([1, 2, 8, 32]))
+        hq = hkv * int(rng.choice([1, 4]))
+        B = int(rng.choice([1, 2, 16, 64]))
+        T = int(rng.integers(1, 200000))
+        fmt = cq.CQFormat(c, b, 128, hkv)
+        split = cq.cq_decode_default_split(fmt, B, hq, T)
+        assert split > 0 and split % 64 == 0 and split <= limit[(c, b)]
+        tiles, n_tiles = split // 64, -(-T // 64)
+        n_split = -(-n_tiles // tiles)
+        assert tiles == -(-n_tiles // n_split)                     # equal splits: no short last one beyond rounding
+        assert n_split == 1 or tiles >= 16 or n_tiles < 32         # never shorter than 16 tiles by choice
+        assert cq.cq_decode_workspace_bytes(fmt, B, hq, T) == 4 * B * hq * n_split * 130
+    # the named workloads
+    assert cq.cq_decode_default_split(cq.CQFormat(4, 8, 128, 32), 16, 32, 4096) == 4096        # one split, no merge
+    assert cq.cq_decode_default_split(cq.CQFormat(8, 8, 128, 32), 4, 32, 131072) == 10944      # 12 x 171 tiles: 3 rounds of 512
+    assert cq.cq_decode_default_split(cq.CQFormat(8, 10, 128, 8), 32, 32, 16384) == 16384
+    assert cq.cq_decode_default_split(cq.CQFormat(8, 8, 128, 32), 1, 32, 131072) == 8192       # 16 splits fill the chip once
