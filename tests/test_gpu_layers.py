@@ -92,3 +92,12 @@ def test_layer_table_refuses_shared_caches_and_bad_pointers():
     with pytest.raises(cq.CQError):          # workspace too small
         table = cq.LayerTable(layers, fmt, 64)
         cq.cq_decode_step_layers(table, 0.1, 10, workspace=torch.empty(64, dtype=torch.uint8, device="cuda"))
+
+
+def test_layered_step_with_splits_beyond_8192_tokens():
+    # CQ-8c8b with one 12288-token split per (sequence, head): the table form without replicas, layered
+    c, b, hq, hkv, B, T, t_cap = 8, 8, 2, 1, 1, 12250, 12288
+    fmt, layers = _layers(65, c, b, hq, hkv, B, T, t_cap, 2)
+    _compare(fmt, layers, T, t_cap, 0.1, split=12288)
+    fmt, layers = _layers(66, c, b, hq, hkv, B, T, t_cap, 2)
+    _compare(fmt, layers, T, t_cap, 0.1, split=10944)
