@@ -399,7 +399,8 @@ cq_status decode_common(const void* q, const void* x_k_new, const void* x_v_new,
     cq_status st = derive(fmt, &f);
     if (st != CQ_OK) return st;
     const bool rope = rope_positions != 0;
-    if (rope && (f.b != 8 || f.head_dim != 128)) return CQ_ERR_UNSUPPORTED;
+    // (the fused step keeps the key centroids in LDS: 256 centroids per group only)
+    if (rope && (f.head_dim != 128 || (f.b != 8 && step))) return CQ_ERR_UNSUPPORTED;
     CacheMap map;
     if (pages) {
         if ((st = paged_map(f, pages, batch, &map, &t_cap)) != CQ_OK) return st;
@@ -699,7 +700,7 @@ cq_status cq_rope_table(double base, int32_t head_dim, int32_t positions, void* 
 int32_t cq_decode_rope_default_split(const cq_format* fmt, int32_t batch, int32_t n_q_heads, int32_t t)
 {
     Derived f;
-    if (derive(fmt, &f) != CQ_OK || f.b != 8 || f.head_dim != 128 || batch <= 0 || n_q_heads <= 0 || t <= 0) return 0;
+    if (derive(fmt, &f) != CQ_OK || f.head_dim != 128 || batch <= 0 || n_q_heads <= 0 || t <= 0) return 0;
     return default_tiles_per_split(f, batch, n_q_heads, t, std::min(decode_rope_max_tiles_per_split(), decode_max_tiles_per_split(f))) * kTileTokens;
 }
 

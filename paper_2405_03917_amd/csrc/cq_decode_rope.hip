@@ -73,6 +73,14 @@ __device__ __forceinline__ CenVec<C> lds_centroid(unsigned byte_addr)
     }
     return v;
 }
+template <int C>
+__device__ __forceinline__ CenVec<C> global_centroid(const uint16_t* p)
+{
+    CenVec<C> v;
+#pragma unroll
+    for (int i = 0; i < C / 2; ++i) v.w[i] = reinterpret_cast<const unsigned*>(p)[i];
+    return v;
+}
 __device__ __forceinline__ float2 lds_load2(unsigned byte_addr)
 {
     typedef float f2 __attribute__((ext_vector_type(2)));
@@ -89,8 +97,8 @@ struct Unrotate {
     unsigned bytes;             // (Gh - u) mod 4
     unsigned dwords;            // ((Gh - u) mod Gh) / 4
 };
-template <int GH>
-__device__ __forceinline__ void group_order(const Tile<GH, 8>& w, const Unrotate& r, unsigned (&d)[GH / 4])
+template <int GH, int B>
+__device__ __forceinline__ void group_order(const Tile<GH, B>& w, const Unrotate& r, unsigned (&d)[GH / 4])
 {
     constexpr int N = GH / 4;
     unsigned x[N];
@@ -118,10 +126,12 @@ __device__ __forceinline__ void group_order(const Tile<GH, 8>& w, const Unrotate
 // pre-rotation keys) against the centroids it has just brought into LDS, patches the tile that
 // holds the position in registers, and finds the value codes in the epilogue.  Same results as
 // cq_encode_kv followed by the attention call, bit for bit.
-template <int GH, int C, int NT, bool STEP>
+// B = 10 (1024 centroids per group: 256 KB of key centroids per head) reads the centroids from
+// global memory (L2) instead of LDS; attention only.
+template <int GH, int C, int NT, bool STEP, int B>
 __global__ __launch_bounds__(NT) void decode_rope_kernel(DecodeArgs a, const float2* tile_tab, const float2* lane_tab)
 {
-    constexpr int B = 8;
+    static_assert(B == 8 || !STEP, "the fused step needs the key centroids in LDS");
     using F = Fmt<GH, B>;
     constexpr int K = F::K, RW = F::RW, R = F::R;
     constexpr int NW = NT / 64;
@@ -207,8 +217,10 @@ __global__ __launch_bounds__(NT) void decode_rope_kernel(DecodeArgs a, const flo
 
     // ---- 1. the head's key centroids and the lane table go to LDS; this lane's query pair ----
     {
-        const uint4* src = reinterpret_cast<const uint4*>(a.k_centroids + (size_t)hkv * GH * K * C);
-        for (int i = tid; i < (int)(kTabBytes / 16); i += NT) reinterpret_cast<uint4*>(smem)[i] = src[i];
+        if constexpr (B == 8) {
+            const uint4* src = reinterpret_cast<const uint4*>(a.k_centroids + (size_t)hkv * GH * K * C);
+            for (int i = tid; i < (int)(kTabBytes / 16); i += NT) reinterpret_cast<uint4*>(smem)[i] = src[i];
+        }
         const uint4* lt = reinterpret_cast<const uint4*>(lane_tab);
         for (int i = tid; i < (int)(kTrgBytes / 16); i += NT) reinterpret_cast<uint4*>(smem + kTabBytes / 4)[i] = lt[i];
     }
@@ -255,6 +267,7 @@ __global__ __launch_bounds__(NT) void decode_rope_kernel(DecodeArgs a, const flo
 
     // ---- 2. phase K: scores ----------------------------------------------------------------
     const unsigned trg_lane = kTabBytes + (unsigned)lane * 8;
+    const uint16_t* k_head = a.k_centroids + (size_t)hkv * GH * K * C;
     Unrotate unrot;
     unrot.bytes = (unsigned)(GH - lane) & 3u;
     unrot.dwords = ((unsigned)(GH - lane) & (unsigned)(GH - 1)) >> 2;
@@ -269,7 +282,9 @@ __global__ __launch_bounds__(NT) void decode_rope_kernel(DecodeArgs a, const flo
         const float qa0 = __builtin_fmaf(qa, cs.x, qb * cs.y), qb0 = __builtin_fmaf(qb, cs.x, -(qa * cs.y));
         // codes in group order: byte g of d[] is the code of group g
         unsigned d[GH / 4];
-        group_order<GH>(w, unrot, d);
+        group_order<GH, B>(w, unrot, d);
+        // b = 10: the high bits of group g sit at bits [2 g + 1 : 2 g] once the word is rotated like the bytes
+        const unsigned hi_rot = B == 10 ? __builtin_amdgcn_alignbit(w.hi, w.hi, 2u * (((unsigned)(GH - lane)) & (unsigned)(GH - 1))) : 0u;
         // the table base is re-materialised per tile: were it a loop invariant, the compiler
         // would keep base + offset of every channel pair in a register of its own (64 of them)
         // instead of using the offset field of the LDS instructions
@@ -278,10 +293,18 @@ __global__ __launch_bounds__(NT) void decode_rope_kernel(DecodeArgs a, const flo
         float acc0 = 0.f, acc1 = 0.f;
 #pragma unroll
         for (int g = 0; g < HALF; ++g) {
-            const unsigned c_first = (d[g >> 2] >> (8 * (g & 3))) & 0xffu;                       // channels < 64
-            const unsigned c_second = (d[(g + HALF) >> 2] >> (8 * ((g + HALF) & 3))) & 0xffu;    // their partners
-            const CenVec<C> ka = lds_centroid<C>(c_first * (C * 2) + (unsigned)(g * K * C * 2));
-            const CenVec<C> kb = lds_centroid<C>(c_second * (C * 2) + (unsigned)((g + HALF) * K * C * 2));
+            unsigned c_first = (d[g >> 2] >> (8 * (g & 3))) & 0xffu;                       // channels < 64
+            unsigned c_second = (d[(g + HALF) >> 2] >> (8 * ((g + HALF) & 3))) & 0xffu;    // their partners
+            CenVec<C> ka, kb;
+            if constexpr (B == 8) {
+                ka = lds_centroid<C>(c_first * (C * 2) + (unsigned)(g * K * C * 2));
+                kb = lds_centroid<C>(c_second * (C * 2) + (unsigned)((g + HALF) * K * C * 2));
+            } else {
+                c_first |= ((hi_rot >> (2 * g)) & 3u) << 8;
+                c_second |= ((hi_rot >> (2 * (g + HALF))) & 3u) << 8;
+                ka = global_centroid<C>(k_head + ((size_t)g * K + c_first) * C);
+                kb = global_centroid<C>(k_head + ((size_t)(g + HALF) * K + c_second) * C);
+            }
 #pragma unroll
             for (int j = 0; j < C; ++j) {
                 const int i = g * C + j;                                    // channel pair (i, i + 64)
@@ -460,11 +483,11 @@ __global__ __launch_bounds__(NT) void decode_rope_kernel(DecodeArgs a, const flo
     }
 }
 
-template <int GH, int C, bool STEP>
+template <int GH, int C, bool STEP, int B = 8>
 cq_status launch_rope_variant(const DecodeArgs& a, const float2* tile_tab, const float2* lane_tab, hipStream_t stream)
 {
     constexpr int NT = 1024;
-    auto kernel = decode_rope_kernel<GH, C, NT, STEP>;
+    auto kernel = decode_rope_kernel<GH, C, NT, STEP, B>;
     static std::once_flag once;
     static hipError_t setup = hipSuccess;
     std::call_once(once, [&] {
@@ -514,6 +537,8 @@ cq_status launch_decode_rope(const DecodeArgs& a, const float* tables, int t_cap
         else if (a.f.gh == 64 && a.f.c == 2)
             st = step ? launch_rope_variant<64, 2, true>(a, tile_tab, lane_tab, stream) : launch_rope_variant<64, 2, false>(a, tile_tab, lane_tab, stream);
     }
+    if (a.f.b == 10 && a.f.head_dim == 128 && a.f.gh == 16 && a.f.c == 8 && a.xk_new == nullptr)
+        st = launch_rope_variant<16, 8, false, 10>(a, tile_tab, lane_tab, stream);
     if (st != CQ_OK) return st;
     if (a.n_split > 1)
         return launch_decode_merge(a.partials, a.out, a.batch * a.n_q_heads, a.n_split, a.f.head_dim, stream);

@@ -17,6 +17,7 @@ from gpu_util import check_attention, codes_to_cache, dev, gpu_attention
 pytestmark = pytest.mark.gpu
 
 ROPE_FORMATS = [(8, 8), (4, 8), (2, 8)]
+ATTN_FORMATS = ROPE_FORMATS + [(8, 10)]         # the 1024-centroid format: attention only (centroids read from L2)
 BASE = 10000.0
 
 
@@ -56,7 +57,7 @@ def test_rope_table_holds_cos_and_sin_of_tile_bases_and_lane_offsets():
     assert np.max(np.abs(tab[:, 1] - np.sin(want))) <= 2.0 ** -24
 
 
-@pytest.mark.parametrize("c,b", ROPE_FORMATS)
+@pytest.mark.parametrize("c,b", ATTN_FORMATS)
 @pytest.mark.parametrize("T", [1, 63, 64, 65, 1000])
 def test_rope_attention_matches_oracle(c, b, T):
     hq, hkv, B, t_cap = 4, 2, 2, 1024
@@ -73,7 +74,7 @@ def test_rope_attention_matches_oracle(c, b, T):
         assert np.max(np.abs(plain - ref)) > 1e-2 * np.max(np.abs(ref))
 
 
-@pytest.mark.parametrize("c,b", ROPE_FORMATS)
+@pytest.mark.parametrize("c,b", ATTN_FORMATS)
 def test_rope_split_invariance_and_ragged_lengths(c, b):
     hq, hkv, B, T, t_cap = 4, 4, 3, 5000, 5056
     fmt, q, kc, vc, ck, cv = _case(7, c, b, hq, hkv, B, T)
@@ -154,12 +155,14 @@ def test_rope_paged_equals_contiguous_bit_for_bit():
     assert np.array_equal(got.cpu().numpy().view(np.uint16), want.view(np.uint16))
 
 
-def test_rope_rejects_the_1024_centroid_format():
+def test_rope_fused_step_rejects_the_1024_centroid_format():
+    # the fused step searches the key centroids in LDS: 256 per group only
     fmt, q, kc, vc, ck, cv = _case(2, 8, 10, 2, 2, 1, 64)
     rope = cq.RopeTable(BASE, 64)
+    x = torch.zeros((1, 256), dtype=torch.float16, device="cuda")
     with pytest.raises(cq.CQError):
-        cq.cq_decode_attention_rope(dev(q), codes_to_cache(kc, fmt, 64), codes_to_cache(vc, fmt, 64), dev(ck), dev(cv),
-                                    0.1, fmt, 64, 64, rope)
+        cq.cq_decode_step_rope(dev(q), x, x.clone(), codes_to_cache(kc, fmt, 64), codes_to_cache(vc, fmt, 64), dev(ck), dev(cv),
+                               0.1, fmt, 64, 64, rope)
 
 
 # ------------------------------------------------------------------------------------------
