@@ -93,6 +93,11 @@ __global__ __launch_bounds__(NT, 4) void decode_split_kernel(DecodeArgs a)
     unsigned long long* keys = reinterpret_cast<unsigned long long*>(
         smem + F::TAB_FLOATS + (F::SCORES_IN_TABLE ? kScratchFloats(NT, D) : max(kMinScoreFloats, a.tiles_per_split * kTileTokens)));
 
+    // the wavefronts' (maximum, sum) pairs of phase K: in the reduction scratch, or (b = 10) behind
+    // everything else; 64 groups per head have no LDS to spare (table + 4096 scores fill half a CU)
+    constexpr bool SLOTS_BEHIND = F::SCORES_IN_TABLE || B == 10;
+    float* slot_area = F::SCORES_IN_TABLE ? scr : reinterpret_cast<float*>(keys) + (STEP ? kKeyFloats(GH) : 0);
+
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -273,7 +278,10 @@ __global__ __launch_bounds__(NT, 4) void decode_split_kernel(DecodeArgs a)
         store_new_codes<GH, B>(const_cast<uint8_t*>(k_codes) + a.map.tile_index(n, hkv, tile_new) * F::TILE_BYTES, keys, u_new, tid);
 
     // ---- 2. phase K: scores --------------------------------------------------------------
-    float lane_max = -INFINITY;
+    // Every lane also keeps the maximum m of its scores and l = sum 2^(s - m) over them (the
+    // usual running pair), so that the split's maximum and the estimate of its l that places the
+    // fixed point of phase V are known as soon as the wavefronts have exchanged one pair each.
+    float lane_m = -1e30f, lane_l = 0.f;        // (finite start: a lane without valid tokens stays at l = 0)
     st.run(kwalk, my_tiles, lane, [&](const Tile<GH, B>& w_in, int k) {
         const int lt = wave + k * NW;                       // tile within the split
         Tile<GH, B> w = w_in;
@@ -287,33 +295,39 @@ __global__ __launch_bounds__(NT, 4) void decode_split_kernel(DecodeArgs a)
         const int tok = (tile0 + lt) * kTileTokens + lane;
         const float sv = tok < t_n ? acc0 + acc1 : -INFINITY;
         sc[sidx(lt * kTileTokens + lane)] = sv;
-        lane_max = fmaxf(lane_max, sv);
+        const float m_new = fmaxf(lane_m, sv);
+        lane_l = __builtin_fmaf(lane_l, __builtin_amdgcn_exp2f(lane_m - m_new), __builtin_amdgcn_exp2f(sv - m_new));
+        lane_m = m_new;
     }, [] {});
     st.begin(vwalk, my_tiles, lane);         // value codes are on their way
 
-    lane_max = wave_max(lane_max);
-    lds_barrier();                                // all table reads done, all scores written
-    // the table is dead: the first 2 NW words of its first row (table columns, never scores)
-    // carry the wavefronts' maxima and sums
-    static_assert(!F::SCORES_IN_TABLE || 2 * NW <= F::LUT_WORDS, "the reduction slots must not touch the scores");
-    if (lane == 0) tab[wave] = lane_max;
-    lds_barrier();
-    float m = tab[0];
+    {
+        const float wave_m = wave_max(lane_m);
+        const float wave_l = wave_sum(lane_l * __builtin_amdgcn_exp2f(lane_m - wave_m));
+        // Where the wavefronts' pairs go.  Formats with spare LDS behind the table exchange them
+        // there, across the barrier that ends the table reads; the others have to wait for that
+        // barrier and use the first row of the (then dead) table.
+        float* slots = SLOTS_BEHIND ? slot_area : tab;
+        if constexpr (!SLOTS_BEHIND) lds_barrier();
+        if (lane == 0) {
+            slots[wave] = wave_m;
+            slots[NW + wave] = wave_l;
+        }
+    }
+    lds_barrier();                                // all table reads done, all scores written, all pairs visible
+    float m, l_est = 0.f;
+    {
+        const float* slots = SLOTS_BEHIND ? slot_area : tab;
+        m = slots[0];
 #pragma unroll
-    for (int w = 1; w < NW; ++w) m = fmaxf(m, tab[w]);
-    // (every split that reaches this point holds at least one valid token, so m is finite)
-    // estimate l = sum_t 2^(s_t - m) to place the fixed point of phase V
-    float l_est = 0.f;
-    for (int i = tid; i < (tile1 - tile0) * kTileTokens; i += NT) l_est += __builtin_amdgcn_exp2f(sc[sidx(i)] - m);
-    l_est = wave_sum(l_est);
-    if (lane == 0) tab[NW + wave] = l_est;
-    lds_barrier();
-    l_est = 0.f;
+        for (int w = 1; w < NW; ++w) m = fmaxf(m, slots[w]);
+        // (every split that reaches this point holds at least one valid token, so m is a score)
 #pragma unroll
-    for (int w = 0; w < NW; ++w) l_est += tab[NW + w];
+        for (int w = 0; w < NW; ++w) l_est = __builtin_fmaf(slots[NW + w], __builtin_amdgcn_exp2f(slots[w] - m), l_est);
+    }
     const int fx = fixed_point_exponent(l_est);
     const float fx_scale = ldexpf(1.f, fx), fx_inv = ldexpf(1.f, -fx);
-    lds_barrier();                                // everyone holds m and fx before the table is cleared
+    if constexpr (!SLOTS_BEHIND) lds_barrier();   // everyone holds m and fx before the table is cleared
     {
         float4* t4 = reinterpret_cast<float4*>(tab);
         if constexpr (F::SCORES_IN_TABLE) {         // clear the table columns of every row, keep the scores
@@ -508,9 +522,10 @@ size_t smem_bytes(int tiles_per_split, int head_dim, bool step)
     using F = Fmt<GH, B, LONG>;
     const int key_floats = step ? kKeyFloats(GH) : 0;
     if (F::SCORES_IN_TABLE) return sizeof(float) * (size_t)(F::TAB_FLOATS + kScratchFloats(NT, head_dim) + key_floats);
-    // behind the table: the score buffer (reused as scratch once the scores are dead), then the keys
+    // behind the table: the score buffer (reused as scratch once the scores are dead), then the
+    // keys, then (b = 10) the wavefronts' reduction slots
     const int sc_floats = std::max(kMinScoreFloats, tiles_per_split * kTileTokens);
-    return sizeof(float) * (size_t)(F::TAB_FLOATS + sc_floats + key_floats);
+    return sizeof(float) * (size_t)(F::TAB_FLOATS + sc_floats + key_floats + (B == 10 ? kSlotFloats : 0));
 }
 
 template <int GH, int C, int B, int NT, bool STEP, bool LAYERS, bool LONG = false>
@@ -582,7 +597,7 @@ cq_status launch_decode_merge(const float* partials, uint16_t* out, int rows, in
 
 int decode_max_tiles_per_split(const Derived& f)
 {
-    if (f.b == 10) return (160 * 1024 / 4 - Fmt<16, 10>::TAB_FLOATS - kKeyFloats(16)) / kTileTokens;   // 382: 160 KB of LDS
+    if (f.b == 10) return (160 * 1024 / 4 - Fmt<16, 10>::TAB_FLOATS - kKeyFloats(16) - kSlotFloats) / kTileTokens;   // 382: 160 KB of LDS
     if (f.gh == 16) return 256 * Fmt<16, 8, true>::SCORE_WORDS / kTileTokens;         // 192: scores inside the table, no replicas
     if (f.gh == 32) return 256 * Fmt<32, 8>::SCORE_WORDS / kTileTokens;               // 128
     return 256;

@@ -19,6 +19,8 @@ typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
 constexpr int kMinScoreFloats = 4096;         // the score buffer doubles as reduction scratch
 // fused step: 2 x Gh 64-bit (distance, index) minima, then the new token's fixed-point weight
 constexpr int kKeyFloats(int gh) { return 2 * 2 * gh + 2; }
+// one (maximum, sum) pair per wavefront, up to 16 wavefronts
+constexpr int kSlotFloats = 32;
 // reduction scratch: 64 words + one row of head_dim floats per wavefront
 constexpr int kScratchFloats(int nt, int head_dim) { return 64 + (nt / 64) * head_dim; }
 
