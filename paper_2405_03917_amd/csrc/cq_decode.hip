@@ -282,10 +282,15 @@ __global__ __launch_bounds__(NT, 4) void decode_split_kernel(DecodeArgs a)
     // usual running pair), so that the split's maximum and the estimate of its l that places the
     // fixed point of phase V are known as soon as the wavefronts have exchanged one pair each.
     float lane_m = -1e30f, lane_l = 0.f;        // (finite start: a lane without valid tokens stays at l = 0)
+    // fused step: the wavefront whose walk meets the new token's tile patches that tile in registers
+    // as if the codes just found were already in the cache
+    const bool meets_new = has_new && (tile_new - tile0) % NW == wave;
+    NewTokenCodes<GH, B> new_codes;
+    if (meets_new) new_codes.build(keys, u_new, lane);
     st.run(kwalk, my_tiles, lane, [&](const Tile<GH, B>& w_in, int k) {
         const int lt = wave + k * NW;                       // tile within the split
         Tile<GH, B> w = w_in;
-        if (has_new && tile0 + lt == tile_new) patch_new_token<GH, B>(w, keys, u_new, lane);
+        if (meets_new && tile0 + lt == tile_new) new_codes.patch(w, u_new, lane);
         float acc0 = 0.f, acc1 = 0.f;
 #pragma unroll
         for (int s = 0; s < GH; s += 2) {

@@ -256,33 +256,50 @@ __device__ __forceinline__ unsigned slot_addr(const Tile<GH, B>& w, const Column
     }
 }
 
-// Fused step: replace the codes of lane u_new's token in a tile's registers by the codes just
-// computed (keys[g] holds group g's (distance, index) minimum), exactly as the cache layout
-// would hold them: slot s of token u carries group (s + u) mod Gh.
+// Fused step: the codes of the new token as the cache layout would hold them (slot s of token u
+// carries group (s + u) mod Gh), from keys[g] = group g's (distance, index) minimum.  Called by
+// the one wavefront whose walk meets the token's tile, before its walk starts: lane i builds
+// word i of the record, and every lane receives all words (wave-uniform values).
 template <int GH, int B>
-__device__ __forceinline__ void patch_new_token(Tile<GH, B>& w, const unsigned long long* keys, int u_new, int lane)
-{
-    if (lane != u_new) return;
-    unsigned hi = 0;
-#pragma unroll
-    for (int pl = 0; pl < GH / 16; ++pl) {
-        unsigned word[4];
-#pragma unroll
-        for (int d = 0; d < 4; ++d) {
-            unsigned x = 0;
+struct NewTokenCodes {
+    unsigned lo[GH / 4];
+    unsigned hi;                        // b = 10 only
+    __device__ __forceinline__ void build(const unsigned long long* keys, int u_new, int lane)
+    {
+        unsigned x = 0, h = 0;
+        if (lane < GH / 4) {
 #pragma unroll
             for (int k = 0; k < 4; ++k) {
-                const int s = 16 * pl + 4 * d + k;
+                const int s = 4 * lane + k;
                 const unsigned code = (unsigned)(keys[(s + u_new) & (GH - 1)] & 0xffffffffu);
                 x |= (code & 0xffu) << (8 * k);
-                if constexpr (B == 10) hi |= (code >> 8) << (2 * s);
+                if constexpr (B == 10) h |= (code >> 8) << (2 * s);
             }
-            word[d] = x;
         }
-        w.lo[pl] = u32x4{word[0], word[1], word[2], word[3]};
+#pragma unroll
+        for (int i = 0; i < GH / 4; ++i) lo[i] = __builtin_amdgcn_readlane(x, i);
+        hi = 0;
+        if constexpr (B == 10) {
+#pragma unroll
+            for (int i = 0; i < GH / 4; ++i) hi |= __builtin_amdgcn_readlane(h, i);
+        }
     }
-    if constexpr (B == 10) w.hi = hi;
-}
+    // lane u_new's token of tile w becomes the new token
+    __device__ __forceinline__ void patch(Tile<GH, B>& w, int u_new, int lane) const
+    {
+        const bool mine = lane == u_new;
+#pragma unroll
+        for (int pl = 0; pl < GH / 16; ++pl) {
+            u32x4 q = w.lo[pl];
+            q.x = mine ? lo[4 * pl] : q.x;
+            q.y = mine ? lo[4 * pl + 1] : q.y;
+            q.z = mine ? lo[4 * pl + 2] : q.z;
+            q.w = mine ? lo[4 * pl + 3] : q.w;
+            w.lo[pl] = q;
+        }
+        if constexpr (B == 10) w.hi = mine ? hi : w.hi;
+    }
+};
 
 // Fused step: store the new token's codes of one KV head into its cache tile.
 template <int GH, int B>

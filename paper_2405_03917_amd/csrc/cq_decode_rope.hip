@@ -272,10 +272,14 @@ __global__ __launch_bounds__(NT) void decode_rope_kernel(DecodeArgs a, const flo
     unrot.bytes = (unsigned)(GH - lane) & 3u;
     unrot.dwords = ((unsigned)(GH - lane) & (unsigned)(GH - 1)) >> 2;
     float lane_max = -INFINITY;
+    // fused step: the wavefront whose walk meets the new token's tile patches that tile in registers
+    const bool meets_new = has_new && (tile_new - tile0) % NW == wave;
+    NewTokenCodes<GH, B> new_codes;
+    if (meets_new) new_codes.build(keys, u_new, lane);
     st.run(kwalk, my_tiles, lane, [&](const Tile<GH, B>& w_in, int k) {
         const int lt = wave + k * NW;
         Tile<GH, B> w = w_in;
-        if (has_new && tile0 + lt == tile_new) patch_new_token<GH, B>(w, keys, u_new, lane);
+        if (meets_new && tile0 + lt == tile_new) new_codes.patch(w, u_new, lane);
         // the query rotated to the tile's base position: lane i holds pair i
         const float2 cs = cs_next;
         cs_next = tile_cs(k + 1);
