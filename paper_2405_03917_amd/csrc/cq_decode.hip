@@ -383,11 +383,11 @@ __global__ __launch_bounds__(NT, 4) void decode_split_kernel(DecodeArgs a)
     // same walk as the table build; thread-private sums over its centroids of group gl in every
     // chunk, then lanes l, l+16, l+32, l+48 and the wavefronts are added up.
     lane_sum = wave_sum_u32(lane_sum);
-    lds_barrier();                                // all bin updates done; the scores are dead
-    if (lane == 0) scr[wave] = __uint_as_float(lane_sum);
 
     // fused step: encode the new value row against the value codebook (same walk, same registers
-    // as the sums below), add its weight to the bins of its codes, store the codes
+    // as the sums below).  A wavefront does this as soon as its own tiles are done, i.e. while it
+    // would otherwise wait at the barrier for the slowest one (the minima go to LDS words of
+    // their own).
     if (has_new) {
 #pragma unroll
         for (int ch = 0; ch < NCH; ++ch) {
@@ -418,7 +418,11 @@ __global__ __launch_bounds__(NT, 4) void decode_split_kernel(DecodeArgs a)
             const unsigned long long vkey = group_lanes_min(vnear.key());
             if (lane < 16) lds_min_u64(&keys[GH + ch * 16 + gl], vkey);
         }
-        lds_barrier();
+    }
+    lds_barrier();                                // all bin updates done; the scores are dead
+    if (lane == 0) scr[wave] = __uint_as_float(lane_sum);
+    // fused step: the new token's weight joins the bins of the codes just found; store the codes
+    if (has_new) {
         if (tid < GH) {
             const unsigned code = (unsigned)(keys[GH + tid] & 0xffffffffu);
             lds_add((code * RW + tid * R) * 4u, *pf_new);
