@@ -36,7 +36,7 @@ if ROOT not in sys.path:
 HBM_PEAK_GBPS = 8000.0          # MI355X published peak, GB/s
 # HBM bytes per launch of the fused decode-step kernel from rocprofv3 counters (FETCH_SIZE x 1.9998
 # + WRITE_SIZE, KiB per dispatch), see profiles/decode_step_kernel_cq4c8b_batch16_ctx4096.md
-TRAFFIC_BYTES_PER_LAUNCH = (67982.3 * 1.9998 + 192.0) * 1024
+TRAFFIC_BYTES_PER_LAUNCH = (67945.9 * 1.9998 + 192.0) * 1024
 METRIC = "decode-attn KV tokens/s & achieved HBM GB/s (% peak); cq_encode tokens/s"
 
 
