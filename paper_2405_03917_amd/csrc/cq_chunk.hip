@@ -18,8 +18,6 @@
 // HBM traffic is the codes, read once per workgroup; the kernel is bound by the matrix cores and
 // the LDS reads that feed them.  Long contexts with few rows are split over workgroups and
 // merged by the decode path's merge kernel (same (m, l, o) partials).
-#include <mutex>
-
 #include "cq_decode_common.hpp"
 
 namespace cq {
@@ -352,18 +350,8 @@ template <int GH, int C, int NW, int B>
 cq_status launch_chunk_variant(const ChunkArgs& a, hipStream_t stream)
 {
     auto kernel = chunk_attention_kernel<GH, C, NW, B>;
-    static std::once_flag once;
-    static hipError_t setup = hipSuccess;
-    std::call_once(once, [&] {
-        hipFuncAttributes attr;
-        setup = hipFuncGetAttributes(&attr, reinterpret_cast<const void*>(kernel));
-        // the tiles are addressed from LDS address 0: no static LDS may precede the dynamic block
-        if (setup == hipSuccess && attr.sharedSizeBytes != 0) setup = hipErrorInvalidValue;
-        if (setup == hipSuccess)
-            setup = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
-                                        hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-    });
-    if (setup != hipSuccess) return CQ_ERR_HIP;
+    static LdsKernelSetup setup;
+    if (setup.ensure(reinterpret_cast<const void*>(kernel)) != hipSuccess) return CQ_ERR_HIP;
     const int qper = a.n_q_heads / a.f.n_kv_heads;
     const int row_blocks = (a.m * qper + NW * 32 - 1) / (NW * 32);
     const unsigned grid = (unsigned)(a.batch * a.n_split * row_blocks * a.f.n_kv_heads);

@@ -29,8 +29,6 @@
 // ds_add_u32, which is why the bins are integers.
 #include <hip/hip_runtime.h>
 
-#include <mutex>
-
 #include "cq_decode_common.hpp"
 
 namespace cq {
@@ -541,18 +539,8 @@ template <int GH, int C, int B, int NT, bool STEP, bool LAYERS, bool LONG = fals
 cq_status launch_variant(const DecodeArgs& a, hipStream_t stream)
 {
     auto kernel = decode_split_kernel<GH, C, B, NT, STEP, LAYERS, LONG>;
-    static std::once_flag once;
-    static hipError_t setup = hipSuccess;
-    std::call_once(once, [&] {
-        hipFuncAttributes attr;
-        setup = hipFuncGetAttributes(&attr, reinterpret_cast<const void*>(kernel));
-        // the kernels address the table from LDS address 0: no static LDS may precede it
-        if (setup == hipSuccess && attr.sharedSizeBytes != 0) setup = hipErrorInvalidValue;
-        if (setup == hipSuccess)
-            setup = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
-                                        hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-    });
-    if (setup != hipSuccess) return CQ_ERR_HIP;
+    static LdsKernelSetup setup;
+    if (setup.ensure(reinterpret_cast<const void*>(kernel)) != hipSuccess) return CQ_ERR_HIP;
     const size_t smem = smem_bytes<GH, B, NT, LONG>(a.tiles_per_split, a.f.head_dim, STEP);
     if (smem > 160 * 1024) return CQ_ERR_INVALID_ARG;
     const unsigned grid = (unsigned)(a.batch * a.n_q_heads * a.n_split) * (unsigned)(a.layers ? a.n_layers : 1);

@@ -18,8 +18,6 @@
 // GROUP without rotation): phase K is bound by the vector ALU, not by HBM.  Phase V, the
 // epilogue and the split-context merge are those of cq_decode.hip.  Both trigonometric tables
 // come from cq_rope_table (computed in fp64).
-#include <mutex>
-
 #include "cq_decode_common.hpp"
 
 namespace cq {
@@ -492,18 +490,8 @@ cq_status launch_rope_variant(const DecodeArgs& a, const float2* tile_tab, const
 {
     constexpr int NT = 1024;
     auto kernel = decode_rope_kernel<GH, C, NT, STEP, B>;
-    static std::once_flag once;
-    static hipError_t setup = hipSuccess;
-    std::call_once(once, [&] {
-        hipFuncAttributes attr;
-        setup = hipFuncGetAttributes(&attr, reinterpret_cast<const void*>(kernel));
-        // LDS is addressed from 0: no static LDS may precede the dynamic block
-        if (setup == hipSuccess && attr.sharedSizeBytes != 0) setup = hipErrorInvalidValue;
-        if (setup == hipSuccess)
-            setup = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
-                                        hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-    });
-    if (setup != hipSuccess) return CQ_ERR_HIP;
+    static LdsKernelSetup setup;
+    if (setup.ensure(reinterpret_cast<const void*>(kernel)) != hipSuccess) return CQ_ERR_HIP;
     const size_t smem = kTabBytes + kTrgBytes + (size_t)a.tiles_per_split * kTileTokens * 4 + (STEP ? kKeyFloats(GH) * 4 : 0);
     if (smem > 160 * 1024) return CQ_ERR_INVALID_ARG;
     const unsigned grid = (unsigned)(a.batch * a.n_q_heads * a.n_split);

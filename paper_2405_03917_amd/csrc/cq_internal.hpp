@@ -5,6 +5,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <mutex>
+
 #include "libcq.h"
 
 namespace cq {
@@ -183,8 +185,9 @@ cq_status launch_encode_tiles(const EncodeArgs& a, hipStream_t stream);
 cq_status launch_decode(const DecodeArgs& a, hipStream_t stream);
 // centroids fp16 [G][2^b][c] of a sub-byte format -> fp16 [G / fuse][256][c fuse] of its fused format
 cq_status launch_expand_codebook(const uint16_t* centroids, const Derived& f, uint16_t* fused, hipStream_t stream);
-// merges the partials of `rows` (sequence, query head) pairs, n_split each, into fp16 rows
+// writes `count` records of a layer table (device memory) from values passed with the launch
 cq_status launch_layer_table_write(const LayerChunk& chunk, int count, LayerPtrs* dst, hipStream_t stream);
+// merges the partials of `rows` (sequence, query head) pairs, n_split each, into fp16 rows
 cq_status launch_decode_merge(const float* partials, uint16_t* out, int rows, int n_split, int head_dim, hipStream_t stream);
 
 // Keys cached before the rotary position embedding (cq_decode_rope.hip).  The table holds, for
@@ -194,5 +197,30 @@ size_t rope_table_floats(int positions);
 cq_status launch_rope_table(double base, int positions, float* table, hipStream_t stream);
 int decode_rope_max_tiles_per_split();
 cq_status launch_decode_rope(const DecodeArgs& a, const float* table, int positions, hipStream_t stream);
+
+// Kernels that address their dynamic LDS block from LDS address 0 and use more than 64 KB of it:
+// once per device (kernel attributes are kept per device) check that no static LDS precedes the
+// block and raise the kernel's dynamic LDS limit to the 160 KB of a gfx950 CU.  One object per
+// kernel instantiation (a function-local static of the launcher).
+struct LdsKernelSetup {
+    static constexpr int kMaxDevices = 64;
+    std::once_flag once[kMaxDevices];
+    hipError_t result[kMaxDevices];
+    hipError_t ensure(const void* kernel)
+    {
+        int dev = 0;
+        const hipError_t e = hipGetDevice(&dev);
+        if (e != hipSuccess) return e;
+        if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+        std::call_once(once[dev], [&] {
+            hipFuncAttributes attr;
+            hipError_t r = hipFuncGetAttributes(&attr, kernel);
+            if (r == hipSuccess && attr.sharedSizeBytes != 0) r = hipErrorInvalidValue;
+            if (r == hipSuccess) r = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+            result[dev] = r;
+        });
+        return result[dev];
+    }
+};
 
 }  // namespace cq
