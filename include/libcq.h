@@ -324,6 +324,12 @@ CQ_API cq_status cq_decode_step_paged(const void *q, const void *x_k_new, const 
  *   with (no positional rotation).
  * The contraction runs on the matrix cores in fp16 with fp32 accumulation: scores are exact
  * products summed in fp32; probabilities enter the value product as two fp16 numbers (22 bits).
+ * Short chunks with tokens_per_split = 0 (m <= 2; m <= 8 / (query heads per KV head) on large
+ * batches) are instead served token by token by the kernel of cq_decode_attention, m launches
+ * in stream order, which is faster there; the results are then bit-identical to m calls of
+ * cq_decode_attention with the contexts of the m tokens.  cq_chunk_default_split and
+ * cq_chunk_workspace_bytes describe whichever path the library takes; an explicit
+ * tokens_per_split always runs the matrix-core kernel.
  * Formats: those of cq_decode_attention (b = 8, 10 at head_dim 128).
  * Errors: as cq_decode_attention; CQ_ERR_INVALID_ARG also for m <= 0 or m > t.
  */

@@ -459,6 +459,9 @@ cq_status decode_common(const void* q, const void* x_k_new, const void* x_v_new,
     a.n_split = n_split;
     a.partials = static_cast<float*>(workspace);
     a.out = static_cast<uint16_t*>(out);
+    a.q_batch_stride = a.out_batch_stride = (int64_t)n_q_heads * f.head_dim;
+    a.seq_len_shift = 0;
+    a.seq_len_floor = 1;
     a.f = f;
     if (rope) return launch_decode_rope(a, static_cast<const float*>(rope_table), rope_positions, static_cast<hipStream_t>(stream));
     return launch_decode(a, static_cast<hipStream_t>(stream));
@@ -532,6 +535,35 @@ int chunk_tiles_per_split(const Derived& f, int batch, int n_q_heads, int m, int
     return (int)((n_tiles + n_split - 1) / n_split);
 }
 
+// Short chunks go through the single-token kernel, one launch per query token (token j with a
+// context shortened by m - 1 - j): the chunk kernel dequantises every tile of the context
+// whatever m is, which costs 8-16 single-token launches on large multi-head batches (measured;
+// divided by the query heads per KV head, which share the dequantised tiles) and 2-3 on small
+// ones (both kernels are then bound by launch and latency).
+bool chunk_by_token(const Derived& f, int batch, int n_q_heads, int m, int t)
+{
+    const int qper = n_q_heads / f.n_kv_heads;
+    const long tiles = (long)batch * f.n_kv_heads * ((t + kTileTokens - 1) / kTileTokens);
+    const int limit = tiles >= 16384 ? std::max(2, 8 / qper) : 2;
+    return m <= limit;
+}
+
+// split (tiles) and workspace need of query token j of a chunk served token by token
+struct TokenCall {
+    int t, tiles, n_split;
+    size_t workspace;
+};
+TokenCall chunk_token_call(const Derived& f, int batch, int n_q_heads, int m, int t, int j)
+{
+    TokenCall c;
+    c.t = t - (m - 1 - j);
+    c.tiles = default_tiles_per_split(f, batch, n_q_heads, c.t);
+    const int n_tiles = (c.t + kTileTokens - 1) / kTileTokens;
+    c.n_split = (n_tiles + c.tiles - 1) / c.tiles;
+    c.workspace = c.n_split > 1 ? sizeof(float) * (size_t)batch * n_q_heads * c.n_split * (f.head_dim + kPartialHeader) : 0;
+    return c;
+}
+
 cq_status chunk_common(const void* q, const void* k_codes, const void* v_codes,
                        const void* k_centroids, const void* v_centroids, float scale, const cq_format* fmt,
                        int32_t batch, int32_t n_q_heads, int32_t m, int32_t t, int32_t t_cap, const cq_page_table* pages,
@@ -557,6 +589,45 @@ cq_status chunk_common(const void* q, const void* k_codes, const void* v_codes,
     if (!aligned16(q) || !aligned16(k_codes) || !aligned16(v_codes) || !aligned16(k_centroids) ||
         !aligned16(v_centroids) || !aligned16(out) || !aligned16(workspace))
         return CQ_ERR_INVALID_ARG;
+    if (tokens_per_split == 0 && chunk_by_token(f, batch, n_q_heads, m, t)) {
+        for (int j = 0; j < m; ++j) {
+            const TokenCall c = chunk_token_call(f, batch, n_q_heads, m, t, j);
+            if (c.workspace && !workspace) return CQ_ERR_INVALID_ARG;
+            if (workspace_bytes < c.workspace) return CQ_ERR_WORKSPACE_TOO_SMALL;
+            if ((int64_t)batch * n_q_heads * c.n_split > 0x7fffffffLL) return CQ_ERR_INVALID_ARG;
+        }
+        const int64_t row = (int64_t)n_q_heads * f.head_dim;
+        for (int j = 0; j < m; ++j) {           // (in stream order: the calls share the workspace)
+            const TokenCall c = chunk_token_call(f, batch, n_q_heads, m, t, j);
+            DecodeArgs a;
+            a.layers = nullptr;
+            a.n_layers = 1;
+            a.wgs_per_layer = batch * n_q_heads * c.n_split;
+            a.q = static_cast<const uint16_t*>(q) + j * row;
+            a.out = static_cast<uint16_t*>(out) + j * row;
+            a.q_batch_stride = a.out_batch_stride = m * row;
+            a.k_codes = static_cast<const uint8_t*>(k_codes);
+            a.v_codes = static_cast<const uint8_t*>(v_codes);
+            a.k_centroids = static_cast<const uint16_t*>(k_centroids);
+            a.v_centroids = static_cast<const uint16_t*>(v_centroids);
+            a.scale_log2e = scale * 1.4426950408889634f;
+            a.batch = batch;
+            a.n_q_heads = n_q_heads;
+            a.t = c.t;
+            a.map = map;
+            a.seq_lens = seq_lens;
+            a.seq_len_shift = m - 1 - j;        // token j of sequence n sees max(seq_lens[n], m) - (m - 1 - j) tokens
+            a.seq_len_floor = j + 1;
+            a.xk_new = a.xv_new = nullptr;
+            a.x_new_stride = 0;
+            a.tiles_per_split = c.tiles;
+            a.n_split = c.n_split;
+            a.partials = static_cast<float*>(workspace);
+            a.f = f;
+            if ((st = launch_decode(a, static_cast<hipStream_t>(stream))) != CQ_OK) return st;
+        }
+        return CQ_OK;
+    }
     const int tiles = tokens_per_split ? tokens_per_split / kTileTokens : chunk_tiles_per_split(f, batch, n_q_heads, m, t);
     const int n_tiles = (t + kTileTokens - 1) / kTileTokens;
     const int n_split = (n_tiles + tiles - 1) / tiles;
@@ -598,6 +669,7 @@ int32_t cq_chunk_default_split(const cq_format* fmt, int32_t batch, int32_t n_q_
     Derived f;
     if (derive(fmt, &f) != CQ_OK || f.head_dim != 128) return 0;
     if (batch <= 0 || n_q_heads <= 0 || n_q_heads % f.n_kv_heads != 0 || m <= 0 || t < m) return 0;
+    if (chunk_by_token(f, batch, n_q_heads, m, t)) return chunk_token_call(f, batch, n_q_heads, m, t, m - 1).tiles * kTileTokens;
     return chunk_tiles_per_split(f, batch, n_q_heads, m, t) * kTileTokens;
 }
 
@@ -608,6 +680,11 @@ size_t cq_chunk_workspace_bytes(const cq_format* fmt, int32_t batch, int32_t n_q
     if (derive(fmt, &f) != CQ_OK || f.head_dim != 128) return 0;
     if (batch <= 0 || n_q_heads <= 0 || n_q_heads % f.n_kv_heads != 0 || m <= 0 || t < m) return 0;
     if (tokens_per_split < 0 || tokens_per_split % kTileTokens != 0) return 0;
+    if (tokens_per_split == 0 && chunk_by_token(f, batch, n_q_heads, m, t)) {
+        size_t need = 0;
+        for (int j = 0; j < m; ++j) need = std::max(need, chunk_token_call(f, batch, n_q_heads, m, t, j).workspace);
+        return need;
+    }
     const int tiles = tokens_per_split ? tokens_per_split / kTileTokens : chunk_tiles_per_split(f, batch, n_q_heads, m, t);
     const int n_tiles = (t + kTileTokens - 1) / kTileTokens;
     const int n_split = (n_tiles + tiles - 1) / tiles;

@@ -151,7 +151,7 @@ __global__ __launch_bounds__(NT, 4) void decode_split_kernel(DecodeArgs a)
     const int hkv = hq / qper;
 
     int t_n = a.t;
-    if (a.seq_lens) t_n = min(max(a.seq_lens[n], 1), a.t);
+    if (a.seq_lens) t_n = min(max(a.seq_lens[n] - a.seq_len_shift, a.seq_len_floor), a.t);
     const int n_tiles = (t_n + kTileTokens - 1) / kTileTokens;
     const int tile0 = split * a.tiles_per_split;
     const int tile1 = min(tile0 + a.tiles_per_split, n_tiles);
@@ -204,7 +204,7 @@ __global__ __launch_bounds__(NT, 4) void decode_split_kernel(DecodeArgs a)
     const int gl = tid & 15;
     unsigned xvw[STEP ? NCH : 1][C / 2];            // fused step: this thread's slices of the new value row
     {
-        const uint16_t* qh = q_ptr + (size_t)(n * a.n_q_heads + hq) * D;
+        const uint16_t* qh = q_ptr + (size_t)n * a.q_batch_stride + (size_t)hq * D;
 #pragma unroll
         for (int ch = 0; ch < NCH; ++ch) {
             const int g = ch * 16 + gl;
@@ -489,7 +489,7 @@ __global__ __launch_bounds__(NT, 4) void decode_split_kernel(DecodeArgs a)
         float o = 0.f;
 #pragma unroll
         for (int w = 0; w < NW; ++w) o += scr[64 + w * D + chn];
-        if (direct) out_ptr[(size_t)(n * a.n_q_heads + hq) * D + chn] = __builtin_bit_cast(uint16_t, (_Float16)(o / l));
+        if (direct) out_ptr[(size_t)n * a.out_batch_stride + (size_t)hq * D + chn] = __builtin_bit_cast(uint16_t, (_Float16)(o / l));
         else part[kPartialHeader + chn] = o;
     }
 }
@@ -497,7 +497,7 @@ __global__ __launch_bounds__(NT, 4) void decode_split_kernel(DecodeArgs a)
 // Merge the partials of all splits of one (sequence, query head): exact rescaling by the
 // overall maximum, then one rounding to fp16.
 __global__ void decode_merge_kernel(const float* partials, uint16_t* out, int n_split, int head_dim,
-                                    const LayerPtrs* layers, int rows_per_layer)
+                                    const LayerPtrs* layers, int rows_per_layer, int n_q_heads, int64_t out_batch_stride)
 {
     int bh = blockIdx.x;
     const int stride = head_dim + kPartialHeader;
@@ -507,6 +507,7 @@ __global__ void decode_merge_kernel(const float* partials, uint16_t* out, int n_
         bh -= layer * rows_per_layer;
         out = layers[layer].out;
     }
+    out += (size_t)(bh / n_q_heads) * out_batch_stride + (size_t)(bh % n_q_heads) * head_dim;
     float m = -INFINITY;
     for (int s = 0; s < n_split; ++s) m = fmaxf(m, p[s * stride]);
     for (int i = threadIdx.x; i < head_dim; i += blockDim.x) {
@@ -519,7 +520,7 @@ __global__ void decode_merge_kernel(const float* partials, uint16_t* out, int n_
             o = __builtin_fmaf(p[s * stride + kPartialHeader + i], w, o);
         }
         const _Float16 h = (_Float16)(o / l);
-        out[(size_t)bh * head_dim + i] = __builtin_bit_cast(uint16_t, h);
+        out[i] = __builtin_bit_cast(uint16_t, h);
     }
 }
 
@@ -585,10 +586,10 @@ cq_status launch_layer_table_write(const LayerChunk& chunk, int count, LayerPtrs
     return hipGetLastError() == hipSuccess ? CQ_OK : CQ_ERR_HIP;
 }
 
-cq_status launch_decode_merge(const float* partials, uint16_t* out, int rows, int n_split, int head_dim, hipStream_t stream)
+cq_status launch_decode_merge(const float* partials, uint16_t* out, int rows, int n_q_heads, int n_split, int head_dim, hipStream_t stream)
 {
     hipLaunchKernelGGL(decode_merge_kernel, dim3((unsigned)rows), dim3(128), 0, stream, partials, out, n_split, head_dim,
-                       static_cast<const LayerPtrs*>(nullptr), 0);
+                       static_cast<const LayerPtrs*>(nullptr), 0, n_q_heads, (int64_t)n_q_heads * head_dim);
     return hipGetLastError() == hipSuccess ? CQ_OK : CQ_ERR_HIP;
 }
 
@@ -609,7 +610,7 @@ cq_status launch_decode(const DecodeArgs& a, hipStream_t stream)
     const int threads = a.f.head_dim <= 64 ? 64 : (a.f.head_dim <= 128 ? 128 : 256);
     const int rows = a.batch * a.n_q_heads;
     hipLaunchKernelGGL(decode_merge_kernel, dim3((unsigned)(rows * (a.layers ? a.n_layers : 1))), dim3(threads), 0, stream,
-                       a.partials, a.out, a.n_split, a.f.head_dim, a.layers, rows);
+                       a.partials, a.out, a.n_split, a.f.head_dim, a.layers, rows, a.n_q_heads, a.out_batch_stride);
     if (hipGetLastError() != hipSuccess) return CQ_ERR_HIP;
     return CQ_OK;
 }

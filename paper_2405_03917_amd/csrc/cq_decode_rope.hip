@@ -533,7 +533,7 @@ cq_status launch_decode_rope(const DecodeArgs& a, const float* tables, int t_cap
         st = launch_rope_variant<16, 8, false, 10>(a, tile_tab, lane_tab, stream);
     if (st != CQ_OK) return st;
     if (a.n_split > 1)
-        return launch_decode_merge(a.partials, a.out, a.batch * a.n_q_heads, a.n_split, a.f.head_dim, stream);
+        return launch_decode_merge(a.partials, a.out, a.batch * a.n_q_heads, a.n_q_heads, a.n_split, a.f.head_dim, stream);
     return CQ_OK;
 }
 

@@ -51,8 +51,11 @@ def test_chunk_attention_matches_oracle(c, b, m, T):
     fmt, q, kc, vc, ck, cv = _case(m + T, c, b, hq, hkv, B, m, T)
     scale = 1.0 / math.sqrt(128)
     ref = O.chunk_attention(q, kc, vc, ck, cv, scale, hkv)
-    out = _gpu(q, codes_to_cache(kc, fmt, t_cap), codes_to_cache(vc, fmt, t_cap), ck, cv, scale, fmt, T, t_cap)
-    _check(out, ref)
+    # split 0: the library's choice (chunks of one or two tokens go token by token through the
+    # single-token kernel); an explicit split always runs the chunk kernel
+    for split in (0, t_cap):
+        out = _gpu(q, codes_to_cache(kc, fmt, t_cap), codes_to_cache(vc, fmt, t_cap), ck, cv, scale, fmt, T, t_cap, split=split)
+        _check(out, ref)
 
 
 @pytest.mark.parametrize("c,b", CHUNK_FORMATS)
@@ -76,11 +79,42 @@ def test_chunk_of_one_token_agrees_with_decode_attention():
     c, b, hq, hkv, B, T, t_cap = 4, 8, 8, 4, 2, 900, 960
     fmt, q, kc, vc, ck, cv = _case(3, c, b, hq, hkv, B, 1, T)
     kcache, vcache = codes_to_cache(kc, fmt, t_cap), codes_to_cache(vc, fmt, t_cap)
-    out = _gpu(q, kcache, vcache, ck, cv, 0.1, fmt, T, t_cap)
     dec = gpu_attention(q[:, 0], kcache, vcache, ck, cv, 0.1, fmt, T, t_cap)
     ref = O.attention(q[:, 0], kc, vc, ck, cv, 0.1, hkv)
+    # by default a chunk of one token IS a single-token attention; the chunk kernel (explicit split) agrees
+    out = _gpu(q, kcache, vcache, ck, cv, 0.1, fmt, T, t_cap)
+    assert np.array_equal(out[:, 0].view(np.uint16), dec.view(np.uint16))
+    out = _gpu(q, kcache, vcache, ck, cv, 0.1, fmt, T, t_cap, split=t_cap)
     check_attention(out[:, 0], ref)
     assert np.max(np.abs(out[:, 0].astype(np.float64) - dec.astype(np.float64))) <= 2e-3 * np.max(np.abs(ref))
+
+
+@pytest.mark.parametrize("c,b,hq,hkv", [(4, 8, 4, 4), (8, 8, 8, 2), (8, 10, 4, 1), (2, 8, 2, 2)])
+def test_short_chunk_equals_token_by_token_decode_attention(c, b, hq, hkv):
+    # m = 2 with ragged lengths (one sequence as short as the chunk): query j of sequence n is the
+    # single-token attention over max(len_n, m) - m + j + 1 tokens, bit for bit, and matches the oracle
+    B, m, T, t_cap = 3, 2, 700, 704
+    fmt, q, kc, vc, ck, cv = _case(11, c, b, hq, hkv, B, m, T)
+    kcache, vcache = codes_to_cache(kc, fmt, t_cap), codes_to_cache(vc, fmt, t_cap)
+    lens = np.array([700, 2, 333], dtype=np.int32)
+    out = _gpu(q, kcache, vcache, ck, cv, 0.1, fmt, T, t_cap, seq_lens=lens)
+    _check(out, O.chunk_attention(q, kc, vc, ck, cv, 0.1, hkv, seq_lens=lens))
+    for j in range(m):
+        lj = lens - (m - 1 - j)
+        dec = gpu_attention(np.ascontiguousarray(q[:, j]), kcache, vcache, ck, cv, 0.1, fmt, T - (m - 1 - j), t_cap, seq_lens=lj)
+        assert np.array_equal(out[:, j].view(np.uint16), dec.view(np.uint16))
+    # the chunk kernel on the same inputs (explicit split) agrees within the tolerance
+    alt = _gpu(q, kcache, vcache, ck, cv, 0.1, fmt, T, t_cap, seq_lens=lens, split=256)
+    assert np.max(np.abs(alt.astype(np.float64) - out.astype(np.float64))) <= 2e-3 * np.max(np.abs(out.astype(np.float64)))
+
+
+def test_short_chunk_splits_long_contexts():
+    # a context long enough for the token-by-token path to split it (and to need the workspace)
+    c, b, hq, hkv, B, m, T, t_cap = 8, 8, 2, 2, 1, 2, 20000, 20032
+    fmt, q, kc, vc, ck, cv = _case(12, c, b, hq, hkv, B, m, T)
+    assert cq.cq_chunk_workspace_bytes(fmt, B, hq, m, T) > 0
+    out = _gpu(q, codes_to_cache(kc, fmt, t_cap), codes_to_cache(vc, fmt, t_cap), ck, cv, 0.1, fmt, T, t_cap)
+    _check(out, O.chunk_attention(q, kc, vc, ck, cv, 0.1, hkv))
 
 
 def test_chunk_whole_sequence_first_query_returns_its_own_value():

@@ -293,6 +293,16 @@ def test_chunk_attention_sizes_and_argument_checks_without_launching():
     assert cq.cq_chunk_default_split(cq.CQFormat(8, 10, 128, 4), 16, 8, 16, 4096) == 512
     assert cq.cq_chunk_default_split(cq.CQFormat(2, 4, 128, 4), 16, 8, 16, 4096) == 0        # sub-byte: through the fused format
     assert cq.cq_chunk_default_split(fmt, 16, 8, 5000, 4096) == 0            # more queries than cached tokens
+    # chunks of one or two tokens (up to 8 with one query head per KV head on large batches) are
+    # served token by token by the single-token kernel: its split, its workspace
+    assert cq.cq_chunk_default_split(fmt, 16, 8, 2, 4096) == cq.cq_decode_default_split(fmt, 16, 8, 4096)
+    assert cq.cq_chunk_workspace_bytes(fmt, 1, 8, 2, 65536) == max(cq.cq_decode_workspace_bytes(fmt, 1, 8, t) for t in (65535, 65536))
+    assert cq.cq_chunk_workspace_bytes(fmt, 1, 8, 2, 65536) > 0
+    assert cq.cq_chunk_workspace_bytes(fmt, 16, 8, 2, 4096) == cq.cq_decode_workspace_bytes(fmt, 16, 8, 4096)
+    mha = cq.CQFormat(4, 8, 128, 32)
+    assert cq.cq_chunk_default_split(mha, 16, 32, 8, 4096) == cq.cq_decode_default_split(mha, 16, 32, 4096)
+    assert cq.cq_chunk_workspace_bytes(mha, 16, 32, 8, 4096) == 0             # one split per token: nothing to merge
+    assert cq.cq_chunk_workspace_bytes(mha, 16, 32, 9, 4096) == 4 * 16 * 9 * 32 * (4096 // cq.cq_chunk_default_split(mha, 16, 32, 9, 4096)) * 130
 
     def run(fm=f, q=0x10000, m=16, t=128, t_cap=128, split=0, ws=0x70000, ws_bytes=1 << 30, hq=8, scale=0.1):
         return int(lib.cq_chunk_attention(_fake(q) if q else None, _fake(0x20000), _fake(0x30000), _fake(0x40000),
