@@ -12,17 +12,19 @@
 //      a second kernel merges the partials of all splits.
 //
 // LDS table layout: one row per code value, RW four-byte words per row (b = 8: 256 rows of 64
-// words = 64 KB; b = 10: 1024 rows of 32 words = 128 KB).  Lane l of a wavefront owns ONE word
+// words = 64 KB; b = 10: 1024 rows of 16 words = 64 KB).  Lane l of a wavefront owns ONE word
 // column at every step s of the walk over a token's Gh slots: column(l, g) with g = (l + s) mod
-// Gh, the group that the cache layout put in slot s of token l.  Within each half-wavefront the
-// 32 columns are different modulo 32 (lanes l and l + 32 may share one: the LDS serves a
-// wavefront in two halves), so neither the table gather nor the bin update ever has a bank
-// conflict.  With 16 groups per head each group is replicated twice to give 32 lanes their own
-// column; the epilogue adds the replicas.  For b = 8 the byte address of a lookup is
-// (code << 8) | (4 * column): one v_perm_b32 from the code word and a per-lane constant.  With
-// 16 or 32 groups per head only words 0..31 of a 256-byte row are columns; words 32..63 of the
-// 256 rows hold the split's scores (8192 of them), which keeps a workgroup under 70 KB of LDS
-// so that two of them share a CU.
+// Gh, the group that the cache layout put in slot s of token l.  With 32 or 64 groups per head
+// the 32 columns of a half-wavefront are different modulo 32 (lanes l and l + 32 may share one:
+// the LDS serves a wavefront in two halves), so neither the table gather nor the bin update ever
+// has a bank conflict.  With 16 groups per head and b = 8 each group is replicated twice to give
+// 32 lanes their own column (the epilogue adds the replicas), except in the form for long splits
+// (LONG) and for b = 10, which keep one column per group and the row space for other uses:
+// measured, the lanes that then share a column cost 2-4 % at equal split length.  For b = 8 the byte address of
+// a lookup is (code << 8) | (4 * column): one v_perm_b32 from the code word and a per-lane
+// constant.  With 16 or 32 groups per head only words 0..31 (0..15: LONG) of a 256-byte row are
+// columns; the remaining words of the 256 rows hold the split's scores (8192 of them; 12288:
+// LONG), which keeps a workgroup under 70 KB of LDS so that two of them share a CU.
 //
 // Measured on MI355X (microbenchmark, per CU): ds_read_b32 gathers and ds_add_u32 run at the
 // same rate with this layout as with linear addresses; ds_add_f32 is about 45 times slower than
