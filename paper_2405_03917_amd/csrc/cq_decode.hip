@@ -67,9 +67,82 @@ __global__ void layer_table_write_kernel(LayerChunk chunk, int count, LayerPtrs*
 // its weight is added to the bins of the codes just found.  The first query head of each KV head
 // stores the codes.  Results equal cq_encode_kv followed by cq_decode_attention bit for bit
 // (the bins are integers: the order of the additions does not matter).
-template <int GH, int C, int B, int NT, bool STEP, bool LAYERS, bool LONG>
-__global__ __launch_bounds__(NT, 4) void decode_split_kernel(DecodeArgs a)
+// A kernel argument is loaded (scalar load from the argument block) where it is first used;
+// left to the compiler, the prologue of this kernel loads its arguments in four dependent
+// stages (head counts; split and context; strides; pointers), each awaited before the next is
+// requested, and an argument added to a late stage delays the first global load (measured: 0.3-0.4
+// us per launch of the attention kernel for two more strides).  early() pins a value in a scalar
+// register at the point of the call, so that everything the workgroup needs before its first
+// global load is requested together at entry and awaited once.
+// (A pointer comes back as a pointer into global memory, which is what every pointer argument
+// of these kernels is: a pointer of unknown provenance would make each access through it a flat
+// instruction.)
+template <class T>
+__device__ __forceinline__ T* early(T* p)
 {
+    unsigned long long x = reinterpret_cast<unsigned long long>(p);
+    asm volatile("" : "+s"(x));
+    return (T*)reinterpret_cast<__attribute__((address_space(1))) T*>(x);
+}
+template <class T>
+__device__ __forceinline__ T early(T v)
+{
+    if constexpr (sizeof(T) == 4) {
+        unsigned x = __builtin_bit_cast(unsigned, v);
+        asm volatile("" : "+s"(x));
+        return __builtin_bit_cast(T, x);
+    } else {
+        static_assert(sizeof(T) == 8, "32- or 64-bit arguments");
+        unsigned long long x = __builtin_bit_cast(unsigned long long, v);
+        asm volatile("" : "+s"(x));
+        return __builtin_bit_cast(T, x);
+    }
+}
+
+template <bool STEP, bool LAYERS>
+__device__ __forceinline__ DecodeArgs early_args(const DecodeArgs& in)
+{
+    DecodeArgs a = in;                  // (what is not named below is read where it is used)
+    a.n_q_heads = early(in.n_q_heads);
+    a.f.n_kv_heads = early(in.f.n_kv_heads);
+    a.n_split = early(in.n_split);
+    a.tiles_per_split = early(in.tiles_per_split);
+    a.t = early(in.t);
+    a.seq_lens = early(in.seq_lens);
+    a.seq_len_shift = early(in.seq_len_shift);
+    a.seq_len_floor = early(in.seq_len_floor);
+    a.map.block_table = early(in.map.block_table);
+    a.map.bt_stride = early(in.map.bt_stride);
+    a.map.n_pages = early(in.map.n_pages);
+    a.map.tiles_cap = early(in.map.tiles_cap);
+    a.map.n_kv_heads = early(in.map.n_kv_heads);
+    a.scale_log2e = early(in.scale_log2e);
+    a.partials = early(in.partials);
+    if constexpr (LAYERS) {
+        a.layers = early(in.layers);
+        a.wgs_per_layer = early(in.wgs_per_layer);
+    } else {
+        a.q = early(in.q);
+        a.k_codes = early(in.k_codes);
+        a.v_codes = early(in.v_codes);
+        a.k_centroids = early(in.k_centroids);
+        a.v_centroids = early(in.v_centroids);
+        a.out = early(in.out);
+        a.q_batch_stride = early(in.q_batch_stride);
+        a.out_batch_stride = early(in.out_batch_stride);
+        if constexpr (STEP) {
+            a.xk_new = early(in.xk_new);
+            a.xv_new = early(in.xv_new);
+        }
+    }
+    if constexpr (STEP) a.x_new_stride = early(in.x_new_stride);
+    return a;
+}
+
+template <int GH, int C, int B, int NT, bool STEP, bool LAYERS, bool LONG>
+__global__ __launch_bounds__(NT, 4) void decode_split_kernel(DecodeArgs a_in)
+{
+    const DecodeArgs a = early_args<STEP, LAYERS>(a_in);
     using F = Fmt<GH, B, LONG>;
     constexpr int K = F::K, RW = F::RW, R = F::R;
     constexpr int NW = NT / 64;         // wavefronts
@@ -118,6 +191,8 @@ __global__ __launch_bounds__(NT, 4) void decode_split_kernel(DecodeArgs a)
     const uint16_t* v_centroids = a.v_centroids;
     uint16_t* out_ptr = a.out;
     float* partials = a.partials;
+    const int64_t q_batch_stride = a.q_batch_stride, out_batch_stride = a.out_batch_stride;
+    const int seq_len_shift = a.seq_len_shift, seq_len_floor = a.seq_len_floor;
     if constexpr (LAYERS) {
         const int layer = bid / a.wgs_per_layer;
         bid -= layer * a.wgs_per_layer;
@@ -153,7 +228,7 @@ __global__ __launch_bounds__(NT, 4) void decode_split_kernel(DecodeArgs a)
     const int hkv = hq / qper;
 
     int t_n = a.t;
-    if (a.seq_lens) t_n = min(max(a.seq_lens[n] - a.seq_len_shift, a.seq_len_floor), a.t);
+    if (a.seq_lens) t_n = min(max(a.seq_lens[n] - seq_len_shift, seq_len_floor), a.t);
     const int n_tiles = (t_n + kTileTokens - 1) / kTileTokens;
     const int tile0 = split * a.tiles_per_split;
     const int tile1 = min(tile0 + a.tiles_per_split, n_tiles);
@@ -206,7 +281,7 @@ __global__ __launch_bounds__(NT, 4) void decode_split_kernel(DecodeArgs a)
     const int gl = tid & 15;
     unsigned xvw[STEP ? NCH : 1][C / 2];            // fused step: this thread's slices of the new value row
     {
-        const uint16_t* qh = q_ptr + (size_t)n * a.q_batch_stride + (size_t)hq * D;
+        const uint16_t* qh = q_ptr + (size_t)n * q_batch_stride + (size_t)hq * D;
 #pragma unroll
         for (int ch = 0; ch < NCH; ++ch) {
             const int g = ch * 16 + gl;
@@ -491,7 +566,7 @@ __global__ __launch_bounds__(NT, 4) void decode_split_kernel(DecodeArgs a)
         float o = 0.f;
 #pragma unroll
         for (int w = 0; w < NW; ++w) o += scr[64 + w * D + chn];
-        if (direct) out_ptr[(size_t)n * a.out_batch_stride + (size_t)hq * D + chn] = __builtin_bit_cast(uint16_t, (_Float16)(o / l));
+        if (direct) out_ptr[(size_t)n * out_batch_stride + (size_t)hq * D + chn] = __builtin_bit_cast(uint16_t, (_Float16)(o / l));
         else part[kPartialHeader + chn] = o;
     }
 }
