@@ -585,14 +585,17 @@ __global__ void decode_merge_kernel(const float* partials, uint16_t* out, int n_
         out = layers[layer].out;
     }
     out += (size_t)(bh / n_q_heads) * out_batch_stride + (size_t)(bh % n_q_heads) * head_dim;
+    // (a split beyond its sequence left m = -inf, l = 0, o = 0: its weight 2^(-inf - m) is 0, and
+    // at least one split holds a token, so m is finite.  Straight-line loops: the loads of all
+    // splits are independent and go out together.)
     float m = -INFINITY;
+#pragma unroll 4
     for (int s = 0; s < n_split; ++s) m = fmaxf(m, p[s * stride]);
     for (int i = threadIdx.x; i < head_dim; i += blockDim.x) {
         float l = 0.f, o = 0.f;
+#pragma unroll 4
         for (int s = 0; s < n_split; ++s) {
-            const float ms = p[s * stride];
-            if (ms == -INFINITY) continue;
-            const float w = __builtin_amdgcn_exp2f(ms - m);
+            const float w = __builtin_amdgcn_exp2f(p[s * stride] - m);
             l = __builtin_fmaf(p[s * stride + 1], w, l);
             o = __builtin_fmaf(p[s * stride + kPartialHeader + i], w, o);
         }
