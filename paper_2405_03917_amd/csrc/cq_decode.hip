@@ -571,8 +571,8 @@ __global__ __launch_bounds__(NT, 4) void decode_split_kernel(DecodeArgs a_in)
     }
 }
 
-// Merge the partials of all splits of one (sequence, query head): exact rescaling by the
-// overall maximum, then one rounding to fp16.
+// Merge the partials of all splits of one (sequence, query head): rescaling to the running
+// maximum split by split, then one rounding to fp16.
 __global__ void decode_merge_kernel(const float* partials, uint16_t* out, int n_split, int head_dim,
                                     const LayerPtrs* layers, int rows_per_layer, int n_q_heads, int64_t out_batch_stride)
 {
@@ -585,19 +585,20 @@ __global__ void decode_merge_kernel(const float* partials, uint16_t* out, int n_
         out = layers[layer].out;
     }
     out += (size_t)(bh / n_q_heads) * out_batch_stride + (size_t)(bh % n_q_heads) * head_dim;
-    // (a split beyond its sequence left m = -inf, l = 0, o = 0: its weight 2^(-inf - m) is 0, and
-    // at least one split holds a token, so m is finite.  Straight-line loops: the loads of all
-    // splits are independent and go out together.)
-    float m = -INFINITY;
-#pragma unroll 4
-    for (int s = 0; s < n_split; ++s) m = fmaxf(m, p[s * stride]);
+    // One pass with a running maximum (the usual rescaling), so that no load waits for a value
+    // computed from another: the loads of all splits go out together.  A split beyond its
+    // sequence left m = -inf, l = 0, o = 0 and gets weight 0.
     for (int i = threadIdx.x; i < head_dim; i += blockDim.x) {
-        float l = 0.f, o = 0.f;
+        float m = -INFINITY, l = 0.f, o = 0.f;
 #pragma unroll 4
         for (int s = 0; s < n_split; ++s) {
-            const float w = __builtin_amdgcn_exp2f(p[s * stride] - m);
-            l = __builtin_fmaf(p[s * stride + 1], w, l);
-            o = __builtin_fmaf(p[s * stride + kPartialHeader + i], w, o);
+            const float ms = p[s * stride], ls = p[s * stride + 1], os = p[s * stride + kPartialHeader + i];
+            const float m_new = fmaxf(m, ms);
+            const float m_safe = m_new == -INFINITY ? 0.f : m_new;
+            const float keep = __builtin_amdgcn_exp2f(m - m_safe), w = __builtin_amdgcn_exp2f(ms - m_safe);
+            l = __builtin_fmaf(l, keep, ls * w);
+            o = __builtin_fmaf(o, keep, os * w);
+            m = m_new;
         }
         const _Float16 h = (_Float16)(o / l);
         out[i] = __builtin_bit_cast(uint16_t, h);
