@@ -103,6 +103,9 @@ template <bool STEP, bool LAYERS>
 __device__ __forceinline__ DecodeArgs early_args(const DecodeArgs& in)
 {
     DecodeArgs a = in;                  // (what is not named below is read where it is used)
+    // (not for a layer-batched launch: its workgroups overlap one another's prologues anyway, and
+    // the pinned registers cost that variant 2 % at 32 groups per head)
+    if constexpr (LAYERS) return a;
     a.n_q_heads = early(in.n_q_heads);
     a.f.n_kv_heads = early(in.f.n_kv_heads);
     a.n_split = early(in.n_split);
@@ -118,24 +121,19 @@ __device__ __forceinline__ DecodeArgs early_args(const DecodeArgs& in)
     a.map.n_kv_heads = early(in.map.n_kv_heads);
     a.scale_log2e = early(in.scale_log2e);
     a.partials = early(in.partials);
-    if constexpr (LAYERS) {
-        a.layers = early(in.layers);
-        a.wgs_per_layer = early(in.wgs_per_layer);
-    } else {
-        a.q = early(in.q);
-        a.k_codes = early(in.k_codes);
-        a.v_codes = early(in.v_codes);
-        a.k_centroids = early(in.k_centroids);
-        a.v_centroids = early(in.v_centroids);
-        a.out = early(in.out);
-        a.q_batch_stride = early(in.q_batch_stride);
-        a.out_batch_stride = early(in.out_batch_stride);
-        if constexpr (STEP) {
-            a.xk_new = early(in.xk_new);
-            a.xv_new = early(in.xv_new);
-        }
+    a.q = early(in.q);
+    a.k_codes = early(in.k_codes);
+    a.v_codes = early(in.v_codes);
+    a.k_centroids = early(in.k_centroids);
+    a.v_centroids = early(in.v_centroids);
+    a.out = early(in.out);
+    a.q_batch_stride = early(in.q_batch_stride);
+    a.out_batch_stride = early(in.out_batch_stride);
+    if constexpr (STEP) {
+        a.xk_new = early(in.xk_new);
+        a.xv_new = early(in.xv_new);
+        a.x_new_stride = early(in.x_new_stride);
     }
-    if constexpr (STEP) a.x_new_stride = early(in.x_new_stride);
     return a;
 }
 
