@@ -127,13 +127,14 @@ def test_chunk_whole_sequence_first_query_returns_its_own_value():
     _check(out, O.chunk_attention(q, kc, vc, ck, cv, 0.2, hkv))
 
 
-def test_chunk_paged_equals_contiguous_bit_for_bit():
-    c, b, hq, hkv, B, m, T, t_cap = 4, 8, 8, 4, 3, 40, 900, 960
+@pytest.mark.parametrize("m,split", [(40, 256), (2, 0)])       # the matrix-core kernel; the token-by-token path
+def test_chunk_paged_equals_contiguous_bit_for_bit(m, split):
+    c, b, hq, hkv, B, T, t_cap = 4, 8, 8, 4, 3, 900, 960
     fmt, q, kc, vc, ck, cv = _case(8, c, b, hq, hkv, B, m, T)
     n_tiles = t_cap // 64
     kcache, vcache = codes_to_cache(kc, fmt, t_cap), codes_to_cache(vc, fmt, t_cap)
     lens = np.array([900, 130, 64], dtype=np.int32)
-    want = _gpu(q, kcache, vcache, ck, cv, 0.1, fmt, T, t_cap, seq_lens=lens, split=256)
+    want = _gpu(q, kcache, vcache, ck, cv, 0.1, fmt, T, t_cap, seq_lens=lens, split=split)
     rng = np.random.default_rng(9)
     n_pages = B * n_tiles + 5
     perm = rng.permutation(n_pages)[:B * n_tiles].astype(np.int32).reshape(B, n_tiles)
@@ -148,7 +149,7 @@ def test_chunk_paged_equals_contiguous_bit_for_bit():
         pools.append(dev(pool.reshape(-1)))
     pages = cq.PageTable(dev(perm), n_pages)
     got = cq.cq_chunk_attention_paged(dev(q), pools[0], pools[1], dev(ck), dev(cv), 0.1, fmt, T, pages,
-                                      seq_lens=dev(lens), tokens_per_split=256)
+                                      seq_lens=dev(lens), tokens_per_split=split)
     torch.cuda.synchronize()
     assert np.array_equal(got.cpu().numpy().view(np.uint16), want.view(np.uint16))
 
