@@ -224,6 +224,54 @@ def extra_measurements(cq, synth, torch):
     return out
 
 
+def config_measurements(cq, synth, torch):
+    """The other two decode workloads of the named configurations, on caches filled by really
+    encoding generated activations: CQ-2c8b (batch 64, context 8192; also its 64 x 512-token
+    prefill encode) and CQ-8c10b with grouped queries (32 query / 8 KV heads, batch 32, context
+    16384)."""
+    out = {}
+    for cfg_id, key in ((3, "decode_cq2c8b_batch64_ctx8192"), (4, "decode_cq8c10b_gqa_batch32_ctx16384")):
+        cfg = synth.CONFIGS[cfg_id]
+        fmt = cq.CQFormat(cfg.c, cfg.b, cfg.head_dim, cfg.n_kv_heads)
+        B, T, D = cfg.batch, cfg.context, cfg.kv_channels
+        rk = synth.tensor_recipe(cfg_id, 0, "k", D)
+        rv = synth.tensor_recipe(cfg_id, 0, "v", D)
+        ck = torch.from_numpy(synth.sample_codebook(rk, cfg.c, cfg.b)).cuda()
+        cv = torch.from_numpy(synth.sample_codebook(rv, cfg.c, cfg.b)).cuda()
+        kcache, vcache = cq.alloc_cache(fmt, B, T), cq.alloc_cache(fmt, B, T)
+        per_seq = kcache.numel() // B
+        for n in range(B):                  # one sequence per call: T tokens x D channels
+            xk = synth.sample_activations_torch(rk, T, 17 * n, "cuda").view(1, T, D)
+            xv = synth.sample_activations_torch(rv, T, 17 * n + 1, "cuda").view(1, T, D)
+            cq.cq_encode_kv(xk, xv, ck, cv, fmt, kcache[n * per_seq:(n + 1) * per_seq],
+                            vcache[n * per_seq:(n + 1) * per_seq], 0, T)
+            del xk, xv
+        torch.cuda.synchronize()
+        q = torch.from_numpy(synth.sample_query(cfg_id, 0, B, cfg.n_q_heads, cfg.head_dim)).cuda()
+        o = torch.empty((B, cfg.n_q_heads, cfg.head_dim), dtype=torch.float16, device="cuda")
+        ws = torch.empty(max(16, cq.cq_decode_workspace_bytes(fmt, B, cfg.n_q_heads, T, 0)), dtype=torch.uint8, device="cuda")
+        scale = 1.0 / math.sqrt(cfg.head_dim)
+        call, _ = cq.prepare_decode_attention(q, kcache, vcache, ck, cv, scale, fmt, T, T, out=o, workspace=ws)
+        med, _ = time_calls(torch, call, 30, 10)
+        code_bytes = B * T * 2 * D * cfg.b // (8 * cfg.c)
+        out[key] = {"workload": f"{cfg.name}: cq_decode_attention of one layer, {cfg.n_q_heads} query / {cfg.n_kv_heads} KV heads "
+                                "(the codes are larger than the 256 MB last-level cache only for CQ-2c8b)",
+                    "ms": med, "kv_tokens_per_s": B * T / (med * 1e-3),
+                    "code_read_GBps": code_bytes / (med * 1e-3) / 1e9,
+                    "frac_of_hbm_peak": code_bytes / (med * 1e-3) / 1e9 / HBM_PEAK_GBPS,
+                    "tokens_per_split": cq.cq_decode_default_split(fmt, B, cfg.n_q_heads, T)}
+        if cfg.encode_tokens > 1:           # the configuration's prefill chunk: B x encode_tokens tokens, one tensor
+            te = cfg.encode_tokens
+            x = synth.sample_activations_torch(rk, B * te, 4242, "cuda").view(B, te, D)
+            enc_ms, _ = time_calls(torch, lambda: cq.cq_encode(x, ck, fmt, kcache, 0, T), 5, 1)
+            out[f"encode_cq{cfg.c}c{cfg.b}b_{B}x{te}"] = {
+                "workload": f"CQ-{cfg.c}c{cfg.b}b, {B} sequences x {te} tokens x {D} channels, one tensor, one cq_encode call",
+                "ms": enc_ms, "tokens_per_s": B * te / (enc_ms * 1e-3)}
+            del x
+        del kcache, vcache
+    return out
+
+
 def cpu_baseline(synth, cfg, budget_s=12.0):
     """The fp64 oracle, as it stands, on this host's cores: one layer-step (encode the new rows,
     attend over the context) for a sub-batch sized to the time budget."""
@@ -413,6 +461,8 @@ def main():
         torch.cuda.empty_cache()
         try:
             result["extra"] = extra_measurements(cq, synth, torch)
+            torch.cuda.empty_cache()
+            result["extra"].update(config_measurements(cq, synth, torch))
             log(f"[bench] extra: {json.dumps(result['extra'])}")
         except Exception as e:      # side measurements must not lose the main line
             result["extra"] = {"error": repr(e)}
