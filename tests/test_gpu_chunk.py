@@ -108,6 +108,19 @@ def test_short_chunk_equals_token_by_token_decode_attention(c, b, hq, hkv):
     assert np.max(np.abs(alt.astype(np.float64) - out.astype(np.float64))) <= 2e-3 * np.max(np.abs(out.astype(np.float64)))
 
 
+@pytest.mark.parametrize("m", [8, 9])
+def test_chunk_around_the_token_by_token_limit_of_a_large_batch(m):
+    # 16 sequences x 32 KV heads x 32 tiles = 16384 tiles: a large batch, where chunks of up to
+    # 8 tokens (one query head per KV head) go token by token and 9 tokens go to the matrix cores
+    c, b, hq, hkv, B, T, t_cap = 8, 8, 32, 32, 16, 2048, 2048
+    fmt, q, kc, vc, ck, cv = _case(13, c, b, hq, hkv, B, m, T)
+    out = _gpu(q, codes_to_cache(kc, fmt, t_cap), codes_to_cache(vc, fmt, t_cap), ck, cv, 0.09, fmt, T, t_cap)
+    # the oracle on three of the sixteen sequences
+    pick = [0, 7, 15]
+    ref = O.chunk_attention(q[pick], kc[pick], vc[pick], ck, cv, 0.09, hkv)
+    _check(out[pick], ref)
+
+
 def test_short_chunk_splits_long_contexts():
     # a context long enough for the token-by-token path to split it (and to need the workspace)
     c, b, hq, hkv, B, m, T, t_cap = 8, 8, 2, 2, 1, 2, 20000, 20032
