@@ -379,8 +379,7 @@ CQ_API cq_status cq_chunk_attention_paged(const void *q, const void *k_pool, con
  * arguments as cq_decode_step plus the table, same results as cq_encode_kv followed by
  * cq_decode_attention_rope, bit for bit.
  * Formats: head_dim 128.  For b = 8 (CQ-8c8b, CQ-4c8b, CQ-2c8b) the kernel keeps a head's key
- * centroids (64 KiB) on chip; CQ-8c10b (256 KiB per head) reads them from global memory and has
- * the attention calls only: cq_decode_step_rope[_paged] returns CQ_ERR_UNSUPPORTED for it.
+ * centroids (64 KiB) on chip; CQ-8c10b (256 KiB per head) reads them from global memory.
  * Workspace size: cq_decode_workspace_bytes with the tokens_per_split actually used.
  * Errors: as cq_decode_attention; CQ_ERR_INVALID_ARG also for a missing or too short table.
  */

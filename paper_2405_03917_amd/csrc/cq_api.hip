@@ -399,8 +399,7 @@ cq_status decode_common(const void* q, const void* x_k_new, const void* x_v_new,
     cq_status st = derive(fmt, &f);
     if (st != CQ_OK) return st;
     const bool rope = rope_positions != 0;
-    // (the fused step keeps the key centroids in LDS: 256 centroids per group only)
-    if (rope && (f.head_dim != 128 || (f.b != 8 && step))) return CQ_ERR_UNSUPPORTED;
+    if (rope && f.head_dim != 128) return CQ_ERR_UNSUPPORTED;
     CacheMap map;
     if (pages) {
         if ((st = paged_map(f, pages, batch, &map, &t_cap)) != CQ_OK) return st;

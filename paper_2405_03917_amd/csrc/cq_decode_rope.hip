@@ -125,11 +125,10 @@ __device__ __forceinline__ void group_order(const Tile<GH, B>& w, const Unrotate
 // holds the position in registers, and finds the value codes in the epilogue.  Same results as
 // cq_encode_kv followed by the attention call, bit for bit.
 // B = 10 (1024 centroids per group: 256 KB of key centroids per head) reads the centroids from
-// global memory (L2) instead of LDS; attention only.
+// global memory (L2) instead of LDS, in phase K and in the fused step's search.
 template <int GH, int C, int NT, bool STEP, int B>
 __global__ __launch_bounds__(NT) void decode_rope_kernel(DecodeArgs a, const float2* tile_tab, const float2* lane_tab)
 {
-    static_assert(B == 8 || !STEP, "the fused step needs the key centroids in LDS");
     using F = Fmt<GH, B>;
     constexpr int K = F::K, RW = F::RW, R = F::R;
     constexpr int NW = NT / 64;
@@ -238,8 +237,9 @@ __global__ __launch_bounds__(NT) void decode_rope_kernel(DecodeArgs a, const flo
     lds_barrier();
 
     // fused step: nearest key centroids of the new row, NT / GH threads per group over the
-    // centroids in LDS (ascending index per thread, 64-bit minimum over the threads: the exact
-    // search of cq_encode with its tie rule); the first query head of the KV head stores the codes
+    // centroids in LDS (b = 10: in global memory; ascending index per thread, 64-bit minimum over
+    // the threads: the exact search of cq_encode with its tie rule); the first query head of the
+    // KV head stores the codes
     if (has_new) {
         constexpr int TPG = NT / GH;
         const int g = tid / TPG;
@@ -252,9 +252,24 @@ __global__ __launch_bounds__(NT) void decode_rope_kernel(DecodeArgs a, const flo
             for (int i = 0; i < C / 2; ++i)
                 xvw[ch][i] = *reinterpret_cast<const unsigned*>(a.xv_new + xrow + (ch * 16 + gl16) * C + 2 * i);
         Nearest knear;
-        for (int j = tid % TPG; j < K; j += TPG) {
-            const CenVec<C> cen = lds_centroid<C>((unsigned)(g * K + j) * (C * 2));
-            knear.offer(centroid_distance<C>(xk, cen.w), j);
+        if constexpr (B == 8) {
+            for (int j = tid % TPG; j < K; j += TPG) {
+                const CenVec<C> cen = lds_centroid<C>((unsigned)(g * K + j) * (C * 2));
+                knear.offer(centroid_distance<C>(xk, cen.w), j);
+            }
+        } else {
+            // 1024 centroids per group stay in global memory: a wavefront reads runs of 64 of them
+            const uint16_t* cg = a.k_centroids + ((size_t)hkv * GH + g) * K * C;
+            constexpr int PER = K / TPG, BATCH = PER < 4 ? PER : 4;
+            static_assert(PER % BATCH == 0, "whole batches of loads");
+#pragma unroll 1
+            for (int j0 = tid % TPG; j0 < K; j0 += TPG * BATCH) {
+                CenVec<C> cen[BATCH];
+#pragma unroll
+                for (int u = 0; u < BATCH; ++u) cen[u] = global_centroid<C>(cg + (size_t)(j0 + u * TPG) * C);
+#pragma unroll
+                for (int u = 0; u < BATCH; ++u) knear.offer(centroid_distance<C>(xk, cen[u].w), j0 + u * TPG);
+            }
         }
         lds_min_u64(&keys[g], knear.key());
         lds_barrier();
@@ -392,7 +407,6 @@ __global__ __launch_bounds__(NT) void decode_rope_kernel(DecodeArgs a, const flo
     // fused step: encode the new value row against the value codebook (the registers of the sums
     // below), add its weight to the bins of its codes, store the codes
     if (has_new) {
-        static_assert(!STEP || EARLY, "the value codebook of the epilogue is in registers");
 #pragma unroll
         for (int ch = 0; ch < NCH; ++ch) {
             float xv[C];
@@ -402,13 +416,22 @@ __global__ __launch_bounds__(NT) void decode_rope_kernel(DecodeArgs a, const flo
                 xv[2 * i] = (float)h.x;
                 xv[2 * i + 1] = (float)h.y;
             }
+            const uint16_t* cvg = a.v_centroids + (size_t)(hkv * GH + ch * 16 + gl16) * K * C;
             Nearest vnear;
 #pragma unroll
-            for (int k = 0; k < KB; ++k) {
-                const int j0 = ((tid + k * NT) >> 4) * JPL;
+            for (int k0 = 0; k0 < IPT; k0 += KB) {
+                Cent16 rawb[EARLY ? 1 : KB];            // (where the codebook is not in registers yet: b = 10)
+                if constexpr (!EARLY) {
 #pragma unroll
-                for (int jj = 0; jj < JPL; ++jj)
-                    vnear.offer(centroid_distance<C>(xv, &rawv[EARLY ? ch : 0][k].w[jj * (C / 2)]), j0 + jj);
+                    for (int k = 0; k < KB; ++k) rawb[k] = load_cent16(cvg + (size_t)((tid + (k0 + k) * NT) >> 4) * 8);
+                }
+#pragma unroll
+                for (int k = 0; k < KB; ++k) {
+                    const int j0 = ((tid + (k0 + k) * NT) >> 4) * JPL;
+                    const Cent16& r = EARLY ? rawv[EARLY ? ch : 0][k] : rawb[EARLY ? 0 : k];
+#pragma unroll
+                    for (int jj = 0; jj < JPL; ++jj) vnear.offer(centroid_distance<C>(xv, &r.w[jj * (C / 2)]), j0 + jj);
+                }
             }
             const unsigned long long vkey = group_lanes_min(vnear.key());
             if (lane < 16) lds_min_u64(&keys[GH + ch * 16 + gl16], vkey);
@@ -529,8 +552,9 @@ cq_status launch_decode_rope(const DecodeArgs& a, const float* tables, int t_cap
         else if (a.f.gh == 64 && a.f.c == 2)
             st = step ? launch_rope_variant<64, 2, true>(a, tile_tab, lane_tab, stream) : launch_rope_variant<64, 2, false>(a, tile_tab, lane_tab, stream);
     }
-    if (a.f.b == 10 && a.f.head_dim == 128 && a.f.gh == 16 && a.f.c == 8 && a.xk_new == nullptr)
-        st = launch_rope_variant<16, 8, false, 10>(a, tile_tab, lane_tab, stream);
+    if (a.f.b == 10 && a.f.head_dim == 128 && a.f.gh == 16 && a.f.c == 8)
+        st = a.xk_new ? launch_rope_variant<16, 8, true, 10>(a, tile_tab, lane_tab, stream)
+                      : launch_rope_variant<16, 8, false, 10>(a, tile_tab, lane_tab, stream);
     if (st != CQ_OK) return st;
     if (a.n_split > 1)
         return launch_decode_merge(a.partials, a.out, a.batch * a.n_q_heads, a.n_q_heads, a.n_split, a.f.head_dim, stream);

@@ -17,7 +17,7 @@ from gpu_util import check_attention, codes_to_cache, dev, gpu_attention
 pytestmark = pytest.mark.gpu
 
 ROPE_FORMATS = [(8, 8), (4, 8), (2, 8)]
-ATTN_FORMATS = ROPE_FORMATS + [(8, 10)]         # the 1024-centroid format: attention only (centroids read from L2)
+ATTN_FORMATS = ROPE_FORMATS + [(8, 10)]         # the 1024-centroid format reads its key centroids from L2
 BASE = 10000.0
 
 
@@ -155,16 +155,6 @@ def test_rope_paged_equals_contiguous_bit_for_bit():
     assert np.array_equal(got.cpu().numpy().view(np.uint16), want.view(np.uint16))
 
 
-def test_rope_fused_step_rejects_the_1024_centroid_format():
-    # the fused step searches the key centroids in LDS: 256 per group only
-    fmt, q, kc, vc, ck, cv = _case(2, 8, 10, 2, 2, 1, 64)
-    rope = cq.RopeTable(BASE, 64)
-    x = torch.zeros((1, 256), dtype=torch.float16, device="cuda")
-    with pytest.raises(cq.CQError):
-        cq.cq_decode_step_rope(dev(q), x, x.clone(), codes_to_cache(kc, fmt, 64), codes_to_cache(vc, fmt, 64), dev(ck), dev(cv),
-                               0.1, fmt, 64, 64, rope)
-
-
 # ------------------------------------------------------------------------------------------
 # fused decode step on pre-rotation caches
 # ------------------------------------------------------------------------------------------
@@ -187,7 +177,7 @@ def _step_case(seed, c, b, hq, hkv, B, T, t_cap):
     return fmt, q, dev(xk1), dev(xv1), kc, vc, ck, cv
 
 
-@pytest.mark.parametrize("c,b", ROPE_FORMATS)
+@pytest.mark.parametrize("c,b", ATTN_FORMATS)
 @pytest.mark.parametrize("hq,hkv,T,split", [(4, 4, 1, 0), (4, 4, 64, 0), (8, 2, 65, 0), (4, 2, 1000, 0),
                                             (4, 4, 1000, 256), (16, 8, 300, 64)])
 def test_rope_step_equals_encode_then_rope_attention(c, b, hq, hkv, T, split):
@@ -203,10 +193,11 @@ def test_rope_step_equals_encode_then_rope_attention(c, b, hq, hkv, T, split):
     assert torch.equal(got.view(torch.int16), want.view(torch.int16)), "outputs differ"
 
 
-def test_rope_step_ragged_lengths_and_oracle():
+@pytest.mark.parametrize("c,b", [(4, 8), (8, 10)])
+def test_rope_step_ragged_lengths_and_oracle(c, b):
     # sequences of different lengths: each new token lands at its own position; also against the
     # oracle end to end (codes of the new rows, then attention with rotation)
-    c, b, hq, hkv, B, T, t_cap = 4, 8, 8, 4, 3, 700, 704
+    hq, hkv, B, T, t_cap = 8, 4, 3, 700, 704
     fmt, q, xk1, xv1, kc, vc, ck, cv = _step_case(9, c, b, hq, hkv, B, T, t_cap)
     rope = cq.RopeTable(BASE, t_cap)
     lens = np.array([700, 1, 65], dtype=np.int32)
@@ -232,8 +223,9 @@ def test_rope_step_ragged_lengths_and_oracle():
             assert not ((codes[n, p:p + 1] != wantc) & ~((d2 - d1) < 1e-6 * d2)).any()
 
 
-def test_rope_step_paged_equals_contiguous():
-    c, b, hq, hkv, B, T, t_cap = 8, 8, 4, 4, 2, 200, 256
+@pytest.mark.parametrize("c,b", [(8, 8), (8, 10)])
+def test_rope_step_paged_equals_contiguous(c, b):
+    hq, hkv, B, T, t_cap = 4, 4, 2, 200, 256
     fmt, q, xk1, xv1, kc, vc, ck, cv = _step_case(10, c, b, hq, hkv, B, T, t_cap)
     rope = cq.RopeTable(BASE, t_cap)
     n_tiles = t_cap // 64

@@ -244,9 +244,9 @@ def test_rope_sizes_and_argument_checks_without_launching():
     assert dec(fmt, ws_bytes=16) == cq.CQ_ERR_WORKSPACE_TOO_SMALL
     assert dec(cq.CQFormat(2, 4, 128, 4)) == cq.CQ_ERR_UNSUPPORTED     # sub-byte: through the fused format
     assert cq.cq_decode_rope_default_split(cq.CQFormat(8, 10, 128, 4), 2, 8, 4096) > 0
-    f10 = cq.CQFormat(8, 10, 128, 4)._c()
-    assert lib.cq_decode_step_rope(_fake(0x10000), _fake(0x11000), _fake(0x12000), 512, _fake(0x20000), _fake(0x30000),
-                                   _fake(0x40000), _fake(0x50000), 0.1, ctypes.byref(f10), 2, 8, 128, 128, None, 0,
+    f64 = cq.CQFormat(8, 8, 64, 4)._c()                                 # head_dim 128 only
+    assert lib.cq_decode_step_rope(_fake(0x10000), _fake(0x11000), _fake(0x12000), 256, _fake(0x20000), _fake(0x30000),
+                                   _fake(0x40000), _fake(0x50000), 0.1, ctypes.byref(f64), 2, 8, 128, 128, None, 0,
                                    _fake(0x80000), 4096, _fake(0x60000), _fake(0x70000), 1 << 30, None) == cq.CQ_ERR_UNSUPPORTED
     assert cq.cq_decode_rope_default_split(cq.CQFormat(2, 8, 128, 32), 64, 32, 64 * 1000) == 64 * 125    # 8 balanced splits of at most 128 tiles (256 without the rotation)
 
