@@ -419,6 +419,37 @@ CQ_API cq_status cq_decode_attention_rope_paged(const void *q, const void *k_poo
                                          void *out, void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * cq_chunk_attention_rope[_paged] -- cq_chunk_attention for caches whose keys were quantized
+ * before the rotary position embedding: causal attention of the LAST m tokens of each sequence,
+ * query token j (rotated by the caller to its own position t_n - m + j) over the cached tokens
+ * 0 .. t_n - m + j.  Served token by token by the kernel of cq_decode_attention_rope (m launches
+ * in stream order), so the results are bit-identical to m calls of cq_decode_attention_rope with
+ * the contexts of the m tokens; meant for the few tokens of a speculative-decoding check (the
+ * time is m times that of a decode step's attention).
+ *   q, out            device, fp16 [batch][m][n_q_heads][head_dim]
+ *   m                 1 <= m <= seq_lens[n] <= t <= t_cap (t <= rope_positions)
+ *   tokens_per_split  of the m single-token calls: 0 = cq_decode_rope_default_split(...) of each
+ *   workspace         device, cq_chunk_rope_workspace_bytes(...) bytes
+ *   everything else as in cq_decode_attention_rope.
+ * Errors: as cq_decode_attention_rope; CQ_ERR_INVALID_ARG also for m <= 0 or m > t; nothing is
+ * launched when the workspace is too small for any of the m tokens.
+ */
+CQ_API size_t cq_chunk_rope_workspace_bytes(const cq_format *fmt, int32_t batch, int32_t n_q_heads, int32_t m, int32_t t,
+                                     int32_t tokens_per_split);
+CQ_API cq_status cq_chunk_attention_rope(const void *q, const void *k_codes, const void *v_codes,
+                                  const void *k_centroids, const void *v_centroids, float scale, const cq_format *fmt,
+                                  int32_t batch, int32_t n_q_heads, int32_t m, int32_t t, int32_t t_cap,
+                                  const int32_t *seq_lens, int32_t tokens_per_split,
+                                  const void *rope_table, int32_t rope_positions,
+                                  void *out, void *workspace, size_t workspace_bytes, void *stream);
+CQ_API cq_status cq_chunk_attention_rope_paged(const void *q, const void *k_pool, const void *v_pool,
+                                        const void *k_centroids, const void *v_centroids, float scale, const cq_format *fmt,
+                                        int32_t batch, int32_t n_q_heads, int32_t m, int32_t t, const cq_page_table *pages,
+                                        const int32_t *seq_lens, int32_t tokens_per_split,
+                                        const void *rope_table, int32_t rope_positions,
+                                        void *out, void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * cq_dequantize -- the inverse lookup ("dequantization", Section 2.2; CQ(A) of Eq. 5 as values):
  * out[n][t][g c + i] = centroids[g][code(n, t_offset + t, g)][i] for t = 0 .. t_count - 1, bit
  * for bit the stored fp16 centroids.  For callers that need dense keys / values (e.g. a

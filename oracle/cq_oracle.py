@@ -183,10 +183,13 @@ def attention(q: np.ndarray, k_codes: np.ndarray, v_codes: np.ndarray,
 
 def chunk_attention(q: np.ndarray, k_codes: np.ndarray, v_codes: np.ndarray,
                     k_centroids: np.ndarray, v_centroids: np.ndarray, scale: float,
-                    n_kv_heads: int, seq_lens: Optional[np.ndarray] = None) -> np.ndarray:
+                    n_kv_heads: int, seq_lens: Optional[np.ndarray] = None,
+                    rope_base: Optional[float] = None) -> np.ndarray:
     """Causal attention of the LAST m tokens of each sequence over its coded cache: Eq. 1 of the
     paper applied once per query token, each over the cached tokens up to and including its own
-    position (the cache already holds the codes of the m tokens).
+    position (the cache already holds the codes of the m tokens).  With `rope_base` the cached keys
+    are pre-rotation keys (Section 3.2) and attention() rotates each to its position; the query
+    tokens arrive rotated.
 
     q fp16 [B, m, Hq, d]: query j of sequence n sits at position t_n - m + j, where t_n =
     seq_lens[n] (default: all T cached tokens), and attends to tokens 0 .. t_n - m + j.
@@ -201,5 +204,5 @@ def chunk_attention(q: np.ndarray, k_codes: np.ndarray, v_codes: np.ndarray,
     for j in range(m):
         lens = (t_n - m + j + 1).astype(np.int32)
         out[:, j] = attention(np.ascontiguousarray(q[:, j]), k_codes, v_codes, k_centroids, v_centroids, scale,
-                              n_kv_heads, seq_lens=lens)
+                              n_kv_heads, seq_lens=lens, rope_base=rope_base)
     return out

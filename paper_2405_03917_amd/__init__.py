@@ -31,7 +31,9 @@ EXPORTS = (
     "cq_fused_format", "cq_expand_codebook", "cq_chunk_default_split", "cq_chunk_workspace_bytes", "cq_chunk_attention", "cq_chunk_attention_paged",
     "cq_layer_table_bytes", "cq_layer_table_fill", "cq_decode_step_layers",
     "cq_rope_table_bytes", "cq_rope_table", "cq_decode_rope_default_split", "cq_decode_attention_rope",
-    "cq_decode_attention_rope_paged", "cq_decode_step_rope", "cq_decode_step_rope_paged", "cq_probe_stream_read", "cq_probe_copy", "cq_probe_mfma",
+    "cq_decode_attention_rope_paged", "cq_decode_step_rope", "cq_decode_step_rope_paged",
+    "cq_chunk_rope_workspace_bytes", "cq_chunk_attention_rope", "cq_chunk_attention_rope_paged",
+    "cq_probe_stream_read", "cq_probe_copy", "cq_probe_mfma",
 )
 
 
@@ -150,6 +152,14 @@ def load() -> ctypes.CDLL:
     lib.cq_chunk_attention_paged.restype = ctypes.c_int
     lib.cq_chunk_attention_paged.argtypes = [vp, vp, vp, vp, vp, ctypes.c_float, fp, i32, i32, i32, i32, pp, vp, i32,
                                              vp, vp, ctypes.c_size_t, vp]
+    lib.cq_chunk_rope_workspace_bytes.restype = ctypes.c_size_t
+    lib.cq_chunk_rope_workspace_bytes.argtypes = [fp, i32, i32, i32, i32, i32]
+    lib.cq_chunk_attention_rope.restype = ctypes.c_int
+    lib.cq_chunk_attention_rope.argtypes = [vp, vp, vp, vp, vp, ctypes.c_float, fp, i32, i32, i32, i32, i32, vp, i32,
+                                            vp, i32, vp, vp, ctypes.c_size_t, vp]
+    lib.cq_chunk_attention_rope_paged.restype = ctypes.c_int
+    lib.cq_chunk_attention_rope_paged.argtypes = [vp, vp, vp, vp, vp, ctypes.c_float, fp, i32, i32, i32, i32, pp, vp, i32,
+                                                  vp, i32, vp, vp, ctypes.c_size_t, vp]
     lib.cq_layer_table_bytes.restype = ctypes.c_size_t
     lib.cq_layer_table_bytes.argtypes = [i32]
     lib.cq_layer_table_fill.restype = ctypes.c_int
@@ -574,6 +584,55 @@ class RopeTable:
 def cq_decode_rope_default_split(fmt: CQFormat, batch: int, n_q_heads: int, t: int) -> int:
     f = fmt._c()
     return int(load().cq_decode_rope_default_split(ctypes.byref(f), batch, n_q_heads, t))
+
+
+def cq_chunk_rope_workspace_bytes(fmt: CQFormat, batch: int, n_q_heads: int, m: int, t: int, tokens_per_split: int = 0) -> int:
+    f = fmt._c()
+    return int(load().cq_chunk_rope_workspace_bytes(ctypes.byref(f), batch, n_q_heads, m, t, tokens_per_split))
+
+
+def prepare_chunk_attention_rope(q, k_codes, v_codes, k_centroids, v_centroids, scale: float, fmt: CQFormat, t: int,
+                                 t_cap: int, rope: "RopeTable", pages=None, seq_lens=None, tokens_per_split: int = 0,
+                                 out=None, workspace=None):
+    """Check and marshal the arguments of cq_chunk_attention_rope (or, with `pages`, of its paged
+    form) once.  q fp16 [B, m, Hq, head_dim], each query token rotated to its own position.
+    Returns (call, out)."""
+    import torch
+    if not isinstance(rope, RopeTable):
+        raise TypeError("rope must be a RopeTable")
+    batch, m, n_q_heads = int(q.shape[0]), int(q.shape[1]), int(q.shape[2])
+    if workspace is None:
+        nbytes = cq_chunk_rope_workspace_bytes(fmt, batch, n_q_heads, m, t, tokens_per_split)
+        if nbytes == 0:
+            raise CQError(CQ_ERR_INVALID_ARG, "cq_chunk_rope_workspace_bytes")
+        workspace = torch.empty(nbytes, dtype=torch.uint8, device=q.device)
+    # the argument checks and the marshalling of the position-independent form, then the table
+    call, out = prepare_chunk_attention(q, k_codes, v_codes, k_centroids, v_centroids, scale, fmt, t, t_cap, pages,
+                                        seq_lens, tokens_per_split, out, workspace)
+    a = call._args
+    args = a[:-3] + (rope.table.data_ptr(), rope.positions) + a[-3:]
+    name = "cq_chunk_attention_rope_paged" if pages is not None else "cq_chunk_attention_rope"
+    return PreparedCall(getattr(load(), name), args, call._keep + (rope,), name), out
+
+
+def cq_chunk_attention_rope(q, k_codes, v_codes, k_centroids, v_centroids, scale: float, fmt: CQFormat, t: int, t_cap: int,
+                            rope: "RopeTable", seq_lens=None, tokens_per_split: int = 0, out=None, workspace=None, stream=None):
+    """cq_chunk_attention for caches whose keys were quantized before RoPE (token by token through
+    the kernel of cq_decode_attention_rope): q, out fp16 [B, m, Hq, head_dim]."""
+    call, out = prepare_chunk_attention_rope(q, k_codes, v_codes, k_centroids, v_centroids, scale, fmt, t, t_cap, rope,
+                                             None, seq_lens, tokens_per_split, out, workspace)
+    call(stream)
+    return out
+
+
+def cq_chunk_attention_rope_paged(q, k_pool, v_pool, k_centroids, v_centroids, scale: float, fmt: CQFormat, t: int, pages,
+                                  rope: "RopeTable", seq_lens=None, tokens_per_split: int = 0, out=None, workspace=None,
+                                  stream=None):
+    """cq_chunk_attention_rope over paged pools."""
+    call, out = prepare_chunk_attention_rope(q, k_pool, v_pool, k_centroids, v_centroids, scale, fmt, t, 0, rope, pages,
+                                             seq_lens, tokens_per_split, out, workspace)
+    call(stream)
+    return out
 
 
 def prepare_decode_attention_rope(q, k_codes, v_codes, k_centroids, v_centroids, scale: float, fmt: CQFormat,

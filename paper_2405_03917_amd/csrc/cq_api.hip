@@ -385,6 +385,13 @@ size_t cq_decode_workspace_bytes(const cq_format* fmt, int32_t batch, int32_t n_
 
 namespace {
 
+// One query token of a chunk served token by token: q and out rows of the token inside
+// [batch][m][n_q_heads][head_dim] tensors, and its context seq_lens[n] - shift (at least floor).
+struct TokenView {
+    int64_t q_batch_stride, out_batch_stride;
+    int seq_len_shift, seq_len_floor;
+};
+
 cq_status decode_common(const void* q, const void* x_k_new, const void* x_v_new, int64_t x_row_stride,
                         const void* k_codes, const void* v_codes,
                         const void* k_centroids, const void* v_centroids,
@@ -393,7 +400,7 @@ cq_status decode_common(const void* q, const void* x_k_new, const void* x_v_new,
                         const int32_t* seq_lens, int32_t tokens_per_split,
                         void* out, void* workspace, size_t workspace_bytes, void* stream, bool step,
                         const void* rope_table = nullptr, int32_t rope_positions = 0,
-                        const LayerPtrs* layers = nullptr, int32_t n_layers = 1)
+                        const LayerPtrs* layers = nullptr, int32_t n_layers = 1, const TokenView* view = nullptr)
 {
     Derived f;
     cq_status st = derive(fmt, &f);
@@ -458,9 +465,10 @@ cq_status decode_common(const void* q, const void* x_k_new, const void* x_v_new,
     a.n_split = n_split;
     a.partials = static_cast<float*>(workspace);
     a.out = static_cast<uint16_t*>(out);
-    a.q_batch_stride = a.out_batch_stride = (int64_t)n_q_heads * f.head_dim;
-    a.seq_len_shift = 0;
-    a.seq_len_floor = 1;
+    a.q_batch_stride = view ? view->q_batch_stride : (int64_t)n_q_heads * f.head_dim;
+    a.out_batch_stride = view ? view->out_batch_stride : (int64_t)n_q_heads * f.head_dim;
+    a.seq_len_shift = view ? view->seq_len_shift : 0;
+    a.seq_len_floor = view ? view->seq_len_floor : 1;
     a.f = f;
     if (rope) return launch_decode_rope(a, static_cast<const float*>(rope_table), rope_positions, static_cast<hipStream_t>(stream));
     return launch_decode(a, static_cast<hipStream_t>(stream));
@@ -822,6 +830,90 @@ cq_status cq_decode_step_rope_paged(const void* q, const void* x_k_new, const vo
     return decode_common(q, x_k_new, x_v_new, x_row_stride, k_pool, v_pool, k_centroids, v_centroids, scale, fmt,
                          batch, n_q_heads, t, 0, pages, seq_lens, tokens_per_split, out, workspace, workspace_bytes,
                          stream, true, rope_table, rope_positions);
+}
+
+namespace {
+
+// split (tiles) and workspace need of query token j of a chunk over pre-RoPE keys
+TokenCall chunk_rope_token_call(const Derived& f, int batch, int n_q_heads, int m, int t, int j, int tokens_per_split)
+{
+    TokenCall c;
+    c.t = t - (m - 1 - j);
+    c.tiles = tokens_per_split ? tokens_per_split / kTileTokens
+                               : default_tiles_per_split(f, batch, n_q_heads, c.t,
+                                                         std::min(decode_rope_max_tiles_per_split(), decode_max_tiles_per_split(f)));
+    const int n_tiles = (c.t + kTileTokens - 1) / kTileTokens;
+    c.n_split = (n_tiles + c.tiles - 1) / c.tiles;
+    c.workspace = sizeof(float) * (size_t)batch * n_q_heads * c.n_split * (f.head_dim + kPartialHeader);
+    return c;
+}
+
+cq_status chunk_rope_common(const void* q, const void* k_codes, const void* v_codes,
+                            const void* k_centroids, const void* v_centroids, float scale, const cq_format* fmt,
+                            int32_t batch, int32_t n_q_heads, int32_t m, int32_t t, int32_t t_cap, const cq_page_table* pages,
+                            const int32_t* seq_lens, int32_t tokens_per_split,
+                            const void* rope_table, int32_t rope_positions,
+                            void* out, void* workspace, size_t workspace_bytes, void* stream)
+{
+    Derived f;
+    const cq_status st0 = derive(fmt, &f);
+    if (st0 != CQ_OK) return st0;
+    if (f.head_dim != 128) return CQ_ERR_UNSUPPORTED;
+    if (!q || !out || batch <= 0 || n_q_heads <= 0 || n_q_heads % f.n_kv_heads != 0) return CQ_ERR_INVALID_ARG;
+    if (m <= 0 || t < m || rope_positions <= 0) return CQ_ERR_INVALID_ARG;
+    if (tokens_per_split < 0 || tokens_per_split % kTileTokens != 0) return CQ_ERR_INVALID_ARG;
+    // all tokens are checked before the first one is launched
+    for (int j = 0; j < m; ++j)
+        if (workspace_bytes < chunk_rope_token_call(f, batch, n_q_heads, m, t, j, tokens_per_split).workspace)
+            return CQ_ERR_WORKSPACE_TOO_SMALL;
+    const int64_t row = (int64_t)n_q_heads * f.head_dim;
+    for (int j = 0; j < m; ++j) {               // (in stream order: the calls share the workspace)
+        const TokenView view{m * row, m * row, m - 1 - j, j + 1};
+        const cq_status st = decode_common(static_cast<const uint16_t*>(q) + j * row, nullptr, nullptr, 0, k_codes, v_codes,
+                                           k_centroids, v_centroids, scale, fmt, batch, n_q_heads, t - (m - 1 - j), t_cap, pages,
+                                           seq_lens, tokens_per_split, static_cast<uint16_t*>(out) + j * row, workspace,
+                                           workspace_bytes, stream, false, rope_table, rope_positions, nullptr, 1, &view);
+        if (st != CQ_OK) return st;
+    }
+    return CQ_OK;
+}
+
+}  // namespace
+
+size_t cq_chunk_rope_workspace_bytes(const cq_format* fmt, int32_t batch, int32_t n_q_heads, int32_t m, int32_t t,
+                                     int32_t tokens_per_split)
+{
+    Derived f;
+    if (derive(fmt, &f) != CQ_OK || f.head_dim != 128) return 0;
+    if (batch <= 0 || n_q_heads <= 0 || n_q_heads % f.n_kv_heads != 0 || m <= 0 || t < m) return 0;
+    if (tokens_per_split < 0 || tokens_per_split % kTileTokens != 0) return 0;
+    if (tokens_per_split / kTileTokens > std::min(decode_rope_max_tiles_per_split(), decode_max_tiles_per_split(f))) return 0;
+    size_t need = 0;
+    for (int j = 0; j < m; ++j) need = std::max(need, chunk_rope_token_call(f, batch, n_q_heads, m, t, j, tokens_per_split).workspace);
+    return need;
+}
+
+cq_status cq_chunk_attention_rope(const void* q, const void* k_codes, const void* v_codes,
+                                  const void* k_centroids, const void* v_centroids, float scale, const cq_format* fmt,
+                                  int32_t batch, int32_t n_q_heads, int32_t m, int32_t t, int32_t t_cap,
+                                  const int32_t* seq_lens, int32_t tokens_per_split,
+                                  const void* rope_table, int32_t rope_positions,
+                                  void* out, void* workspace, size_t workspace_bytes, void* stream)
+{
+    return chunk_rope_common(q, k_codes, v_codes, k_centroids, v_centroids, scale, fmt, batch, n_q_heads, m, t, t_cap, nullptr,
+                             seq_lens, tokens_per_split, rope_table, rope_positions, out, workspace, workspace_bytes, stream);
+}
+
+cq_status cq_chunk_attention_rope_paged(const void* q, const void* k_pool, const void* v_pool,
+                                        const void* k_centroids, const void* v_centroids, float scale, const cq_format* fmt,
+                                        int32_t batch, int32_t n_q_heads, int32_t m, int32_t t, const cq_page_table* pages,
+                                        const int32_t* seq_lens, int32_t tokens_per_split,
+                                        const void* rope_table, int32_t rope_positions,
+                                        void* out, void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (!pages) return CQ_ERR_INVALID_ARG;
+    return chunk_rope_common(q, k_pool, v_pool, k_centroids, v_centroids, scale, fmt, batch, n_q_heads, m, t, 0, pages,
+                             seq_lens, tokens_per_split, rope_table, rope_positions, out, workspace, workspace_bytes, stream);
 }
 
 cq_status cq_decode_attention_rope_paged(const void* q, const void* k_pool, const void* v_pool,

@@ -384,7 +384,8 @@ cq_status launch_chunk_attention(const ChunkArgs& a, hipStream_t stream)
     }
     if (st != CQ_OK) return st;
     if (a.n_split > 1)
-        return launch_decode_merge(a.partials, a.out, a.batch * a.m * a.n_q_heads, a.n_q_heads, a.n_split, a.f.head_dim, stream);
+        return launch_decode_merge(a.partials, a.out, a.batch * a.m * a.n_q_heads, a.n_q_heads, (int64_t)a.n_q_heads * a.f.head_dim, a.n_split,
+                                   a.f.head_dim, stream);
     return CQ_OK;
 }
 

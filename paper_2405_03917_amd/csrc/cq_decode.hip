@@ -665,10 +665,11 @@ cq_status launch_layer_table_write(const LayerChunk& chunk, int count, LayerPtrs
     return hipGetLastError() == hipSuccess ? CQ_OK : CQ_ERR_HIP;
 }
 
-cq_status launch_decode_merge(const float* partials, uint16_t* out, int rows, int n_q_heads, int n_split, int head_dim, hipStream_t stream)
+cq_status launch_decode_merge(const float* partials, uint16_t* out, int rows, int n_q_heads, int64_t out_batch_stride,
+                              int n_split, int head_dim, hipStream_t stream)
 {
     hipLaunchKernelGGL(decode_merge_kernel, dim3((unsigned)rows), dim3(128), 0, stream, partials, out, n_split, head_dim,
-                       static_cast<const LayerPtrs*>(nullptr), 0, n_q_heads, (int64_t)n_q_heads * head_dim);
+                       static_cast<const LayerPtrs*>(nullptr), 0, n_q_heads, out_batch_stride);
     return hipGetLastError() == hipSuccess ? CQ_OK : CQ_ERR_HIP;
 }
 

@@ -175,7 +175,7 @@ __global__ __launch_bounds__(NT) void decode_rope_kernel(DecodeArgs a, const flo
     const int hkv = hq / qper;
 
     int t_n = a.t;
-    if (a.seq_lens) t_n = min(max(a.seq_lens[n], 1), a.t);
+    if (a.seq_lens) t_n = min(max(a.seq_lens[n] - a.seq_len_shift, a.seq_len_floor), a.t);
     const int n_tiles = (t_n + kTileTokens - 1) / kTileTokens;
     const int tile0 = split * a.tiles_per_split;
     const int tile1 = min(tile0 + a.tiles_per_split, n_tiles);
@@ -221,7 +221,7 @@ __global__ __launch_bounds__(NT) void decode_rope_kernel(DecodeArgs a, const flo
         const uint4* lt = reinterpret_cast<const uint4*>(lane_tab);
         for (int i = tid; i < (int)(kTrgBytes / 16); i += NT) reinterpret_cast<uint4*>(smem + kTabBytes / 4)[i] = lt[i];
     }
-    const uint16_t* qh = a.q + (size_t)(n * a.n_q_heads + hq) * D;
+    const uint16_t* qh = a.q + (size_t)n * a.q_batch_stride + (size_t)hq * D;
     const float qa = (float)__builtin_bit_cast(_Float16, qh[lane]) * a.scale_log2e;
     const float qb = (float)__builtin_bit_cast(_Float16, qh[lane + kPairs]) * a.scale_log2e;
     st.begin(kwalk, my_tiles, lane);
@@ -503,7 +503,7 @@ __global__ __launch_bounds__(NT) void decode_rope_kernel(DecodeArgs a, const flo
         float o = 0.f;
 #pragma unroll
         for (int w = 0; w < NW; ++w) o += scr[64 + w * D + chn];
-        if (direct) a.out[(size_t)(n * a.n_q_heads + hq) * D + chn] = __builtin_bit_cast(uint16_t, (_Float16)(o / l));
+        if (direct) a.out[(size_t)n * a.out_batch_stride + (size_t)hq * D + chn] = __builtin_bit_cast(uint16_t, (_Float16)(o / l));
         else part[kPartialHeader + chn] = o;
     }
 }
@@ -557,7 +557,7 @@ cq_status launch_decode_rope(const DecodeArgs& a, const float* tables, int t_cap
                       : launch_rope_variant<16, 8, false, 10>(a, tile_tab, lane_tab, stream);
     if (st != CQ_OK) return st;
     if (a.n_split > 1)
-        return launch_decode_merge(a.partials, a.out, a.batch * a.n_q_heads, a.n_q_heads, a.n_split, a.f.head_dim, stream);
+        return launch_decode_merge(a.partials, a.out, a.batch * a.n_q_heads, a.n_q_heads, a.out_batch_stride, a.n_split, a.f.head_dim, stream);
     return CQ_OK;
 }
 

@@ -113,8 +113,7 @@ struct DecodeArgs {
     uint16_t* out;
     // q and out are [batch][n_q_heads][head_dim] with these batch strides (elements); sequence n
     // attends to min(max(seq_lens[n] - seq_len_shift, seq_len_floor), t) tokens.  (Other than
-    // n_q_heads * head_dim, 0 and 1 only where a chunk of query tokens is served token by token;
-    // the pre-RoPE kernel ignores all four.)
+    // n_q_heads * head_dim, 0 and 1 only where a chunk of query tokens is served token by token.)
     int64_t q_batch_stride, out_batch_stride;
     int seq_len_shift, seq_len_floor;
     // layer-batched launch (null: one layer): workgroup blockIdx / wgs_per_layer serves layer
@@ -194,7 +193,9 @@ cq_status launch_expand_codebook(const uint16_t* centroids, const Derived& f, ui
 // writes `count` records of a layer table (device memory) from values passed with the launch
 cq_status launch_layer_table_write(const LayerChunk& chunk, int count, LayerPtrs* dst, hipStream_t stream);
 // merges the partials of `rows` (sequence, query head) pairs, n_split each, into fp16 rows
-cq_status launch_decode_merge(const float* partials, uint16_t* out, int rows, int n_q_heads, int n_split, int head_dim, hipStream_t stream);
+// (row r goes to out + (r / n_q_heads) * out_batch_stride + (r % n_q_heads) * head_dim)
+cq_status launch_decode_merge(const float* partials, uint16_t* out, int rows, int n_q_heads, int64_t out_batch_stride,
+                              int n_split, int head_dim, hipStream_t stream);
 
 // Keys cached before the rotary position embedding (cq_decode_rope.hip).  The table holds, for
 // head_dim 128, cos / sin of (64 * tile) * theta_i for every tile of `positions` tokens, then

@@ -301,3 +301,53 @@ def test_rope_attention_and_step_sweep(case):
         out = _gpu(q, kcache, vcache, ck, cv, 0.09, fmt, T, t_cap, rope, seq_lens=lens, split=split)
     ref = O.attention(q, kc, vc, ck, cv, 0.09, hkv, seq_lens=lens, rope_base=BASE)
     check_attention(out, ref)
+
+
+# ------------------------------------------------------------------------------------------
+# several query tokens over pre-rotation caches (token by token through the decode kernel)
+# ------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("c,b", ATTN_FORMATS)
+@pytest.mark.parametrize("hq,hkv,m,T,split", [(4, 4, 1, 1, 0), (4, 2, 3, 3, 0), (8, 2, 5, 700, 0), (4, 4, 4, 1000, 256)])
+def test_rope_chunk_matches_oracle_and_token_by_token_calls(c, b, hq, hkv, m, T, split):
+    B, t_cap = 3, 1024
+    fmt, _, kc, vc, ck, cv = _case(50 + m + T, c, b, hq, hkv, B, T)
+    q = np.random.default_rng(m * 1000 + T).standard_normal((B, m, hq, 128)).astype(np.float16)
+    lens = np.array([T, max(m, T // 3), max(m, T - 1)], dtype=np.int32)
+    rope = cq.RopeTable(BASE, t_cap)
+    kcache, vcache = codes_to_cache(kc, fmt, t_cap), codes_to_cache(vc, fmt, t_cap)
+    out = cq.cq_chunk_attention_rope(dev(q), kcache, vcache, dev(ck), dev(cv), 0.1, fmt, T, t_cap, rope,
+                                     seq_lens=dev(lens), tokens_per_split=split)
+    torch.cuda.synchronize()
+    out = out.cpu().numpy()
+    ref = O.chunk_attention(q, kc, vc, ck, cv, 0.1, hkv, seq_lens=lens, rope_base=BASE)
+    check_attention(out.reshape(B * m, hq, 128), ref.reshape(B * m, hq, 128))
+    for j in range(m):
+        dec = _gpu(np.ascontiguousarray(q[:, j]), kcache, vcache, ck, cv, 0.1, fmt, T - (m - 1 - j), t_cap, rope,
+                   seq_lens=lens - (m - 1 - j), split=split)
+        assert np.array_equal(out[:, j].view(np.uint16), dec.view(np.uint16))
+
+
+def test_rope_chunk_paged_equals_contiguous():
+    c, b, hq, hkv, B, m, T, t_cap = 4, 8, 8, 4, 2, 3, 500, 512
+    fmt, _, kc, vc, ck, cv = _case(77, c, b, hq, hkv, B, T)
+    q = np.random.default_rng(78).standard_normal((B, m, hq, 128)).astype(np.float16)
+    rope = cq.RopeTable(BASE, t_cap)
+    kcache, vcache = codes_to_cache(kc, fmt, t_cap), codes_to_cache(vc, fmt, t_cap)
+    lens = dev(np.array([500, 77], dtype=np.int32))
+    want = cq.cq_chunk_attention_rope(dev(q), kcache, vcache, dev(ck), dev(cv), 0.1, fmt, T, t_cap, rope, seq_lens=lens)
+    n_tiles = t_cap // 64
+    n_pages = B * n_tiles + 2
+    perm = np.random.default_rng(5).permutation(n_pages)[:B * n_tiles].astype(np.int32).reshape(B, n_tiles)
+    tb = cq.cq_code_bytes_per_token_head(fmt) * 64
+    pools = []
+    for cache in (kcache, vcache):
+        src = cache.cpu().numpy().reshape(B, hkv, n_tiles, tb)
+        pool = np.full((n_pages, hkv, tb), 0x77, dtype=np.uint8)
+        for n in range(B):
+            for i in range(n_tiles):
+                pool[perm[n, i]] = src[n, :, i]
+        pools.append(dev(pool.reshape(-1)))
+    pages = cq.PageTable(dev(perm), n_pages)
+    got = cq.cq_chunk_attention_rope_paged(dev(q), pools[0], pools[1], dev(ck), dev(cv), 0.1, fmt, T, pages, rope, seq_lens=lens)
+    torch.cuda.synchronize()
+    assert torch.equal(got.view(torch.int16), want.view(torch.int16))

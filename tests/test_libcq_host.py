@@ -248,6 +248,17 @@ def test_rope_sizes_and_argument_checks_without_launching():
     assert lib.cq_decode_step_rope(_fake(0x10000), _fake(0x11000), _fake(0x12000), 256, _fake(0x20000), _fake(0x30000),
                                    _fake(0x40000), _fake(0x50000), 0.1, ctypes.byref(f64), 2, 8, 128, 128, None, 0,
                                    _fake(0x80000), 4096, _fake(0x60000), _fake(0x70000), 1 << 30, None) == cq.CQ_ERR_UNSUPPORTED
+    # several query tokens over such caches: the workspace of the largest of the m single-token calls
+    assert cq.cq_chunk_rope_workspace_bytes(fmt, 2, 8, 3, 4096) == max(
+        cq.cq_decode_workspace_bytes(fmt, 2, 8, t, cq.cq_decode_rope_default_split(fmt, 2, 8, t)) for t in (4094, 4095, 4096))
+    assert cq.cq_chunk_rope_workspace_bytes(fmt, 2, 8, 5000, 4096) == 0 and cq.cq_chunk_rope_workspace_bytes(fmt, 2, 8, 3, 4096, 100) == 0
+
+    def chunk(m=3, t=128, ws_bytes=1 << 30, pos=4096, split=0):
+        return int(lib.cq_chunk_attention_rope(_fake(0x10000), _fake(0x20000), _fake(0x30000), _fake(0x40000), _fake(0x50000),
+                                               0.1, ctypes.byref(fmt._c()), 2, 8, m, t, 128, None, split, _fake(0x80000), pos,
+                                               _fake(0x60000), _fake(0x70000), ws_bytes, None))
+    assert chunk(m=0) == cq.CQ_ERR_INVALID_ARG and chunk(m=129) == cq.CQ_ERR_INVALID_ARG and chunk(pos=0) == cq.CQ_ERR_INVALID_ARG
+    assert chunk(split=100) == cq.CQ_ERR_INVALID_ARG and chunk(ws_bytes=16) == cq.CQ_ERR_WORKSPACE_TOO_SMALL
     assert cq.cq_decode_rope_default_split(cq.CQFormat(2, 8, 128, 32), 64, 32, 64 * 1000) == 64 * 125    # 8 balanced splits of at most 128 tiles (256 without the rotation)
 
 

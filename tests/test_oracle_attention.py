@@ -292,6 +292,25 @@ def test_chunk_attention_equals_torch_sdpa_with_a_causal_mask(Hq, Hkv):
     assert np.allclose(out, want.permute(0, 2, 1, 3).numpy(), rtol=1e-12, atol=1e-13)
 
 
+def test_chunk_attention_over_pre_rotation_keys_equals_torch_sdpa_over_rotated_keys():
+    # the keys rotated by hand (complex-number form) and a library attention with the causal mask
+    import torch
+    B, m, Hq, Hkv, d, T, c, b = 2, 5, 4, 2, 128, 19, 8, 4
+    q, kc, vc, ck, cv = _chunk_case(33, B, m, Hq, Hkv, d, T, c, b)
+    scale, base = 0.11, 10000.0
+    out = O.chunk_attention(q, kc, vc, ck, cv, scale, Hkv, rope_base=base)
+    khat = _dequant_np(kc, ck).reshape(B, T, Hkv, d)
+    krot = _rotate_complex(khat, np.arange(T)[None, :, None], base)
+    k = torch.from_numpy(krot).permute(0, 2, 1, 3).repeat_interleave(Hq // Hkv, dim=1)
+    v = torch.from_numpy(_dequant_np(vc, cv)).reshape(B, T, Hkv, d).permute(0, 2, 1, 3).repeat_interleave(Hq // Hkv, dim=1)
+    qt = torch.from_numpy(q.astype(np.float64)).permute(0, 2, 1, 3)
+    mask = torch.arange(T)[None, :] <= (T - m + torch.arange(m))[:, None]
+    want = torch.nn.functional.scaled_dot_product_attention(qt, k, v, attn_mask=mask, scale=scale)
+    assert np.allclose(out, want.permute(0, 2, 1, 3).numpy(), rtol=1e-11, atol=1e-12)
+    # and it is not the position-independent result
+    assert not np.allclose(out, O.chunk_attention(q, kc, vc, ck, cv, scale, Hkv), rtol=1e-3, atol=1e-3)
+
+
 def test_chunk_attention_special_cases():
     B, m, Hq, Hkv, d, T, c, b = 2, 5, 2, 2, 8, 11, 2, 3
     q, kc, vc, ck, cv = _chunk_case(32, B, m, Hq, Hkv, d, T, c, b)
