@@ -255,6 +255,24 @@ def test_decode_split_invariance_and_ragged_lengths(c, b):
         assert np.max(np.abs(o - outs[0])) <= 2e-3 * np.max(np.abs(outs[0]))
 
 
+@pytest.mark.parametrize("c,b", DECODE_FORMATS)
+@pytest.mark.parametrize("gain", [1e-3, 40.0])
+def test_decode_extreme_score_ranges(c, b, gain):
+    # scores spread over thousands of octaves (softmax close to an argmax; the running (maximum, sum)
+    # pairs of phase K see differences far beyond the exponent range of 2^x), and scores that are
+    # all but equal (uniform weights): one split and several, a ragged tail, a one-token sequence
+    hq, hkv, B, T, t_cap = 4, 2, 3, 3000, 3008
+    fmt, q, kc, vc, ck, cv = _attn_case(21, c, b, hq, hkv, B, T)
+    q = (q.astype(np.float32) * gain).astype(np.float16)
+    lens = np.array([3000, 1, 1999], dtype=np.int32)
+    ref = O.attention(q, kc, vc, ck, cv, 1.0, hkv, seq_lens=lens)
+    kcache, vcache = codes_to_cache(kc, fmt, t_cap), codes_to_cache(vc, fmt, t_cap)
+    for split in (0, 3008, 320):
+        out = gpu_attention(q, kcache, vcache, ck, cv, 1.0, fmt, T, t_cap, seq_lens=lens, tokens_per_split=split)
+        assert np.isfinite(out.astype(np.float64)).all()
+        check_attention(out, ref)
+
+
 def test_decode_1024_centroid_format_one_long_split():
     # CQ-8c10b keeps up to 24448 tokens per split on chip: 20000 tokens in one split, and in three
     c, b, hq, hkv, B, T, t_cap = 8, 10, 2, 1, 1, 20000, 20032
