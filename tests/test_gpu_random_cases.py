@@ -140,3 +140,58 @@ def test_random_valid_call_matches_oracle(i):
                else cq.cq_decode_attention(dev(q), kcache, vcache, dck, dcv, scale, fmt, T, t_cap, **kw))
     torch.cuda.synchronize()
     check_attention(out.cpu().numpy(), ref)
+
+
+ENCODE_FORMATS = FORMATS + [(1, 2), (2, 2), (1, 4), (2, 4), (4, 4)]
+
+
+@pytest.mark.parametrize("i", range(54))
+def test_random_valid_encode_matches_oracle(i):
+    """cq_encode / cq_encode_kv on strided inputs at random offsets, every format (the sub-byte
+    ones through their fused byte codes): the oracle's codes up to near ties, and no byte of any
+    other token touched."""
+    rng = np.random.default_rng(9000 + i)
+    c, b = ENCODE_FORMATS[i % len(ENCODE_FORMATS)]
+    hkv = int(rng.choice([1, 2, 3, 8]))
+    B = int(rng.integers(1, 4))
+    t_new = int(rng.choice([1, 2, 15, 16, 17, 31, 32, 33, 63, 64, 65, 200, int(rng.integers(1, 700))]))
+    t_off = int(rng.choice([0, 1, 63, 64, 100, int(rng.integers(0, 300))]))
+    t_cap = -(-(t_off + t_new) // 64) * 64 + 64 * int(rng.integers(0, 2))
+    both, pad, gap = bool(rng.random() < 0.5), int(rng.choice([0, 8, 64])), int(rng.choice([0, 3]))
+    fmt = cq.CQFormat(c, b, 128, hkv)
+    D = hkv * 128
+    rk, rv = synth.tensor_recipe(300 + i, 0, "k", D), synth.tensor_recipe(300 + i, 0, "v", D)
+    if b >= 8:
+        ck, cv = synth.sample_codebook(rk, c, b), synth.sample_codebook(rv, c, b)
+    else:
+        ck = (rng.standard_normal((D // c, 1 << b, c)) * 1.5).astype(np.float16)
+        cv = (rng.standard_normal((D // c, 1 << b, c)) * 1.5).astype(np.float16)
+    xk = np.stack([synth.sample_activations(rk, t_new, chunk=n) for n in range(B)])
+    xv = np.stack([synth.sample_activations(rv, t_new, chunk=50 + n) for n in range(B)])
+
+    def strided(x):                                 # rows and sequences further apart than they need to be
+        buf = torch.full((B, t_new + gap, D + pad), 7.0, dtype=torch.float16, device="cuda")
+        buf[:, :t_new, :D] = dev(x)
+        return buf[:, :t_new, :D]
+
+    fill = 0xA5
+    kcache = torch.full((cq.cq_cache_bytes(fmt, B, t_cap),), fill, dtype=torch.uint8, device="cuda")
+    vcache = torch.full_like(kcache, fill)
+    if both:
+        cq.cq_encode_kv(strided(xk), strided(xv), dev(ck), dev(cv), fmt, kcache, vcache, t_off, t_cap)
+    else:
+        cq.cq_encode(strided(xk), dev(ck), fmt, kcache, t_off, t_cap)
+        cq.cq_encode(strided(xv), dev(cv), fmt, vcache, t_off, t_cap)
+    torch.cuda.synchronize()
+    stored = fmt if b >= 8 else cq.cq_fused_format(fmt)         # the format of the bytes in the cache
+    untouched = np.ones(t_cap, dtype=bool)
+    untouched[t_off:t_off + t_new] = False
+    blank = cache_to_codes(torch.full_like(kcache, fill), stored, B, t_cap, t_cap)
+    for cache, x, cb in ((kcache, xk, ck), (vcache, xv, cv)):
+        codes = cache_to_codes(cache, stored, B, t_cap, t_new, t_off)
+        if b < 8:       # a byte holds the codes of 8 / b neighbouring groups, lowest group in the lowest bits
+            fuse = 8 // b
+            codes = np.stack([(codes >> (b * k)) & ((1 << b) - 1) for k in range(fuse)], axis=-1).reshape(B, t_new, -1)
+        for n in range(B):
+            check_codes(codes[n], x[n], cb)
+        assert np.array_equal(cache_to_codes(cache, stored, B, t_cap, t_cap)[:, untouched], blank[:, untouched])
