@@ -78,6 +78,8 @@ typedef struct cq_format {
 } cq_format;
 
 #define CQ_TILE_TOKENS 64
+/* size of the library's own scratch array (per GPU), used by cq_decode_attention_static only */
+#define CQ_STATIC_SCRATCH_BYTES (4u << 20)
 
 /* Library version, major * 10000 + minor * 100 + patch. */
 CQ_API int32_t cq_version(void);
@@ -171,6 +173,31 @@ CQ_API cq_status cq_decode_attention(const void *q,
                               const int32_t *seq_lens, int32_t tokens_per_split,
                               void *out, void *workspace, size_t workspace_bytes,
                               void *stream);
+
+/*
+ * cq_decode_attention_static -- cq_decode_attention for callers that cannot allocate device
+ * memory and have no workspace to pass: code under HIP graph capture, tight serving loops,
+ * harnesses that forbid allocation.  Same arguments, kernels and results (bit for bit) as
+ * cq_decode_attention, minus the workspace: the partial results of the context splits live in
+ * an array of CQ_STATIC_SCRATCH_BYTES (4 MiB) inside the library, which each GPU the library
+ * runs on holds until the process ends.  The call allocates and frees nothing; the first call
+ * on a device looks the array's address up once.
+ *   Limit: batch * n_q_heads * n_split * (2 + head_dim) * 4 bytes must fit the array (8065 rows
+ *   of (sequence, query head, split) at head_dim 128), else CQ_ERR_WORKSPACE_TOO_SMALL; a call
+ *   with one split uses none of it.
+ *   All calls on one GPU share the array: calls that may overlap on a GPU (different streams,
+ *   concurrently replayed graphs) race on it and must use cq_decode_attention with workspaces
+ *   of their own.  Nothing in the array has to start at zero and no call depends on what an
+ *   earlier one left there.
+ * Errors: as cq_decode_attention; CQ_ERR_HIP also when the array's address cannot be obtained.
+ */
+CQ_API cq_status cq_decode_attention_static(const void *q,
+                              const void *k_codes, const void *v_codes,
+                              const void *k_centroids, const void *v_centroids,
+                              float scale, const cq_format *fmt,
+                              int32_t batch, int32_t n_q_heads, int32_t t, int32_t t_cap,
+                              const int32_t *seq_lens, int32_t tokens_per_split,
+                              void *out, void *stream);
 
 /*
  * cq_decode_step -- one fused launch that equals cq_encode_kv of ONE new token per sequence

@@ -26,7 +26,7 @@ TILE_TOKENS = 64
 EXPORTS = (
     "cq_version", "cq_status_string", "cq_format_check", "cq_code_bytes_per_token_head",
     "cq_cache_bytes", "cq_encode", "cq_encode_kv", "cq_decode_default_split", "cq_decode_workspace_bytes",
-    "cq_decode_attention", "cq_decode_step", "cq_dequantize", "cq_paged_cache_bytes", "cq_encode_kv_paged",
+    "cq_decode_attention", "cq_decode_attention_static", "cq_decode_step", "cq_dequantize", "cq_paged_cache_bytes", "cq_encode_kv_paged",
     "cq_decode_attention_paged", "cq_decode_step_paged", "cq_kmeans_workspace_bytes", "cq_kmeans_fit",
     "cq_fused_format", "cq_expand_codebook", "cq_chunk_default_split", "cq_chunk_workspace_bytes", "cq_chunk_attention", "cq_chunk_attention_paged",
     "cq_layer_table_bytes", "cq_layer_table_fill", "cq_decode_step_layers",
@@ -116,6 +116,9 @@ def load() -> ctypes.CDLL:
     lib.cq_decode_attention.restype = ctypes.c_int
     lib.cq_decode_attention.argtypes = [vp, vp, vp, vp, vp, ctypes.c_float, fp, i32, i32, i32, i32,
                                         vp, i32, vp, vp, ctypes.c_size_t, vp]
+    lib.cq_decode_attention_static.restype = ctypes.c_int
+    lib.cq_decode_attention_static.argtypes = [vp, vp, vp, vp, vp, ctypes.c_float, fp, i32, i32, i32, i32,
+                                               vp, i32, vp, vp]
     lib.cq_decode_step.restype = ctypes.c_int
     lib.cq_decode_step.argtypes = [vp, vp, vp, i64, vp, vp, vp, vp, ctypes.c_float, fp, i32, i32, i32, i32,
                                    vp, i32, vp, vp, ctypes.c_size_t, vp]
@@ -370,6 +373,54 @@ def prepare_decode_attention(q, k_codes, v_codes, k_centroids, v_centroids, scal
             tokens_per_split, out.data_ptr(), workspace.data_ptr(), workspace.numel())
     keep = (q, k_codes, v_codes, k_centroids, v_centroids, seq_lens, out, workspace, f)
     return PreparedCall(load().cq_decode_attention, args, keep, "cq_decode_attention"), out
+
+
+STATIC_SCRATCH_BYTES = 4 << 20
+
+
+def prepare_decode_attention_static(q, k_codes, v_codes, k_centroids, v_centroids, scale: float, fmt: CQFormat,
+                                    t: int, t_cap: int, out, seq_lens=None, tokens_per_split: int = 0):
+    """Check and marshal the arguments of cq_decode_attention_static once (the caller brings
+    `out`; nothing is allocated here or in the call).  Returns the call."""
+    import torch
+    _dev(q, torch.float16, "q")
+    _dev(k_codes, torch.uint8, "k_codes")
+    _dev(v_codes, torch.uint8, "v_codes")
+    _dev(k_centroids, torch.float16, "k_centroids")
+    _dev(v_centroids, torch.float16, "v_centroids")
+    _dev(out, torch.float16, "out")
+    if q.dim() != 3 or not q.is_contiguous() or q.shape[2] != fmt.head_dim:
+        raise ValueError("q must be contiguous [B, Hq, head_dim]")
+    for name, cb in (("k_centroids", k_centroids), ("v_centroids", v_centroids)):
+        if not cb.is_contiguous() or tuple(cb.shape) != (fmt.groups, 1 << fmt.b, fmt.c):
+            raise ValueError(f"{name} must be contiguous [G, 2^b, c]")
+    batch, n_q_heads = int(q.shape[0]), int(q.shape[1])
+    need_cache = cq_cache_bytes(fmt, batch, t_cap)
+    if k_codes.numel() < need_cache or v_codes.numel() < need_cache:
+        raise ValueError("code caches are smaller than cq_cache_bytes(fmt, batch, t_cap)")
+    if tuple(out.shape) != (batch, n_q_heads, fmt.head_dim) or not out.is_contiguous():
+        raise ValueError("out must be contiguous [B, Hq, head_dim]")
+    sl_ptr = None
+    if seq_lens is not None:
+        _dev(seq_lens, torch.int32, "seq_lens")
+        if tuple(seq_lens.shape) != (batch,) or not seq_lens.is_contiguous():
+            raise ValueError("seq_lens must be contiguous int32 [B]")
+        sl_ptr = seq_lens.data_ptr()
+    f = fmt._c()
+    args = (q.data_ptr(), k_codes.data_ptr(), v_codes.data_ptr(), k_centroids.data_ptr(),
+            v_centroids.data_ptr(), float(scale), ctypes.byref(f), batch, n_q_heads, t, t_cap, sl_ptr,
+            tokens_per_split, out.data_ptr())
+    keep = (q, k_codes, v_codes, k_centroids, v_centroids, seq_lens, out, f)
+    return PreparedCall(load().cq_decode_attention_static, args, keep, "cq_decode_attention_static")
+
+
+def cq_decode_attention_static(q, k_codes, v_codes, k_centroids, v_centroids, scale: float, fmt: CQFormat,
+                               t: int, t_cap: int, out, seq_lens=None, tokens_per_split: int = 0, stream=None):
+    """cq_decode_attention without a workspace (the library's static scratch array holds the
+    partial results); `out` fp16 [B, Hq, head_dim] is the caller's."""
+    prepare_decode_attention_static(q, k_codes, v_codes, k_centroids, v_centroids, scale, fmt, t, t_cap, out,
+                                    seq_lens, tokens_per_split)(stream)
+    return out
 
 
 def cq_decode_attention(q, k_codes, v_codes, k_centroids, v_centroids, scale: float, fmt: CQFormat,

@@ -8,6 +8,12 @@
 
 #include "cq_internal.hpp"
 
+// Scratch of cq_decode_attention_static: the partial results of the context splits, for callers
+// that cannot pass (or allocate) a workspace.  Every GPU the library runs on holds its own copy
+// of the array for the life of the process.  In host code the name below is only a stand-in
+// for the symbol: the array's device address is looked up once per device (StaticScratch).
+static __device__ __align__(256) unsigned char scratch[CQ_STATIC_SCRATCH_BYTES];
+
 namespace cq {
 
 cq_status derive(const cq_format* fmt, Derived* out)
@@ -60,6 +66,32 @@ cq_status derive_any(const cq_format* fmt, Derived* out)
 namespace {
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+// Device address of `scratch` on the current device: asked for on the first use on each
+// device (with that device current) and kept; host code passes this pointer, never the
+// array's name, to kernels.
+struct StaticScratch {
+    static constexpr int kMaxDevices = 64;
+    std::once_flag once[kMaxDevices];
+    hipError_t result[kMaxDevices];
+    void* ptr[kMaxDevices];
+    hipError_t get(void** out)
+    {
+        int dev = 0;
+        const hipError_t e = hipGetDevice(&dev);
+        if (e != hipSuccess) return e;
+        if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+        std::call_once(once[dev], [&] {
+            void* p = nullptr;
+            result[dev] = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+            ptr[dev] = p;
+        });
+        if (result[dev] != hipSuccess || !ptr[dev]) return result[dev] != hipSuccess ? result[dev] : hipErrorInvalidSymbol;
+        *out = ptr[dev];
+        return hipSuccess;
+    }
+};
+StaticScratch g_static_scratch;
 
 int default_tiles_per_split(const Derived& f, int batch, int n_q_heads, int t, int max_tiles)
 {
@@ -400,12 +432,19 @@ cq_status decode_common(const void* q, const void* x_k_new, const void* x_v_new,
                         const int32_t* seq_lens, int32_t tokens_per_split,
                         void* out, void* workspace, size_t workspace_bytes, void* stream, bool step,
                         const void* rope_table = nullptr, int32_t rope_positions = 0,
-                        const LayerPtrs* layers = nullptr, int32_t n_layers = 1, const TokenView* view = nullptr)
+                        const LayerPtrs* layers = nullptr, int32_t n_layers = 1, const TokenView* view = nullptr,
+                        bool static_scratch = false)
 {
     Derived f;
     cq_status st = derive(fmt, &f);
     if (st != CQ_OK) return st;
     const bool rope = rope_positions != 0;
+    // the library's own scratch array takes the workspace's place (its address is only looked up
+    // once every check below has passed); until then a stand-in keeps the checks uniform
+    if (static_scratch) {
+        workspace = reinterpret_cast<void*>(uintptr_t{256});
+        workspace_bytes = CQ_STATIC_SCRATCH_BYTES;
+    }
     if (rope && f.head_dim != 128) return CQ_ERR_UNSUPPORTED;
     CacheMap map;
     if (pages) {
@@ -442,6 +481,7 @@ cq_status decode_common(const void* q, const void* x_k_new, const void* x_v_new,
     const size_t need = sizeof(float) * (size_t)batch * n_q_heads * n_split * (f.head_dim + kPartialHeader) * n_layers;
     if (workspace_bytes < need) return CQ_ERR_WORKSPACE_TOO_SMALL;
     if ((int64_t)batch * n_q_heads * n_split * n_layers > 0x7fffffffLL) return CQ_ERR_INVALID_ARG;
+    if (static_scratch && g_static_scratch.get(&workspace) != hipSuccess) return CQ_ERR_HIP;
 
     DecodeArgs a;
     a.layers = layers;
@@ -486,6 +526,18 @@ cq_status cq_decode_attention(const void* q, const void* k_codes, const void* v_
     return decode_common(q, nullptr, nullptr, 0, k_codes, v_codes, k_centroids, v_centroids, scale, fmt, batch,
                          n_q_heads, t, t_cap, nullptr, seq_lens, tokens_per_split, out, workspace, workspace_bytes, stream,
                          false);
+}
+
+cq_status cq_decode_attention_static(const void* q, const void* k_codes, const void* v_codes,
+                                     const void* k_centroids, const void* v_centroids,
+                                     float scale, const cq_format* fmt,
+                                     int32_t batch, int32_t n_q_heads, int32_t t, int32_t t_cap,
+                                     const int32_t* seq_lens, int32_t tokens_per_split,
+                                     void* out, void* stream)
+{
+    return decode_common(q, nullptr, nullptr, 0, k_codes, v_codes, k_centroids, v_centroids, scale, fmt, batch,
+                         n_q_heads, t, t_cap, nullptr, seq_lens, tokens_per_split, out, nullptr, 0, stream,
+                         false, nullptr, 0, nullptr, 1, nullptr, true);
 }
 
 cq_status cq_decode_attention_paged(const void* q, const void* k_pool, const void* v_pool,

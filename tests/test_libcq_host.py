@@ -114,6 +114,33 @@ def test_decode_rejects_bad_arguments_without_launching():
     assert _decode(cq.CQFormat(8, 7, 128, 4)) == cq.CQ_ERR_UNSUPPORTED
 
 
+def _decode_static(fmt, batch=2, hq=8, t=128, t_cap=128, split=0, ptrs=None, scale=0.1):
+    f = fmt._c()
+    p = dict(q=0x10000, kc=0x20000, vc=0x30000, ck=0x40000, cv=0x50000, out=0x60000)
+    p.update(ptrs or {})
+    return int(cq.load().cq_decode_attention_static(_fake(p["q"]), _fake(p["kc"]), _fake(p["vc"]), _fake(p["ck"]),
+                                                    _fake(p["cv"]), scale, ctypes.byref(f), batch, hq, t, t_cap, None,
+                                                    split, _fake(p["out"]), None))
+
+
+def test_static_scratch_decode_rejects_bad_arguments_and_sizes_without_launching():
+    fmt = cq.CQFormat(8, 8, 128, 4)
+    E = cq.CQ_ERR_INVALID_ARG
+    for k in ("q", "kc", "vc", "ck", "cv", "out"):
+        assert _decode_static(fmt, ptrs={k: 0}) == E, k
+    assert _decode_static(fmt, hq=6) == E
+    assert _decode_static(fmt, t=0) == E
+    assert _decode_static(fmt, split=100) == E
+    assert _decode_static(cq.CQFormat(8, 7, 128, 4)) == cq.CQ_ERR_UNSUPPORTED
+    # partials beyond the 4 MiB array: 8066 rows of (2 + 128) floats do not fit, 8065 do (checked
+    # through the size rule only: a fitting call would go on to launch)
+    assert cq.STATIC_SCRATCH_BYTES == 4 << 20
+    assert cq.STATIC_SCRATCH_BYTES // (130 * 4) == 8065
+    big = cq.CQFormat(8, 8, 128, 32)
+    assert _decode_static(big, batch=64, hq=32, t=4096, t_cap=4096, split=512) == cq.CQ_ERR_WORKSPACE_TOO_SMALL
+    assert _decode_static(big, batch=1, hq=32, t=64 * 253, t_cap=64 * 253, split=64) == cq.CQ_ERR_WORKSPACE_TOO_SMALL
+
+
 def test_workspace_size_matches_the_split_arithmetic():
     fmt = cq.CQFormat(8, 8, 128, 32)
     # explicit split: ceil(t / split) partials of (2 + head_dim) floats per (sequence, query head)
