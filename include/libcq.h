@@ -154,8 +154,9 @@ CQ_API size_t cq_decode_workspace_bytes(const cq_format *fmt, int32_t batch, int
  *   tokens_per_split  0 = library default; otherwise a multiple of 64: each workgroup handles
  *                     that many tokens of one (sequence, query head) and a second kernel merges
  *                     the partial softmax results (exact rescaling by the running maximum);
- *                     at most 12288 / 8192 / 16384 / 24448 tokens for CQ-8c8b / 4c8b / 2c8b /
- *                     8c10b (the scores of a split stay on chip)
+ *                     CQ-8c8b / 4c8b: any length (a workgroup walks its split in chunks of
+ *                     8192 tokens with one score table); CQ-2c8b: at most 8192 tokens,
+ *                     CQ-8c10b: at most 16384 (one chunk, whose scores stay in registers)
  *   out               device, fp16 [batch][n_q_heads][head_dim]
  *   workspace         device scratch of at least cq_decode_workspace_bytes(...) bytes; contents
  *                     need not be initialised and are overwritten

@@ -95,14 +95,13 @@ StaticScratch g_static_scratch;
 
 int default_tiles_per_split(const Derived& f, int batch, int n_q_heads, int t, int max_tiles)
 {
-    // A workgroup costs its tiles plus a fixed part (table build, reductions, bins x centroids:
-    // each reads a whole head's codebook), here expressed in tiles of streaming time; the chip
-    // runs `slots` workgroups at a time (two per CU; one for the 1024-centroid format), in
-    // rounds.  Take the number of splits that minimises rounds x (tiles + fixed) over the
-    // splits the on-chip score buffer allows, down to 16 tiles per split.
+    // A workgroup costs its tiles plus a fixed part (table build, bins x centroids: each reads a
+    // whole head's codebook), here expressed in tiles of streaming time; the chip runs `slots`
+    // workgroups at a time (two per CU), in rounds.  Take the number of splits that minimises
+    // rounds x (tiles + fixed) over the splits the kernel allows, down to 16 tiles per split.
     const int n_tiles = (t + kTileTokens - 1) / kTileTokens;
     const long bh = (long)batch * n_q_heads;
-    const long slots = f.b == 10 ? 256 : 512;
+    const long slots = 512;
     const long fixed = f.b == 10 ? 180 : (f.gh == 16 ? 60 : (f.gh == 32 ? 30 : 15));
     const long ns_min = (n_tiles + max_tiles - 1) / max_tiles;
     const long ns_max = std::max<long>(ns_min, n_tiles / 16);

@@ -246,7 +246,7 @@ def test_decode_split_invariance_and_ragged_lengths(c, b):
     ref = O.attention(q, kc, vc, ck, cv, scale, hkv, seq_lens=lens)
     kcache, vcache = codes_to_cache(kc, fmt, t_cap), codes_to_cache(vc, fmt, t_cap)
     outs = []
-    for split in (0, 64, 448, 4032, 7936 if b != 10 else 24448):
+    for split in (0, 64, 448, 4032, 7936 if b != 10 else 16384):
         out = gpu_attention(q, kcache, vcache, ck, cv, scale, fmt, T, t_cap, seq_lens=lens, tokens_per_split=split)
         check_attention(out, ref)
         outs.append(out.astype(np.float64))
@@ -274,43 +274,71 @@ def test_decode_extreme_score_ranges(c, b, gain):
 
 
 def test_decode_1024_centroid_format_one_long_split():
-    # CQ-8c10b keeps up to 24448 tokens per split on chip: 20000 tokens in one split, and in three
-    c, b, hq, hkv, B, T, t_cap = 8, 10, 2, 1, 1, 20000, 20032
+    # CQ-8c10b scores up to 16384 tokens per split (one chunk of 32 tiles per wavefront): 16000 tokens
+    # in one split, and in two
+    c, b, hq, hkv, B, T, t_cap = 8, 10, 2, 1, 1, 16000, 16000
     fmt, q, kc, vc, ck, cv = _attn_case(11, c, b, hq, hkv, B, T)
     ref = O.attention(q, kc, vc, ck, cv, 0.1, hkv)
     kcache, vcache = codes_to_cache(kc, fmt, t_cap), codes_to_cache(vc, fmt, t_cap)
-    for split in (24448, 8064, 0):
+    for split in (16384, 8064, 0):
         out = gpu_attention(q, kcache, vcache, ck, cv, 0.1, fmt, T, t_cap, tokens_per_split=split)
         check_attention(out, ref)
-    assert cq.cq_decode_workspace_bytes(fmt, B, hq, T, 24448 + 64) == 0        # beyond the on-chip buffer
+    assert cq.cq_decode_workspace_bytes(fmt, B, hq, T, 16384 + 64) == 0        # beyond one chunk
+    assert cq.cq_decode_workspace_bytes(cq.CQFormat(2, 8, 128, 1), B, hq, T, 8192 + 64) == 0
 
 
-def test_decode_cq8c8b_splits_beyond_8192_tokens_use_the_table_without_replicas():
-    # 16 groups per head: up to 8192 tokens per split the table has two columns per group, beyond
-    # (to 12288) one; both against the oracle, and the fused step in the long form bit for bit
-    c, b, hq, hkv, B, T, t_cap = 8, 8, 2, 1, 2, 12200, 12288
-    fmt, q, kc, vc, ck, cv = _attn_case(12, c, b, hq, hkv, B, T)
-    lens = np.array([12200, 9000], dtype=np.int32)
-    ref = O.attention(q, kc, vc, ck, cv, 0.1, hkv, seq_lens=lens)
+def test_decode_long_splits_walk_several_chunks():
+    # 16 / 32 groups per head: a workgroup walks its split in chunks of 8192 tokens with one score
+    # table; splits of one chunk, of two and a bit, and the whole 40000-token context in one split,
+    # against the oracle, and the fused step over a five-chunk split bit for bit
+    for c, b in ((8, 8), (4, 8)):
+        hq, hkv, B, T, t_cap = 2, 1, 2, 40000, 40064
+        fmt, q, kc, vc, ck, cv = _attn_case(12, c, b, hq, hkv, B, T)
+        lens = np.array([40000, 9000], dtype=np.int32)
+        ref = O.attention(q, kc, vc, ck, cv, 0.1, hkv, seq_lens=lens)
+        kcache, vcache = codes_to_cache(kc, fmt, t_cap), codes_to_cache(vc, fmt, t_cap)
+        for split in (8192, 8256, 10944, 12288, 20032, 32768, 40064):
+            out = gpu_attention(q, kcache, vcache, ck, cv, 0.1, fmt, T, t_cap, seq_lens=lens, tokens_per_split=split)
+            check_attention(out, ref)
+        x1k = np.concatenate([synth.sample_activations(synth.tensor_recipe(32, 0, "k", 128), 1, chunk=n) for n in range(B)])
+        x1v = np.concatenate([synth.sample_activations(synth.tensor_recipe(32, 0, "v", 128), 1, chunk=n) for n in range(B)])
+        k2, v2 = kcache.clone(), vcache.clone()
+        per_seq = kcache.numel() // B
+        for n in range(B):
+            sl = slice(n * per_seq, (n + 1) * per_seq)
+            cq.cq_encode_kv(dev(x1k[n].copy().reshape(1, 1, -1)), dev(x1v[n].copy().reshape(1, 1, -1)), dev(ck), dev(cv), fmt, k2[sl], v2[sl],
+                            int(lens[n]) - 1, t_cap)
+        want = cq.cq_decode_attention(dev(q), k2, v2, dev(ck), dev(cv), 0.1, fmt, T, t_cap, seq_lens=dev(lens), tokens_per_split=40064)
+        got = cq.cq_decode_step(dev(q), dev(x1k), dev(x1v), kcache, vcache, dev(ck), dev(cv), 0.1, fmt, T, t_cap, seq_lens=dev(lens),
+                                tokens_per_split=40064)
+        torch.cuda.synchronize()
+        assert torch.equal(kcache, k2) and torch.equal(vcache, v2)
+        assert torch.equal(got.view(torch.int16), want.view(torch.int16))
+
+
+@pytest.mark.parametrize("order", ["ascending", "descending", "spike_late"])
+def test_decode_chunks_whose_scores_grow_or_shrink_along_the_context(order):
+    # The bins keep one fixed-point scale across the chunks of a split; it is set from the first
+    # chunk and lowered (all bins shifted right) when later chunks would overflow it.  Tokens sorted
+    # by score force both extremes: ascending, every chunk outweighs all chunks before it (a shift
+    # per chunk, earlier bins fade out); descending, later chunks round to nothing; and one token
+    # that outweighs everything, late in the context.  One split = five chunks, and three splits.
+    c, b, hq, hkv, B, T, t_cap = 8, 8, 1, 1, 1, 36000, 36032
+    fmt, q, kc, vc, ck, cv = _attn_case(13, c, b, hq, hkv, B, T)
+    q = (q.astype(np.float32) * 6.0).astype(np.float16)
+    _, scores = O.attention(q, kc, vc, ck, cv, 1.0, hkv, want_scores=True)
+    perm = np.argsort(scores[0, 0])
+    if order == "descending":
+        perm = perm[::-1]
+    elif order == "spike_late":
+        perm = np.concatenate([np.random.default_rng(5).permutation(perm[:-1])[:30000], perm[-1:],
+                               np.random.default_rng(5).permutation(perm[:-1])[30000:]])
+    kc, vc = np.ascontiguousarray(kc[:, perm]), np.ascontiguousarray(vc[:, perm])
+    ref = O.attention(q, kc, vc, ck, cv, 1.0, hkv)
     kcache, vcache = codes_to_cache(kc, fmt, t_cap), codes_to_cache(vc, fmt, t_cap)
-    for split in (8192, 8256, 10944, 12288):
-        out = gpu_attention(q, kcache, vcache, ck, cv, 0.1, fmt, T, t_cap, seq_lens=lens, tokens_per_split=split)
+    for split in (36032, 12032):
+        out = gpu_attention(q, kcache, vcache, ck, cv, 1.0, fmt, T, t_cap, tokens_per_split=split)
         check_attention(out, ref)
-    assert cq.cq_decode_workspace_bytes(fmt, B, hq, T, 12288 + 64) == 0
-    x1k = np.concatenate([synth.sample_activations(synth.tensor_recipe(32, 0, "k", 128), 1, chunk=n) for n in range(B)])
-    x1v = np.concatenate([synth.sample_activations(synth.tensor_recipe(32, 0, "v", 128), 1, chunk=n) for n in range(B)])
-    k2, v2 = kcache.clone(), vcache.clone()
-    per_seq = kcache.numel() // B
-    for n in range(B):
-        sl = slice(n * per_seq, (n + 1) * per_seq)
-        cq.cq_encode_kv(dev(x1k[n].copy().reshape(1, 1, -1)), dev(x1v[n].copy().reshape(1, 1, -1)), dev(ck), dev(cv), fmt, k2[sl], v2[sl],
-                        int(lens[n]) - 1, t_cap)
-    want = cq.cq_decode_attention(dev(q), k2, v2, dev(ck), dev(cv), 0.1, fmt, T, t_cap, seq_lens=dev(lens), tokens_per_split=12288)
-    got = cq.cq_decode_step(dev(q), dev(x1k), dev(x1v), kcache, vcache, dev(ck), dev(cv), 0.1, fmt, T, t_cap, seq_lens=dev(lens),
-                            tokens_per_split=12288)
-    torch.cuda.synchronize()
-    assert torch.equal(kcache, k2) and torch.equal(vcache, v2)
-    assert torch.equal(got.view(torch.int16), want.view(torch.int16))
 
 
 def test_decode_single_token_returns_the_dequantized_value_bit_exactly():

@@ -108,7 +108,8 @@ def test_decode_rejects_bad_arguments_without_launching():
     assert _decode(fmt, t_cap=96, t=64) == E
     assert _decode(fmt, split=100) == E                    # not a multiple of 64
     assert _decode(fmt, split=-64) == E
-    assert _decode(fmt, split=64 * 1000) == E              # beyond the on-chip score buffer
+    assert _decode(cq.CQFormat(2, 8, 128, 4), split=64 * 129) == E      # beyond one chunk of scores (64 groups per head)
+    assert _decode(cq.CQFormat(8, 10, 128, 4), split=64 * 257) == E     # ... (1024 centroids)
     assert _decode(fmt, scale=float("nan")) == E
     assert _decode(fmt, ws_bytes=16) == cq.CQ_ERR_WORKSPACE_TOO_SMALL
     assert _decode(cq.CQFormat(8, 7, 128, 4)) == cq.CQ_ERR_UNSUPPORTED
@@ -378,7 +379,7 @@ def test_subbyte_formats_sizes_and_argument_checks_without_launching():
 def test_default_split_is_balanced_within_the_on_chip_limits_and_fills_the_chip():
     import numpy as np
     rng = np.random.default_rng(11)
-    limit = {(8, 8): 12288, (4, 8): 8192, (2, 8): 16384, (8, 10): 24448}
+    limit = {(8, 8): 1 << 26, (4, 8): 1 << 26, (2, 8): 8192, (8, 10): 16384}
     for _ in range(300):
         c, b = [(8, 8), (4, 8), (2, 8), (8, 10)][int(rng.integers(0, 4))]
         hkv = int(rng.choice([1, 2, 8, 32]))
@@ -395,6 +396,6 @@ def test_default_split_is_balanced_within_the_on_chip_limits_and_fills_the_chip(
         assert cq.cq_decode_workspace_bytes(fmt, B, hq, T) == 4 * B * hq * n_split * 130
     # the named workloads
     assert cq.cq_decode_default_split(cq.CQFormat(4, 8, 128, 32), 16, 32, 4096) == 4096        # one split, no merge
-    assert cq.cq_decode_default_split(cq.CQFormat(8, 8, 128, 32), 4, 32, 131072) == 10944      # 12 x 171 tiles: 3 rounds of 512
+    assert cq.cq_decode_default_split(cq.CQFormat(8, 8, 128, 32), 4, 32, 131072) == 32768      # 4 x 512 tiles: all 512 workgroups at once
     assert cq.cq_decode_default_split(cq.CQFormat(8, 10, 128, 8), 32, 32, 16384) == 16384
     assert cq.cq_decode_default_split(cq.CQFormat(8, 8, 128, 32), 1, 32, 131072) == 8192       # 16 splits fill the chip once
