@@ -508,6 +508,7 @@ cq_status decode_common(const void* q, const void* x_k_new, const void* x_v_new,
     a.out_batch_stride = view ? view->out_batch_stride : (int64_t)n_q_heads * f.head_dim;
     a.seq_len_shift = view ? view->seq_len_shift : 0;
     a.seq_len_floor = view ? view->seq_len_floor : 1;
+    a.merge_counters = nullptr;
     a.f = f;
     if (rope) return launch_decode_rope(a, static_cast<const float*>(rope_table), rope_positions, static_cast<hipStream_t>(stream));
     return launch_decode(a, static_cast<hipStream_t>(stream));

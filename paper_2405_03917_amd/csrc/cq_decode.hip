@@ -37,6 +37,9 @@
 
 #include "cq_decode_common.hpp"
 
+// arrival counters of the in-kernel merge (see MergeCounters); 512 KB per GPU
+static __device__ __align__(256) unsigned merge_counters[16 * 8192];
+
 namespace cq {
 namespace {
 
@@ -46,6 +49,9 @@ constexpr int kDecodeWaves = kDecodeThreads / 64;
 // b = 10: 32 (one chunk must hold the longest split, 16384 tokens), and 16 for splits that fit
 constexpr int kChunkTiles8 = 16;
 constexpr int kChunkTiles10 = 32;
+constexpr int kMergeRows = 8192;        // arrival counters per set (rows of one launch)
+constexpr int kMergeSets = 16;          // sets (streams served) per device
+static_assert(sizeof(merge_counters) == sizeof(unsigned) * kMergeRows * kMergeSets, "size of the counter array");
 
 // LayerPtrs as the kernel reads it.  A pointer read from memory could point anywhere (LDS,
 // scratch) as far as the compiler knows, and every access through it would be a flat instruction,
@@ -138,6 +144,44 @@ __device__ __forceinline__ DecodeArgs early_args(const DecodeArgs& in)
         a.x_new_stride = early(in.x_new_stride);
     }
     return a;
+}
+
+// Merge the partials of all splits of one (sequence, query head): one pass with a running
+// maximum (the usual rescaling), so that no load waits for a value computed from another and
+// the loads of all splits go out together; then one rounding to fp16.  A split beyond its
+// sequence left m = -inf, l = 0, o = 0 and gets weight 0.  DEVICE_LOADS: the partials were
+// written by other workgroups of the running kernel: read them with device-scope loads.
+template <bool DEVICE_LOADS>
+__device__ __forceinline__ float partial_load(const float* p)
+{
+    if constexpr (DEVICE_LOADS) return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    else return *p;
+}
+template <bool DEVICE_LOADS>
+__device__ __forceinline__ void merge_splits(const float* p, int n_split, int head_dim, uint16_t* out, int tid, int nt)
+{
+    const int stride = head_dim + kPartialHeader;
+    for (int i = tid; i < head_dim; i += nt) {
+        float m = -INFINITY, l = 0.f, o = 0.f;
+#pragma unroll 4
+        for (int s = 0; s < n_split; ++s) {
+            const float ms = partial_load<DEVICE_LOADS>(p + s * stride), ls = partial_load<DEVICE_LOADS>(p + s * stride + 1),
+                        os = partial_load<DEVICE_LOADS>(p + s * stride + kPartialHeader + i);
+            const float m_new = fmaxf(m, ms);
+            const float m_safe = m_new == -INFINITY ? 0.f : m_new;
+            const float keep = __builtin_amdgcn_exp2f(m - m_safe), w = __builtin_amdgcn_exp2f(ms - m_safe);
+            l = __builtin_fmaf(l, keep, ls * w);
+            o = __builtin_fmaf(o, keep, os * w);
+            m = m_new;
+        }
+        const _Float16 h = (_Float16)(o / l);
+        out[i] = __builtin_bit_cast(uint16_t, h);
+    }
+}
+// (device-scope store: written through to where every workgroup's device-scope loads find it)
+__device__ __forceinline__ void partial_store(float* p, float v)
+{
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
 // ---- layout of the workgroup's LDS ---------------------------------------------------------
@@ -381,9 +425,34 @@ __global__ __launch_bounds__(kDecodeThreads, 4) void decode_split_kernel(DecodeA
     const int tile1 = min(tile0 + a.tiles_per_split, n_tiles);
 
     float* part = partials + ((size_t)(n * a.n_q_heads + hq) * a.n_split + split) * (D + kPartialHeader);
+    // The last split of a (sequence, query head) to finish merges them all (when the launch
+    // brought counters; else a merge kernel follows).  Partials are written with device-scope
+    // stores (write-through) and the merging workgroup reads them with device-scope loads, so
+    // no cache has to be written back or invalidated as a whole (a device-scope release fence
+    // per workgroup, which writes the whole L2 back, cost 50 us on a 90 us launch).  Order:
+    // every thread's stores are complete at the barrier (it waits for them), then one thread
+    // counts the workgroup in; the workgroup that counts the last split takes the counter back
+    // to zero for the next call and merges.
+    auto count_and_merge = [&] {
+        if (!a.merge_counters) return;
+        __syncthreads();
+        unsigned* flag = sums;
+        if (tid == 0) {
+            const size_t row = (size_t)(part - a.partials) / ((size_t)(D + kPartialHeader) * a.n_split);
+            const unsigned arrived = __hip_atomic_fetch_add(a.merge_counters + row, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            const bool last = arrived == (unsigned)a.n_split - 1u;
+            if (last) __hip_atomic_store(a.merge_counters + row, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            *flag = last;
+        }
+        __syncthreads();
+        if (!*flag) return;
+        merge_splits<true>(part - (size_t)split * (D + kPartialHeader), a.n_split, D,
+                           out_ptr + (size_t)n * out_batch_stride + (size_t)hq * D, tid, NT);
+    };
     if (tile0 >= tile1) {               // this split lies beyond the sequence: neutral partial
-        if (tid == 0) { part[0] = -INFINITY; part[1] = 0.f; }
-        for (int i = tid; i < D; i += NT) part[kPartialHeader + i] = 0.f;
+        if (tid == 0) { partial_store(part, -INFINITY); partial_store(part + 1, 0.f); }
+        for (int i = tid; i < D; i += NT) partial_store(part + kPartialHeader + i, 0.f);
+        count_and_merge();
         return;
     }
 
@@ -858,18 +927,19 @@ __global__ __launch_bounds__(kDecodeThreads, 4) void decode_split_kernel(DecodeA
 #pragma unroll
     for (int w = 0; w < NW; ++w) l_fix += sums[w];
     const float l = (float)l_fix * unit;
-    const bool direct = a.n_split == 1;             // a single split needs no merge kernel
+    const bool direct = a.n_split == 1;             // a single split needs no merge
     if (tid == 0 && !direct) {
-        part[0] = m_run;
-        part[1] = l;
+        partial_store(part, m_run);
+        partial_store(part + 1, l);
     }
     for (int chn = tid; chn < D; chn += NT) {
         float o = 0.f;
 #pragma unroll
         for (int w = 0; w < NW; ++w) o += scr[64 + w * D + chn];
         if (direct) out_ptr[(size_t)n * out_batch_stride + (size_t)hq * D + chn] = __builtin_bit_cast(uint16_t, (_Float16)(o / l));
-        else part[kPartialHeader + chn] = o;
+        else partial_store(part + kPartialHeader + chn, o);
     }
+    if (!direct) count_and_merge();
 }
 
 // Merge the partials of all splits of one (sequence, query head): rescaling to the running
@@ -886,25 +956,56 @@ __global__ void decode_merge_kernel(const float* partials, uint16_t* out, int n_
         out = layers[layer].out;
     }
     out += (size_t)(bh / n_q_heads) * out_batch_stride + (size_t)(bh % n_q_heads) * head_dim;
-    // One pass with a running maximum (the usual rescaling), so that no load waits for a value
-    // computed from another: the loads of all splits go out together.  A split beyond its
-    // sequence left m = -inf, l = 0, o = 0 and gets weight 0.
-    for (int i = threadIdx.x; i < head_dim; i += blockDim.x) {
-        float m = -INFINITY, l = 0.f, o = 0.f;
-#pragma unroll 4
-        for (int s = 0; s < n_split; ++s) {
-            const float ms = p[s * stride], ls = p[s * stride + 1], os = p[s * stride + kPartialHeader + i];
-            const float m_new = fmaxf(m, ms);
-            const float m_safe = m_new == -INFINITY ? 0.f : m_new;
-            const float keep = __builtin_amdgcn_exp2f(m - m_safe), w = __builtin_amdgcn_exp2f(ms - m_safe);
-            l = __builtin_fmaf(l, keep, ls * w);
-            o = __builtin_fmaf(o, keep, os * w);
-            m = m_new;
-        }
-        const _Float16 h = (_Float16)(o / l);
-        out[i] = __builtin_bit_cast(uint16_t, h);
-    }
+    merge_splits<false>(p, n_split, head_dim, out, threadIdx.x, blockDim.x);
 }
+
+// Arrival counters of the in-kernel merge: one per (sequence, query head) row of a launch.  They
+// start at zero (static storage) and every launch leaves them at zero, so they need no clearing;
+// what they need is that no two launches that can overlap share a set.  Launches on one stream
+// never overlap, so every stream gets a set of its own (the first kMergeSets streams that ask,
+// per device; a stream keeps its set).  A stream under graph capture gets none: replays of its
+// graph may run on other streams, at the same time as one another.  Whoever gets no set runs
+// the separate merge kernel instead.
+struct MergeCounters {
+    static constexpr int kMaxDevices = 64;
+    struct PerDevice {
+        std::mutex mu;
+        unsigned* base = nullptr;
+        bool failed = false;
+        hipStream_t streams[kMergeSets];
+        int n = 0;
+    };
+    PerDevice dev[kMaxDevices];
+
+    unsigned* for_stream(hipStream_t stream, int rows)
+    {
+        if (rows > kMergeRows) return nullptr;
+        hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
+        if (hipStreamIsCapturing(stream, &cap) != hipSuccess || cap != hipStreamCaptureStatusNone) {
+            (void)hipGetLastError();
+            return nullptr;
+        }
+        int d = 0;
+        if (hipGetDevice(&d) != hipSuccess || d < 0 || d >= kMaxDevices) return nullptr;
+        PerDevice& pd = dev[d];
+        std::lock_guard<std::mutex> lock(pd.mu);
+        if (pd.failed) return nullptr;
+        if (!pd.base) {
+            void* p = nullptr;
+            if (hipGetSymbolAddress(&p, HIP_SYMBOL(merge_counters)) != hipSuccess || !p) {
+                pd.failed = true;
+                return nullptr;
+            }
+            pd.base = static_cast<unsigned*>(p);
+        }
+        for (int i = 0; i < pd.n; ++i)
+            if (pd.streams[i] == stream) return pd.base + (size_t)i * kMergeRows;
+        if (pd.n == kMergeSets) return nullptr;
+        pd.streams[pd.n] = stream;
+        return pd.base + (size_t)(pd.n++) * kMergeRows;
+    }
+};
+MergeCounters g_merge_counters;
 
 template <int GH, int C, int B, int NS, bool STEP, bool LAYERS>
 cq_status launch_variant(const DecodeArgs& a, hipStream_t stream)
@@ -969,15 +1070,18 @@ int decode_max_tiles_per_split(const Derived& f)
     return 1 << 20;
 }
 
-cq_status launch_decode(const DecodeArgs& a, hipStream_t stream)
+cq_status launch_decode(const DecodeArgs& a_in, hipStream_t stream)
 {
+    DecodeArgs a = a_in;
+    const int rows = a.batch * a.n_q_heads;
+    const int all_rows = rows * (a.layers ? a.n_layers : 1);
+    a.merge_counters = a.n_split > 1 ? g_merge_counters.for_stream(stream, all_rows) : nullptr;
     // (a layer-batched launch is always a fused step: its table holds the new rows)
     const cq_status st = a.layers ? launch_format<true, true>(a, stream)
                          : a.xk_new ? launch_format<true, false>(a, stream) : launch_format<false, false>(a, stream);
-    if (st != CQ_OK || a.n_split == 1) return st;
+    if (st != CQ_OK || a.n_split == 1 || a.merge_counters) return st;
     const int threads = a.f.head_dim <= 64 ? 64 : (a.f.head_dim <= 128 ? 128 : 256);
-    const int rows = a.batch * a.n_q_heads;
-    hipLaunchKernelGGL(decode_merge_kernel, dim3((unsigned)(rows * (a.layers ? a.n_layers : 1))), dim3(threads), 0, stream,
+    hipLaunchKernelGGL(decode_merge_kernel, dim3((unsigned)all_rows), dim3(threads), 0, stream,
                        a.partials, a.out, a.n_split, a.f.head_dim, a.layers, rows, a.n_q_heads, a.out_batch_stride);
     if (hipGetLastError() != hipSuccess) return CQ_ERR_HIP;
     return CQ_OK;

@@ -121,6 +121,9 @@ struct DecodeArgs {
     // its partials follow those of the layers before it
     const LayerPtrs* layers;
     int n_layers, wgs_per_layer;
+    // arrival counters of the in-kernel merge, one per (sequence, query head) row (set by the
+    // launcher; null: the partials are merged by a kernel of their own)
+    unsigned* merge_counters;
     Derived f;
 };
 
