@@ -7,16 +7,21 @@ Workload (the second named configuration): CQ-4c8b (2 bits per channel) on a Lla
 KV cache -- 32 layers, batch 16, 32 heads x 128, context 4096, MHA.  One STEP is one decode step
 of the whole hot path over all 32 layers: per layer, encode the 16 new key rows and the 16 new
 value rows into cache position 4095 and attend over all 4096 cached tokens -- one fused
-cq_decode_step launch, bit-identical to cq_encode_kv followed by cq_decode_attention.  Every layer has its own codebooks, caches, queries and new rows (4 GiB of
-codes in total, far more than the 256 MB Infinity Cache, so code reads are real HBM reads).
+cq_decode_step launch, bit-identical to cq_encode_kv followed by cq_decode_attention.  Every layer
+has its own codebooks, caches, queries and new rows (4 GiB of codes in total, far more than the
+256 MB last-level cache, so code reads are real HBM reads).
 
 Inputs are synthetic and resident in HBM before the timed region: correlated-Gaussian K/V rows
 (synth/generator.py) drawn on the device and REALLY encoded with cq_encode to fill the caches.
 
-The timed region replays a HIP graph of the step (32 kernel launches) K times between two
-synchronisations.  After it, the same launches are run eagerly with a HIP event pair around
-every cq_decode_step call to obtain the kernel's own average duration (with a single context
-split, as here, that call is exactly one kernel).
+The timed region is K steps of 32 prepared calls in stream order, between two HIP events on the
+launching stream and a host clock on both sides of a synchronize (the headline).  The same K
+steps are also timed as replays of a captured HIP graph (reported beside it).
+
+`extra` holds the other four named configurations and the remaining entry points, each decode
+and encode entry with a `roofline` object of its own.  Every decode entry rotates over enough
+independent cache sets that consecutive launches touch more than the 256 MB last-level cache
+(`buffer_sets`, `cache_resident: false`).
 
 One JSON line is printed on stdout; progress goes to stderr.
 """
@@ -26,6 +31,7 @@ import argparse
 import json
 import math
 import os
+import re
 import sys
 import time
 
@@ -34,14 +40,57 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0          # MI355X published peak, GB/s
-# HBM bytes per launch of the fused decode-step kernel from rocprofv3 counters (FETCH_SIZE x 1.9998
-# + WRITE_SIZE, KiB per dispatch), see profiles/decode_step_kernel_cq4c8b_batch16_ctx4096.md
-TRAFFIC_BYTES_PER_LAUNCH = (67945.9 * 1.9998 + 192.0) * 1024
+LAST_LEVEL_CACHE_BYTES = 256e6
+# vector ALU: 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz lane-instructions per second (the published
+# 157.3 TFLOP/s of fp32 counts a packed FMA, 4 flops, per lane-instruction)
+VALU_PEAK_LANE_OPS = 256 * 4 * 16 * 2.4e9
+FP32_VECTOR_PEAK_TFLOPS = 157.3
+FP16_MFMA_PEAK_TFLOPS = 2500.0
 METRIC = "decode-attn KV tokens/s & achieved HBM GB/s (% peak); cq_encode tokens/s"
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "hbm_traffic_per_launch.txt")
 
 
 def log(*a):
     print(*a, file=sys.stderr, flush=True)
+
+
+def measured_traffic(kernel_key: str):
+    """HBM bytes per launch of a kernel from the committed rocprofv3 counter summary
+    (profiles/hbm_traffic_per_launch.txt: `key <tab> bytes <tab> provenance`), or None when the
+    file has no line for it."""
+    try:
+        with open(TRAFFIC_FILE) as f:
+            for line in f:
+                if line.startswith("#") or not line.strip():
+                    continue
+                parts = line.rstrip("\n").split("\t")
+                if len(parts) >= 2 and parts[0] == kernel_key:
+                    return float(parts[1])
+    except OSError:
+        pass
+    return None
+
+
+def hbm_roofline(kernel: str, traffic_key: str, code_bytes: int, ms: float, launches: int, **more):
+    achieved = code_bytes / (ms * 1e-3) / 1e9
+    r = {"bound": "hbm", "kernel": kernel, "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+         "frac": achieved / HBM_PEAK_GBPS, "traffic": measured_traffic(traffic_key),
+         "algorithmic_bytes_per_launch": code_bytes, "avg_launch_ms": ms, "launches_timed": launches}
+    r.update(more)
+    return r
+
+
+def encode_roofline(kernel: str, tokens: int, channels: int, n_centroids: int, ms: float, mfma: bool):
+    """cq_encode: D * 2^b (token channel, centroid) pairs per token.  The MFMA-filtered kernel spends
+    2.25 vector lane-instructions per (token, centroid) score (c channels each) on the running
+    maxima, the matrix cores do the multiply-adds; the direct kernel spends 2c + 3 per score."""
+    pairs = tokens * channels * n_centroids
+    t = ms * 1e-3
+    r = {"bound": "alu", "kernel": kernel, "unit": "T lane-instr/s", "peak": VALU_PEAK_LANE_OPS / 1e12,
+         "algorithmic_flops_per_token": 3 * channels * n_centroids,
+         "algorithmic_TFLOPs": 3 * pairs / t / 1e12, "fp32_vector_peak_TFLOPs": FP32_VECTOR_PEAK_TFLOPS,
+         "avg_launch_ms": ms}
+    return r, pairs / t
 
 
 class LayerState:
@@ -52,6 +101,7 @@ class LayerState:
 def build_workload(cq, synth, torch, cfg, n_layers, fill_chunk_tokens=16384):
     """Allocate and fill every layer's buffers.  Cache positions 0 .. T-2 come from encoding
     device-generated activations; the last position is written by the timed step itself."""
+    import numpy as np
     fmt = cq.CQFormat(cfg.c, cfg.b, cfg.head_dim, cfg.n_kv_heads)
     B, T, D = cfg.batch, cfg.context, cfg.kv_channels
     t_cap = (T + 63) // 64 * 64
@@ -80,7 +130,6 @@ def build_workload(cq, synth, torch, cfg, n_layers, fill_chunk_tokens=16384):
                     t0 += tn
                     del x
         st.q = dev(synth.sample_query(cfg.cfg_id, layer, B, cfg.n_q_heads, cfg.head_dim))
-        import numpy as np
         tnew = min(cfg.encode_tokens, T)
         st.xk_new = dev(np.stack([synth.sample_activations(rk, tnew, chunk=1000 + n) for n in range(B)]))
         st.xv_new = dev(np.stack([synth.sample_activations(rv, tnew, chunk=1000 + n) for n in range(B)]))
@@ -106,15 +155,11 @@ def prepare_calls(cq, fmt, cfg, t_cap, layers, scale):
                                             st.ck, st.cv, scale, fmt, T, t_cap, out=st.out, workspace=st.ws)
 
 
-def run_step(layers, events=None):
+def run_step(layers):
     """One decode step: per layer ONE cq_decode_step launch (encode the new K/V rows of the 16
     sequences into position T-1, then attend over all T positions)."""
-    for i, st in enumerate(layers):
-        if events is not None:
-            events[i][0].record()
+    for st in layers:
         st.step()
-        if events is not None:
-            events[i][1].record()
 
 
 def run_step_unfused(layers):
@@ -125,6 +170,7 @@ def run_step_unfused(layers):
 
 
 def time_calls(torch, fn, iters, warmup=2):
+    """Median and mean of `iters` calls of fn, each between its own HIP event pair."""
     for _ in range(warmup):
         fn()
     torch.cuda.synchronize()
@@ -138,76 +184,230 @@ def time_calls(torch, fn, iters, warmup=2):
     return ts[len(ts) // 2], sum(ts) / len(ts)
 
 
-def extra_measurements(cq, synth, torch):
-    """Decode attention at 1 bit per channel on a long context (CQ-8c8b, batch 4, 131072 tokens)
-    and prefill-sized cq_encode (32768 tokens): the cases the headline targets are quoted on."""
-    import numpy as np
-    out = {}
-    cfg = synth.CONFIGS[5]
-    fmt = cq.CQFormat(cfg.c, cfg.b, cfg.head_dim, cfg.n_kv_heads)
+def time_rotating(torch, calls, rounds, warmup=1):
+    """Mean duration (ms) of one call when the calls (one per buffer set) are launched round robin,
+    back to back, `rounds` times between ONE HIP event pair: launch-to-launch time, gaps included."""
+    for _ in range(warmup):
+        for c in calls:
+            c()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(rounds):
+        for c in calls:
+            c()
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) / (rounds * len(calls))
+
+
+def sets_beyond_cache(code_bytes):
+    """Buffer sets to rotate over so that a launch never finds its codes in the last-level cache:
+    the sets touched between two uses of one set must exceed the cache."""
+    return max(3, int(math.ceil(2.0 * LAST_LEVEL_CACHE_BYTES / code_bytes)) + 1)
+
+
+def fill_cache_set(cq, synth, torch, cfg, fmt, set_id, chunk_tokens):
+    """One set of device buffers of a configuration: codebooks (their own per set), K / V caches
+    filled by really encoding generated activations, queries, output, workspace."""
     B, T, D = cfg.batch, cfg.context, cfg.kv_channels
-    rk = synth.tensor_recipe(5, 0, "k", D)
-    rv = synth.tensor_recipe(5, 0, "v", D)
+    rk = synth.tensor_recipe(cfg.cfg_id, set_id, "k", D)
+    rv = synth.tensor_recipe(cfg.cfg_id, set_id, "v", D)
     ck = torch.from_numpy(synth.sample_codebook(rk, cfg.c, cfg.b)).cuda()
     cv = torch.from_numpy(synth.sample_codebook(rv, cfg.c, cfg.b)).cuda()
     kcache, vcache = cq.alloc_cache(fmt, B, T), cq.alloc_cache(fmt, B, T)
     per_seq = kcache.numel() // B
-    chunk = cfg.encode_tokens
-    enc_ms = None
     for n in range(B):
-        for t0 in range(0, T, chunk):
-            xk = synth.sample_activations_torch(rk, chunk, 31 * n + t0, "cuda").view(1, chunk, D)
-            xv = synth.sample_activations_torch(rv, chunk, 31 * n + t0 + 1, "cuda").view(1, chunk, D)
-            if enc_ms is None:      # time the 32768-token prefill encode once (per tensor)
-                enc_ms, _ = time_calls(torch, lambda: cq.cq_encode(xk, ck, fmt, kcache[:per_seq], 0, T), 5, 1)
-            cq.cq_encode(xk, ck, fmt, kcache[n * per_seq:(n + 1) * per_seq], t0, T)
-            cq.cq_encode(xv, cv, fmt, vcache[n * per_seq:(n + 1) * per_seq], t0, T)
+        for t0 in range(0, T, chunk_tokens):
+            tn = min(chunk_tokens, T - t0)
+            xk = synth.sample_activations_torch(rk, tn, 31 * n + t0, "cuda").view(1, tn, D)
+            xv = synth.sample_activations_torch(rv, tn, 31 * n + t0 + 1, "cuda").view(1, tn, D)
+            cq.cq_encode_kv(xk, xv, ck, cv, fmt, kcache[n * per_seq:(n + 1) * per_seq], vcache[n * per_seq:(n + 1) * per_seq], t0, T)
             del xk, xv
-    torch.cuda.synchronize()
-    out["encode_prefill"] = {"workload": "CQ-8c8b, 32768 tokens x 4096 channels, one tensor",
-                             "ms": enc_ms, "tokens_per_s": chunk / (enc_ms * 1e-3)}
-    q = torch.from_numpy(synth.sample_query(5, 0, B, cfg.n_q_heads, cfg.head_dim)).cuda()
-    o = torch.empty((B, cfg.n_q_heads, cfg.head_dim), dtype=torch.float16, device="cuda")
-    ws = torch.empty(cq.cq_decode_workspace_bytes(fmt, B, cfg.n_q_heads, T, 0), dtype=torch.uint8, device="cuda")
-    scale = 1.0 / math.sqrt(cfg.head_dim)
-    med, mean = time_calls(torch, lambda: cq.cq_decode_attention(q, kcache, vcache, ck, cv, scale, fmt, T, T,
-                                                                 out=o, workspace=ws), 20, 3)
+    q = torch.from_numpy(synth.sample_query(cfg.cfg_id, set_id, B, cfg.n_q_heads, cfg.head_dim)).cuda()
+    out = torch.empty((B, cfg.n_q_heads, cfg.head_dim), dtype=torch.float16, device="cuda")
+    ws = torch.empty(max(16, cq.cq_decode_workspace_bytes(fmt, B, cfg.n_q_heads, T, 0)), dtype=torch.uint8, device="cuda")
+    return dict(ck=ck, cv=cv, kcache=kcache, vcache=vcache, q=q, out=out, ws=ws, rk=rk, rv=rv)
+
+
+def kernel_name(cfg, step=False, ns=None):
+    gh = cfg.head_dim // cfg.c
+    if ns is None:
+        tiles = (cfg.context + 63) // 64
+        import paper_2405_03917_amd as cq
+        fmt = cq.CQFormat(cfg.c, cfg.b, cfg.head_dim, cfg.n_kv_heads)
+        split = cq.cq_decode_default_split(fmt, cfg.batch, cfg.n_q_heads, cfg.context) // 64
+        per_wave = (min(split, tiles) + 7) // 8
+        full = 32 if cfg.b == 10 else 16
+        ns = full // 2 if per_wave <= full // 2 else full
+    return f"decode_split_kernel<{gh}, {cfg.c}, {cfg.b}, {ns}, {'true' if step else 'false'}, false>"
+
+
+def decode_config_entry(cq, synth, torch, cfg_id, rounds, label):
+    """cq_decode_attention of one layer of a named configuration, rotating over cache sets."""
+    cfg = synth.CONFIGS[cfg_id]
+    fmt = cq.CQFormat(cfg.c, cfg.b, cfg.head_dim, cfg.n_kv_heads)
+    B, T, D = cfg.batch, cfg.context, cfg.kv_channels
     code_bytes = B * T * 2 * D * cfg.b // (8 * cfg.c)
-    out["decode_long_context"] = {
-        "workload": "CQ-8c8b, batch 4, 32 heads x 128, context 131072, one layer (split kernel + merge)",
-        "ms": med, "kv_tokens_per_s": B * T / (med * 1e-3),
-        "code_read_GBps": code_bytes / (med * 1e-3) / 1e9,
-        "frac_of_hbm_peak": code_bytes / (med * 1e-3) / 1e9 / HBM_PEAK_GBPS,
-        "tokens_per_split": cq.cq_decode_default_split(fmt, B, cfg.n_q_heads, T)}
+    n_sets = sets_beyond_cache(code_bytes)
+    scale = 1.0 / math.sqrt(cfg.head_dim)
+    sets, calls = [], []
+    for s in range(n_sets):
+        st = fill_cache_set(cq, synth, torch, cfg, fmt, s, min(T, 32768))
+        call, _ = cq.prepare_decode_attention(st["q"], st["kcache"], st["vcache"], st["ck"], st["cv"], scale, fmt, T, T,
+                                              out=st["out"], workspace=st["ws"])
+        sets.append(st)
+        calls.append(call)
+    torch.cuda.synchronize()
+    ms = time_rotating(torch, calls, rounds)
+    split = cq.cq_decode_default_split(fmt, B, cfg.n_q_heads, T)
+    kname = kernel_name(cfg)
+    entry = {"workload": f"{label}: cq_decode_attention of one layer, {cfg.n_q_heads} query / {cfg.n_kv_heads} KV heads, "
+                         f"batch {B}, context {T}",
+             "ms": ms, "kv_tokens_per_s": B * T / (ms * 1e-3), "code_read_GBps": code_bytes / (ms * 1e-3) / 1e9,
+             "frac_of_hbm_peak": code_bytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, "tokens_per_split": split,
+             "splits_merged_in_kernel": split < T, "buffer_sets": n_sets, "cache_resident": False,
+             "bytes_between_reuse": code_bytes * (n_sets - 1),
+             "roofline": hbm_roofline(kname, kname, code_bytes, ms, rounds * n_sets)}
+    return cfg, fmt, sets, entry
+
+
+def extra_measurements(cq, synth, torch):
+    """The other named configurations and entry points."""
+    import numpy as np
+    out = {}
+    scale = 1.0 / math.sqrt(128)
+
+    # ---- configuration 1: CQ-8c8b, batch 1, context 1024: encode all 1024 tokens of K and V, then one
+    # decode step.  Latency-bound (1 MiB of codes); 64 buffer sets of 9 MiB (codebooks included).
+    cfg = synth.CONFIGS[1]
+    fmt = cq.CQFormat(cfg.c, cfg.b, cfg.head_dim, cfg.n_kv_heads)
+    T, D = cfg.context, cfg.kv_channels
+    n_sets = 40
+    sets, enc_calls, dec_calls = [], [], []
+    for s in range(n_sets):
+        rk = synth.tensor_recipe(1, s, "k", D)
+        rv = synth.tensor_recipe(1, s, "v", D)
+        st = dict(ck=torch.from_numpy(synth.sample_codebook(rk, cfg.c, cfg.b)).cuda(),
+                  cv=torch.from_numpy(synth.sample_codebook(rv, cfg.c, cfg.b)).cuda(),
+                  xk=synth.sample_activations_torch(rk, T, s, "cuda").view(1, T, D),
+                  xv=synth.sample_activations_torch(rv, T, s + 1000, "cuda").view(1, T, D),
+                  kcache=cq.alloc_cache(fmt, 1, T), vcache=cq.alloc_cache(fmt, 1, T),
+                  q=torch.from_numpy(synth.sample_query(1, s, 1, cfg.n_q_heads, cfg.head_dim)).cuda(),
+                  out=torch.empty((1, cfg.n_q_heads, cfg.head_dim), dtype=torch.float16, device="cuda"))
+        st["ws"] = torch.empty(max(16, cq.cq_decode_workspace_bytes(fmt, 1, cfg.n_q_heads, T, 0)), dtype=torch.uint8, device="cuda")
+        enc_calls.append(cq.prepare_encode_kv(st["xk"], st["xv"], st["ck"], st["cv"], fmt, st["kcache"], st["vcache"], 0, T))
+        dec_calls.append(cq.prepare_decode_attention(st["q"], st["kcache"], st["vcache"], st["ck"], st["cv"], scale, fmt, T, T,
+                                                     out=st["out"], workspace=st["ws"])[0])
+        sets.append(st)
+    torch.cuda.synchronize()
+    both = []
+    for e, d in zip(enc_calls, dec_calls):
+        both.append(lambda e=e, d=d: (e(), d()))
+    ms_both = time_rotating(torch, both, 5)
+    ms_enc = time_rotating(torch, enc_calls, 5)
+    ms_dec = time_rotating(torch, dec_calls, 5)
+    code_bytes = T * 2 * D * cfg.b // (8 * cfg.c)
+    enc_r, enc_pairs = encode_roofline("encode_mfma_kernel<16, 8, 8, *> (K and V in one cq_encode_kv launch)", 2 * T, D, 256, ms_enc, True)
+    enc_r.update(achieved=2.25 * enc_pairs / 8 / 1e12, frac=2.25 * enc_pairs / 8 / VALU_PEAK_LANE_OPS)
+    out["cfg1_encode_1024_tokens_then_one_decode_step"] = {
+        "workload": "CQ-8c8b, batch 1, 32 heads x 128, context 1024: cq_encode_kv of all 1024 tokens (K and V), then "
+                    "cq_decode_attention over them; latency of the pair and of each call (launch to launch, rotating sets)",
+        "ms_encode_plus_decode": ms_both, "ms_encode_kv": ms_enc, "ms_decode_attention": ms_dec,
+        "encode_tokens_per_s_per_tensor": T / (ms_enc * 1e-3) , "decode_kv_tokens_per_s": T / (ms_dec * 1e-3),
+        "buffer_sets": n_sets, "cache_resident": False, "bytes_between_reuse": (n_sets - 1) * (code_bytes + 2 * 2 * D * 256 + 2 * 2 * T * D),
+        "note": "latency-bound: 1 MiB of codes is 0.13 us of HBM time; the decode launch is one table build and one epilogue",
+        "roofline": hbm_roofline(kernel_name(cfg), kernel_name(cfg), code_bytes, ms_dec, 5 * n_sets),
+        "roofline_encode": enc_r}
+    del sets, enc_calls, dec_calls, both
+    torch.cuda.empty_cache()
+
+    # ---- configuration 5: CQ-8c8b, batch 4, context 131072 (the 1-bit-per-channel long-context case)
+    cfg, fmt, sets, entry = decode_config_entry(cq, synth, torch, 5, 8, "CQ-8c8b long context")
+    out["decode_long_context"] = entry
+    B, T, D = cfg.batch, cfg.context, cfg.kv_channels
+    code_bytes = B * T * 2 * D * cfg.b // (8 * cfg.c)
+    st0 = sets[0]
+    # the same call through the entry point that allocates nothing (static scratch for the partials)
+    call_s = cq.prepare_decode_attention_static(st0["q"], st0["kcache"], st0["vcache"], st0["ck"], st0["cv"], scale, fmt, T, T, st0["out"])
+    calls_s = [cq.prepare_decode_attention_static(s["q"], s["kcache"], s["vcache"], s["ck"], s["cv"], scale, fmt, T, T, s["out"]) for s in sets]
+    out["decode_long_context"]["ms_static_scratch_entry_point"] = time_rotating(torch, calls_s, 4)
+    del call_s, calls_s
+    # its prefill-sized encode: 32768 tokens x 4096 channels, one tensor
+    chunk = cfg.encode_tokens
+    xk = synth.sample_activations_torch(st0["rk"], chunk, 777, "cuda").view(1, chunk, D)
+    scratch_cache = cq.alloc_cache(fmt, 1, chunk)
+    enc_ms, _ = time_calls(torch, lambda: cq.cq_encode(xk, st0["ck"], fmt, scratch_cache, 0, chunk), 5, 1)
+    enc_r, enc_pairs = encode_roofline("encode_mfma_kernel<16, 8, 8, 4>", chunk, D, 256, enc_ms, True)
+    enc_r.update(achieved=2.25 * enc_pairs / 8 / 1e12, frac=2.25 * enc_pairs / 8 / VALU_PEAK_LANE_OPS)
+    out["encode_prefill"] = {"workload": "CQ-8c8b, 32768 tokens x 4096 channels, one tensor, one cq_encode call",
+                             "ms": enc_ms, "tokens_per_s": chunk / (enc_ms * 1e-3), "roofline": enc_r}
+    del xk, scratch_cache
     # the same caches read as pre-RoPE keys (query-side rotation; phase K is ALU-bound)
     rope = cq.RopeTable(10000.0, T)
     split_r = cq.cq_decode_rope_default_split(fmt, B, cfg.n_q_heads, T)
-    ws_r = torch.empty(cq.cq_decode_workspace_bytes(fmt, B, cfg.n_q_heads, T, split_r), dtype=torch.uint8, device="cuda")
-    call_r, _ = cq.prepare_decode_attention_rope(q, kcache, vcache, ck, cv, scale, fmt, T, T, rope,
-                                                 tokens_per_split=split_r, out=o, workspace=ws_r)
-    med_r, _ = time_calls(torch, call_r, 10, 2)
+    calls_r = []
+    for s in sets:
+        ws_r = torch.empty(cq.cq_decode_workspace_bytes(fmt, B, cfg.n_q_heads, T, split_r), dtype=torch.uint8, device="cuda")
+        calls_r.append(cq.prepare_decode_attention_rope(s["q"], s["kcache"], s["vcache"], s["ck"], s["cv"], scale, fmt, T, T, rope,
+                                                        tokens_per_split=split_r, out=s["out"], workspace=ws_r)[0])
+    ms_r = time_rotating(torch, calls_r, 3)
     out["decode_long_context_pre_rope_keys"] = {
         "workload": "as decode_long_context, keys cached before RoPE (cq_decode_attention_rope, base 10000)",
-        "ms": med_r, "kv_tokens_per_s": B * T / (med_r * 1e-3),
-        "code_read_GBps": code_bytes / (med_r * 1e-3) / 1e9, "tokens_per_split": split_r,
-        "slowdown_vs_position_independent": med_r / med}
+        "ms": ms_r, "kv_tokens_per_s": B * T / (ms_r * 1e-3),
+        "code_read_GBps": code_bytes / (ms_r * 1e-3) / 1e9, "tokens_per_split": split_r,
+        "slowdown_vs_position_independent": ms_r / entry["ms"], "buffer_sets": len(sets), "cache_resident": False,
+        "roofline": hbm_roofline("decode_rope_kernel<16, 8, *>", "decode_rope_kernel<16, 8>", code_bytes, ms_r, 3 * len(sets),
+                                 note="bound by the vector ALU (per-token rotation), not by HBM; the HBM fraction is what the "
+                                      "metric asks for")}
+    del calls_r
     # a prefill chunk over the same caches: the last 512 tokens of each sequence attend causally
     # (cq_chunk_attention on the matrix cores); 4 x 32 x 512 query rows x ~130816 visible tokens each
     m_chunk = 512
     qc = torch.randn((B, m_chunk, cfg.n_q_heads, cfg.head_dim), device="cuda").half()
-    call_c, _ = cq.prepare_chunk_attention(qc, kcache, vcache, ck, cv, scale, fmt, T, T)
-    med_c, _ = time_calls(torch, call_c, 5, 1)
+    call_c, _ = cq.prepare_chunk_attention(qc, st0["kcache"], st0["vcache"], st0["ck"], st0["cv"], scale, fmt, T, T)
+    med_c, _ = time_calls(torch, call_c, 4, 1)
     pairs = B * cfg.n_q_heads * sum(T - m_chunk + j + 1 for j in range(m_chunk))
+    executed = pairs * 6 * cfg.head_dim / (med_c * 1e-3) / 1e12
     out["chunk_attention_long_context"] = {
         "workload": "CQ-8c8b, batch 4, 32 heads x 128, context 131072: causal attention of the last 512 tokens "
                     "(cq_chunk_attention)",
         "ms": med_c, "query_token_pairs_per_s": pairs / (med_c * 1e-3),
         "useful_TFLOPs": pairs * 4 * cfg.head_dim / (med_c * 1e-3) / 1e12,
-        "mfma_TFLOPs_executed": pairs * 6 * cfg.head_dim / (med_c * 1e-3) / 1e12,
-        "frac_of_fp16_mfma_peak_executed": pairs * 6 * cfg.head_dim / (med_c * 1e-3) / 1e12 / 2500.0}
-    del kcache, vcache, qc
-    # centroid learning on a calibration tensor of the paper's size (16 sequences x 2048 tokens):
+        "roofline": {"bound": "mfma", "kernel": "chunk_attention_kernel<16, 8, 8>", "achieved": executed, "peak": FP16_MFMA_PEAK_TFLOPS,
+                     "unit": "TFLOP/s", "frac": executed / FP16_MFMA_PEAK_TFLOPS, "traffic": None,
+                     "note": "executed fp16 MFMA work (probabilities split into two fp16 parts: 6 d flops per pair, 4 d useful)"}}
+    del qc, call_c, sets, st0
+    torch.cuda.empty_cache()
+
+    # ---- configurations 3 and 4
+    for cfg_id, key, label in ((3, "decode_cq2c8b_batch64_ctx8192", "CQ-2c8b"),
+                               (4, "decode_cq8c10b_gqa_batch32_ctx16384", "CQ-8c10b, grouped queries")):
+        cfg, fmt, sets, entry = decode_config_entry(cq, synth, torch, cfg_id, 6, label)
+        if cfg_id == 4:
+            entry["binding_ceiling"] = ("not HBM: per workgroup the score table and the epilogue each walk a 256 KB codebook "
+                                        "(L2) against 640 KB of codes, and the four query heads of a KV head repeat both")
+        out[key] = entry
+        if cfg.encode_tokens > 1:           # the configuration's prefill chunk: B x encode_tokens tokens, one tensor
+            B, T, D, te = cfg.batch, cfg.context, cfg.kv_channels, cfg.encode_tokens
+            x = synth.sample_activations_torch(sets[0]["rk"], B * te, 4242, "cuda").view(B, te, D)
+            enc_ms, _ = time_calls(torch, lambda: cq.cq_encode(x, sets[0]["ck"], fmt, sets[0]["kcache"], 0, T), 5, 1)
+            gh = cfg.head_dim // cfg.c
+            enc_r, enc_pairs = encode_roofline(f"encode_mfma_kernel<{gh}, {cfg.c}, {cfg.b}, 4>", B * te, D, 1 << cfg.b, enc_ms, True)
+            enc_r.update(achieved=2.25 * enc_pairs / cfg.c / 1e12, frac=2.25 * enc_pairs / cfg.c / VALU_PEAK_LANE_OPS)
+            out[f"encode_cq{cfg.c}c{cfg.b}b_{B}x{te}"] = {
+                "workload": f"CQ-{cfg.c}c{cfg.b}b, {B} sequences x {te} tokens x {D} channels, one tensor, one cq_encode call",
+                "ms": enc_ms, "tokens_per_s": B * te / (enc_ms * 1e-3), "roofline": enc_r}
+            del x
+        del sets
+        torch.cuda.empty_cache()
+
+    # ---- centroid learning on a calibration tensor of the paper's size (16 sequences x 2048 tokens):
     # k-means++ and 100 Lloyd iterations for each of the 512 groups of one CQ-8c8b tensor
+    cfg = synth.CONFIGS[5]
+    fmt = cq.CQFormat(cfg.c, cfg.b, cfg.head_dim, cfg.n_kv_heads)
+    D = cfg.kv_channels
+    rk = synth.tensor_recipe(5, 0, "k", D)
     n_cal, iters = 16 * 2048, 100
     xcal = synth.sample_activations_torch(rk, n_cal, 977, "cuda").view(n_cal, D)
     g = torch.Generator(device="cuda")
@@ -216,59 +416,17 @@ def extra_measurements(cq, synth, torch):
     wsk = torch.empty(cq.cq_kmeans_workspace_bytes(fmt, n_cal), dtype=torch.uint8, device="cuda")
     init_ms, _ = time_calls(torch, lambda: cq.cq_kmeans_fit(xcal, fmt, 0, rnd=rnd, workspace=wsk), 3, 1)
     fit_ms, _ = time_calls(torch, lambda: cq.cq_kmeans_fit(xcal, fmt, iters, rnd=rnd, workspace=wsk), 3, 1)
+    per_iter = (fit_ms - init_ms) / iters
+    pairs_iter = n_cal * fmt.groups * 256
     out["centroid_learning"] = {
         "workload": "CQ-8c8b, 32768 calibration tokens x 4096 channels, one tensor: k-means++ then 100 Lloyd "
                     "iterations in each of 512 groups (cq_kmeans_fit)",
-        "ms": fit_ms, "kmeanspp_ms": init_ms, "ms_per_iteration": (fit_ms - init_ms) / iters,
-        "seconds_for_64_tensors": fit_ms * 64 / 1e3}
-    return out
-
-
-def config_measurements(cq, synth, torch):
-    """The other two decode workloads of the named configurations, on caches filled by really
-    encoding generated activations: CQ-2c8b (batch 64, context 8192; also its 64 x 512-token
-    prefill encode) and CQ-8c10b with grouped queries (32 query / 8 KV heads, batch 32, context
-    16384)."""
-    out = {}
-    for cfg_id, key in ((3, "decode_cq2c8b_batch64_ctx8192"), (4, "decode_cq8c10b_gqa_batch32_ctx16384")):
-        cfg = synth.CONFIGS[cfg_id]
-        fmt = cq.CQFormat(cfg.c, cfg.b, cfg.head_dim, cfg.n_kv_heads)
-        B, T, D = cfg.batch, cfg.context, cfg.kv_channels
-        rk = synth.tensor_recipe(cfg_id, 0, "k", D)
-        rv = synth.tensor_recipe(cfg_id, 0, "v", D)
-        ck = torch.from_numpy(synth.sample_codebook(rk, cfg.c, cfg.b)).cuda()
-        cv = torch.from_numpy(synth.sample_codebook(rv, cfg.c, cfg.b)).cuda()
-        kcache, vcache = cq.alloc_cache(fmt, B, T), cq.alloc_cache(fmt, B, T)
-        per_seq = kcache.numel() // B
-        for n in range(B):                  # one sequence per call: T tokens x D channels
-            xk = synth.sample_activations_torch(rk, T, 17 * n, "cuda").view(1, T, D)
-            xv = synth.sample_activations_torch(rv, T, 17 * n + 1, "cuda").view(1, T, D)
-            cq.cq_encode_kv(xk, xv, ck, cv, fmt, kcache[n * per_seq:(n + 1) * per_seq],
-                            vcache[n * per_seq:(n + 1) * per_seq], 0, T)
-            del xk, xv
-        torch.cuda.synchronize()
-        q = torch.from_numpy(synth.sample_query(cfg_id, 0, B, cfg.n_q_heads, cfg.head_dim)).cuda()
-        o = torch.empty((B, cfg.n_q_heads, cfg.head_dim), dtype=torch.float16, device="cuda")
-        ws = torch.empty(max(16, cq.cq_decode_workspace_bytes(fmt, B, cfg.n_q_heads, T, 0)), dtype=torch.uint8, device="cuda")
-        scale = 1.0 / math.sqrt(cfg.head_dim)
-        call, _ = cq.prepare_decode_attention(q, kcache, vcache, ck, cv, scale, fmt, T, T, out=o, workspace=ws)
-        med, _ = time_calls(torch, call, 30, 10)
-        code_bytes = B * T * 2 * D * cfg.b // (8 * cfg.c)
-        out[key] = {"workload": f"{cfg.name}: cq_decode_attention of one layer, {cfg.n_q_heads} query / {cfg.n_kv_heads} KV heads "
-                                "(the codes are larger than the 256 MB last-level cache only for CQ-2c8b)",
-                    "ms": med, "kv_tokens_per_s": B * T / (med * 1e-3),
-                    "code_read_GBps": code_bytes / (med * 1e-3) / 1e9,
-                    "frac_of_hbm_peak": code_bytes / (med * 1e-3) / 1e9 / HBM_PEAK_GBPS,
-                    "tokens_per_split": cq.cq_decode_default_split(fmt, B, cfg.n_q_heads, T)}
-        if cfg.encode_tokens > 1:           # the configuration's prefill chunk: B x encode_tokens tokens, one tensor
-            te = cfg.encode_tokens
-            x = synth.sample_activations_torch(rk, B * te, 4242, "cuda").view(B, te, D)
-            enc_ms, _ = time_calls(torch, lambda: cq.cq_encode(x, ck, fmt, kcache, 0, T), 5, 1)
-            out[f"encode_cq{cfg.c}c{cfg.b}b_{B}x{te}"] = {
-                "workload": f"CQ-{cfg.c}c{cfg.b}b, {B} sequences x {te} tokens x {D} channels, one tensor, one cq_encode call",
-                "ms": enc_ms, "tokens_per_s": B * te / (enc_ms * 1e-3)}
-            del x
-        del kcache, vcache
+        "ms": fit_ms, "kmeanspp_ms": init_ms, "ms_per_iteration": per_iter,
+        "seconds_for_64_tensors": fit_ms * 64 / 1e3,
+        "roofline": {"bound": "alu", "kernel": "kmeans_assign_kernel + kmeans_update_kernel, per iteration (fp32 subtract, multiply, "
+                                               "add per (token channel, centroid) pair: 3 flops)",
+                     "achieved": 3 * 8 * pairs_iter / (per_iter * 1e-3) / 1e12, "peak": FP32_VECTOR_PEAK_TFLOPS,
+                     "unit": "TFLOP/s", "frac": 3 * 8 * pairs_iter / (per_iter * 1e-3) / 1e12 / FP32_VECTOR_PEAK_TFLOPS, "traffic": None}}
     return out
 
 
@@ -315,8 +473,9 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--layers", type=int, default=0, help="override the number of layers (debug only)")
-    ap.add_argument("--no-extra", action="store_true", help="skip the long-context / prefill side measurements")
+    ap.add_argument("--no-extra", action="store_true", help="skip the other configurations and entry points")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    ap.add_argument("--only-extra", action="store_true", help="(profiling aid) run only the `extra` measurements")
     args = ap.parse_args()
     if args.gpus != 1:
         log("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1")
@@ -331,6 +490,9 @@ def main():
         sys.exit(1)
     cq.load()
     torch.cuda.set_device(0)
+    if args.only_extra:
+        print(json.dumps({"extra": extra_measurements(cq, synth, torch)}), flush=True)
+        return
     cfg = synth.CONFIGS[2]
     n_layers = args.layers or cfg.layers
     scale = 1.0 / math.sqrt(cfg.head_dim)
@@ -345,7 +507,7 @@ def main():
         run_step(layers)
     torch.cuda.synchronize()
 
-    # capture the step (3 * layers launches) in a HIP graph on a side stream
+    # capture the step (one launch per layer) in a HIP graph on a side stream
     graph = torch.cuda.CUDAGraph()
     side = torch.cuda.Stream()
     side.wait_stream(torch.cuda.current_stream())
@@ -359,9 +521,8 @@ def main():
     torch.cuda.synchronize()
 
     # ---- timed region: exactly K steps between a HIP event pair on the launching stream and a
-    # host clock read on both sides of a synchronize.  The step is timed twice, launched as a
-    # replay of the captured graph and as 32 prepared calls in stream order; the faster way of
-    # launching the same kernels is the reported one (both are printed).
+    # host clock read on both sides of a synchronize.  Headline: 32 prepared calls per step in
+    # stream order.  The same steps as replays of the captured graph are reported beside it.
     def timed(step_fn):
         ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         torch.cuda.synchronize()
@@ -372,8 +533,8 @@ def main():
         ev1.record()
         torch.cuda.synchronize()
         return time.perf_counter() - t0, ev0.elapsed_time(ev1)
-    dt_graph, ev_graph = timed(graph.replay)
-    dt_eager, ev_eager = timed(lambda: run_step(layers))
+    dt, ev_ms = timed(lambda: run_step(layers))
+    dt_graph, _ = timed(graph.replay)
     # the same step as ONE launch over all layers (possible because the workload's layers are
     # independent; reported beside the headline, which stays with one launch per layer)
     table = cq.LayerTable([dict(q=st.q, x_k_new=st.xk_new[:, 0, :], x_v_new=st.xv_new[:, 0, :], k_codes=st.kcache,
@@ -382,30 +543,23 @@ def main():
     step_all = cq.prepare_decode_step_layers(table, scale, cfg.context)
     step_all()
     dt_layers, _ = timed(step_all)
-    launch_mode = "HIP graph of 1 launch per layer" if dt_graph <= dt_eager else "32 prepared calls in stream order"
-    dt, ev_ms = (dt_graph, ev_graph) if dt_graph <= dt_eager else (dt_eager, ev_eager)
     ms_per_step = dt / args.steps * 1e3
     kv_tokens = cfg.batch * cfg.context * n_layers
     value = kv_tokens / (dt / args.steps)
-    log(f"[bench] graph replay {dt_graph / args.steps * 1e3:.3f} ms/step, stream-order launches "
-        f"{dt_eager / args.steps * 1e3:.3f} ms/step -> {value:.3e} KV tokens/s ({launch_mode})")
+    log(f"[bench] stream-order launches {ms_per_step:.3f} ms/step, graph replay {dt_graph / args.steps * 1e3:.3f} ms/step "
+        f"-> {value:.3e} KV tokens/s")
 
-    # mean duration of one launch over the timed region (one launch per layer; the few hundred
-    # nanoseconds of dispatch between back-to-back graph nodes are included)
+    # mean duration of one launch over the timed region (one launch per layer; the gap between
+    # consecutive launches is included)
     dec_ms = ev_ms / (args.steps * n_layers)
     code_bytes = cfg.batch * cfg.context * 2 * cfg.kv_channels * cfg.b // (8 * cfg.c)   # per launch
-    achieved = code_bytes / (dec_ms * 1e-3) / 1e9
-    roofline = {"bound": "hbm", "kernel": "decode_split_kernel<32,4,8,512,true,false,false> (cq_decode_step; one launch = one layer)",
-                "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS,
-                "traffic": TRAFFIC_BYTES_PER_LAUNCH if n_layers == cfg.layers else None,
-                "algorithmic_bytes_per_launch": code_bytes, "avg_launch_ms": dec_ms,
-                "launches_timed": args.steps * n_layers}
-    log(f"[bench] step kernel avg {dec_ms * 1e3:.1f} us -> {achieved:.0f} GB/s of code reads "
-        f"({100 * achieved / HBM_PEAK_GBPS:.1f}% of 8 TB/s)")
+    kname = kernel_name(cfg, step=True)
+    roofline = hbm_roofline(kname + " (cq_decode_step; one launch = one layer)", kname, code_bytes, dec_ms, args.steps * n_layers)
+    log(f"[bench] step kernel avg {dec_ms * 1e3:.1f} us launch to launch -> {roofline['achieved']:.0f} GB/s of code reads "
+        f"({100 * roofline['frac']:.1f}% of 8 TB/s)")
 
-    # eager launches of the same step, and of its two-launch form, for comparison
+    # the two-launch form of the step, and plain decode attention alone, for comparison
     unf_med, _ = time_calls(torch, lambda: run_step_unfused(layers), 5, 1)
-    # plain decode attention alone (no fused encode), back to back over the 32 layers
     def dec_all():
         for st in layers:
             st.dec()
@@ -423,9 +577,9 @@ def main():
     copy_med, _ = time_calls(torch, lambda: cq.cq_probe_copy(big[:half], big[half:2 * half]), 5, 1)
     del big
     roofline["stream_read_GBps"] = stream_gbps
-    roofline["frac_of_stream_read"] = achieved / stream_gbps
+    roofline["frac_of_stream_read"] = roofline["achieved"] / stream_gbps
     roofline["copy_256MiB_GBps_read_plus_write"] = 2 * half / (copy_med * 1e-3) / 1e9
-    log(f"[bench] streaming-read yardstick: {stream_gbps:.0f} GB/s; decode kernel at {100 * achieved / stream_gbps:.1f}% of it; "
+    log(f"[bench] streaming-read yardstick: {stream_gbps:.0f} GB/s; decode kernel at {100 * roofline['achieved'] / stream_gbps:.1f}% of it; "
         f"copy {roofline['copy_256MiB_GBps_read_plus_write']:.0f} GB/s (read+write)")
 
     # encode share of the step (same launches, events around the two encodes of each layer)
@@ -434,35 +588,41 @@ def main():
             st.enc_kv()
     enc_med, _ = time_calls(torch, enc_all, 10, 2)
     enc_med /= len(layers)
+    enc_r, enc_pairs = encode_roofline("encode_centroids_kernel<32, 4, 8> (K and V rows in one launch)", 2 * cfg.batch,
+                                       cfg.kv_channels, 256, enc_med, False)
+    enc_r.update(achieved=(2 * cfg.c + 3) * enc_pairs / cfg.c / 1e12, frac=(2 * cfg.c + 3) * enc_pairs / cfg.c / VALU_PEAK_LANE_OPS,
+                 note="launch- and latency-bound: 32 rows against a 2 x 2 MiB codebook; the fused step hides it")
     result = {
         "metric": METRIC, "value": value, "unit": "KV tokens/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "dtype_note": "fp16 inputs (activations, queries, centroids) and fp16 output; lookup tables, scores, softmax and "
+                      "accumulation in fp32; probability bins in 32-bit fixed point",
         "config": {"workload": "CQ-4c8b decode step, 32 layers, batch 16, 32 heads x 128, context 4096, MHA; "
                                "per layer: one cq_decode_step launch = encode 16 new K rows + 16 new V rows, then decode attention",
                    "format": "CQ-4c8b", "batch": cfg.batch, "context": cfg.context, "layers": n_layers,
-                   "launch": launch_mode, "tokens_per_split":
+                   "launch": "32 prepared calls in stream order", "tokens_per_split":
                        cq.cq_decode_default_split(fmt, cfg.batch, cfg.n_q_heads, cfg.context)},
         "roofline": roofline,
         "hbm_code_read_GBps_whole_step": kv_tokens * 2 * cfg.kv_channels * cfg.b // (8 * cfg.c) / (dt / args.steps) / 1e9,
-        "graph_replay_ms_per_step": dt_graph / args.steps * 1e3,
-        "stream_order_ms_per_step": dt_eager / args.steps * 1e3, "unfused_eager_ms_per_step": unf_med,
+        "stream_order_ms_per_step": ms_per_step, "graph_replay_ms_per_step": dt_graph / args.steps * 1e3,
+        "unfused_eager_ms_per_step": unf_med,
         "layer_batched_launch_ms_per_step": dt_layers / args.steps * 1e3,
         "decode_attention_only": {"workload": "cq_decode_attention of one layer (no fused encode), eager back-to-back "
-                                              "launches, HIP events", "ms": dec_only_ms,
-                                  "code_read_GBps": code_bytes / (dec_only_ms * 1e-3) / 1e9},
+                                              "launches over the 32 layers' caches, HIP events", "ms": dec_only_ms,
+                                  "code_read_GBps": code_bytes / (dec_only_ms * 1e-3) / 1e9, "buffer_sets": n_layers,
+                                  "cache_resident": False,
+                                  "roofline": hbm_roofline(kernel_name(cfg), kernel_name(cfg), code_bytes, dec_only_ms, 5 * n_layers)},
         "encode_decode_step": {"workload": "16 new K rows + 16 new V rows x 4096 channels, one cq_encode_kv launch "
                                            "(mean over 32 back-to-back launches)", "ms": enc_med,
-                               "tokens_per_s_per_tensor": cfg.batch / (enc_med * 1e-3)},
+                               "tokens_per_s_per_tensor": cfg.batch / (enc_med * 1e-3), "roofline": enc_r},
     }
-    del graph
+    del graph, table, step_all
     if not args.no_extra:
         del layers
         torch.cuda.empty_cache()
         try:
             result["extra"] = extra_measurements(cq, synth, torch)
-            torch.cuda.empty_cache()
-            result["extra"].update(config_measurements(cq, synth, torch))
             log(f"[bench] extra: {json.dumps(result['extra'])}")
         except Exception as e:      # side measurements must not lose the main line
             result["extra"] = {"error": repr(e)}

@@ -181,6 +181,7 @@ static int attention_impl(const uint16_t *q, const uint16_t *k_codes, const uint
             double *vhat = (double *)malloc(sizeof(double) * L * d);
             double *s = (double *)malloc(sizeof(double) * L);
             if (!khat || !vhat || !s) {
+#pragma omp atomic write
                 failed = 1;
                 free(khat); free(vhat); free(s);
                 continue;

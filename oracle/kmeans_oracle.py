@@ -44,8 +44,11 @@ def build(force: bool = False) -> str:
 def _load():
     global _lib
     if _lib is None:
-        build()
-        lib = ctypes.CDLL(_LIB)
+        # CQ_KMEANS_ORACLE_LIB names a library built elsewhere (the host-sanitizer run of the tests), taken as it is
+        override = os.environ.get("CQ_KMEANS_ORACLE_LIB")
+        if not override:
+            build()
+        lib = ctypes.CDLL(override or _LIB)
         u16p = ctypes.POINTER(ctypes.c_uint16)
         f32p = ctypes.POINTER(ctypes.c_float)
         f64p = ctypes.POINTER(ctypes.c_double)

@@ -14,7 +14,8 @@ from dataclasses import dataclass
 from typing import Optional
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_PKG, "libcq.so")
+# (LIBCQ_PATH names a build of the library elsewhere, e.g. the host-sanitizer build of the tests)
+LIB_PATH = os.environ.get("LIBCQ_PATH") or os.path.join(_PKG, "libcq.so")
 
 CQ_OK = 0
 CQ_ERR_INVALID_ARG = 1
@@ -822,6 +823,14 @@ def cq_paged_cache_bytes(fmt: CQFormat, n_pages: int) -> int:
     return n
 
 
+def _check_centroids(fmt: CQFormat, k_centroids, v_centroids) -> None:
+    import torch
+    for name, cb in (("k_centroids", k_centroids), ("v_centroids", v_centroids)):
+        _dev(cb, torch.float16, name)
+        if not cb.is_contiguous() or tuple(cb.shape) != (fmt.groups, 1 << fmt.b, fmt.c):
+            raise ValueError(f"{name} must be contiguous [G, 2^b, c]")
+
+
 def cq_encode_kv_paged(x_k, x_v, k_centroids, v_centroids, fmt: CQFormat, k_pool, v_pool, pages: PageTable,
                        t_offset: int, stream=None) -> None:
     """cq_encode_kv into paged pools: x fp16 [B, T_new, D]; tokens go to positions t_offset ... of
@@ -833,11 +842,14 @@ def cq_encode_kv_paged(x_k, x_v, k_centroids, v_centroids, fmt: CQFormat, k_pool
             raise ValueError(f"{name} must be [B, T_new, D] with unit channel stride")
     if x_k.shape != x_v.shape or x_k.stride() != x_v.stride():
         raise ValueError("x_k and x_v must have the same shape and strides")
+    _check_centroids(fmt, k_centroids, v_centroids)
     need = cq_paged_cache_bytes(fmt, pages.n_pages)
     for name, t in (("k_pool", k_pool), ("v_pool", v_pool)):
         _dev(t, torch.uint8, name)
         if t.numel() < need:
             raise ValueError(f"{name} is smaller than cq_paged_cache_bytes(fmt, n_pages)")
+    if pages.block_table.shape[0] < x_k.shape[0]:
+        raise ValueError("block table has fewer rows than the batch")
     st = load().cq_encode_kv_paged(x_k.data_ptr(), x_v.data_ptr(), x_k.stride(0), x_k.stride(1), k_centroids.data_ptr(),
                                    v_centroids.data_ptr(), ctypes.byref(fmt._c()), int(x_k.shape[0]), int(x_k.shape[1]),
                                    k_pool.data_ptr(), v_pool.data_ptr(), ctypes.byref(pages._c), t_offset,
@@ -853,6 +865,7 @@ def _paged_decode(fn_name, q, x_k_new, x_v_new, k_pool, v_pool, k_centroids, v_c
     if q.dim() != 3 or not q.is_contiguous() or q.shape[2] != fmt.head_dim:
         raise ValueError("q must be contiguous [B, Hq, head_dim]")
     batch, n_q_heads = int(q.shape[0]), int(q.shape[1])
+    _check_centroids(fmt, k_centroids, v_centroids)
     need = cq_paged_cache_bytes(fmt, pages.n_pages)
     for name, p in (("k_pool", k_pool), ("v_pool", v_pool)):
         _dev(p, torch.uint8, name)

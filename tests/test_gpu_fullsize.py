@@ -1,8 +1,10 @@
 """GPU parity at the full sizes of the named workloads, in the launch configuration bench.py
 times (default context split, caches filled by REALLY encoding generated activations on the
 device).  The oracle cannot redo these sizes whole, so it recomputes sampled outputs one by one:
-all groups of sampled tokens for cq_encode, whole (sequence, head) rows for cq_decode_attention
-and, for the workload bench.py times, for the fused cq_decode_step."""
+all groups of 64 sampled tokens (first and last tile of a chunk included; the first and the last
+chunk of two sequences) for cq_encode, 40 to 64 whole (sequence, head) rows -- every query head,
+hence every KV head, the first and the last row -- for cq_decode_attention and, for the workload
+bench.py times, for the fused cq_decode_step.  Every row is merged from all its context splits."""
 import math
 
 import numpy as np
@@ -18,6 +20,33 @@ from gpu_util import (check_attention, check_codes, dev, head_stream_codes, orac
 pytestmark = pytest.mark.gpu
 
 
+def _oracle_rows(rows, q_h, kcache, vcache, ck_h, cv_h, fmt, B, T, scale, rep, rope_base=None):
+    """fp64 attention of the sampled (sequence, query head) rows in ONE oracle call: the rows become
+    the heads of a one-sequence layer whose head i has the codes of row i's (sequence, KV head)
+    stream and that KV head's codebooks (the oracle treats heads independently and runs them in
+    parallel).  Returns [len(rows), head_dim]."""
+    from oracle import cq_oracle as O
+    Gh = fmt.head_dim // fmt.c
+    kc = np.concatenate([head_stream_codes(kcache, fmt, B, T, n, hq // rep, T) for n, hq in rows], axis=1)[None]
+    vc = np.concatenate([head_stream_codes(vcache, fmt, B, T, n, hq // rep, T) for n, hq in rows], axis=1)[None]
+    ck = np.concatenate([ck_h[(hq // rep) * Gh:(hq // rep + 1) * Gh] for _, hq in rows])
+    cv = np.concatenate([cv_h[(hq // rep) * Gh:(hq // rep + 1) * Gh] for _, hq in rows])
+    q = np.stack([q_h[n, hq] for n, hq in rows])[None]
+    kw = {} if rope_base is None else {"rope_base": rope_base}
+    return O.attention(q, kc, vc, ck, cv, scale, len(rows), **kw)[0], kc[0], vc[0]
+
+
+def _sample_rows(rng, B, n_q_heads, n_rows):
+    """(sequence, query head) rows: every query head (hence every KV head) at least once, the first and
+    the last row of the launch, the rest at random."""
+    picks = [(0, 0), (B - 1, n_q_heads - 1)]
+    picks += [(int(rng.integers(0, B)), h) for h in range(n_q_heads)]
+    seen = set(picks)
+    while len(seen) < n_rows:
+        seen.add((int(rng.integers(0, B)), int(rng.integers(0, n_q_heads))))
+    return sorted(seen | set(picks))
+
+
 def _fill_and_check(cfg_id, n_attn_samples, n_token_samples, chunk_tokens, fused_step=False):
     cfg = synth.CONFIGS[cfg_id]
     fmt = cq.CQFormat(cfg.c, cfg.b, cfg.head_dim, cfg.n_kv_heads)
@@ -29,7 +58,7 @@ def _fill_and_check(cfg_id, n_attn_samples, n_token_samples, chunk_tokens, fused
     ck, cv = dev(ck_h), dev(cv_h)
     kcache, vcache = cq.alloc_cache(fmt, B, T), cq.alloc_cache(fmt, B, T)
     per_seq = kcache.numel() // B
-    check_seq = int(rng.integers(0, B))
+    check_seqs = {0: 0, int(rng.integers(0, B)): (T - 1) // chunk_tokens * chunk_tokens}   # sequence -> chunk start
     for n in range(B):
         for t0 in range(0, T, chunk_tokens):
             tn = min(chunk_tokens, T - t0)
@@ -37,13 +66,13 @@ def _fill_and_check(cfg_id, n_attn_samples, n_token_samples, chunk_tokens, fused
             xv = synth.sample_activations_torch(rv, tn, 17 * n + t0 + 5, "cuda").view(1, tn, D)
             cq.cq_encode(xk, ck, fmt, kcache[n * per_seq:(n + 1) * per_seq], t0, T)
             cq.cq_encode(xv, cv, fmt, vcache[n * per_seq:(n + 1) * per_seq], t0, T)
-            if n == check_seq and t0 == 0:
+            if check_seqs.get(n) == t0:
                 # cq_encode, sampled tokens of this chunk, all groups, both tensors
                 rows = np.sort(rng.choice(tn, size=n_token_samples, replace=False))
                 rows[0], rows[-1] = 0, tn - 1
                 torch.cuda.synchronize()
-                kc = sequence_codes(kcache, fmt, B, T, n, tn)
-                vc = sequence_codes(vcache, fmt, B, T, n, tn)
+                kc = sequence_codes(kcache, fmt, B, T, n, tn, t0)
+                vc = sequence_codes(vcache, fmt, B, T, n, tn, t0)
                 check_codes(kc[rows], xk[0, rows].cpu().numpy(), ck_h)
                 check_codes(vc[rows], xv[0, rows].cpu().numpy(), cv_h)
             del xk, xv
@@ -54,15 +83,9 @@ def _fill_and_check(cfg_id, n_attn_samples, n_token_samples, chunk_tokens, fused
     out_h = out.cpu().numpy()
     assert np.all(np.isfinite(out_h.astype(np.float64)))
     rep = cfg.n_q_heads // cfg.n_kv_heads
-    picks = {(0, 0), (B - 1, cfg.n_q_heads - 1)}
-    while len(picks) < n_attn_samples:
-        picks.add((int(rng.integers(0, B)), int(rng.integers(0, cfg.n_q_heads))))
-    for n, hq in sorted(picks):
-        hk = hq // rep
-        kc = head_stream_codes(kcache, fmt, B, T, n, hk, T)
-        vc = head_stream_codes(vcache, fmt, B, T, n, hk, T)
-        ref = oracle_head_attention(q_h[n, hq], kc, vc, ck_h[hk * Gh:(hk + 1) * Gh], cv_h[hk * Gh:(hk + 1) * Gh], scale)
-        check_attention(out_h[n, hq][None], ref[None])
+    picks = _sample_rows(rng, B, cfg.n_q_heads, n_attn_samples)
+    ref, _, _ = _oracle_rows(picks, q_h, kcache, vcache, ck_h, cv_h, fmt, B, T, scale, rep)
+    check_attention(np.stack([out_h[n, hq] for n, hq in picks]), ref)
     if fused_step:
         # the launch bench.py times: one cq_decode_step per layer (new rows go to position T - 1)
         xk1 = synth.sample_activations_torch(rk, B, 9001, "cuda").view(B, D)
@@ -77,15 +100,13 @@ def _fill_and_check(cfg_id, n_attn_samples, n_token_samples, chunk_tokens, fused
         assert torch.equal(out2.view(torch.int16), ref.view(torch.int16))
         out2_h = out2.cpu().numpy()
         xk1_h, xv1_h = xk1.cpu().numpy(), xv1.cpu().numpy()
-        for n, hq in sorted(picks):
+        ref64, kc_rows, vc_rows = _oracle_rows(picks, q_h, kcache, vcache, ck_h, cv_h, fmt, B, T, scale, rep)
+        check_attention(np.stack([out2_h[n, hq] for n, hq in picks]), ref64)
+        for i, (n, hq) in enumerate(picks):          # the new token's codes in the sampled streams
             hk = hq // rep
-            kc = head_stream_codes(kcache, fmt, B, T, n, hk, T)
-            vc = head_stream_codes(vcache, fmt, B, T, n, hk, T)
             sl = slice(hk * cfg.head_dim, (hk + 1) * cfg.head_dim)
-            check_codes(kc[T - 1:], xk1_h[n:n + 1, sl], ck_h[hk * Gh:(hk + 1) * Gh])
-            check_codes(vc[T - 1:], xv1_h[n:n + 1, sl], cv_h[hk * Gh:(hk + 1) * Gh])
-            ref64 = oracle_head_attention(q_h[n, hq], kc, vc, ck_h[hk * Gh:(hk + 1) * Gh], cv_h[hk * Gh:(hk + 1) * Gh], scale)
-            check_attention(out2_h[n, hq][None], ref64[None])
+            check_codes(kc_rows[T - 1:, i * Gh:(i + 1) * Gh], xk1_h[n:n + 1, sl], ck_h[hk * Gh:(hk + 1) * Gh])
+            check_codes(vc_rows[T - 1:, i * Gh:(i + 1) * Gh], xv1_h[n:n + 1, sl], cv_h[hk * Gh:(hk + 1) * Gh])
         # the same step for two layers in one launch (cq_decode_step_layers): this layer, and a second
         # one with its own caches and the query heads in another order
         q2 = dev(np.ascontiguousarray(q_h[:, ::-1]))
@@ -103,28 +124,24 @@ def _fill_and_check(cfg_id, n_attn_samples, n_token_samples, chunk_tokens, fused
         from oracle import cq_oracle as O
         rope = cq.RopeTable(10000.0, T)
         out3 = cq.cq_decode_attention_rope(dev(q_h), kcache, vcache, ck, cv, scale, fmt, T, T, rope).cpu().numpy()
-        for n, hq in sorted(picks)[:3]:
-            hk = hq // rep
-            kc = head_stream_codes(kcache, fmt, B, T, n, hk, T)
-            vc = head_stream_codes(vcache, fmt, B, T, n, hk, T)
-            ref3 = O.attention(q_h[n, hq][None, None, :], kc[None], vc[None], ck_h[hk * Gh:(hk + 1) * Gh],
-                               cv_h[hk * Gh:(hk + 1) * Gh], scale, 1, rope_base=10000.0)[0, 0]
-            check_attention(out3[n, hq][None], ref3[None])
+        rows3 = picks[:8]
+        ref3, _, _ = _oracle_rows(rows3, q_h, kcache, vcache, ck_h, cv_h, fmt, B, T, scale, rep, rope_base=10000.0)
+        check_attention(np.stack([out3[n, hq] for n, hq in rows3]), ref3)
     return cq.cq_decode_default_split(fmt, B, cfg.n_q_heads, T)
 
 
 def test_config2_one_layer_cq4c8b_batch16_ctx4096():
-    split = _fill_and_check(2, n_attn_samples=6, n_token_samples=12, chunk_tokens=4096, fused_step=True)
+    split = _fill_and_check(2, n_attn_samples=64, n_token_samples=64, chunk_tokens=4096, fused_step=True)
     assert split == 4096           # the configuration bench.py times: one split, no merge kernel
 
 
 def test_config3_cq2c8b_batch64_ctx8192():
-    _fill_and_check(3, n_attn_samples=4, n_token_samples=8, chunk_tokens=8192)
+    _fill_and_check(3, n_attn_samples=64, n_token_samples=64, chunk_tokens=8192)
 
 
 def test_config4_cq8c10b_gqa_batch32_ctx16384():
-    _fill_and_check(4, n_attn_samples=4, n_token_samples=8, chunk_tokens=16384)
+    _fill_and_check(4, n_attn_samples=64, n_token_samples=64, chunk_tokens=16384)
 
 
 def test_config5_cq8c8b_batch4_ctx131072():
-    _fill_and_check(5, n_attn_samples=3, n_token_samples=8, chunk_tokens=32768)
+    _fill_and_check(5, n_attn_samples=40, n_token_samples=64, chunk_tokens=32768)

@@ -46,6 +46,78 @@ def test_weighted_single_cluster_is_the_exact_weighted_mean():
         assert cent[0, 0, ch] == want
 
 
+def test_weight_quantisation_keeps_22_bits_of_the_largest_weight():
+    # Hand-computed: the largest weight of a group becomes an integer in [2^21, 2^22), so a weight of
+    # 2^-21 of the largest is the integer 1 and a weight of 2^-22 of it (or less) is 0 and leaves the mean.
+    # Two points, x = 0 with weight 1 and x = 1000 with weight w: the mean is 1000 wq / (2^21 + wq).
+    # A scale exponent off by one in either direction moves both answers.
+    x = np.array([[0.0], [1000.0]], dtype=np.float16)
+    for w_small, wq in ((2.0 ** -21, 1), (2.0 ** -22, 0), (1.5 * 2.0 ** -21, 1), (3.0 * 2.0 ** -21, 3), (2.0 ** -40, 0)):
+        w = np.array([[1.0], [w_small]], dtype=np.float32)
+        cent, _, _ = KO.lloyd(x, 1, np.zeros((1, 1, 1), np.float32), 1, w)
+        want = np.float32(float(Fraction(1000 * wq, 2 ** 21 + wq)))
+        assert cent[0, 0, 0] == want, (w_small, cent[0, 0, 0], want)
+        assert list(KO.integer_weights(w, 2, 1)[0]) == [2 ** 21, wq]
+    # the scale follows the largest weight, whatever its size: 3 * 2^k has the integer 3 * 2^20
+    for k in (-30, 0, 17):
+        w = np.array([[3.0 * 2.0 ** k], [2.0 ** k]], dtype=np.float32)
+        assert list(KO.integer_weights(w, 2, 1)[0]) == [3 * 2 ** 20, 2 ** 20]
+
+
+def test_weighted_update_against_plain_fp64_eq6_with_weights_over_30_binades():
+    # Eq. 6's update in plain fp64 (weighted mean of every cluster with the real-valued weights) against
+    # the oracle's integer-weight arithmetic, weights spread over 34 binades (squared gradients span many
+    # decades).  Integer weights deviate from w 2^kw by less than one unit, i.e. by less than 2^-21 of
+    # the group's largest weight each, so a cluster's mean moves by at most
+    # n_cluster 2^-21 w_max spread / W_cluster; clusters that hold a weight within 2^10 of the largest
+    # therefore agree to 1e-4 of the spread, which is asserted; the weighted objective (Eq. 6) of the
+    # oracle's centroids exceeds that of the plain update by no more than 1e-5 of itself.
+    rng = np.random.default_rng(77)
+    n, c, k = 4000, 4, 8
+    x, lab, _ = _blobs(rng, n, c, k, spread=0.3)
+    w = (2.0 ** rng.uniform(-34, 0, size=(n, 1))).astype(np.float32)
+    w[:k, 0] = rng.uniform(0.5, 1.0, size=k)                       # every cluster holds a heavy point
+    lab[:k] = np.arange(k)
+    x[:k] = x[[np.flatnonzero(lab == j)[-1] for j in range(k)]]
+    start = np.stack([x[lab == j].astype(np.float64).mean(0) for j in range(k)])[None].astype(np.float32)
+    cent, assign, _ = KO.lloyd(x, c, start, 1, w)
+    x64, w64 = x.astype(np.float64), w[:, 0].astype(np.float64)
+    d = ((x64[:, None, :] - start[0].astype(np.float64)[None]) ** 2).sum(-1)
+    a = d.argmin(1)
+    assert np.array_equal(a, assign[0])                             # (well separated blobs: no close calls)
+    spread = x64.max(0) - x64.min(0)
+    obj_plain = obj_oracle = 0.0
+    for j in range(k):
+        m = a == j
+        plain = (w64[m, None] * x64[m]).sum(0) / w64[m].sum()
+        assert np.all(np.abs(cent[0, j] - plain) <= 1e-4 * spread + 2.0 ** -22 * np.abs(plain))
+        obj_plain += (w64[m] * ((x64[m] - plain) ** 2).sum(-1)).sum()
+        obj_oracle += (w64[m] * ((x64[m] - cent[0, j].astype(np.float64)) ** 2).sum(-1)).sum()
+    assert obj_plain <= obj_oracle <= obj_plain * (1 + 1e-5)
+
+
+def test_sampling_scale_keeps_tiny_masses_and_never_overflows():
+    # The k-means++ masses are integers floor(p 2^kq) scaled so that their sum over N points stays
+    # below 2^62 while the largest keeps about 62 - log2 N bits.  (a) A point whose mass is 2^-40 of the
+    # largest still owns an interval: with 4 points the largest mass is 2^59 units and this one 2^19,
+    # at the bottom of the range (the point comes first) of 2^60 + 2^19 units in all, so exactly the
+    # random words below 2^23 pick it.  A scale one bit off moves that boundary; 20 bits too small
+    # would give the point no interval at all.  (b) 2^16 points of equal mass: the random
+    # word 2^63 (the middle of the range) picks the middle point; a scale three or more bits too
+    # large would overflow the 64-bit sum.
+    x = np.zeros((4, 2), dtype=np.float16)
+    x[:, 0] = [2.0 ** -10, 0.0, 1024.0, -1024.0]          # first pick: index 1 (the origin), rnd = 2^62
+    first = 2 ** 62                                        # floor(2^62 * 4 / 2^64) = 1
+    for r1, want in ((2 ** 22, 0), (2 ** 23 - 1, 0), (2 ** 23, 2)):
+        picks, _ = KO.kmeanspp(x, 2, 2, np.array([[first, r1]], dtype=np.uint64))
+        assert list(picks[0]) == [1, want], (r1, picks)
+    n = 2 ** 16
+    x = np.zeros((n, 2), dtype=np.float16)
+    x[1:, 0] = 1.0                                         # all but the first centre at the same distance
+    picks, _ = KO.kmeanspp(x, 2, 2, np.array([[0, 2 ** 63]], dtype=np.uint64))
+    assert picks[0, 0] == 0 and picks[0, 1] in (n // 2, n // 2 + 1)
+
+
 @pytest.mark.parametrize("c", [2, 4, 8])
 def test_lloyd_matches_sklearn_and_scipy_from_the_same_centres(c):
     rng = np.random.default_rng(10 + c)
