@@ -377,7 +377,16 @@ def extra_measurements(cq, synth, torch):
         "roofline": {"bound": "mfma", "kernel": "chunk_attention_kernel<16, 8, 8>", "achieved": executed, "peak": FP16_MFMA_PEAK_TFLOPS,
                      "unit": "TFLOP/s", "frac": executed / FP16_MFMA_PEAK_TFLOPS, "traffic": None,
                      "note": "executed fp16 MFMA work (probabilities split into two fp16 parts: 6 d flops per pair, 4 d useful)"}}
-    del qc, call_c, sets, st0
+    # the same chunk over the caches read as pre-RoPE keys: each key tile is rotated once in LDS
+    call_cr, _ = cq.prepare_chunk_attention_rope(qc, st0["kcache"], st0["vcache"], st0["ck"], st0["cv"], scale, fmt, T, T, rope)
+    med_cr, _ = time_calls(torch, call_cr, 4, 1)
+    out["chunk_attention_long_context_pre_rope_keys"] = {
+        "workload": "as chunk_attention_long_context, keys cached before RoPE (cq_chunk_attention_rope, base 10000)",
+        "ms": med_cr, "query_token_pairs_per_s": pairs / (med_cr * 1e-3), "slowdown_vs_position_independent": med_cr / med_c,
+        "roofline": {"bound": "mfma", "kernel": "chunk_attention_kernel<16, 8, 8, 8, true>",
+                     "achieved": pairs * 6 * cfg.head_dim / (med_cr * 1e-3) / 1e12, "peak": FP16_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
+                     "frac": pairs * 6 * cfg.head_dim / (med_cr * 1e-3) / 1e12 / FP16_MFMA_PEAK_TFLOPS, "traffic": None}}
+    del qc, call_c, call_cr, sets, st0
     torch.cuda.empty_cache()
 
     # ---- configurations 3 and 4

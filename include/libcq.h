@@ -448,19 +448,22 @@ CQ_API cq_status cq_decode_attention_rope_paged(const void *q, const void *k_poo
 
 /*
  * cq_chunk_attention_rope[_paged] -- cq_chunk_attention for caches whose keys were quantized
- * before the rotary position embedding: causal attention of the LAST m tokens of each sequence,
- * query token j (rotated by the caller to its own position t_n - m + j) over the cached tokens
- * 0 .. t_n - m + j.  Served token by token by the kernel of cq_decode_attention_rope (m launches
- * in stream order), so the results are bit-identical to m calls of cq_decode_attention_rope with
- * the contexts of the m tokens; meant for the few tokens of a speculative-decoding check (the
- * time is m times that of a decode step's attention).
+ * before the rotary position embedding (Section 3.2): causal attention of the LAST m tokens of
+ * each sequence, query token j (rotated by the caller to its own position t_n - m + j) over the
+ * cached tokens 0 .. t_n - m + j.  Chunks of more than two tokens (and any chunk when
+ * tokens_per_split is given) run on the matrix cores like cq_chunk_attention: each 64-token tile
+ * of keys is dequantised and rotated to its tokens' positions once per (tile, KV head) in fp32,
+ * rounded to fp16 and multiplied with all query rows of the workgroup.  With tokens_per_split = 0,
+ * chunks of one or two tokens are served token by token by the kernel of
+ * cq_decode_attention_rope (m launches in stream order, bit-identical to m calls of it).
  *   q, out            device, fp16 [batch][m][n_q_heads][head_dim]
  *   m                 1 <= m <= seq_lens[n] <= t <= t_cap (t <= rope_positions)
- *   tokens_per_split  of the m single-token calls: 0 = cq_decode_rope_default_split(...) of each
+ *   tokens_per_split  0 = library default; otherwise a multiple of 64 (context split of the
+ *                     matrix-core kernel, as in cq_chunk_attention)
  *   workspace         device, cq_chunk_rope_workspace_bytes(...) bytes
  *   everything else as in cq_decode_attention_rope.
  * Errors: as cq_decode_attention_rope; CQ_ERR_INVALID_ARG also for m <= 0 or m > t; nothing is
- * launched when the workspace is too small for any of the m tokens.
+ * launched when the workspace is too small.
  */
 CQ_API size_t cq_chunk_rope_workspace_bytes(const cq_format *fmt, int32_t batch, int32_t n_q_heads, int32_t m, int32_t t,
                                      int32_t tokens_per_split);

@@ -627,12 +627,20 @@ cq_status chunk_common(const void* q, const void* k_codes, const void* v_codes,
                        const void* k_centroids, const void* v_centroids, float scale, const cq_format* fmt,
                        int32_t batch, int32_t n_q_heads, int32_t m, int32_t t, int32_t t_cap, const cq_page_table* pages,
                        const int32_t* seq_lens, int32_t tokens_per_split,
-                       void* out, void* workspace, size_t workspace_bytes, void* stream)
+                       void* out, void* workspace, size_t workspace_bytes, void* stream,
+                       const void* rope_table = nullptr, int32_t rope_positions = 0)
 {
     Derived f;
     cq_status st = derive(fmt, &f);
     if (st != CQ_OK) return st;
     if (f.head_dim != 128) return CQ_ERR_UNSUPPORTED;
+    // keys cached before the rotary embedding: always the matrix-core kernel here (its caller serves
+    // the shortest chunks token by token itself)
+    const bool rope = rope_positions != 0;
+    if (rope) {
+        if (!rope_table || !aligned16(rope_table)) return CQ_ERR_INVALID_ARG;
+        if (rope_positions < 0 || rope_positions % kTileTokens != 0 || t > rope_positions) return CQ_ERR_INVALID_ARG;
+    }
     CacheMap map;
     if (pages) {
         if ((st = paged_map(f, pages, batch, &map, &t_cap)) != CQ_OK) return st;
@@ -648,7 +656,7 @@ cq_status chunk_common(const void* q, const void* k_codes, const void* v_codes,
     if (!aligned16(q) || !aligned16(k_codes) || !aligned16(v_codes) || !aligned16(k_centroids) ||
         !aligned16(v_centroids) || !aligned16(out) || !aligned16(workspace))
         return CQ_ERR_INVALID_ARG;
-    if (tokens_per_split == 0 && chunk_by_token(f, batch, n_q_heads, m, t)) {
+    if (!rope && tokens_per_split == 0 && chunk_by_token(f, batch, n_q_heads, m, t)) {
         for (int j = 0; j < m; ++j) {
             const TokenCall c = chunk_token_call(f, batch, n_q_heads, m, t, j);
             if (c.workspace && !workspace) return CQ_ERR_INVALID_ARG;
@@ -717,6 +725,8 @@ cq_status chunk_common(const void* q, const void* k_codes, const void* v_codes,
     a.n_split = n_split;
     a.partials = static_cast<float*>(workspace);
     a.out = static_cast<uint16_t*>(out);
+    a.rope_tile_tab = static_cast<const float2*>(rope_table);
+    a.rope_lane_tab = rope ? a.rope_tile_tab + (size_t)(rope_positions / kTileTokens) * 64 : nullptr;
     a.f = f;
     return launch_chunk_attention(a, static_cast<hipStream_t>(stream));
 }
@@ -886,6 +896,10 @@ cq_status cq_decode_step_rope_paged(const void* q, const void* x_k_new, const vo
 
 namespace {
 
+// Chunks of one or two query tokens over pre-RoPE keys go through the single-token kernel (one
+// launch per token), as long as the caller leaves the context split to the library.
+bool chunk_rope_by_token(int m, int tokens_per_split) { return tokens_per_split == 0 && m <= 2; }
+
 // split (tiles) and workspace need of query token j of a chunk over pre-RoPE keys
 TokenCall chunk_rope_token_call(const Derived& f, int batch, int n_q_heads, int m, int t, int j, int tokens_per_split)
 {
@@ -914,6 +928,11 @@ cq_status chunk_rope_common(const void* q, const void* k_codes, const void* v_co
     if (!q || !out || batch <= 0 || n_q_heads <= 0 || n_q_heads % f.n_kv_heads != 0) return CQ_ERR_INVALID_ARG;
     if (m <= 0 || t < m || rope_positions <= 0) return CQ_ERR_INVALID_ARG;
     if (tokens_per_split < 0 || tokens_per_split % kTileTokens != 0) return CQ_ERR_INVALID_ARG;
+    // chunks of more than two tokens (or with a split of the caller's): the matrix-core kernel, which
+    // rotates each dequantised key tile once for all query rows
+    if (!chunk_rope_by_token(m, tokens_per_split))
+        return chunk_common(q, k_codes, v_codes, k_centroids, v_centroids, scale, fmt, batch, n_q_heads, m, t, t_cap, pages,
+                            seq_lens, tokens_per_split, out, workspace, workspace_bytes, stream, rope_table, rope_positions);
     // all tokens are checked before the first one is launched
     for (int j = 0; j < m; ++j)
         if (workspace_bytes < chunk_rope_token_call(f, batch, n_q_heads, m, t, j, tokens_per_split).workspace)
@@ -939,7 +958,12 @@ size_t cq_chunk_rope_workspace_bytes(const cq_format* fmt, int32_t batch, int32_
     if (derive(fmt, &f) != CQ_OK || f.head_dim != 128) return 0;
     if (batch <= 0 || n_q_heads <= 0 || n_q_heads % f.n_kv_heads != 0 || m <= 0 || t < m) return 0;
     if (tokens_per_split < 0 || tokens_per_split % kTileTokens != 0) return 0;
-    if (tokens_per_split / kTileTokens > std::min(decode_rope_max_tiles_per_split(), decode_max_tiles_per_split(f))) return 0;
+    if (!chunk_rope_by_token(m, tokens_per_split)) {
+        const int tiles = tokens_per_split ? tokens_per_split / kTileTokens : chunk_tiles_per_split(f, batch, n_q_heads, m, t);
+        const int n_tiles = (t + kTileTokens - 1) / kTileTokens;
+        const int n_split = (n_tiles + tiles - 1) / tiles;
+        return sizeof(float) * (size_t)batch * m * n_q_heads * n_split * (f.head_dim + kPartialHeader);
+    }
     size_t need = 0;
     for (int j = 0; j < m; ++j) need = std::max(need, chunk_rope_token_call(f, batch, n_q_heads, m, t, j, tokens_per_split).workspace);
     return need;

@@ -33,8 +33,9 @@ constexpr int kKsStride = 272;                    // bytes per token row of the 
 constexpr int kVtStride = 136;                    // bytes per channel row of the transposed value tile (128 + 8)
 constexpr int kKsBytes = kTileTokens * kKsStride; // 17408
 constexpr int kVtBytes = 128 * kVtStride;         // 17408
-constexpr int kStageBytes = kKsBytes + kVtBytes;
-constexpr unsigned kRawBase = 2 * kStageBytes;    // behind the two stages: the raw code tiles (K, V) of two tiles
+// a stage: the key tile, the transposed value tile and (rotated keys only) the low parts of the key tile
+constexpr int kStageBytes(bool rope) { return kKsBytes + kVtBytes + (rope ? kKsBytes : 0); }
+constexpr unsigned kRawBase(bool rope) { return 2 * kStageBytes(rope); }     // behind the two stages: the raw code tiles (K, V) of two tiles
 constexpr float kProbScale = 4096.f;              // 2^12
 
 __device__ __forceinline__ half8_t lds_half8(unsigned byte_addr)
@@ -53,9 +54,23 @@ __device__ __forceinline__ half4_t lds_half4(unsigned byte_addr)
 // token's record.  A wavefront thus gathers from ONE group's centroids at a time: its 64 lanes
 // touch the 8 to 32 cache lines of that group's table instead of 64 lines of 64 tables, which is
 // what the texture path charges for.
-template <int GH, int C, int NW, int B>
+//
+// ROPE (keys cached before the rotary position embedding): thread (u, e) takes groups e, e + NW,
+// e + 2 NW, ... instead, so that it holds both halves of its channel pairs (channel i of the head
+// is rotated with channel i + 64, i.e. group g with group g + Gh/2), and store() rotates the
+// pairs to the token's position before the keys go to LDS: once per (tile, KV head), for all
+// query rows of the workgroup.
+template <int GH, int C, int NW, int B, bool ROPE>
 struct Dequant {
     static constexpr int GPT = GH / NW;                 // groups per thread
+    static_assert(!ROPE || GPT % 2 == 0, "a thread holds both groups of a pair");
+    static constexpr int NP = ROPE ? GPT / 2 * C : 1;   // channel pairs per thread
+    float2 cs[NP];                                      // ROPE: cos / sin of (position * theta) of this thread's pairs
+    // ROPE: low parts of the rotated keys.  A rotated key is kept as the sum of two fp16 numbers
+    // (22 bits): rounded to one, its error of 2^-11 reaches the scores and leaves 4e-4 of a
+    // row's largest output element, which fails the 2e-3 bar on the small elements
+    unsigned kwl[ROPE ? GPT : 1][C / 2];
+    __device__ __forceinline__ static int group(int e, int gi) { return ROPE ? e + gi * NW : e * GPT + gi; }
     static constexpr int K = 1 << B;                    // centroids per group
     static constexpr int TILE = kTileTokens * GH * B / 8;   // bytes of one tile's codes (b = 10: low bytes, then high-bit words)
     static constexpr int LOADERS = TILE / 16;           // threads that carry one record of K and one of V
@@ -84,10 +99,10 @@ struct Dequant {
     __device__ __forceinline__ void gather(unsigned raw_stage, const uint16_t* ck_head, const uint16_t* cv_head, int tid)
     {
         typedef __attribute__((address_space(3))) uint8_t lds_b;
-        const int u = tid & 63, g0 = (tid >> 6) * GPT;
+        const int u = tid & 63, e = tid >> 6;
 #pragma unroll
         for (int gi = 0; gi < GPT; ++gi) {
-            const int g = g0 + gi;
+            const int g = group(e, gi);
             const unsigned slot = (unsigned)(g - u) & (unsigned)(GH - 1);
             const unsigned off = (slot >> 4) * 1024 + (unsigned)u * 16 + (slot & 15);
             unsigned kc = *(lds_b*)(raw_stage + off);
@@ -108,17 +123,67 @@ struct Dequant {
         }
     }
 
+    // ROPE: cos / sin of the rotation of this thread's pairs for the tokens of `tile`, by angle
+    // addition from the table's two parts (64 tile theta_i per tile, u theta_i per lane)
+    __device__ __forceinline__ void request_angles(const float2* tile_tab, const float2* lane_tab, int tile, int tid)
+    {
+        if constexpr (ROPE) {
+            const int u = tid & 63, e = tid >> 6;
+#pragma unroll
+            for (int gi = 0; gi < GPT / 2; ++gi)
+#pragma unroll
+                for (int i = 0; i < C; ++i) {
+                    const int p = group(e, gi) * C + i;             // pair index = channel of the first half
+                    const float2 t = tile_tab[(size_t)tile * 64 + p], l = lane_tab[p * 64 + u];
+                    cs[gi * C + i] = make_float2(t.x * l.x - t.y * l.y, t.y * l.x + t.x * l.y);
+                }
+        }
+    }
+    // rotate the gathered keys: (k_i, k_{i+64}) -> (k_i cos - k_{i+64} sin, k_{i+64} cos + k_i sin), fp32, one
+    // rounding to fp16
+    __device__ __forceinline__ void rotate()
+    {
+        if constexpr (ROPE) {
+#pragma unroll
+            for (int gi = 0; gi < GPT / 2; ++gi)
+#pragma unroll
+                for (int i = 0; i < C / 2; ++i) {
+                    const half2_t lo = __builtin_bit_cast(half2_t, kw[gi][i]), hi = __builtin_bit_cast(half2_t, kw[gi + GPT / 2][i]);
+                    const float2 c0 = cs[gi * C + 2 * i], c1 = cs[gi * C + 2 * i + 1];
+                    const float fl0 = (float)lo.x * c0.x - (float)hi.x * c0.y, fh0 = (float)hi.x * c0.x + (float)lo.x * c0.y;
+                    const float fl1 = (float)lo.y * c1.x - (float)hi.y * c1.y, fh1 = (float)hi.y * c1.x + (float)lo.y * c1.y;
+                    half2_t rl, rh, el, eh;
+                    rl.x = (_Float16)fl0;
+                    rh.x = (_Float16)fh0;
+                    rl.y = (_Float16)fl1;
+                    rh.y = (_Float16)fh1;
+                    el.x = (_Float16)(fl0 - (float)rl.x);
+                    eh.x = (_Float16)(fh0 - (float)rh.x);
+                    el.y = (_Float16)(fl1 - (float)rl.y);
+                    eh.y = (_Float16)(fh1 - (float)rh.y);
+                    kw[gi][i] = __builtin_bit_cast(unsigned, rl);
+                    kw[gi + GPT / 2][i] = __builtin_bit_cast(unsigned, rh);
+                    kwl[gi][i] = __builtin_bit_cast(unsigned, el);
+                    kwl[gi + GPT / 2][i] = __builtin_bit_cast(unsigned, eh);
+                }
+        }
+    }
+
     __device__ __forceinline__ void store(unsigned stage, int tid) const
     {
         typedef __attribute__((address_space(3))) unsigned lds_u;
         typedef __attribute__((address_space(3))) uint16_t lds_h;
-        const int u = tid & 63, g0 = (tid >> 6) * GPT;
+        const int u = tid & 63, e = tid >> 6;
 #pragma unroll
         for (int gi = 0; gi < GPT; ++gi) {
-            const int g = g0 + gi;
+            const int g = group(e, gi);
             const unsigned kaddr = stage + (unsigned)u * kKsStride + (unsigned)g * (C * 2);
 #pragma unroll
             for (int i = 0; i < C / 2; ++i) *(lds_u*)(kaddr + 4 * i) = kw[gi][i];
+            if constexpr (ROPE) {
+#pragma unroll
+                for (int i = 0; i < C / 2; ++i) *(lds_u*)(kaddr + kKsBytes + kVtBytes + 4 * i) = kwl[gi][i];
+            }
             const unsigned vaddr = stage + kKsBytes + (unsigned)(g * C) * kVtStride + (unsigned)u * 2;
 #pragma unroll
             for (int i = 0; i < C / 2; ++i) {
@@ -129,11 +194,11 @@ struct Dequant {
     }
 };
 
-template <int GH, int C, int NW, int B>
+template <int GH, int C, int NW, int B, bool ROPE>
 __global__ __launch_bounds__(NW * 64) void chunk_attention_kernel(ChunkArgs a)
 {
     constexpr int kRowsPerWg = NW * 32;
-    constexpr unsigned kRawStageBytes = Dequant<GH, C, NW, B>::RAW_STAGE;
+    constexpr unsigned kRawStageBytes = Dequant<GH, C, NW, B, ROPE>::RAW_STAGE;
     using F = Fmt<GH, B>;
     constexpr int D = 128;
     static_assert(GH * C == D, "head_dim 128");
@@ -204,24 +269,27 @@ __global__ __launch_bounds__(NW * 64) void chunk_attention_kernel(ChunkArgs a)
 
     // software pipeline over the tiles: while tile k is multiplied, the centroids of tile k + 1
     // are on their way from L2 and the codes of tile k + 2 from HBM
-    Dequant<GH, C, NW, B> dq;
+    Dequant<GH, C, NW, B, ROPE> dq;
     if (tile0 < tile1) {
         dq.load_raw(tile_ptr(a.k_codes, tile0), tile_ptr(a.v_codes, tile0), tid);
-        dq.store_raw(kRawBase, tid);
+        dq.store_raw(kRawBase(ROPE), tid);
         if (tile0 + 1 < tile1) dq.load_raw(tile_ptr(a.k_codes, tile0 + 1), tile_ptr(a.v_codes, tile0 + 1), tid);
         lds_barrier();
-        dq.gather(kRawBase, ck_head, cv_head, tid);
+        dq.gather(kRawBase(ROPE), ck_head, cv_head, tid);
+        dq.request_angles(a.rope_tile_tab, a.rope_lane_tab, tile0, tid);
+        dq.rotate();
         dq.store(0, tid);
-        if (tile0 + 1 < tile1) dq.store_raw(kRawBase + kRawStageBytes, tid);
+        if (tile0 + 1 < tile1) dq.store_raw(kRawBase(ROPE) + kRawStageBytes, tid);
     }
     lds_barrier();
 
     for (int tile = tile0; tile < tile1; ++tile) {
         const unsigned par = (unsigned)((tile - tile0) & 1);
-        const unsigned stage = par * kStageBytes;
+        const unsigned stage = par * kStageBytes(ROPE);
         const bool more = tile + 1 < tile1;
         if (more) {
-            dq.gather(kRawBase + (par ^ 1u) * kRawStageBytes, ck_head, cv_head, tid);     // codes of tile + 1
+            dq.gather(kRawBase(ROPE) + (par ^ 1u) * kRawStageBytes, ck_head, cv_head, tid);     // codes of tile + 1
+            dq.request_angles(a.rope_tile_tab, a.rope_lane_tab, tile + 1, tid);
             if (tile + 2 < tile1) dq.load_raw(tile_ptr(a.k_codes, tile + 2), tile_ptr(a.v_codes, tile + 2), tid);
             __builtin_amdgcn_sched_barrier(0);          // requests first, then the multiplications
         }
@@ -240,6 +308,11 @@ __global__ __launch_bounds__(NW * 64) void chunk_attention_kernel(ChunkArgs a)
 #pragma unroll
                 for (int s = 0; s < 8; ++s)
                     acc[tb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(lds_half8(krow + 32 * s), qreg[s], acc[tb], 0, 0, 0);
+                if constexpr (ROPE) {           // ... and the low parts of the rotated keys
+#pragma unroll
+                    for (int s = 0; s < 8; ++s)
+                        acc[tb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(lds_half8(krow + kKsBytes + kVtBytes + 32 * s), qreg[s], acc[tb], 0, 0, 0);
+                }
             }
 #pragma unroll
             for (int tb = 0; tb < 2; ++tb) {
@@ -304,9 +377,10 @@ __global__ __launch_bounds__(NW * 64) void chunk_attention_kernel(ChunkArgs a)
         }
         // the next tile goes to the other stage (its last readers passed the previous barrier)
         if (more) {
-            dq.store(stage ^ kStageBytes, tid);
+            dq.rotate();
+            dq.store(par ? 0u : (unsigned)kStageBytes(ROPE), tid);
             // the raw tile read two steps ago (tile's own codes) makes room for those of tile + 2
-            if (tile + 2 < tile1) dq.store_raw(kRawBase + par * kRawStageBytes, tid);
+            if (tile + 2 < tile1) dq.store_raw(kRawBase(ROPE) + par * kRawStageBytes, tid);
         }
         lds_barrier();
     }
@@ -346,16 +420,16 @@ __global__ __launch_bounds__(NW * 64) void chunk_attention_kernel(ChunkArgs a)
     }
 }
 
-template <int GH, int C, int NW, int B>
+template <int GH, int C, int NW, int B, bool ROPE>
 cq_status launch_chunk_variant(const ChunkArgs& a, hipStream_t stream)
 {
-    auto kernel = chunk_attention_kernel<GH, C, NW, B>;
+    auto kernel = chunk_attention_kernel<GH, C, NW, B, ROPE>;
     static LdsKernelSetup setup;
     if (setup.ensure(reinterpret_cast<const void*>(kernel)) != hipSuccess) return CQ_ERR_HIP;
     const int qper = a.n_q_heads / a.f.n_kv_heads;
     const int row_blocks = (a.m * qper + NW * 32 - 1) / (NW * 32);
     const unsigned grid = (unsigned)(a.batch * a.n_split * row_blocks * a.f.n_kv_heads);
-    const size_t lds = 2 * kStageBytes + 2 * Dequant<GH, C, NW, B>::RAW_STAGE;
+    const size_t lds = 2 * kStageBytes(ROPE) + 2 * Dequant<GH, C, NW, B, ROPE>::RAW_STAGE;
     hipLaunchKernelGGL(kernel, dim3(grid), dim3(NW * 64), lds, stream, a);
     return hipGetLastError() == hipSuccess ? CQ_OK : CQ_ERR_HIP;
 }
@@ -364,8 +438,12 @@ template <int GH, int C, int B>
 cq_status launch_chunk_rows(const ChunkArgs& a, hipStream_t stream)
 {
     const int rows = a.m * (a.n_q_heads / a.f.n_kv_heads);
-    if (chunk_rows_per_workgroup(rows) == 128) return launch_chunk_variant<GH, C, 4, B>(a, stream);
-    return launch_chunk_variant<GH, C, 8, B>(a, stream);
+    if (a.rope_tile_tab) {
+        if (chunk_rows_per_workgroup(rows) == 128) return launch_chunk_variant<GH, C, 4, B, true>(a, stream);
+        return launch_chunk_variant<GH, C, 8, B, true>(a, stream);
+    }
+    if (chunk_rows_per_workgroup(rows) == 128) return launch_chunk_variant<GH, C, 4, B, false>(a, stream);
+    return launch_chunk_variant<GH, C, 8, B, false>(a, stream);
 }
 
 }  // namespace

@@ -141,6 +141,10 @@ struct ChunkArgs {
     int tiles_per_split, n_split;
     float* partials;          // [batch][m][n_q_heads][n_split][2 + head_dim]
     uint16_t* out;            // fp16 [batch][m][n_q_heads][head_dim]
+    // keys cached before the rotary position embedding (null: keys are used as stored): the two
+    // parts of the table of cq_rope_table, cos / sin of (64 tile theta_i) and of (lane theta_i)
+    const float2* rope_tile_tab;
+    const float2* rope_lane_tab;
     Derived f;
 };
 int chunk_rows_per_workgroup(int rows_per_kv_head);

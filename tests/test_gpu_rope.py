@@ -304,10 +304,12 @@ def test_rope_attention_and_step_sweep(case):
 
 
 # ------------------------------------------------------------------------------------------
-# several query tokens over pre-rotation caches (token by token through the decode kernel)
+# several query tokens over pre-rotation caches: the matrix-core kernel (key tiles rotated once
+# per tile and KV head); chunks of one or two tokens token by token through the decode kernel
 # ------------------------------------------------------------------------------------------
 @pytest.mark.parametrize("c,b", ATTN_FORMATS)
-@pytest.mark.parametrize("hq,hkv,m,T,split", [(4, 4, 1, 1, 0), (4, 2, 3, 3, 0), (8, 2, 5, 700, 0), (4, 4, 4, 1000, 256)])
+@pytest.mark.parametrize("hq,hkv,m,T,split", [(4, 4, 1, 1, 0), (4, 2, 2, 333, 0), (4, 2, 3, 3, 0), (8, 2, 5, 700, 0), (4, 4, 4, 1000, 256),
+                                              (4, 2, 31, 65, 0), (4, 2, 33, 129, 1024), (4, 2, 100, 1000, 0)])
 def test_rope_chunk_matches_oracle_and_token_by_token_calls(c, b, hq, hkv, m, T, split):
     B, t_cap = 3, 1024
     fmt, _, kc, vc, ck, cv = _case(50 + m + T, c, b, hq, hkv, B, T)
@@ -321,10 +323,39 @@ def test_rope_chunk_matches_oracle_and_token_by_token_calls(c, b, hq, hkv, m, T,
     out = out.cpu().numpy()
     ref = O.chunk_attention(q, kc, vc, ck, cv, 0.1, hkv, seq_lens=lens, rope_base=BASE)
     check_attention(out.reshape(B * m, hq, 128), ref.reshape(B * m, hq, 128))
-    for j in range(m):
+    for j in range(m if m <= 5 else 0):
         dec = _gpu(np.ascontiguousarray(q[:, j]), kcache, vcache, ck, cv, 0.1, fmt, T - (m - 1 - j), t_cap, rope,
-                   seq_lens=lens - (m - 1 - j), split=split)
-        assert np.array_equal(out[:, j].view(np.uint16), dec.view(np.uint16))
+                   seq_lens=lens - (m - 1 - j))
+        if m <= 2 and split == 0:       # served token by token: the decode kernel's own results
+            assert np.array_equal(out[:, j].view(np.uint16), dec.view(np.uint16))
+        else:                           # the matrix-core kernel agrees with it within the tolerance
+            assert np.max(np.abs(out[:, j].astype(np.float64) - dec.astype(np.float64))) <= 2e-3 * np.max(np.abs(ref[:, j]))
+
+
+@pytest.mark.parametrize("c,b", ATTN_FORMATS)
+def test_rope_chunk_splits_ragged_lengths_many_rows_and_far_positions(c, b):
+    # 70 query tokens x 4 query heads per KV head = 280 rows per KV head (three 128-row blocks), context
+    # splits, ragged lengths; then the same chunk at positions beyond 30000 (base 500000)
+    hq, hkv, B, m, T, t_cap = 8, 2, 3, 70, 1500, 1536
+    fmt, _, kc, vc, ck, cv = _case(7, c, b, hq, hkv, B, T)
+    q = np.random.default_rng(70).standard_normal((B, m, hq, 128)).astype(np.float16)
+    lens = np.array([1500, 70, 777], dtype=np.int32)
+    ref = O.chunk_attention(q, kc, vc, ck, cv, 0.1, hkv, seq_lens=lens, rope_base=BASE)
+    rope = cq.RopeTable(BASE, t_cap)
+    kcache, vcache = codes_to_cache(kc, fmt, t_cap), codes_to_cache(vc, fmt, t_cap)
+    for split in (0, 64, 512, 1536):
+        out = cq.cq_chunk_attention_rope(dev(q), kcache, vcache, dev(ck), dev(cv), 0.1, fmt, T, t_cap, rope,
+                                         seq_lens=dev(lens), tokens_per_split=split)
+        torch.cuda.synchronize()
+        check_attention(out.cpu().numpy().reshape(B * m, hq, 128), ref.reshape(B * m, hq, 128))
+    hq, hkv, B, m, T, t_cap = 4, 1, 1, 40, 32000, 32000
+    fmt, _, kc, vc, ck, cv = _case(8, c, b, hq, hkv, B, T)
+    q = np.random.default_rng(71).standard_normal((B, m, hq, 128)).astype(np.float16)
+    ref = O.chunk_attention(q, kc, vc, ck, cv, 0.1, hkv, rope_base=500000.0)
+    out = cq.cq_chunk_attention_rope(dev(q), codes_to_cache(kc, fmt, t_cap), codes_to_cache(vc, fmt, t_cap), dev(ck), dev(cv), 0.1, fmt,
+                                     T, t_cap, cq.RopeTable(500000.0, t_cap))
+    torch.cuda.synchronize()
+    check_attention(out.cpu().numpy().reshape(B * m, hq, 128), ref.reshape(B * m, hq, 128))
 
 
 def test_rope_chunk_paged_equals_contiguous():

@@ -276,17 +276,26 @@ def test_rope_sizes_and_argument_checks_without_launching():
     assert lib.cq_decode_step_rope(_fake(0x10000), _fake(0x11000), _fake(0x12000), 256, _fake(0x20000), _fake(0x30000),
                                    _fake(0x40000), _fake(0x50000), 0.1, ctypes.byref(f64), 2, 8, 128, 128, None, 0,
                                    _fake(0x80000), 4096, _fake(0x60000), _fake(0x70000), 1 << 30, None) == cq.CQ_ERR_UNSUPPORTED
-    # several query tokens over such caches: the workspace of the largest of the m single-token calls
-    assert cq.cq_chunk_rope_workspace_bytes(fmt, 2, 8, 3, 4096) == max(
-        cq.cq_decode_workspace_bytes(fmt, 2, 8, t, cq.cq_decode_rope_default_split(fmt, 2, 8, t)) for t in (4094, 4095, 4096))
+    # several query tokens over such caches.  One or two tokens (library's split): the workspace of the
+    # largest of the m single-token calls; more, or a split of the caller's: that of the matrix-core kernel
+    assert cq.cq_chunk_rope_workspace_bytes(fmt, 2, 8, 2, 4096) == max(
+        cq.cq_decode_workspace_bytes(fmt, 2, 8, t, cq.cq_decode_rope_default_split(fmt, 2, 8, t)) for t in (4095, 4096))
+    assert cq.cq_chunk_rope_workspace_bytes(fmt, 2, 8, 3, 4096) == 4 * 2 * 3 * 8 * 130 * (4096 // cq.cq_chunk_default_split(fmt, 2, 8, 3, 4096))
+    assert cq.cq_chunk_rope_workspace_bytes(fmt, 2, 8, 2, 4096, 1024) == 4 * 2 * 2 * 8 * 4 * 130
     assert cq.cq_chunk_rope_workspace_bytes(fmt, 2, 8, 5000, 4096) == 0 and cq.cq_chunk_rope_workspace_bytes(fmt, 2, 8, 3, 4096, 100) == 0
 
-    def chunk(m=3, t=128, ws_bytes=1 << 30, pos=4096, split=0):
+    def chunk(m=3, t=128, t_cap=128, ws_bytes=1 << 30, pos=4096, split=0, table=0x80000):
         return int(lib.cq_chunk_attention_rope(_fake(0x10000), _fake(0x20000), _fake(0x30000), _fake(0x40000), _fake(0x50000),
-                                               0.1, ctypes.byref(fmt._c()), 2, 8, m, t, 128, None, split, _fake(0x80000), pos,
+                                               0.1, ctypes.byref(fmt._c()), 2, 8, m, t, t_cap, None, split, _fake(table) if table else None, pos,
                                                _fake(0x60000), _fake(0x70000), ws_bytes, None))
     assert chunk(m=0) == cq.CQ_ERR_INVALID_ARG and chunk(m=129) == cq.CQ_ERR_INVALID_ARG and chunk(pos=0) == cq.CQ_ERR_INVALID_ARG
-    assert chunk(split=100) == cq.CQ_ERR_INVALID_ARG and chunk(ws_bytes=16) == cq.CQ_ERR_WORKSPACE_TOO_SMALL
+    assert chunk(split=100) == cq.CQ_ERR_INVALID_ARG and chunk(m=2, ws_bytes=16) == cq.CQ_ERR_WORKSPACE_TOO_SMALL
+    # the matrix-core form: table and workspace checks
+    assert chunk(t=4096, t_cap=4096, split=64, ws_bytes=16) == cq.CQ_ERR_WORKSPACE_TOO_SMALL
+    assert chunk(t=4096, t_cap=4096, split=64, table=0) == cq.CQ_ERR_INVALID_ARG
+    assert chunk(t=4096, t_cap=4096, split=64, table=0x80004) == cq.CQ_ERR_INVALID_ARG
+    assert chunk(t=4096, t_cap=4096, split=64, pos=2048) == cq.CQ_ERR_INVALID_ARG      # table shorter than the context
+    assert chunk(t=4096, t_cap=4096, split=64, pos=4100) == cq.CQ_ERR_INVALID_ARG
     assert cq.cq_decode_rope_default_split(cq.CQFormat(2, 8, 128, 32), 64, 32, 64 * 1000) == 64 * 125    # 8 balanced splits of at most 128 tiles (256 without the rotation)
 
 
