@@ -93,7 +93,7 @@ struct StaticScratch {
 };
 StaticScratch g_static_scratch;
 
-int default_tiles_per_split(const Derived& f, int batch, int n_q_heads, int t, int max_tiles)
+int default_tiles_per_split(const Derived& f, int batch, int n_q_heads, int t, int max_tiles, bool rope = false)
 {
     // A workgroup costs its tiles plus a fixed part (table build, bins x centroids: each reads a
     // whole head's codebook), here expressed in tiles of streaming time; the chip runs `slots`
@@ -101,8 +101,10 @@ int default_tiles_per_split(const Derived& f, int batch, int n_q_heads, int t, i
     // rounds x (tiles + fixed) over the splits the kernel allows, down to 16 tiles per split.
     const int n_tiles = (t + kTileTokens - 1) / kTileTokens;
     const long bh = (long)batch * n_q_heads;
-    const long slots = 512;
-    const long fixed = f.b == 10 ? 180 : (f.gh == 16 ? 60 : (f.gh == 32 ? 30 : 15));
+    // (keys cached before RoPE: one workgroup per CU, and a tile costs several times the arithmetic,
+    // so the fixed part is worth fewer of them)
+    const long slots = rope ? 256 : 512;
+    const long fixed = rope ? (f.b == 10 ? 32 : 8) : (f.b == 10 ? 180 : (f.gh == 16 ? 60 : (f.gh == 32 ? 30 : 15)));
     const long ns_min = (n_tiles + max_tiles - 1) / max_tiles;
     const long ns_max = std::max<long>(ns_min, n_tiles / 16);
     long best_ns = ns_min, best_cost = -1;
@@ -122,6 +124,11 @@ int default_tiles_per_split(const Derived& f, int batch, int n_q_heads, int t, i
 int default_tiles_per_split(const Derived& f, int batch, int n_q_heads, int t)
 {
     return default_tiles_per_split(f, batch, n_q_heads, t, decode_max_tiles_per_split(f));
+}
+
+int rope_default_tiles_per_split(const Derived& f, int batch, int n_q_heads, int t)
+{
+    return default_tiles_per_split(f, batch, n_q_heads, t, decode_rope_max_tiles_per_split(), true);
 }
 
 }  // namespace
@@ -473,7 +480,7 @@ cq_status decode_common(const void* q, const void* x_k_new, const void* x_v_new,
     }
     const int max_tiles = rope ? decode_rope_max_tiles_per_split() : decode_max_tiles_per_split(f);
     const int tiles = tokens_per_split ? tokens_per_split / kTileTokens
-                                       : default_tiles_per_split(f, batch, n_q_heads, t, max_tiles);
+                                       : default_tiles_per_split(f, batch, n_q_heads, t, max_tiles, rope);
     if (tiles > max_tiles) return CQ_ERR_INVALID_ARG;
     const int n_tiles = (t + kTileTokens - 1) / kTileTokens;
     const int n_split = (n_tiles + tiles - 1) / tiles;
@@ -847,7 +854,7 @@ int32_t cq_decode_rope_default_split(const cq_format* fmt, int32_t batch, int32_
 {
     Derived f;
     if (derive(fmt, &f) != CQ_OK || f.head_dim != 128 || batch <= 0 || n_q_heads <= 0 || t <= 0) return 0;
-    return default_tiles_per_split(f, batch, n_q_heads, t, std::min(decode_rope_max_tiles_per_split(), decode_max_tiles_per_split(f))) * kTileTokens;
+    return rope_default_tiles_per_split(f, batch, n_q_heads, t) * kTileTokens;
 }
 
 cq_status cq_decode_attention_rope(const void* q, const void* k_codes, const void* v_codes,
@@ -906,8 +913,7 @@ TokenCall chunk_rope_token_call(const Derived& f, int batch, int n_q_heads, int 
     TokenCall c;
     c.t = t - (m - 1 - j);
     c.tiles = tokens_per_split ? tokens_per_split / kTileTokens
-                               : default_tiles_per_split(f, batch, n_q_heads, c.t,
-                                                         std::min(decode_rope_max_tiles_per_split(), decode_max_tiles_per_split(f)));
+                               : rope_default_tiles_per_split(f, batch, n_q_heads, c.t);
     const int n_tiles = (c.t + kTileTokens - 1) / kTileTokens;
     c.n_split = (n_tiles + c.tiles - 1) / c.tiles;
     c.workspace = sizeof(float) * (size_t)batch * n_q_heads * c.n_split * (f.head_dim + kPartialHeader);

@@ -5,19 +5,22 @@
 // head form a pair that is rotated by position * base^(-2i/d); the query arrives already rotated.
 //
 // The rotation angle differs per channel pair, so the score of a token can no longer be summed
-// from one table entry per group.  Instead the rotation is moved to the query side,
-//     q . R_t k  =  sum_i  k_i a_i(t) + k_{i+64} b_i(t),
-//     a_i(t) = q_i cos(t th_i) + q_{i+64} sin(t th_i),  b_i(t) = q_{i+64} cos(t th_i) - q_i sin(t th_i),
-// and split by the angle-addition theorem into a per-tile part (t0 = 64 * tile: one rotated query
-// per tile and wavefront, lane i computing pair i; the other lanes fetch it with v_readlane) and a
-// per-lane part (the token's offset within the tile: a table cos / sin(lane * th_i), 32 KB of LDS):
-//     a_i(t0 + u) = cos(u th_i) a_i(t0) + sin(u th_i) b_i(t0),   b_i(t0 + u) = cos(u th_i) b_i(t0) - sin(u th_i) a_i(t0).
-// Lane = token as in the position-independent kernel; the key centroids themselves (fp16, 64 KB
-// per head) take the place of the score table in LDS, and a token costs, per channel pair, one
-// 8-byte LDS read, two lane reads and six VALU instructions (against one gather and one add per
-// GROUP without rotation): phase K is bound by the vector ALU, not by HBM.  Phase V, the
-// epilogue and the split-context merge are those of cq_decode.hip.  Both trigonometric tables
-// come from cq_rope_table (computed in fp64).
+// from one table entry per group.  With t = t0 + u (t0 = 64 * tile, u = the token's lane) the
+// rotation is split by the angle-addition theorem: the key is rotated to the tile's base position,
+//     X_i = k_i cos(t0 th_i) - k_{i+64} sin(t0 th_i),   Y_i = k_{i+64} cos(t0 th_i) + k_i sin(t0 th_i),
+// (the cosines and sines of a tile are the same for all its tokens: scalar operands, read with
+// scalar loads from a [tile][pair] table), and the rest of the way is taken by the query instead,
+//     q . R_t k  =  sum_i  X_i A_i(u) + Y_i B_i(u),
+//     A_i(u) = q_i cos(u th_i) + q_{i+64} sin(u th_i),   B_i(u) = q_{i+64} cos(u th_i) - q_i sin(u th_i),
+// which depends on the lane only: 128 registers per lane, computed once per workgroup from a
+// [pair][lane] table.  Lane = token as in the position-independent kernel; the key centroids
+// themselves (fp16, 64 KB per head) take the place of the score table in LDS, and a token costs,
+// per channel pair, six VALU instructions (against one gather and one add per GROUP without
+// rotation) and no LDS access beyond its centroids: phase K is bound by the vector ALU, not by
+// HBM.  512 threads, one workgroup per CU (the registers of the per-lane query want two
+// wavefronts per SIMD at most).  Phase V, the epilogue and the split-context merge are those of
+// the position-independent kernel.  Both trigonometric tables come from cq_rope_table (computed
+// in fp64).
 #include "cq_decode_common.hpp"
 
 namespace cq {
@@ -25,7 +28,9 @@ namespace {
 
 constexpr int kPairs = 64;                        // head_dim / 2
 constexpr unsigned kTabBytes = 65536;             // centroids (phase K), then bins (phase V)
-constexpr unsigned kTrgBytes = kPairs * 64 * 8;   // cos / sin(lane * theta_i)
+constexpr int kRopeThreads = 512;
+struct CosSin { float c, s; };
+constexpr unsigned kScrBytes = (64 + kRopeThreads / 64 * 128) * 4;     // reductions: two rows of per-wavefront scalars, per-wavefront outputs
 
 __global__ void rope_tables_kernel(double base, int n_tiles, float2* tile_tab, float2* lane_tab)
 {
@@ -79,11 +84,28 @@ __device__ __forceinline__ CenVec<C> global_centroid(const uint16_t* p)
     for (int i = 0; i < C / 2; ++i) v.w[i] = reinterpret_cast<const unsigned*>(p)[i];
     return v;
 }
-__device__ __forceinline__ float2 lds_load2(unsigned byte_addr)
+// One mixed-precision multiply-add: the fp16 half HI of register `w`, times the fp32 scalar `s`,
+// plus / minus the fp32 `c` (or plus nothing).  Written out because the compiler converts a half
+// that is used twice to fp32 first (one more instruction per channel) instead of letting both
+// users read it as it is.  Volatile: the statements stay in the order written, which is batches of
+// sixteen independent ones (a wavefront has one partner on its SIMD to hide a dependent
+// instruction's latency behind, so it has to bring its own independent work).
+__device__ __forceinline__ float mix_mul(bool HI, unsigned w, float s)
 {
-    typedef float f2 __attribute__((ext_vector_type(2)));
-    const f2 a = *(__attribute__((address_space(3))) f2*)(byte_addr);
-    return make_float2(a.x, a.y);
+    float d;
+    if (HI) asm volatile("v_fma_mix_f32 %0, %1, %2, 0 op_sel:[1,0,0] op_sel_hi:[1,0,0]" : "=v"(d) : "v"(w), "s"(s));
+    else asm volatile("v_fma_mix_f32 %0, %1, %2, 0 op_sel:[0,0,0] op_sel_hi:[1,0,0]" : "=v"(d) : "v"(w), "s"(s));
+    return d;
+}
+template <bool MINUS>
+__device__ __forceinline__ float mix_fma(bool HI, unsigned w, float s, float c)
+{
+    float d;
+    if (HI && MINUS) asm volatile("v_fma_mix_f32 %0, %1, %2, -%3 op_sel:[1,0,0] op_sel_hi:[1,0,0]" : "=v"(d) : "v"(w), "s"(s), "v"(c));
+    else if (HI) asm volatile("v_fma_mix_f32 %0, %1, %2, %3 op_sel:[1,0,0] op_sel_hi:[1,0,0]" : "=v"(d) : "v"(w), "s"(s), "v"(c));
+    else if (MINUS) asm volatile("v_fma_mix_f32 %0, %1, %2, -%3 op_sel:[0,0,0] op_sel_hi:[1,0,0]" : "=v"(d) : "v"(w), "s"(s), "v"(c));
+    else asm volatile("v_fma_mix_f32 %0, %1, %2, %3 op_sel:[0,0,0] op_sel_hi:[1,0,0]" : "=v"(d) : "v"(w), "s"(s), "v"(c));
+    return d;
 }
 
 // A token's codes in group order.  The cache stores the code of group (s + u) mod Gh in slot s
@@ -140,11 +162,12 @@ __global__ __launch_bounds__(NT) void decode_rope_kernel(DecodeArgs a, const flo
     constexpr int UNITS = 16 * K / JPL;
     constexpr int IPT = UNITS / NT;
     static_assert(D == 128 && UNITS % NT == 0, "head_dim 128");
-    constexpr unsigned SC_BASE = kTabBytes + kTrgBytes;
+    static_assert(NT == kRopeThreads, "LDS layout");
+    constexpr unsigned SC_BASE = kTabBytes + kScrBytes;
     extern __shared__ float smem[];
-    float* tab = smem;                                              // bins in phase V
+    float* tab = smem;                                              // centroids in phase K, bins in phase V
     float* sc = smem + SC_BASE / 4;                                 // scores of the split
-    float* scr = smem + kTabBytes / 4;                              // reductions (the lane table is dead by then)
+    float* scr = smem + kTabBytes / 4;                              // reductions
     // fused step: (distance, index) minima per group, keys[0..GH) for K, [GH..2GH) for V, then the new token's weight
     unsigned long long* keys = reinterpret_cast<unsigned long long*>(smem + SC_BASE / 4 + a.tiles_per_split * kTileTokens);
 
@@ -210,28 +233,20 @@ __global__ __launch_bounds__(NT) void decode_rope_kernel(DecodeArgs a, const flo
         vwalk = kwalk;
         vwalk.base = a.v_codes + stream_idx;
     }
+    // phase K keeps one tile in flight ahead of the one it works on (a tile is thousands of cycles
+    // of arithmetic; every further copy of its body would only crowd the instruction cache)
+    Streamer<GH, B, 1> stk;
     Streamer<GH, B, PF> st;
 
-    // ---- 1. the head's key centroids and the lane table go to LDS; this lane's query pair ----
-    {
-        if constexpr (B == 8) {
-            const uint4* src = reinterpret_cast<const uint4*>(a.k_centroids + (size_t)hkv * GH * K * C);
-            for (int i = tid; i < (int)(kTabBytes / 16); i += NT) reinterpret_cast<uint4*>(smem)[i] = src[i];
-        }
-        const uint4* lt = reinterpret_cast<const uint4*>(lane_tab);
-        for (int i = tid; i < (int)(kTrgBytes / 16); i += NT) reinterpret_cast<uint4*>(smem + kTabBytes / 4)[i] = lt[i];
+    // ---- 1. the head's key centroids go to LDS; this lane's query, rotated back by its offset ----
+    if constexpr (B == 8) {
+        const uint4* src = reinterpret_cast<const uint4*>(a.k_centroids + (size_t)hkv * GH * K * C);
+        for (int i = tid; i < (int)(kTabBytes / 16); i += NT) reinterpret_cast<uint4*>(smem)[i] = src[i];
     }
-    const uint16_t* qh = a.q + (size_t)n * a.q_batch_stride + (size_t)hq * D;
-    const float qa = (float)__builtin_bit_cast(_Float16, qh[lane]) * a.scale_log2e;
-    const float qb = (float)__builtin_bit_cast(_Float16, qh[lane + kPairs]) * a.scale_log2e;
-    st.begin(kwalk, my_tiles, lane);
-    // cos / sin of the first tile's base position for this lane's pair (one tile ahead from now on)
-    auto tile_cs = [&](int k) {
-        const int kk = k < my_tiles ? k : (my_tiles > 0 ? my_tiles - 1 : 0);
-        const int tile = my_tiles > 0 ? tile0 + wave + kk * NW : tile0;
-        return tile_tab[(size_t)tile * kPairs + lane];
-    };
-    float2 cs_next = tile_cs(0);
+    stk.begin(kwalk, my_tiles, lane);
+    // cos / sin of the tiles' base positions: uniform per wavefront, read through the scalar cache
+    typedef __attribute__((address_space(4))) const CosSin tile_cs_t;
+    tile_cs_t* tile_cs = (tile_cs_t*)reinterpret_cast<unsigned long long>(tile_tab);
     const int gl16 = tid & 15;
     unsigned xvw[STEP ? NCH : 1][C / 2];            // fused step: this thread's slices of the new value row
     lds_barrier();
@@ -279,7 +294,22 @@ __global__ __launch_bounds__(NT) void decode_rope_kernel(DecodeArgs a, const flo
         store_new_codes<GH, B>(const_cast<uint8_t*>(a.k_codes) + a.map.tile_index(n, hkv, tile_new) * F::TILE_BYTES, keys, u_new, tid);
 
     // ---- 2. phase K: scores ----------------------------------------------------------------
-    const unsigned trg_lane = kTabBytes + (unsigned)lane * 8;
+    float qa[kPairs], qb[kPairs];
+    {
+        const unsigned* qh = reinterpret_cast<const unsigned*>(a.q + (size_t)n * a.q_batch_stride + (size_t)hq * D);
+#pragma unroll
+        for (int i = 0; i < kPairs; i += 2) {
+            // (the query is the same for all lanes: scalar loads)
+            const half2_t lo = __builtin_bit_cast(half2_t, qh[i >> 1]), hi = __builtin_bit_cast(half2_t, qh[(i + kPairs) >> 1]);
+#pragma unroll
+            for (int e = 0; e < 2; ++e) {
+                const float2 cs = lane_tab[(i + e) * 64 + lane];
+                const float q0 = (float)(e ? lo.y : lo.x) * a.scale_log2e, q1 = (float)(e ? hi.y : hi.x) * a.scale_log2e;
+                qa[i + e] = __builtin_fmaf(q0, cs.x, q1 * cs.y);
+                qb[i + e] = __builtin_fmaf(q1, cs.x, -(q0 * cs.y));
+            }
+        }
+    }
     const uint16_t* k_head = a.k_centroids + (size_t)hkv * GH * K * C;
     Unrotate unrot;
     unrot.bytes = (unsigned)(GH - lane) & 3u;
@@ -289,55 +319,96 @@ __global__ __launch_bounds__(NT) void decode_rope_kernel(DecodeArgs a, const flo
     const bool meets_new = has_new && (tile_new - tile0) % NW == wave;
     NewTokenCodes<GH, B> new_codes;
     if (meets_new) new_codes.build(keys, u_new, lane);
-    st.run(kwalk, my_tiles, lane, [&](const Tile<GH, B>& w_in, int k) {
+    constexpr int kBatch = 8;                       // channel pairs per batch of scalars and centroids
+    constexpr int GPB = kBatch / C;                 // groups (of each half of the head) per batch
+    CosSin cur[kBatch];
+    {
+        tile_cs_t* first = tile_cs + (size_t)(my_tiles > 0 ? tile0 + wave : tile0) * kPairs;
+#pragma unroll
+        for (int e = 0; e < kBatch; ++e) { cur[e].c = first[e].c; cur[e].s = first[e].s; }
+    }
+    stk.run(kwalk, my_tiles, lane, [&](const Tile<GH, B>& w_in, int k) {
         const int lt = wave + k * NW;
         Tile<GH, B> w = w_in;
         if (meets_new && tile0 + lt == tile_new) new_codes.patch(w, u_new, lane);
-        // the query rotated to the tile's base position: lane i holds pair i
-        const float2 cs = cs_next;
-        cs_next = tile_cs(k + 1);
-        const float qa0 = __builtin_fmaf(qa, cs.x, qb * cs.y), qb0 = __builtin_fmaf(qb, cs.x, -(qa * cs.y));
+        tile_cs_t* cs = tile_cs + (size_t)(tile0 + lt) * kPairs;
         // codes in group order: byte g of d[] is the code of group g
         unsigned d[GH / 4];
         group_order<GH, B>(w, unrot, d);
         // b = 10: the high bits of group g sit at bits [2 g + 1 : 2 g] once the word is rotated like the bytes
         const unsigned hi_rot = B == 10 ? __builtin_amdgcn_alignbit(w.hi, w.hi, 2u * (((unsigned)(GH - lane)) & (unsigned)(GH - 1))) : 0u;
-        // the table base is re-materialised per tile: were it a loop invariant, the compiler
-        // would keep base + offset of every channel pair in a register of its own (64 of them)
-        // instead of using the offset field of the LDS instructions
-        unsigned trg_base = trg_lane;
-        asm volatile("" : "+v"(trg_base));
-        float acc0 = 0.f, acc1 = 0.f;
+        float acc[8];
 #pragma unroll
-        for (int g = 0; g < HALF; ++g) {
-            unsigned c_first = (d[g >> 2] >> (8 * (g & 3))) & 0xffu;                       // channels < 64
-            unsigned c_second = (d[(g + HALF) >> 2] >> (8 * ((g + HALF) & 3))) & 0xffu;    // their partners
-            CenVec<C> ka, kb;
-            if constexpr (B == 8) {
-                ka = lds_centroid<C>(c_first * (C * 2) + (unsigned)(g * K * C * 2));
-                kb = lds_centroid<C>(c_second * (C * 2) + (unsigned)((g + HALF) * K * C * 2));
-            } else {
-                c_first |= ((hi_rot >> (2 * g)) & 3u) << 8;
-                c_second |= ((hi_rot >> (2 * (g + HALF))) & 3u) << 8;
-                ka = global_centroid<C>(k_head + ((size_t)g * K + c_first) * C);
-                kb = global_centroid<C>(k_head + ((size_t)(g + HALF) * K + c_second) * C);
+        for (int e = 0; e < 8; ++e) acc[e] = 0.f;
+        // centroids of a batch: both halves' groups bi GPB .. of the head
+        auto centroids = [&](int bi, CenVec<C> (&ka)[GPB], CenVec<C> (&kb)[GPB], float after) {
+#pragma unroll
+            for (int gg = 0; gg < GPB; ++gg) {
+                const int g = bi * GPB + gg;
+                unsigned c_first = (d[g >> 2] >> (8 * (g & 3))) & 0xffu;                       // channels < 64
+                unsigned c_second = (d[(g + HALF) >> 2] >> (8 * ((g + HALF) & 3))) & 0xffu;    // their partners
+                if constexpr (B == 10) {
+                    c_first |= ((hi_rot >> (2 * g)) & 3u) << 8;
+                    c_second |= ((hi_rot >> (2 * (g + HALF))) & 3u) << 8;
+                }
+                asm volatile("" : "+v"(c_first), "+v"(c_second) : "v"(after));
+                if constexpr (B == 8) {
+                    ka[gg] = lds_centroid<C>(c_first * (C * 2) + (unsigned)(g * K * C * 2));
+                    kb[gg] = lds_centroid<C>(c_second * (C * 2) + (unsigned)((g + HALF) * K * C * 2));
+                } else {
+                    ka[gg] = global_centroid<C>(k_head + ((size_t)g * K + c_first) * C);
+                    kb[gg] = global_centroid<C>(k_head + ((size_t)(g + HALF) * K + c_second) * C);
+                }
+            }
+        };
+        CenVec<C> ka[GPB], kb[GPB];
+        centroids(0, ka, kb, 0.f);
+#pragma unroll
+        for (int bi = 0; bi < kPairs / kBatch; ++bi) {
+            CosSin nxt[kBatch];
+            CenVec<C> ka_n[GPB], kb_n[GPB];
+            // pair e of the batch: channel pair (i, i + 64), i = kBatch bi + e, group bi GPB + e / C, channel j = e % C of it;
+            // x, y: the key rotated to the tile's base position
+#pragma unroll
+            for (int h = 0; h < kBatch; h += 8) {
+                float t1[8], t2[8], x[8], y[8];
+#pragma unroll
+                for (int e = h; e < h + 8; ++e) t1[e - h] = mix_mul((e % C) & 1, kb[e / C].w[(e % C) >> 1], cur[e].s);
+                if (h == 0) {
+                    // The next batch's scalars (behind the last batch: the next tile's) and centroids
+                    // are requested here: behind the first use of this batch's (a wait for a scalar load
+                    // is a wait for everything outstanding, so nothing may be in flight at that
+                    // point that is not needed yet), a batch of arithmetic ahead of their own use.
+                    tile_cs_t* nx = bi + 1 < kPairs / kBatch ? cs + (bi + 1) * kBatch
+                                                             : tile_cs + (size_t)(tile0 + (k + 1 < my_tiles ? lt + NW : lt)) * kPairs;
+                    asm volatile("" : "+s"(nx) : "v"(t1[0]));
+#pragma unroll
+                    for (int e = 0; e < kBatch; ++e) { nxt[e].c = nx[e].c; nxt[e].s = nx[e].s; }
+                    if (bi + 1 < kPairs / kBatch) centroids(bi + 1, ka_n, kb_n, t1[0]);
+                }
+#pragma unroll
+                for (int e = h; e < h + 8; ++e) t2[e - h] = mix_mul((e % C) & 1, ka[e / C].w[(e % C) >> 1], cur[e].s);
+#pragma unroll
+                for (int e = h; e < h + 8; ++e) x[e - h] = mix_fma<true>((e % C) & 1, ka[e / C].w[(e % C) >> 1], cur[e].c, t1[e - h]);
+#pragma unroll
+                for (int e = h; e < h + 8; ++e) y[e - h] = mix_fma<false>((e % C) & 1, kb[e / C].w[(e % C) >> 1], cur[e].c, t2[e - h]);
+#pragma unroll
+                for (int e = h; e < h + 8; ++e) acc[e & 7] = __builtin_fmaf(x[e - h], qa[bi * kBatch + e], acc[e & 7]);
+#pragma unroll
+                for (int e = h; e < h + 8; ++e) acc[e & 7] = __builtin_fmaf(y[e - h], qb[bi * kBatch + e], acc[e & 7]);
+                // (left alone, the compiler moves the multiply-adds of all batches behind the last
+                // rotation, with every rotated key of the tile in a register of its own until then:
+                // the sums pass through a statement that keeps its place among the rotations)
+                asm volatile("" : "+v"(acc[0]), "+v"(acc[1]), "+v"(acc[2]), "+v"(acc[3]), "+v"(acc[4]), "+v"(acc[5]), "+v"(acc[6]), "+v"(acc[7]));
             }
 #pragma unroll
-            for (int j = 0; j < C; ++j) {
-                const int i = g * C + j;                                    // channel pair (i, i + 64)
-                // the tile-rotated query of pair i sits in lane i: one scalar each
-                const float2 q0 = make_float2(__uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(qa0), i)),
-                                              __uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(qb0), i)));
-                const float2 tr = lds_load2(trg_base + i * 512);
-                const float av = __builtin_fmaf(tr.x, q0.x, tr.y * q0.y);
-                const float bv = __builtin_fmaf(tr.x, q0.y, -(tr.y * q0.x));
-                const half2_t ha = __builtin_bit_cast(half2_t, ka.w[j >> 1]);
-                const half2_t hb = __builtin_bit_cast(half2_t, kb.w[j >> 1]);
-                const float kav = (float)((j & 1) ? ha.y : ha.x), kbv = (float)((j & 1) ? hb.y : hb.x);
-                acc0 = __builtin_fmaf(kav, av, acc0);
-                acc1 = __builtin_fmaf(kbv, bv, acc1);
+            for (int e = 0; e < kBatch; ++e) cur[e] = nxt[e];
+            if (bi + 1 < kPairs / kBatch) {
+#pragma unroll
+                for (int gg = 0; gg < GPB; ++gg) { ka[gg] = ka_n[gg]; kb[gg] = kb_n[gg]; }
             }
         }
+        const float acc0 = (acc[0] + acc[1]) + (acc[2] + acc[3]), acc1 = (acc[4] + acc[5]) + (acc[6] + acc[7]);
         const int tok = (tile0 + lt) * kTileTokens + lane;
         const float sv = tok < t_n ? acc0 + acc1 : -INFINITY;
         sc[lt * kTileTokens + lane] = sv;
@@ -511,11 +582,11 @@ __global__ __launch_bounds__(NT) void decode_rope_kernel(DecodeArgs a, const flo
 template <int GH, int C, bool STEP, int B = 8>
 cq_status launch_rope_variant(const DecodeArgs& a, const float2* tile_tab, const float2* lane_tab, hipStream_t stream)
 {
-    constexpr int NT = 1024;
+    constexpr int NT = kRopeThreads;
     auto kernel = decode_rope_kernel<GH, C, NT, STEP, B>;
     static LdsKernelSetup setup;
     if (setup.ensure(reinterpret_cast<const void*>(kernel)) != hipSuccess) return CQ_ERR_HIP;
-    const size_t smem = kTabBytes + kTrgBytes + (size_t)a.tiles_per_split * kTileTokens * 4 + (STEP ? kKeyFloats(GH) * 4 : 0);
+    const size_t smem = kTabBytes + kScrBytes + (size_t)a.tiles_per_split * kTileTokens * 4 + (STEP ? kKeyFloats(GH) * 4 : 0);
     if (smem > 160 * 1024) return CQ_ERR_INVALID_ARG;
     const unsigned grid = (unsigned)(a.batch * a.n_q_heads * a.n_split);
     hipLaunchKernelGGL(kernel, dim3(grid), dim3(NT), smem, stream, a, tile_tab, lane_tab);
@@ -524,7 +595,7 @@ cq_status launch_rope_variant(const DecodeArgs& a, const float2* tile_tab, const
 
 }  // namespace
 
-int decode_rope_max_tiles_per_split() { return 128; }
+int decode_rope_max_tiles_per_split() { return 256; }
 
 size_t rope_table_floats(int t_cap) { return ((size_t)(t_cap / kTileTokens) * kPairs + (size_t)kPairs * 64) * 2; }
 

@@ -110,8 +110,9 @@ def test_rope_long_context_and_other_base():
     base = 500000.0
     rope = cq.RopeTable(base, t_cap)
     ref = O.attention(q, kc, vc, ck, cv, 0.1, hkv, rope_base=base)
-    out = _gpu(q, codes_to_cache(kc, fmt, t_cap), codes_to_cache(vc, fmt, t_cap), ck, cv, 0.1, fmt, T, t_cap, rope)
-    check_attention(out, ref)
+    kcache, vcache = codes_to_cache(kc, fmt, t_cap), codes_to_cache(vc, fmt, t_cap)
+    for split in (0, 16384):                # the library's split, and the longest one a workgroup takes
+        check_attention(_gpu(q, kcache, vcache, ck, cv, 0.1, fmt, T, t_cap, rope, split=split), ref)
 
 
 def test_rope_zero_query_gives_the_uniform_weights_of_plain_attention():

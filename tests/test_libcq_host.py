@@ -268,7 +268,7 @@ def test_rope_sizes_and_argument_checks_without_launching():
     assert dec(fmt, table=0) == E and dec(fmt, table=0x80004) == E
     assert dec(fmt, positions=0) == E and dec(fmt, positions=100) == E
     assert dec(fmt, t=128, t_cap=128, positions=64) == E           # table shorter than the context
-    assert dec(fmt, split=64 * 129, t=64 * 200, t_cap=64 * 200, positions=64 * 200) == E   # beyond the score buffer
+    assert dec(fmt, split=64 * 257, t=64 * 300, t_cap=64 * 300, positions=64 * 300) == E   # beyond the score buffer
     assert dec(fmt, ws_bytes=16) == cq.CQ_ERR_WORKSPACE_TOO_SMALL
     assert dec(cq.CQFormat(2, 4, 128, 4)) == cq.CQ_ERR_UNSUPPORTED     # sub-byte: through the fused format
     assert cq.cq_decode_rope_default_split(cq.CQFormat(8, 10, 128, 4), 2, 8, 4096) > 0
@@ -296,7 +296,7 @@ def test_rope_sizes_and_argument_checks_without_launching():
     assert chunk(t=4096, t_cap=4096, split=64, table=0x80004) == cq.CQ_ERR_INVALID_ARG
     assert chunk(t=4096, t_cap=4096, split=64, pos=2048) == cq.CQ_ERR_INVALID_ARG      # table shorter than the context
     assert chunk(t=4096, t_cap=4096, split=64, pos=4100) == cq.CQ_ERR_INVALID_ARG
-    assert cq.cq_decode_rope_default_split(cq.CQFormat(2, 8, 128, 32), 64, 32, 64 * 1000) == 64 * 125    # 8 balanced splits of at most 128 tiles (256 without the rotation)
+    assert cq.cq_decode_rope_default_split(cq.CQFormat(2, 8, 128, 32), 64, 32, 64 * 1000) == 64 * 250    # 4 balanced splits of at most 256 tiles
 
 
 def test_layer_table_argument_checks_without_copying():
