@@ -357,9 +357,17 @@ def extra_measurements(cq, synth, torch):
         "ms": ms_r, "kv_tokens_per_s": B * T / (ms_r * 1e-3),
         "code_read_GBps": code_bytes / (ms_r * 1e-3) / 1e9, "tokens_per_split": split_r,
         "slowdown_vs_position_independent": ms_r / entry["ms"], "buffer_sets": len(sets), "cache_resident": False,
-        "roofline": hbm_roofline("decode_rope_kernel<16, 8, *>", "decode_rope_kernel<16, 8>", code_bytes, ms_r, 3 * len(sets),
+        "roofline": hbm_roofline("decode_rope_kernel<16, 8, 512, false, 8>", "decode_rope_kernel<16, 8, 512, false, 8>", code_bytes, ms_r,
+                                 3 * len(sets),
                                  note="bound by the vector ALU (per-token rotation), not by HBM; the HBM fraction is what the "
-                                      "metric asks for")}
+                                      "metric asks for"),
+        # 6 vector instructions per (token, head, channel pair) is what the rotation and the dot product need
+        # (4 mixed-precision multiply-adds with a scalar cosine / sine, 2 plain ones); the peak is one vector
+        # instruction per SIMD every 4 cycles
+        "roofline_alu": {"bound": "alu", "unit": "T lane-instr/s", "peak": (VALU_PEAK_LANE_OPS / 1e12),
+                         "achieved": B * cfg.n_q_heads * T * 64 * 6 / (ms_r * 1e-3) / 1e12,
+                         "frac": B * cfg.n_q_heads * T * 64 * 6 / (ms_r * 1e-3) / 1e12 / (VALU_PEAK_LANE_OPS / 1e12),
+                         "algorithmic_lane_instructions_per_token_head": 384}}
     del calls_r
     # a prefill chunk over the same caches: the last 512 tokens of each sequence attend causally
     # (cq_chunk_attention on the matrix cores); 4 x 32 x 512 query rows x ~130816 visible tokens each
