@@ -4,9 +4,11 @@
 // For one group (c channels, K = 2^b centroids) and a tile of tokens, argmin_j |x - c_j|^2 =
 // argmax_j (x . c_j - |c_j|^2 / 2).  One MFMA evaluates that score for 32 tokens x 32 centroids:
 // the K dimension of the matrix product carries the c channels plus three fp16 pieces of
-// -|c_j|^2 / 2 (their sum is exact to fp32 precision; see "Scaling").  Each lane then keeps the two largest
-// scores it sees, with the position of a score packed into its four lowest mantissa bits (2.5
-// VALU instructions per score instead of the 2 c + 3 of the direct form).
+// -|c_j|^2 / 2 (their sum is exact to fp32 precision; see "Scaling").  The two largest scores of a
+// token are then found in two levels: each lane keeps the two largest QUAD maxima it sees (the
+// maximum of four scores, with the quad's number packed into its five lowest mantissa bits:
+// 1.2 VALU instructions per score instead of the 2 c + 3 of the direct form), and the four
+// scores of the winning quad are evaluated once more, with packed dot products in fp32.
 //
 // Scaling.  A group whose largest |c_j|^2 is small is multiplied (centroids and tokens alike)
 // by a power of two 2^s, s >= 0, that brings the largest scaled |c'|^2 into [2^12, 2^14): the
@@ -16,13 +18,17 @@
 // are handed to the exact path whole.
 //
 // Error bound.  With M = |x'| |c'|_max + |c'|_max^2 / 2 >= sum of the absolute values of the
-// terms of any score, in units of 2^-20 M: |c|^2 summed in fp32 (0.5); the matrix core aligns the
-// exact products to the largest one and drops what falls below about 2^-24 of it -- at most
-// 2^-23 M for each of at most 11 terms and the final rounding (1.5; measured on such operands:
-// never above 0.2); the four packed bits move a score by less than 16 units in its last place
-// (1.9).  Two scores therefore
-// compare correctly whenever they differ by more than 2 * 3.9 * 2^-20 M < 2^-17 M; the test
-// below uses 1.5 * 2^-17 M.  If the best beats the runner-up by more than that, the best IS the
+// terms of any score, in units of 2^-20 M.  A quad maximum from the matrix core: |c|^2 summed in
+// fp32 (0.5); the matrix core aligns the exact products to the largest one and drops what falls
+// below about 2^-24 of it -- at most 2^-23 M for each of at most 11 terms and the final rounding
+// (1.5; measured on such operands: never above 0.2); the five packed bits move a score by less
+// than 32 units in its last place (3.9): 5.9 in all.  A score of the winning quad from the
+// vector ALU: |c|^2 (0.5), c / 2 + 2 roundings to fp32 (0.4), two packed bits (0.5): 1.4.  The
+// best is always of the second kind, the runner-up of either, so the two compare correctly
+// whenever they differ by more than 7.3 units; the test below uses 8 = 2^-17 M.  (If rounding
+// made the wrong quad win, the true best's quad maximum is the runner-up and lies within 7.3
+// units of the reported best: the test fails and the pair is re-done.)  If the best beats the
+// runner-up by more than that, the best IS the
 // nearest centroid in exact arithmetic.  Otherwise (a near tie or an exact tie) the (token,
 // group) pair is re-done at once by the direct form -- sum_i (x_i - c_i)^2 in fp32, channel
 // order, lowest index on ties; on the scaled values, which changes no bit of the comparison --
@@ -170,6 +176,7 @@ __global__ __launch_bounds__(NW * 64) void encode_mfma_kernel(EncodeArgs a)
     constexpr int NT = NW * 64;
     constexpr int KDIM = A::KDIM, HALF = A::HALF;
     constexpr int NBLK = K / 32;                     // 32-centroid blocks
+    constexpr int NSB = NBLK / 8;                    // runs of 8 blocks (the packed quad number has 5 bits)
     constexpr int P = GH / 16;
     constexpr int TILE_LOW = kTileTokens * GH;
     constexpr int TILE_BYTES = kTileTokens * GH * B / 8;
@@ -299,8 +306,8 @@ __global__ __launch_bounds__(NW * 64) void encode_mfma_kernel(EncodeArgs a)
             fetch(g + 1);
             load_x(g + 1, xnext);
         }
-        // 1.5 * 2^-17 M with M >= |x'| |c'|max + |c'|max^2 / 2 (1 % slack for the roundings of this line)
-        const float thr = (1.01f * (__builtin_sqrtf(x2 * gs.c2max_scaled) + 0.5f * gs.c2max_scaled)) * (1.5f / 131072.0f);
+        // 2^-17 M with M >= |x'| |c'|max + |c'|max^2 / 2 (1 % slack for the roundings of this line)
+        const float thr = (1.01f * (__builtin_sqrtf(x2 * gs.c2max_scaled) + 0.5f * gs.c2max_scaled)) * (1.0f / 131072.0f);
         const bool exact_only = gs.too_big || x_over;
 
 #pragma unroll
@@ -339,44 +346,96 @@ __global__ __launch_bounds__(NW * 64) void encode_mfma_kernel(EncodeArgs a)
                 }
             }
 
+            // The two largest of the lane's 16 NBLK scores, found in two levels.  Level 1: the
+            // maximum of every quad of scores (the 4 consecutive centroids 8 q + 4 (lane / 32) .. + 3
+            // of a block: registers 4 q .. 4 q + 3) with the quad's number, 4 (blk % 8) + q, packed
+            // into its five lowest mantissa bits, and a running (best, runner-up) over those:
+            // 1.2 VALU instructions per score instead of the 2.8 of tracking every score.  Level
+            // 2, below: the four scores of the winning quad again, in fp32 on the vector ALU.
             float gbest = LOWEST, gsecond = LOWEST;
-            int gblk = 0;
-#pragma unroll 2
-            for (int blk = 0; blk < NBLK; ++blk) {
-                const vec_t aop = *reinterpret_cast<const vec_t*>(&cba[buf][(blk * 32 + (lane & 31)) * KDIM + (lane >> 5) * HALF]);
-                const float16_t d = mfma<C>(aop, bop);
-                float bbest = LOWEST, bsecond = LOWEST;
-                // two scores per step: the runner-up of {best, second, k1, k2} with second <= best
-                // is max(median(best, k1, k2), second)
+            int gsb = 0;                                 // block / 8 of gbest (more than 8 blocks: b = 10)
+#pragma unroll 1
+            for (int sb = 0; sb < NSB; ++sb) {
+                float sbest = LOWEST, ssecond = LOWEST;
+#pragma unroll                  // (whole: the quad numbers are then immediates of one v_and_or_b32)
+                for (int b8 = 0; b8 < 8; ++b8) {
+                    const int blk = sb * 8 + b8;
+                    const vec_t aop = *reinterpret_cast<const vec_t*>(&cba[buf][(blk * 32 + (lane & 31)) * KDIM + (lane >> 5) * HALF]);
+                    const float16_t d = mfma<C>(aop, bop);
+                    float qm[4];
 #pragma unroll
-                for (int i = 0; i < 16; i += 2) {
-                    const float k1 = __uint_as_float((__float_as_uint(d[i]) & 0xfffffff0u) | (unsigned)i);
-                    const float k2 = __uint_as_float((__float_as_uint(d[i + 1]) & 0xfffffff0u) | (unsigned)(i + 1));
-                    bsecond = fmaxf(bsecond, __builtin_amdgcn_fmed3f(bbest, k1, k2));
-                    bbest = fmaxf(fmaxf(bbest, k1), k2);
+                    for (int q = 0; q < 4; ++q) {
+                        const float m = fmaxf(fmaxf(fmaxf(d[4 * q], d[4 * q + 1]), d[4 * q + 2]), d[4 * q + 3]);
+                        qm[q] = __uint_as_float((__float_as_uint(m) & 0xffffffe0u) | (unsigned)(4 * b8 + q));
+                    }
+                    // two quads per step: the runner-up of {best, second, k1, k2} with second <= best
+                    // is max(median(best, k1, k2), second)
+#pragma unroll
+                    for (int q = 0; q < 4; q += 2) {
+                        ssecond = fmaxf(ssecond, __builtin_amdgcn_fmed3f(sbest, qm[q], qm[q + 1]));
+                        sbest = fmaxf(fmaxf(sbest, qm[q]), qm[q + 1]);
+                    }
                 }
-                gsecond = fmaxf(fmaxf(fminf(gbest, bbest), gsecond), bsecond);
-                gblk = bbest > gbest ? blk : gblk;
-                gbest = fmaxf(gbest, bbest);
+                if constexpr (NSB == 1) {
+                    gbest = sbest;
+                    gsecond = ssecond;
+                } else {
+                    gsecond = fmaxf(fmaxf(fminf(gbest, sbest), gsecond), ssecond);
+                    gsb = sbest > gbest ? sb : gsb;
+                    gbest = fmaxf(gbest, sbest);
+                }
             }
             // lanes l and l + 32 saw the two halves of every block's rows for token l % 32
             const float obest = __shfl_xor(gbest, 32), osecond = __shfl_xor(gsecond, 32);
-            const int oblk = __shfl_xor(gblk, 32);
+            const int osb = NSB == 1 ? 0 : __shfl_xor(gsb, 32);
             const bool other = obest > gbest;
             const float best = fmaxf(gbest, obest);
             const float second = fmaxf(fmaxf(fminf(gbest, obest), gsecond), osecond);
-            const int wblk = other ? oblk : gblk;
+            const int wsb = other ? osb : gsb;
             const int whalf = other ? 1 - (lane >> 5) : (lane >> 5);
             const int u = 32 * h + (lane & 31);                      // token of the tile
             const int slot = (g - u) & (GH - 1);
+            // level 2: the winning quad's four centroids against this token, x . c - |c|^2 / 2 in fp32
+            // from the records in LDS (every lane has its token's channels; lanes < 32 keep the result)
+            const int quad = (int)(__float_as_uint(best) & 31u);
+            const int j0 = (wsb * 8 + (quad >> 2)) * 32 + 8 * (quad & 3) + 4 * whalf;
+            // (v_dot2_f32_f16: exact products of the fp16 pairs, fp32 sums; the centroid's number
+            // within the quad rides in the two lowest mantissa bits)
+            float qk[4];
+            const half2_t ones = half2_t{(_Float16)1.0f, (_Float16)1.0f};
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const unsigned* r = reinterpret_cast<const unsigned*>(&cba[buf][(j0 + e) * KDIM]);
+                unsigned w[C / 2 + 2];
+                if constexpr (C == 8) {
+                    const uint4 a0 = *reinterpret_cast<const uint4*>(r);
+                    const uint2 a1 = *reinterpret_cast<const uint2*>(r + 4);
+                    w[0] = a0.x; w[1] = a0.y; w[2] = a0.z; w[3] = a0.w; w[4] = a1.x; w[5] = a1.y;
+                } else if constexpr (C == 4) {
+                    const uint4 a0 = *reinterpret_cast<const uint4*>(r);
+                    w[0] = a0.x; w[1] = a0.y; w[2] = a0.z; w[3] = a0.w;
+                } else {
+                    const uint4 a0 = *reinterpret_cast<const uint4*>(r);
+                    w[0] = a0.x; w[1] = a0.y; w[2] = a0.z;
+                }
+                // the three pieces of -|c|^2 / 2 sit behind the C channels: (h1, h2), (h3, 0)
+                float sc = __builtin_amdgcn_fdot2(__builtin_bit_cast(half2_t, w[C / 2 + 1]), ones, 0.f, false);
+                sc = __builtin_amdgcn_fdot2(__builtin_bit_cast(half2_t, w[C / 2]), ones, sc, false);
+#pragma unroll
+                for (int i = 0; i < C / 2; ++i)
+                    sc = __builtin_amdgcn_fdot2(__builtin_bit_cast(half2_t, xh[i]), __builtin_bit_cast(half2_t, w[i]), sc, false);
+                qk[e] = __uint_as_float((__float_as_uint(sc) & 0xfffffffcu) | (unsigned)e);
+            }
+            const float q01 = fmaxf(qk[0], qk[1]);
+            const float qbest_k = fmaxf(fmaxf(q01, qk[2]), qk[3]);
+            const float qsecond = fmaxf(fminf(qk[0], qk[1]), __builtin_amdgcn_fmed3f(q01, qk[2], qk[3]));
+            const int qarg = (int)(__float_as_uint(qbest_k) & 3u);
+            const float qbest = __uint_as_float(__float_as_uint(qbest_k) & 0xfffffffcu);
             bool unsure = false;
             if (lane < 32) {
-                const unsigned bits = __float_as_uint(best);
-                const int i = (int)(bits & 15u);
-                const int code = wblk * 32 + 8 * (i >> 2) + 4 * whalf + (i & 3);
-                const float bv = __uint_as_float(bits & 0xfffffff0u);
-                const float sv = __uint_as_float(__float_as_uint(second) & 0xfffffff0u);
-                unsure = !(bv - sv > thr_h) || exact_h != 0;
+                const int code = j0 + qarg;
+                const float sv = fmaxf(__uint_as_float(__float_as_uint(second) & 0xffffffe0u), qsecond);
+                unsure = !(qbest - sv > thr_h) || exact_h != 0;
                 rec[wave][(slot >> 4) * 1024 + u * 16 + (slot & 15)] = (uint8_t)(code & 0xff);
                 if constexpr (B == 10) code16[wave][u][g] = (uint16_t)code;
             }
@@ -404,7 +463,11 @@ __global__ __launch_bounds__(NW * 64) void encode_mfma_kernel(EncodeArgs a)
                     dmin = dj < dmin ? dj : dmin;
                 }
                 const unsigned wmin = wave_min_u32(dmin);
-                const unsigned code = wave_min_u32(dmin == wmin ? jmin : ~0u);
+                // the lowest index among the lanes that hold the minimum: almost always one lane
+                const unsigned long long holders = __ballot(dmin == wmin);
+                unsigned code;
+                if ((holders & (holders - 1)) == 0) code = (unsigned)__builtin_amdgcn_readlane((int)jmin, (int)__builtin_ctzll(holders));
+                else code = wave_min_u32(dmin == wmin ? jmin : ~0u);
                 if (lane == r) {
                     rec[wave][(slot >> 4) * 1024 + u * 16 + (slot & 15)] = (uint8_t)(code & 0xff);
                     if constexpr (B == 10) code16[wave][u][g] = (uint16_t)code;
