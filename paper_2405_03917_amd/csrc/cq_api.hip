@@ -128,6 +128,11 @@ int default_tiles_per_split(const Derived& f, int batch, int n_q_heads, int t)
 
 int rope_default_tiles_per_split(const Derived& f, int batch, int n_q_heads, int t)
 {
+    // grouped queries with byte codes: the kernel that shares the key rotation among four query
+    // heads, one workgroup per (sequence, KV head, four query heads, split), shorter splits
+    const int qper = n_q_heads / f.n_kv_heads;
+    if (f.b == 8 && qper >= 2)
+        return default_tiles_per_split(f, batch, f.n_kv_heads * ((qper + 3) / 4), t, decode_rope_shared_max_tiles_per_split(), true);
     return default_tiles_per_split(f, batch, n_q_heads, t, decode_rope_max_tiles_per_split(), true);
 }
 
@@ -480,7 +485,8 @@ cq_status decode_common(const void* q, const void* x_k_new, const void* x_v_new,
     }
     const int max_tiles = rope ? decode_rope_max_tiles_per_split() : decode_max_tiles_per_split(f);
     const int tiles = tokens_per_split ? tokens_per_split / kTileTokens
-                                       : default_tiles_per_split(f, batch, n_q_heads, t, max_tiles, rope);
+                                       : (rope ? rope_default_tiles_per_split(f, batch, n_q_heads, t)
+                                               : default_tiles_per_split(f, batch, n_q_heads, t, max_tiles));
     if (tiles > max_tiles) return CQ_ERR_INVALID_ARG;
     const int n_tiles = (t + kTileTokens - 1) / kTileTokens;
     const int n_split = (n_tiles + tiles - 1) / tiles;

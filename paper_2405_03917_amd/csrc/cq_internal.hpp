@@ -210,6 +210,7 @@ cq_status launch_decode_merge(const float* partials, uint16_t* out, int rows, in
 size_t rope_table_floats(int positions);
 cq_status launch_rope_table(double base, int positions, float* table, hipStream_t stream);
 int decode_rope_max_tiles_per_split();
+int decode_rope_shared_max_tiles_per_split();
 cq_status launch_decode_rope(const DecodeArgs& a, const float* table, int positions, hipStream_t stream);
 
 // Kernels that address their dynamic LDS block from LDS address 0 and use more than 64 KB of it:

@@ -102,6 +102,25 @@ def test_rope_grouped_queries_and_eight_kv_heads():
     check_attention(out, ref)
 
 
+@pytest.mark.parametrize("c,b", ROPE_FORMATS)
+@pytest.mark.parametrize("hq,hkv", [(4, 2), (6, 2), (16, 2), (32, 8), (10, 1)])
+def test_rope_grouped_queries_share_the_key_rotation(c, b, hq, hkv):
+    # two or more query heads per KV head with byte codes: the kernel that rotates every key once
+    # for (up to) four query heads.  2, 3, 8, 4 and 10 query heads per KV head (a partly filled
+    # last group of four included), ragged lengths, one and several splits; at the split limit of
+    # that kernel and one tile beyond it (where the per-head kernel takes over).
+    B, T, t_cap = 2, 6100, 6144
+    fmt, q, kc, vc, ck, cv = _case(11 + hq, c, b, hq, hkv, B, T)
+    scale = 0.1
+    lens = np.array([T, 2300], dtype=np.int32)
+    rope = cq.RopeTable(BASE, t_cap)
+    ref = O.attention(q, kc, vc, ck, cv, scale, hkv, seq_lens=lens, rope_base=BASE)
+    kcache, vcache = codes_to_cache(kc, fmt, t_cap), codes_to_cache(vc, fmt, t_cap)
+    for split in (0, 64 * 88, 64 * 89, 64 * 7):
+        check_attention(_gpu(q, kcache, vcache, ck, cv, scale, fmt, T, t_cap, rope, seq_lens=lens, split=split), ref)
+    assert cq.cq_decode_rope_default_split(fmt, B, hq, T) <= 64 * 88
+
+
 def test_rope_long_context_and_other_base():
     # positions up to 40000: angles of tens of thousands of radians for the fast pairs
     c, b, hq, hkv, B, T = 8, 8, 2, 1, 1, 40000
