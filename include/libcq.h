@@ -400,7 +400,10 @@ CQ_API cq_status cq_chunk_attention_paged(const void *q, const void *k_pool, con
  *   q              rotated to its own position, otherwise as before
  *   rope_table     device, as written by cq_rope_table(base, 128, rope_positions, ...)
  *   rope_positions must be >= t
- *   tokens_per_split  0 = cq_decode_rope_default_split(...); at most 16384
+ *   tokens_per_split  0 = cq_decode_rope_default_split(...); at most 16384.  With two or more query
+ *                     heads per KV head and byte codes, splits of at most 5632 tokens (the default
+ *                     then) run the kernel that rotates each key once for four query heads;
+ *                     longer ones the kernel that serves one query head per workgroup
  * cq_decode_step_rope[_paged]: the fused decode step (cq_decode_step[_paged]) for such caches:
  * the new key row is passed BEFORE the rotation (it is quantized as it is; position t - 1, or
  * seq_lens[n] - 1, rotates it like every cached key), the new value row as always; same
