@@ -621,15 +621,18 @@ __device__ __forceinline__ float mixv_mul(bool HI, unsigned w, float s)
 }
 // (Its result feeds a matrix instruction.  The compiler does not look inside an asm statement, so
 // it cannot know that a vector instruction wrote the register and leaves out the two wait states
-// that a matrix instruction reading it needs: they are part of the statement.)
+// that a matrix instruction reading it needs.  The caller keeps the two apart instead: all
+// sixteen results of a batch pass through one more (empty) statement before the first matrix
+// instruction may read any of them, so that at least eight instructions lie between a result
+// and its use.)
 template <bool MINUS>
 __device__ __forceinline__ float mixv_fma(bool HI, unsigned w, float s, float c)
 {
     float d;
-    if (HI && MINUS) asm volatile("v_fma_mix_f32 %0, %1, %2, -%3 op_sel:[1,0,0] op_sel_hi:[1,0,0]\n\ts_nop 1" : "=v"(d) : "v"(w), "v"(s), "v"(c));
-    else if (HI) asm volatile("v_fma_mix_f32 %0, %1, %2, %3 op_sel:[1,0,0] op_sel_hi:[1,0,0]\n\ts_nop 1" : "=v"(d) : "v"(w), "v"(s), "v"(c));
-    else if (MINUS) asm volatile("v_fma_mix_f32 %0, %1, %2, -%3 op_sel:[0,0,0] op_sel_hi:[1,0,0]\n\ts_nop 1" : "=v"(d) : "v"(w), "v"(s), "v"(c));
-    else asm volatile("v_fma_mix_f32 %0, %1, %2, %3 op_sel:[0,0,0] op_sel_hi:[1,0,0]\n\ts_nop 1" : "=v"(d) : "v"(w), "v"(s), "v"(c));
+    if (HI && MINUS) asm volatile("v_fma_mix_f32 %0, %1, %2, -%3 op_sel:[1,0,0] op_sel_hi:[1,0,0]" : "=v"(d) : "v"(w), "v"(s), "v"(c));
+    else if (HI) asm volatile("v_fma_mix_f32 %0, %1, %2, %3 op_sel:[1,0,0] op_sel_hi:[1,0,0]" : "=v"(d) : "v"(w), "v"(s), "v"(c));
+    else if (MINUS) asm volatile("v_fma_mix_f32 %0, %1, %2, -%3 op_sel:[0,0,0] op_sel_hi:[1,0,0]" : "=v"(d) : "v"(w), "v"(s), "v"(c));
+    else asm volatile("v_fma_mix_f32 %0, %1, %2, %3 op_sel:[0,0,0] op_sel_hi:[1,0,0]" : "=v"(d) : "v"(w), "v"(s), "v"(c));
     return d;
 }
 
@@ -825,7 +828,8 @@ __global__ __launch_bounds__(NT) void decode_rope_gqa_kernel(DecodeArgs a, const
         tile_cs(k + 1, cs_next);
         unsigned d[GH / 4];
         group_order<GH, B>(w, unrot, d);
-        f4 acc0 = {0.f, 0.f, 0.f, 0.f}, acc1 = {0.f, 0.f, 0.f, 0.f};
+        // four accumulators: a matrix instruction that adds to the result of the one before it has to wait for it
+        f4 acc0 = {0.f, 0.f, 0.f, 0.f}, acc1 = {0.f, 0.f, 0.f, 0.f}, acc2 = {0.f, 0.f, 0.f, 0.f}, acc3 = {0.f, 0.f, 0.f, 0.f};
         auto centroids = [&](int bi, CenVec<C> (&ka)[GPB], CenVec<C> (&kb)[GPB], float after) {
 #pragma unroll
             for (int gg = 0; gg < GPB; ++gg) {
@@ -853,13 +857,21 @@ __global__ __launch_bounds__(NT) void decode_rope_gqa_kernel(DecodeArgs a, const
             for (int e = 0; e < kBatch; ++e) x[e] = mixv_fma<true>((e % C) & 1, ka[e / C].w[(e % C) >> 1], cu[bi * kBatch + e], t1[e]);
 #pragma unroll
             for (int e = 0; e < kBatch; ++e) y[e] = mixv_fma<false>((e % C) & 1, kb[e / C].w[(e % C) >> 1], cu[bi * kBatch + e], t2[e]);
+            static_assert(kBatch == 8, "operands of the statement below");
+            asm volatile("" : "+v"(x[0]), "+v"(x[1]), "+v"(x[2]), "+v"(x[3]), "+v"(x[4]), "+v"(x[5]), "+v"(x[6]), "+v"(x[7]),
+                              "+v"(y[0]), "+v"(y[1]), "+v"(y[2]), "+v"(y[3]), "+v"(y[4]), "+v"(y[5]), "+v"(y[6]), "+v"(y[7]));
 #pragma unroll
             for (int e = 0; e < kBatch; ++e) {
                 const int i = bi * kBatch + e;              // pair i: register i / 16 of the block of lanes i % 16
-                acc0 = mfma_pair(qa, x[e], acc0, i);
-                acc1 = mfma_pair(qb, y[e], acc1, i);
+                if (e & 1) {
+                    acc2 = mfma_pair(qa, x[e], acc2, i);
+                    acc3 = mfma_pair(qb, y[e], acc3, i);
+                } else {
+                    acc0 = mfma_pair(qa, x[e], acc0, i);
+                    acc1 = mfma_pair(qb, y[e], acc1, i);
+                }
             }
-            asm volatile("" : "+v"(acc0), "+v"(acc1));
+            asm volatile("" : "+v"(acc0), "+v"(acc1), "+v"(acc2), "+v"(acc3));
             if (bi + 1 < kPairs / kBatch) {
 #pragma unroll
                 for (int gg = 0; gg < GPB; ++gg) { ka[gg] = ka_n[gg]; kb[gg] = kb_n[gg]; }
@@ -868,7 +880,7 @@ __global__ __launch_bounds__(NT) void decode_rope_gqa_kernel(DecodeArgs a, const
         const int tok = (tile0 + lt) * kTileTokens + lane;
         const bool live = tok < t_n;
 #pragma unroll
-        for (int h = 0; h < QH; ++h) sc[h * split_tokens + lt * kTileTokens + lane] = live ? acc0[h] + acc1[h] : -INFINITY;
+        for (int h = 0; h < QH; ++h) sc[h * split_tokens + lt * kTileTokens + lane] = live ? (acc0[h] + acc1[h]) + (acc2[h] + acc3[h]) : -INFINITY;
     }, [] {});
     lds_barrier();                                  // all centroid reads done, all scores written
 
