@@ -431,7 +431,7 @@ def extra_measurements(cq, synth, torch):
     gen = torch.Generator(device="cuda")
     gen.manual_seed(5)
     qg = torch.randn((Bg, Hq_g, 128), device="cuda", generator=gen).half()
-    shared_calls, per_head_calls, plain_calls = [], [], []
+    shared_calls, per_head_calls = [], []
     split_g = cq.cq_decode_rope_default_split(fmt_g, Bg, Hq_g, Tg)
     keep = []
     for _ in range(3):
@@ -443,19 +443,17 @@ def extra_measurements(cq, synth, torch):
         keep.append((kc_, vc_, ck_, cv_))
         shared_calls.append(cq.prepare_decode_attention_rope(qg, kc_, vc_, ck_, cv_, 0.088, fmt_g, Tg, Tg, rope_g, tokens_per_split=split_g)[0])
         per_head_calls.append(cq.prepare_decode_attention_rope(qg, kc_, vc_, ck_, cv_, 0.088, fmt_g, Tg, Tg, rope_g, tokens_per_split=Tg)[0])
-        plain_calls.append(cq.prepare_decode_attention(qg, kc_, vc_, ck_, cv_, 0.088, fmt_g, Tg, Tg)[0])
-    ms_sh, ms_ph, ms_pl = (time_rotating(torch, c, 3) for c in (shared_calls, per_head_calls, plain_calls))
+    ms_sh, ms_ph = (time_rotating(torch, c, 3) for c in (shared_calls, per_head_calls))
     out["decode_gqa_pre_rope_keys_cq8c8b_batch32_ctx16384"] = {
         "workload": "CQ-8c8b, 32 query / 8 KV heads, batch 32, context 16384, keys cached before RoPE (cq_decode_attention_rope): "
                     "one workgroup rotates every key once for the four query heads of its KV head",
         "ms": ms_sh, "tokens_per_split": split_g, "kv_tokens_per_s": Bg * Tg / (ms_sh * 1e-3),
         "ms_one_query_head_per_workgroup": ms_ph, "speedup_from_sharing": ms_ph / ms_sh,
-        "ms_position_independent": ms_pl, "slowdown_vs_position_independent": ms_sh / ms_pl,
         "buffer_sets": 3, "cache_resident": False,
         "roofline": hbm_roofline("decode_rope_gqa_kernel<16, 8, 512, false>", "decode_rope_gqa_kernel<16, 8, 512, false>", code_bytes_g, ms_sh, 9,
                                  note="bound by vector and matrix instruction issue (per channel pair 4 vector + 2 matrix "
                                       "instructions for four heads), not by HBM")}
-    del keep, shared_calls, per_head_calls, plain_calls, qg
+    del keep, shared_calls, per_head_calls, qg
     torch.cuda.empty_cache()
 
     # ---- centroid learning on a calibration tensor of the paper's size (16 sequences x 2048 tokens):
