@@ -145,3 +145,47 @@ def test_config4_cq8c10b_gqa_batch32_ctx16384():
 
 def test_config5_cq8c8b_batch4_ctx131072():
     _fill_and_check(5, n_attn_samples=40, n_token_samples=64, chunk_tokens=32768)
+
+
+def test_grouped_queries_over_pre_rope_keys_cq8c8b_batch32_ctx16384():
+    # the grouped-query entry of bench.py: CQ-8c8b, 32 query / 8 KV heads, batch 32, context 16384, keys
+    # cached before RoPE, the library's split (the kernel that rotates each key once for the four
+    # query heads of a KV head).  Uniform random codes in the caches (as the bench entry has), 64
+    # sampled (sequence, query head) rows -- every query head, first and last row -- recomputed
+    # whole by the fp64 oracle; the same rows through the kernel that serves one query head per
+    # workgroup (a split beyond the shared kernel's limit); and the fused step on top of it.
+    fmt = cq.CQFormat(8, 8, 128, 8)
+    B, T, hq, rep = 32, 16384, 32, 4
+    rng = np.random.default_rng(77)
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(77)
+    nb = cq.cq_cache_bytes(fmt, B, T)
+    kcache = torch.randint(0, 256, (nb,), dtype=torch.uint8, device="cuda", generator=gen)
+    vcache = torch.randint(0, 256, (nb,), dtype=torch.uint8, device="cuda", generator=gen)
+    rk, rv = synth.tensor_recipe(4, 0, "k", fmt.channels), synth.tensor_recipe(4, 0, "v", fmt.channels)
+    ck_h, cv_h = synth.sample_codebook(rk, 8, 8), synth.sample_codebook(rv, 8, 8)
+    ck, cv = dev(ck_h), dev(cv_h)
+    q_h = rng.standard_normal((B, hq, 128)).astype(np.float16)
+    scale = 1.0 / math.sqrt(128)
+    rope = cq.RopeTable(10000.0, T)
+    split = cq.cq_decode_rope_default_split(fmt, B, hq, T)
+    assert split <= 64 * 88
+    picks = _sample_rows(rng, B, hq, 64)
+    ref, _, _ = _oracle_rows(picks, q_h, kcache, vcache, ck_h, cv_h, fmt, B, T, scale, rep, rope_base=10000.0)
+    out = cq.cq_decode_attention_rope(dev(q_h), kcache, vcache, ck, cv, scale, fmt, T, T, rope).cpu().numpy()
+    check_attention(np.stack([out[n, h] for n, h in picks]), ref)
+    out1 = cq.cq_decode_attention_rope(dev(q_h), kcache, vcache, ck, cv, scale, fmt, T, T, rope, tokens_per_split=T).cpu().numpy()
+    check_attention(np.stack([out1[n, h] for n, h in picks]), ref)
+    # the fused step: new rows at position T - 1, equal to encode + attention bit for bit, caches included
+    xk1 = synth.sample_activations_torch(rk, B, 9001, "cuda").view(B, fmt.channels)
+    xv1 = synth.sample_activations_torch(rv, B, 9002, "cuda").view(B, fmt.channels)
+    k1, v1 = kcache.clone(), vcache.clone()
+    cq.cq_encode_kv(xk1[:, None, :], xv1[:, None, :], ck, cv, fmt, k1, v1, T - 1, T)
+    want = cq.cq_decode_attention_rope(dev(q_h), k1, v1, ck, cv, scale, fmt, T, T, rope)
+    got = cq.cq_decode_step_rope(dev(q_h), xk1, xv1, kcache, vcache, ck, cv, scale, fmt, T, T, rope)
+    torch.cuda.synchronize()
+    assert torch.equal(kcache, k1) and torch.equal(vcache, v1)
+    assert torch.equal(got.view(torch.int16), want.view(torch.int16))
+    ref2, _, _ = _oracle_rows(picks[:16], q_h, kcache, vcache, ck_h, cv_h, fmt, B, T, scale, rep, rope_base=10000.0)
+    got_h = got.cpu().numpy()
+    check_attention(np.stack([got_h[n, h] for n, h in picks[:16]]), ref2)
