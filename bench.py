@@ -595,7 +595,8 @@ def main():
                                 v_codes=st.vcache, k_centroids=st.ck, v_centroids=st.cv, out=st.out) for st in layers],
                           fmt, t_cap)
     step_all = cq.prepare_decode_step_layers(table, scale, cfg.context)
-    step_all()
+    for _ in range(max(1, args.warmup)):
+        step_all()
     dt_layers, _ = timed(step_all)
     ms_per_step = dt / args.steps * 1e3
     kv_tokens = cfg.batch * cfg.context * n_layers
