@@ -97,13 +97,16 @@ int default_tiles_per_split(const Derived& f, int batch, int n_q_heads, int t, i
 {
     // A workgroup costs its tiles plus a fixed part (table build, bins x centroids: each reads a
     // whole head's codebook), here expressed in tiles of streaming time; the chip runs `slots`
-    // workgroups at a time (two per CU), in rounds.  Take the number of splits that minimises
+    // workgroups at a time, in rounds.  Take the number of splits that minimises
     // rounds x (tiles + fixed) over the splits the kernel allows, down to 16 tiles per split.
     const int n_tiles = (t + kTileTokens - 1) / kTileTokens;
     const long bh = (long)batch * n_q_heads;
-    // (keys cached before RoPE: one workgroup per CU, and a tile costs several times the arithmetic,
-    // so the fixed part is worth fewer of them)
-    const long slots = rope ? 256 : 512;
+    // Two workgroups per CU stream a few per cent faster than one, and pay the fixed part twice,
+    // one after the other: with byte codes that is worth it from about 768 tiles per CU on
+    // (measured: below, one workgroup per CU is 2 to 4 us faster at every size).  Keys cached
+    // before RoPE run one workgroup per CU, and a tile costs several times the arithmetic, so the
+    // fixed part is worth fewer of them.
+    const long slots = rope ? 256 : (f.b == 8 && bh * n_tiles < 768L * 256 ? 256 : 512);
     const long fixed = rope ? (f.b == 10 ? 32 : 8) : (f.b == 10 ? 180 : (f.gh == 16 ? 60 : (f.gh == 32 ? 30 : 15)));
     const long ns_min = (n_tiles + max_tiles - 1) / max_tiles;
     const long ns_max = std::max<long>(ns_min, n_tiles / 16);

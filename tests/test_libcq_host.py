@@ -407,4 +407,6 @@ def test_default_split_is_balanced_within_the_on_chip_limits_and_fills_the_chip(
     assert cq.cq_decode_default_split(cq.CQFormat(4, 8, 128, 32), 16, 32, 4096) == 4096        # one split, no merge
     assert cq.cq_decode_default_split(cq.CQFormat(8, 8, 128, 32), 4, 32, 131072) == 32768      # 4 x 512 tiles: all 512 workgroups at once
     assert cq.cq_decode_default_split(cq.CQFormat(8, 10, 128, 8), 32, 32, 16384) == 16384
-    assert cq.cq_decode_default_split(cq.CQFormat(8, 8, 128, 32), 1, 32, 131072) == 8192       # 16 splits fill the chip once
+    assert cq.cq_decode_default_split(cq.CQFormat(8, 8, 128, 32), 1, 32, 131072) == 16384      # shorter job: one workgroup per CU
+    assert cq.cq_decode_default_split(cq.CQFormat(8, 8, 128, 32), 8, 32, 16384) == 16384       # 256 rows: no split at all
+    assert cq.cq_decode_default_split(cq.CQFormat(4, 8, 128, 32), 1, 32, 32768) == 4096
