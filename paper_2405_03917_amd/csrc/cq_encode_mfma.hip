@@ -135,6 +135,22 @@ __device__ __forceinline__ float norm2(const unsigned (&w)[N])
     }
     return s;
 }
+// The same for SCALED values (of a group's centroids, of a token's slice), whose norm lies far
+// above fp16's subnormals: exact products summed in fp32 pair by pair (v_dot2_f32_f16, one
+// instruction per pair instead of two conversions and two multiply-adds).  Whatever that
+// instruction does with a subnormal component, its square is below 4e-9 against a unit of the
+// error bound of 2e-3 or more.
+template <int N>
+__device__ __forceinline__ float norm2_scaled(const unsigned (&w)[N])
+{
+    float s = 0.f;
+#pragma unroll
+    for (int i = 0; i < N; ++i) {
+        const half2_t h = __builtin_bit_cast(half2_t, w[i]);
+        s = __builtin_amdgcn_fdot2(h, h, s, false);
+    }
+    return s;
+}
 
 // The group's power-of-two scale from its largest |c|^2 (bits of a non-negative float):
 // s >= 0 with 4^s c2max in [2^12, 2^14) when c2max < 2^12, else s = 0; at most 30 (fp16 data
@@ -145,21 +161,21 @@ struct GroupScale {
     float c2max_scaled;     // c2max * 4^s
     bool too_big;           // |c|^2 / 2 would not fit fp16: the filter steps aside
 };
+// (c2bits is wavefront-uniform: everything here but one multiplication is scalar integer work)
 __device__ __forceinline__ GroupScale group_scale(unsigned c2bits)
 {
     GroupScale r;
     const int e = (int)((c2bits >> 23) & 0xffu) - 127;
     int s = (13 - e) >> 1;
     s = s > 30 ? 30 : (s < 0 ? 0 : s);
-    const int s1 = s >> 1, s2 = s - s1;
-    const _Float16 a = (_Float16)__uint_as_float((unsigned)(127 + s1) << 23);
-    const _Float16 b = (_Float16)__uint_as_float((unsigned)(127 + s2) << 23);
-    r.m1 = half2_t{a, a};
-    r.m2 = half2_t{b, b};
+    const int s1 = s >> 1, s2 = s - s1;                     // both at most 15: 2^15 is an fp16 number
+    const unsigned a = (unsigned)(15 + s1) << 10, b = (unsigned)(15 + s2) << 10;     // fp16 bits of 2^s1, 2^s2
+    r.m1 = __builtin_bit_cast(half2_t, a | (a << 16));
+    r.m2 = __builtin_bit_cast(half2_t, b | (b << 16));
     r.f1 = __uint_as_float((unsigned)(127 + s) << 23);
     r.f2 = __uint_as_float((unsigned)(127 + 2 * s) << 23);
     r.c2max_scaled = __uint_as_float(c2bits) * r.f2;
-    r.too_big = !(__uint_as_float(c2bits) < 60000.f);
+    r.too_big = c2bits >= 0x476a6000u;                      // |c|^2 >= 60000 (bits of a non-negative float order like it)
     return r;
 }
 __device__ __forceinline__ unsigned scale_pair(unsigned w, const GroupScale& gs)
@@ -219,12 +235,15 @@ __global__ __launch_bounds__(NW * 64) void encode_mfma_kernel(EncodeArgs a)
         }
     };
     auto commit = [&](int buf, int g) {
-        const GroupScale gs = group_scale(c2bits[g]);
+        const GroupScale gs = group_scale((unsigned)__builtin_amdgcn_readfirstlane((int)c2bits[g]));
 #pragma unroll
         for (int k = 0; k < SPT; ++k) {
             const int j = tid + k * NT;
             if (j >= K) continue;
-            const float v = gs.too_big ? 0.f : -0.5f * gs.f2 * norm2<C / 2>(craw[k]);    // -|c'|^2 / 2
+            unsigned cs[C / 2];
+#pragma unroll
+            for (int i = 0; i < C / 2; ++i) cs[i] = scale_pair(craw[k][i], gs);
+            const float v = gs.too_big ? 0.f : -0.5f * norm2_scaled<C / 2>(cs);          // -|c'|^2 / 2
             const _Float16 h1 = (_Float16)v;
             const float r1 = v - (float)h1;
             const _Float16 h2 = (_Float16)r1;
@@ -232,9 +251,6 @@ __global__ __launch_bounds__(NW * 64) void encode_mfma_kernel(EncodeArgs a)
             const _Float16 zero = (_Float16)0.0f;
             const unsigned w12 = __builtin_bit_cast(unsigned, half2_t{h1, h2});
             const unsigned w30 = __builtin_bit_cast(unsigned, half2_t{h3, zero});
-            unsigned cs[C / 2];
-#pragma unroll
-            for (int i = 0; i < C / 2; ++i) cs[i] = scale_pair(craw[k][i], gs);
             uint4* dst = reinterpret_cast<uint4*>(&cba[buf][j * KDIM]);
             if constexpr (C == 8) {
                 dst[0] = make_uint4(cs[0], cs[1], cs[2], cs[3]);
@@ -293,15 +309,17 @@ __global__ __launch_bounds__(NW * 64) void encode_mfma_kernel(EncodeArgs a)
     __syncthreads();
     for (int g = 0; g < GH; ++g) {
         const int buf = g & 1;
-        const GroupScale gs = group_scale(c2bits[g]);
+        const GroupScale gs = group_scale((unsigned)__builtin_amdgcn_readfirstlane((int)c2bits[g]));
         // this lane's token: its slice of the group (fetched one group ahead), scaled, and |x'|^2
         unsigned xw[C / 2], xs[C / 2];
 #pragma unroll
         for (int i = 0; i < C / 2; ++i) xw[i] = xnext[i];
-        const float x2 = norm2<C / 2>(xw) * gs.f2;
+#pragma unroll
+        for (int i = 0; i < C / 2; ++i) xs[i] = scale_pair(xw[i], gs);
+        const float x2 = norm2_scaled<C / 2>(xs);                // (infinite where the scaling overflowed)
         const bool x_over = !(x2 < 1.0e9f);                      // |x'| beyond 2^15: not as fp16
 #pragma unroll
-        for (int i = 0; i < C / 2; ++i) xs[i] = x_over ? 0u : scale_pair(xw[i], gs);
+        for (int i = 0; i < C / 2; ++i) xs[i] = x_over ? 0u : xs[i];
         if (g + 1 < GH) {
             fetch(g + 1);
             load_x(g + 1, xnext);
@@ -310,16 +328,22 @@ __global__ __launch_bounds__(NW * 64) void encode_mfma_kernel(EncodeArgs a)
         const float thr = (1.01f * (__builtin_sqrtf(x2 * gs.c2max_scaled) + 0.5f * gs.c2max_scaled)) * (1.0f / 131072.0f);
         const bool exact_only = gs.too_big || x_over;
 
+        // Level 1, once per half of the tile (tokens 32 h .. 32 h + 31 are the 32 columns of the
+        // matrix product): the two largest of the lane's 16 NBLK scores.  The maximum of every quad
+        // of scores (the 4 consecutive centroids 8 q + 4 (lane / 32) .. + 3 of a block: registers
+        // 4 q .. 4 q + 3) with the quad's number, 4 (blk % 8) + q, packed into its five lowest
+        // mantissa bits, and a running (best, runner-up) over those: 1.2 VALU instructions per
+        // score instead of the 2.8 of tracking every score.
+        float hbest[2], hsecond[2];
+        int hsb[2];
 #pragma unroll
         for (int h = 0; h < 2; ++h) {
-            // B operand: lanes < 32 carry the channels of token 32 h + lane, lanes >= 32 the ones
-            // that pick up the pieces of -|c|^2 / 2
-            const int src_lane = 32 * h + (lane & 31);
+            // B operand: lanes < 32 carry the channels of token 32 h + lane (their own for h = 0,
+            // the partner lane's for h = 1), lanes >= 32 the ones that pick up the pieces of
+            // -|c|^2 / 2
             unsigned xh[C / 2];
 #pragma unroll
-            for (int i = 0; i < C / 2; ++i) xh[i] = __shfl(xs[i], src_lane);
-            const float thr_h = __shfl(thr, src_lane);
-            const int exact_h = __shfl(exact_only ? 1 : 0, src_lane);
+            for (int i = 0; i < C / 2; ++i) xh[i] = h == 0 ? xs[i] : __shfl_xor(xs[i], 32);
             const _Float16 one = (_Float16)1.0f, zero = (_Float16)0.0f;
             vec_t bop;
             if constexpr (C == 8) {
@@ -346,12 +370,6 @@ __global__ __launch_bounds__(NW * 64) void encode_mfma_kernel(EncodeArgs a)
                 }
             }
 
-            // The two largest of the lane's 16 NBLK scores, found in two levels.  Level 1: the
-            // maximum of every quad of scores (the 4 consecutive centroids 8 q + 4 (lane / 32) .. + 3
-            // of a block: registers 4 q .. 4 q + 3) with the quad's number, 4 (blk % 8) + q, packed
-            // into its five lowest mantissa bits, and a running (best, runner-up) over those:
-            // 1.2 VALU instructions per score instead of the 2.8 of tracking every score.  Level
-            // 2, below: the four scores of the winning quad again, in fp32 on the vector ALU.
             float gbest = LOWEST, gsecond = LOWEST;
             int gsb = 0;                                 // block / 8 of gbest (more than 8 blocks: b = 10)
 #pragma unroll 1
@@ -385,93 +403,102 @@ __global__ __launch_bounds__(NW * 64) void encode_mfma_kernel(EncodeArgs a)
                     gbest = fmaxf(gbest, sbest);
                 }
             }
-            // lanes l and l + 32 saw the two halves of every block's rows for token l % 32
-            const float obest = __shfl_xor(gbest, 32), osecond = __shfl_xor(gsecond, 32);
-            const int osb = NSB == 1 ? 0 : __shfl_xor(gsb, 32);
-            const bool other = obest > gbest;
-            const float best = fmaxf(gbest, obest);
-            const float second = fmaxf(fmaxf(fminf(gbest, obest), gsecond), osecond);
-            const int wsb = other ? osb : gsb;
-            const int whalf = other ? 1 - (lane >> 5) : (lane >> 5);
-            const int u = 32 * h + (lane & 31);                      // token of the tile
-            const int slot = (g - u) & (GH - 1);
-            // level 2: the winning quad's four centroids against this token, x . c - |c|^2 / 2 in fp32
-            // from the records in LDS (every lane has its token's channels; lanes < 32 keep the result)
-            const int quad = (int)(__float_as_uint(best) & 31u);
-            const int j0 = (wsb * 8 + (quad >> 2)) * 32 + 8 * (quad & 3) + 4 * whalf;
-            // (v_dot2_f32_f16: exact products of the fp16 pairs, fp32 sums; the centroid's number
-            // within the quad rides in the two lowest mantissa bits)
-            float qk[4];
-            const half2_t ones = half2_t{(_Float16)1.0f, (_Float16)1.0f};
+            hbest[h] = gbest;
+            hsecond[h] = gsecond;
+            hsb[h] = gsb;
+        }
+        // Lanes l and l + 32 saw the two halves of every block's rows for tokens l % 32 (h = 0) and
+        // 32 + l % 32 (h = 1).  Each lane now takes its OWN token (token `lane`, in half lane / 32):
+        // its own scan of that half, and the partner lane's, which sends it in exchange for the
+        // other half's.  Everything below runs once per tile and group, on all 64 lanes.
+        const int hi = lane >> 5;
+        const float gbest = hi ? hbest[1] : hbest[0], gsecond = hi ? hsecond[1] : hsecond[0];
+        const float obest = __shfl_xor(hi ? hbest[0] : hbest[1], 32), osecond = __shfl_xor(hi ? hsecond[0] : hsecond[1], 32);
+        const int gsb = hi ? hsb[1] : hsb[0];
+        const int osb = NSB == 1 ? 0 : __shfl_xor(hi ? hsb[0] : hsb[1], 32);
+        const bool other = obest > gbest;
+        const float best = fmaxf(gbest, obest);
+        const float second = fmaxf(fmaxf(fminf(gbest, obest), gsecond), osecond);
+        const int wsb = other ? osb : gsb;
+        const int whalf = other ? 1 - hi : hi;
+        const int u = lane;                                      // token of the tile
+        const int slot = (g - u) & (GH - 1);
+        // Level 2: the winning quad's four centroids against this token, x . c - |c|^2 / 2 in fp32
+        // from the records in LDS.
+        const int quad = (int)(__float_as_uint(best) & 31u);
+        const int j0 = (wsb * 8 + (quad >> 2)) * 32 + 8 * (quad & 3) + 4 * whalf;
+        // (v_dot2_f32_f16: exact products of the fp16 pairs, fp32 sums; the centroid's number
+        // within the quad rides in the two lowest mantissa bits)
+        float qk[4];
+        const half2_t ones = half2_t{(_Float16)1.0f, (_Float16)1.0f};
 #pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                const unsigned* r = reinterpret_cast<const unsigned*>(&cba[buf][(j0 + e) * KDIM]);
-                unsigned w[C / 2 + 2];
-                if constexpr (C == 8) {
-                    const uint4 a0 = *reinterpret_cast<const uint4*>(r);
-                    const uint2 a1 = *reinterpret_cast<const uint2*>(r + 4);
-                    w[0] = a0.x; w[1] = a0.y; w[2] = a0.z; w[3] = a0.w; w[4] = a1.x; w[5] = a1.y;
-                } else if constexpr (C == 4) {
-                    const uint4 a0 = *reinterpret_cast<const uint4*>(r);
-                    w[0] = a0.x; w[1] = a0.y; w[2] = a0.z; w[3] = a0.w;
-                } else {
-                    const uint4 a0 = *reinterpret_cast<const uint4*>(r);
-                    w[0] = a0.x; w[1] = a0.y; w[2] = a0.z;
-                }
-                // the three pieces of -|c|^2 / 2 sit behind the C channels: (h1, h2), (h3, 0)
-                float sc = __builtin_amdgcn_fdot2(__builtin_bit_cast(half2_t, w[C / 2 + 1]), ones, 0.f, false);
-                sc = __builtin_amdgcn_fdot2(__builtin_bit_cast(half2_t, w[C / 2]), ones, sc, false);
-#pragma unroll
-                for (int i = 0; i < C / 2; ++i)
-                    sc = __builtin_amdgcn_fdot2(__builtin_bit_cast(half2_t, xh[i]), __builtin_bit_cast(half2_t, w[i]), sc, false);
-                qk[e] = __uint_as_float((__float_as_uint(sc) & 0xfffffffcu) | (unsigned)e);
+        for (int e = 0; e < 4; ++e) {
+            const unsigned* r = reinterpret_cast<const unsigned*>(&cba[buf][(j0 + e) * KDIM]);
+            unsigned w[C / 2 + 2];
+            if constexpr (C == 8) {
+                const uint4 a0 = *reinterpret_cast<const uint4*>(r);
+                const uint2 a1 = *reinterpret_cast<const uint2*>(r + 4);
+                w[0] = a0.x; w[1] = a0.y; w[2] = a0.z; w[3] = a0.w; w[4] = a1.x; w[5] = a1.y;
+            } else if constexpr (C == 4) {
+                const uint4 a0 = *reinterpret_cast<const uint4*>(r);
+                w[0] = a0.x; w[1] = a0.y; w[2] = a0.z; w[3] = a0.w;
+            } else {
+                const uint4 a0 = *reinterpret_cast<const uint4*>(r);
+                w[0] = a0.x; w[1] = a0.y; w[2] = a0.z;
             }
-            const float q01 = fmaxf(qk[0], qk[1]);
-            const float qbest_k = fmaxf(fmaxf(q01, qk[2]), qk[3]);
-            const float qsecond = fmaxf(fminf(qk[0], qk[1]), __builtin_amdgcn_fmed3f(q01, qk[2], qk[3]));
-            const int qarg = (int)(__float_as_uint(qbest_k) & 3u);
-            const float qbest = __uint_as_float(__float_as_uint(qbest_k) & 0xfffffffcu);
-            bool unsure = false;
-            if (lane < 32) {
-                const int code = j0 + qarg;
-                const float sv = fmaxf(__uint_as_float(__float_as_uint(second) & 0xffffffe0u), qsecond);
-                unsure = !(qbest - sv > thr_h) || exact_h != 0;
+            // the three pieces of -|c|^2 / 2 sit behind the C channels: (h1, h2), (h3, 0)
+            float sc = __builtin_amdgcn_fdot2(__builtin_bit_cast(half2_t, w[C / 2 + 1]), ones, 0.f, false);
+            sc = __builtin_amdgcn_fdot2(__builtin_bit_cast(half2_t, w[C / 2]), ones, sc, false);
+#pragma unroll
+            for (int i = 0; i < C / 2; ++i)
+                sc = __builtin_amdgcn_fdot2(__builtin_bit_cast(half2_t, xs[i]), __builtin_bit_cast(half2_t, w[i]), sc, false);
+            qk[e] = __uint_as_float((__float_as_uint(sc) & 0xfffffffcu) | (unsigned)e);
+        }
+        const float q01 = fmaxf(qk[0], qk[1]);
+        const float qbest_k = fmaxf(fmaxf(q01, qk[2]), qk[3]);
+        const float qsecond = fmaxf(fminf(qk[0], qk[1]), __builtin_amdgcn_fmed3f(q01, qk[2], qk[3]));
+        const int qarg = (int)(__float_as_uint(qbest_k) & 3u);
+        const float qbest = __uint_as_float(__float_as_uint(qbest_k) & 0xfffffffcu);
+        bool unsure;
+        {
+            const int code = j0 + qarg;
+            const float sv = fmaxf(__uint_as_float(__float_as_uint(second) & 0xffffffe0u), qsecond);
+            unsure = !(qbest - sv > thr) || exact_only;
+            rec[wave][(slot >> 4) * 1024 + u * 16 + (slot & 15)] = (uint8_t)(code & 0xff);
+            if constexpr (B == 10) code16[wave][u][g] = (uint16_t)code;
+        }
+
+        // exact re-do of the unsure tokens of this tile, one at a time by the whole wavefront
+        unsigned long long todo = __ballot(unsure);
+        while (todo) {
+            const int r = (int)__builtin_ctzll(todo);
+            todo &= todo - 1;
+            float x[C];
+#pragma unroll
+            for (int i = 0; i < C / 2; ++i) {
+                const half2_t hh = __builtin_bit_cast(half2_t, (unsigned)__builtin_amdgcn_readlane((int)xw[i], r));
+                x[2 * i] = (float)hh.x * gs.f1;                // exact in fp32
+                x[2 * i + 1] = (float)hh.y * gs.f1;
+            }
+            unsigned dmin = ~0u, jmin = 0;
+#pragma unroll 4
+            for (int j = lane; j < K; j += 64) {
+                unsigned cw[C / 2];
+#pragma unroll
+                for (int i = 0; i < C / 2; ++i) cw[i] = *reinterpret_cast<const unsigned*>(&cba[buf][j * KDIM + 2 * i]);
+                const unsigned dj = exact_distance_bits<C>(x, cw);
+                jmin = dj < dmin ? (unsigned)j : jmin;       // increasing j: the lowest index stays on ties
+                dmin = dj < dmin ? dj : dmin;
+            }
+            const unsigned wmin = wave_min_u32(dmin);
+            // the lowest index among the lanes that hold the minimum: almost always one lane
+            const unsigned long long holders = __ballot(dmin == wmin);
+            unsigned code;
+            if ((holders & (holders - 1)) == 0) code = (unsigned)__builtin_amdgcn_readlane((int)jmin, (int)__builtin_ctzll(holders));
+            else code = wave_min_u32(dmin == wmin ? jmin : ~0u);
+            if (lane == r) {
                 rec[wave][(slot >> 4) * 1024 + u * 16 + (slot & 15)] = (uint8_t)(code & 0xff);
                 if constexpr (B == 10) code16[wave][u][g] = (uint16_t)code;
-            }
-
-            // exact re-do of the unsure tokens of this half, one at a time by the whole wavefront
-            unsigned todo = (unsigned)__ballot(unsure);                 // lanes < 32 only
-            while (todo) {
-                const int r = __builtin_ctz(todo);
-                todo &= todo - 1;
-                float x[C];
-#pragma unroll
-                for (int i = 0; i < C / 2; ++i) {
-                    const half2_t hh = __builtin_bit_cast(half2_t, (unsigned)__builtin_amdgcn_readlane((int)xw[i], 32 * h + r));
-                    x[2 * i] = (float)hh.x * gs.f1;                // exact in fp32
-                    x[2 * i + 1] = (float)hh.y * gs.f1;
-                }
-                unsigned dmin = ~0u, jmin = 0;
-#pragma unroll 4
-                for (int j = lane; j < K; j += 64) {
-                    unsigned cw[C / 2];
-#pragma unroll
-                    for (int i = 0; i < C / 2; ++i) cw[i] = *reinterpret_cast<const unsigned*>(&cba[buf][j * KDIM + 2 * i]);
-                    const unsigned dj = exact_distance_bits<C>(x, cw);
-                    jmin = dj < dmin ? (unsigned)j : jmin;       // increasing j: the lowest index stays on ties
-                    dmin = dj < dmin ? dj : dmin;
-                }
-                const unsigned wmin = wave_min_u32(dmin);
-                // the lowest index among the lanes that hold the minimum: almost always one lane
-                const unsigned long long holders = __ballot(dmin == wmin);
-                unsigned code;
-                if ((holders & (holders - 1)) == 0) code = (unsigned)__builtin_amdgcn_readlane((int)jmin, (int)__builtin_ctzll(holders));
-                else code = wave_min_u32(dmin == wmin ? jmin : ~0u);
-                if (lane == r) {
-                    rec[wave][(slot >> 4) * 1024 + u * 16 + (slot & 15)] = (uint8_t)(code & 0xff);
-                    if constexpr (B == 10) code16[wave][u][g] = (uint16_t)code;
-                }
             }
         }
         if (g + 1 < GH) commit(buf ^ 1, g + 1);
