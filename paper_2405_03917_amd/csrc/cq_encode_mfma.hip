@@ -183,9 +183,14 @@ __device__ __forceinline__ unsigned scale_pair(unsigned w, const GroupScale& gs)
     return __builtin_bit_cast(unsigned, __builtin_bit_cast(half2_t, w) * gs.m1 * gs.m2);
 }
 
-template <int GH, int C, int B, int NW>
+// GS (group split, for problems too small to fill the chip with one wavefront per tile): the NW
+// wavefronts of a workgroup share ONE tile and take GH / NW groups each; a wavefront stages its
+// groups' codebooks by itself, into a buffer of its own, so nothing but the prologue and the
+// final store of the tile's records is synchronised across the workgroup.
+template <int GH, int C, int B, int NW, bool GS = false>
 __global__ __launch_bounds__(NW * 64) void encode_mfma_kernel(EncodeArgs a)
 {
+    static_assert(!GS || (B == 8 && GH % NW == 0), "group split: byte codes, groups divisible among the wavefronts");
     using A = Aug<C>;
     using vec_t = typename A::vec_t;
     constexpr int K = 1 << B;
@@ -198,21 +203,26 @@ __global__ __launch_bounds__(NW * 64) void encode_mfma_kernel(EncodeArgs a)
     constexpr int TILE_BYTES = kTileTokens * GH * B / 8;
     constexpr float LOWEST = -3.0e38f;
 
-    __shared__ __attribute__((aligned(16))) _Float16 cba[2][K * KDIM];     // augmented codebook records
+    constexpr int SNT = GS ? 64 : NT;                // threads that stage a group's codebook together
+    constexpr int NTILE = GS ? 1 : NW;               // tiles per workgroup
+    // augmented codebook records: two buffers that the workgroup alternates, or (GS) one per wavefront
+    __shared__ __attribute__((aligned(16))) _Float16 cba[GS ? NW : 2][K * KDIM];
     __shared__ unsigned c2bits[GH];                                       // bits of max_j |c_j|^2 per group
-    __shared__ __attribute__((aligned(16))) uint8_t rec[NW][TILE_LOW];     // low code bytes, cache order
+    __shared__ __attribute__((aligned(16))) uint8_t rec[NTILE][TILE_LOW];  // low code bytes, cache order
     __shared__ uint16_t code16[B == 10 ? NW : 1][B == 10 ? kTileTokens : 1][B == 10 ? GH : 1];
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int stid = GS ? lane : tid;                // index among the threads that stage together
+    const int tw = GS ? 0 : wave;                    // this wavefront's tile among the workgroup's
     const int hkv = blockIdx.y;
     const int n = blockIdx.z % a.batch;
     const EncodeTensor& ten = a.tensor[blockIdx.z / a.batch];
 
     const int first_tile = a.t_offset / kTileTokens;
     const int t_end = a.t_offset + a.t_new;
-    const int tile = first_tile + blockIdx.x * NW + wave;
+    const int tile = first_tile + blockIdx.x * NTILE + tw;
     const int pos = tile * kTileTokens + lane;                   // this lane's token (cache position)
     const bool valid = pos >= a.t_offset && pos < t_end;
     const uint16_t* xbase = ten.x + (size_t)n * ten.x_batch_stride + (size_t)hkv * GH * C;
@@ -221,13 +231,13 @@ __global__ __launch_bounds__(NW * 64) void encode_mfma_kernel(EncodeArgs a)
     // Staging of a group's codebook is split in two so that the global loads of group g + 1 fly
     // while group g is computed: fetch() issues them into registers, commit() turns centroid j
     // into its record [channels | three pieces of -|c|^2/2, zeros] in LDS.
-    constexpr int SPT = (K + NT - 1) / NT;           // centroids staged per thread
+    constexpr int SPT = (K + SNT - 1) / SNT;         // centroids staged per thread
     unsigned craw[SPT][C / 2];
     auto fetch = [&](int g) {
         const uint16_t* src = ten.centroids + (size_t)(hkv * GH + g) * K * C;
 #pragma unroll
         for (int k = 0; k < SPT; ++k) {
-            const int j = tid + k * NT;
+            const int j = stid + k * SNT;
             if (j < K) {
 #pragma unroll
                 for (int i = 0; i < C / 2; ++i) craw[k][i] = *reinterpret_cast<const unsigned*>(src + j * C + 2 * i);
@@ -238,7 +248,7 @@ __global__ __launch_bounds__(NW * 64) void encode_mfma_kernel(EncodeArgs a)
         const GroupScale gs = group_scale((unsigned)__builtin_amdgcn_readfirstlane((int)c2bits[g]));
 #pragma unroll
         for (int k = 0; k < SPT; ++k) {
-            const int j = tid + k * NT;
+            const int j = stid + k * SNT;
             if (j >= K) continue;
             unsigned cs[C / 2];
 #pragma unroll
@@ -302,13 +312,14 @@ __global__ __launch_bounds__(NW * 64) void encode_mfma_kernel(EncodeArgs a)
         __syncthreads();
     }
 
-    fetch(0);
-    commit(0, 0);
+    const int g_begin = GS ? wave * (GH / NW) : 0, g_end = GS ? g_begin + GH / NW : GH;
+    fetch(g_begin);
+    commit(GS ? wave : 0, g_begin);
     unsigned xnext[C / 2];
-    load_x(0, xnext);
+    load_x(g_begin, xnext);
     __syncthreads();
-    for (int g = 0; g < GH; ++g) {
-        const int buf = g & 1;
+    for (int g = g_begin; g < g_end; ++g) {
+        const int buf = GS ? wave : (g & 1);
         const GroupScale gs = group_scale((unsigned)__builtin_amdgcn_readfirstlane((int)c2bits[g]));
         // this lane's token: its slice of the group (fetched one group ahead), scaled, and |x'|^2
         unsigned xw[C / 2], xs[C / 2];
@@ -320,7 +331,7 @@ __global__ __launch_bounds__(NW * 64) void encode_mfma_kernel(EncodeArgs a)
         const bool x_over = !(x2 < 1.0e9f);                      // |x'| beyond 2^15: not as fp16
 #pragma unroll
         for (int i = 0; i < C / 2; ++i) xs[i] = x_over ? 0u : xs[i];
-        if (g + 1 < GH) {
+        if (g + 1 < g_end) {
             fetch(g + 1);
             load_x(g + 1, xnext);
         }
@@ -464,7 +475,7 @@ __global__ __launch_bounds__(NW * 64) void encode_mfma_kernel(EncodeArgs a)
             const int code = j0 + qarg;
             const float sv = fmaxf(__uint_as_float(__float_as_uint(second) & 0xffffffe0u), qsecond);
             unsure = !(qbest - sv > thr) || exact_only;
-            rec[wave][(slot >> 4) * 1024 + u * 16 + (slot & 15)] = (uint8_t)(code & 0xff);
+            rec[tw][(slot >> 4) * 1024 + u * 16 + (slot & 15)] = (uint8_t)(code & 0xff);
             if constexpr (B == 10) code16[wave][u][g] = (uint16_t)code;
         }
 
@@ -497,12 +508,17 @@ __global__ __launch_bounds__(NW * 64) void encode_mfma_kernel(EncodeArgs a)
             if ((holders & (holders - 1)) == 0) code = (unsigned)__builtin_amdgcn_readlane((int)jmin, (int)__builtin_ctzll(holders));
             else code = wave_min_u32(dmin == wmin ? jmin : ~0u);
             if (lane == r) {
-                rec[wave][(slot >> 4) * 1024 + u * 16 + (slot & 15)] = (uint8_t)(code & 0xff);
+                rec[tw][(slot >> 4) * 1024 + u * 16 + (slot & 15)] = (uint8_t)(code & 0xff);
                 if constexpr (B == 10) code16[wave][u][g] = (uint16_t)code;
             }
         }
-        if (g + 1 < GH) commit(buf ^ 1, g + 1);
-        __syncthreads();
+        // (GS: the wavefront is the only reader of its buffer, and its LDS operations keep their order)
+        if (g + 1 < g_end) commit(GS ? wave : buf ^ 1, g + 1);
+        if constexpr (!GS) __syncthreads();
+    }
+    if constexpr (GS) {
+        __syncthreads();                // the tile's codes of all groups are in rec
+        if (wave != 0) return;
     }
 
     // store this lane's token
@@ -510,7 +526,7 @@ __global__ __launch_bounds__(NW * 64) void encode_mfma_kernel(EncodeArgs a)
         uint8_t* tp = ten.codes + a.map.tile_index(n, hkv, tile) * TILE_BYTES;
 #pragma unroll
         for (int p = 0; p < P; ++p) {
-            const uint4 v = *reinterpret_cast<const uint4*>(&rec[wave][p * 1024 + lane * 16]);
+            const uint4 v = *reinterpret_cast<const uint4*>(&rec[tw][p * 1024 + lane * 16]);
             *reinterpret_cast<uint4*>(tp + p * 1024 + lane * 16) = v;
         }
         if constexpr (B == 10) {
@@ -522,6 +538,11 @@ __global__ __launch_bounds__(NW * 64) void encode_mfma_kernel(EncodeArgs a)
         }
     }
 }
+
+// below this many (tile, head, sequence, tensor) items a call takes the group-split kernel
+constexpr long kGroupSplitBelow = 4096;
+// ... and up to this many, eight wavefronts per tile instead of four
+constexpr long kGroupSplitEightBelow = 1024;
 
 template <int GH, int C, int B>
 cq_status launch_mfma_format(const EncodeArgs& a, hipStream_t stream)
@@ -536,6 +557,17 @@ cq_status launch_mfma_format(const EncodeArgs& a, hipStream_t stream)
         constexpr int NW = 4;
         dim3 grid((unsigned)((n_tiles + NW - 1) / NW), (unsigned)a.f.n_kv_heads, (unsigned)(a.batch * a.n_tensors));
         hipLaunchKernelGGL((encode_mfma_kernel<GH, C, B, NW>), grid, dim3(NW * 64), 0, stream, a);
+    } else if (B == 8 && wave_tiles < kGroupSplitBelow) {
+        // few tiles: several wavefronts per tile, a share of the groups each (a wavefront's chain
+        // of groups is the latency of such a call); eight wavefronts while those still fit the
+        // chip at once, else four
+        if constexpr (B == 8) {
+            dim3 grid((unsigned)n_tiles, (unsigned)a.f.n_kv_heads, (unsigned)(a.batch * a.n_tensors));
+            if (wave_tiles <= kGroupSplitEightBelow)
+                hipLaunchKernelGGL((encode_mfma_kernel<GH, C, B, 8, true>), grid, dim3(8 * 64), 0, stream, a);
+            else
+                hipLaunchKernelGGL((encode_mfma_kernel<GH, C, B, 4, true>), grid, dim3(4 * 64), 0, stream, a);
+        }
     } else {
         constexpr int NW = 1;
         dim3 grid((unsigned)n_tiles, (unsigned)a.f.n_kv_heads, (unsigned)(a.batch * a.n_tensors));

@@ -89,6 +89,38 @@ def test_encode_large_batch_of_tiles_uses_the_wide_kernel():
         check_codes(codes[n, rows], xg[n, rows].cpu().numpy(), cb)
 
 
+@pytest.mark.parametrize("c,b", [(8, 8), (4, 8), (2, 8)])
+@pytest.mark.parametrize("hkv,B,T,t_off", [(8, 2, 1000, 37),      # 256 (tile, head, sequence) items: eight wavefronts share a tile
+                                           (8, 4, 4100, 37),      # 2080: four wavefronts share a tile
+                                           (32, 64, 130, 5),      # 6144 items of 3 tiles per sequence: one wavefront per tile
+                                           (32, 4, 4100, 37)])    # 8320: four tiles per workgroup
+def test_encode_every_launch_shape_of_the_matrix_core_kernel(c, b, hkv, B, T, t_off):
+    # the library picks the kernel's shape from the amount of work; each shape against the oracle
+    # on sampled rows, at an offset that leaves the first and the last tile ragged
+    fmt = cq.CQFormat(c, b, 128, hkv)
+    D = hkv * 128
+    t_cap = (t_off + T + 63) // 64 * 64
+    r = synth.tensor_recipe(16, 0, "k", D)
+    cb = synth.sample_codebook(r, c, b)
+    xg = synth.sample_activations_torch(r, B * T, 2, "cuda").reshape(B, T, D)
+    cache = torch.full((cq.cq_cache_bytes(fmt, B, t_cap),), 0xA5, dtype=torch.uint8, device="cuda")
+    cq.cq_encode(xg, dev(cb), fmt, cache, t_off, t_cap)
+    torch.cuda.synchronize()
+    codes = cache_to_codes(cache, fmt, B, t_cap, T, t_off)
+    rng = np.random.default_rng(c * 1000 + hkv + T)
+    for n in sorted({0, B - 1, int(rng.integers(0, B))}):
+        rows = np.sort(rng.choice(T, size=16, replace=False))
+        rows[:5] = [0, 63 - t_off, 64 - t_off, T - 2, T - 1]
+        check_codes(codes[n, rows], xg[n, rows].cpu().numpy(), cb)
+    # nothing outside [t_off, t_off + T) was written
+    fill = torch.full_like(cache, 0xA5)
+    assert np.array_equal(cache_to_codes(cache, fmt, B, t_cap, t_off, 0), cache_to_codes(fill, fmt, B, t_cap, t_off, 0))
+    tail = t_cap - (t_off + T)
+    if tail:
+        assert np.array_equal(cache_to_codes(cache, fmt, B, t_cap, tail, t_off + T),
+                              cache_to_codes(fill, fmt, B, t_cap, tail, t_off + T))
+
+
 @pytest.mark.parametrize("c,b", FORMATS)
 @pytest.mark.parametrize("t_new,t_off", [(3, 130), (200, 37)])
 def test_encode_kv_equals_two_encodes(c, b, t_new, t_off):
