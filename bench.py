@@ -385,7 +385,7 @@ def extra_measurements(cq, synth, torch):
                     "(cq_chunk_attention)",
         "ms": med_c, "query_token_pairs_per_s": pairs / (med_c * 1e-3),
         "useful_TFLOPs": pairs * 4 * cfg.head_dim / (med_c * 1e-3) / 1e12,
-        "roofline": {"bound": "mfma", "kernel": "chunk_attention_kernel<16, 8, 8>", "achieved": executed, "peak": FP16_MFMA_PEAK_TFLOPS,
+        "roofline": {"bound": "mfma", "kernel": "chunk_attention_kernel<16, 8, 8, 8, false>", "achieved": executed, "peak": FP16_MFMA_PEAK_TFLOPS,
                      "unit": "TFLOP/s", "frac": executed / FP16_MFMA_PEAK_TFLOPS, "traffic": None,
                      "note": "executed fp16 MFMA work (probabilities split into two fp16 parts: 6 d flops per pair, 4 d useful)"}}
     # the same chunk over the caches read as pre-RoPE keys: each key tile is rotated once in LDS
