@@ -244,8 +244,22 @@ __global__ __launch_bounds__(NW * 64) void encode_mfma_kernel(EncodeArgs a)
             }
         }
     };
+    // bits of max_j |c_j|^2 of the group being committed.  Not GS: from the prologue pass below.  GS:
+    // the wavefront holds the whole group in craw and takes the maximum itself (c2_staged then
+    // serves the group's turn in the main loop), which spares the small call that pass
+    unsigned c2_staged = 0;
     auto commit = [&](int buf, int g) {
-        const GroupScale gs = group_scale((unsigned)__builtin_amdgcn_readfirstlane((int)c2bits[g]));
+        unsigned c2;
+        if constexpr (GS) {
+            float m = 0.f;
+#pragma unroll
+            for (int k = 0; k < SPT; ++k)
+                if (stid + k * SNT < K) m = fmaxf(m, norm2<C / 2>(craw[k]));
+            c2 = c2_staged = wave_max_u32(__float_as_uint(m));
+        } else {
+            c2 = (unsigned)__builtin_amdgcn_readfirstlane((int)c2bits[g]);
+        }
+        const GroupScale gs = group_scale(c2);
 #pragma unroll
         for (int k = 0; k < SPT; ++k) {
             const int j = stid + k * SNT;
@@ -279,7 +293,7 @@ __global__ __launch_bounds__(NW * 64) void encode_mfma_kernel(EncodeArgs a)
 
     // max_j |c_j|^2 of every group of this head: each thread takes 16-byte pieces of the head's
     // codebooks; a group's pieces are a multiple of 64, so a wavefront works on one group at a time
-    {
+    if constexpr (!GS) {
         constexpr int CH = K * C / 8;                // 16-byte pieces per group
         constexpr int ROUNDS = GH * CH / NT;
         static_assert(CH % 64 == 0 && (GH * CH) % NT == 0, "a wavefront's pieces must share a group");
@@ -317,10 +331,10 @@ __global__ __launch_bounds__(NW * 64) void encode_mfma_kernel(EncodeArgs a)
     commit(GS ? wave : 0, g_begin);
     unsigned xnext[C / 2];
     load_x(g_begin, xnext);
-    __syncthreads();
+    if constexpr (!GS) __syncthreads();
     for (int g = g_begin; g < g_end; ++g) {
         const int buf = GS ? wave : (g & 1);
-        const GroupScale gs = group_scale((unsigned)__builtin_amdgcn_readfirstlane((int)c2bits[g]));
+        const GroupScale gs = group_scale(GS ? c2_staged : (unsigned)__builtin_amdgcn_readfirstlane((int)c2bits[g]));
         // this lane's token: its slice of the group (fetched one group ahead), scaled, and |x'|^2
         unsigned xw[C / 2], xs[C / 2];
 #pragma unroll
