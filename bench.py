@@ -311,7 +311,7 @@ def extra_measurements(cq, synth, torch):
     ms_enc = time_rotating(torch, enc_calls, 5)
     ms_dec = time_rotating(torch, dec_calls, 5)
     code_bytes = T * 2 * D * cfg.b // (8 * cfg.c)
-    enc_r, enc_pairs = encode_roofline("encode_mfma_kernel<16, 8, 8, 8, true> (K and V in one cq_encode_kv launch)", 2 * T, D, 256, ms_enc, True)
+    enc_r, enc_pairs = encode_roofline("encode_mfma_kernel<16, 8, 8, 8, true, 1> (K and V in one cq_encode_kv launch)", 2 * T, D, 256, ms_enc, True)
     enc_r.update(achieved=MFMA_SCORE_OPS * enc_pairs / 8 / 1e12, frac=MFMA_SCORE_OPS * enc_pairs / 8 / VALU_PEAK_LANE_OPS)
     out["cfg1_encode_1024_tokens_then_one_decode_step"] = {
         "workload": "CQ-8c8b, batch 1, 32 heads x 128, context 1024: cq_encode_kv of all 1024 tokens (K and V), then "
@@ -341,7 +341,7 @@ def extra_measurements(cq, synth, torch):
     xk = synth.sample_activations_torch(st0["rk"], chunk, 777, "cuda").view(1, chunk, D)
     scratch_cache = cq.alloc_cache(fmt, 1, chunk)
     enc_ms, _ = time_calls(torch, lambda: cq.cq_encode(xk, st0["ck"], fmt, scratch_cache, 0, chunk), 5, 1)
-    enc_r, enc_pairs = encode_roofline("encode_mfma_kernel<16, 8, 8, 4, false>", chunk, D, 256, enc_ms, True)
+    enc_r, enc_pairs = encode_roofline("encode_mfma_kernel<16, 8, 8, 4, true, 4>", chunk, D, 256, enc_ms, True)
     enc_r.update(achieved=MFMA_SCORE_OPS * enc_pairs / 8 / 1e12, frac=MFMA_SCORE_OPS * enc_pairs / 8 / VALU_PEAK_LANE_OPS)
     out["encode_prefill"] = {"workload": "CQ-8c8b, 32768 tokens x 4096 channels, one tensor, one cq_encode call",
                              "ms": enc_ms, "tokens_per_s": chunk / (enc_ms * 1e-3), "roofline": enc_r}
@@ -413,7 +413,7 @@ def extra_measurements(cq, synth, torch):
             x = synth.sample_activations_torch(sets[0]["rk"], B * te, 4242, "cuda").view(B, te, D)
             enc_ms, _ = time_calls(torch, lambda: cq.cq_encode(x, sets[0]["ck"], fmt, sets[0]["kcache"], 0, T), 5, 1)
             gh = cfg.head_dim // cfg.c
-            enc_r, enc_pairs = encode_roofline(f"encode_mfma_kernel<{gh}, {cfg.c}, {cfg.b}, 4, false>", B * te, D, 1 << cfg.b, enc_ms, True)
+            enc_r, enc_pairs = encode_roofline((f"encode_mfma_kernel<{gh}, {cfg.c}, {cfg.b}, 4, true, 4>" if cfg.b == 8 else f"encode_mfma_kernel<{gh}, {cfg.c}, {cfg.b}, 4, false, 1>"), B * te, D, 1 << cfg.b, enc_ms, True)
             enc_r.update(achieved=MFMA_SCORE_OPS * enc_pairs / cfg.c / 1e12, frac=MFMA_SCORE_OPS * enc_pairs / cfg.c / VALU_PEAK_LANE_OPS)
             out[f"encode_cq{cfg.c}c{cfg.b}b_{B}x{te}"] = {
                 "workload": f"CQ-{cfg.c}c{cfg.b}b, {B} sequences x {te} tokens x {D} channels, one tensor, one cq_encode call",

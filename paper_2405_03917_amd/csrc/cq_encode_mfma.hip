@@ -183,14 +183,17 @@ __device__ __forceinline__ unsigned scale_pair(unsigned w, const GroupScale& gs)
     return __builtin_bit_cast(unsigned, __builtin_bit_cast(half2_t, w) * gs.m1 * gs.m2);
 }
 
-// GS (group split, for problems too small to fill the chip with one wavefront per tile): the NW
-// wavefronts of a workgroup share ONE tile and take GH / NW groups each; a wavefront stages its
-// groups' codebooks by itself, into a buffer of its own, so nothing but the prologue and the
-// final store of the tile's records is synchronised across the workgroup.
-template <int GH, int C, int B, int NW, bool GS = false>
+// GS (group split): the NW wavefronts of a workgroup share TILES tiles and take GH / NW groups
+// each, for every one of those tiles; a wavefront stages its groups' codebooks by itself, into a
+// buffer of its own, so nothing but the final store of the tiles' records is synchronised across
+// the workgroup.  TILES = 1 spreads a small problem over the chip (a wavefront's chain of groups
+// is the latency of such a call); TILES = NW costs the staging of the shared-buffer form
+// without its barrier per group.
+template <int GH, int C, int B, int NW, bool GS = false, int TILES = 1>
 __global__ __launch_bounds__(NW * 64) void encode_mfma_kernel(EncodeArgs a)
 {
     static_assert(!GS || (B == 8 && GH % NW == 0), "group split: byte codes, groups divisible among the wavefronts");
+    static_assert(GS || TILES == 1, "several tiles per wavefront: group split only");
     using A = Aug<C>;
     using vec_t = typename A::vec_t;
     constexpr int K = 1 << B;
@@ -204,7 +207,8 @@ __global__ __launch_bounds__(NW * 64) void encode_mfma_kernel(EncodeArgs a)
     constexpr float LOWEST = -3.0e38f;
 
     constexpr int SNT = GS ? 64 : NT;                // threads that stage a group's codebook together
-    constexpr int NTILE = GS ? 1 : NW;               // tiles per workgroup
+    constexpr int NTILE = GS ? TILES : NW;           // tiles per workgroup
+    constexpr int TPW = GS ? TILES : 1;              // tiles per wavefront
     // augmented codebook records: two buffers that the workgroup alternates, or (GS) one per wavefront
     __shared__ __attribute__((aligned(16))) _Float16 cba[GS ? NW : 2][K * KDIM];
     __shared__ unsigned c2bits[GH];                                       // bits of max_j |c_j|^2 per group
@@ -215,18 +219,25 @@ __global__ __launch_bounds__(NW * 64) void encode_mfma_kernel(EncodeArgs a)
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int stid = GS ? lane : tid;                // index among the threads that stage together
-    const int tw = GS ? 0 : wave;                    // this wavefront's tile among the workgroup's
     const int hkv = blockIdx.y;
     const int n = blockIdx.z % a.batch;
     const EncodeTensor& ten = a.tensor[blockIdx.z / a.batch];
 
     const int first_tile = a.t_offset / kTileTokens;
     const int t_end = a.t_offset + a.t_new;
-    const int tile = first_tile + blockIdx.x * NTILE + tw;
-    const int pos = tile * kTileTokens + lane;                   // this lane's token (cache position)
-    const bool valid = pos >= a.t_offset && pos < t_end;
+    const int last_tile = (t_end - 1) / kTileTokens;
+    // tile t of this wavefront (GS: of the workgroup); this lane's token in it (cache position)
+    auto tile_index = [&](int t) { return GS ? t : wave; };
+    auto tile_at = [&](int t) { return first_tile + (int)blockIdx.x * NTILE + tile_index(t); };
+    auto valid_at = [&](int t) {
+        const int pos = tile_at(t) * kTileTokens + lane;
+        return pos >= a.t_offset && pos < t_end;
+    };
     const uint16_t* xbase = ten.x + (size_t)n * ten.x_batch_stride + (size_t)hkv * GH * C;
-    const uint16_t* xrow = xbase + (size_t)(valid ? pos - a.t_offset : 0) * ten.x_row_stride;
+    auto xrow_at = [&](int t) {
+        const int pos = tile_at(t) * kTileTokens + lane;
+        return xbase + (size_t)(valid_at(t) ? pos - a.t_offset : 0) * ten.x_row_stride;
+    };
 
     // Staging of a group's codebook is split in two so that the global loads of group g + 1 fly
     // while group g is computed: fetch() issues them into registers, commit() turns centroid j
@@ -286,7 +297,8 @@ __global__ __launch_bounds__(NW * 64) void encode_mfma_kernel(EncodeArgs a)
             }
         }
     };
-    auto load_x = [&](int g, unsigned (&dst)[C / 2]) {
+    auto load_x = [&](int g, int t, unsigned (&dst)[C / 2]) {
+        const uint16_t* xrow = xrow_at(t);
 #pragma unroll
         for (int i = 0; i < C / 2; ++i) dst[i] = *reinterpret_cast<const unsigned*>(xrow + g * C + 2 * i);
     };
@@ -329,26 +341,35 @@ __global__ __launch_bounds__(NW * 64) void encode_mfma_kernel(EncodeArgs a)
     const int g_begin = GS ? wave * (GH / NW) : 0, g_end = GS ? g_begin + GH / NW : GH;
     fetch(g_begin);
     commit(GS ? wave : 0, g_begin);
-    unsigned xnext[C / 2];
-    load_x(g_begin, xnext);
+    // the token slices of the tiles to come, in the order of their use: xnext[0] is the next one
+    unsigned xnext[TPW][C / 2];
+#pragma unroll
+    for (int t = 0; t < TPW; ++t) load_x(g_begin, t, xnext[t]);
     if constexpr (!GS) __syncthreads();
     for (int g = g_begin; g < g_end; ++g) {
         const int buf = GS ? wave : (g & 1);
         const GroupScale gs = group_scale(GS ? c2_staged : (unsigned)__builtin_amdgcn_readfirstlane((int)c2bits[g]));
+        if (g + 1 < g_end) fetch(g + 1);
+#pragma unroll 1
+      for (int t = 0; t < TPW; ++t) {
+        const int ti = tile_index(t);
         // this lane's token: its slice of the group (fetched one group ahead), scaled, and |x'|^2
         unsigned xw[C / 2], xs[C / 2];
 #pragma unroll
-        for (int i = 0; i < C / 2; ++i) xw[i] = xnext[i];
+        for (int i = 0; i < C / 2; ++i) xw[i] = xnext[0][i];
+        // (the slices loaded earlier move up before the new request goes out: nothing in flight is touched)
+#pragma unroll
+        for (int k = 0; k + 1 < TPW; ++k)
+#pragma unroll
+            for (int i = 0; i < C / 2; ++i) xnext[k][i] = xnext[k + 1][i];
+        if (g + 1 < g_end) load_x(g + 1, t, xnext[TPW - 1]);
+        if (TPW > 1 && tile_at(t) > last_tile) continue;        // (a workgroup's tiles beyond the call's last)
 #pragma unroll
         for (int i = 0; i < C / 2; ++i) xs[i] = scale_pair(xw[i], gs);
         const float x2 = norm2_scaled<C / 2>(xs);                // (infinite where the scaling overflowed)
         const bool x_over = !(x2 < 1.0e9f);                      // |x'| beyond 2^15: not as fp16
 #pragma unroll
         for (int i = 0; i < C / 2; ++i) xs[i] = x_over ? 0u : xs[i];
-        if (g + 1 < g_end) {
-            fetch(g + 1);
-            load_x(g + 1, xnext);
-        }
         // 2^-17 M with M >= |x'| |c'|max + |c'|max^2 / 2 (1 % slack for the roundings of this line)
         const float thr = (1.01f * (__builtin_sqrtf(x2 * gs.c2max_scaled) + 0.5f * gs.c2max_scaled)) * (1.0f / 131072.0f);
         const bool exact_only = gs.too_big || x_over;
@@ -489,7 +510,7 @@ __global__ __launch_bounds__(NW * 64) void encode_mfma_kernel(EncodeArgs a)
             const int code = j0 + qarg;
             const float sv = fmaxf(__uint_as_float(__float_as_uint(second) & 0xffffffe0u), qsecond);
             unsure = !(qbest - sv > thr) || exact_only;
-            rec[tw][(slot >> 4) * 1024 + u * 16 + (slot & 15)] = (uint8_t)(code & 0xff);
+            rec[ti][(slot >> 4) * 1024 + u * 16 + (slot & 15)] = (uint8_t)(code & 0xff);
             if constexpr (B == 10) code16[wave][u][g] = (uint16_t)code;
         }
 
@@ -522,25 +543,25 @@ __global__ __launch_bounds__(NW * 64) void encode_mfma_kernel(EncodeArgs a)
             if ((holders & (holders - 1)) == 0) code = (unsigned)__builtin_amdgcn_readlane((int)jmin, (int)__builtin_ctzll(holders));
             else code = wave_min_u32(dmin == wmin ? jmin : ~0u);
             if (lane == r) {
-                rec[tw][(slot >> 4) * 1024 + u * 16 + (slot & 15)] = (uint8_t)(code & 0xff);
+                rec[ti][(slot >> 4) * 1024 + u * 16 + (slot & 15)] = (uint8_t)(code & 0xff);
                 if constexpr (B == 10) code16[wave][u][g] = (uint16_t)code;
             }
         }
+      }
         // (GS: the wavefront is the only reader of its buffer, and its LDS operations keep their order)
         if (g + 1 < g_end) commit(GS ? wave : buf ^ 1, g + 1);
         if constexpr (!GS) __syncthreads();
     }
-    if constexpr (GS) {
-        __syncthreads();                // the tile's codes of all groups are in rec
-        if (wave != 0) return;
-    }
+    if constexpr (GS) __syncthreads();  // the tiles' codes of all groups are in rec
 
-    // store this lane's token
-    if (valid) {
-        uint8_t* tp = ten.codes + a.map.tile_index(n, hkv, tile) * TILE_BYTES;
+    // store this lane's token (GS: the wavefronts share the workgroup's tiles out)
+    for (int t = GS ? wave : 0; t < (GS ? TILES : 1); t += GS ? NW : 1) {
+        if (!valid_at(t)) continue;
+        const int ti = tile_index(t);
+        uint8_t* tp = ten.codes + a.map.tile_index(n, hkv, tile_at(t)) * TILE_BYTES;
 #pragma unroll
         for (int p = 0; p < P; ++p) {
-            const uint4 v = *reinterpret_cast<const uint4*>(&rec[tw][p * 1024 + lane * 16]);
+            const uint4 v = *reinterpret_cast<const uint4*>(&rec[ti][p * 1024 + lane * 16]);
             *reinterpret_cast<uint4*>(tp + p * 1024 + lane * 16) = v;
         }
         if constexpr (B == 10) {
@@ -553,9 +574,10 @@ __global__ __launch_bounds__(NW * 64) void encode_mfma_kernel(EncodeArgs a)
     }
 }
 
-// below this many (tile, head, sequence, tensor) items a call takes the group-split kernel
+// Byte codes: up to kGroupSplitEightBelow (tile, head, sequence, tensor) items eight wavefronts
+// share a tile, below kGroupSplitBelow (and for sequences of fewer than four tiles) four; larger
+// calls give four tiles to a workgroup of four wavefronts.
 constexpr long kGroupSplitBelow = 4096;
-// ... and up to this many, eight wavefronts per tile instead of four
 constexpr long kGroupSplitEightBelow = 1024;
 
 template <int GH, int C, int B>
@@ -565,27 +587,25 @@ cq_status launch_mfma_format(const EncodeArgs& a, hipStream_t stream)
     const int last_tile = (a.t_offset + a.t_new - 1) / kTileTokens;
     const int n_tiles = last_tile - first_tile + 1;
     const long wave_tiles = (long)n_tiles * a.f.n_kv_heads * a.batch * a.n_tensors;
-    // four tiles per workgroup share one staging of each group's codebook; small problems take one
-    // tile per workgroup to spread over the CUs
-    if (wave_tiles >= 4096 && n_tiles >= 4) {
-        constexpr int NW = 4;
-        dim3 grid((unsigned)((n_tiles + NW - 1) / NW), (unsigned)a.f.n_kv_heads, (unsigned)(a.batch * a.n_tensors));
-        hipLaunchKernelGGL((encode_mfma_kernel<GH, C, B, NW>), grid, dim3(NW * 64), 0, stream, a);
-    } else if (B == 8 && wave_tiles < kGroupSplitBelow) {
-        // few tiles: several wavefronts per tile, a share of the groups each (a wavefront's chain
-        // of groups is the latency of such a call); eight wavefronts while those still fit the
-        // chip at once, else four
-        if constexpr (B == 8) {
-            dim3 grid((unsigned)n_tiles, (unsigned)a.f.n_kv_heads, (unsigned)(a.batch * a.n_tensors));
-            if (wave_tiles <= kGroupSplitEightBelow)
-                hipLaunchKernelGGL((encode_mfma_kernel<GH, C, B, 8, true>), grid, dim3(8 * 64), 0, stream, a);
-            else
-                hipLaunchKernelGGL((encode_mfma_kernel<GH, C, B, 4, true>), grid, dim3(4 * 64), 0, stream, a);
+    const unsigned gy = (unsigned)a.f.n_kv_heads, gz = (unsigned)(a.batch * a.n_tensors);
+    if constexpr (B == 8) {
+        if (wave_tiles <= kGroupSplitEightBelow) {
+            hipLaunchKernelGGL((encode_mfma_kernel<GH, C, B, 8, true, 1>), dim3((unsigned)n_tiles, gy, gz), dim3(8 * 64), 0, stream, a);
+        } else if (wave_tiles < kGroupSplitBelow || n_tiles < 4) {
+            hipLaunchKernelGGL((encode_mfma_kernel<GH, C, B, 4, true, 1>), dim3((unsigned)n_tiles, gy, gz), dim3(4 * 64), 0, stream, a);
+        } else {
+            hipLaunchKernelGGL((encode_mfma_kernel<GH, C, B, 4, true, 4>), dim3((unsigned)((n_tiles + 3) / 4), gy, gz), dim3(4 * 64), 0, stream, a);
         }
     } else {
-        constexpr int NW = 1;
-        dim3 grid((unsigned)n_tiles, (unsigned)a.f.n_kv_heads, (unsigned)(a.batch * a.n_tensors));
-        hipLaunchKernelGGL((encode_mfma_kernel<GH, C, B, NW>), grid, dim3(NW * 64), 0, stream, a);
+        // 1024 centroids per group: one buffer per wavefront would not fit; four tiles per workgroup
+        // share one staging of each group's codebook, small problems take one tile per workgroup
+        if (wave_tiles >= 4096 && n_tiles >= 4) {
+            constexpr int NW = 4;
+            hipLaunchKernelGGL((encode_mfma_kernel<GH, C, B, NW>), dim3((unsigned)((n_tiles + NW - 1) / NW), gy, gz), dim3(NW * 64), 0, stream, a);
+        } else {
+            constexpr int NW = 1;
+            hipLaunchKernelGGL((encode_mfma_kernel<GH, C, B, NW>), dim3((unsigned)n_tiles, gy, gz), dim3(NW * 64), 0, stream, a);
+        }
     }
     if (hipGetLastError() != hipSuccess) return CQ_ERR_HIP;
     return CQ_OK;

@@ -92,8 +92,8 @@ def test_encode_large_batch_of_tiles_uses_the_wide_kernel():
 @pytest.mark.parametrize("c,b", [(8, 8), (4, 8), (2, 8)])
 @pytest.mark.parametrize("hkv,B,T,t_off", [(8, 2, 1000, 37),      # 256 (tile, head, sequence) items: eight wavefronts share a tile
                                            (8, 4, 4100, 37),      # 2080: four wavefronts share a tile
-                                           (32, 64, 130, 5),      # 6144 items of 3 tiles per sequence: one wavefront per tile
-                                           (32, 4, 4100, 37)])    # 8320: four tiles per workgroup
+                                           (32, 64, 130, 5),      # 6144 items, but only 3 tiles per sequence: as before
+                                           (32, 4, 4100, 37)])    # 8320: four tiles per workgroup (65 tiles: the last one has three to skip)
 def test_encode_every_launch_shape_of_the_matrix_core_kernel(c, b, hkv, B, T, t_off):
     # the library picks the kernel's shape from the amount of work; each shape against the oracle
     # on sampled rows, at an offset that leaves the first and the last tile ragged
