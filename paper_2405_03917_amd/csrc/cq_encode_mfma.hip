@@ -351,203 +351,203 @@ __global__ __launch_bounds__(NW * 64) void encode_mfma_kernel(EncodeArgs a)
         const GroupScale gs = group_scale(GS ? c2_staged : (unsigned)__builtin_amdgcn_readfirstlane((int)c2bits[g]));
         if (g + 1 < g_end) fetch(g + 1);
 #pragma unroll 1
-      for (int t = 0; t < TPW; ++t) {
-        const int ti = tile_index(t);
-        // this lane's token: its slice of the group (fetched one group ahead), scaled, and |x'|^2
-        unsigned xw[C / 2], xs[C / 2];
+        for (int t = 0; t < TPW; ++t) {
+            const int ti = tile_index(t);
+            // this lane's token: its slice of the group (fetched one group ahead), scaled, and |x'|^2
+            unsigned xw[C / 2], xs[C / 2];
 #pragma unroll
-        for (int i = 0; i < C / 2; ++i) xw[i] = xnext[0][i];
-        // (the slices loaded earlier move up before the new request goes out: nothing in flight is touched)
+            for (int i = 0; i < C / 2; ++i) xw[i] = xnext[0][i];
+            // (the slices loaded earlier move up before the new request goes out: nothing in flight is touched)
 #pragma unroll
-        for (int k = 0; k + 1 < TPW; ++k)
+            for (int k = 0; k + 1 < TPW; ++k)
 #pragma unroll
-            for (int i = 0; i < C / 2; ++i) xnext[k][i] = xnext[k + 1][i];
-        if (g + 1 < g_end) load_x(g + 1, t, xnext[TPW - 1]);
-        if (TPW > 1 && tile_at(t) > last_tile) continue;        // (a workgroup's tiles beyond the call's last)
+                for (int i = 0; i < C / 2; ++i) xnext[k][i] = xnext[k + 1][i];
+            if (g + 1 < g_end) load_x(g + 1, t, xnext[TPW - 1]);
+            if (TPW > 1 && tile_at(t) > last_tile) continue;        // (a workgroup's tiles beyond the call's last)
 #pragma unroll
-        for (int i = 0; i < C / 2; ++i) xs[i] = scale_pair(xw[i], gs);
-        const float x2 = norm2_scaled<C / 2>(xs);                // (infinite where the scaling overflowed)
-        const bool x_over = !(x2 < 1.0e9f);                      // |x'| beyond 2^15: not as fp16
+            for (int i = 0; i < C / 2; ++i) xs[i] = scale_pair(xw[i], gs);
+            const float x2 = norm2_scaled<C / 2>(xs);                // (infinite where the scaling overflowed)
+            const bool x_over = !(x2 < 1.0e9f);                      // |x'| beyond 2^15: not as fp16
 #pragma unroll
-        for (int i = 0; i < C / 2; ++i) xs[i] = x_over ? 0u : xs[i];
-        // 2^-17 M with M >= |x'| |c'|max + |c'|max^2 / 2 (1 % slack for the roundings of this line)
-        const float thr = (1.01f * (__builtin_sqrtf(x2 * gs.c2max_scaled) + 0.5f * gs.c2max_scaled)) * (1.0f / 131072.0f);
-        const bool exact_only = gs.too_big || x_over;
+            for (int i = 0; i < C / 2; ++i) xs[i] = x_over ? 0u : xs[i];
+            // 2^-17 M with M >= |x'| |c'|max + |c'|max^2 / 2 (1 % slack for the roundings of this line)
+            const float thr = (1.01f * (__builtin_sqrtf(x2 * gs.c2max_scaled) + 0.5f * gs.c2max_scaled)) * (1.0f / 131072.0f);
+            const bool exact_only = gs.too_big || x_over;
 
-        // Level 1, once per half of the tile (tokens 32 h .. 32 h + 31 are the 32 columns of the
-        // matrix product): the two largest of the lane's 16 NBLK scores.  The maximum of every quad
-        // of scores (the 4 consecutive centroids 8 q + 4 (lane / 32) .. + 3 of a block: registers
-        // 4 q .. 4 q + 3) with the quad's number, 4 (blk % 8) + q, packed into its five lowest
-        // mantissa bits, and a running (best, runner-up) over those: 1.2 VALU instructions per
-        // score instead of the 2.8 of tracking every score.
-        float hbest[2], hsecond[2];
-        int hsb[2];
+            // Level 1, once per half of the tile (tokens 32 h .. 32 h + 31 are the 32 columns of the
+            // matrix product): the two largest of the lane's 16 NBLK scores.  The maximum of every quad
+            // of scores (the 4 consecutive centroids 8 q + 4 (lane / 32) .. + 3 of a block: registers
+            // 4 q .. 4 q + 3) with the quad's number, 4 (blk % 8) + q, packed into its five lowest
+            // mantissa bits, and a running (best, runner-up) over those: 1.2 VALU instructions per
+            // score instead of the 2.8 of tracking every score.
+            float hbest[2], hsecond[2];
+            int hsb[2];
 #pragma unroll
-        for (int h = 0; h < 2; ++h) {
-            // B operand: lanes < 32 carry the channels of token 32 h + lane (their own for h = 0,
-            // the partner lane's for h = 1), lanes >= 32 the ones that pick up the pieces of
-            // -|c|^2 / 2
-            unsigned xh[C / 2];
+            for (int h = 0; h < 2; ++h) {
+                // B operand: lanes < 32 carry the channels of token 32 h + lane (their own for h = 0,
+                // the partner lane's for h = 1), lanes >= 32 the ones that pick up the pieces of
+                // -|c|^2 / 2
+                unsigned xh[C / 2];
 #pragma unroll
-            for (int i = 0; i < C / 2; ++i) xh[i] = h == 0 ? xs[i] : __shfl_xor(xs[i], 32);
-            const _Float16 one = (_Float16)1.0f, zero = (_Float16)0.0f;
-            vec_t bop;
-            if constexpr (C == 8) {
-                if (lane < 32) {
-                    const half2_t p0 = __builtin_bit_cast(half2_t, xh[0]), p1 = __builtin_bit_cast(half2_t, xh[1]);
-                    const half2_t p2 = __builtin_bit_cast(half2_t, xh[2]), p3 = __builtin_bit_cast(half2_t, xh[3]);
-                    bop = vec_t{p0.x, p0.y, p1.x, p1.y, p2.x, p2.y, p3.x, p3.y};
+                for (int i = 0; i < C / 2; ++i) xh[i] = h == 0 ? xs[i] : __shfl_xor(xs[i], 32);
+                const _Float16 one = (_Float16)1.0f, zero = (_Float16)0.0f;
+                vec_t bop;
+                if constexpr (C == 8) {
+                    if (lane < 32) {
+                        const half2_t p0 = __builtin_bit_cast(half2_t, xh[0]), p1 = __builtin_bit_cast(half2_t, xh[1]);
+                        const half2_t p2 = __builtin_bit_cast(half2_t, xh[2]), p3 = __builtin_bit_cast(half2_t, xh[3]);
+                        bop = vec_t{p0.x, p0.y, p1.x, p1.y, p2.x, p2.y, p3.x, p3.y};
+                    } else {
+                        bop = vec_t{one, one, one, zero, zero, zero, zero, zero};
+                    }
+                } else if constexpr (C == 4) {
+                    if (lane < 32) {
+                        const half2_t p0 = __builtin_bit_cast(half2_t, xh[0]), p1 = __builtin_bit_cast(half2_t, xh[1]);
+                        bop = vec_t{p0.x, p0.y, p1.x, p1.y};
+                    } else {
+                        bop = vec_t{one, one, one, zero};
+                    }
                 } else {
-                    bop = vec_t{one, one, one, zero, zero, zero, zero, zero};
+                    if (lane < 32) {
+                        const half2_t p0 = __builtin_bit_cast(half2_t, xh[0]);
+                        bop = vec_t{p0.x, p0.y, one, one};
+                    } else {
+                        bop = vec_t{one, zero, zero, zero};
+                    }
                 }
-            } else if constexpr (C == 4) {
-                if (lane < 32) {
-                    const half2_t p0 = __builtin_bit_cast(half2_t, xh[0]), p1 = __builtin_bit_cast(half2_t, xh[1]);
-                    bop = vec_t{p0.x, p0.y, p1.x, p1.y};
-                } else {
-                    bop = vec_t{one, one, one, zero};
-                }
-            } else {
-                if (lane < 32) {
-                    const half2_t p0 = __builtin_bit_cast(half2_t, xh[0]);
-                    bop = vec_t{p0.x, p0.y, one, one};
-                } else {
-                    bop = vec_t{one, zero, zero, zero};
-                }
-            }
 
-            float gbest = LOWEST, gsecond = LOWEST;
-            int gsb = 0;                                 // block / 8 of gbest (more than 8 blocks: b = 10)
+                float gbest = LOWEST, gsecond = LOWEST;
+                int gsb = 0;                                 // block / 8 of gbest (more than 8 blocks: b = 10)
 #pragma unroll 1
-            for (int sb = 0; sb < NSB; ++sb) {
-                float sbest = LOWEST, ssecond = LOWEST;
+                for (int sb = 0; sb < NSB; ++sb) {
+                    float sbest = LOWEST, ssecond = LOWEST;
 #pragma unroll                  // (whole: the quad numbers are then immediates of one v_and_or_b32)
-                for (int b8 = 0; b8 < 8; ++b8) {
-                    const int blk = sb * 8 + b8;
-                    const vec_t aop = *reinterpret_cast<const vec_t*>(&cba[buf][(blk * 32 + (lane & 31)) * KDIM + (lane >> 5) * HALF]);
-                    const float16_t d = mfma<C>(aop, bop);
-                    float qm[4];
+                    for (int b8 = 0; b8 < 8; ++b8) {
+                        const int blk = sb * 8 + b8;
+                        const vec_t aop = *reinterpret_cast<const vec_t*>(&cba[buf][(blk * 32 + (lane & 31)) * KDIM + (lane >> 5) * HALF]);
+                        const float16_t d = mfma<C>(aop, bop);
+                        float qm[4];
 #pragma unroll
-                    for (int q = 0; q < 4; ++q) {
-                        const float m = fmaxf(fmaxf(fmaxf(d[4 * q], d[4 * q + 1]), d[4 * q + 2]), d[4 * q + 3]);
-                        qm[q] = __uint_as_float((__float_as_uint(m) & 0xffffffe0u) | (unsigned)(4 * b8 + q));
+                        for (int q = 0; q < 4; ++q) {
+                            const float m = fmaxf(fmaxf(fmaxf(d[4 * q], d[4 * q + 1]), d[4 * q + 2]), d[4 * q + 3]);
+                            qm[q] = __uint_as_float((__float_as_uint(m) & 0xffffffe0u) | (unsigned)(4 * b8 + q));
+                        }
+                        // two quads per step: the runner-up of {best, second, k1, k2} with second <= best
+                        // is max(median(best, k1, k2), second)
+#pragma unroll
+                        for (int q = 0; q < 4; q += 2) {
+                            ssecond = fmaxf(ssecond, __builtin_amdgcn_fmed3f(sbest, qm[q], qm[q + 1]));
+                            sbest = fmaxf(fmaxf(sbest, qm[q]), qm[q + 1]);
+                        }
                     }
-                    // two quads per step: the runner-up of {best, second, k1, k2} with second <= best
-                    // is max(median(best, k1, k2), second)
-#pragma unroll
-                    for (int q = 0; q < 4; q += 2) {
-                        ssecond = fmaxf(ssecond, __builtin_amdgcn_fmed3f(sbest, qm[q], qm[q + 1]));
-                        sbest = fmaxf(fmaxf(sbest, qm[q]), qm[q + 1]);
+                    if constexpr (NSB == 1) {
+                        gbest = sbest;
+                        gsecond = ssecond;
+                    } else {
+                        gsecond = fmaxf(fmaxf(fminf(gbest, sbest), gsecond), ssecond);
+                        gsb = sbest > gbest ? sb : gsb;
+                        gbest = fmaxf(gbest, sbest);
                     }
                 }
-                if constexpr (NSB == 1) {
-                    gbest = sbest;
-                    gsecond = ssecond;
+                hbest[h] = gbest;
+                hsecond[h] = gsecond;
+                hsb[h] = gsb;
+            }
+            // Lanes l and l + 32 saw the two halves of every block's rows for tokens l % 32 (h = 0) and
+            // 32 + l % 32 (h = 1).  Each lane now takes its OWN token (token `lane`, in half lane / 32):
+            // its own scan of that half, and the partner lane's, which sends it in exchange for the
+            // other half's.  Everything below runs once per tile and group, on all 64 lanes.
+            const int hi = lane >> 5;
+            const float gbest = hi ? hbest[1] : hbest[0], gsecond = hi ? hsecond[1] : hsecond[0];
+            const float obest = __shfl_xor(hi ? hbest[0] : hbest[1], 32), osecond = __shfl_xor(hi ? hsecond[0] : hsecond[1], 32);
+            const int gsb = hi ? hsb[1] : hsb[0];
+            const int osb = NSB == 1 ? 0 : __shfl_xor(hi ? hsb[0] : hsb[1], 32);
+            const bool other = obest > gbest;
+            const float best = fmaxf(gbest, obest);
+            const float second = fmaxf(fmaxf(fminf(gbest, obest), gsecond), osecond);
+            const int wsb = other ? osb : gsb;
+            const int whalf = other ? 1 - hi : hi;
+            const int u = lane;                                      // token of the tile
+            const int slot = (g - u) & (GH - 1);
+            // Level 2: the winning quad's four centroids against this token, x . c - |c|^2 / 2 in fp32
+            // from the records in LDS.
+            const int quad = (int)(__float_as_uint(best) & 31u);
+            const int j0 = (wsb * 8 + (quad >> 2)) * 32 + 8 * (quad & 3) + 4 * whalf;
+            // (v_dot2_f32_f16: exact products of the fp16 pairs, fp32 sums; the centroid's number
+            // within the quad rides in the two lowest mantissa bits)
+            float qk[4];
+            const half2_t ones = half2_t{(_Float16)1.0f, (_Float16)1.0f};
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const unsigned* r = reinterpret_cast<const unsigned*>(&cba[buf][(j0 + e) * KDIM]);
+                unsigned w[C / 2 + 2];
+                if constexpr (C == 8) {
+                    const uint4 a0 = *reinterpret_cast<const uint4*>(r);
+                    const uint2 a1 = *reinterpret_cast<const uint2*>(r + 4);
+                    w[0] = a0.x; w[1] = a0.y; w[2] = a0.z; w[3] = a0.w; w[4] = a1.x; w[5] = a1.y;
+                } else if constexpr (C == 4) {
+                    const uint4 a0 = *reinterpret_cast<const uint4*>(r);
+                    w[0] = a0.x; w[1] = a0.y; w[2] = a0.z; w[3] = a0.w;
                 } else {
-                    gsecond = fmaxf(fmaxf(fminf(gbest, sbest), gsecond), ssecond);
-                    gsb = sbest > gbest ? sb : gsb;
-                    gbest = fmaxf(gbest, sbest);
+                    const uint4 a0 = *reinterpret_cast<const uint4*>(r);
+                    w[0] = a0.x; w[1] = a0.y; w[2] = a0.z;
                 }
-            }
-            hbest[h] = gbest;
-            hsecond[h] = gsecond;
-            hsb[h] = gsb;
-        }
-        // Lanes l and l + 32 saw the two halves of every block's rows for tokens l % 32 (h = 0) and
-        // 32 + l % 32 (h = 1).  Each lane now takes its OWN token (token `lane`, in half lane / 32):
-        // its own scan of that half, and the partner lane's, which sends it in exchange for the
-        // other half's.  Everything below runs once per tile and group, on all 64 lanes.
-        const int hi = lane >> 5;
-        const float gbest = hi ? hbest[1] : hbest[0], gsecond = hi ? hsecond[1] : hsecond[0];
-        const float obest = __shfl_xor(hi ? hbest[0] : hbest[1], 32), osecond = __shfl_xor(hi ? hsecond[0] : hsecond[1], 32);
-        const int gsb = hi ? hsb[1] : hsb[0];
-        const int osb = NSB == 1 ? 0 : __shfl_xor(hi ? hsb[0] : hsb[1], 32);
-        const bool other = obest > gbest;
-        const float best = fmaxf(gbest, obest);
-        const float second = fmaxf(fmaxf(fminf(gbest, obest), gsecond), osecond);
-        const int wsb = other ? osb : gsb;
-        const int whalf = other ? 1 - hi : hi;
-        const int u = lane;                                      // token of the tile
-        const int slot = (g - u) & (GH - 1);
-        // Level 2: the winning quad's four centroids against this token, x . c - |c|^2 / 2 in fp32
-        // from the records in LDS.
-        const int quad = (int)(__float_as_uint(best) & 31u);
-        const int j0 = (wsb * 8 + (quad >> 2)) * 32 + 8 * (quad & 3) + 4 * whalf;
-        // (v_dot2_f32_f16: exact products of the fp16 pairs, fp32 sums; the centroid's number
-        // within the quad rides in the two lowest mantissa bits)
-        float qk[4];
-        const half2_t ones = half2_t{(_Float16)1.0f, (_Float16)1.0f};
+                // the three pieces of -|c|^2 / 2 sit behind the C channels: (h1, h2), (h3, 0)
+                float sc = __builtin_amdgcn_fdot2(__builtin_bit_cast(half2_t, w[C / 2 + 1]), ones, 0.f, false);
+                sc = __builtin_amdgcn_fdot2(__builtin_bit_cast(half2_t, w[C / 2]), ones, sc, false);
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            const unsigned* r = reinterpret_cast<const unsigned*>(&cba[buf][(j0 + e) * KDIM]);
-            unsigned w[C / 2 + 2];
-            if constexpr (C == 8) {
-                const uint4 a0 = *reinterpret_cast<const uint4*>(r);
-                const uint2 a1 = *reinterpret_cast<const uint2*>(r + 4);
-                w[0] = a0.x; w[1] = a0.y; w[2] = a0.z; w[3] = a0.w; w[4] = a1.x; w[5] = a1.y;
-            } else if constexpr (C == 4) {
-                const uint4 a0 = *reinterpret_cast<const uint4*>(r);
-                w[0] = a0.x; w[1] = a0.y; w[2] = a0.z; w[3] = a0.w;
-            } else {
-                const uint4 a0 = *reinterpret_cast<const uint4*>(r);
-                w[0] = a0.x; w[1] = a0.y; w[2] = a0.z;
+                for (int i = 0; i < C / 2; ++i)
+                    sc = __builtin_amdgcn_fdot2(__builtin_bit_cast(half2_t, xs[i]), __builtin_bit_cast(half2_t, w[i]), sc, false);
+                qk[e] = __uint_as_float((__float_as_uint(sc) & 0xfffffffcu) | (unsigned)e);
             }
-            // the three pieces of -|c|^2 / 2 sit behind the C channels: (h1, h2), (h3, 0)
-            float sc = __builtin_amdgcn_fdot2(__builtin_bit_cast(half2_t, w[C / 2 + 1]), ones, 0.f, false);
-            sc = __builtin_amdgcn_fdot2(__builtin_bit_cast(half2_t, w[C / 2]), ones, sc, false);
-#pragma unroll
-            for (int i = 0; i < C / 2; ++i)
-                sc = __builtin_amdgcn_fdot2(__builtin_bit_cast(half2_t, xs[i]), __builtin_bit_cast(half2_t, w[i]), sc, false);
-            qk[e] = __uint_as_float((__float_as_uint(sc) & 0xfffffffcu) | (unsigned)e);
-        }
-        const float q01 = fmaxf(qk[0], qk[1]);
-        const float qbest_k = fmaxf(fmaxf(q01, qk[2]), qk[3]);
-        const float qsecond = fmaxf(fminf(qk[0], qk[1]), __builtin_amdgcn_fmed3f(q01, qk[2], qk[3]));
-        const int qarg = (int)(__float_as_uint(qbest_k) & 3u);
-        const float qbest = __uint_as_float(__float_as_uint(qbest_k) & 0xfffffffcu);
-        bool unsure;
-        {
-            const int code = j0 + qarg;
-            const float sv = fmaxf(__uint_as_float(__float_as_uint(second) & 0xffffffe0u), qsecond);
-            unsure = !(qbest - sv > thr) || exact_only;
-            rec[ti][(slot >> 4) * 1024 + u * 16 + (slot & 15)] = (uint8_t)(code & 0xff);
-            if constexpr (B == 10) code16[wave][u][g] = (uint16_t)code;
-        }
-
-        // exact re-do of the unsure tokens of this tile, one at a time by the whole wavefront
-        unsigned long long todo = __ballot(unsure);
-        while (todo) {
-            const int r = (int)__builtin_ctzll(todo);
-            todo &= todo - 1;
-            float x[C];
-#pragma unroll
-            for (int i = 0; i < C / 2; ++i) {
-                const half2_t hh = __builtin_bit_cast(half2_t, (unsigned)__builtin_amdgcn_readlane((int)xw[i], r));
-                x[2 * i] = (float)hh.x * gs.f1;                // exact in fp32
-                x[2 * i + 1] = (float)hh.y * gs.f1;
-            }
-            unsigned dmin = ~0u, jmin = 0;
-#pragma unroll 4
-            for (int j = lane; j < K; j += 64) {
-                unsigned cw[C / 2];
-#pragma unroll
-                for (int i = 0; i < C / 2; ++i) cw[i] = *reinterpret_cast<const unsigned*>(&cba[buf][j * KDIM + 2 * i]);
-                const unsigned dj = exact_distance_bits<C>(x, cw);
-                jmin = dj < dmin ? (unsigned)j : jmin;       // increasing j: the lowest index stays on ties
-                dmin = dj < dmin ? dj : dmin;
-            }
-            const unsigned wmin = wave_min_u32(dmin);
-            // the lowest index among the lanes that hold the minimum: almost always one lane
-            const unsigned long long holders = __ballot(dmin == wmin);
-            unsigned code;
-            if ((holders & (holders - 1)) == 0) code = (unsigned)__builtin_amdgcn_readlane((int)jmin, (int)__builtin_ctzll(holders));
-            else code = wave_min_u32(dmin == wmin ? jmin : ~0u);
-            if (lane == r) {
+            const float q01 = fmaxf(qk[0], qk[1]);
+            const float qbest_k = fmaxf(fmaxf(q01, qk[2]), qk[3]);
+            const float qsecond = fmaxf(fminf(qk[0], qk[1]), __builtin_amdgcn_fmed3f(q01, qk[2], qk[3]));
+            const int qarg = (int)(__float_as_uint(qbest_k) & 3u);
+            const float qbest = __uint_as_float(__float_as_uint(qbest_k) & 0xfffffffcu);
+            bool unsure;
+            {
+                const int code = j0 + qarg;
+                const float sv = fmaxf(__uint_as_float(__float_as_uint(second) & 0xffffffe0u), qsecond);
+                unsure = !(qbest - sv > thr) || exact_only;
                 rec[ti][(slot >> 4) * 1024 + u * 16 + (slot & 15)] = (uint8_t)(code & 0xff);
                 if constexpr (B == 10) code16[wave][u][g] = (uint16_t)code;
             }
+
+            // exact re-do of the unsure tokens of this tile, one at a time by the whole wavefront
+            unsigned long long todo = __ballot(unsure);
+            while (todo) {
+                const int r = (int)__builtin_ctzll(todo);
+                todo &= todo - 1;
+                float x[C];
+#pragma unroll
+                for (int i = 0; i < C / 2; ++i) {
+                    const half2_t hh = __builtin_bit_cast(half2_t, (unsigned)__builtin_amdgcn_readlane((int)xw[i], r));
+                    x[2 * i] = (float)hh.x * gs.f1;                // exact in fp32
+                    x[2 * i + 1] = (float)hh.y * gs.f1;
+                }
+                unsigned dmin = ~0u, jmin = 0;
+#pragma unroll 4
+                for (int j = lane; j < K; j += 64) {
+                    unsigned cw[C / 2];
+#pragma unroll
+                    for (int i = 0; i < C / 2; ++i) cw[i] = *reinterpret_cast<const unsigned*>(&cba[buf][j * KDIM + 2 * i]);
+                    const unsigned dj = exact_distance_bits<C>(x, cw);
+                    jmin = dj < dmin ? (unsigned)j : jmin;       // increasing j: the lowest index stays on ties
+                    dmin = dj < dmin ? dj : dmin;
+                }
+                const unsigned wmin = wave_min_u32(dmin);
+                // the lowest index among the lanes that hold the minimum: almost always one lane
+                const unsigned long long holders = __ballot(dmin == wmin);
+                unsigned code;
+                if ((holders & (holders - 1)) == 0) code = (unsigned)__builtin_amdgcn_readlane((int)jmin, (int)__builtin_ctzll(holders));
+                else code = wave_min_u32(dmin == wmin ? jmin : ~0u);
+                if (lane == r) {
+                    rec[ti][(slot >> 4) * 1024 + u * 16 + (slot & 15)] = (uint8_t)(code & 0xff);
+                    if constexpr (B == 10) code16[wave][u][g] = (uint16_t)code;
+                }
+            }
         }
-      }
         // (GS: the wavefront is the only reader of its buffer, and its LDS operations keep their order)
         if (g + 1 < g_end) commit(GS ? wave : buf ^ 1, g + 1);
         if constexpr (!GS) __syncthreads();
