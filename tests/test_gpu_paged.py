@@ -82,6 +82,40 @@ def test_paged_encode_and_decode_equal_the_contiguous_calls(c, b):
     check_attention(got.cpu().numpy(), O.attention(q, kcodes, vcodes, ck, cv, 0.09, hkv))
 
 
+@pytest.mark.parametrize("c,b", [(8, 8), (2, 8), (8, 10)])
+def test_paged_prefill_of_a_large_call_equals_the_contiguous_one(c, b):
+    # enough (tile, head, sequence, tensor) items for the workgroup shapes that serve several tiles
+    # (33 tiles per sequence: the last workgroup of a sequence has tiles to skip), appended at an
+    # offset that leaves the first tile ragged
+    hkv, hq, B, T, t_off = 32, 32, 2, 2100, 30
+    fmt = cq.CQFormat(c, b, 128, hkv)
+    D = hkv * 128
+    rk, rv = synth.tensor_recipe(90 + c, 0, "k", D), synth.tensor_recipe(90 + c, 0, "v", D)
+    xk = synth.sample_activations_torch(rk, B * T, 3, "cuda").reshape(B, T, D)
+    xv = synth.sample_activations_torch(rv, B * T, 4, "cuda").reshape(B, T, D)
+    ckd, cvd = dev(synth.sample_codebook(rk, c, b)), dev(synth.sample_codebook(rv, c, b))
+    tiles = -(-(t_off + T) // 64)
+    t_cap = tiles * 64
+    n_pages = B * tiles + 7
+    perm = np.random.default_rng(c).permutation(n_pages)
+    table = perm[:B * tiles].reshape(B, tiles)
+    pages = cq.PageTable(dev(table.astype(np.int32)), n_pages)
+    kc = torch.full((cq.cq_cache_bytes(fmt, B, t_cap),), 0xA5, dtype=torch.uint8, device="cuda")
+    vc = torch.full_like(kc, 0xA5)
+    cq.cq_encode_kv(xk, xv, ckd, cvd, fmt, kc, vc, t_off, t_cap)
+    kp = torch.full((cq.cq_paged_cache_bytes(fmt, n_pages),), 0xA5, dtype=torch.uint8, device="cuda")
+    vp = torch.full_like(kp, 0xA5)
+    cq.cq_encode_kv_paged(xk, xv, ckd, cvd, fmt, kp, vp, pages, t_off)
+    torch.cuda.synchronize()
+    assert torch.equal(_pool_to_cache(kp, fmt, table, n_pages), kc)
+    assert torch.equal(_pool_to_cache(vp, fmt, table, n_pages), vc)
+    # (the contiguous call at this size against the oracle, on sampled rows)
+    from gpu_util import check_codes
+    codes = cache_to_codes(kc, fmt, B, t_cap, T, t_off)
+    rows = np.array([0, 33, 34, 1000, T - 65, T - 1])
+    check_codes(codes[1, rows], xk[1, rows].cpu().numpy(), synth.sample_codebook(rk, c, b))
+
+
 @pytest.mark.parametrize("c,b", FORMATS)
 def test_paged_decode_step_equals_the_contiguous_step(c, b):
     hkv, hq, B, T = 2, 4, 3, 200
