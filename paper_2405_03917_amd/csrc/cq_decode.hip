@@ -320,6 +320,15 @@ __device__ __forceinline__ Tile<GH, B> load_tile_desc(const uint8_t* tile, bool 
     return w;
 }
 
+// minimum over the four neighbouring lanes that walk the same group's codebook
+__device__ __forceinline__ unsigned long long quad_lanes_min(unsigned long long key)
+{
+    unsigned long long o = __shfl_xor(key, 1);
+    key = o < key ? o : key;
+    o = __shfl_xor(key, 2);
+    return o < key ? o : key;
+}
+
 // STEP = true is the fused decode step: the workgroup whose split holds the newest position
 // (t_n - 1) also encodes that token's key and value rows for its KV head.  Keys: while it builds
 // the score table (the key codebook is in registers anyway); the tile that holds the position is
@@ -509,9 +518,14 @@ __global__ __launch_bounds__(kDecodeThreads, 4) void decode_split_kernel(DecodeA
     Tile<GH, B> buf[PF];
 
     // ---- 1. score table ------------------------------------------------------------------
-    // unit u = tid + k NT of a 16-group chunk: group gl = u % 16 (fixed per thread), centroids
+    // unit u = tid + k NT of a 16-group chunk: group gl = (u / 4) % 16 (fixed per thread), centroids
     // j0 .. j0 + JPL - 1 with j0 = (u / 16) * JPL.  A wavefront's loads are 16 segments of 64 B.
-    const int gl = tid & 15;
+    const int gl = (tid >> 2) & 15;
+    // 16-byte piece k of the thread's walk through a group's codebook: the four lanes of a group
+    // read four neighbouring pieces (64 contiguous bytes), and 16 neighbouring lanes four groups
+    // (with lanes l, l + 16, l + 32, l + 48 on a group instead, the 16 lanes that the memory
+    // pipeline takes together touched 16 cache lines for 16 bytes each)
+    auto piece = [&](int k) { return (((tid + k * NT) >> 6) << 2) + (tid & 3); };
     unsigned xvw[STEP ? NCH : 1][C / 2];            // fused step: this thread's slices of the new value row
     {
         const uint16_t* qh = q_ptr + (size_t)n * q_batch_stride + (size_t)hq * D;
@@ -539,7 +553,7 @@ __global__ __launch_bounds__(kDecodeThreads, 4) void decode_split_kernel(DecodeA
             for (int k0 = 0; k0 < IPT; k0 += KB) {
                 Cent16 raw[KB];
 #pragma unroll
-                for (int k = 0; k < KB; ++k) raw[k] = load_cent16(ck + (size_t)((tid + (k0 + k) * NT) >> 4) * 8);
+                for (int k = 0; k < KB; ++k) raw[k] = load_cent16(ck + (size_t)piece(k0 + k) * 8);
                 // the first key tiles are requested behind the first centroids: tile requests must
                 // go out as early as possible (the kernel is bound by HBM from its first
                 // microsecond), but not in front of the loads the table build waits for
@@ -567,7 +581,7 @@ __global__ __launch_bounds__(kDecodeThreads, 4) void decode_split_kernel(DecodeA
                 }
 #pragma unroll
                 for (int k = 0; k < KB; ++k) {
-                    const int j0 = ((tid + (k0 + k) * NT) >> 4) * JPL;
+                    const int j0 = piece(k0 + k) * JPL;
 #pragma unroll
                     for (int jj = 0; jj < JPL; ++jj) {
                         float dot = 0.f;
@@ -584,8 +598,8 @@ __global__ __launch_bounds__(kDecodeThreads, 4) void decode_split_kernel(DecodeA
                 }
             }
             if (has_new) {
-                const unsigned long long kkey = group_lanes_min(knear.key());
-                if (lane < 16) lds_min_u64(&keys[g], kkey);
+                const unsigned long long kkey = quad_lanes_min(knear.key());
+                if ((lane & 3) == 0) lds_min_u64(&keys[g], kkey);
             }
         }
     }
@@ -665,7 +679,7 @@ __global__ __launch_bounds__(kDecodeThreads, 4) void decode_split_kernel(DecodeA
             for (int ch = 0; ch < NCH; ++ch) {
                 const uint16_t* cv = v_centroids + (size_t)(hkv * GH + ch * 16 + gl) * K * C;
 #pragma unroll
-                for (int kk = 0; kk < IPT; ++kk) rawv[ch][kk] = load_cent16(cv + (size_t)((tid + kk * NT) >> 4) * 8);
+                for (int kk = 0; kk < IPT; ++kk) rawv[ch][kk] = load_cent16(cv + (size_t)piece(kk) * 8);
             }
         }
     };
@@ -824,7 +838,7 @@ __global__ __launch_bounds__(kDecodeThreads, 4) void decode_split_kernel(DecodeA
 
     // ---- 3. epilogue: o = bins . C_V -----------------------------------------------------
     // same walk as the table build; thread-private sums over its centroids of group gl in every
-    // chunk, then lanes l, l+16, l+32, l+48 and the wavefronts are added up.
+    // chunk, then the four lanes of a group and the wavefronts are added up.
     lane_sum = wave_sum_u32(lane_sum);
 
     // fused step: encode the new value row against the value codebook (same walk, same registers
@@ -848,18 +862,18 @@ __global__ __launch_bounds__(kDecodeThreads, 4) void decode_split_kernel(DecodeA
                 Cent16 rawb[EARLY ? 1 : KB];
                 if constexpr (!EARLY) {
 #pragma unroll
-                    for (int k = 0; k < KB; ++k) rawb[k] = load_cent16(cv + (size_t)((tid + (k0 + k) * NT) >> 4) * 8);
+                    for (int k = 0; k < KB; ++k) rawb[k] = load_cent16(cv + (size_t)piece(k0 + k) * 8);
                 }
 #pragma unroll
                 for (int k = 0; k < KB; ++k) {
-                    const int j0 = ((tid + (k0 + k) * NT) >> 4) * JPL;
+                    const int j0 = piece(k0 + k) * JPL;
                     const Cent16& r = EARLY ? rawv[EARLY ? ch : 0][k] : rawb[EARLY ? 0 : k];
 #pragma unroll
                     for (int jj = 0; jj < JPL; ++jj) vnear.offer(centroid_distance<C>(xv, &r.w[jj * (C / 2)]), j0 + jj);
                 }
             }
-            const unsigned long long vkey = group_lanes_min(vnear.key());
-            if (lane < 16) lds_min_u64(&keys[GH + ch * 16 + gl], vkey);
+            const unsigned long long vkey = quad_lanes_min(vnear.key());
+            if ((lane & 3) == 0) lds_min_u64(&keys[GH + ch * 16 + gl], vkey);
         }
     }
     lds_barrier();                                // all bin updates done
@@ -887,12 +901,12 @@ __global__ __launch_bounds__(kDecodeThreads, 4) void decode_split_kernel(DecodeA
             if constexpr (!EARLY) {
                 const uint16_t* cv = v_centroids + (size_t)(hkv * GH + ch * 16 + gl) * K * C;
 #pragma unroll
-                for (int k = 0; k < KB; ++k) rawv[0][k] = load_cent16(cv + (size_t)((tid + (k0 + k) * NT) >> 4) * 8);
+                for (int k = 0; k < KB; ++k) rawv[0][k] = load_cent16(cv + (size_t)piece(k0 + k) * 8);
             }
             const Cent16 (&raw)[KB] = rawv[EARLY ? ch : 0];
 #pragma unroll
             for (int k = 0; k < KB; ++k) {
-                const int j0 = ((tid + (k0 + k) * NT) >> 4) * JPL;
+                const int j0 = piece(k0 + k) * JPL;
 #pragma unroll
                 for (int jj = 0; jj < JPL; ++jj) {
                     const float* src = tab + F::word(j0 + jj, F::BIN0 + (ch * 16 + gl) * R);
@@ -911,12 +925,12 @@ __global__ __launch_bounds__(kDecodeThreads, 4) void decode_split_kernel(DecodeA
         }
 #pragma unroll
         for (int i = 0; i < C; ++i) {
-            acc[ch][i] += __shfl_xor(acc[ch][i], 16);
-            acc[ch][i] += __shfl_xor(acc[ch][i], 32);
+            acc[ch][i] += __shfl_xor(acc[ch][i], 1);
+            acc[ch][i] += __shfl_xor(acc[ch][i], 2);
         }
     }
     // per-wave results: scr[64 + wave * D + channel]
-    if (lane < 16) {
+    if ((lane & 3) == 0) {
 #pragma unroll
         for (int ch = 0; ch < NCH; ++ch)
 #pragma unroll
