@@ -320,15 +320,6 @@ __device__ __forceinline__ Tile<GH, B> load_tile_desc(const uint8_t* tile, bool 
     return w;
 }
 
-// minimum over the four neighbouring lanes that walk the same group's codebook
-__device__ __forceinline__ unsigned long long quad_lanes_min(unsigned long long key)
-{
-    unsigned long long o = __shfl_xor(key, 1);
-    key = o < key ? o : key;
-    o = __shfl_xor(key, 2);
-    return o < key ? o : key;
-}
-
 // STEP = true is the fused decode step: the workgroup whose split holds the newest position
 // (t_n - 1) also encodes that token's key and value rows for its KV head.  Keys: while it builds
 // the score table (the key codebook is in registers anyway); the tile that holds the position is

@@ -112,12 +112,12 @@ __device__ __forceinline__ void load_row_slice(const uint16_t* p, float (&x)[C])
     }
 }
 
-// minimum over the four lanes l, l+16, l+32, l+48 that walk the same group
-__device__ __forceinline__ unsigned long long group_lanes_min(unsigned long long key)
+// minimum over the four neighbouring lanes that walk the same group's codebook
+__device__ __forceinline__ unsigned long long quad_lanes_min(unsigned long long key)
 {
-    unsigned long long o = __shfl_xor(key, 16);
+    unsigned long long o = __shfl_xor(key, 1);
     key = o < key ? o : key;
-    o = __shfl_xor(key, 32);
+    o = __shfl_xor(key, 2);
     return o < key ? o : key;
 }
 

@@ -247,7 +247,10 @@ __global__ __launch_bounds__(NT) void decode_rope_kernel(DecodeArgs a, const flo
     // cos / sin of the tiles' base positions: uniform per wavefront, read through the scalar cache
     typedef __attribute__((address_space(4))) const CosSin tile_cs_t;
     tile_cs_t* tile_cs = (tile_cs_t*)reinterpret_cast<unsigned long long>(tile_tab);
-    const int gl16 = tid & 15;
+    // (the four lanes of a group are neighbours and read four neighbouring 16-byte pieces of its
+    // value codebook: 64 contiguous bytes, four cache lines per 16 lanes instead of sixteen)
+    const int gl16 = (tid >> 2) & 15;
+    auto piece = [&](int k) { return (((tid + k * NT) >> 6) << 2) + (tid & 3); };
     unsigned xvw[STEP ? NCH : 1][C / 2];            // fused step: this thread's slices of the new value row
     lds_barrier();
 
@@ -465,7 +468,7 @@ __global__ __launch_bounds__(NT) void decode_rope_kernel(DecodeArgs a, const flo
             for (int ch = 0; ch < NCH; ++ch) {
                 const uint16_t* cv = a.v_centroids + (size_t)(hkv * GH + ch * 16 + gl16) * K * C;
 #pragma unroll
-                for (int k = 0; k < IPT; ++k) rawv[ch][k] = load_cent16(cv + (size_t)((tid + k * NT) >> 4) * 8);
+                for (int k = 0; k < IPT; ++k) rawv[ch][k] = load_cent16(cv + (size_t)piece(k) * 8);
             }
         }
     });
@@ -494,18 +497,18 @@ __global__ __launch_bounds__(NT) void decode_rope_kernel(DecodeArgs a, const flo
                 Cent16 rawb[EARLY ? 1 : KB];            // (where the codebook is not in registers yet: b = 10)
                 if constexpr (!EARLY) {
 #pragma unroll
-                    for (int k = 0; k < KB; ++k) rawb[k] = load_cent16(cvg + (size_t)((tid + (k0 + k) * NT) >> 4) * 8);
+                    for (int k = 0; k < KB; ++k) rawb[k] = load_cent16(cvg + (size_t)piece(k0 + k) * 8);
                 }
 #pragma unroll
                 for (int k = 0; k < KB; ++k) {
-                    const int j0 = ((tid + (k0 + k) * NT) >> 4) * JPL;
+                    const int j0 = piece(k0 + k) * JPL;
                     const Cent16& r = EARLY ? rawv[EARLY ? ch : 0][k] : rawb[EARLY ? 0 : k];
 #pragma unroll
                     for (int jj = 0; jj < JPL; ++jj) vnear.offer(centroid_distance<C>(xv, &r.w[jj * (C / 2)]), j0 + jj);
                 }
             }
-            const unsigned long long vkey = group_lanes_min(vnear.key());
-            if (lane < 16) lds_min_u64(&keys[GH + ch * 16 + gl16], vkey);
+            const unsigned long long vkey = quad_lanes_min(vnear.key());
+            if ((lane & 3) == 0) lds_min_u64(&keys[GH + ch * 16 + gl16], vkey);
         }
         lds_barrier();
         if (tid < GH) {
@@ -526,12 +529,12 @@ __global__ __launch_bounds__(NT) void decode_rope_kernel(DecodeArgs a, const flo
             if constexpr (!EARLY) {
                 const uint16_t* cv = a.v_centroids + (size_t)(hkv * GH + ch * 16 + gl16) * K * C;
 #pragma unroll
-                for (int k = 0; k < KB; ++k) rawv[0][k] = load_cent16(cv + (size_t)((tid + (k0 + k) * NT) >> 4) * 8);
+                for (int k = 0; k < KB; ++k) rawv[0][k] = load_cent16(cv + (size_t)piece(k0 + k) * 8);
             }
             const Cent16 (&raw)[KB] = rawv[EARLY ? ch : 0];
 #pragma unroll
             for (int k = 0; k < KB; ++k) {
-                const int j0 = ((tid + (k0 + k) * NT) >> 4) * JPL;
+                const int j0 = piece(k0 + k) * JPL;
 #pragma unroll
                 for (int jj = 0; jj < JPL; ++jj) {
                     const float* src = tab + (j0 + jj) * RW + (ch * 16 + gl16) * R;
@@ -550,11 +553,11 @@ __global__ __launch_bounds__(NT) void decode_rope_kernel(DecodeArgs a, const flo
         }
 #pragma unroll
         for (int i = 0; i < C; ++i) {
-            acc[ch][i] += __shfl_xor(acc[ch][i], 16);
-            acc[ch][i] += __shfl_xor(acc[ch][i], 32);
+            acc[ch][i] += __shfl_xor(acc[ch][i], 1);
+            acc[ch][i] += __shfl_xor(acc[ch][i], 2);
         }
     }
-    if (lane < 16) {
+    if ((lane & 3) == 0) {
 #pragma unroll
         for (int ch = 0; ch < NCH; ++ch)
 #pragma unroll
@@ -886,7 +889,10 @@ __global__ __launch_bounds__(NT) void decode_rope_gqa_kernel(DecodeArgs a, const
 
     // ---- 3. per head: softmax reference, phase V, epilogue ----------------------------------
     col.init(lane);
-    const int gl16 = tid & 15;
+    // (the four lanes of a group are neighbours and read four neighbouring 16-byte pieces of its
+    // value codebook: 64 contiguous bytes, four cache lines per 16 lanes instead of sixteen)
+    const int gl16 = (tid >> 2) & 15;
+    auto piece = [&](int k) { return (((tid + k * NT) >> 6) << 2) + (tid & 3); };
     constexpr int KB = IPT < 8 ? IPT : 8;
     const int n_tok = (tile1 - tile0) * kTileTokens;
     unsigned* pf_new = reinterpret_cast<unsigned*>(keys + 2 * GH);
@@ -904,16 +910,16 @@ __global__ __launch_bounds__(NT) void decode_rope_gqa_kernel(DecodeArgs a, const
             for (int k0 = 0; k0 < IPT; k0 += KB) {
                 Cent16 rawb[KB];
 #pragma unroll
-                for (int k = 0; k < KB; ++k) rawb[k] = load_cent16(cvg + (size_t)((tid + (k0 + k) * NT) >> 4) * 8);
+                for (int k = 0; k < KB; ++k) rawb[k] = load_cent16(cvg + (size_t)piece(k0 + k) * 8);
 #pragma unroll
                 for (int k = 0; k < KB; ++k) {
-                    const int j0 = ((tid + (k0 + k) * NT) >> 4) * JPL;
+                    const int j0 = piece(k0 + k) * JPL;
 #pragma unroll
                     for (int jj = 0; jj < JPL; ++jj) vnear.offer(centroid_distance<C>(xv, &rawb[k].w[jj * (C / 2)]), j0 + jj);
                 }
             }
-            const unsigned long long vkey = group_lanes_min(vnear.key());
-            if (lane < 16) lds_min_u64(&keys[GH + ch * 16 + gl16], vkey);
+            const unsigned long long vkey = quad_lanes_min(vnear.key());
+            if ((lane & 3) == 0) lds_min_u64(&keys[GH + ch * 16 + gl16], vkey);
         }
         lds_barrier();
         if (writer)
@@ -931,7 +937,7 @@ __global__ __launch_bounds__(NT) void decode_rope_gqa_kernel(DecodeArgs a, const
         for (int ch = 0; ch < NCH; ++ch) {
             const uint16_t* cv = a.v_centroids + (size_t)(hkv * GH + ch * 16 + gl16) * K * C;
 #pragma unroll
-            for (int k = 0; k < IPT; ++k) rawv[ch][k] = load_cent16(cv + (size_t)((tid + k * NT) >> 4) * 8);
+            for (int k = 0; k < IPT; ++k) rawv[ch][k] = load_cent16(cv + (size_t)piece(k) * 8);
         }
     }
     for (int h0 = 0; h0 < heads; h0 += HP) {
@@ -1031,12 +1037,12 @@ __global__ __launch_bounds__(NT) void decode_rope_gqa_kernel(DecodeArgs a, const
                 for (int k0 = 0; k0 < IPT; k0 += KB) {
                     if constexpr (!KEEP) {
 #pragma unroll
-                        for (int k = 0; k < KB; ++k) rawv[0][k] = load_cent16(cv + (size_t)((tid + (k0 + k) * NT) >> 4) * 8);
+                        for (int k = 0; k < KB; ++k) rawv[0][k] = load_cent16(cv + (size_t)piece(k0 + k) * 8);
                     }
                     const Cent16 (&raw)[KB] = rawv[KEEP ? ch : 0];
 #pragma unroll
                     for (int k = 0; k < KB; ++k) {
-                        const int j0 = ((tid + (k0 + k) * NT) >> 4) * JPL;
+                        const int j0 = piece(k0 + k) * JPL;
 #pragma unroll
                         for (int jj = 0; jj < JPL; ++jj) {
                             const float* src = tab + (j0 + jj) * RW + (ch * 16 + gl16) * R + 32 * e;
@@ -1055,11 +1061,11 @@ __global__ __launch_bounds__(NT) void decode_rope_gqa_kernel(DecodeArgs a, const
                 }
 #pragma unroll
                 for (int i = 0; i < C; ++i) {
-                    acc[ch][i] += __shfl_xor(acc[ch][i], 16);
-                    acc[ch][i] += __shfl_xor(acc[ch][i], 32);
+                    acc[ch][i] += __shfl_xor(acc[ch][i], 1);
+                    acc[ch][i] += __shfl_xor(acc[ch][i], 2);
                 }
             }
-            if (lane < 16) {
+            if ((lane & 3) == 0) {
 #pragma unroll
                 for (int ch = 0; ch < NCH; ++ch)
 #pragma unroll
