@@ -348,12 +348,18 @@ __global__ __launch_bounds__(kDecodeThreads, 4) void decode_split_kernel(DecodeA
     constexpr int PF = B == 10 ? 2 : (GH == 16 ? 4 : (GH == 32 ? 2 : 1));
     static_assert(NS % PF == 0 && NS >= PF, "the ring of tiles in flight must divide a chunk");
     constexpr int JPL = 8 / C;          // centroids per 16-byte load
-    constexpr int NCH = GH / 16;        // 16-group chunks of the codebook walk
-    constexpr int UNITS = 16 * K / JPL; // 16-byte loads per 16-group chunk
+    // groups per chunk of the codebook walk; 64 / GPC neighbouring lanes are on a group and read as
+    // many neighbouring 16-byte pieces.  (Measured: four lanes, 64 contiguous bytes, is the
+    // optimum; eight -- whole cache lines, but eight lanes on one LDS column and twice the chunks
+    // -- is 3 to 10 % slower at every format.)
+    constexpr int GPC = 16;
+    constexpr int LPG = 64 / GPC;
+    constexpr int NCH = GH / GPC;       // chunks of the codebook walk
+    constexpr int UNITS = GPC * K / JPL;    // 16-byte loads per chunk
     constexpr int IPT = UNITS / NT;     // ... per thread
     constexpr int KB = IPT < 8 ? IPT : 8;   // ... requested together
     constexpr int KU = IPT / KB <= 2 ? IPT / KB : 1;    // (1024 rows: the batches stay a loop, for registers)
-    static_assert(UNITS % NT == 0 && NT % 16 == 0, "thread count must divide the codebook walk");
+    static_assert(UNITS % NT == 0 && NT % 64 == 0, "thread count must divide the codebook walk");
     extern __shared__ float smem[];
     float* tab = smem;                              // [K][RW]: score table (and bins)
     float* slots = smem + F::SLOTS;
@@ -509,20 +515,19 @@ __global__ __launch_bounds__(kDecodeThreads, 4) void decode_split_kernel(DecodeA
     Tile<GH, B> buf[PF];
 
     // ---- 1. score table ------------------------------------------------------------------
-    // unit u = tid + k NT of a 16-group chunk: group gl = (u / 4) % 16 (fixed per thread), centroids
-    // j0 .. j0 + JPL - 1 with j0 = (u / 16) * JPL.  A wavefront's loads are 16 segments of 64 B.
-    const int gl = (tid >> 2) & 15;
-    // 16-byte piece k of the thread's walk through a group's codebook: the four lanes of a group
-    // read four neighbouring pieces (64 contiguous bytes), and 16 neighbouring lanes four groups
-    // (with lanes l, l + 16, l + 32, l + 48 on a group instead, the 16 lanes that the memory
-    // pipeline takes together touched 16 cache lines for 16 bytes each)
-    auto piece = [&](int k) { return (((tid + k * NT) >> 6) << 2) + (tid & 3); };
+    // A chunk of the walk is GPC groups; a thread stays on group gl of every chunk.  16-byte piece
+    // k of its walk through a group's codebook (centroids j0 .. j0 + JPL - 1, j0 = piece * JPL):
+    // the LPG lanes of a group are neighbours and read LPG neighbouring pieces, so the 16 lanes
+    // that the memory pipeline takes together read four runs of 64 bytes (with lanes l, l + 16,
+    // l + 32, l + 48 on a group, as it first was, they touched 16 lines for 16 bytes each).
+    const int gl = (tid / LPG) % GPC;
+    auto piece = [&](int k) { return ((tid + k * NT) >> 6) * LPG + (tid % LPG); };
     unsigned xvw[STEP ? NCH : 1][C / 2];            // fused step: this thread's slices of the new value row
     {
         const uint16_t* qh = q_ptr + (size_t)n * q_batch_stride + (size_t)hq * D;
 #pragma unroll
         for (int ch = 0; ch < NCH; ++ch) {
-            const int g = ch * 16 + gl;
+            const int g = ch * GPC + gl;
             const uint16_t* ck = k_centroids + (size_t)(hkv * GH + g) * K * C;
             unsigned qw[C / 2];
 #pragma unroll
@@ -589,8 +594,8 @@ __global__ __launch_bounds__(kDecodeThreads, 4) void decode_split_kernel(DecodeA
                 }
             }
             if (has_new) {
-                const unsigned long long kkey = quad_lanes_min(knear.key());
-                if ((lane & 3) == 0) lds_min_u64(&keys[g], kkey);
+                const unsigned long long kkey = group_lanes_min<LPG>(knear.key());
+                if (lane % LPG == 0) lds_min_u64(&keys[g], kkey);
             }
         }
     }
@@ -668,7 +673,7 @@ __global__ __launch_bounds__(kDecodeThreads, 4) void decode_split_kernel(DecodeA
         if constexpr (EARLY) {
 #pragma unroll
             for (int ch = 0; ch < NCH; ++ch) {
-                const uint16_t* cv = v_centroids + (size_t)(hkv * GH + ch * 16 + gl) * K * C;
+                const uint16_t* cv = v_centroids + (size_t)(hkv * GH + ch * GPC + gl) * K * C;
 #pragma unroll
                 for (int kk = 0; kk < IPT; ++kk) rawv[ch][kk] = load_cent16(cv + (size_t)piece(kk) * 8);
             }
@@ -846,7 +851,7 @@ __global__ __launch_bounds__(kDecodeThreads, 4) void decode_split_kernel(DecodeA
                 xv[2 * i] = (float)h.x;
                 xv[2 * i + 1] = (float)h.y;
             }
-            const uint16_t* cv = v_centroids + (size_t)(hkv * GH + ch * 16 + gl) * K * C;
+            const uint16_t* cv = v_centroids + (size_t)(hkv * GH + ch * GPC + gl) * K * C;
             Nearest vnear;
 #pragma unroll(KU)
             for (int k0 = 0; k0 < IPT; k0 += KB) {
@@ -863,8 +868,8 @@ __global__ __launch_bounds__(kDecodeThreads, 4) void decode_split_kernel(DecodeA
                     for (int jj = 0; jj < JPL; ++jj) vnear.offer(centroid_distance<C>(xv, &r.w[jj * (C / 2)]), j0 + jj);
                 }
             }
-            const unsigned long long vkey = quad_lanes_min(vnear.key());
-            if ((lane & 3) == 0) lds_min_u64(&keys[GH + ch * 16 + gl], vkey);
+            const unsigned long long vkey = group_lanes_min<LPG>(vnear.key());
+            if (lane % LPG == 0) lds_min_u64(&keys[GH + ch * GPC + gl], vkey);
         }
     }
     lds_barrier();                                // all bin updates done
@@ -890,7 +895,7 @@ __global__ __launch_bounds__(kDecodeThreads, 4) void decode_split_kernel(DecodeA
 #pragma unroll(KU)
         for (int k0 = 0; k0 < IPT; k0 += KB) {
             if constexpr (!EARLY) {
-                const uint16_t* cv = v_centroids + (size_t)(hkv * GH + ch * 16 + gl) * K * C;
+                const uint16_t* cv = v_centroids + (size_t)(hkv * GH + ch * GPC + gl) * K * C;
 #pragma unroll
                 for (int k = 0; k < KB; ++k) rawv[0][k] = load_cent16(cv + (size_t)piece(k0 + k) * 8);
             }
@@ -900,7 +905,7 @@ __global__ __launch_bounds__(kDecodeThreads, 4) void decode_split_kernel(DecodeA
                 const int j0 = piece(k0 + k) * JPL;
 #pragma unroll
                 for (int jj = 0; jj < JPL; ++jj) {
-                    const float* src = tab + F::word(j0 + jj, F::BIN0 + (ch * 16 + gl) * R);
+                    const float* src = tab + F::word(j0 + jj, F::BIN0 + (ch * GPC + gl) * R);
                     unsigned cnt;
                     if constexpr (R == 2) { const uint2 x = *reinterpret_cast<const uint2*>(src); cnt = x.x + x.y; }
                     else cnt = *reinterpret_cast<const unsigned*>(src);
@@ -916,16 +921,16 @@ __global__ __launch_bounds__(kDecodeThreads, 4) void decode_split_kernel(DecodeA
         }
 #pragma unroll
         for (int i = 0; i < C; ++i) {
-            acc[ch][i] += __shfl_xor(acc[ch][i], 1);
-            acc[ch][i] += __shfl_xor(acc[ch][i], 2);
+#pragma unroll
+            for (int m = 1; m < LPG; m <<= 1) acc[ch][i] += __shfl_xor(acc[ch][i], m);
         }
     }
     // per-wave results: scr[64 + wave * D + channel]
-    if ((lane & 3) == 0) {
+    if (lane % LPG == 0) {
 #pragma unroll
         for (int ch = 0; ch < NCH; ++ch)
 #pragma unroll
-            for (int i = 0; i < C; ++i) scr[64 + wave * D + (ch * 16 + gl) * C + i] = acc[ch][i];
+            for (int i = 0; i < C; ++i) scr[64 + wave * D + (ch * GPC + gl) * C + i] = acc[ch][i];
     }
     lds_barrier();
     unsigned l_fix = l_carry;                       // exact: integer adds

@@ -112,13 +112,16 @@ __device__ __forceinline__ void load_row_slice(const uint16_t* p, float (&x)[C])
     }
 }
 
-// minimum over the four neighbouring lanes that walk the same group's codebook
-__device__ __forceinline__ unsigned long long quad_lanes_min(unsigned long long key)
+// minimum over the LPG neighbouring lanes that walk the same group's codebook
+template <int LPG>
+__device__ __forceinline__ unsigned long long group_lanes_min(unsigned long long key)
 {
-    unsigned long long o = __shfl_xor(key, 1);
-    key = o < key ? o : key;
-    o = __shfl_xor(key, 2);
-    return o < key ? o : key;
+#pragma unroll
+    for (int m = 1; m < LPG; m <<= 1) {
+        const unsigned long long o = __shfl_xor(key, m);
+        key = o < key ? o : key;
+    }
+    return key;
 }
 
 // Fixed-point scale for the probabilities of one split: with l_est = sum_t 2^(s_t - m) (fp32),

@@ -507,7 +507,7 @@ __global__ __launch_bounds__(NT) void decode_rope_kernel(DecodeArgs a, const flo
                     for (int jj = 0; jj < JPL; ++jj) vnear.offer(centroid_distance<C>(xv, &r.w[jj * (C / 2)]), j0 + jj);
                 }
             }
-            const unsigned long long vkey = quad_lanes_min(vnear.key());
+            const unsigned long long vkey = group_lanes_min<4>(vnear.key());
             if ((lane & 3) == 0) lds_min_u64(&keys[GH + ch * 16 + gl16], vkey);
         }
         lds_barrier();
@@ -918,7 +918,7 @@ __global__ __launch_bounds__(NT) void decode_rope_gqa_kernel(DecodeArgs a, const
                     for (int jj = 0; jj < JPL; ++jj) vnear.offer(centroid_distance<C>(xv, &rawb[k].w[jj * (C / 2)]), j0 + jj);
                 }
             }
-            const unsigned long long vkey = quad_lanes_min(vnear.key());
+            const unsigned long long vkey = group_lanes_min<4>(vnear.key());
             if ((lane & 3) == 0) lds_min_u64(&keys[GH + ch * 16 + gl16], vkey);
         }
         lds_barrier();
