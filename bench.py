@@ -524,8 +524,8 @@ def cpu_baseline(synth, cfg, budget_s=12.0):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=30)
     ap.add_argument("--layers", type=int, default=0, help="override the number of layers (debug only)")
     ap.add_argument("--no-extra", action="store_true", help="skip the other configurations and entry points")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
