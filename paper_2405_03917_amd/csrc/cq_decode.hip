@@ -351,7 +351,8 @@ __global__ __launch_bounds__(kDecodeThreads, 4) void decode_split_kernel(DecodeA
     // groups per chunk of the codebook walk; 64 / GPC neighbouring lanes are on a group and read as
     // many neighbouring 16-byte pieces.  (Measured: four lanes, 64 contiguous bytes, is the
     // optimum; eight -- whole cache lines, but eight lanes on one LDS column and twice the chunks
-    // -- is 3 to 10 % slower at every format.)
+    // -- is 3 to 10 % slower at every format, two -- all 32 LDS columns in one store, but 32-byte
+    // runs -- 2 to 12 %.)
     constexpr int GPC = 16;
     constexpr int LPG = 64 / GPC;
     constexpr int NCH = GH / GPC;       // chunks of the codebook walk
